@@ -1,0 +1,219 @@
+"""CPU oracle for DSVT's Dynamic Sparse Window Attention (arXiv 2301.06051).
+
+TEST INFRASTRUCTURE ONLY.  A plain, slow, float64 numpy statement of what the
+paper defines, written to be checked against the paper by eye.  It shares no
+code with the HIP path and must never be imported by it: only the tests, the
+smoke check and the benchmark's CPU-baseline leg call into this file.
+
+What each function follows:
+  partition      Sec. 3.2 "Dynamic set partition": window split, Eq. (2) set
+                 count, Eq. (3) slot index, Eq. (4) INDEX; "Rotated set
+                 attention": X-/Y-axis main order; "Hybrid window partition":
+                 window shift.
+  set_attention  Eq. (5): MHSA over every set in one batch, PE added to the
+                 logits, duplicated slots masked as keys (sentence after Eq. 3).
+  layer / block  Appendix "Network Architecture", DSVT-P paragraph: MHSA,
+                 residual, LN, 2-layer MLP with GELU, residual, LN; a block is
+                 an X-axis layer followed by a Y-axis layer (Eq. 5, Fig. 3).
+  attn_pool      Sec. 3.3, Eq. (6) max-pool query and Eq. (7) attention over
+                 the densified pooling region.
+
+Readings taken where the paper is silent (each listed in the design notes):
+0-based ranks; Eq. (3) evaluated as an exact integer floor; x (resp. y) most
+significant in the inner-window order, z least; windows shifted without wrap,
+windows and sets numbered in ascending window key; PE = a learned relative
+position bias table per head indexed by the coordinate difference query-key;
+LN eps 1e-5, exact (erf) GELU, logit scale 1/sqrt(d); pooling output =
+LN(P + Attn(P, region)).
+Parity unpinned by the paper itself: the PE form, the pooling wrapper
+(residual + LN) and LN eps / GELU form -- they are pinned only to the stated
+reading (library LN / GELU / MHSA routines and brute force).
+"""
+import numpy as np
+from scipy.special import erf
+
+F64 = np.float64
+
+
+# ----------------------------------------------------------------------------
+# Partition (Sec. 3.2, Eq. 2-4)
+# ----------------------------------------------------------------------------
+def windows_per_axis(grid, win, shift):
+    """Windows needed to cover cells 0..grid-1 once they are moved by +shift."""
+    return tuple((g + s + w - 1) // w for g, s, w in zip(grid, shift, win))
+
+
+def window_and_inner_keys(coords, grid, win, shift, axis):
+    """Step 1-2: window key (batch most significant) and inner-window sort key."""
+    c = np.asarray(coords, dtype=np.int64)
+    b, x, y, z = c[:, 0], c[:, 1] + shift[0], c[:, 2] + shift[1], c[:, 3] + shift[2]
+    L, W, H = win
+    nwx, nwy, nwz = windows_per_axis(grid, win, shift)
+    win_key = ((b * nwx + x // L) * nwy + y // W) * nwz + z // H
+    xi, yi, zi = x % L, y % W, z % H
+    if axis == 0:                       # X-axis main order: x, then y, then z
+        inner = (xi * W + yi) * H + zi
+    else:                               # Y-axis main order: y, then x, then z
+        inner = (yi * L + xi) * H + zi
+    return win_key, inner
+
+
+def partition(coords, grid, win, shift, tau, axis):
+    """Rotated dynamic set partition of sparse voxels.
+
+    coords int [N,4] rows (b,x,y,z).  Returns a dict with
+      set_inds   int32 [S,tau]  voxel index held by every slot (Eq. 3-4)
+      voxel_slot int32 [N]      first flat slot s*tau+k holding each voxel
+      set_win    int32 [S]      window key of every set
+      n_sets     S = sum over non-empty windows of Eq. (2)
+      win_keys / win_counts     the non-empty windows and their N
+    """
+    n = len(coords)
+    win_key, inner = window_and_inner_keys(coords, grid, win, shift, axis)
+    order = np.lexsort((inner, win_key))            # sort voxel ids by (window, inner key)
+    keys, starts, counts = np.unique(win_key[order], return_index=True, return_counts=True)
+    rows, set_win = [], []
+    for wk, base, N in zip(keys, starts, counts):
+        N = int(N)
+        S = N // tau + (1 if N % tau > 0 else 0)                    # Eq. (2)
+        t = np.arange(S * tau, dtype=np.int64)                      # t = j*tau + k
+        q = (t * N) // (S * tau)                                    # Eq. (3), exact floor
+        rows.append(order[base + q].reshape(S, tau))                # Eq. (4): INDEX by inner-window rank
+        set_win += [wk] * S
+    set_inds = np.concatenate(rows, 0) if rows else np.zeros((0, tau), np.int64)
+    flat = set_inds.reshape(-1)
+    voxel_slot = np.full(n, -1, dtype=np.int64)
+    u, first = np.unique(flat, return_index=True)
+    voxel_slot[u] = first
+    return dict(set_inds=set_inds.astype(np.int32), voxel_slot=voxel_slot.astype(np.int32),
+                set_win=np.asarray(set_win, dtype=np.int32), n_sets=len(set_inds), tau=tau,
+                win_keys=keys, win_counts=counts)
+
+
+# ----------------------------------------------------------------------------
+# Layer pieces (appendix "Network Architecture")
+# ----------------------------------------------------------------------------
+def layer_norm(x, g, b, eps):
+    mu = x.mean(-1, keepdims=True)
+    var = ((x - mu) ** 2).mean(-1, keepdims=True)
+    return (x - mu) / np.sqrt(var + eps) * g + b
+
+
+def gelu(x):
+    return 0.5 * x * (1.0 + erf(x / np.sqrt(2.0)))
+
+
+def softmax_rows(logits):
+    m = logits.max(-1, keepdims=True)
+    e = np.exp(logits - m)
+    return e / e.sum(-1, keepdims=True)
+
+
+def rel_index(o_query, o_key, win):
+    """Index into a head's relative-position table for coordinate difference query - key."""
+    L, W, H = win
+    d = o_query - o_key
+    return ((d[..., 0] + L - 1) * (2 * W - 1) + (d[..., 1] + W - 1)) * (2 * H - 1) + (d[..., 2] + H - 1)
+
+
+def set_attention(w, maps, coords, x, dup_mode=0, chunk=1024):
+    """y[N,C] = per-set multi-head self-attention (Eq. 5), out-projected and returned per voxel.
+
+    dup_mode 0: a slot that repeats the previous slot's voxel is masked as a key, so every
+    set member counts once.  dup_mode 1: repeats stay as keys.
+    """
+    x = np.asarray(x, F64)
+    C, h = w["C"], w["heads"]
+    d = C // h
+    set_inds = maps["set_inds"].astype(np.int64)
+    S, tau = set_inds.shape
+    wqkv, bqkv = np.asarray(w["w_qkv"], F64), np.asarray(w["b_qkv"], F64)
+    wo, bo = np.asarray(w["w_o"], F64), np.asarray(w["b_o"], F64)
+    table = None if w.get("rel_bias") is None else np.asarray(w["rel_bias"], F64)
+    xyz = np.asarray(coords, np.int64)[:, 1:4]
+    Y = np.empty((S, tau, C), F64)
+    for s0 in range(0, S, chunk):                       # sets are independent: chunks only bound memory
+        inds = set_inds[s0:s0 + chunk]
+        F = x[inds]                                     # INDEX, Eq. (4): [s,tau,C]
+        O = xyz[inds]                                   #                  [s,tau,3]
+        qkv = F @ wqkv.T + bqkv
+        q, k, v = (qkv[..., i * C:(i + 1) * C].reshape(-1, tau, h, d).transpose(0, 2, 1, 3) for i in range(3))
+        logits = q @ k.transpose(0, 1, 3, 2) / np.sqrt(d)          # [s,h,tau(query),tau(key)]
+        if table is not None:
+            idx = rel_index(O[:, :, None, :], O[:, None, :, :], w["win"])     # [s,query,key]
+            logits = logits + table[:, idx].transpose(1, 0, 2, 3)
+        if dup_mode == 0:
+            dup = np.zeros(inds.shape, bool)
+            dup[:, 1:] = inds[:, 1:] == inds[:, :-1]
+            logits = np.where(dup[:, None, None, :], -np.inf, logits)
+        p = softmax_rows(logits)
+        o = (p @ v).transpose(0, 2, 1, 3).reshape(-1, tau, C)
+        Y[s0:s0 + chunk] = o @ wo.T + bo
+    return Y.reshape(S * tau, C)[maps["voxel_slot"].astype(np.int64)]
+
+
+def layer(w, maps, coords, x, dup_mode=0):
+    """One DSVT layer: x1 = LN(x + MHSA(x)); x2 = LN(x1 + MLP(x1))."""
+    x = np.asarray(x, F64)
+    x1 = layer_norm(x + set_attention(w, maps, coords, x, dup_mode),
+                    np.asarray(w["ln1_g"], F64), np.asarray(w["ln1_b"], F64), w["ln_eps"])
+    hid = gelu(x1 @ np.asarray(w["w_1"], F64).T + np.asarray(w["b_1"], F64))
+    mlp = hid @ np.asarray(w["w_2"], F64).T + np.asarray(w["b_2"], F64)
+    return layer_norm(x1 + mlp, np.asarray(w["ln2_g"], F64), np.asarray(w["ln2_b"], F64), w["ln_eps"])
+
+
+def block(w_pair, maps_pair, coords, x, dup_mode=0):
+    """One DSVT block: X-axis layer then Y-axis layer (Eq. 5)."""
+    x = layer(w_pair[0], maps_pair[0], coords, x, dup_mode)
+    return layer(w_pair[1], maps_pair[1], coords, x, dup_mode)
+
+
+def stack(weights, coords, x, grid, win, shifts, tau, dup_mode=0):
+    """Backbone of len(weights) blocks; block b uses window shift shifts[b % len(shifts)]."""
+    maps = {}
+    for b, w_pair in enumerate(weights):
+        sh = tuple(shifts[b % len(shifts)])
+        if sh not in maps:
+            maps[sh] = [partition(coords, grid, win, sh, tau, axis) for axis in (0, 1)]
+        x = block(w_pair, maps[sh], coords, x, dup_mode)
+    return x
+
+
+# ----------------------------------------------------------------------------
+# Attention-style 3D pooling (Sec. 3.3, Eq. 6-7)
+# ----------------------------------------------------------------------------
+def attn_pool(w, coords, x, grid, pool, mask_empty=1):
+    """Pool every non-empty l x w x h region to one voxel.
+
+    Returns (out_coords int32 [M,4] in ascending region key, out float64 [M,C]).
+    Query = channel-wise max over the region's occupied voxels (Eq. 6); keys/values = the
+    densified region (Eq. 7): occupied slots only when mask_empty == 1, all l*w*h slots with
+    zero features in the holes when mask_empty == 0.
+    """
+    x = np.asarray(x, F64)
+    c = np.asarray(coords, np.int64)
+    C, h = w["C"], w["heads"]
+    d = C // h
+    pl, pw, ph = pool
+    Xp, Yp, Zp = (grid[0] + pl - 1) // pl, (grid[1] + pw - 1) // pw, (grid[2] + ph - 1) // ph
+    rx, ry, rz = c[:, 1] // pl, c[:, 2] // pw, c[:, 3] // ph
+    key = ((c[:, 0] * Xp + rx) * Yp + ry) * Zp + rz
+    slot = ((c[:, 1] % pl) * pw + (c[:, 2] % pw)) * ph + (c[:, 3] % ph)
+    ukeys, region = np.unique(key, return_inverse=True)
+    M, P = len(ukeys), pl * pw * ph
+    dense = np.zeros((M, P, C), F64)                    # region padded to dense
+    occ = np.zeros((M, P), bool)
+    dense[region, slot] = x
+    occ[region, slot] = True
+    pooled = np.where(occ[:, :, None], dense, -np.inf).max(1)          # Eq. (6)
+    g = lambda name: np.asarray(w[name], F64)
+    q = (pooled @ g("w_q").T + g("b_q")).reshape(M, h, 1, d)
+    k = (dense @ g("w_k").T + g("b_k")).reshape(M, P, h, d).transpose(0, 2, 1, 3)
+    v = (dense @ g("w_v").T + g("b_v")).reshape(M, P, h, d).transpose(0, 2, 1, 3)
+    logits = (q @ k.transpose(0, 1, 3, 2)) / np.sqrt(d)                # [M,h,1,P]
+    if mask_empty:
+        logits = np.where(occ[:, None, None, :], logits, -np.inf)
+    o = (softmax_rows(logits) @ v).reshape(M, C)                       # Eq. (7)
+    out = layer_norm(pooled + o @ g("w_o").T + g("b_o"), g("ln_g"), g("ln_b"), w["ln_eps"])
+    out_coords = np.stack([ukeys // (Xp * Yp * Zp), (ukeys // (Yp * Zp)) % Xp, (ukeys // Zp) % Yp, ukeys % Zp], 1)
+    return out_coords.astype(np.int32), out
