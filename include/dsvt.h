@@ -1,0 +1,162 @@
+/*
+ * dsvt.h -- C ABI of libdsvt: Dynamic Sparse Window Attention (DSVT, arXiv 2301.06051)
+ * for AMD MI355X (gfx950).
+ *
+ * Conventions for every entry point
+ *   - Plain C, one shared object.  No entry point allocates, frees or keeps any pointer.
+ *   - Pointers marked [device] are device memory owned by the caller; pointers marked
+ *     [host] are ordinary host memory.  Structs themselves are read on the host.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the null
+ *     stream) and the call returns without waiting for it.
+ *   - Row-major arrays; matrix weights are [out, in].  Feature arrays and matrix weights
+ *     share one element type (`dtype`): DSVT_F32 or DSVT_BF16.  Biases, LayerNorm
+ *     parameters and the relative-position table are always float.
+ *   - Return value: DSVT_OK, or a negative code for what the host can see (bad argument,
+ *     unsupported shape, workspace too small, launch failure).  Nothing is enqueued when a
+ *     negative code is returned.  Errors only a kernel can see (a coordinate outside the
+ *     grid, a repeated coordinate, more sets than `max_sets`) OR bits into the caller's
+ *     [device] `status` word; outputs are then unspecified but no access leaves the
+ *     caller's buffers.
+ *   - Voxel coordinates are int32 rows (b, x, y, z), 0 <= b < batch, unique per call.
+ */
+#ifndef DSVT_H
+#define DSVT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { DSVT_OK = 0, DSVT_EINVAL = -1, DSVT_ENOSPC = -2, DSVT_EHIP = -3, DSVT_EUNSUPPORTED = -4 };
+enum { DSVT_F32 = 0, DSVT_BF16 = 1 };
+/* bits of the device status word */
+enum { DSVT_ST_COORD_RANGE = 1, DSVT_ST_COORD_REPEAT = 2, DSVT_ST_SET_OVERFLOW = 4 };
+
+/* ---------------------------------------------------------------------------------------
+ * Set partition (Sec. 3.2 "Dynamic set partition", Eq. 2-4; "Rotated set attention";
+ * "Hybrid window partition").
+ * ------------------------------------------------------------------------------------ */
+typedef struct {
+  int32_t grid[3];  /* cells along X, Y, Z                                             */
+  int32_t win[3];   /* window size L, W, H in cells                                    */
+  int32_t shift[3]; /* cells added to (x,y,z) before the window split; 0 <= shift < win */
+  int32_t tau;      /* set size: slots per set                                         */
+  int32_t batch;    /* frames in the call; b is the top digit of the window key        */
+  int32_t axis;     /* inner-window order: 0 = x,y,z most-to-least significant (X-axis
+                       main order), 1 = y,x,z (Y-axis main order)                       */
+} dsvt_part_cfg;
+
+/* Host-only.  Upper bound on the number of sets, floor(N/tau) + min(N, #windows), and the
+ * bytes of scratch dsvt_partition needs for n_voxels voxels.  Either output may be NULL. */
+int dsvt_partition_bound(const dsvt_part_cfg* cfg, int32_t n_voxels, int32_t* max_sets, size_t* ws_bytes);
+
+/* Builds the slot maps of one (window configuration, axis).
+ *   window key  = ((b*nWx + (x+sx)/L)*nWy + (y+sy)/W)*nWz + (z+sz)/H, nW* = ceil((grid+shift)/win)
+ *   per window with N voxels: S = ceil(N/tau) sets (Eq. 2); slot k of its j-th set holds the
+ *   voxel of inner-window rank floor((j*tau+k)*N / (S*tau)) (Eq. 3, exact integer floor).
+ *   Windows are taken in ascending key, sets of a window in ascending j.
+ * coords     [device] int32 [n_voxels,4]
+ * set_inds   [device] int32 [max_sets,tau] out: voxel index per slot; rows >= *n_sets untouched
+ * voxel_slot [device] int32 [n_voxels]     out: smallest flat slot s*tau+k that holds the voxel
+ * n_sets     [device] int32 scalar         out: total number of sets
+ * set_win    [device] int32 [max_sets]     out: window key of every set; may be NULL
+ * ws         [device] scratch of at least the bytes dsvt_partition_bound reports
+ * status     [device] int32 word, OR-ed with DSVT_ST_* bits (the caller zeroes it)
+ * Errors: DSVT_EINVAL (NULL pointer, non-positive size, shift outside [0,win), axis not 0/1,
+ * key space of 2^31 or more cells), DSVT_ENOSPC (ws_bytes too small), DSVT_EHIP. */
+int dsvt_partition(const dsvt_part_cfg* cfg, const int32_t* coords, int32_t n_voxels,
+                   int32_t* set_inds, int32_t* voxel_slot, int32_t* n_sets, int32_t max_sets,
+                   int32_t* set_win, void* ws, size_t ws_bytes, int32_t* status, void* stream);
+
+/* The maps one layer consumes (outputs of dsvt_partition, all [device]). */
+typedef struct {
+  int32_t n_voxels, max_sets, tau;
+  const int32_t* set_inds;   /* [max_sets,tau]                                          */
+  const int32_t* voxel_slot; /* [n_voxels]; the attention kernels re-derive the first-occurrence
+                                rule from set_inds on chip and do not read it: may be NULL */
+  const int32_t* n_sets;     /* scalar, <= max_sets                                     */
+} dsvt_maps;
+
+/* ---------------------------------------------------------------------------------------
+ * One DSVT layer's parameters (appendix "Network Architecture": MHSA, residual, LN,
+ * MLP C -> hidden -> C with GELU, residual, LN; Eq. 5 for PE).
+ * ------------------------------------------------------------------------------------ */
+typedef struct {
+  int32_t C, heads, hidden, dtype;
+  const void *w_qkv; /* [3C,C] rows: Q outputs, then K, then V     [device] */
+  const void *w_o;   /* [C,C]                                       [device] */
+  const void *w_1;   /* [hidden,C]                                  [device] */
+  const void *w_2;   /* [C,hidden]                                  [device] */
+  const float *b_qkv, *b_o, *b_1, *b_2;            /* [3C] [C] [hidden] [C]  [device] */
+  const float *ln1_g, *ln1_b, *ln2_g, *ln2_b;      /* [C] each               [device] */
+  float ln_eps;
+  const float* rel_bias; /* [device] [heads, (2L-1)(2W-1)(2H-1)] added to the logit of (query a,
+                            key b) at index ((xa-xb+L-1)*(2W-1) + ya-yb+W-1)*(2H-1) + za-zb+H-1;
+                            NULL = no positional term                                    */
+  int32_t win[3];        /* L, W, H of the window the maps were built with               */
+  int32_t dup_mode;      /* 0: a slot repeating its predecessor's voxel is masked as a key
+                               (sentence after Eq. 3); 1: repeated slots stay as keys    */
+} dsvt_layer_w;
+
+/* Supported shapes: (C,heads,hidden) = (64,4,128) in F32 or BF16 and (192,8,384) in BF16, tau <= 48;
+ * anything else returns DSVT_EUNSUPPORTED. */
+
+/* Host-only: scratch bytes the two calls below need (currently 0; callers must still ask). */
+int dsvt_block_workspace_size(const dsvt_layer_w* layer, int32_t n_voxels, size_t* bytes);
+
+/* y = MHSA over every set (Eq. 5, first two lines: INDEX, then attention with PE), out-projected
+ * and returned per voxel; no residual, LN or MLP.
+ * coords [device] int32 [N,4]; x [device] [N,C] in; y [device] [N,C] out (must not alias x). */
+int dsvt_set_attention(const dsvt_layer_w* layer, const dsvt_maps* maps, const int32_t* coords,
+                       const void* x, void* y, void* ws, size_t ws_bytes, void* stream);
+
+/* One DSVT block (Eq. 5, Fig. 3): the full layer with maps[0] (X-axis partition), then the full
+ * layer with maps[1] (Y-axis partition).  x_out [device] [N,C] may be x_in itself. */
+int dsvt_block(const dsvt_layer_w layer[2], const dsvt_maps maps[2], const int32_t* coords,
+               const void* x_in, void* x_out, void* ws, size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------
+ * Attention-style 3D pooling (Sec. 3.3, Eq. 6-7).
+ * ------------------------------------------------------------------------------------ */
+typedef struct {
+  int32_t grid[3];  /* input cells X, Y, Z                                              */
+  int32_t pool[3];  /* region l, w, h in cells; l*w*h <= 8                               */
+  int32_t batch, C, heads, dtype;
+  const void *w_q, *w_k, *w_v, *w_o;             /* [C,C] each   [device] */
+  const float *b_q, *b_k, *b_v, *b_o, *ln_g, *ln_b; /* [C] each  [device] */
+  float ln_eps;
+  int32_t mask_empty; /* 1: keys/values are the region's occupied voxels; 0: all l*w*h slots,
+                         holes carrying zero features (so their key/value are the biases) */
+} dsvt_pool_cfg;
+
+int dsvt_attn_pool_workspace_size(const dsvt_pool_cfg* cfg, int32_t n_voxels, size_t* bytes);
+
+/* Every non-empty region (b, x/l, y/w, z/h) becomes one output voxel, in ascending key
+ * ((b*Xp + x/l)*Yp + y/w)*Zp + z/h.  P = channel-wise max over the region's voxels (Eq. 6) is the
+ * query; out = LN(P + Attn(Q = P, KV = region) W_o + b_o) (Eq. 7).
+ * out_coords [device] int32 [n_voxels,4] (first *n_out rows written: b, x/l, y/w, z/h)
+ * out        [device] [n_voxels,C]       (first *n_out rows written)
+ * n_out      [device] int32 scalar */
+int dsvt_attn_pool(const dsvt_pool_cfg* cfg, const int32_t* coords, const void* x, int32_t n_voxels,
+                   int32_t* out_coords, void* out, int32_t* n_out,
+                   void* ws, size_t ws_bytes, int32_t* status, void* stream);
+
+/* ---------------------------------------------------------------------------------------
+ * Instrumentation for benchmarks (not part of the method): per-kernel time from hipEvent pairs
+ * recorded around every launch while enabled.  Host-only; not thread-safe.
+ * dsvt_prof_enable creates events for up to max_launches launches (later ones go unrecorded);
+ * dsvt_prof_collect waits for them, fills total_ms[k] / launches[k] for the
+ * dsvt_prof_kernel_count() kernel ids (names from dsvt_prof_kernel_name), destroys the events
+ * and switches recording off.
+ * ------------------------------------------------------------------------------------ */
+int dsvt_prof_enable(int32_t max_launches);
+int dsvt_prof_collect(float* total_ms /*[host]*/, int32_t* launches /*[host]*/, int32_t n_kernels);
+int32_t dsvt_prof_kernel_count(void);
+const char* dsvt_prof_kernel_name(int32_t id);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DSVT_H */

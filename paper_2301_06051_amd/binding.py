@@ -1,0 +1,234 @@
+"""ctypes binding of libdsvt.so: argument marshalling only.
+
+Every step of the path runs inside the HIP library; PyTorch supplies device memory and the
+stream.  There is no CPU fallback: a missing library raises.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libdsvt.so")
+
+DSVT_OK, DSVT_EINVAL, DSVT_ENOSPC, DSVT_EHIP, DSVT_EUNSUPPORTED = 0, -1, -2, -3, -4
+DSVT_F32, DSVT_BF16 = 0, 1
+ST_COORD_RANGE, ST_COORD_REPEAT, ST_SET_OVERFLOW = 1, 2, 4
+_ERR = {-1: "DSVT_EINVAL", -2: "DSVT_ENOSPC", -3: "DSVT_EHIP", -4: "DSVT_EUNSUPPORTED"}
+_DT = {"f32": (DSVT_F32, torch.float32), "bf16": (DSVT_BF16, torch.bfloat16)}
+
+I32x3 = C.c_int32 * 3
+
+
+class PartCfg(C.Structure):
+    _fields_ = [("grid", I32x3), ("win", I32x3), ("shift", I32x3), ("tau", C.c_int32), ("batch", C.c_int32),
+                ("axis", C.c_int32)]
+
+
+class Maps(C.Structure):
+    _fields_ = [("n_voxels", C.c_int32), ("max_sets", C.c_int32), ("tau", C.c_int32), ("set_inds", C.c_void_p),
+                ("voxel_slot", C.c_void_p), ("n_sets", C.c_void_p)]
+
+
+class LayerW(C.Structure):
+    _fields_ = [("C", C.c_int32), ("heads", C.c_int32), ("hidden", C.c_int32), ("dtype", C.c_int32),
+                ("w_qkv", C.c_void_p), ("w_o", C.c_void_p), ("w_1", C.c_void_p), ("w_2", C.c_void_p),
+                ("b_qkv", C.c_void_p), ("b_o", C.c_void_p), ("b_1", C.c_void_p), ("b_2", C.c_void_p),
+                ("ln1_g", C.c_void_p), ("ln1_b", C.c_void_p), ("ln2_g", C.c_void_p), ("ln2_b", C.c_void_p),
+                ("ln_eps", C.c_float), ("rel_bias", C.c_void_p), ("win", I32x3), ("dup_mode", C.c_int32)]
+
+
+class PoolCfg(C.Structure):
+    _fields_ = [("grid", I32x3), ("pool", I32x3), ("batch", C.c_int32), ("C", C.c_int32), ("heads", C.c_int32),
+                ("dtype", C.c_int32), ("w_q", C.c_void_p), ("w_k", C.c_void_p), ("w_v", C.c_void_p),
+                ("w_o", C.c_void_p), ("b_q", C.c_void_p), ("b_k", C.c_void_p), ("b_v", C.c_void_p),
+                ("b_o", C.c_void_p), ("ln_g", C.c_void_p), ("ln_b", C.c_void_p), ("ln_eps", C.c_float),
+                ("mask_empty", C.c_int32)]
+
+
+_lib = None
+
+
+def lib():
+    """The loaded C-ABI library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                               "(there is no fallback path)")
+        L = C.CDLL(LIB_PATH)
+        vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
+        L.dsvt_partition_bound.argtypes = [C.POINTER(PartCfg), i32, C.POINTER(i32), C.POINTER(sz)]
+        L.dsvt_partition.argtypes = [C.POINTER(PartCfg), vp, i32, vp, vp, vp, i32, vp, vp, sz, vp, vp]
+        L.dsvt_block_workspace_size.argtypes = [C.POINTER(LayerW), i32, C.POINTER(sz)]
+        L.dsvt_set_attention.argtypes = [C.POINTER(LayerW), C.POINTER(Maps), vp, vp, vp, vp, sz, vp]
+        L.dsvt_block.argtypes = [C.POINTER(LayerW), C.POINTER(Maps), vp, vp, vp, vp, sz, vp]
+        L.dsvt_attn_pool_workspace_size.argtypes = [C.POINTER(PoolCfg), i32, C.POINTER(sz)]
+        L.dsvt_attn_pool.argtypes = [C.POINTER(PoolCfg), vp, vp, i32, vp, vp, vp, vp, sz, vp, vp]
+        L.dsvt_prof_enable.argtypes = [i32]
+        L.dsvt_prof_collect.argtypes = [C.POINTER(C.c_float), C.POINTER(i32), i32]
+        L.dsvt_prof_kernel_count.restype = i32
+        L.dsvt_prof_kernel_name.argtypes = [i32]
+        L.dsvt_prof_kernel_name.restype = C.c_char_p
+        _lib = L
+    return _lib
+
+
+class DsvtError(RuntimeError):
+    def __init__(self, where, rc):
+        super().__init__(f"{where} returned {_ERR.get(rc, rc)}")
+        self.rc = rc
+
+
+def _check(where, rc):
+    if rc != DSVT_OK:
+        raise DsvtError(where, rc)
+
+
+def _stream(stream):
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream if stream is None else stream)
+
+
+def _ptr(t):
+    return C.c_void_p(0 if t is None else t.data_ptr())
+
+
+def _dev(a, dtype):
+    return torch.as_tensor(np.ascontiguousarray(a)).to(device="cuda", dtype=dtype).contiguous()
+
+
+def part_cfg(grid, win, shift, tau, batch, axis):
+    return PartCfg(I32x3(*grid), I32x3(*win), I32x3(*shift), tau, batch, axis)
+
+
+def dsvt_partition_bound(cfg, n_voxels):
+    ms, ws = C.c_int32(0), C.c_size_t(0)
+    _check("dsvt_partition_bound", lib().dsvt_partition_bound(C.byref(cfg), n_voxels, C.byref(ms), C.byref(ws)))
+    return ms.value, ws.value
+
+
+class SetMaps:
+    """Device buffers of one (window configuration, axis) and the struct the kernels read."""
+
+    def __init__(self, cfg, n_voxels, max_sets=None):
+        bound, ws_bytes = dsvt_partition_bound(cfg, n_voxels)
+        self.cfg, self.n_voxels, self.tau = cfg, n_voxels, cfg.tau
+        self.max_sets = bound if max_sets is None else max_sets
+        i32 = dict(dtype=torch.int32, device="cuda")
+        self.set_inds = torch.full((self.max_sets, cfg.tau), -1, **i32)
+        self.voxel_slot = torch.full((n_voxels,), -1, **i32)
+        self.set_win = torch.full((self.max_sets,), -1, **i32)
+        self.n_sets = torch.zeros((1,), **i32)
+        self.status = torch.zeros((1,), **i32)
+        self.ws = torch.empty((ws_bytes,), dtype=torch.uint8, device="cuda")
+        self.struct = Maps(n_voxels, self.max_sets, cfg.tau, self.set_inds.data_ptr(), self.voxel_slot.data_ptr(),
+                           self.n_sets.data_ptr())
+
+
+def dsvt_partition(cfg, coords, out=None, stream=None):
+    """coords: int32 cuda tensor [N,4].  Returns the SetMaps it filled (allocated here unless given)."""
+    assert coords.is_cuda and coords.dtype == torch.int32 and coords.is_contiguous() and coords.shape[1] == 4
+    n = coords.shape[0]
+    out = SetMaps(cfg, n) if out is None else out
+    assert out.n_voxels == n
+    rc = lib().dsvt_partition(C.byref(cfg), _ptr(coords), n, _ptr(out.set_inds), _ptr(out.voxel_slot),
+                              _ptr(out.n_sets), out.max_sets, _ptr(out.set_win), _ptr(out.ws), out.ws.numel(),
+                              _ptr(out.status), _stream(stream))
+    _check("dsvt_partition", rc)
+    return out
+
+
+class LayerWeights:
+    """Device copy of one DSVT layer's parameters (from a synth-style dict of numpy arrays)."""
+
+    def __init__(self, w, dup_mode=0):
+        code, tdt = _DT[w["dtype"]]
+        f32 = torch.float32
+        self.t = {k: _dev(w[k], tdt) for k in ("w_qkv", "w_o", "w_1", "w_2")}
+        self.t.update({k: _dev(w[k], f32) for k in ("b_qkv", "b_o", "b_1", "b_2", "ln1_g", "ln1_b", "ln2_g", "ln2_b")})
+        self.t["rel_bias"] = None if w.get("rel_bias") is None else _dev(w["rel_bias"], f32)
+        self.dtype, self.C = tdt, w["C"]
+        p = lambda k: self.t[k].data_ptr() if self.t[k] is not None else None
+        self.struct = LayerW(w["C"], w["heads"], w["hidden"], code, p("w_qkv"), p("w_o"), p("w_1"), p("w_2"),
+                             p("b_qkv"), p("b_o"), p("b_1"), p("b_2"), p("ln1_g"), p("ln1_b"), p("ln2_g"), p("ln2_b"),
+                             w["ln_eps"], p("rel_bias"), I32x3(*w["win"]), dup_mode)
+
+
+def dsvt_block_workspace_size(layer, n_voxels):
+    sz = C.c_size_t(0)
+    _check("dsvt_block_workspace_size", lib().dsvt_block_workspace_size(C.byref(layer.struct), n_voxels, C.byref(sz)))
+    return sz.value
+
+
+def _ws(nbytes, ws):
+    if ws is None:
+        ws = torch.empty((max(nbytes, 1),), dtype=torch.uint8, device="cuda")
+    return ws
+
+
+def dsvt_set_attention(layer, maps, coords, x, y=None, ws=None, stream=None):
+    assert x.is_cuda and x.dtype == layer.dtype and x.is_contiguous() and x.shape == (maps.n_voxels, layer.C)
+    y = torch.empty_like(x) if y is None else y
+    ws = _ws(dsvt_block_workspace_size(layer, maps.n_voxels), ws)
+    rc = lib().dsvt_set_attention(C.byref(layer.struct), C.byref(maps.struct), _ptr(coords), _ptr(x), _ptr(y),
+                                  _ptr(ws), ws.numel(), _stream(stream))
+    _check("dsvt_set_attention", rc)
+    return y
+
+
+def dsvt_block(layers, maps, coords, x_in, x_out=None, ws=None, stream=None):
+    """layers: (X-axis LayerWeights, Y-axis LayerWeights); maps: (X-axis SetMaps, Y-axis SetMaps)."""
+    assert x_in.is_cuda and x_in.dtype == layers[0].dtype and x_in.is_contiguous()
+    x_out = torch.empty_like(x_in) if x_out is None else x_out
+    ws = _ws(dsvt_block_workspace_size(layers[0], maps[0].n_voxels), ws)
+    lw = (LayerW * 2)(layers[0].struct, layers[1].struct)
+    mp = (Maps * 2)(maps[0].struct, maps[1].struct)
+    rc = lib().dsvt_block(lw, mp, _ptr(coords), _ptr(x_in), _ptr(x_out), _ptr(ws), ws.numel(), _stream(stream))
+    _check("dsvt_block", rc)
+    return x_out
+
+
+class PoolWeights:
+    def __init__(self, w, grid, pool, batch, mask_empty=1):
+        code, tdt = _DT[w["dtype"]]
+        self.t = {k: _dev(w[k], tdt) for k in ("w_q", "w_k", "w_v", "w_o")}
+        self.t.update({k: _dev(w[k], torch.float32) for k in ("b_q", "b_k", "b_v", "b_o", "ln_g", "ln_b")})
+        self.dtype, self.C = tdt, w["C"]
+        p = lambda k: self.t[k].data_ptr()
+        self.struct = PoolCfg(I32x3(*grid), I32x3(*pool), batch, w["C"], w["heads"], code, p("w_q"), p("w_k"),
+                              p("w_v"), p("w_o"), p("b_q"), p("b_k"), p("b_v"), p("b_o"), p("ln_g"), p("ln_b"),
+                              w["ln_eps"], mask_empty)
+
+
+def dsvt_attn_pool_workspace_size(pool, n_voxels):
+    sz = C.c_size_t(0)
+    _check("dsvt_attn_pool_workspace_size",
+           lib().dsvt_attn_pool_workspace_size(C.byref(pool.struct), n_voxels, C.byref(sz)))
+    return sz.value
+
+
+def dsvt_attn_pool(pool, coords, x, out=None, ws=None, stream=None):
+    """Returns (out_coords [N,4], out [N,C], n_out device scalar, status); the first n_out rows are valid."""
+    n = coords.shape[0]
+    assert x.is_cuda and x.dtype == pool.dtype and x.is_contiguous() and x.shape == (n, pool.C)
+    if out is None:
+        out = (torch.zeros((n, 4), dtype=torch.int32, device="cuda"), torch.zeros_like(x),
+               torch.zeros((1,), dtype=torch.int32, device="cuda"), torch.zeros((1,), dtype=torch.int32, device="cuda"))
+    ws = _ws(dsvt_attn_pool_workspace_size(pool, n), ws)
+    rc = lib().dsvt_attn_pool(C.byref(pool.struct), _ptr(coords), _ptr(x), n, _ptr(out[0]), _ptr(out[1]), _ptr(out[2]),
+                              _ptr(ws), ws.numel(), _ptr(out[3]), _stream(stream))
+    _check("dsvt_attn_pool", rc)
+    return out
+
+
+def prof_enable(max_launches):
+    _check("dsvt_prof_enable", lib().dsvt_prof_enable(max_launches))
+
+
+def prof_collect():
+    """{kernel name: (total ms, launches)} for the launches recorded since prof_enable."""
+    n = lib().dsvt_prof_kernel_count()
+    ms, cnt = (C.c_float * n)(), (C.c_int32 * n)()
+    _check("dsvt_prof_collect", lib().dsvt_prof_collect(ms, cnt, n))
+    return {lib().dsvt_prof_kernel_name(k).decode(): (float(ms[k]), int(cnt[k])) for k in range(n)}

@@ -1,0 +1,231 @@
+// dsvt_partition: rotated dynamic set partition (Sec. 3.2, Eq. 2-4) on gfx950.
+//
+// Voxel cells are unique, so the sort by (window key, inner-window key) is done without
+// comparing anything: every voxel sets one bit in an occupancy bitmap laid out as
+// [window][inner key], and a voxel's inner-window rank is the number of set bits before its
+// own inside its window's bit range.  Per window a wavefront (or a slice of one) pop-counts
+// the words and leaves a running prefix per word; one scan over the windows turns voxel and
+// set counts into offsets; then every voxel writes the slots that Eq. (3) assigns to its rank:
+//   floor(t*N/(S*tau)) == d   <=>   ceil(d*S*tau/N) <= t < ceil((d+1)*S*tau/N).
+#include "common.h"
+
+namespace {
+
+constexpr uint32_t kBadKey = 0xFFFFFFFFu;
+
+struct PartGeom {
+  int32_t grid[3], win[3], shift[3], nw[3];
+  int32_t batch, tau, axis;
+  int32_t words_per_win;   // 32-bit bitmap words per window (window volume rounded up to 32)
+  int32_t n_windows;       // batch * nw[0] * nw[1] * nw[2]
+};
+
+__global__ void k_clear(uint32_t* __restrict__ words, int64_t n) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) words[i] = 0u;
+}
+
+// One thread per voxel: composite key = window key * (32*words_per_win) + inner key; set its bit.
+__global__ void k_mark(PartGeom g, const int4* __restrict__ coords, int32_t n, uint32_t* __restrict__ bitmap,
+                       uint32_t* __restrict__ keys, int32_t* __restrict__ status) {
+  int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  int4 c = coords[i];                       // (b, x, y, z)
+  bool ok = c.x >= 0 && c.x < g.batch && c.y >= 0 && c.y < g.grid[0] && c.z >= 0 && c.z < g.grid[1] &&
+            c.w >= 0 && c.w < g.grid[2];
+  if (!ok) {
+    keys[i] = kBadKey;
+    atomicOr(status, DSVT_ST_COORD_RANGE);
+    return;
+  }
+  int32_t x = c.y + g.shift[0], y = c.z + g.shift[1], z = c.w + g.shift[2];
+  int32_t wx = x / g.win[0], wy = y / g.win[1], wz = z / g.win[2];
+  int32_t xi = x - wx * g.win[0], yi = y - wy * g.win[1], zi = z - wz * g.win[2];
+  uint32_t wkey = (uint32_t)(((c.x * g.nw[0] + wx) * g.nw[1] + wy) * g.nw[2] + wz);
+  uint32_t inner = g.axis == 0 ? (uint32_t)((xi * g.win[1] + yi) * g.win[2] + zi)
+                               : (uint32_t)((yi * g.win[0] + xi) * g.win[2] + zi);
+  uint32_t key = wkey * (uint32_t)(g.words_per_win * 32) + inner;
+  uint32_t bit = 1u << (key & 31u);
+  uint32_t old = atomicOr(&bitmap[key >> 5], bit);
+  if (old & bit) atomicOr(status, DSVT_ST_COORD_REPEAT);
+  keys[i] = key;
+}
+
+// `group` lanes (a power of two <= 64) per window: pop-count the window's words, leave in
+// word_prefix[] the number of set bits in the window's earlier words, and the window total.
+__global__ void k_window_count(const uint32_t* __restrict__ bitmap, uint32_t* __restrict__ word_prefix,
+                               int32_t* __restrict__ win_count, int32_t n_windows, int32_t words_per_win,
+                               int32_t group) {
+  int32_t tid = blockIdx.x * blockDim.x + threadIdx.x;
+  int32_t w = tid / group, lane = tid & (group - 1);
+  if (w >= n_windows) return;               // whole groups leave together
+  const int64_t base = (int64_t)w * words_per_win;
+  uint32_t running = 0;
+  for (int32_t w0 = 0; w0 < words_per_win; w0 += group) {
+    int32_t j = w0 + lane;
+    uint32_t v = j < words_per_win ? (uint32_t)__popc(bitmap[base + j]) : 0u;
+    uint32_t incl = v;
+    for (int32_t d = 1; d < group; d <<= 1) {
+      uint32_t up = __shfl_up(incl, d, group);
+      if (lane >= d) incl += up;
+    }
+    if (j < words_per_win) word_prefix[base + j] = running + incl - v;
+    running += __shfl(incl, group - 1, group);
+  }
+  if (lane == 0) win_count[w] = (int32_t)running;
+}
+
+// One workgroup: exclusive scans of voxels-per-window and sets-per-window (Eq. 2).
+__global__ void __launch_bounds__(1024) k_scan_windows(const int32_t* __restrict__ win_count,
+                                                       int32_t* __restrict__ win_soff, int32_t n_windows,
+                                                       int32_t tau, int32_t max_sets, int32_t* __restrict__ n_sets,
+                                                       int32_t* __restrict__ status) {
+  __shared__ int32_t wave_tot[16];
+  __shared__ int32_t carry_s;
+  const int32_t tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  if (tid == 0) carry_s = 0;
+  __syncthreads();
+  for (int32_t base = 0; base < n_windows; base += 1024) {
+    int32_t w = base + tid;
+    int32_t nvox = w < n_windows ? win_count[w] : 0;
+    int32_t s = (nvox + tau - 1) / tau;
+    int32_t incl = s;
+    for (int32_t d = 1; d < 64; d <<= 1) {
+      int32_t up = __shfl_up(incl, d, 64);
+      if (lane >= d) incl += up;
+    }
+    if (lane == 63) wave_tot[wv] = incl;
+    __syncthreads();
+    int32_t before = carry_s;
+    for (int32_t k = 0; k < wv; ++k) before += wave_tot[k];
+    if (w < n_windows) win_soff[w] = before + incl - s;
+    __syncthreads();
+    if (tid == 1023) carry_s = before + incl;
+    __syncthreads();
+  }
+  if (tid == 0) {
+    *n_sets = carry_s;
+    if (carry_s > max_sets) atomicOr(status, DSVT_ST_SET_OVERFLOW);
+  }
+}
+
+// One thread per voxel: rank d inside its window, then the slots t with floor(t*N/(S*tau)) == d.
+__global__ void k_emit(const uint32_t* __restrict__ keys, int32_t n, const uint32_t* __restrict__ bitmap,
+                       const uint32_t* __restrict__ word_prefix, const int32_t* __restrict__ win_count,
+                       const int32_t* __restrict__ win_soff, int32_t words_per_win, int32_t tau, int32_t max_sets,
+                       int32_t* __restrict__ set_inds, int32_t* __restrict__ voxel_slot,
+                       int32_t* __restrict__ set_win) {
+  int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  uint32_t key = keys[i];
+  if (key == kBadKey) { voxel_slot[i] = -1; return; }
+  uint32_t word = key >> 5, bit = key & 31u;
+  int32_t w = (int32_t)(word / (uint32_t)words_per_win);
+  int64_t d = word_prefix[word] + (uint32_t)__popc(bitmap[word] & ((1u << bit) - 1u));
+  int64_t N = win_count[w];
+  int64_t S = (N + tau - 1) / tau, T = S * tau;
+  int64_t t_lo = (d * T + N - 1) / N, t_hi = ((d + 1) * T + N - 1) / N;
+  int64_t base = (int64_t)win_soff[w] * tau, cap = (int64_t)max_sets * tau;
+  voxel_slot[i] = (int32_t)(base + t_lo);
+  for (int64_t t = t_lo; t < t_hi; ++t) {
+    int64_t slot = base + t;
+    if (slot >= cap) break;
+    set_inds[slot] = i;
+    if (set_win != nullptr && t % tau == 0) set_win[slot / tau] = w;
+  }
+}
+
+struct PartPlan {
+  PartGeom g;
+  size_t off_bitmap, off_prefix, off_count, off_soff, off_keys, total;
+  int64_t n_words;
+};
+
+int make_plan(const dsvt_part_cfg* cfg, int32_t n_voxels, PartPlan* p) {
+  if (cfg == nullptr || n_voxels <= 0 || cfg->tau <= 0 || cfg->batch <= 0 || (cfg->axis != 0 && cfg->axis != 1))
+    return DSVT_EINVAL;
+  PartGeom& g = p->g;
+  int64_t vol = 1, nwin = cfg->batch;
+  for (int a = 0; a < 3; ++a) {
+    if (cfg->grid[a] <= 0 || cfg->win[a] <= 0 || cfg->shift[a] < 0 || cfg->shift[a] >= cfg->win[a]) return DSVT_EINVAL;
+    g.grid[a] = cfg->grid[a]; g.win[a] = cfg->win[a]; g.shift[a] = cfg->shift[a];
+    g.nw[a] = (int32_t)dsvt_ceil_div((int64_t)cfg->grid[a] + cfg->shift[a], cfg->win[a]);
+    vol *= cfg->win[a];
+    nwin *= g.nw[a];
+    if (vol >= (1ll << 31) || nwin >= (1ll << 31)) return DSVT_EINVAL;
+  }
+  g.batch = cfg->batch; g.tau = cfg->tau; g.axis = cfg->axis;
+  int64_t wpw = dsvt_ceil_div(vol, 32);
+  if (nwin * wpw * 32 >= (1ll << 31)) return DSVT_EINVAL;   // composite keys are 32-bit
+  g.words_per_win = (int32_t)wpw;
+  g.n_windows = (int32_t)nwin;
+  p->n_words = nwin * wpw;
+  size_t o = 0;
+  p->off_bitmap = o; o = dsvt_align_up(o + (size_t)p->n_words * 4, 256);
+  p->off_prefix = o; o = dsvt_align_up(o + (size_t)p->n_words * 4, 256);
+  p->off_count = o;  o = dsvt_align_up(o + (size_t)nwin * 4, 256);
+  p->off_soff = o;   o = dsvt_align_up(o + (size_t)nwin * 4, 256);
+  p->off_keys = o;   o = dsvt_align_up(o + (size_t)n_voxels * 4, 256);
+  p->total = o;
+  return DSVT_OK;
+}
+
+}  // namespace
+
+extern "C" int dsvt_partition_bound(const dsvt_part_cfg* cfg, int32_t n_voxels, int32_t* max_sets, size_t* ws_bytes) {
+  PartPlan p;
+  int rc = make_plan(cfg, n_voxels, &p);
+  if (rc != DSVT_OK) return rc;
+  int64_t bound = n_voxels / cfg->tau + (n_voxels < p.g.n_windows ? n_voxels : p.g.n_windows);
+  if (bound * cfg->tau >= (1ll << 31)) return DSVT_EINVAL;
+  if (max_sets) *max_sets = (int32_t)bound;
+  if (ws_bytes) *ws_bytes = p.total;
+  return DSVT_OK;
+}
+
+extern "C" int dsvt_partition(const dsvt_part_cfg* cfg, const int32_t* coords, int32_t n_voxels, int32_t* set_inds,
+                              int32_t* voxel_slot, int32_t* n_sets, int32_t max_sets, int32_t* set_win, void* ws,
+                              size_t ws_bytes, int32_t* status, void* stream) {
+  PartPlan p;
+  int rc = make_plan(cfg, n_voxels, &p);
+  if (rc != DSVT_OK) return rc;
+  if (!coords || !set_inds || !voxel_slot || !n_sets || !ws || !status || max_sets <= 0) return DSVT_EINVAL;
+  if ((int64_t)max_sets * cfg->tau >= (1ll << 31)) return DSVT_EINVAL;
+  if (ws_bytes < p.total) return DSVT_ENOSPC;
+  hipStream_t st = (hipStream_t)stream;
+  char* base = (char*)ws;
+  uint32_t* bitmap = (uint32_t*)(base + p.off_bitmap);
+  uint32_t* prefix = (uint32_t*)(base + p.off_prefix);
+  int32_t* count = (int32_t*)(base + p.off_count);
+  int32_t* soff = (int32_t*)(base + p.off_soff);
+  uint32_t* keys = (uint32_t*)(base + p.off_keys);
+  const int tb = 256;
+  {
+    dsvt_prof_scope ps(DSVT_K_PART_CLEAR, st);
+    k_clear<<<(unsigned)dsvt_ceil_div(p.n_words, tb), tb, 0, st>>>(bitmap, p.n_words);
+  }
+  {
+    dsvt_prof_scope ps(DSVT_K_PART_MARK, st);
+    k_mark<<<(unsigned)dsvt_ceil_div(n_voxels, tb), tb, 0, st>>>(p.g, (const int4*)coords, n_voxels, bitmap, keys, status);
+  }
+  int32_t group = 1;
+  while (group < 64 && group < p.g.words_per_win) group <<= 1;
+  {
+    dsvt_prof_scope ps(DSVT_K_PART_COUNT, st);
+    int64_t threads = (int64_t)p.g.n_windows * group;
+    k_window_count<<<(unsigned)dsvt_ceil_div(threads, tb), tb, 0, st>>>(bitmap, prefix, count, p.g.n_windows,
+                                                                        p.g.words_per_win, group);
+  }
+  {
+    dsvt_prof_scope ps(DSVT_K_PART_SCAN, st);
+    k_scan_windows<<<1, 1024, 0, st>>>(count, soff, p.g.n_windows, cfg->tau, max_sets, n_sets, status);
+  }
+  {
+    dsvt_prof_scope ps(DSVT_K_PART_EMIT, st);
+    k_emit<<<(unsigned)dsvt_ceil_div(n_voxels, tb), tb, 0, st>>>(keys, n_voxels, bitmap, prefix, count, soff,
+                                                                 p.g.words_per_win, cfg->tau, max_sets, set_inds,
+                                                                 voxel_slot, set_win);
+  }
+  DSVT_HIP_TRY(hipGetLastError());
+  return DSVT_OK;
+}

@@ -1,0 +1,40 @@
+"""Helpers for the GPU parity tests: move synthetic inputs to the device, compare with the oracle."""
+import numpy as np
+import torch
+
+import paper_2301_06051_amd as dsvt
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}      # max |gpu - oracle| / max |oracle| per output tensor
+
+
+def rel_err(gpu, ref):
+    gpu = gpu.detach().to(torch.float64).cpu().numpy() if isinstance(gpu, torch.Tensor) else np.asarray(gpu, np.float64)
+    ref = np.asarray(ref, np.float64)
+    assert gpu.shape == ref.shape
+    assert np.all(np.isfinite(gpu))
+    return float(np.abs(gpu - ref).max() / np.abs(ref).max())
+
+
+def dev_coords(coords):
+    return torch.as_tensor(np.ascontiguousarray(coords, dtype=np.int32)).cuda()
+
+
+def dev_feats(x, dtype):
+    return torch.as_tensor(x).cuda().to(torch.bfloat16 if dtype == "bf16" else torch.float32).contiguous()
+
+
+def gpu_maps(coords_d, grid, win, shift, tau, batch, axis):
+    cfg = dsvt.part_cfg(grid, win, shift, tau, batch, axis)
+    return dsvt.dsvt_partition(cfg, coords_d)
+
+
+def assert_maps_equal(gm, om):
+    """Bit-exact comparison of the GPU maps with the oracle's."""
+    torch.cuda.synchronize()
+    assert int(gm.status.item()) == 0
+    n_sets = int(gm.n_sets.item())
+    assert n_sets == om["n_sets"] <= gm.max_sets
+    assert np.array_equal(gm.set_inds[:n_sets].cpu().numpy(), om["set_inds"])
+    assert np.array_equal(gm.voxel_slot.cpu().numpy(), om["voxel_slot"])
+    assert np.array_equal(gm.set_win[:n_sets].cpu().numpy(), om["set_win"])
+    assert torch.all(gm.set_inds[n_sets:] == -1)          # rows past n_sets are left alone

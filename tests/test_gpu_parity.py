@@ -1,0 +1,158 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle on the same seeded inputs.
+
+Index maps must match bit for bit; features to TOL (1e-4 fp32, 2e-2 bf16) as
+max |gpu - oracle| / max |oracle| per output tensor.
+"""
+import numpy as np
+import pytest
+import torch
+
+import synth
+from oracle import dsvt_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+dsvt = pytest.importorskip("paper_2301_06051_amd")
+from gpu_util import TOL, assert_maps_equal, dev_coords, dev_feats, gpu_maps, rel_err  # noqa: E402
+
+
+def _say(msg):
+    print(f"[case] {msg}", flush=True)
+
+
+# ------------------------------------------------------------------ partition
+@pytest.mark.parametrize("cid,n", [(1, None), (2, None), (3, None), (5, None), (2, 777), (3, 5000)])
+@pytest.mark.parametrize("axis", [0, 1])
+def test_partition_bit_exact(cid, n, axis):
+    cfg = synth.CONFIGS[cid]
+    coords = synth.make_frame(cid, n=n)
+    shift = cfg["shifts"][-1]
+    _say(f"partition cfg{cid} n={len(coords)} axis={axis} shift={shift}")
+    om = orc.partition(coords, cfg["grid"], cfg["win"], shift, cfg["tau"], axis)
+    gm = gpu_maps(dev_coords(coords), cfg["grid"], cfg["win"], shift, cfg["tau"], cfg["batch"], axis)
+    assert_maps_equal(gm, om)
+
+
+@pytest.mark.parametrize("n", [1, 35, 36, 37, 72, 73])
+def test_partition_single_window_edges(n):
+    """One window holding n voxels around the multiples of tau, including a lone voxel."""
+    _say(f"partition one window n={n}")
+    grid, win, tau = (12, 12, 1), (12, 12, 1), 36
+    coords = np.concatenate([np.zeros((n, 1), np.int64), synth.frame_uniform(3, grid, n)], 1).astype(np.int32)
+    for axis in (0, 1):
+        om = orc.partition(coords, grid, win, (0, 0, 0), tau, axis)
+        gm = gpu_maps(dev_coords(coords), grid, win, (0, 0, 0), tau, 1, axis)
+        assert_maps_equal(gm, om)
+
+
+def test_partition_odd_geometry_and_batch():
+    """Window volume not a multiple of 32, grid not a multiple of the window, 3 frames, shift on all axes."""
+    grid, win, shift, tau = (29, 17, 9), (5, 7, 3), (2, 6, 1), 11
+    coords = np.concatenate([np.concatenate([np.full((900, 1), b), synth.frame_uniform(50 + b, grid, 900)], 1)
+                             for b in range(3)]).astype(np.int32)
+    _say("partition odd geometry")
+    for axis in (0, 1):
+        om = orc.partition(coords, grid, win, shift, tau, axis)
+        gm = gpu_maps(dev_coords(coords), grid, win, shift, tau, 3, axis)
+        assert_maps_equal(gm, om)
+
+
+def test_partition_reports_bad_input_without_faulting():
+    grid, win, tau = (24, 24, 1), (12, 12, 1), 36
+    coords = np.concatenate([np.zeros((200, 1), np.int64), synth.frame_uniform(4, grid, 200)], 1).astype(np.int32)
+    cfg = dsvt.part_cfg(grid, win, (0, 0, 0), tau, 1, 0)
+    _say("partition status bits")
+    bad = coords.copy(); bad[5, 1] = 24                           # outside the grid
+    gm = dsvt.dsvt_partition(cfg, dev_coords(bad)); torch.cuda.synchronize()
+    assert int(gm.status.item()) & dsvt.binding.ST_COORD_RANGE
+    rep = coords.copy(); rep[7] = rep[8]                          # repeated cell
+    gm = dsvt.dsvt_partition(cfg, dev_coords(rep)); torch.cuda.synchronize()
+    assert int(gm.status.item()) & dsvt.binding.ST_COORD_REPEAT
+    small = dsvt.SetMaps(cfg, 200, max_sets=3)                    # too few set rows
+    gm = dsvt.dsvt_partition(cfg, dev_coords(coords), out=small); torch.cuda.synchronize()
+    assert int(gm.status.item()) & dsvt.binding.ST_SET_OVERFLOW
+    assert int(gm.n_sets.item()) == orc.partition(coords, grid, win, (0, 0, 0), tau, 0)["n_sets"]
+    with pytest.raises(dsvt.DsvtError) as e:
+        dsvt.dsvt_partition(dsvt.part_cfg(grid, win, (12, 0, 0), tau, 1, 0), dev_coords(coords), out=gm)
+    assert e.value.rc == dsvt.binding.DSVT_EINVAL
+
+
+# ------------------------------------------------------------------ set attention / block
+def _layer_case(cid, n, seed, rel_bias=True, shift=None):
+    cfg = synth.CONFIGS[cid]
+    coords = synth.make_frame(cid, n=n)
+    x = synth.make_features(seed, len(coords), cfg["C"], cfg["dtype"])
+    shift = cfg["shifts"][-1] if shift is None else shift
+    mk = lambda s: synth.make_layer_weights(s, cfg["C"], cfg["heads"], cfg["hidden"], cfg["win"], cfg["dtype"], rel_bias)
+    return cfg, coords, x, shift, mk
+
+
+@pytest.mark.parametrize("cid,n", [(1, None), (2, 5000), (3, 8000), (5, 12000)])
+@pytest.mark.parametrize("dup_mode", [0, 1])
+@pytest.mark.parametrize("rel_bias", [True, False])
+def test_set_attention_parity(cid, n, dup_mode, rel_bias):
+    cfg, coords, x, shift, mk = _layer_case(cid, n, 31, rel_bias)
+    w = mk(61)
+    _say(f"set_attention cfg{cid} n={len(coords)} dup={dup_mode} pe={rel_bias}")
+    om = orc.partition(coords, cfg["grid"], cfg["win"], shift, cfg["tau"], 1)
+    ref = orc.set_attention(w, om, coords, x, dup_mode)
+    cd = dev_coords(coords)
+    gm = gpu_maps(cd, cfg["grid"], cfg["win"], shift, cfg["tau"], cfg["batch"], 1)
+    y = dsvt.dsvt_set_attention(dsvt.LayerWeights(w, dup_mode), gm, cd, dev_feats(x, cfg["dtype"]))
+    torch.cuda.synchronize()
+    err = rel_err(y, ref)
+    _say(f"  rel err {err:.3e}")
+    assert err < TOL[cfg["dtype"]]
+
+
+@pytest.mark.parametrize("cid,n", [(1, None), (2, 5000), (3, 8000)])
+def test_block_parity(cid, n):
+    cfg, coords, x, shift, mk = _layer_case(cid, n, 32)
+    ws = [mk(71), mk(72)]
+    _say(f"block cfg{cid} n={len(coords)}")
+    oms = [orc.partition(coords, cfg["grid"], cfg["win"], shift, cfg["tau"], a) for a in (0, 1)]
+    ref = orc.block(ws, oms, coords, x)
+    cd = dev_coords(coords)
+    gms = [gpu_maps(cd, cfg["grid"], cfg["win"], shift, cfg["tau"], cfg["batch"], a) for a in (0, 1)]
+    xd = dev_feats(x, cfg["dtype"])
+    out = dsvt.dsvt_block([dsvt.LayerWeights(w) for w in ws], gms, cd, xd)
+    torch.cuda.synchronize()
+    err = rel_err(out, ref)
+    _say(f"  rel err {err:.3e}")
+    assert err < TOL[cfg["dtype"]]
+    # in place gives the same bits
+    again = dsvt.dsvt_block([dsvt.LayerWeights(w) for w in ws], gms, cd, xd, x_out=xd)
+    torch.cuda.synchronize()
+    assert again.data_ptr() == xd.data_ptr() and torch.equal(again, out)
+
+
+def test_stack_parity_full_pillar_frame():
+    """The benchmark workload: 30,000-pillar frame, 4 blocks x 2 layers, windows shifted on odd blocks."""
+    cfg, coords, x, _, _ = _layer_case(2, None, 33)
+    ws = [[synth.make_layer_weights(200 + 2 * b + a, cfg["C"], cfg["heads"], cfg["hidden"], cfg["win"], cfg["dtype"])
+           for a in (0, 1)] for b in range(cfg["blocks"])]
+    _say("stack cfg2 full frame")
+    ref = orc.stack(ws, coords, x, cfg["grid"], cfg["win"], cfg["shifts"], cfg["tau"])
+    cd = dev_coords(coords)
+    maps = {sh: [gpu_maps(cd, cfg["grid"], cfg["win"], sh, cfg["tau"], 1, a) for a in (0, 1)] for sh in cfg["shifts"]}
+    xd = dev_feats(x, cfg["dtype"])
+    for b, pair in enumerate(ws):
+        xd = dsvt.dsvt_block([dsvt.LayerWeights(w) for w in pair], maps[cfg["shifts"][b % 2]], cd, xd)
+    torch.cuda.synchronize()
+    err = rel_err(xd, ref)
+    _say(f"  rel err after 8 layers {err:.3e}")
+    assert err < TOL["bf16"]
+
+
+def test_layer_argument_errors():
+    cfg, coords, x, shift, mk = _layer_case(1, 300, 34)
+    cd = dev_coords(coords)
+    gm = gpu_maps(cd, cfg["grid"], cfg["win"], shift, cfg["tau"], 1, 0)
+    w = mk(81)
+    w_bad = dict(w); w_bad["C"], w_bad["heads"] = 96, 4
+    lw = dsvt.LayerWeights(w)
+    lw.struct.C = 96
+    lw.C = 96
+    with pytest.raises(dsvt.DsvtError) as e:
+        dsvt.dsvt_set_attention(lw, gm, cd, torch.zeros((300, 96), device="cuda"))
+    assert e.value.rc == dsvt.binding.DSVT_EUNSUPPORTED

@@ -1,0 +1,44 @@
+"""The C-ABI library loads and exports every function include/dsvt.h declares (no compute calls)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_2301_06051_amd", "libdsvt.so")
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "dsvt.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dsvt_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_declares_the_four_entry_points():
+    names = _declared()
+    for must in ("dsvt_partition", "dsvt_set_attention", "dsvt_block", "dsvt_attn_pool"):
+        assert must in names
+
+
+def test_library_exports_every_declared_symbol():
+    if not os.path.exists(LIB):
+        import __graft_entry__
+        __graft_entry__.build()
+    lib = ctypes.CDLL(LIB)
+    for name in _declared():
+        assert hasattr(lib, name), name
+
+
+def test_host_only_calls_work_without_a_gpu():
+    """dsvt_partition_bound is pure host arithmetic: the set bound and a positive scratch size."""
+    if not os.path.exists(LIB):
+        pytest.skip("library not built")
+    from paper_2301_06051_amd import binding as b
+    cfg = b.part_cfg((468, 468, 1), (12, 12, 1), (6, 6, 0), 36, 1, 0)
+    max_sets, ws = b.dsvt_partition_bound(cfg, 30000)
+    assert max_sets == 30000 // 36 + 40 * 40 and ws > 0
+    with pytest.raises(b.DsvtError):
+        b.dsvt_partition_bound(b.part_cfg((468, 468, 1), (12, 12, 1), (12, 0, 0), 36, 1, 0), 30000)
+    with pytest.raises(b.DsvtError):
+        b.dsvt_partition_bound(b.part_cfg((468, 468, 1), (12, 12, 1), (0, 0, 0), 36, 1, 2), 30000)
