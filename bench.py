@@ -135,7 +135,7 @@ def main():
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "configs[1]: 468x468x1 pillar frame, 30000 voxels, C=192, 8 heads, tau=36, "
                                "win 12x12x1, 4 blocks x 2 layers, shift (6,6,0) on odd blocks",
-                   "launch": "hip_graph" if use_graph else "eager", "n_sets": n_sets, "rho": round(float(rho), 4)},
+                   "launch": "hip_graph" if use_graph else "eager", "n_sets": {"shift" + "_".join(map(str, k)): v for k, v in n_sets.items()}, "rho": round(float(rho), 4)},
         "ms_per_frame": round(ms_per_step, 4),
         "kernel_ms_per_step": {k: round(v, 4) for k, v in per_step_ms.items()},
         "kernel_us_per_launch": {k: round(v, 2) for k, v in per_launch_us.items()},
