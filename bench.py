@@ -96,7 +96,7 @@ def main():
     ms_per_step = dt / args.steps * 1e3
 
     # Per-kernel time: the same steps again, eagerly, with an event pair around every launch.
-    launches_per_step = 4 * 5 + 4 * 4
+    launches_per_step = 4 * 6 + 4 * 2
     prof_steps = min(args.steps, 50)
     dsvt.prof_enable(launches_per_step * prof_steps)
     for _ in range(prof_steps):
@@ -106,11 +106,11 @@ def main():
     per_launch_us = {k: 1e3 * ms / n for k, (ms, n) in prof.items() if n}
     per_step_ms = {k: ms / prof_steps for k, (ms, n) in prof.items() if n}
 
-    # Roofline of the dominant kernel.  Algorithmic flops per voxel per layer (duplicate-row and
-    # tile-padding work not counted): set attention 8 C^2 + 4 tau C rho, FFN 8 C^2.
+    # Roofline of the dominant kernel, the fused layer.  Algorithmic flops per voxel per layer
+    # (duplicate-row and tile-padding work not counted): 16 C^2 + 4 tau C rho.
     rho = np.mean([n_sets[cfg["shifts"][b % len(cfg["shifts"])]] for b in range(cfg["blocks"])]) * tau / N
-    flops = {"set_attention": N * (8 * C * C + 4 * tau * C * rho), "ffn": N * 8 * C * C}
-    dom = max(("set_attention", "ffn"), key=lambda k: per_step_ms.get(k, 0.0))
+    flops = {"layer": N * (16 * C * C + 4 * tau * C * rho)}
+    dom = "layer"
     achieved = flops[dom] / (per_launch_us[dom] * 1e-6) / 1e12
     peak = 2500.0
     roofline = {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s",

@@ -48,9 +48,11 @@ typedef struct {
                        main order), 1 = y,x,z (Y-axis main order)                       */
 } dsvt_part_cfg;
 
-/* Host-only.  Upper bound on the number of sets, floor(N/tau) + min(N, #windows), and the
- * bytes of scratch dsvt_partition needs for n_voxels voxels.  Either output may be NULL. */
-int dsvt_partition_bound(const dsvt_part_cfg* cfg, int32_t n_voxels, int32_t* max_sets, size_t* ws_bytes);
+/* Host-only.  Upper bound on the number of sets, floor(N/tau) + min(N, #windows), on the number
+ * of workgroup tiles (see dsvt_maps), and the bytes of scratch dsvt_partition needs for n_voxels
+ * voxels.  Any output may be NULL. */
+int dsvt_partition_bound(const dsvt_part_cfg* cfg, int32_t n_voxels, int32_t* max_sets, int32_t* max_tiles,
+                         size_t* ws_bytes);
 
 /* Builds the slot maps of one (window configuration, axis).
  *   window key  = ((b*nWx + (x+sx)/L)*nWy + (y+sy)/W)*nWz + (z+sz)/H, nW* = ceil((grid+shift)/win)
@@ -62,13 +64,18 @@ int dsvt_partition_bound(const dsvt_part_cfg* cfg, int32_t n_voxels, int32_t* ma
  * voxel_slot [device] int32 [n_voxels]     out: smallest flat slot s*tau+k that holds the voxel
  * n_sets     [device] int32 scalar         out: total number of sets
  * set_win    [device] int32 [max_sets]     out: window key of every set; may be NULL
+ * tile_first [device] int32 [max_tiles+1]  out: work list for the layer kernels (see dsvt_maps): sets
+ *                                               tile_first[t] .. tile_first[t+1]-1 form tile t; may be NULL
+ * n_tiles    [device] int32 scalar         out: number of tiles; NULL iff tile_first is NULL
  * ws         [device] scratch of at least the bytes dsvt_partition_bound reports
  * status     [device] int32 word, OR-ed with DSVT_ST_* bits (the caller zeroes it)
  * Errors: DSVT_EINVAL (NULL pointer, non-positive size, shift outside [0,win), axis not 0/1,
- * key space of 2^31 or more cells), DSVT_ENOSPC (ws_bytes too small), DSVT_EHIP. */
+ * key space of 2^31 or more cells), DSVT_ENOSPC (ws_bytes too small), DSVT_EUNSUPPORTED (a tile
+ * list asked for with tau > 48), DSVT_EHIP. */
 int dsvt_partition(const dsvt_part_cfg* cfg, const int32_t* coords, int32_t n_voxels,
                    int32_t* set_inds, int32_t* voxel_slot, int32_t* n_sets, int32_t max_sets,
-                   int32_t* set_win, void* ws, size_t ws_bytes, int32_t* status, void* stream);
+                   int32_t* set_win, int32_t* tile_first, int32_t* n_tiles, int32_t max_tiles,
+                   void* ws, size_t ws_bytes, int32_t* status, void* stream);
 
 /* The maps one layer consumes (outputs of dsvt_partition, all [device]). */
 typedef struct {
@@ -77,6 +84,12 @@ typedef struct {
   const int32_t* voxel_slot; /* [n_voxels]; the attention kernels re-derive the first-occurrence
                                 rule from set_inds on chip and do not read it: may be NULL */
   const int32_t* n_sets;     /* scalar, <= max_sets                                     */
+  /* Optional work list from dsvt_partition (both NULL or both set): tile t covers the sets
+   * tile_first[t] .. tile_first[t+1]-1, whose distinct voxels fit one 96-row workgroup tile.
+   * Without it a workgroup takes two consecutive sets. */
+  int32_t max_tiles;         /* rows of tile_first minus one                            */
+  const int32_t* tile_first; /* [max_tiles+1]                                           */
+  const int32_t* n_tiles;    /* scalar, <= max_tiles                                    */
 } dsvt_maps;
 
 /* ---------------------------------------------------------------------------------------

@@ -28,7 +28,8 @@ class PartCfg(C.Structure):
 
 class Maps(C.Structure):
     _fields_ = [("n_voxels", C.c_int32), ("max_sets", C.c_int32), ("tau", C.c_int32), ("set_inds", C.c_void_p),
-                ("voxel_slot", C.c_void_p), ("n_sets", C.c_void_p)]
+                ("voxel_slot", C.c_void_p), ("n_sets", C.c_void_p), ("max_tiles", C.c_int32),
+                ("tile_first", C.c_void_p), ("n_tiles", C.c_void_p)]
 
 
 class LayerW(C.Structure):
@@ -59,8 +60,8 @@ def lib():
                                "(there is no fallback path)")
         L = C.CDLL(LIB_PATH)
         vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
-        L.dsvt_partition_bound.argtypes = [C.POINTER(PartCfg), i32, C.POINTER(i32), C.POINTER(sz)]
-        L.dsvt_partition.argtypes = [C.POINTER(PartCfg), vp, i32, vp, vp, vp, i32, vp, vp, sz, vp, vp]
+        L.dsvt_partition_bound.argtypes = [C.POINTER(PartCfg), i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(sz)]
+        L.dsvt_partition.argtypes = [C.POINTER(PartCfg), vp, i32, vp, vp, vp, i32, vp, vp, vp, i32, vp, sz, vp, vp]
         L.dsvt_block_workspace_size.argtypes = [C.POINTER(LayerW), i32, C.POINTER(sz)]
         L.dsvt_set_attention.argtypes = [C.POINTER(LayerW), C.POINTER(Maps), vp, vp, vp, vp, sz, vp]
         L.dsvt_block.argtypes = [C.POINTER(LayerW), C.POINTER(Maps), vp, vp, vp, vp, sz, vp]
@@ -103,16 +104,17 @@ def part_cfg(grid, win, shift, tau, batch, axis):
 
 
 def dsvt_partition_bound(cfg, n_voxels):
-    ms, ws = C.c_int32(0), C.c_size_t(0)
-    _check("dsvt_partition_bound", lib().dsvt_partition_bound(C.byref(cfg), n_voxels, C.byref(ms), C.byref(ws)))
-    return ms.value, ws.value
+    ms, mt, ws = C.c_int32(0), C.c_int32(0), C.c_size_t(0)
+    _check("dsvt_partition_bound",
+           lib().dsvt_partition_bound(C.byref(cfg), n_voxels, C.byref(ms), C.byref(mt), C.byref(ws)))
+    return ms.value, mt.value, ws.value
 
 
 class SetMaps:
     """Device buffers of one (window configuration, axis) and the struct the kernels read."""
 
-    def __init__(self, cfg, n_voxels, max_sets=None):
-        bound, ws_bytes = dsvt_partition_bound(cfg, n_voxels)
+    def __init__(self, cfg, n_voxels, max_sets=None, tiles=True):
+        bound, tile_bound, ws_bytes = dsvt_partition_bound(cfg, n_voxels)
         self.cfg, self.n_voxels, self.tau = cfg, n_voxels, cfg.tau
         self.max_sets = bound if max_sets is None else max_sets
         i32 = dict(dtype=torch.int32, device="cuda")
@@ -122,8 +124,13 @@ class SetMaps:
         self.n_sets = torch.zeros((1,), **i32)
         self.status = torch.zeros((1,), **i32)
         self.ws = torch.empty((ws_bytes,), dtype=torch.uint8, device="cuda")
+        self.max_tiles = tile_bound if (tiles and tile_bound > 0 and cfg.tau <= 48) else 0
+        self.tile_first = torch.full((self.max_tiles + 1,), -1, **i32) if self.max_tiles else None
+        self.n_tiles = torch.zeros((1,), **i32) if self.max_tiles else None
         self.struct = Maps(n_voxels, self.max_sets, cfg.tau, self.set_inds.data_ptr(), self.voxel_slot.data_ptr(),
-                           self.n_sets.data_ptr())
+                           self.n_sets.data_ptr(), self.max_tiles,
+                           self.tile_first.data_ptr() if self.max_tiles else None,
+                           self.n_tiles.data_ptr() if self.max_tiles else None)
 
 
 def dsvt_partition(cfg, coords, out=None, stream=None):
@@ -133,8 +140,9 @@ def dsvt_partition(cfg, coords, out=None, stream=None):
     out = SetMaps(cfg, n) if out is None else out
     assert out.n_voxels == n
     rc = lib().dsvt_partition(C.byref(cfg), _ptr(coords), n, _ptr(out.set_inds), _ptr(out.voxel_slot),
-                              _ptr(out.n_sets), out.max_sets, _ptr(out.set_win), _ptr(out.ws), out.ws.numel(),
-                              _ptr(out.status), _stream(stream))
+                              _ptr(out.n_sets), out.max_sets, _ptr(out.set_win), _ptr(out.tile_first),
+                              _ptr(out.n_tiles), out.max_tiles, _ptr(out.ws), out.ws.numel(), _ptr(out.status),
+                              _stream(stream))
     _check("dsvt_partition", rc)
     return out
 

@@ -1,24 +1,26 @@
-// dsvt_set_attention / dsvt_block: one DSVT layer on gfx950 (Sec. 3.2 Eq. 4-5; appendix
-// "Network Architecture").
+// dsvt_set_attention / dsvt_block: one DSVT layer per kernel launch on gfx950 (Sec. 3.2 Eq. 4-5;
+// appendix "Network Architecture").
 //
-// k_set_attention: a workgroup owns SETS_PER_WG consecutive sets.  It reads their slot rows of
-// set_inds, keeps the first occurrence of every voxel (repeats are adjacent, Eq. 3 is monotone),
-// and gathers those voxels' features into an LDS tile -- the tau x C tile of Eq. (4) with the
-// repeated rows squeezed out, since a masked repeat contributes nothing as a key and its query
-// row would be thrown away.  Q/K/V projection, per-(set, head) softmax(QK^T + PE)V, the output
-// projection, the residual and LayerNorm all run on that tile; the result rows go straight back
-// to the voxels' rows of the output (every voxel is in exactly one set, Thm A.2-A.3).
-// k_ffn: row tiles of LN(x + W2 gelu(W1 x + b1) + b2).
+// k_layer: a workgroup owns a run of consecutive sets (a "tile" of at most 96 rows).  It reads
+// their slot rows of set_inds, keeps the first occurrence of every voxel (repeats are adjacent,
+// Eq. 3 is monotone), and gathers those voxels' features into an LDS tile -- the tau x C tiles of
+// Eq. (4) with the repeated rows squeezed out, since a masked repeat contributes nothing as a key
+// and its query row would be thrown away.  Q/K/V projection, per-(set, head) softmax(QK^T + PE)V,
+// output projection, residual + LayerNorm, the MLP and the second residual + LayerNorm all run
+// on that tile in LDS and registers; the rows then go straight back to the voxels' rows of the
+// output (every voxel is in exactly one set, Thm A.2-A.3), so a layer reads and writes [N, C] once.
 #include "common.h"
 #include "mma.h"
 
 namespace {
 
-constexpr int kSetsPerWg = 2;
 constexpr int kTauMax = 48;
-constexpr int kRowsMax = kSetsPerWg * kTauMax;   // 96 rows = 6 MFMA row tiles
-constexpr int kRtMax = kRowsMax / 16;
+constexpr int kRowsMax = 96;                     // rows of a tile = 6 MFMA row tiles
 constexpr int kKeyTiles = kTauMax / 16;          // 3
+constexpr int kMaxSets = kRowsMax / 4;           // every set takes at least 4 rows of a tile
+constexpr int kFixedSets = kRowsMax / kTauMax;   // sets per workgroup when no tile list is given
+constexpr int kWaves = 8;
+constexpr int kStatGroups = 4;                   // output-tile groups of the LayerNorm phases
 
 struct LayerDev {
   const void *w_qkv, *w_o, *w_1, *w_2;
@@ -28,88 +30,174 @@ struct LayerDev {
   int dup_mode;
 };
 
-template <typename T, int C, int HEADS> struct AttnLds {
+struct MapsDev {
+  const int32_t *set_inds, *n_sets, *tile_first, *n_tiles;
+  int32_t max_sets, tau, n_voxels;
+};
+
+template <typename T, int C, int HEADS, int HID> struct LayerLds {
   static constexpr int D = C / HEADS;
   static constexpr int PAD = lds_pad<T>();
   static constexpr int LDX = C + PAD;            // pitch of [row][feature] tiles, elements of T
   static constexpr int LDV = kRowsMax + PAD;     // pitch of V^T [feature][row]
-  static constexpr int LDY = C + 4;              // pitch of the fp32 staging tile
+  static constexpr int LDH = HID + PAD;          // pitch of the MLP hidden tile
   static constexpr size_t kTile = (size_t)kRowsMax * LDX * sizeof(T);
   static constexpr size_t off_x = 0, off_q = kTile, off_k = 2 * kTile, off_v = 3 * kTile;
   static constexpr size_t kVt = (size_t)C * LDV * sizeof(T);
-  static constexpr size_t off_y = off_k;         // fp32 staging reuses K and V^T once attention is done
+  static constexpr size_t off_h = off_q;         // hidden tile reuses Q and K once attention is done
   static constexpr size_t off_misc = off_v + kVt;
-  static constexpr size_t kMisc = (size_t)(kSetsPerWg * kTauMax + 3 * kRowsMax + 2 * kSetsPerWg + 2) * 4;
+  static constexpr size_t kMisc = (size_t)(3 * kRowsMax + 2 * kMaxSets + 2 + 2 * kStatGroups * kRowsMax) * 4;
   static constexpr size_t total = off_misc + kMisc;
-  static_assert((size_t)kRowsMax * LDY * 4 <= kTile + kVt, "fp32 staging must fit in K + V^T");
+  static_assert((size_t)kRowsMax * LDH * sizeof(T) <= 2 * kTile, "hidden tile must fit in Q + K");
   static_assert(C % 64 == 0 && D % Mma<T>::KL == 0 && D % 4 == 0, "shape");
 };
 
-template <typename T, int C, int HEADS, int NW, int NT_QKV, int NT_O>
-__global__ void __launch_bounds__(NW * 64)
-k_set_attention(LayerDev p, const int32_t* __restrict__ set_inds, const int32_t* __restrict__ n_sets_ptr,
-                int32_t max_sets, int32_t tau, int32_t n_voxels, const int4* __restrict__ coords,
-                const T* x, T* out, int full_layer) {   // out may be x (rows are read, then written, by one workgroup)
-  typedef AttnLds<T, C, HEADS> L;
+// LayerNorm over the C features of every row, for values spread over the workgroup in
+// accumulator layout: this wavefront holds features o0 .. o0 + 16*NT - 1 (group og of
+// kStatGroups) of rows 16*(rt0 + r) + m, r < cnt.  Two-pass (mean, then centred squares) with
+// the per-group partial sums exchanged through LDS.  Every thread of the workgroup must call it.
+template <typename T, int NT>
+__device__ __forceinline__ void layer_norm_tile(f32x4 (&v)[NT][3], int C, int o0, int og, int rt0, int cnt, float* stat,
+                                                const float* __restrict__ gamma, const float* __restrict__ beta,
+                                                float eps, T* dst, int ldd) {
+  typedef typename Mma<T>::Vec4 Vec4;
+  const int lane = threadIdx.x & 63, m = lane & 15, g = lane >> 4;
+  float* stat1 = stat;
+  float* stat2 = stat + kStatGroups * kRowsMax;
+  float mean[3], rs[3];
+#pragma unroll
+  for (int r = 0; r < 3; ++r) {
+    float s = 0.f;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) s += v[nt][r][0] + v[nt][r][1] + v[nt][r][2] + v[nt][r][3];
+    s += __shfl_xor(s, 16, 64);
+    s += __shfl_xor(s, 32, 64);
+    if (g == 0 && r < cnt) stat1[og * kRowsMax + 16 * (rt0 + r) + m] = s;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int r = 0; r < 3; ++r) {
+    mean[r] = 0.f;
+    if (r < cnt) {
+      const int row = 16 * (rt0 + r) + m;
+      float t = 0.f;
+#pragma unroll
+      for (int k = 0; k < kStatGroups; ++k) t += stat1[k * kRowsMax + row];
+      mean[r] = t / (float)C;
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      v[nt][r] -= mean[r];
+      s += v[nt][r][0] * v[nt][r][0] + v[nt][r][1] * v[nt][r][1] + v[nt][r][2] * v[nt][r][2] + v[nt][r][3] * v[nt][r][3];
+    }
+    s += __shfl_xor(s, 16, 64);
+    s += __shfl_xor(s, 32, 64);
+    if (g == 0 && r < cnt) stat2[og * kRowsMax + 16 * (rt0 + r) + m] = s;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int r = 0; r < 3; ++r) {
+    if (r < cnt) {
+      const int row = 16 * (rt0 + r) + m;
+      float t = 0.f;
+#pragma unroll
+      for (int k = 0; k < kStatGroups; ++k) t += stat2[k * kRowsMax + row];
+      rs[r] = rsqrtf(t / (float)C + eps);
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        const int o = o0 + 16 * nt + 4 * g;
+        const f32x4 ga = *reinterpret_cast<const f32x4*>(gamma + o), be = *reinterpret_cast<const f32x4*>(beta + o);
+        *reinterpret_cast<Vec4*>(dst + row * ldd + o) = pack4<T>(v[nt][r] * rs[r] * ga + be);
+      }
+    }
+  }
+}
+
+template <typename T, int C, int HEADS, int HID, int NT_QKV, int NT_O, int NT_1, int NT_2, int KSPLIT_2>
+__global__ void __launch_bounds__(kWaves * 64)
+k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* out, int full_layer) {
+  // out may be x: a tile's rows are read, then written, by this workgroup only
+  typedef LayerLds<T, C, HEADS, HID> L;
   typedef Mma<T> M;
   typedef typename M::Frag Frag;
   typedef typename M::Vec4 Vec4;
-  constexpr int D = L::D, LDX = L::LDX, LDV = L::LDV, LDY = L::LDY, KC = M::KC, KL = M::KL;
-  constexpr int NTHREADS = NW * 64;
+  constexpr int D = L::D, LDX = L::LDX, LDV = L::LDV, LDH = L::LDH, KC = M::KC, KL = M::KL;
+  constexpr int NW = kWaves, NTHREADS = NW * 64;
+  static_assert(C / (16 * NT_O) == kStatGroups && C / (16 * NT_2) == kStatGroups, "LayerNorm phases: one item per wave");
   extern __shared__ __align__(16) unsigned char smem[];
   T* Xs = reinterpret_cast<T*>(smem + L::off_x);
   T* Qs = reinterpret_cast<T*>(smem + L::off_q);
   T* Ks = reinterpret_cast<T*>(smem + L::off_k);
   T* Vt = reinterpret_cast<T*>(smem + L::off_v);
-  float* Yf = reinterpret_cast<float*>(smem + L::off_y);
-  int32_t* inds = reinterpret_cast<int32_t*>(smem + L::off_misc);
-  int32_t* row_vox = inds + kSetsPerWg * kTauMax;
+  T* Hs = reinterpret_cast<T*>(smem + L::off_h);
+  int32_t* row_vox = reinterpret_cast<int32_t*>(smem + L::off_misc);
   int32_t* row_lin = row_vox + kRowsMax;
   float* row_mult = reinterpret_cast<float*>(row_lin + kRowsMax);
-  int32_t* set_r0 = reinterpret_cast<int32_t*>(row_mult + kRowsMax);   // [kSetsPerWg + 1]
-  int32_t* set_nu = set_r0 + kSetsPerWg + 1;                            // [kSetsPerWg]
+  int32_t* set_r0 = reinterpret_cast<int32_t*>(row_mult + kRowsMax);   // [kMaxSets + 1]
+  int32_t* set_nu = set_r0 + kMaxSets + 1;                              // [kMaxSets + 1]
+  float* stat = reinterpret_cast<float*>(set_nu + kMaxSets + 1);        // [2][kStatGroups][kRowsMax]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, m = lane & 15, g = lane >> 4;
-  int n_sets = *n_sets_ptr;
-  n_sets = n_sets < max_sets ? n_sets : max_sets;
-  const int s_base = blockIdx.x * kSetsPerWg;
-  const int ns = (n_sets - s_base) < kSetsPerWg ? (n_sets - s_base) : kSetsPerWg;
-  if (ns <= 0) return;
+
+  // The first Q/K/V weight fragments are requested before anything else: their latency hides
+  // behind the row bookkeeping and the gather.
+  GemmPhase<T, NT_QKV, C, 3 * C, NW, 1> qkv(p.w_qkv, wave);
+  qkv.issue(0);
+
+  int n_sets = *mp.n_sets;
+  n_sets = n_sets < mp.max_sets ? n_sets : mp.max_sets;
+  int s_begin, s_end;
+  if (mp.tile_first != nullptr) {
+    if ((int)blockIdx.x >= *mp.n_tiles) return;
+    s_begin = mp.tile_first[blockIdx.x];
+    s_end = mp.tile_first[blockIdx.x + 1];
+  } else {
+    s_begin = blockIdx.x * kFixedSets;
+    s_end = s_begin + kFixedSets;
+  }
+  s_end = s_end < n_sets ? s_end : n_sets;
+  int ns = s_end - s_begin;
+  if (ns <= 0 || s_begin < 0) return;
+  ns = ns < kMaxSets ? ns : kMaxSets;
+  const int tau = mp.tau;
 
   // ---- 1. slots -> compact rows (first occurrences only; each set starts on a multiple of 4 rows)
   for (int r = tid; r < kRowsMax; r += NTHREADS) { row_vox[r] = -1; row_lin[r] = 0; row_mult[r] = 0.f; }
-  const int nslots = ns * tau;
-  if (tid < nslots) inds[tid] = set_inds[(size_t)s_base * tau + tid];
-  __syncthreads();
-  int my_set = 0, my_rank = 0, my_mult = 0, my_v = -1;
-  bool my_first = false;
-  if (tid < nslots) {
-    my_set = tid / tau;
-    const int k = tid - my_set * tau;
-    const int32_t* row = inds + my_set * tau;
-    my_v = row[k];
-    my_first = (k == 0) || (row[k - 1] != my_v);
-    for (int k2 = 0; k2 < tau; ++k2) {
-      const int u = row[k2];
-      const bool f2 = (k2 == 0) || (row[k2 - 1] != u);
-      my_rank += (k2 < k && f2) ? 1 : 0;
-      my_mult += (u == my_v) ? 1 : 0;
-    }
-    if (k == tau - 1) set_nu[my_set] = my_rank + (my_first ? 1 : 0);
+  for (int ls = wave; ls < ns; ls += NW) {
+    const int v = lane < tau ? mp.set_inds[(size_t)(s_begin + ls) * tau + lane] : -2;
+    const int prev = __shfl_up(v, 1, 64);
+    const bool first = lane < tau && (lane == 0 || v != prev);
+    const unsigned long long mask = __ballot(first);
+    if (lane == 0) set_nu[ls] = __popcll(mask);
   }
   __syncthreads();
   if (tid == 0) {
-    int r = 0;
-    for (int s = 0; s < ns; ++s) { set_r0[s] = r; r += (set_nu[s] + 3) & ~3; }
-    set_r0[ns] = r;
+    int r = 0, keep = 0;
+    for (int s = 0; s < ns; ++s) {
+      const int padded = (set_nu[s] + 3) & ~3;
+      if (r + padded > kRowsMax) break;          // cannot happen with a tile list built for 96 rows
+      set_r0[s] = r; r += padded; keep = s + 1;
+    }
+    set_r0[keep] = r;
+    set_nu[kMaxSets] = keep;
   }
   __syncthreads();
-  if (tid < nslots && my_first && my_v >= 0 && my_v < n_voxels) {
-    const int r = set_r0[my_set] + my_rank;
-    const int4 c = coords[my_v];
-    row_vox[r] = my_v;
-    row_mult[r] = (float)my_mult;
-    row_lin[r] = (c.y * p.rel_my + c.z) * p.rel_mz + c.w;
+  ns = set_nu[kMaxSets];
+  for (int ls = wave; ls < ns; ls += NW) {
+    const int v = lane < tau ? mp.set_inds[(size_t)(s_begin + ls) * tau + lane] : -2;
+    const int prev = __shfl_up(v, 1, 64);
+    const bool first = lane < tau && (lane == 0 || v != prev);
+    const unsigned long long mask = __ballot(first);
+    if (first && v >= 0 && v < mp.n_voxels) {
+      const int r = set_r0[ls] + __popcll(mask & ((1ull << lane) - 1ull));
+      const unsigned long long later = mask >> (lane + 1);
+      const int run = later ? (__ffsll((long long)later)) : (tau - lane);   // slots holding this voxel
+      const int4 c = coords[v];
+      row_vox[r] = v;
+      row_mult[r] = (float)run;
+      row_lin[r] = (c.y * p.rel_my + c.z) * p.rel_mz + c.w;
+    }
   }
   __syncthreads();
   const int R = set_r0[ns];
@@ -131,23 +219,18 @@ k_set_attention(LayerDev p, const int32_t* __restrict__ set_inds, const int32_t*
   // ---- 3. Q, K, V = X W^T + b; Q pre-scaled by 1/sqrt(d); V stored transposed
   {
     const float scale = rsqrtf((float)D);
-    const T* W = reinterpret_cast<const T*>(p.w_qkv);
-    for (int og = wave; og < 3 * C / (16 * NT_QKV); og += NW) {
-      const int o0 = og * 16 * NT_QKV;
-      f32x4 acc[NT_QKV][kRtMax];
-      zero_acc(acc);
-      gemm_wx<T, NT_QKV, kRtMax>(W, C, o0, Xs, LDX, C, RT, acc);
+    qkv.run(Xs, LDX, RT, [&](int o0, int rt0, int cnt, f32x4 (&acc)[NT_QKV][3]) {
 #pragma unroll
       for (int nt = 0; nt < NT_QKV; ++nt) {
-        const int ot = o0 + 16 * nt;             // tile never straddles the Q/K/V boundary (C % 16 == 0)
+        const int ot = o0 + 16 * nt;             // a tile never straddles the Q/K/V boundary (C % 16 == 0)
         const int o = ot + 4 * g;
         const f32x4 b4 = *reinterpret_cast<const f32x4*>(p.b_qkv + o);
         const int sel = ot / C;
 #pragma unroll
-        for (int rt = 0; rt < kRtMax; ++rt) {
-          if (rt < RT) {
-            const int row = 16 * rt + m;
-            f32x4 v = acc[nt][rt] + b4;
+        for (int r = 0; r < 3; ++r) {
+          if (r < cnt) {
+            const int row = 16 * (rt0 + r) + m;
+            f32x4 v = acc[nt][r] + b4;
             if (sel == 0) {
               v *= scale;
               *reinterpret_cast<Vec4*>(Qs + row * LDX + o) = pack4<T>(v);
@@ -160,8 +243,10 @@ k_set_attention(LayerDev p, const int32_t* __restrict__ set_inds, const int32_t*
           }
         }
       }
-    }
+    });
   }
+  GemmPhase<T, NT_O, C, C, NW, 1> oproj(p.w_o, wave);
+  oproj.issue(0);                                // in flight during the attention phase
   __syncthreads();
 
   // ---- 4. per (set, head): P = softmax(Q K^T + PE), O = P V; O overwrites the head's Q columns
@@ -301,148 +386,88 @@ k_set_attention(LayerDev p, const int32_t* __restrict__ set_inds, const int32_t*
   }
   __syncthreads();
 
-  // ---- 5. Y = O Wo^T + bo (+ x), staged in fp32 over the dead K / V^T tiles
-  {
-    const T* W = reinterpret_cast<const T*>(p.w_o);
-    for (int og = wave; og < C / (16 * NT_O); og += NW) {
-      const int o0 = og * 16 * NT_O;
-      f32x4 acc[NT_O][kRtMax];
-      zero_acc(acc);
-      gemm_wx<T, NT_O, kRtMax>(W, C, o0, Qs, LDX, C, RT, acc);
+  // ---- 5. Y = O Wo^T + bo (+ x), then LayerNorm; result (or raw Y) replaces x in Xs
+  f32x4 keep[NT_O][3];
+  int k_o0 = 0, k_rt0 = 0, k_cnt = 0;
+  oproj.run(Qs, LDX, RT, [&](int o0, int rt0, int cnt, f32x4 (&acc)[NT_O][3]) {
+    k_o0 = o0; k_rt0 = rt0; k_cnt = cnt;
 #pragma unroll
-      for (int nt = 0; nt < NT_O; ++nt) {
-        const int o = o0 + 16 * nt + 4 * g;
-        const f32x4 b4 = *reinterpret_cast<const f32x4*>(p.b_o + o);
+    for (int nt = 0; nt < NT_O; ++nt) {
+      const int o = o0 + 16 * nt + 4 * g;
+      const f32x4 b4 = *reinterpret_cast<const f32x4*>(p.b_o + o);
 #pragma unroll
-        for (int rt = 0; rt < kRtMax; ++rt) {
-          if (rt < RT) {
-            const int row = 16 * rt + m;
-            f32x4 v = acc[nt][rt] + b4;
-            if (full_layer) {
-              const Vec4 xr = *reinterpret_cast<const Vec4*>(Xs + row * LDX + o);
-              v += f32x4{to_f32<T>(xr[0]), to_f32<T>(xr[1]), to_f32<T>(xr[2]), to_f32<T>(xr[3])};
-            }
-            *reinterpret_cast<f32x4*>(Yf + row * LDY + o) = v;
-          }
+      for (int r = 0; r < 3; ++r) {
+        keep[nt][r] = acc[nt][r] + b4;
+        if (full_layer && r < cnt) {
+          const Vec4 xr = *reinterpret_cast<const Vec4*>(Xs + (16 * (rt0 + r) + m) * LDX + o);
+          keep[nt][r] += f32x4{to_f32<T>(xr[0]), to_f32<T>(xr[1]), to_f32<T>(xr[2]), to_f32<T>(xr[3])};
         }
       }
     }
-  }
-  __syncthreads();
-
-  // ---- 6. LayerNorm per row and scatter back to the voxel's row
-  for (int r = wave; r < R; r += NW) {
-    const int v = row_vox[r];
-    if (v < 0) continue;
-    float vals[C / 64];
-    float s1 = 0.f;
+  });
+  if (!full_layer) {
 #pragma unroll
-    for (int j = 0; j < C / 64; ++j) { vals[j] = Yf[r * LDY + lane + 64 * j]; s1 += vals[j]; }
-    if (full_layer) {
-      const float mean = wave_sum(s1) * (1.0f / C);
-      float s2 = 0.f;
+    for (int nt = 0; nt < NT_O; ++nt)
 #pragma unroll
-      for (int j = 0; j < C / 64; ++j) { vals[j] -= mean; s2 += vals[j] * vals[j]; }
-      const float rs = rsqrtf(wave_sum(s2) * (1.0f / C) + p.ln_eps);
-#pragma unroll
-      for (int j = 0; j < C / 64; ++j) vals[j] = vals[j] * rs * p.ln1_g[lane + 64 * j] + p.ln1_b[lane + 64 * j];
-    }
-#pragma unroll
-    for (int j = 0; j < C / 64; ++j) out[(size_t)v * C + lane + 64 * j] = (T)vals[j];
-  }
-}
+      for (int r = 0; r < 3; ++r)
+        if (r < k_cnt)
+          *reinterpret_cast<Vec4*>(Xs + (16 * (k_rt0 + r) + m) * LDX + k_o0 + 16 * nt + 4 * g) = pack4<T>(keep[nt][r]);
+  } else {
+    GemmPhase<T, NT_1, C, HID, NW, 1> ffn1(p.w_1, wave);
+    ffn1.issue(0);                               // in flight during the LayerNorm exchange
+    layer_norm_tile<T, NT_O>(keep, C, k_o0, k_o0 / (16 * NT_O), k_rt0, k_cnt, stat, p.ln1_g, p.ln1_b, p.ln_eps, Xs, LDX);
+    __syncthreads();
 
-// ------------------------------------------------------------------------------------------
-constexpr int kFfnRows = 64;
-
-template <typename T, int C, int HID> struct FfnLds {
-  static constexpr int PAD = lds_pad<T>();
-  static constexpr int LDX = C + PAD, LDH = HID + PAD, LDY = C + 4;
-  static constexpr size_t off_x = 0;
-  static constexpr size_t off_h = off_x + (size_t)kFfnRows * LDX * sizeof(T);
-  static constexpr size_t off_y = off_h + (size_t)kFfnRows * LDH * sizeof(T);
-  static constexpr size_t total = off_y + (size_t)kFfnRows * LDY * 4;
-};
-
-template <typename T, int C, int HID, int NW, int NT_1, int NT_2>
-__global__ void __launch_bounds__(NW * 64)
-k_ffn(LayerDev p, const T* x1, T* out, int32_t n) {   // out may be x1
-  typedef FfnLds<T, C, HID> L;
-  typedef typename Mma<T>::Vec4 Vec4;
-  constexpr int LDX = L::LDX, LDH = L::LDH, LDY = L::LDY, RT = kFfnRows / 16, NTHREADS = NW * 64;
-  extern __shared__ __align__(16) unsigned char smem[];
-  T* Xs = reinterpret_cast<T*>(smem + L::off_x);
-  T* Hs = reinterpret_cast<T*>(smem + L::off_h);
-  float* Yf = reinterpret_cast<float*>(smem + L::off_y);
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, m = lane & 15, g = lane >> 4;
-  const int row0 = blockIdx.x * kFfnRows;
-  {
-    constexpr int CH = C * (int)sizeof(T) / 16;
-    for (int idx = tid; idx < kFfnRows * CH; idx += NTHREADS) {
-      const int r = idx / CH, c = idx - r * CH;
-      uint4 val = make_uint4(0u, 0u, 0u, 0u);
-      if (row0 + r < n) val = reinterpret_cast<const uint4*>(x1 + (size_t)(row0 + r) * C)[c];
-      *reinterpret_cast<uint4*>(reinterpret_cast<unsigned char*>(Xs) + (size_t)r * LDX * sizeof(T) + c * 16) = val;
-    }
-  }
-  __syncthreads();
-  {
-    const T* W = reinterpret_cast<const T*>(p.w_1);
-    for (int og = wave; og < HID / (16 * NT_1); og += NW) {
-      const int o0 = og * 16 * NT_1;
-      f32x4 acc[NT_1][RT];
-      zero_acc(acc);
-      gemm_wx<T, NT_1, RT>(W, C, o0, Xs, LDX, C, RT, acc);
+    // ---- 6. MLP: H = gelu(x1 W1^T + b1) over the dead Q/K tiles; x2 = LN(x1 + H W2^T + b2)
+    ffn1.run(Xs, LDX, RT, [&](int o0, int rt0, int cnt, f32x4 (&acc)[NT_1][3]) {
 #pragma unroll
       for (int nt = 0; nt < NT_1; ++nt) {
         const int o = o0 + 16 * nt + 4 * g;
         const f32x4 b4 = *reinterpret_cast<const f32x4*>(p.b_1 + o);
 #pragma unroll
-        for (int rt = 0; rt < RT; ++rt) {
-          f32x4 v = acc[nt][rt] + b4;
-          v = f32x4{gelu_erf(v[0]), gelu_erf(v[1]), gelu_erf(v[2]), gelu_erf(v[3])};
-          *reinterpret_cast<Vec4*>(Hs + (16 * rt + m) * LDH + o) = pack4<T>(v);
+        for (int r = 0; r < 3; ++r) {
+          if (r < cnt) {
+            f32x4 v = acc[nt][r] + b4;
+            v = f32x4{gelu_erf(v[0]), gelu_erf(v[1]), gelu_erf(v[2]), gelu_erf(v[3])};
+            *reinterpret_cast<Vec4*>(Hs + (16 * (rt0 + r) + m) * LDH + o) = pack4<T>(v);
+          }
         }
       }
-    }
-  }
-  __syncthreads();
-  {
-    const T* W = reinterpret_cast<const T*>(p.w_2);
-    for (int og = wave; og < C / (16 * NT_2); og += NW) {
-      const int o0 = og * 16 * NT_2;
-      f32x4 acc[NT_2][RT];
-      zero_acc(acc);
-      gemm_wx<T, NT_2, RT>(W, HID, o0, Hs, LDH, HID, RT, acc);
+    });
+    GemmPhase<T, NT_2, HID, C, NW, KSPLIT_2> ffn2(p.w_2, wave);
+    ffn2.issue(0);
+    __syncthreads();
+    f32x4 keep2[NT_2][3];
+    ffn2.run(Hs, LDH, RT, [&](int o0, int rt0, int cnt, f32x4 (&acc)[NT_2][3]) {
+      k_o0 = o0; k_rt0 = rt0; k_cnt = cnt;
 #pragma unroll
       for (int nt = 0; nt < NT_2; ++nt) {
         const int o = o0 + 16 * nt + 4 * g;
         const f32x4 b4 = *reinterpret_cast<const f32x4*>(p.b_2 + o);
 #pragma unroll
-        for (int rt = 0; rt < RT; ++rt) {
-          const int row = 16 * rt + m;
-          const Vec4 xr = *reinterpret_cast<const Vec4*>(Xs + row * LDX + o);
-          f32x4 v = acc[nt][rt] + b4 + f32x4{to_f32<T>(xr[0]), to_f32<T>(xr[1]), to_f32<T>(xr[2]), to_f32<T>(xr[3])};
-          *reinterpret_cast<f32x4*>(Yf + row * LDY + o) = v;
+        for (int r = 0; r < 3; ++r) {
+          keep2[nt][r] = acc[nt][r] + b4;
+          if (r < cnt) {
+            const Vec4 xr = *reinterpret_cast<const Vec4*>(Xs + (16 * (rt0 + r) + m) * LDX + o);
+            keep2[nt][r] += f32x4{to_f32<T>(xr[0]), to_f32<T>(xr[1]), to_f32<T>(xr[2]), to_f32<T>(xr[3])};
+          }
         }
       }
-    }
+    });
+    layer_norm_tile<T, NT_2>(keep2, C, k_o0, k_o0 / (16 * NT_2), k_rt0, k_cnt, stat, p.ln2_g, p.ln2_b, p.ln_eps, Xs, LDX);
   }
   __syncthreads();
-  for (int r = wave; r < kFfnRows; r += NW) {
-    if (row0 + r >= n) break;
-    float vals[C / 64];
-    float s1 = 0.f;
-#pragma unroll
-    for (int j = 0; j < C / 64; ++j) { vals[j] = Yf[r * LDY + lane + 64 * j]; s1 += vals[j]; }
-    const float mean = wave_sum(s1) * (1.0f / C);
-    float s2 = 0.f;
-#pragma unroll
-    for (int j = 0; j < C / 64; ++j) { vals[j] -= mean; s2 += vals[j] * vals[j]; }
-    const float rs = rsqrtf(wave_sum(s2) * (1.0f / C) + p.ln_eps);
-#pragma unroll
-    for (int j = 0; j < C / 64; ++j)
-      out[(size_t)(row0 + r) * C + lane + 64 * j] = (T)(vals[j] * rs * p.ln2_g[lane + 64 * j] + p.ln2_b[lane + 64 * j]);
+
+  // ---- 7. scatter: rows of Xs -> the voxels' rows of out, 16 bytes per thread
+  {
+    constexpr int CH = C * (int)sizeof(T) / 16;
+    for (int idx = tid; idx < R * CH; idx += NTHREADS) {
+      const int r = idx / CH, c = idx - r * CH;
+      const int v = row_vox[r];
+      if (v >= 0)
+        reinterpret_cast<uint4*>(out + (size_t)v * C)[c] =
+            *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(Xs) + (size_t)r * LDX * sizeof(T) + c * 16);
+    }
   }
 }
 
@@ -471,7 +496,7 @@ int check_layer(const dsvt_layer_w& w, bool need_mlp) {
   if (!((w.C == 64 && w.heads == 4 && w.hidden == 128) || (w.C == 192 && w.heads == 8 && w.hidden == 384)))
     return DSVT_EUNSUPPORTED;
   if (w.dtype == DSVT_F32 && w.C != 64) return DSVT_EUNSUPPORTED;   // the fp32 C=192 tiles exceed the 160 KB LDS
-  const void* ptrs[] = {w.w_qkv, w.w_o, w.w_1, w.w_2, w.b_qkv, w.b_o, w.b_1, w.b_2};
+  const void* ptrs[] = {w.w_qkv, w.w_o, w.w_1, w.w_2, w.b_qkv, w.b_o, w.b_1, w.b_2, w.ln1_g, w.ln1_b, w.ln2_g, w.ln2_b};
   for (const void* q : ptrs) if (q && !aligned16(q)) return DSVT_EINVAL;
   return DSVT_OK;
 }
@@ -479,6 +504,8 @@ int check_layer(const dsvt_layer_w& w, bool need_mlp) {
 int check_maps(const dsvt_maps& mp) {
   if (!mp.set_inds || !mp.n_sets || mp.n_voxels <= 0 || mp.max_sets <= 0 || mp.tau <= 0) return DSVT_EINVAL;
   if (mp.tau > kTauMax) return DSVT_EUNSUPPORTED;
+  if ((mp.tile_first != nullptr) != (mp.n_tiles != nullptr)) return DSVT_EINVAL;
+  if (mp.tile_first != nullptr && mp.max_tiles <= 0) return DSVT_EINVAL;
   return DSVT_OK;
 }
 
@@ -488,50 +515,30 @@ template <typename K> int allow_lds(K kernel, size_t bytes) {
   return DSVT_OK;
 }
 
-constexpr int kAttnWaves = 4, kFfnWaves = 4;
-
-template <typename T, int C, int HEADS, int NT_QKV, int NT_O>
-int launch_attention(const dsvt_layer_w& w, const dsvt_maps& mp, const int32_t* coords, const void* x, void* out,
-                     int full, hipStream_t st) {
-  auto kern = k_set_attention<T, C, HEADS, kAttnWaves, NT_QKV, NT_O>;
-  constexpr size_t lds = AttnLds<T, C, HEADS>::total;
+template <typename T, int C, int HEADS, int HID, int NT_QKV, int NT_O, int NT_1, int NT_2, int KSPLIT_2>
+int launch_layer(const dsvt_layer_w& w, const dsvt_maps& mp, const int32_t* coords, const void* x, void* out, int full,
+                 hipStream_t st) {
+  auto kern = k_layer<T, C, HEADS, HID, NT_QKV, NT_O, NT_1, NT_2, KSPLIT_2>;
+  constexpr size_t lds = LayerLds<T, C, HEADS, HID>::total;
   static int prepared = allow_lds(kern, lds);
   if (prepared != DSVT_OK) return prepared;
-  const unsigned grid = (unsigned)dsvt_ceil_div(mp.max_sets, kSetsPerWg);
-  dsvt_prof_scope ps(DSVT_K_ATTN, st);
-  kern<<<grid, kAttnWaves * 64, lds, st>>>(to_dev(w), mp.set_inds, mp.n_sets, mp.max_sets, mp.tau, mp.n_voxels,
-                                           reinterpret_cast<const int4*>(coords), reinterpret_cast<const T*>(x),
-                                           reinterpret_cast<T*>(out), full);
+  MapsDev md;
+  md.set_inds = mp.set_inds; md.n_sets = mp.n_sets; md.tile_first = mp.tile_first; md.n_tiles = mp.n_tiles;
+  md.max_sets = mp.max_sets; md.tau = mp.tau; md.n_voxels = mp.n_voxels;
+  const unsigned grid = mp.tile_first ? (unsigned)mp.max_tiles : (unsigned)dsvt_ceil_div(mp.max_sets, kFixedSets);
+  dsvt_prof_scope ps(DSVT_K_LAYER, st);
+  kern<<<grid, kWaves * 64, lds, st>>>(to_dev(w), md, reinterpret_cast<const int4*>(coords),
+                                       reinterpret_cast<const T*>(x), reinterpret_cast<T*>(out), full);
   return DSVT_OK;
 }
 
-template <typename T, int C, int HID, int NT_1, int NT_2>
-int launch_ffn(const dsvt_layer_w& w, const void* x1, void* out, int32_t n, hipStream_t st) {
-  auto kern = k_ffn<T, C, HID, kFfnWaves, NT_1, NT_2>;
-  constexpr size_t lds = FfnLds<T, C, HID>::total;
-  static int prepared = allow_lds(kern, lds);
-  if (prepared != DSVT_OK) return prepared;
-  dsvt_prof_scope ps(DSVT_K_FFN, st);
-  kern<<<(unsigned)dsvt_ceil_div(n, kFfnRows), kFfnWaves * 64, lds, st>>>(to_dev(w), reinterpret_cast<const T*>(x1),
-                                                                         reinterpret_cast<T*>(out), n);
-  return DSVT_OK;
-}
-
-int run_attention(const dsvt_layer_w& w, const dsvt_maps& mp, const int32_t* coords, const void* x, void* out, int full,
-                  hipStream_t st) {
+int run_layer(const dsvt_layer_w& w, const dsvt_maps& mp, const int32_t* coords, const void* x, void* out, int full,
+              hipStream_t st) {
   if (w.dtype == DSVT_BF16) {
-    if (w.C == 192) return launch_attention<bf16_t, 192, 8, 3, 3>(w, mp, coords, x, out, full, st);
-    return launch_attention<bf16_t, 64, 4, 3, 1>(w, mp, coords, x, out, full, st);
+    if (w.C == 192) return launch_layer<bf16_t, 192, 8, 384, 3, 3, 3, 3, 2>(w, mp, coords, x, out, full, st);
+    return launch_layer<bf16_t, 64, 4, 128, 3, 1, 2, 1, 1>(w, mp, coords, x, out, full, st);
   }
-  return launch_attention<float, 64, 4, 3, 1>(w, mp, coords, x, out, full, st);
-}
-
-int run_ffn(const dsvt_layer_w& w, const void* x1, void* out, int32_t n, hipStream_t st) {
-  if (w.dtype == DSVT_BF16) {
-    if (w.C == 192) return launch_ffn<bf16_t, 192, 384, 3, 3>(w, x1, out, n, st);
-    return launch_ffn<bf16_t, 64, 128, 2, 1>(w, x1, out, n, st);
-  }
-  return launch_ffn<float, 64, 128, 2, 1>(w, x1, out, n, st);
+  return launch_layer<float, 64, 4, 128, 3, 1, 2, 1, 1>(w, mp, coords, x, out, full, st);
 }
 
 }  // namespace
@@ -551,7 +558,7 @@ extern "C" int dsvt_set_attention(const dsvt_layer_w* layer, const dsvt_maps* ma
   rc = check_maps(*maps);
   if (rc != DSVT_OK) return rc;
   if (!aligned16(x) || !aligned16(y) || !aligned16(coords)) return DSVT_EINVAL;
-  rc = run_attention(*layer, *maps, coords, x, y, 0, (hipStream_t)stream);
+  rc = run_layer(*layer, *maps, coords, x, y, 0, (hipStream_t)stream);
   if (rc != DSVT_OK) return rc;
   DSVT_HIP_TRY(hipGetLastError());
   return DSVT_OK;
@@ -573,11 +580,7 @@ extern "C" int dsvt_block(const dsvt_layer_w layer[2], const dsvt_maps maps[2], 
   hipStream_t st = (hipStream_t)stream;
   const void* src = x_in;
   for (int l = 0; l < 2; ++l) {
-    // A set's workgroup reads its voxels' rows before it writes them and no other workgroup
-    // touches those rows, so the attention half may run in place; so may the row-tiled FFN.
-    int rc = run_attention(layer[l], maps[l], coords, src, x_out, 1, st);
-    if (rc != DSVT_OK) return rc;
-    rc = run_ffn(layer[l], x_out, x_out, maps[l].n_voxels, st);
+    int rc = run_layer(layer[l], maps[l], coords, src, x_out, 1, st);
     if (rc != DSVT_OK) return rc;
     src = x_out;
   }

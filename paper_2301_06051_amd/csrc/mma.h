@@ -63,31 +63,91 @@ template <typename T> __device__ __forceinline__ float to_f32(T v) { return (flo
 // start in different banks.
 template <typename T> constexpr int lds_pad() { return 16 / (int)sizeof(T); }
 
-// acc[nt][rt] += W[o0 + 16*nt + .][0..K) . X[16*rt + .][0..K) for nt < NT, rt < rt_count.
-// W: global, row pitch ldw elements.  X: LDS, row pitch ldx elements (16-byte multiple).
-template <typename T, int NT, int RT_MAX>
-__device__ __forceinline__ void gemm_wx(const T* __restrict__ W, int ldw, int o0, const T* Xs, int ldx, int K,
-                                        int rt_count, f32x4 (&acc)[NT][RT_MAX]) {
+// A-operand fragments of NT output tiles over KF consecutive k-fragments, kept in registers so
+// that all of a tile group's weight loads are in flight at once.
+template <typename T, int NT, int KF> struct AReg { typename Mma<T>::Frag f[KF][NT]; };
+
+// W: global [out, in] with row pitch ldw; rows o0 .. o0 + 16*NT - 1, k from k0.
+template <typename T, int NT, int KF>
+__device__ __forceinline__ void load_a(AReg<T, NT, KF>& a, const T* __restrict__ W, int ldw, int o0, int k0) {
   typedef typename Mma<T>::Frag Frag;
-  constexpr int KC = Mma<T>::KC, KL = Mma<T>::KL;
   const int lane = threadIdx.x & 63, m = lane & 15, g = lane >> 4;
-  const T* wp = W + (size_t)(o0 + m) * ldw + g * KL;
-  const T* xp = Xs + m * ldx + g * KL;
-#pragma unroll 2
-  for (int k0 = 0; k0 < K; k0 += KC) {
-    Frag a[NT];
+  const T* wp = W + (size_t)(o0 + m) * ldw + k0 + g * Mma<T>::KL;
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) a[nt] = *reinterpret_cast<const Frag*>(wp + (size_t)(16 * nt) * ldw + k0);
+  for (int kf = 0; kf < KF; ++kf)
 #pragma unroll
-    for (int rt = 0; rt < RT_MAX; ++rt) {
-      if (rt < rt_count) {
-        Frag b = *reinterpret_cast<const Frag*>(xp + (16 * rt) * ldx + k0);
+    for (int nt = 0; nt < NT; ++nt)
+      a.f[kf][nt] = *reinterpret_cast<const Frag*>(wp + (size_t)(16 * nt) * ldw + kf * Mma<T>::KC);
+}
+
+// acc[nt][r] += W-fragments . X[16*(rt0+r) + .][k0 ...) for r < rt_cnt (<= RH).  X: LDS, pitch ldx.
+template <typename T, int NT, int KF, int RH>
+__device__ __forceinline__ void mma_rows(const AReg<T, NT, KF>& a, const T* Xs, int ldx, int k0, int rt0, int rt_cnt,
+                                         f32x4 (&acc)[NT][RH]) {
+  typedef typename Mma<T>::Frag Frag;
+  const int lane = threadIdx.x & 63, m = lane & 15, g = lane >> 4;
+  const T* xp = Xs + (16 * rt0 + m) * ldx + k0 + g * Mma<T>::KL;
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) acc[nt][rt] = Mma<T>::mma(a[nt], b, acc[nt][rt]);
+  for (int kf = 0; kf < KF; ++kf) {
+#pragma unroll
+    for (int r = 0; r < RH; ++r) {
+      if (r < rt_cnt) {
+        const Frag b = *reinterpret_cast<const Frag*>(xp + (16 * r) * ldx + kf * Mma<T>::KC);
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) acc[nt][r] = Mma<T>::mma(a.f[kf][nt], b, acc[nt][r]);
       }
     }
   }
 }
+
+// One GEMM phase of a workgroup of NW wavefronts: Out^T[NOUT x rows] = W[NOUT x K] . X^T.
+// Work items are (group of NT output tiles, half of the row tiles); wavefront w takes items
+// w, w + NW, ...  Each item's weights are loaded in KSPLIT units of K/KSPLIT columns, and unit
+// u + 1 is requested before unit u is consumed, so global-load latency overlaps the MFMAs.
+template <typename T, int NT, int K, int NOUT, int NW, int KSPLIT> struct GemmPhase {
+  static constexpr int KC = Mma<T>::KC;
+  static constexpr int KFU = K / KC / KSPLIT;
+  static constexpr int N_OG = NOUT / (16 * NT);
+  static constexpr int N_ITEMS = 2 * N_OG;
+  static constexpr int IPW = N_ITEMS / NW;
+  static constexpr int UNITS = IPW * KSPLIT;
+  static constexpr int RH = 3;               // row tiles per item: half of at most 6
+  static_assert(N_ITEMS % NW == 0 && K % (KC * KSPLIT) == 0 && NOUT % (16 * NT) == 0, "phase shape");
+  AReg<T, NT, KFU> a[2];
+  const T* W;
+  int wave;
+
+  __device__ __forceinline__ GemmPhase(const void* w, int wave_) : W(reinterpret_cast<const T*>(w)), wave(wave_) {}
+
+  __device__ __forceinline__ void issue(int u) {
+    const int item = wave + (u / KSPLIT) * NW;
+    load_a<T, NT, KFU>(a[u & 1], W, K, (item % N_OG) * 16 * NT, (u % KSPLIT) * KFU * KC);
+  }
+
+  // Needs issue(0) beforehand.  epi(o0, rt0, cnt, acc): acc[nt][r][i] is output feature
+  // o0 + 16*nt + 4*g + i of row 16*(rt0 + r) + m, for r < cnt.
+  template <typename Epi> __device__ __forceinline__ void run(const T* Xs, int ldx, int RT, Epi epi) {
+    const int h0 = (RT + 1) >> 1;
+#pragma unroll
+    for (int it = 0; it < IPW; ++it) {
+      const int item = wave + it * NW;
+      const int og = item % N_OG, half = item / N_OG;
+      const int rt0 = half ? h0 : 0, cnt = half ? RT - h0 : h0;
+      f32x4 acc[NT][RH];
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int r = 0; r < RH; ++r) acc[nt][r] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int kh = 0; kh < KSPLIT; ++kh) {
+        const int u = it * KSPLIT + kh;
+        if (u + 1 < UNITS) issue(u + 1);
+        mma_rows<T, NT, KFU, RH>(a[u & 1], Xs, ldx, kh * KFU * KC, rt0, cnt, acc);
+      }
+      epi(og * 16 * NT, rt0, cnt, acc);
+    }
+  }
+};
 
 template <int NT, int RT_MAX> __device__ __forceinline__ void zero_acc(f32x4 (&acc)[NT][RT_MAX]) {
 #pragma unroll

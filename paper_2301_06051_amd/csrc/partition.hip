@@ -131,14 +131,76 @@ __global__ void k_emit(const uint32_t* __restrict__ keys, int32_t n, const uint3
     int64_t slot = base + t;
     if (slot >= cap) break;
     set_inds[slot] = i;
-    if (set_win != nullptr && t % tau == 0) set_win[slot / tau] = w;
+    if (t % tau == 0) set_win[slot / tau] = w;
   }
+}
+
+
+// Rows a set occupies in a layer workgroup's tile: its distinct voxels (closed form from Eq. 3),
+// rounded up to a multiple of 4.
+__device__ __forceinline__ int32_t padded_rows(int32_t s, const int32_t* __restrict__ set_win,
+                                               const int32_t* __restrict__ win_count,
+                                               const int32_t* __restrict__ win_soff, int32_t tau,
+                                               int32_t n_windows) {
+  const int32_t w = set_win[s];
+  if (w < 0 || w >= n_windows || win_count[w] <= 0) return 4;   // only reachable after a reported input error
+  const int64_t N = win_count[w], S = (N + tau - 1) / tau, j = s - win_soff[w];
+  const int64_t lo = (j * tau * N) / (S * tau), hi = ((j * tau + tau - 1) * N) / (S * tau);
+  return (int32_t)((hi - lo + 1 + 3) & ~3ll);
+}
+
+// One workgroup: cut the set sequence into tiles for the layer kernels.  With P(s) the running
+// sum of padded rows before set s, set s goes to tile P(s) / rows_per_cut; a tile then holds at
+// most rows_per_cut - 4 + pad4(tau) rows and no tile is empty.
+__global__ void __launch_bounds__(1024) k_tiles(const int32_t* __restrict__ set_win,
+                                                const int32_t* __restrict__ win_count,
+                                                const int32_t* __restrict__ win_soff, const int32_t* __restrict__ n_sets_ptr,
+                                                int32_t set_cap, int32_t tau, int32_t n_windows, int32_t rows_per_cut,
+                                                int32_t* __restrict__ tile_first, int32_t* __restrict__ n_tiles,
+                                                int32_t max_tiles) {
+  __shared__ int32_t wave_tot[16];
+  __shared__ int32_t carry_s;
+  const int32_t tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  int32_t n_sets = *n_sets_ptr;
+  n_sets = n_sets < set_cap ? n_sets : set_cap;
+  if (tid == 0) carry_s = 0;
+  __syncthreads();
+  for (int32_t base = 0; base < n_sets; base += 1024) {
+    const int32_t s = base + tid;
+    const int32_t rows = s < n_sets ? padded_rows(s, set_win, win_count, win_soff, tau, n_windows) : 0;
+    int32_t incl = rows;
+    for (int32_t d = 1; d < 64; d <<= 1) {
+      int32_t up = __shfl_up(incl, d, 64);
+      if (lane >= d) incl += up;
+    }
+    if (lane == 63) wave_tot[wv] = incl;
+    __syncthreads();
+    int32_t before = carry_s;
+    for (int32_t k = 0; k < wv; ++k) before += wave_tot[k];
+    const int32_t P = before + incl - rows;                 // rows before set s
+    if (s < n_sets) {
+      const int32_t tile = P / rows_per_cut;
+      bool first = s == 0;
+      if (!first) first = (P - padded_rows(s - 1, set_win, win_count, win_soff, tau, n_windows)) / rows_per_cut != tile;
+      if (first && tile < max_tiles) tile_first[tile] = s;
+      if (s == n_sets - 1) {
+        const int32_t nt = tile + 1 < max_tiles ? tile + 1 : max_tiles;
+        *n_tiles = nt;
+        tile_first[nt] = n_sets;
+      }
+    }
+    __syncthreads();
+    if (tid == 1023) carry_s = before + incl;
+    __syncthreads();
+  }
+  if (n_sets <= 0 && tid == 0) { *n_tiles = 0; tile_first[0] = 0; }
 }
 
 struct PartPlan {
   PartGeom g;
-  size_t off_bitmap, off_prefix, off_count, off_soff, off_keys, total;
+  size_t off_bitmap, off_prefix, off_count, off_soff, off_keys, off_setwin, total;
   int64_t n_words;
+  int32_t set_bound, tile_bound, rows_per_cut;
 };
 
 int make_plan(const dsvt_part_cfg* cfg, int32_t n_voxels, PartPlan* p) {
@@ -166,32 +228,49 @@ int make_plan(const dsvt_part_cfg* cfg, int32_t n_voxels, PartPlan* p) {
   p->off_count = o;  o = dsvt_align_up(o + (size_t)nwin * 4, 256);
   p->off_soff = o;   o = dsvt_align_up(o + (size_t)nwin * 4, 256);
   p->off_keys = o;   o = dsvt_align_up(o + (size_t)n_voxels * 4, 256);
+  const int64_t bound = n_voxels / cfg->tau + (n_voxels < nwin ? n_voxels : nwin);
+  if (bound * cfg->tau >= (1ll << 31)) return DSVT_EINVAL;
+  p->set_bound = (int32_t)bound;
+  p->off_setwin = o; o = dsvt_align_up(o + (size_t)bound * 4, 256);
+  // tiles of the layer kernels: 96 rows, every set padded to a multiple of 4 rows
+  const int64_t pad_tau = (cfg->tau + 3) & ~3;
+  p->rows_per_cut = (int32_t)(100 - pad_tau);
+  p->tile_bound = p->rows_per_cut > 0 ? (int32_t)((n_voxels + 3 * bound) / p->rows_per_cut + 1) : 0;
   p->total = o;
   return DSVT_OK;
 }
 
 }  // namespace
 
-extern "C" int dsvt_partition_bound(const dsvt_part_cfg* cfg, int32_t n_voxels, int32_t* max_sets, size_t* ws_bytes) {
+extern "C" int dsvt_partition_bound(const dsvt_part_cfg* cfg, int32_t n_voxels, int32_t* max_sets, int32_t* max_tiles,
+                                    size_t* ws_bytes) {
   PartPlan p;
   int rc = make_plan(cfg, n_voxels, &p);
   if (rc != DSVT_OK) return rc;
-  int64_t bound = n_voxels / cfg->tau + (n_voxels < p.g.n_windows ? n_voxels : p.g.n_windows);
-  if (bound * cfg->tau >= (1ll << 31)) return DSVT_EINVAL;
-  if (max_sets) *max_sets = (int32_t)bound;
+  if (max_sets) *max_sets = p.set_bound;
+  if (max_tiles) *max_tiles = p.tile_bound;
   if (ws_bytes) *ws_bytes = p.total;
   return DSVT_OK;
 }
 
 extern "C" int dsvt_partition(const dsvt_part_cfg* cfg, const int32_t* coords, int32_t n_voxels, int32_t* set_inds,
-                              int32_t* voxel_slot, int32_t* n_sets, int32_t max_sets, int32_t* set_win, void* ws,
-                              size_t ws_bytes, int32_t* status, void* stream) {
+                              int32_t* voxel_slot, int32_t* n_sets, int32_t max_sets, int32_t* set_win,
+                              int32_t* tile_first, int32_t* n_tiles, int32_t max_tiles, void* ws, size_t ws_bytes,
+                              int32_t* status, void* stream) {
   PartPlan p;
   int rc = make_plan(cfg, n_voxels, &p);
   if (rc != DSVT_OK) return rc;
   if (!coords || !set_inds || !voxel_slot || !n_sets || !ws || !status || max_sets <= 0) return DSVT_EINVAL;
   if ((int64_t)max_sets * cfg->tau >= (1ll << 31)) return DSVT_EINVAL;
   if (ws_bytes < p.total) return DSVT_ENOSPC;
+  if ((tile_first != nullptr) != (n_tiles != nullptr)) return DSVT_EINVAL;
+  if (tile_first != nullptr && (max_tiles <= 0 || p.rows_per_cut < 48)) return max_tiles <= 0 ? DSVT_EINVAL : DSVT_EUNSUPPORTED;
+  // window key of every set: the caller's array, or scratch when it is not wanted
+  int32_t set_cap = max_sets;
+  if (set_win == nullptr) {
+    set_win = (int32_t*)((char*)ws + p.off_setwin);
+    set_cap = max_sets < p.set_bound ? max_sets : p.set_bound;
+  }
   hipStream_t st = (hipStream_t)stream;
   char* base = (char*)ws;
   uint32_t* bitmap = (uint32_t*)(base + p.off_bitmap);
@@ -223,8 +302,13 @@ extern "C" int dsvt_partition(const dsvt_part_cfg* cfg, const int32_t* coords, i
   {
     dsvt_prof_scope ps(DSVT_K_PART_EMIT, st);
     k_emit<<<(unsigned)dsvt_ceil_div(n_voxels, tb), tb, 0, st>>>(keys, n_voxels, bitmap, prefix, count, soff,
-                                                                 p.g.words_per_win, cfg->tau, max_sets, set_inds,
+                                                                 p.g.words_per_win, cfg->tau, set_cap, set_inds,
                                                                  voxel_slot, set_win);
+  }
+  if (tile_first != nullptr) {
+    dsvt_prof_scope ps(DSVT_K_PART_TILES, st);
+    k_tiles<<<1, 1024, 0, st>>>(set_win, count, soff, n_sets, set_cap, cfg->tau, p.g.n_windows, p.rows_per_cut, tile_first, n_tiles,
+                                max_tiles);
   }
   DSVT_HIP_TRY(hipGetLastError());
   return DSVT_OK;

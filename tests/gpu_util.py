@@ -23,9 +23,24 @@ def dev_feats(x, dtype):
     return torch.as_tensor(x).cuda().to(torch.bfloat16 if dtype == "bf16" else torch.float32).contiguous()
 
 
-def gpu_maps(coords_d, grid, win, shift, tau, batch, axis):
+def gpu_maps(coords_d, grid, win, shift, tau, batch, axis, tiles=True):
     cfg = dsvt.part_cfg(grid, win, shift, tau, batch, axis)
-    return dsvt.dsvt_partition(cfg, coords_d)
+    return dsvt.dsvt_partition(cfg, coords_d, out=dsvt.SetMaps(cfg, coords_d.shape[0], tiles=tiles))
+
+
+def assert_tiles_valid(gm, om):
+    """The workgroup tile list is a scheduling aid, not part of the method: check that it is a
+    partition of the set sequence into runs whose distinct voxels (each set padded to a multiple
+    of 4 rows) fit 96 rows."""
+    if not gm.max_tiles:
+        return
+    nt = int(gm.n_tiles.item())
+    tf = gm.tile_first[:nt + 1].cpu().numpy()
+    assert 0 < nt <= gm.max_tiles and tf[0] == 0 and tf[-1] == om["n_sets"] and np.all(np.diff(tf) > 0)
+    si = om["set_inds"]
+    uniq = 1 + (np.diff(si, axis=1) != 0).sum(1)
+    rows = np.add.reduceat((uniq + 3) // 4 * 4, tf[:-1])
+    assert rows.max() <= 96
 
 
 def assert_maps_equal(gm, om):
@@ -38,3 +53,4 @@ def assert_maps_equal(gm, om):
     assert np.array_equal(gm.voxel_slot.cpu().numpy(), om["voxel_slot"])
     assert np.array_equal(gm.set_win[:n_sets].cpu().numpy(), om["set_win"])
     assert torch.all(gm.set_inds[n_sets:] == -1)          # rows past n_sets are left alone
+    assert_tiles_valid(gm, om)

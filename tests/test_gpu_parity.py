@@ -105,15 +105,16 @@ def test_set_attention_parity(cid, n, dup_mode, rel_bias):
     assert err < TOL[cfg["dtype"]]
 
 
+@pytest.mark.parametrize("tiles", [True, False])
 @pytest.mark.parametrize("cid,n", [(1, None), (2, 5000), (3, 8000)])
-def test_block_parity(cid, n):
+def test_block_parity(cid, n, tiles):
     cfg, coords, x, shift, mk = _layer_case(cid, n, 32)
     ws = [mk(71), mk(72)]
-    _say(f"block cfg{cid} n={len(coords)}")
+    _say(f"block cfg{cid} n={len(coords)} tiles={tiles}")
     oms = [orc.partition(coords, cfg["grid"], cfg["win"], shift, cfg["tau"], a) for a in (0, 1)]
     ref = orc.block(ws, oms, coords, x)
     cd = dev_coords(coords)
-    gms = [gpu_maps(cd, cfg["grid"], cfg["win"], shift, cfg["tau"], cfg["batch"], a) for a in (0, 1)]
+    gms = [gpu_maps(cd, cfg["grid"], cfg["win"], shift, cfg["tau"], cfg["batch"], a, tiles) for a in (0, 1)]
     xd = dev_feats(x, cfg["dtype"])
     out = dsvt.dsvt_block([dsvt.LayerWeights(w) for w in ws], gms, cd, xd)
     torch.cuda.synchronize()
