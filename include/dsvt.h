@@ -111,10 +111,19 @@ typedef struct {
   int32_t win[3];        /* L, W, H of the window the maps were built with               */
   int32_t dup_mode;      /* 0: a slot repeating its predecessor's voxel is masked as a key
                                (sentence after Eq. 3); 1: repeated slots stay as keys    */
+  const void* packed;    /* [device] the four matrices re-ordered for the matrix cores by
+                            dsvt_layer_pack; the layer kernels read the matrices only from here */
 } dsvt_layer_w;
 
 /* Supported shapes: (C,heads,hidden) = (64,4,128) in F32 or BF16 and (192,8,384) in BF16, tau <= 48;
  * anything else returns DSVT_EUNSUPPORTED. */
+
+/* Weight preparation, once per layer (weights do not change between frames).
+ * dsvt_layer_packed_size: host-only, bytes of the packed buffer for this layer's shape.
+ * dsvt_layer_pack: enqueue the re-ordering of w_qkv, w_o, w_1, w_2 into `packed` ([device], 16-byte
+ * aligned, at least that many bytes; DSVT_ENOSPC otherwise).  Afterwards set layer->packed = packed. */
+int dsvt_layer_packed_size(const dsvt_layer_w* layer, size_t* bytes);
+int dsvt_layer_pack(const dsvt_layer_w* layer, void* packed, size_t bytes, void* stream);
 
 /* Host-only: scratch bytes the two calls below need (currently 0; callers must still ask). */
 int dsvt_block_workspace_size(const dsvt_layer_w* layer, int32_t n_voxels, size_t* bytes);

@@ -37,7 +37,8 @@ class LayerW(C.Structure):
                 ("w_qkv", C.c_void_p), ("w_o", C.c_void_p), ("w_1", C.c_void_p), ("w_2", C.c_void_p),
                 ("b_qkv", C.c_void_p), ("b_o", C.c_void_p), ("b_1", C.c_void_p), ("b_2", C.c_void_p),
                 ("ln1_g", C.c_void_p), ("ln1_b", C.c_void_p), ("ln2_g", C.c_void_p), ("ln2_b", C.c_void_p),
-                ("ln_eps", C.c_float), ("rel_bias", C.c_void_p), ("win", I32x3), ("dup_mode", C.c_int32)]
+                ("ln_eps", C.c_float), ("rel_bias", C.c_void_p), ("win", I32x3), ("dup_mode", C.c_int32),
+                ("packed", C.c_void_p)]
 
 
 class PoolCfg(C.Structure):
@@ -62,6 +63,8 @@ def lib():
         vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
         L.dsvt_partition_bound.argtypes = [C.POINTER(PartCfg), i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(sz)]
         L.dsvt_partition.argtypes = [C.POINTER(PartCfg), vp, i32, vp, vp, vp, i32, vp, vp, vp, i32, vp, sz, vp, vp]
+        L.dsvt_layer_packed_size.argtypes = [C.POINTER(LayerW), C.POINTER(sz)]
+        L.dsvt_layer_pack.argtypes = [C.POINTER(LayerW), vp, sz, vp]
         L.dsvt_block_workspace_size.argtypes = [C.POINTER(LayerW), i32, C.POINTER(sz)]
         L.dsvt_set_attention.argtypes = [C.POINTER(LayerW), C.POINTER(Maps), vp, vp, vp, vp, sz, vp]
         L.dsvt_block.argtypes = [C.POINTER(LayerW), C.POINTER(Maps), vp, vp, vp, vp, sz, vp]
@@ -160,7 +163,12 @@ class LayerWeights:
         p = lambda k: self.t[k].data_ptr() if self.t[k] is not None else None
         self.struct = LayerW(w["C"], w["heads"], w["hidden"], code, p("w_qkv"), p("w_o"), p("w_1"), p("w_2"),
                              p("b_qkv"), p("b_o"), p("b_1"), p("b_2"), p("ln1_g"), p("ln1_b"), p("ln2_g"), p("ln2_b"),
-                             w["ln_eps"], p("rel_bias"), I32x3(*w["win"]), dup_mode)
+                             w["ln_eps"], p("rel_bias"), I32x3(*w["win"]), dup_mode, None)
+        nbytes = C.c_size_t(0)
+        _check("dsvt_layer_packed_size", lib().dsvt_layer_packed_size(C.byref(self.struct), C.byref(nbytes)))
+        self.packed = torch.empty((nbytes.value,), dtype=torch.uint8, device="cuda")
+        _check("dsvt_layer_pack", lib().dsvt_layer_pack(C.byref(self.struct), _ptr(self.packed), nbytes.value, _stream(None)))
+        self.struct.packed = self.packed.data_ptr()
 
 
 def dsvt_block_workspace_size(layer, n_voxels):

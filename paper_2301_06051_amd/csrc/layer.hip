@@ -16,19 +16,30 @@ namespace {
 
 constexpr int kTauMax = 48;
 constexpr int kRowsMax = 96;                     // rows of a tile = 6 MFMA row tiles
-constexpr int kKeyTiles = kTauMax / 16;          // 3
 constexpr int kMaxSets = kRowsMax / 4;           // every set takes at least 4 rows of a tile
+constexpr int kRowsPad = kRowsMax + 16;          // per-row arrays are read 4 at a time up to 15 rows past a set's end
+constexpr int kMaxItems = 2 * (kRowsMax / 16 + kMaxSets);   // attention items: (set, query tile, half of the heads)
 constexpr int kFixedSets = kRowsMax / kTauMax;   // sets per workgroup when no tile list is given
-constexpr int kWaves = 8;
-constexpr int kStatGroups = 4;                   // output-tile groups of the LayerNorm phases
+constexpr int kWaves = 4;                        // one per SIMD: the LDS tile leaves room for one workgroup per CU
+constexpr int kStatGroups = kWaves;              // LayerNorm phases: every wavefront owns C / 4 features of all rows
 
 struct LayerDev {
-  const void *w_qkv, *w_o, *w_1, *w_2;
+  const void *w_qkv, *w_o, *w_1, *w_2;       // packed (see mma.h)
   const float *b_qkv, *b_o, *b_1, *b_2, *ln1_g, *ln1_b, *ln2_g, *ln2_b, *rel_bias;
   float ln_eps;
   int rel_size, rel_const, rel_my, rel_mz;   // table entries per head; index = lin(q) - lin(k) + rel_const
   int dup_mode;
+#ifdef DSVT_PHASE_CLOCKS
+  long long* clk;                            // [blocks][16] shader-clock stamps of wavefront 0 (debug builds)
+#endif
 };
+
+#ifdef DSVT_PHASE_CLOCKS
+long long* g_phase_clocks = nullptr;
+#define DSVT_CLK(k) do { if (p.clk && threadIdx.x == 0) p.clk[blockIdx.x * 16 + (k)] = clock64(); } while (0)
+#else
+#define DSVT_CLK(k) do {} while (0)
+#endif
 
 struct MapsDev {
   const int32_t *set_inds, *n_sets, *tile_first, *n_tiles;
@@ -46,7 +57,7 @@ template <typename T, int C, int HEADS, int HID> struct LayerLds {
   static constexpr size_t kVt = (size_t)C * LDV * sizeof(T);
   static constexpr size_t off_h = off_q;         // hidden tile reuses Q and K once attention is done
   static constexpr size_t off_misc = off_v + kVt;
-  static constexpr size_t kMisc = (size_t)(3 * kRowsMax + 2 * kMaxSets + 2 + 2 * kStatGroups * kRowsMax) * 4;
+  static constexpr size_t kMisc = (size_t)(3 * kRowsPad + 2 * kMaxSets + 2 + 2 * kStatGroups * kRowsMax + kMaxItems + 1) * 4;
   static constexpr size_t total = off_misc + kMisc;
   static_assert((size_t)kRowsMax * LDH * sizeof(T) <= 2 * kTile, "hidden tile must fit in Q + K");
   static_assert(C % 64 == 0 && D % Mma<T>::KL == 0 && D % 4 == 0, "shape");
@@ -54,75 +65,207 @@ template <typename T, int C, int HEADS, int HID> struct LayerLds {
 
 // LayerNorm over the C features of every row, for values spread over the workgroup in
 // accumulator layout: this wavefront holds features o0 .. o0 + 16*NT - 1 (group og of
-// kStatGroups) of rows 16*(rt0 + r) + m, r < cnt.  Two-pass (mean, then centred squares) with
-// the per-group partial sums exchanged through LDS.  Every thread of the workgroup must call it.
-template <typename T, int NT>
-__device__ __forceinline__ void layer_norm_tile(f32x4 (&v)[NT][3], int C, int o0, int og, int rt0, int cnt, float* stat,
-                                                const float* __restrict__ gamma, const float* __restrict__ beta,
-                                                float eps, T* dst, int ldd) {
+// kStatGroups) of rows 16*r + m, r < RT.  Per-group sums of x and x^2 (fp32) are exchanged
+// through LDS; variance = E[x^2] - mean^2.  Every thread of the workgroup must call it.
+template <typename T, int NT, int C>
+__device__ __forceinline__ void layer_norm_tile(f32x4 (&v)[NT][kRowTiles], int o0, int og, int RT, float* stat,
+                                                const f32x4 (&ga)[NT], const f32x4 (&be)[NT], float eps, T* dst,
+                                                int ldd) {
   typedef typename Mma<T>::Vec4 Vec4;
   const int lane = threadIdx.x & 63, m = lane & 15, g = lane >> 4;
   float* stat1 = stat;
   float* stat2 = stat + kStatGroups * kRowsMax;
-  float mean[3], rs[3];
 #pragma unroll
-  for (int r = 0; r < 3; ++r) {
-    float s = 0.f;
+  for (int r = 0; r < kRowTiles; ++r) {
+    if (r < RT) {
+      float s = 0.f, q = 0.f;
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) s += v[nt][r][0] + v[nt][r][1] + v[nt][r][2] + v[nt][r][3];
-    s += __shfl_xor(s, 16, 64);
-    s += __shfl_xor(s, 32, 64);
-    if (g == 0 && r < cnt) stat1[og * kRowsMax + 16 * (rt0 + r) + m] = s;
+      for (int nt = 0; nt < NT; ++nt) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { s += v[nt][r][i]; q = fmaf(v[nt][r][i], v[nt][r][i], q); }
+      }
+      s = col_sum(s);
+      q = col_sum(q);
+      if (g == 0) { stat1[og * kRowsMax + 16 * r + m] = s; stat2[og * kRowsMax + 16 * r + m] = q; }
+    }
   }
   __syncthreads();
 #pragma unroll
-  for (int r = 0; r < 3; ++r) {
-    mean[r] = 0.f;
-    if (r < cnt) {
-      const int row = 16 * (rt0 + r) + m;
-      float t = 0.f;
+  for (int r = 0; r < kRowTiles; ++r) {
+    if (r < RT) {
+      const int row = 16 * r + m;
+      float s = 0.f, q = 0.f;
 #pragma unroll
-      for (int k = 0; k < kStatGroups; ++k) t += stat1[k * kRowsMax + row];
-      mean[r] = t / (float)C;
-    }
-    float s = 0.f;
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-      v[nt][r] -= mean[r];
-      s += v[nt][r][0] * v[nt][r][0] + v[nt][r][1] * v[nt][r][1] + v[nt][r][2] * v[nt][r][2] + v[nt][r][3] * v[nt][r][3];
-    }
-    s += __shfl_xor(s, 16, 64);
-    s += __shfl_xor(s, 32, 64);
-    if (g == 0 && r < cnt) stat2[og * kRowsMax + 16 * (rt0 + r) + m] = s;
-  }
-  __syncthreads();
-#pragma unroll
-  for (int r = 0; r < 3; ++r) {
-    if (r < cnt) {
-      const int row = 16 * (rt0 + r) + m;
-      float t = 0.f;
-#pragma unroll
-      for (int k = 0; k < kStatGroups; ++k) t += stat2[k * kRowsMax + row];
-      rs[r] = rsqrtf(t / (float)C + eps);
+      for (int k = 0; k < kStatGroups; ++k) { s += stat1[k * kRowsMax + row]; q += stat2[k * kRowsMax + row]; }
+      const float mean = s * (1.0f / C);
+      const float rs = rsqrtf(fmaxf(fmaf(-mean, mean, q * (1.0f / C)), 0.f) + eps);
+      const float sh = -mean * rs;
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) {
         const int o = o0 + 16 * nt + 4 * g;
-        const f32x4 ga = *reinterpret_cast<const f32x4*>(gamma + o), be = *reinterpret_cast<const f32x4*>(beta + o);
-        *reinterpret_cast<Vec4*>(dst + row * ldd + o) = pack4<T>(v[nt][r] * rs[r] * ga + be);
+        f32x4 y;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) y[i] = fmaf(fmaf(v[nt][r][i], rs, sh), ga[nt][i], be[nt][i]);
+        *reinterpret_cast<Vec4*>(dst + row * ldd + o) = pack4<T>(y);
       }
     }
   }
 }
 
-template <typename T, int C, int HEADS, int HID, int NT_QKV, int NT_O, int NT_1, int NT_2, int KSPLIT_2>
-__global__ void __launch_bounds__(kWaves * 64)
-k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* out, int full_layer) {
-  // out may be x: a tile's rows are read, then written, by this workgroup only
+// Attention of one (set, query tile, half of the heads) item (Eq. 5): for each of its heads,
+// logits = Q K^T (+ PE), softmax over the set's distinct voxels, O = P V; O overwrites the Q
+// entries it was computed from.  KTC = key tiles of the set (compile time: no branches inside).
+// S^T is produced key-major (keys as MFMA rows) so that a lane holds 4 keys of ONE query: the
+// softmax reductions are in-lane plus two cross-lane steps, and P^T is already laid out as the B
+// operand of O^T = V^T P^T.  The positional term depends on (query, key) only through the
+// coordinate difference, i.e. one table row [idx][heads] per pair, fetched once for all heads.
+template <typename T, int C, int HEADS, int HID, int KTC>
+__device__ __forceinline__ void attn_item(const LayerDev& p, T* Qs, const T* Ks, const T* Vt, const int32_t* row_lin,
+                                          const float* row_mult, int r0, int nu, int qt, int hh, int rows_ready) {
   typedef LayerLds<T, C, HEADS, HID> L;
   typedef Mma<T> M;
   typedef typename M::Frag Frag;
   typedef typename M::Vec4 Vec4;
-  constexpr int D = L::D, LDX = L::LDX, LDV = L::LDV, LDH = L::LDH, KC = M::KC, KL = M::KL;
+  constexpr int D = L::D, LDX = L::LDX, LDV = L::LDV, KC = M::KC, KL = M::KL, HG = HEADS / 2;
+  constexpr int TPC = KC / 16;                    // key tiles per PV fragment: 2 (bf16) or 1 (fp32)
+  constexpr int NCH = (KTC + TPC - 1) / TPC;
+  static_assert(HG == 2 || HG == 4, "heads per item");
+  const int lane = threadIdx.x & 63, m = lane & 15, g = lane >> 4;
+  const int qi = 16 * qt + m;
+  const int qrow = r0 + (qi < nu ? qi : nu - 1);
+
+  constexpr float kLog2e = 1.4426950408889634f;
+  const float scale2 = rsqrtf((float)D) * kLog2e;
+  const bool dup = p.dup_mode != 0;
+  float bias[KTC][4][HG];
+  float mult[KTC][4];
+#pragma unroll
+  for (int kt = 0; kt < KTC; ++kt)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      mult[kt][i] = 1.0f;
+#pragma unroll
+      for (int hl = 0; hl < HG; ++hl) bias[kt][i][hl] = 0.f;
+    }
+  if (p.rel_bias != nullptr) {
+    const int ql = row_lin[qrow] + p.rel_const;
+#pragma unroll
+    for (int kt = 0; kt < KTC; ++kt) {
+      const int4 kl = *reinterpret_cast<const int4*>(row_lin + r0 + 16 * kt + 4 * g);
+      const int kls[4] = {kl.x, kl.y, kl.z, kl.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        int idx = ql - kls[i];
+        idx = idx < 0 ? 0 : (idx >= p.rel_size ? p.rel_size - 1 : idx);
+        const float* tp = p.rel_bias + (size_t)idx * HEADS + hh * HG;
+        if constexpr (HG == 4) {
+          const f32x4 t = *reinterpret_cast<const f32x4*>(tp);
+          bias[kt][i][0] = t[0] * kLog2e; bias[kt][i][1] = t[1] * kLog2e; bias[kt][i][2] = t[2] * kLog2e;
+          bias[kt][i][3] = t[3] * kLog2e;
+        } else {
+          const float2 t = *reinterpret_cast<const float2*>(tp);
+          bias[kt][i][0] = t.x * kLog2e; bias[kt][i][1] = t.y * kLog2e;
+        }
+      }
+    }
+  }
+  if (p.dup_mode) {
+#pragma unroll
+    for (int kt = 0; kt < KTC; ++kt) {
+      const f32x4 t = *reinterpret_cast<const f32x4*>(row_mult + r0 + 16 * kt + 4 * g);
+      mult[kt][0] = t[0]; mult[kt][1] = t[1]; mult[kt][2] = t[2]; mult[kt][3] = t[3];
+    }
+  }
+
+#pragma unroll
+  for (int hl = 0; hl < HG; ++hl) {
+    const int h = hh * HG + hl;
+    f32x4 S[KTC];                                 // S[kt][i]: key 16*kt + 4*g + i, query 16*qt + m
+#pragma unroll
+    for (int kt = 0; kt < KTC; ++kt) S[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kc = 0; kc < D; kc += KC) {
+      const int kk = kc + g * KL;
+      const bool live = kk < D;                   // lanes past the head width feed zeros
+      const int kkc = live ? kk : 0;
+      Frag fb = *reinterpret_cast<const Frag*>(Qs + qrow * LDX + h * D + kkc);
+      fb = live ? fb : M::zero();
+#pragma unroll
+      for (int kt = 0; kt < KTC; ++kt) {
+        const int ki = 16 * kt + m;
+        Frag fa = *reinterpret_cast<const Frag*>(Ks + (r0 + (ki < nu ? ki : nu - 1)) * LDX + h * D + kkc);
+        fa = live ? fa : M::zero();
+        S[kt] = M::mma(fa, fb, S[kt]);
+      }
+    }
+    // logits in units of log2(e): l = (q.k / sqrt(d) + PE) * log2(e), so exp is a bare exp2
+    float mx = -INFINITY;
+#pragma unroll
+    for (int kt = 0; kt < KTC; ++kt)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float l = (16 * kt + 4 * g + i < nu) ? fmaf(S[kt][i], scale2, bias[kt][i][hl]) : -INFINITY;
+        S[kt][i] = l;
+        mx = fmaxf(mx, l);
+      }
+    mx = col_max(mx);
+    float sum = 0.f;
+#pragma unroll
+    for (int kt = 0; kt < KTC; ++kt)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        float e = __builtin_amdgcn_exp2f(S[kt][i] - mx);                          // exp2(-inf) = 0 for masked keys
+        if (dup) e *= mult[kt][i];
+        S[kt][i] = e;
+        sum += e;
+      }
+    sum = col_sum(sum);
+    const float inv = __builtin_amdgcn_rcpf(sum);
+
+    // O^T[dv][q] = sum_key V^T[dv][key] P^T[key][q]
+#pragma unroll
+    for (int dt = 0; dt < (D + 15) / 16; ++dt) {
+      f32x4 O = f32x4{0.f, 0.f, 0.f, 0.f};
+      const int dv = 16 * dt + m;
+      const bool dlive = dv < D;
+      const T* vrow = Vt + (h * D + (dlive ? dv : 0)) * LDV;
+#pragma unroll
+      for (int c = 0; c < NCH; ++c) {
+        Frag fa, fb;
+        if constexpr (TPC == 2) {
+          const int c0 = r0 + 32 * c + 4 * g, c1 = c0 + 16;
+          const bool ok0 = dlive && c0 < rows_ready, ok1 = dlive && (2 * c + 1 < KTC) && c1 < rows_ready;
+          bf16x4 lo = *reinterpret_cast<const bf16x4*>(vrow + (c0 < rows_ready ? c0 : 0));
+          bf16x4 hi = *reinterpret_cast<const bf16x4*>(vrow + (c1 < rows_ready ? c1 : 0));
+          const bf16x4 z4 = {0, 0, 0, 0};
+          lo = ok0 ? lo : z4;
+          hi = ok1 ? hi : z4;
+          fa = Frag{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+          const f32x4 p0 = S[2 * c];
+          const f32x4 p1 = (2 * c + 1 < KTC) ? S[(2 * c + 1 < KTC) ? 2 * c + 1 : 0] : f32x4{0.f, 0.f, 0.f, 0.f};
+          fb = Frag{(bf16_t)p0[0], (bf16_t)p0[1], (bf16_t)p0[2], (bf16_t)p0[3],
+                    (bf16_t)p1[0], (bf16_t)p1[1], (bf16_t)p1[2], (bf16_t)p1[3]};
+        } else {
+          const int c0 = r0 + 16 * c + 4 * g;
+          fa = *reinterpret_cast<const Frag*>(vrow + (c0 < rows_ready ? c0 : 0));
+          fa = (dlive && c0 < rows_ready) ? fa : M::zero();
+          fb = S[c];
+        }
+        O = M::mma(fa, fb, O);
+      }
+      if (qi < nu && 16 * dt + 4 * g < D)
+        *reinterpret_cast<Vec4*>(Qs + (r0 + qi) * LDX + h * D + 16 * dt + 4 * g) = pack4<T>(O * inv);
+    }
+  }
+}
+
+template <typename T, int C, int HEADS, int HID, int NT_QKV, int NT_O, int NT_1, int NT_2>
+__global__ void __launch_bounds__(kWaves * 64)
+k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* out, int full_layer) {
+  // out may be x: a tile's rows are read, then written, by this workgroup only
+  typedef LayerLds<T, C, HEADS, HID> L;
+  typedef typename Mma<T>::Vec4 Vec4;
+  constexpr int LDX = L::LDX, LDV = L::LDV, LDH = L::LDH;
   constexpr int NW = kWaves, NTHREADS = NW * 64;
   static_assert(C / (16 * NT_O) == kStatGroups && C / (16 * NT_2) == kStatGroups, "LayerNorm phases: one item per wave");
   extern __shared__ __align__(16) unsigned char smem[];
@@ -132,18 +275,20 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
   T* Vt = reinterpret_cast<T*>(smem + L::off_v);
   T* Hs = reinterpret_cast<T*>(smem + L::off_h);
   int32_t* row_vox = reinterpret_cast<int32_t*>(smem + L::off_misc);
-  int32_t* row_lin = row_vox + kRowsMax;
-  float* row_mult = reinterpret_cast<float*>(row_lin + kRowsMax);
-  int32_t* set_r0 = reinterpret_cast<int32_t*>(row_mult + kRowsMax);   // [kMaxSets + 1]
+  int32_t* row_lin = row_vox + kRowsPad;
+  float* row_mult = reinterpret_cast<float*>(row_lin + kRowsPad);
+  int32_t* set_r0 = reinterpret_cast<int32_t*>(row_mult + kRowsPad);   // [kMaxSets + 1]
   int32_t* set_nu = set_r0 + kMaxSets + 1;                              // [kMaxSets + 1]
   float* stat = reinterpret_cast<float*>(set_nu + kMaxSets + 1);        // [2][kStatGroups][kRowsMax]
+  int32_t* items = reinterpret_cast<int32_t*>(stat + 2 * kStatGroups * kRowsMax);   // [kMaxItems + 1]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, m = lane & 15, g = lane >> 4;
 
   // The first Q/K/V weight fragments are requested before anything else: their latency hides
   // behind the row bookkeeping and the gather.
-  GemmPhase<T, NT_QKV, C, 3 * C, NW, 1> qkv(p.w_qkv, wave);
-  qkv.issue(0);
+  DSVT_CLK(0);
+  GemmPhase<T, NT_QKV, C, 3 * C, NW> qkv(reinterpret_cast<const T*>(p.w_qkv), wave);
+  qkv.prefetch();
 
   int n_sets = *mp.n_sets;
   n_sets = n_sets < mp.max_sets ? n_sets : mp.max_sets;
@@ -163,7 +308,7 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
   const int tau = mp.tau;
 
   // ---- 1. slots -> compact rows (first occurrences only; each set starts on a multiple of 4 rows)
-  for (int r = tid; r < kRowsMax; r += NTHREADS) { row_vox[r] = -1; row_lin[r] = 0; row_mult[r] = 0.f; }
+  for (int r = tid; r < kRowsPad; r += NTHREADS) { row_vox[r] = -1; row_lin[r] = 0; row_mult[r] = 0.f; }
   for (int ls = wave; ls < ns; ls += NW) {
     const int v = lane < tau ? mp.set_inds[(size_t)(s_begin + ls) * tau + lane] : -2;
     const int prev = __shfl_up(v, 1, 64);
@@ -181,6 +326,13 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
     }
     set_r0[keep] = r;
     set_nu[kMaxSets] = keep;
+    int n = 0;                                   // attention items: (set, query tile, half of the heads)
+    for (int s = 0; s < keep; ++s) {
+      const int kts = (set_nu[s] + 15) >> 4;
+      for (int qt = 0; qt < kts; ++qt)
+        for (int hh = 0; hh < 2; ++hh) items[n++] = s | (qt << 8) | (hh << 12) | (kts << 16);
+    }
+    items[kMaxItems] = n;
   }
   __syncthreads();
   ns = set_nu[kMaxSets];
@@ -202,11 +354,13 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
   __syncthreads();
   const int R = set_r0[ns];
   const int RT = (R + 15) >> 4;
+  const int RTK = ((RT + 1) >> 1) << 1;          // the LayerNorm phases run on an even number of row tiles
+  DSVT_CLK(1);
 
   // ---- 2. gather (Eq. 4): rows of x -> Xs, 16 bytes per thread, dead rows zero
   {
     constexpr int CH = C * (int)sizeof(T) / 16;
-    for (int idx = tid; idx < RT * 16 * CH; idx += NTHREADS) {
+    for (int idx = tid; idx < RTK * 16 * CH; idx += NTHREADS) {
       const int r = idx / CH, c = idx - r * CH;
       const int v = row_vox[r];
       uint4 val = make_uint4(0u, 0u, 0u, 0u);
@@ -215,248 +369,124 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
     }
   }
   __syncthreads();
+  DSVT_CLK(2);
 
-  // ---- 3. Q, K, V = X W^T + b; Q pre-scaled by 1/sqrt(d); V stored transposed
+  // ---- 3. Q, K, V = X W^T + b; V stored transposed
   {
-    const float scale = rsqrtf((float)D);
-    qkv.run(Xs, LDX, RT, [&](int o0, int rt0, int cnt, f32x4 (&acc)[NT_QKV][3]) {
+    qkv.run(Xs, LDX, RT, p.b_qkv, [&](int o0, int r, f32x4 (&acc)[NT_QKV]) {
+      const int row = 16 * r + m;
 #pragma unroll
       for (int nt = 0; nt < NT_QKV; ++nt) {
         const int ot = o0 + 16 * nt;             // a tile never straddles the Q/K/V boundary (C % 16 == 0)
         const int o = ot + 4 * g;
-        const f32x4 b4 = *reinterpret_cast<const f32x4*>(p.b_qkv + o);
-        const int sel = ot / C;
+        const f32x4 v = acc[nt];
+        if (ot < C) {
+          *reinterpret_cast<Vec4*>(Qs + row * LDX + o) = pack4<T>(v);
+        } else if (ot < 2 * C) {
+          *reinterpret_cast<Vec4*>(Ks + row * LDX + (o - C)) = pack4<T>(v);
+        } else {
 #pragma unroll
-        for (int r = 0; r < 3; ++r) {
-          if (r < cnt) {
-            const int row = 16 * (rt0 + r) + m;
-            f32x4 v = acc[nt][r] + b4;
-            if (sel == 0) {
-              v *= scale;
-              *reinterpret_cast<Vec4*>(Qs + row * LDX + o) = pack4<T>(v);
-            } else if (sel == 1) {
-              *reinterpret_cast<Vec4*>(Ks + row * LDX + (o - C)) = pack4<T>(v);
-            } else {
-#pragma unroll
-              for (int i = 0; i < 4; ++i) Vt[(o - 2 * C + i) * LDV + row] = (T)v[i];
-            }
-          }
+          for (int i = 0; i < 4; ++i) Vt[(o - 2 * C + i) * LDV + row] = (T)v[i];
         }
       }
     });
   }
-  GemmPhase<T, NT_O, C, C, NW, 1> oproj(p.w_o, wave);
-  oproj.issue(0);                                // in flight during the attention phase
+  GemmPhase<T, NT_O, C, C, NW> oproj(reinterpret_cast<const T*>(p.w_o), wave);
+  oproj.prefetch();                              // in flight during the attention phase
+  const int o_own = wave * 16 * NT_O;            // this wavefront's features in the LayerNorm phases
+  f32x4 bo4[NT_O], g1[NT_O], be1[NT_O];
+#pragma unroll
+  for (int nt = 0; nt < NT_O; ++nt) {
+    bo4[nt] = *reinterpret_cast<const f32x4*>(p.b_o + o_own + 16 * nt + 4 * g);
+    g1[nt] = full_layer ? *reinterpret_cast<const f32x4*>(p.ln1_g + o_own + 16 * nt + 4 * g) : bo4[nt];
+    be1[nt] = full_layer ? *reinterpret_cast<const f32x4*>(p.ln1_b + o_own + 16 * nt + 4 * g) : bo4[nt];
+  }
   __syncthreads();
+  DSVT_CLK(3);
 
-  // ---- 4. per (set, head): P = softmax(Q K^T + PE), O = P V; O overwrites the head's Q columns
-  for (int item = wave; item < ns * HEADS; item += NW) {
-    const int s = item / HEADS, h = item - s * HEADS;
-    const int r0 = set_r0[s], nu = set_nu[s];
-    const int KT = (nu + 15) >> 4;
-    f32x4 S[kKeyTiles][kKeyTiles];               // S[kt][qt][i]: key 16kt+4g+i, query 16qt+m
-#pragma unroll
-    for (int a = 0; a < kKeyTiles; ++a)
-#pragma unroll
-      for (int b = 0; b < kKeyTiles; ++b) S[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int kc = 0; kc < D; kc += KC) {
-      const int kk = kc + g * KL;
-      Frag fa[kKeyTiles], fb[kKeyTiles];
-#pragma unroll
-      for (int t = 0; t < kKeyTiles; ++t) {
-        fa[t] = M::zero(); fb[t] = M::zero();
-        if (t < KT && kk < D) {
-          int rr = 16 * t + m; rr = r0 + (rr < nu ? rr : nu - 1);
-          fa[t] = *reinterpret_cast<const Frag*>(Ks + rr * LDX + h * D + kk);
-          fb[t] = *reinterpret_cast<const Frag*>(Qs + rr * LDX + h * D + kk);
-        }
-      }
-#pragma unroll
-      for (int kt = 0; kt < kKeyTiles; ++kt)
-#pragma unroll
-        for (int qt = 0; qt < kKeyTiles; ++qt)
-          if (kt < KT && qt < KT) S[kt][qt] = M::mma(fa[kt], fb[qt], S[kt][qt]);
+  // ---- 4. attention inside every set; O overwrites Q
+  {
+    const int n_items = items[kMaxItems];
+    for (int it = wave; it < n_items; it += NW) {
+      const int d = items[it];
+      const int s = d & 255, qt = (d >> 8) & 15, hh = (d >> 12) & 1, kts = d >> 16;
+      const int r0 = set_r0[s], nu = set_nu[s];
+      if (kts == 1) attn_item<T, C, HEADS, HID, 1>(p, Qs, Ks, Vt, row_lin, row_mult, r0, nu, qt, hh, RT * 16);
+      else if (kts == 2) attn_item<T, C, HEADS, HID, 2>(p, Qs, Ks, Vt, row_lin, row_mult, r0, nu, qt, hh, RT * 16);
+      else attn_item<T, C, HEADS, HID, 3>(p, Qs, Ks, Vt, row_lin, row_mult, r0, nu, qt, hh, RT * 16);
     }
-    float inv[kKeyTiles];
-    const float* table = p.rel_bias ? p.rel_bias + (size_t)h * p.rel_size : nullptr;
+  }
+  __syncthreads();
+  DSVT_CLK(4);
+
+  // ---- 5. Y = O Wo^T + bo (+ x), then LayerNorm; result (or raw Y) replaces x in Xs
+  f32x4 keep[NT_O][kRowTiles];
+  if (RTK == 2) oproj.template run_keep<2>(Qs, LDX, bo4, keep);
+  else if (RTK == 4) oproj.template run_keep<4>(Qs, LDX, bo4, keep);
+  else oproj.template run_keep<6>(Qs, LDX, bo4, keep);
 #pragma unroll
-    for (int qt = 0; qt < kKeyTiles; ++qt) {
-      inv[qt] = 0.f;
-      if (qt < KT) {
-        int q = 16 * qt + m; q = q < nu ? q : nu - 1;
-        const int ql = row_lin[r0 + q] + p.rel_const;
-        float mx = -INFINITY;
+  for (int nt = 0; nt < NT_O; ++nt) {
+    const int o = o_own + 16 * nt + 4 * g;
 #pragma unroll
-        for (int kt = 0; kt < kKeyTiles; ++kt) {
-          if (kt < KT) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-              const int key = 16 * kt + 4 * g + i;
-              float l = -INFINITY;
-              if (key < nu) {
-                l = S[kt][qt][i];
-                if (table) {
-                  int idx = ql - row_lin[r0 + key];
-                  idx = idx < 0 ? 0 : (idx >= p.rel_size ? p.rel_size - 1 : idx);
-                  l += table[idx];
-                }
-              }
-              S[kt][qt][i] = l;
-              mx = fmaxf(mx, l);
-            }
-          }
-        }
-        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        float sum = 0.f;
-#pragma unroll
-        for (int kt = 0; kt < kKeyTiles; ++kt) {
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            float e = 0.f;
-            if (kt < KT) {
-              const int key = 16 * kt + 4 * g + i;
-              if (key < nu) {
-                e = __expf(S[kt][qt][i] - mx);
-                if (p.dup_mode) e *= row_mult[r0 + key];
-              }
-            }
-            S[kt][qt][i] = e;
-            sum += e;
-          }
-        }
-        sum += __shfl_xor(sum, 16, 64);
-        sum += __shfl_xor(sum, 32, 64);
-        inv[qt] = 1.0f / sum;
-      }
-    }
-    // O^T[dv][q] = sum_key V^T[dv][key] P^T[key][q]; P^T comes straight from the registers above.
-    constexpr int TPC = KC / 16;                  // key tiles per fragment: 2 (bf16) or 1 (fp32)
-    constexpr int NCH = (kKeyTiles + TPC - 1) / TPC;
-#pragma unroll
-    for (int dt = 0; dt < (D + 15) / 16; ++dt) {
-      f32x4 O[kKeyTiles];
-#pragma unroll
-      for (int qt = 0; qt < kKeyTiles; ++qt) O[qt] = f32x4{0.f, 0.f, 0.f, 0.f};
-      const int dv = 16 * dt + m;
-#pragma unroll
-      for (int c = 0; c < NCH; ++c) {
-        if (c * TPC < KT) {
-          Frag fa = M::zero();
-          if (dv < D) {
-            const T* vrow = Vt + (h * D + dv) * LDV + r0 + 4 * g;
-            if constexpr (TPC == 2) {
-              bf16x4 lo = {0, 0, 0, 0}, hi = {0, 0, 0, 0};
-              if (r0 + 32 * c + 4 * g < RT * 16) lo = *reinterpret_cast<const bf16x4*>(vrow + 32 * c);
-              if (2 * c + 1 < KT && r0 + 32 * c + 16 + 4 * g < RT * 16)
-                hi = *reinterpret_cast<const bf16x4*>(vrow + 32 * c + 16);
-              fa = Frag{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-            } else {
-              if (r0 + 16 * c + 4 * g < RT * 16) fa = *reinterpret_cast<const Frag*>(vrow + 16 * c);
-            }
-          }
-#pragma unroll
-          for (int qt = 0; qt < kKeyTiles; ++qt) {
-            if (qt < KT) {
-              Frag fb;
-              if constexpr (TPC == 2) {
-                const f32x4 p0 = S[2 * c][qt];
-                const f32x4 p1 = (2 * c + 1 < kKeyTiles) ? S[(2 * c + 1 < kKeyTiles) ? 2 * c + 1 : 0][qt]
-                                                         : f32x4{0.f, 0.f, 0.f, 0.f};
-                fb = Frag{(bf16_t)p0[0], (bf16_t)p0[1], (bf16_t)p0[2], (bf16_t)p0[3],
-                          (bf16_t)p1[0], (bf16_t)p1[1], (bf16_t)p1[2], (bf16_t)p1[3]};
-              } else {
-                fb = S[c][qt];
-              }
-              O[qt] = M::mma(fa, fb, O[qt]);
-            }
-          }
-        }
-      }
-#pragma unroll
-      for (int qt = 0; qt < kKeyTiles; ++qt) {
-        const int q = 16 * qt + m;
-        if (qt < KT && q < nu && 16 * dt + 4 * g < D) {
-          const f32x4 o4 = O[qt] * inv[qt];
-          *reinterpret_cast<Vec4*>(Qs + (r0 + q) * LDX + h * D + 16 * dt + 4 * g) = pack4<T>(o4);
+    for (int r = 0; r < kRowTiles; ++r) {
+      if (r < RTK) {
+        if (full_layer) {
+          const Vec4 xr = *reinterpret_cast<const Vec4*>(Xs + (16 * r + m) * LDX + o);
+          keep[nt][r] += f32x4{to_f32<T>(xr[0]), to_f32<T>(xr[1]), to_f32<T>(xr[2]), to_f32<T>(xr[3])};
+        } else {
+          *reinterpret_cast<Vec4*>(Xs + (16 * r + m) * LDX + o) = pack4<T>(keep[nt][r]);
         }
       }
     }
   }
-  __syncthreads();
-
-  // ---- 5. Y = O Wo^T + bo (+ x), then LayerNorm; result (or raw Y) replaces x in Xs
-  f32x4 keep[NT_O][3];
-  int k_o0 = 0, k_rt0 = 0, k_cnt = 0;
-  oproj.run(Qs, LDX, RT, [&](int o0, int rt0, int cnt, f32x4 (&acc)[NT_O][3]) {
-    k_o0 = o0; k_rt0 = rt0; k_cnt = cnt;
-#pragma unroll
-    for (int nt = 0; nt < NT_O; ++nt) {
-      const int o = o0 + 16 * nt + 4 * g;
-      const f32x4 b4 = *reinterpret_cast<const f32x4*>(p.b_o + o);
-#pragma unroll
-      for (int r = 0; r < 3; ++r) {
-        keep[nt][r] = acc[nt][r] + b4;
-        if (full_layer && r < cnt) {
-          const Vec4 xr = *reinterpret_cast<const Vec4*>(Xs + (16 * (rt0 + r) + m) * LDX + o);
-          keep[nt][r] += f32x4{to_f32<T>(xr[0]), to_f32<T>(xr[1]), to_f32<T>(xr[2]), to_f32<T>(xr[3])};
-        }
-      }
-    }
-  });
-  if (!full_layer) {
-#pragma unroll
-    for (int nt = 0; nt < NT_O; ++nt)
-#pragma unroll
-      for (int r = 0; r < 3; ++r)
-        if (r < k_cnt)
-          *reinterpret_cast<Vec4*>(Xs + (16 * (k_rt0 + r) + m) * LDX + k_o0 + 16 * nt + 4 * g) = pack4<T>(keep[nt][r]);
-  } else {
-    GemmPhase<T, NT_1, C, HID, NW, 1> ffn1(p.w_1, wave);
-    ffn1.issue(0);                               // in flight during the LayerNorm exchange
-    layer_norm_tile<T, NT_O>(keep, C, k_o0, k_o0 / (16 * NT_O), k_rt0, k_cnt, stat, p.ln1_g, p.ln1_b, p.ln_eps, Xs, LDX);
+  if (full_layer) {
+    GemmPhase<T, NT_1, C, HID, NW> ffn1(reinterpret_cast<const T*>(p.w_1), wave);
+    ffn1.prefetch();                             // in flight during the LayerNorm exchange
+    layer_norm_tile<T, NT_O, C>(keep, o_own, wave, RTK, stat, g1, be1, p.ln_eps, Xs, LDX);
     __syncthreads();
+    DSVT_CLK(5);
 
     // ---- 6. MLP: H = gelu(x1 W1^T + b1) over the dead Q/K tiles; x2 = LN(x1 + H W2^T + b2)
-    ffn1.run(Xs, LDX, RT, [&](int o0, int rt0, int cnt, f32x4 (&acc)[NT_1][3]) {
+    ffn1.run(Xs, LDX, RT, p.b_1, [&](int o0, int r, f32x4 (&acc)[NT_1]) {
 #pragma unroll
       for (int nt = 0; nt < NT_1; ++nt) {
         const int o = o0 + 16 * nt + 4 * g;
-        const f32x4 b4 = *reinterpret_cast<const f32x4*>(p.b_1 + o);
-#pragma unroll
-        for (int r = 0; r < 3; ++r) {
-          if (r < cnt) {
-            f32x4 v = acc[nt][r] + b4;
-            v = f32x4{gelu_erf(v[0]), gelu_erf(v[1]), gelu_erf(v[2]), gelu_erf(v[3])};
-            *reinterpret_cast<Vec4*>(Hs + (16 * (rt0 + r) + m) * LDH + o) = pack4<T>(v);
-          }
-        }
+        f32x4 v = acc[nt];
+        v = f32x4{gelu_erf_fast(v[0]), gelu_erf_fast(v[1]), gelu_erf_fast(v[2]), gelu_erf_fast(v[3])};
+        *reinterpret_cast<Vec4*>(Hs + (16 * r + m) * LDH + o) = pack4<T>(v);
       }
     });
-    GemmPhase<T, NT_2, HID, C, NW, KSPLIT_2> ffn2(p.w_2, wave);
-    ffn2.issue(0);
+    GemmPhase<T, NT_2, HID, C, NW> ffn2(reinterpret_cast<const T*>(p.w_2), wave);
+    ffn2.prefetch();
+    const int o_own2 = wave * 16 * NT_2;
+    f32x4 b24[NT_2], g2[NT_2], be2[NT_2];
+#pragma unroll
+    for (int nt = 0; nt < NT_2; ++nt) {
+      b24[nt] = *reinterpret_cast<const f32x4*>(p.b_2 + o_own2 + 16 * nt + 4 * g);
+      g2[nt] = *reinterpret_cast<const f32x4*>(p.ln2_g + o_own2 + 16 * nt + 4 * g);
+      be2[nt] = *reinterpret_cast<const f32x4*>(p.ln2_b + o_own2 + 16 * nt + 4 * g);
+    }
     __syncthreads();
-    f32x4 keep2[NT_2][3];
-    ffn2.run(Hs, LDH, RT, [&](int o0, int rt0, int cnt, f32x4 (&acc)[NT_2][3]) {
-      k_o0 = o0; k_rt0 = rt0; k_cnt = cnt;
+    DSVT_CLK(6);
+    f32x4 keep2[NT_2][kRowTiles];
+    if (RTK == 2) ffn2.template run_keep<2>(Hs, LDH, b24, keep2);
+    else if (RTK == 4) ffn2.template run_keep<4>(Hs, LDH, b24, keep2);
+    else ffn2.template run_keep<6>(Hs, LDH, b24, keep2);
 #pragma unroll
-      for (int nt = 0; nt < NT_2; ++nt) {
-        const int o = o0 + 16 * nt + 4 * g;
-        const f32x4 b4 = *reinterpret_cast<const f32x4*>(p.b_2 + o);
+    for (int nt = 0; nt < NT_2; ++nt) {
+      const int o = o_own2 + 16 * nt + 4 * g;
 #pragma unroll
-        for (int r = 0; r < 3; ++r) {
-          keep2[nt][r] = acc[nt][r] + b4;
-          if (r < cnt) {
-            const Vec4 xr = *reinterpret_cast<const Vec4*>(Xs + (16 * (rt0 + r) + m) * LDX + o);
-            keep2[nt][r] += f32x4{to_f32<T>(xr[0]), to_f32<T>(xr[1]), to_f32<T>(xr[2]), to_f32<T>(xr[3])};
-          }
+      for (int r = 0; r < kRowTiles; ++r) {
+        if (r < RTK) {
+          const Vec4 xr = *reinterpret_cast<const Vec4*>(Xs + (16 * r + m) * LDX + o);
+          keep2[nt][r] += f32x4{to_f32<T>(xr[0]), to_f32<T>(xr[1]), to_f32<T>(xr[2]), to_f32<T>(xr[3])};
         }
       }
-    });
-    layer_norm_tile<T, NT_2>(keep2, C, k_o0, k_o0 / (16 * NT_2), k_rt0, k_cnt, stat, p.ln2_g, p.ln2_b, p.ln_eps, Xs, LDX);
+    }
+    layer_norm_tile<T, NT_2, C>(keep2, o_own2, wave, RTK, stat, g2, be2, p.ln_eps, Xs, LDX);
   }
   __syncthreads();
+  DSVT_CLK(7);
 
   // ---- 7. scatter: rows of Xs -> the voxels' rows of out, 16 bytes per thread
   {
@@ -469,26 +499,72 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
             *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(Xs) + (size_t)r * LDX * sizeof(T) + c * 16);
     }
   }
+  DSVT_CLK(8);
+#ifdef DSVT_PHASE_CLOCKS
+  if (p.clk && threadIdx.x == 0) { p.clk[blockIdx.x * 16 + 9] = R; p.clk[blockIdx.x * 16 + 10] = ns; }
+#endif
 }
 
 // ------------------------------------------------------------------------------------------
+// Packed buffer of a layer: the four matrices in fragment order, each on a 256-byte boundary.
+struct PackedLayout { size_t off[5], total; int out[4], k[4]; int rel_size; };   // off[4]: position table [index][heads]
+PackedLayout packed_layout(const dsvt_layer_w& w) {
+  PackedLayout pl;
+  const size_t es = w.dtype == DSVT_BF16 ? 2 : 4;
+  const int out[4] = {3 * w.C, w.C, w.hidden, w.C}, k[4] = {w.C, w.C, w.C, w.hidden};
+  size_t o = 0;
+  for (int i = 0; i < 4; ++i) { pl.off[i] = o; pl.out[i] = out[i]; pl.k[i] = k[i]; o = dsvt_align_up(o + (size_t)out[i] * k[i] * es, 256); }
+  pl.rel_size = (2 * w.win[0] - 1) * (2 * w.win[1] - 1) * (2 * w.win[2] - 1);
+  pl.off[4] = o;
+  if (w.rel_bias != nullptr) o = dsvt_align_up(o + (size_t)pl.rel_size * w.heads * 4, 256);
+  pl.total = o;
+  return pl;
+}
+
+// dst fragment order <- src [out, in]; one thread per 16-byte lane slot.
+template <typename T>
+__global__ void k_pack(const T* __restrict__ src, T* __restrict__ dst, int out, int k) {
+  constexpr int KC = Mma<T>::KC, KL = Mma<T>::KL;
+  const int nkf = k / KC;
+  const long long slot = (long long)blockIdx.x * blockDim.x + threadIdx.x;     // (tile, kf, lane)
+  if (slot >= (long long)(out / 16) * nkf * 64) return;
+  const int lane = (int)(slot & 63), kf = (int)((slot >> 6) % nkf), tile = (int)((slot >> 6) / nkf);
+  const T* s = src + (size_t)(tile * 16 + (lane & 15)) * k + kf * KC + (lane >> 4) * KL;
+  T* d = dst + (size_t)slot * KL;
+#pragma unroll
+  for (int e = 0; e < KL; ++e) d[e] = s[e];
+}
+
+// [heads][size] -> [size][heads]
+__global__ void k_pack_table(const float* __restrict__ src, float* __restrict__ dst, int heads, int size) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < heads * size) dst[(i % size) * heads + i / size] = src[i];
+}
+
 LayerDev to_dev(const dsvt_layer_w& w) {
   LayerDev d;
-  d.w_qkv = w.w_qkv; d.w_o = w.w_o; d.w_1 = w.w_1; d.w_2 = w.w_2;
+  const PackedLayout pl = packed_layout(w);
+  const char* pk = reinterpret_cast<const char*>(w.packed);
+  d.w_qkv = pk + pl.off[0]; d.w_o = pk + pl.off[1]; d.w_1 = pk + pl.off[2]; d.w_2 = pk + pl.off[3];
   d.b_qkv = w.b_qkv; d.b_o = w.b_o; d.b_1 = w.b_1; d.b_2 = w.b_2;
   d.ln1_g = w.ln1_g; d.ln1_b = w.ln1_b; d.ln2_g = w.ln2_g; d.ln2_b = w.ln2_b;
-  d.rel_bias = w.rel_bias; d.ln_eps = w.ln_eps; d.dup_mode = w.dup_mode;
+  d.rel_bias = w.rel_bias ? reinterpret_cast<const float*>(pk + pl.off[4]) : nullptr;
+  d.ln_eps = w.ln_eps; d.dup_mode = w.dup_mode;
   const int my = 2 * w.win[1] - 1, mz = 2 * w.win[2] - 1;
   d.rel_my = my; d.rel_mz = mz;
   d.rel_size = (2 * w.win[0] - 1) * my * mz;
   d.rel_const = ((w.win[0] - 1) * my + (w.win[1] - 1)) * mz + (w.win[2] - 1);
+#ifdef DSVT_PHASE_CLOCKS
+  d.clk = g_phase_clocks;
+#endif
   return d;
 }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-int check_layer(const dsvt_layer_w& w, bool need_mlp) {
+int check_layer(const dsvt_layer_w& w, bool need_mlp, bool need_packed = true) {
   if (!w.w_qkv || !w.w_o || !w.b_qkv || !w.b_o) return DSVT_EINVAL;
+  if (need_packed && (!w.packed || !aligned16(w.packed))) return DSVT_EINVAL;
   if (need_mlp && (!w.w_1 || !w.w_2 || !w.b_1 || !w.b_2 || !w.ln1_g || !w.ln1_b || !w.ln2_g || !w.ln2_b)) return DSVT_EINVAL;
   if (w.dtype != DSVT_F32 && w.dtype != DSVT_BF16) return DSVT_EINVAL;
   if (w.dup_mode != 0 && w.dup_mode != 1) return DSVT_EINVAL;
@@ -515,10 +591,10 @@ template <typename K> int allow_lds(K kernel, size_t bytes) {
   return DSVT_OK;
 }
 
-template <typename T, int C, int HEADS, int HID, int NT_QKV, int NT_O, int NT_1, int NT_2, int KSPLIT_2>
+template <typename T, int C, int HEADS, int HID, int NT_QKV, int NT_O, int NT_1, int NT_2>
 int launch_layer(const dsvt_layer_w& w, const dsvt_maps& mp, const int32_t* coords, const void* x, void* out, int full,
                  hipStream_t st) {
-  auto kern = k_layer<T, C, HEADS, HID, NT_QKV, NT_O, NT_1, NT_2, KSPLIT_2>;
+  auto kern = k_layer<T, C, HEADS, HID, NT_QKV, NT_O, NT_1, NT_2>;
   constexpr size_t lds = LayerLds<T, C, HEADS, HID>::total;
   static int prepared = allow_lds(kern, lds);
   if (prepared != DSVT_OK) return prepared;
@@ -535,13 +611,54 @@ int launch_layer(const dsvt_layer_w& w, const dsvt_maps& mp, const int32_t* coor
 int run_layer(const dsvt_layer_w& w, const dsvt_maps& mp, const int32_t* coords, const void* x, void* out, int full,
               hipStream_t st) {
   if (w.dtype == DSVT_BF16) {
-    if (w.C == 192) return launch_layer<bf16_t, 192, 8, 384, 3, 3, 3, 3, 2>(w, mp, coords, x, out, full, st);
-    return launch_layer<bf16_t, 64, 4, 128, 3, 1, 2, 1, 1>(w, mp, coords, x, out, full, st);
+    if (w.C == 192) return launch_layer<bf16_t, 192, 8, 384, 3, 3, 3, 3>(w, mp, coords, x, out, full, st);
+    return launch_layer<bf16_t, 64, 4, 128, 3, 1, 2, 1>(w, mp, coords, x, out, full, st);
   }
-  return launch_layer<float, 64, 4, 128, 3, 1, 2, 1, 1>(w, mp, coords, x, out, full, st);
+  return launch_layer<float, 64, 4, 128, 3, 1, 2, 1>(w, mp, coords, x, out, full, st);
 }
 
 }  // namespace
+
+#ifdef DSVT_PHASE_CLOCKS
+extern "C" void dsvt_debug_phase_clocks(long long* dev_buf) { g_phase_clocks = dev_buf; }
+#endif
+
+extern "C" int dsvt_layer_packed_size(const dsvt_layer_w* layer, size_t* bytes) {
+  if (!layer || !bytes) return DSVT_EINVAL;
+  int rc = check_layer(*layer, true, false);
+  if (rc != DSVT_OK) return rc;
+  *bytes = packed_layout(*layer).total;
+  return DSVT_OK;
+}
+
+extern "C" int dsvt_layer_pack(const dsvt_layer_w* layer, void* packed, size_t bytes, void* stream) {
+  if (!layer || !packed || !aligned16(packed)) return DSVT_EINVAL;
+  int rc = check_layer(*layer, true, false);
+  if (rc != DSVT_OK) return rc;
+  const PackedLayout pl = packed_layout(*layer);
+  if (bytes < pl.total) return DSVT_ENOSPC;
+  const void* src[4] = {layer->w_qkv, layer->w_o, layer->w_1, layer->w_2};
+  hipStream_t st = (hipStream_t)stream;
+  for (int i = 0; i < 4; ++i) {
+    char* dst = reinterpret_cast<char*>(packed) + pl.off[i];
+    if (layer->dtype == DSVT_BF16) {
+      const long long slots = (long long)(pl.out[i] / 16) * (pl.k[i] / Mma<bf16_t>::KC) * 64;
+      k_pack<bf16_t><<<(unsigned)dsvt_ceil_div(slots, 256), 256, 0, st>>>(reinterpret_cast<const bf16_t*>(src[i]),
+                                                                        reinterpret_cast<bf16_t*>(dst), pl.out[i], pl.k[i]);
+    } else {
+      const long long slots = (long long)(pl.out[i] / 16) * (pl.k[i] / Mma<float>::KC) * 64;
+      k_pack<float><<<(unsigned)dsvt_ceil_div(slots, 256), 256, 0, st>>>(reinterpret_cast<const float*>(src[i]),
+                                                                       reinterpret_cast<float*>(dst), pl.out[i], pl.k[i]);
+    }
+  }
+  if (layer->rel_bias != nullptr) {
+    const int n = pl.rel_size * layer->heads;
+    k_pack_table<<<(unsigned)dsvt_ceil_div(n, 256), 256, 0, st>>>(
+        layer->rel_bias, reinterpret_cast<float*>(reinterpret_cast<char*>(packed) + pl.off[4]), layer->heads, pl.rel_size);
+  }
+  DSVT_HIP_TRY(hipGetLastError());
+  return DSVT_OK;
+}
 
 extern "C" int dsvt_block_workspace_size(const dsvt_layer_w* layer, int32_t n_voxels, size_t* bytes) {
   if (!layer || !bytes || n_voxels <= 0) return DSVT_EINVAL;

@@ -63,88 +63,121 @@ template <typename T> __device__ __forceinline__ float to_f32(T v) { return (flo
 // start in different banks.
 template <typename T> constexpr int lds_pad() { return 16 / (int)sizeof(T); }
 
-// A-operand fragments of NT output tiles over KF consecutive k-fragments, kept in registers so
-// that all of a tile group's weight loads are in flight at once.
-template <typename T, int NT, int KF> struct AReg { typename Mma<T>::Frag f[KF][NT]; };
+// Packed weights.  A matrix W [OUT, K] is stored fragment by fragment in the order the MFMA "A"
+// operand wants it: fragment (tile, kf) -- output rows 16*tile .. +15, k in [kf*KC, (kf+1)*KC) --
+// is 1 KB, lane l's 16 bytes at offset 16*l, fragments ordered [tile][kf].  A wavefront's load of
+// one fragment is then one fully coalesced 1 KB read (the [out, in] layout would touch 16 rows
+// of 64 bytes each, which the L1/L2 path serves about 3x slower).
+template <typename T> __host__ __device__ constexpr size_t packed_elems(int out, int k) { return (size_t)out * k; }
 
-// W: global [out, in] with row pitch ldw; rows o0 .. o0 + 16*NT - 1, k from k0.
-template <typename T, int NT, int KF>
-__device__ __forceinline__ void load_a(AReg<T, NT, KF>& a, const T* __restrict__ W, int ldw, int o0, int k0) {
+// A-operand fragments of NT output tiles over the whole K, kept in registers: every weight
+// fragment is loaded from memory once per workgroup tile and reused for all its rows.
+template <typename T, int NT, int NKF> struct AFull { typename Mma<T>::Frag f[NKF][NT]; };
+// B-operand fragments of one row tile (16 rows) over the whole K.
+template <typename T, int NKF> struct BRow { typename Mma<T>::Frag f[NKF]; };
+
+// Wp: packed matrix with NKF = K / KC fragments per tile; tiles tile0 .. tile0 + NT - 1.
+template <typename T, int NT, int NKF>
+__device__ __forceinline__ void load_a(AFull<T, NT, NKF>& a, const T* __restrict__ Wp, int tile0) {
   typedef typename Mma<T>::Frag Frag;
-  const int lane = threadIdx.x & 63, m = lane & 15, g = lane >> 4;
-  const T* wp = W + (size_t)(o0 + m) * ldw + k0 + g * Mma<T>::KL;
+  const int lane = threadIdx.x & 63;
+  const Frag* fp = reinterpret_cast<const Frag*>(Wp) + (size_t)tile0 * NKF * 64 + lane;
 #pragma unroll
-  for (int kf = 0; kf < KF; ++kf)
+  for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt)
-      a.f[kf][nt] = *reinterpret_cast<const Frag*>(wp + (size_t)(16 * nt) * ldw + kf * Mma<T>::KC);
+    for (int kf = 0; kf < NKF; ++kf) a.f[kf][nt] = fp[(nt * NKF + kf) * 64];
 }
 
-// acc[nt][r] += W-fragments . X[16*(rt0+r) + .][k0 ...) for r < rt_cnt (<= RH).  X: LDS, pitch ldx.
-template <typename T, int NT, int KF, int RH>
-__device__ __forceinline__ void mma_rows(const AReg<T, NT, KF>& a, const T* Xs, int ldx, int k0, int rt0, int rt_cnt,
-                                         f32x4 (&acc)[NT][RH]) {
+// Xs: LDS [rows][ldx]; row tile r.
+template <typename T, int NKF>
+__device__ __forceinline__ void load_b(BRow<T, NKF>& b, const T* Xs, int ldx, int r) {
   typedef typename Mma<T>::Frag Frag;
   const int lane = threadIdx.x & 63, m = lane & 15, g = lane >> 4;
-  const T* xp = Xs + (16 * rt0 + m) * ldx + k0 + g * Mma<T>::KL;
+  const T* xp = Xs + (16 * r + m) * ldx + g * Mma<T>::KL;
 #pragma unroll
-  for (int kf = 0; kf < KF; ++kf) {
-#pragma unroll
-    for (int r = 0; r < RH; ++r) {
-      if (r < rt_cnt) {
-        const Frag b = *reinterpret_cast<const Frag*>(xp + (16 * r) * ldx + kf * Mma<T>::KC);
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) acc[nt][r] = Mma<T>::mma(a.f[kf][nt], b, acc[nt][r]);
-      }
-    }
-  }
+  for (int kf = 0; kf < NKF; ++kf) b.f[kf] = *reinterpret_cast<const Frag*>(xp + kf * Mma<T>::KC);
 }
+
+template <typename T, int NT, int NKF>
+__device__ __forceinline__ void mma_row(f32x4 (&acc)[NT], const AFull<T, NT, NKF>& a, const BRow<T, NKF>& b) {
+#pragma unroll
+  for (int kf = 0; kf < NKF; ++kf)
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) acc[nt] = Mma<T>::mma(a.f[kf][nt], b.f[kf], acc[nt]);
+}
+
+constexpr int kRowTiles = 6;                     // row tiles of a workgroup tile (96 rows)
 
 // One GEMM phase of a workgroup of NW wavefronts: Out^T[NOUT x rows] = W[NOUT x K] . X^T.
-// Work items are (group of NT output tiles, half of the row tiles); wavefront w takes items
-// w, w + NW, ...  Each item's weights are loaded in KSPLIT units of K/KSPLIT columns, and unit
-// u + 1 is requested before unit u is consumed, so global-load latency overlaps the MFMAs.
-template <typename T, int NT, int K, int NOUT, int NW, int KSPLIT> struct GemmPhase {
+// A work item is a group of NT output tiles over all row tiles; wavefront w takes items
+// w, w + NW, ...  An item's weight fragments sit in registers for the whole item, the next item's
+// are requested before the current one is consumed, and inside an item the activations of row
+// tile r + 1 are read from LDS while row tile r is in the matrix cores.  Every weight fragment
+// is loaded by exactly one wavefront and every activation fragment feeds NT MFMAs.
+template <typename T, int NT, int K, int NOUT, int NW> struct GemmPhase {
   static constexpr int KC = Mma<T>::KC;
-  static constexpr int KFU = K / KC / KSPLIT;
-  static constexpr int N_OG = NOUT / (16 * NT);
-  static constexpr int N_ITEMS = 2 * N_OG;
+  static constexpr int NKF = K / KC;
+  static constexpr int N_ITEMS = NOUT / (16 * NT);
   static constexpr int IPW = N_ITEMS / NW;
-  static constexpr int UNITS = IPW * KSPLIT;
-  static constexpr int RH = 3;               // row tiles per item: half of at most 6
-  static_assert(N_ITEMS % NW == 0 && K % (KC * KSPLIT) == 0 && NOUT % (16 * NT) == 0, "phase shape");
-  AReg<T, NT, KFU> a[2];
-  const T* W;
+  static_assert(N_ITEMS % NW == 0 && K % KC == 0 && NOUT % (16 * NT) == 0, "phase shape");
+  AFull<T, NT, NKF> a[IPW > 1 ? 2 : 1];
+  const T* Wp;
   int wave;
 
-  __device__ __forceinline__ GemmPhase(const void* w, int wave_) : W(reinterpret_cast<const T*>(w)), wave(wave_) {}
+  __device__ __forceinline__ GemmPhase(const T* wp, int wave_) : Wp(wp), wave(wave_) {}
 
-  __device__ __forceinline__ void issue(int u) {
-    const int item = wave + (u / KSPLIT) * NW;
-    load_a<T, NT, KFU>(a[u & 1], W, K, (item % N_OG) * 16 * NT, (u % KSPLIT) * KFU * KC);
-  }
+  // Request the weights of this wavefront's first item (may be called long before run()).
+  __device__ __forceinline__ void prefetch() { load_a<T, NT, NKF>(a[0], Wp, wave * NT); }
 
-  // Needs issue(0) beforehand.  epi(o0, rt0, cnt, acc): acc[nt][r][i] is output feature
-  // o0 + 16*nt + 4*g + i of row 16*(rt0 + r) + m, for r < cnt.
-  template <typename Epi> __device__ __forceinline__ void run(const T* Xs, int ldx, int RT, Epi epi) {
-    const int h0 = (RT + 1) >> 1;
+  // Row tiles in a rolled loop, two per trip.  epi(o0, r, acc): acc[nt][i] is output feature
+  // o0 + 16*nt + 4*g + i of row 16*r + m, bias included.  The bias is fetched before the next
+  // item's weights are requested, so waiting for it never waits for them.
+  template <typename Epi>
+  __device__ __forceinline__ void run(const T* Xs, int ldx, int RT, const float* __restrict__ bias, Epi epi) {
+    const int g4 = ((threadIdx.x & 63) >> 4) * 4;
 #pragma unroll
     for (int it = 0; it < IPW; ++it) {
       const int item = wave + it * NW;
-      const int og = item % N_OG, half = item / N_OG;
-      const int rt0 = half ? h0 : 0, cnt = half ? RT - h0 : h0;
-      f32x4 acc[NT][RH];
+      f32x4 b4[NT];
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt)
+      for (int nt = 0; nt < NT; ++nt) b4[nt] = *reinterpret_cast<const f32x4*>(bias + item * 16 * NT + 16 * nt + g4);
+      if (it + 1 < IPW) load_a<T, NT, NKF>(a[(it + 1) & 1], Wp, (item + NW) * NT);
+      const AFull<T, NT, NKF>& A = a[it & 1];
+      BRow<T, NKF> b0, b1;
+      load_b<T, NKF>(b0, Xs, ldx, 0);
+      for (int r = 0; r < RT; r += 2) {
+        const bool two = r + 1 < RT;
+        if (two) load_b<T, NKF>(b1, Xs, ldx, r + 1);
+        f32x4 acc0[NT], acc1[NT];                // the bias is the accumulators' initial value
 #pragma unroll
-        for (int r = 0; r < RH; ++r) acc[nt][r] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int kh = 0; kh < KSPLIT; ++kh) {
-        const int u = it * KSPLIT + kh;
-        if (u + 1 < UNITS) issue(u + 1);
-        mma_rows<T, NT, KFU, RH>(a[u & 1], Xs, ldx, kh * KFU * KC, rt0, cnt, acc);
+        for (int nt = 0; nt < NT; ++nt) { acc0[nt] = b4[nt]; acc1[nt] = b4[nt]; }
+        mma_row<T, NT, NKF>(acc0, A, b0);
+        if (two) {
+          if (r + 2 < RT) load_b<T, NKF>(b0, Xs, ldx, r + 2);
+          mma_row<T, NT, NKF>(acc1, A, b1);
+        }
+        epi(item * 16 * NT, r, acc0);
+        if (two) epi(item * 16 * NT, r + 1, acc1);
       }
-      epi(og * 16 * NT, rt0, cnt, acc);
+    }
+  }
+
+  // One item per wavefront, RTC row tiles unrolled, all accumulators returned (the LayerNorm
+  // phases need a row's values in registers across a workgroup barrier).
+  template <int RTC>
+  __device__ __forceinline__ void run_keep(const T* Xs, int ldx, const f32x4 (&b4)[NT], f32x4 (&acc)[NT][kRowTiles]) {
+    static_assert(IPW == 1, "one item per wavefront");
+    BRow<T, NKF> b[2];
+    load_b<T, NKF>(b[0], Xs, ldx, 0);
+#pragma unroll
+    for (int r = 0; r < RTC; ++r) {
+      if (r + 1 < RTC) load_b<T, NKF>(b[(r + 1) & 1], Xs, ldx, r + 1);
+      f32x4 t[NT];
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) t[nt] = b4[nt];
+      mma_row<T, NT, NKF>(t, a[0], b[r & 1]);
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) acc[nt][r] = t[nt];
     }
   }
 };
@@ -156,6 +189,26 @@ template <int NT, int RT_MAX> __device__ __forceinline__ void zero_acc(f32x4 (&a
     for (int rt = 0; rt < RT_MAX; ++rt) acc[nt][rt] = f32x4{0.f, 0.f, 0.f, 0.f};
 }
 
+// Reductions over the four lanes m, m + 16, m + 32, m + 48 (one accumulator column) with the
+// gfx950 lane-swap instructions: permlane16_swap(x, x) returns x's 16-lane rows (0,0,2,2) and
+// (1,1,3,3), permlane32_swap(x, x) its halves (lo,lo) and (hi,hi); no LDS round trip.
+__device__ __forceinline__ float col_sum(float v) {
+  const unsigned u = __float_as_uint(v);
+  const auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  const float s = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+  const unsigned w = __float_as_uint(s);
+  const auto b = __builtin_amdgcn_permlane32_swap(w, w, false, false);
+  return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+__device__ __forceinline__ float col_max(float v) {
+  const unsigned u = __float_as_uint(v);
+  const auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  const float s = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+  const unsigned w = __float_as_uint(s);
+  const auto b = __builtin_amdgcn_permlane32_swap(w, w, false, false);
+  return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
@@ -163,3 +216,19 @@ __device__ __forceinline__ float wave_sum(float v) {
 }
 
 __device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
+
+// erf-GELU with erf from the rational approximation 1 - (1 + a1 z + ... + a6 z^6)^-16 of
+// Abramowitz & Stegun 7.1.28 (|error| <= 3e-7): x * Phi(x) = 0.5 x (1 + erf(x / sqrt 2)).
+__device__ __forceinline__ float gelu_erf_fast(float x) {
+  const float z = fabsf(x) * 0.70710678118654752f;
+  float p = 0.0000430638f;
+  p = fmaf(p, z, 0.0002765672f);
+  p = fmaf(p, z, 0.0001520143f);
+  p = fmaf(p, z, 0.0092705272f);
+  p = fmaf(p, z, 0.0422820123f);
+  p = fmaf(p, z, 0.0705230784f);
+  p = fmaf(p, z, 1.0f);
+  p = p * p; p = p * p; p = p * p; p = p * p;          // ^16
+  const float e = 1.0f - __builtin_amdgcn_rcpf(p);                 // erf(|x| / sqrt 2)
+  return 0.5f * x + 0.5f * fabsf(x) * e;
+}
