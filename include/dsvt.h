@@ -151,7 +151,13 @@ typedef struct {
   float ln_eps;
   int32_t mask_empty; /* 1: keys/values are the region's occupied voxels; 0: all l*w*h slots,
                          holes carrying zero features (so their key/value are the biases) */
+  const void* packed; /* [device] matrices and key/value biases re-ordered by dsvt_pool_pack; the
+                         kernels read them only from here */
 } dsvt_pool_cfg;
+
+/* Weight preparation, once per pooling module: as dsvt_layer_packed_size / dsvt_layer_pack. */
+int dsvt_pool_packed_size(const dsvt_pool_cfg* cfg, size_t* bytes);
+int dsvt_pool_pack(const dsvt_pool_cfg* cfg, void* packed, size_t bytes, void* stream);
 
 int dsvt_attn_pool_workspace_size(const dsvt_pool_cfg* cfg, int32_t n_voxels, size_t* bytes);
 
@@ -160,7 +166,9 @@ int dsvt_attn_pool_workspace_size(const dsvt_pool_cfg* cfg, int32_t n_voxels, si
  * query; out = LN(P + Attn(Q = P, KV = region) W_o + b_o) (Eq. 7).
  * out_coords [device] int32 [n_voxels,4] (first *n_out rows written: b, x/l, y/w, z/h)
  * out        [device] [n_voxels,C]       (first *n_out rows written)
- * n_out      [device] int32 scalar */
+ * n_out      [device] int32 scalar
+ * Supported: (C,heads) = (64,4) in F32 or BF16, (192,8) in BF16; l*w*h <= 8; out must not alias x.
+ * status gets DSVT_ST_COORD_RANGE for a coordinate outside the grid (that voxel is skipped). */
 int dsvt_attn_pool(const dsvt_pool_cfg* cfg, const int32_t* coords, const void* x, int32_t n_voxels,
                    int32_t* out_coords, void* out, int32_t* n_out,
                    void* ws, size_t ws_bytes, int32_t* status, void* stream);

@@ -46,7 +46,7 @@ class PoolCfg(C.Structure):
                 ("dtype", C.c_int32), ("w_q", C.c_void_p), ("w_k", C.c_void_p), ("w_v", C.c_void_p),
                 ("w_o", C.c_void_p), ("b_q", C.c_void_p), ("b_k", C.c_void_p), ("b_v", C.c_void_p),
                 ("b_o", C.c_void_p), ("ln_g", C.c_void_p), ("ln_b", C.c_void_p), ("ln_eps", C.c_float),
-                ("mask_empty", C.c_int32)]
+                ("mask_empty", C.c_int32), ("packed", C.c_void_p)]
 
 
 _lib = None
@@ -68,6 +68,8 @@ def lib():
         L.dsvt_block_workspace_size.argtypes = [C.POINTER(LayerW), i32, C.POINTER(sz)]
         L.dsvt_set_attention.argtypes = [C.POINTER(LayerW), C.POINTER(Maps), vp, vp, vp, vp, sz, vp]
         L.dsvt_block.argtypes = [C.POINTER(LayerW), C.POINTER(Maps), vp, vp, vp, vp, sz, vp]
+        L.dsvt_pool_packed_size.argtypes = [C.POINTER(PoolCfg), C.POINTER(sz)]
+        L.dsvt_pool_pack.argtypes = [C.POINTER(PoolCfg), vp, sz, vp]
         L.dsvt_attn_pool_workspace_size.argtypes = [C.POINTER(PoolCfg), i32, C.POINTER(sz)]
         L.dsvt_attn_pool.argtypes = [C.POINTER(PoolCfg), vp, vp, i32, vp, vp, vp, vp, sz, vp, vp]
         L.dsvt_prof_enable.argtypes = [i32]
@@ -214,7 +216,12 @@ class PoolWeights:
         p = lambda k: self.t[k].data_ptr()
         self.struct = PoolCfg(I32x3(*grid), I32x3(*pool), batch, w["C"], w["heads"], code, p("w_q"), p("w_k"),
                               p("w_v"), p("w_o"), p("b_q"), p("b_k"), p("b_v"), p("b_o"), p("ln_g"), p("ln_b"),
-                              w["ln_eps"], mask_empty)
+                              w["ln_eps"], mask_empty, None)
+        nbytes = C.c_size_t(0)
+        _check("dsvt_pool_packed_size", lib().dsvt_pool_packed_size(C.byref(self.struct), C.byref(nbytes)))
+        self.packed = torch.empty((nbytes.value,), dtype=torch.uint8, device="cuda")
+        _check("dsvt_pool_pack", lib().dsvt_pool_pack(C.byref(self.struct), _ptr(self.packed), nbytes.value, _stream(None)))
+        self.struct.packed = self.packed.data_ptr()
 
 
 def dsvt_attn_pool_workspace_size(pool, n_voxels):

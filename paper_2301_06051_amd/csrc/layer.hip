@@ -15,13 +15,10 @@
 namespace {
 
 constexpr int kTauMax = 48;
-constexpr int kRowsMax = 96;                     // rows of a tile = 6 MFMA row tiles
 constexpr int kMaxSets = kRowsMax / 4;           // every set takes at least 4 rows of a tile
 constexpr int kRowsPad = kRowsMax + 16;          // per-row arrays are read 4 at a time up to 15 rows past a set's end
 constexpr int kMaxItems = 2 * (kRowsMax / 16 + kMaxSets);   // attention items: (set, query tile, half of the heads)
 constexpr int kFixedSets = kRowsMax / kTauMax;   // sets per workgroup when no tile list is given
-constexpr int kWaves = 4;                        // one per SIMD: the LDS tile leaves room for one workgroup per CU
-constexpr int kStatGroups = kWaves;              // LayerNorm phases: every wavefront owns C / 4 features of all rows
 
 struct LayerDev {
   const void *w_qkv, *w_o, *w_1, *w_2;       // packed (see mma.h)
@@ -62,55 +59,6 @@ template <typename T, int C, int HEADS, int HID> struct LayerLds {
   static_assert((size_t)kRowsMax * LDH * sizeof(T) <= 2 * kTile, "hidden tile must fit in Q + K");
   static_assert(C % 64 == 0 && D % Mma<T>::KL == 0 && D % 4 == 0, "shape");
 };
-
-// LayerNorm over the C features of every row, for values spread over the workgroup in
-// accumulator layout: this wavefront holds features o0 .. o0 + 16*NT - 1 (group og of
-// kStatGroups) of rows 16*r + m, r < RT.  Per-group sums of x and x^2 (fp32) are exchanged
-// through LDS; variance = E[x^2] - mean^2.  Every thread of the workgroup must call it.
-template <typename T, int NT, int C>
-__device__ __forceinline__ void layer_norm_tile(f32x4 (&v)[NT][kRowTiles], int o0, int og, int RT, float* stat,
-                                                const f32x4 (&ga)[NT], const f32x4 (&be)[NT], float eps, T* dst,
-                                                int ldd) {
-  typedef typename Mma<T>::Vec4 Vec4;
-  const int lane = threadIdx.x & 63, m = lane & 15, g = lane >> 4;
-  float* stat1 = stat;
-  float* stat2 = stat + kStatGroups * kRowsMax;
-#pragma unroll
-  for (int r = 0; r < kRowTiles; ++r) {
-    if (r < RT) {
-      float s = 0.f, q = 0.f;
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) { s += v[nt][r][i]; q = fmaf(v[nt][r][i], v[nt][r][i], q); }
-      }
-      s = col_sum(s);
-      q = col_sum(q);
-      if (g == 0) { stat1[og * kRowsMax + 16 * r + m] = s; stat2[og * kRowsMax + 16 * r + m] = q; }
-    }
-  }
-  __syncthreads();
-#pragma unroll
-  for (int r = 0; r < kRowTiles; ++r) {
-    if (r < RT) {
-      const int row = 16 * r + m;
-      float s = 0.f, q = 0.f;
-#pragma unroll
-      for (int k = 0; k < kStatGroups; ++k) { s += stat1[k * kRowsMax + row]; q += stat2[k * kRowsMax + row]; }
-      const float mean = s * (1.0f / C);
-      const float rs = rsqrtf(fmaxf(fmaf(-mean, mean, q * (1.0f / C)), 0.f) + eps);
-      const float sh = -mean * rs;
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt) {
-        const int o = o0 + 16 * nt + 4 * g;
-        f32x4 y;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) y[i] = fmaf(fmaf(v[nt][r][i], rs, sh), ga[nt][i], be[nt][i]);
-        *reinterpret_cast<Vec4*>(dst + row * ldd + o) = pack4<T>(y);
-      }
-    }
-  }
-}
 
 // Attention of one (set, query tile, half of the heads) item (Eq. 5): for each of its heads,
 // logits = Q K^T (+ PE), softmax over the set's distinct voxels, O = P V; O overwrites the Q
@@ -519,20 +467,6 @@ PackedLayout packed_layout(const dsvt_layer_w& w) {
   if (w.rel_bias != nullptr) o = dsvt_align_up(o + (size_t)pl.rel_size * w.heads * 4, 256);
   pl.total = o;
   return pl;
-}
-
-// dst fragment order <- src [out, in]; one thread per 16-byte lane slot.
-template <typename T>
-__global__ void k_pack(const T* __restrict__ src, T* __restrict__ dst, int out, int k) {
-  constexpr int KC = Mma<T>::KC, KL = Mma<T>::KL;
-  const int nkf = k / KC;
-  const long long slot = (long long)blockIdx.x * blockDim.x + threadIdx.x;     // (tile, kf, lane)
-  if (slot >= (long long)(out / 16) * nkf * 64) return;
-  const int lane = (int)(slot & 63), kf = (int)((slot >> 6) % nkf), tile = (int)((slot >> 6) / nkf);
-  const T* s = src + (size_t)(tile * 16 + (lane & 15)) * k + kf * KC + (lane >> 4) * KL;
-  T* d = dst + (size_t)slot * KL;
-#pragma unroll
-  for (int e = 0; e < KL; ++e) d[e] = s[e];
 }
 
 // [heads][size] -> [size][heads]

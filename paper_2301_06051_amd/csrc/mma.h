@@ -106,7 +106,10 @@ __device__ __forceinline__ void mma_row(f32x4 (&acc)[NT], const AFull<T, NT, NKF
     for (int nt = 0; nt < NT; ++nt) acc[nt] = Mma<T>::mma(a.f[kf][nt], b.f[kf], acc[nt]);
 }
 
-constexpr int kRowTiles = 6;                     // row tiles of a workgroup tile (96 rows)
+constexpr int kRowTiles = 6;                     // row tiles of a workgroup tile
+constexpr int kRowsMax = 16 * kRowTiles;         // 96 rows
+constexpr int kWaves = 4;                        // wavefronts per workgroup, one per SIMD: the LDS tile leaves room for one workgroup per CU
+constexpr int kStatGroups = kWaves;              // LayerNorm phases: every wavefront owns C / 4 features of all rows
 
 // One GEMM phase of a workgroup of NW wavefronts: Out^T[NOUT x rows] = W[NOUT x K] . X^T.
 // A work item is a group of NT output tiles over all row tiles; wavefront w takes items
@@ -232,3 +235,67 @@ __device__ __forceinline__ float gelu_erf_fast(float x) {
   const float e = 1.0f - __builtin_amdgcn_rcpf(p);                 // erf(|x| / sqrt 2)
   return 0.5f * x + 0.5f * fabsf(x) * e;
 }
+
+// LayerNorm over the C features of every row, for values spread over the workgroup in
+// accumulator layout: this wavefront holds features o0 .. o0 + 16*NT - 1 (group og of
+// kStatGroups) of rows 16*r + m, r < RT.  Per-group sums of x and x^2 (fp32) are exchanged
+// through LDS; variance = E[x^2] - mean^2.  Every thread of the workgroup must call it.
+template <typename T, int NT, int C>
+__device__ __forceinline__ void layer_norm_tile(f32x4 (&v)[NT][kRowTiles], int o0, int og, int RT, float* stat,
+                                                const f32x4 (&ga)[NT], const f32x4 (&be)[NT], float eps, T* dst,
+                                                int ldd) {
+  typedef typename Mma<T>::Vec4 Vec4;
+  const int lane = threadIdx.x & 63, m = lane & 15, g = lane >> 4;
+  float* stat1 = stat;
+  float* stat2 = stat + kStatGroups * kRowsMax;
+#pragma unroll
+  for (int r = 0; r < kRowTiles; ++r) {
+    if (r < RT) {
+      float s = 0.f, q = 0.f;
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { s += v[nt][r][i]; q = fmaf(v[nt][r][i], v[nt][r][i], q); }
+      }
+      s = col_sum(s);
+      q = col_sum(q);
+      if (g == 0) { stat1[og * kRowsMax + 16 * r + m] = s; stat2[og * kRowsMax + 16 * r + m] = q; }
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int r = 0; r < kRowTiles; ++r) {
+    if (r < RT) {
+      const int row = 16 * r + m;
+      float s = 0.f, q = 0.f;
+#pragma unroll
+      for (int k = 0; k < kStatGroups; ++k) { s += stat1[k * kRowsMax + row]; q += stat2[k * kRowsMax + row]; }
+      const float mean = s * (1.0f / C);
+      const float rs = rsqrtf(fmaxf(fmaf(-mean, mean, q * (1.0f / C)), 0.f) + eps);
+      const float sh = -mean * rs;
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        const int o = o0 + 16 * nt + 4 * g;
+        f32x4 y;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) y[i] = fmaf(fmaf(v[nt][r][i], rs, sh), ga[nt][i], be[nt][i]);
+        *reinterpret_cast<Vec4*>(dst + row * ldd + o) = pack4<T>(y);
+      }
+    }
+  }
+}
+
+// dst fragment order <- src [out, in]; one thread per 16-byte lane slot.
+template <typename T>
+__global__ void k_pack(const T* __restrict__ src, T* __restrict__ dst, int out, int k) {
+  constexpr int KC = Mma<T>::KC, KL = Mma<T>::KL;
+  const int nkf = k / KC;
+  const long long slot = (long long)blockIdx.x * blockDim.x + threadIdx.x;     // (tile, kf, lane)
+  if (slot >= (long long)(out / 16) * nkf * 64) return;
+  const int lane = (int)(slot & 63), kf = (int)((slot >> 6) % nkf), tile = (int)((slot >> 6) / nkf);
+  const T* s = src + (size_t)(tile * 16 + (lane & 15)) * k + kf * KC + (lane >> 4) * KL;
+  T* d = dst + (size_t)slot * KL;
+#pragma unroll
+  for (int e = 0; e < KL; ++e) d[e] = s[e];
+}
+

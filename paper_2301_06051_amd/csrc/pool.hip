@@ -1,15 +1,422 @@
-// dsvt_attn_pool: attention-style 3D pooling (Sec. 3.3, Eq. 6-7).  Not built yet.
+// dsvt_attn_pool: attention-style 3D pooling (Sec. 3.3, Eq. 6-7) on gfx950.
+//
+// Grouping: pooled cells are unique keys in a bounded grid, so -- as in the set partition -- the
+// output order (ascending region key) comes from an occupancy bitmap and a pop-count prefix, with
+// no sort.  Every voxel then writes its index into the dense slot table of its region
+// ("convert the sparse region into dense").
+// Attention: a workgroup takes kRowsMax / P consecutive regions; their dense slots (holes = zero
+// rows) are one <=96-row LDS tile.  Max-pool over the occupied slots gives the query row (Eq. 6);
+// K/V of all slots and Q of the pooled rows are MFMA projections; the P-key softmax per head is
+// plain ALU work; output projection, residual and LayerNorm follow the layer kernels (Eq. 7).
 #include "common.h"
+#include "mma.h"
+
+namespace {
+
+constexpr int kMaxPool = 8;                       // slots of a pooling region
+constexpr int kQRows = 32;                        // pooled rows of a tile, padded to two MFMA row tiles
+
+struct PoolGeom {
+  int32_t grid[3], pool[3], pg[3];                // cells, region size, pooled cells per axis
+  int32_t batch, P;
+};
+
+__global__ void kp_clear(uint32_t* __restrict__ words, int64_t n_words, int32_t* __restrict__ pool_inds, int64_t n_inds) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n_words) words[i] = 0u;
+  if (i < n_inds) pool_inds[i] = -1;
+}
+
+__device__ __forceinline__ bool pool_key(const PoolGeom& g, int4 c, uint32_t* key, int32_t* slot) {
+  const bool ok = c.x >= 0 && c.x < g.batch && c.y >= 0 && c.y < g.grid[0] && c.z >= 0 && c.z < g.grid[1] &&
+                  c.w >= 0 && c.w < g.grid[2];
+  if (!ok) return false;
+  const int32_t px = c.y / g.pool[0], py = c.z / g.pool[1], pz = c.w / g.pool[2];
+  *key = (uint32_t)(((c.x * g.pg[0] + px) * g.pg[1] + py) * g.pg[2] + pz);
+  *slot = ((c.y - px * g.pool[0]) * g.pool[1] + (c.z - py * g.pool[1])) * g.pool[2] + (c.w - pz * g.pool[2]);
+  return true;
+}
+
+__global__ void kp_mark(PoolGeom g, const int4* __restrict__ coords, int32_t n, uint32_t* __restrict__ bitmap,
+                        int32_t* __restrict__ status) {
+  const int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  uint32_t key; int32_t slot;
+  if (!pool_key(g, coords[i], &key, &slot)) { atomicOr(status, DSVT_ST_COORD_RANGE); return; }
+  atomicOr(&bitmap[key >> 5], 1u << (key & 31u));
+}
+
+// One workgroup: exclusive pop-count scan over the bitmap words; the total is the output count.
+__global__ void __launch_bounds__(1024) kp_scan(const uint32_t* __restrict__ bitmap, int32_t* __restrict__ word_prefix,
+                                                int64_t n_words, int32_t* __restrict__ n_out) {
+  __shared__ int32_t wave_tot[16];
+  __shared__ int32_t carry_s;
+  const int32_t tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  if (tid == 0) carry_s = 0;
+  __syncthreads();
+  for (int64_t base = 0; base < n_words; base += 1024) {
+    const int64_t w = base + tid;
+    const int32_t v = w < n_words ? __popc(bitmap[w]) : 0;
+    int32_t incl = v;
+    for (int32_t d = 1; d < 64; d <<= 1) {
+      const int32_t up = __shfl_up(incl, d, 64);
+      if (lane >= d) incl += up;
+    }
+    if (lane == 63) wave_tot[wv] = incl;
+    __syncthreads();
+    int32_t before = carry_s;
+    for (int32_t k = 0; k < wv; ++k) before += wave_tot[k];
+    if (w < n_words) word_prefix[w] = before + incl - v;
+    __syncthreads();
+    if (tid == 1023) carry_s = before + incl;
+    __syncthreads();
+  }
+  if (tid == 0) *n_out = carry_s;
+}
+
+__global__ void kp_emit(PoolGeom g, const int4* __restrict__ coords, int32_t n, const uint32_t* __restrict__ bitmap,
+                        const int32_t* __restrict__ word_prefix, int32_t* __restrict__ pool_inds,
+                        int32_t* __restrict__ out_coords) {
+  const int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const int4 c = coords[i];
+  uint32_t key; int32_t slot;
+  if (!pool_key(g, c, &key, &slot)) return;
+  const uint32_t word = key >> 5, bit = key & 31u;
+  const int32_t m = word_prefix[word] + __popc(bitmap[word] & ((1u << bit) - 1u));   // m < number of regions <= n
+  pool_inds[(int64_t)m * g.P + slot] = i;
+  // every member of a region writes the same pooled coordinates
+  reinterpret_cast<int4*>(out_coords)[m] = make_int4(c.x, c.y / g.pool[0], c.z / g.pool[1], c.w / g.pool[2]);
+}
+
+struct PoolDev {
+  const void *w_kv, *w_q, *w_o;                   // packed: [2C, C] (K rows then V rows), [C, C], [C, C]
+  const float *b_kv, *b_q, *b_o, *ln_g, *ln_b;    // b_kv: [2C] in scratch (b_k then b_v)
+  float ln_eps;
+  int32_t P, mask_empty;
+};
+
+template <typename T, int C> struct PoolLds {
+  static constexpr int PAD = lds_pad<T>();
+  static constexpr int LDX = C + PAD;
+  static constexpr size_t kTile = (size_t)kRowsMax * LDX * sizeof(T);
+  static constexpr size_t kQTile = (size_t)kQRows * LDX * sizeof(T);
+  static constexpr size_t off_x = 0, off_k = kTile, off_v = 2 * kTile, off_p = 3 * kTile, off_q = off_p + kQTile;
+  static constexpr size_t off_misc = off_q + kQTile;
+  static constexpr size_t total = off_misc + (size_t)(kRowsMax + 2 * kStatGroups * kRowsMax) * 4;
+};
+
+template <typename T, int C, int HEADS, int NT_KV, int NT_C>
+__global__ void __launch_bounds__(kWaves * 64)
+kp_attention(PoolDev p, const int32_t* __restrict__ pool_inds, const int32_t* __restrict__ n_out_ptr,
+             const T* __restrict__ x, T* __restrict__ out) {
+  typedef PoolLds<T, C> L;
+  typedef typename Mma<T>::Vec4 Vec4;
+  constexpr int LDX = L::LDX, D = C / HEADS, NW = kWaves, NTHREADS = NW * 64;
+  constexpr int CH = C * (int)sizeof(T) / 16;
+  extern __shared__ __align__(16) unsigned char smem[];
+  T* Xs = reinterpret_cast<T*>(smem + L::off_x);      // dense slot rows (holes zero)
+  T* Ks = reinterpret_cast<T*>(smem + L::off_k);
+  T* Vs = reinterpret_cast<T*>(smem + L::off_v);
+  T* Ps = reinterpret_cast<T*>(smem + L::off_p);      // pooled rows: query input, residual, finally the output
+  T* Qs = reinterpret_cast<T*>(smem + L::off_q);      // Q, then O
+  int32_t* row_vox = reinterpret_cast<int32_t*>(smem + L::off_misc);
+  float* stat = reinterpret_cast<float*>(row_vox + kRowsMax);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 4;
+  const int P = p.P;
+  const int MR = kRowsMax / P < kQRows ? kRowsMax / P : kQRows;     // regions per tile
+
+  GemmPhase<T, NT_KV, C, 2 * C, NW> kv(reinterpret_cast<const T*>(p.w_kv), wave);
+  kv.prefetch();
+  const int n_out = *n_out_ptr;
+  const int m0 = blockIdx.x * MR;
+  if (m0 >= n_out) return;
+  const int mr = (n_out - m0) < MR ? (n_out - m0) : MR;
+  const int rows = mr * P;
+  const int RT = (rows + 15) >> 4;
+
+  for (int r = tid; r < kRowsMax; r += NTHREADS) row_vox[r] = r < rows ? pool_inds[(size_t)m0 * P + r] : -1;
+  __syncthreads();
+  for (int idx = tid; idx < RT * 16 * CH; idx += NTHREADS) {
+    const int r = idx / CH, c = idx - r * CH;
+    const int v = row_vox[r];
+    uint4 val = make_uint4(0u, 0u, 0u, 0u);
+    if (v >= 0) val = reinterpret_cast<const uint4*>(x + (size_t)v * C)[c];
+    *reinterpret_cast<uint4*>(reinterpret_cast<unsigned char*>(Xs) + (size_t)r * LDX * sizeof(T) + c * 16) = val;
+  }
+  __syncthreads();
+  // Eq. (6): channel-wise max over the region's occupied slots -> Ps (rows >= mr zero)
+  for (int idx = tid; idx < kQRows * C; idx += NTHREADS) {
+    const int mm = idx / C, c = idx - mm * C;
+    float best = -INFINITY;
+    bool any = false;
+    if (mm < mr)
+      for (int s = 0; s < P; ++s)
+        if (row_vox[mm * P + s] >= 0) { best = fmaxf(best, to_f32<T>(Xs[(mm * P + s) * LDX + c])); any = true; }
+    Ps[mm * LDX + c] = (T)(any ? best : 0.f);
+  }
+  __syncthreads();
+
+  // K, V of every slot; Q of the pooled rows
+  kv.run(Xs, LDX, RT, p.b_kv, [&](int o0, int r, f32x4 (&acc)[NT_KV]) {
+    const int row = 16 * r + (lane & 15);
+#pragma unroll
+    for (int nt = 0; nt < NT_KV; ++nt) {
+      const int ot = o0 + 16 * nt, o = ot + 4 * g;
+      if (ot < C) *reinterpret_cast<Vec4*>(Ks + row * LDX + o) = pack4<T>(acc[nt]);
+      else *reinterpret_cast<Vec4*>(Vs + row * LDX + (o - C)) = pack4<T>(acc[nt]);
+    }
+  });
+  GemmPhase<T, NT_C, C, C, NW> qp(reinterpret_cast<const T*>(p.w_q), wave);
+  qp.prefetch();
+  qp.run(Ps, LDX, kQRows / 16, p.b_q, [&](int o0, int r, f32x4 (&acc)[NT_C]) {
+    const int row = 16 * r + (lane & 15);
+#pragma unroll
+    for (int nt = 0; nt < NT_C; ++nt) *reinterpret_cast<Vec4*>(Qs + row * LDX + o0 + 16 * nt + 4 * g) = pack4<T>(acc[nt]);
+  });
+  GemmPhase<T, NT_C, C, C, NW> op(reinterpret_cast<const T*>(p.w_o), wave);
+  op.prefetch();
+  const int o_own = wave * 16 * NT_C;
+  f32x4 bo4[NT_C], ga[NT_C], be[NT_C];
+#pragma unroll
+  for (int nt = 0; nt < NT_C; ++nt) {
+    bo4[nt] = *reinterpret_cast<const f32x4*>(p.b_o + o_own + 16 * nt + 4 * g);
+    ga[nt] = *reinterpret_cast<const f32x4*>(p.ln_g + o_own + 16 * nt + 4 * g);
+    be[nt] = *reinterpret_cast<const f32x4*>(p.ln_b + o_own + 16 * nt + 4 * g);
+  }
+  __syncthreads();
+
+  // Eq. (7): per (region, head) softmax over its slots; O replaces the head's Q entries
+  {
+    const float scale = rsqrtf((float)D);
+    for (int it = tid; it < mr * HEADS; it += NTHREADS) {
+      const int mm = it / HEADS, h = it - mm * HEADS;
+      T* q = Qs + mm * LDX + h * D;
+      float qv[D], logit[kMaxPool], o[D];
+#pragma unroll
+      for (int j = 0; j < D; ++j) { qv[j] = to_f32<T>(q[j]); o[j] = 0.f; }
+      float mx = -INFINITY;
+#pragma unroll
+      for (int s = 0; s < kMaxPool; ++s) {
+        logit[s] = -INFINITY;
+        if (s < P) {
+          const bool live = !p.mask_empty || row_vox[mm * P + s] >= 0;
+          const T* k = Ks + (mm * P + s) * LDX + h * D;
+          float acc = 0.f;
+#pragma unroll
+          for (int j = 0; j < D; ++j) acc = fmaf(qv[j], to_f32<T>(k[j]), acc);
+          logit[s] = live ? acc * scale : -INFINITY;
+          mx = fmaxf(mx, logit[s]);
+        }
+      }
+      float sum = 0.f;
+#pragma unroll
+      for (int s = 0; s < kMaxPool; ++s) {
+        if (s < P) {
+          const float e = __expf(logit[s] - mx);
+          sum += e;
+          const T* v = Vs + (mm * P + s) * LDX + h * D;
+#pragma unroll
+          for (int j = 0; j < D; ++j) o[j] = fmaf(e, to_f32<T>(v[j]), o[j]);
+        }
+      }
+      const float inv = 1.0f / sum;
+#pragma unroll
+      for (int j = 0; j < D; ++j) q[j] = (T)(o[j] * inv);
+    }
+  }
+  __syncthreads();
+
+  // out = LN(P + O Wo^T + bo)
+  f32x4 keep[NT_C][kRowTiles];
+  op.template run_keep<kQRows / 16>(Qs, LDX, bo4, keep);
+#pragma unroll
+  for (int nt = 0; nt < NT_C; ++nt)
+#pragma unroll
+    for (int r = 0; r < kQRows / 16; ++r) {
+      const Vec4 xr = *reinterpret_cast<const Vec4*>(Ps + (16 * r + (lane & 15)) * LDX + o_own + 16 * nt + 4 * g);
+      keep[nt][r] += f32x4{to_f32<T>(xr[0]), to_f32<T>(xr[1]), to_f32<T>(xr[2]), to_f32<T>(xr[3])};
+    }
+  layer_norm_tile<T, NT_C, C>(keep, o_own, wave, kQRows / 16, stat, ga, be, p.ln_eps, Ps, LDX);
+  __syncthreads();
+  for (int idx = tid; idx < mr * CH; idx += NTHREADS) {
+    const int r = idx / CH, c = idx - r * CH;
+    reinterpret_cast<uint4*>(out + (size_t)(m0 + r) * C)[c] =
+        *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(Ps) + (size_t)r * LDX * sizeof(T) + c * 16);
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+struct PoolPlan {
+  PoolGeom g;
+  int64_t n_words;
+  size_t off_bitmap, off_prefix, off_inds, total;
+};
+
+bool aligned16(const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; }
+
+int make_plan(const dsvt_pool_cfg* cfg, int32_t n_voxels, PoolPlan* pl) {
+  if (!cfg || n_voxels <= 0 || cfg->batch <= 0) return DSVT_EINVAL;
+  PoolGeom& g = pl->g;
+  int64_t cells = cfg->batch, P = 1;
+  for (int a = 0; a < 3; ++a) {
+    if (cfg->grid[a] <= 0 || cfg->pool[a] <= 0) return DSVT_EINVAL;
+    g.grid[a] = cfg->grid[a]; g.pool[a] = cfg->pool[a];
+    g.pg[a] = (int32_t)dsvt_ceil_div(cfg->grid[a], cfg->pool[a]);
+    cells *= g.pg[a]; P *= cfg->pool[a];
+    if (cells >= (1ll << 31) || P > kMaxPool) return cells >= (1ll << 31) ? DSVT_EINVAL : DSVT_EUNSUPPORTED;
+  }
+  g.batch = cfg->batch; g.P = (int32_t)P;
+  pl->n_words = dsvt_ceil_div(cells, 32);
+  size_t o = 0;
+  pl->off_bitmap = o; o = dsvt_align_up(o + (size_t)pl->n_words * 4, 256);
+  pl->off_prefix = o; o = dsvt_align_up(o + (size_t)pl->n_words * 4, 256);
+  pl->off_inds = o;   o = dsvt_align_up(o + (size_t)n_voxels * P * 4, 256);
+  pl->total = o;
+  return DSVT_OK;
+}
+
+int check_pool(const dsvt_pool_cfg& c, bool need_packed) {
+  if (!c.w_q || !c.w_k || !c.w_v || !c.w_o || !c.b_q || !c.b_k || !c.b_v || !c.b_o || !c.ln_g || !c.ln_b) return DSVT_EINVAL;
+  if (c.dtype != DSVT_F32 && c.dtype != DSVT_BF16) return DSVT_EINVAL;
+  if (c.mask_empty != 0 && c.mask_empty != 1) return DSVT_EINVAL;
+  if (!((c.C == 64 && c.heads == 4) || (c.C == 192 && c.heads == 8))) return DSVT_EUNSUPPORTED;
+  if (c.dtype == DSVT_F32 && c.C != 64) return DSVT_EUNSUPPORTED;
+  if (need_packed && (!c.packed || !aligned16(c.packed))) return DSVT_EINVAL;
+  const void* ptrs[] = {c.w_q, c.w_k, c.w_v, c.w_o, c.b_q, c.b_k, c.b_v, c.b_o, c.ln_g, c.ln_b};
+  for (const void* q : ptrs) if (!aligned16(q)) return DSVT_EINVAL;
+  return DSVT_OK;
+}
+
+// packed buffer: [w_k; w_v] as one [2C, C] matrix, w_q, w_o (fragment order), then b_k|b_v as floats
+struct PoolPacked { size_t off_kv, off_q, off_o, off_bkv, total; };
+PoolPacked pool_packed(const dsvt_pool_cfg& c) {
+  const size_t es = c.dtype == DSVT_BF16 ? 2 : 4, cc = (size_t)c.C * c.C * es;
+  PoolPacked pp;
+  size_t o = 0;
+  pp.off_kv = o; o = dsvt_align_up(o + 2 * cc, 256);
+  pp.off_q = o;  o = dsvt_align_up(o + cc, 256);
+  pp.off_o = o;  o = dsvt_align_up(o + cc, 256);
+  pp.off_bkv = o; o = dsvt_align_up(o + (size_t)2 * c.C * 4, 256);
+  pp.total = o;
+  return pp;
+}
+
+__global__ void kp_copy_f32(const float* __restrict__ src, float* __restrict__ dst, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = src[i];
+}
+
+template <typename T> void pack_matrix(const void* src, void* dst, int out, int k, hipStream_t st) {
+  const long long slots = (long long)(out / 16) * (k / Mma<T>::KC) * 64;
+  k_pack<T><<<(unsigned)dsvt_ceil_div(slots, 256), 256, 0, st>>>(reinterpret_cast<const T*>(src), reinterpret_cast<T*>(dst), out, k);
+}
+
+template <typename K> int allow_lds(K kernel, size_t bytes) {
+  DSVT_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   (int)bytes));
+  return DSVT_OK;
+}
+
+template <typename T, int C, int HEADS, int NT_KV, int NT_C>
+int launch_pool_attention(const dsvt_pool_cfg& c, const PoolPlan& pl, const int32_t* pool_inds, const int32_t* n_out,
+                          const void* x, void* out, int32_t n_voxels, hipStream_t st) {
+  auto kern = kp_attention<T, C, HEADS, NT_KV, NT_C>;
+  constexpr size_t lds = PoolLds<T, C>::total;
+  static int prepared = allow_lds(kern, lds);
+  if (prepared != DSVT_OK) return prepared;
+  const PoolPacked pp = pool_packed(c);
+  const char* pk = reinterpret_cast<const char*>(c.packed);
+  PoolDev d;
+  d.w_kv = pk + pp.off_kv; d.w_q = pk + pp.off_q; d.w_o = pk + pp.off_o;
+  d.b_kv = reinterpret_cast<const float*>(pk + pp.off_bkv);
+  d.b_q = c.b_q; d.b_o = c.b_o; d.ln_g = c.ln_g; d.ln_b = c.ln_b; d.ln_eps = c.ln_eps;
+  d.P = pl.g.P; d.mask_empty = c.mask_empty;
+  const int mr = kRowsMax / pl.g.P < kQRows ? kRowsMax / pl.g.P : kQRows;
+  dsvt_prof_scope ps(DSVT_K_POOL_ATTN, st);
+  kern<<<(unsigned)dsvt_ceil_div(n_voxels, mr), kWaves * 64, lds, st>>>(d, pool_inds, n_out, reinterpret_cast<const T*>(x),
+                                                                        reinterpret_cast<T*>(out));
+  return DSVT_OK;
+}
+
+}  // namespace
+
+extern "C" int dsvt_pool_packed_size(const dsvt_pool_cfg* cfg, size_t* bytes) {
+  if (!cfg || !bytes) return DSVT_EINVAL;
+  int rc = check_pool(*cfg, false);
+  if (rc != DSVT_OK) return rc;
+  *bytes = pool_packed(*cfg).total;
+  return DSVT_OK;
+}
+
+extern "C" int dsvt_pool_pack(const dsvt_pool_cfg* cfg, void* packed, size_t bytes, void* stream) {
+  if (!cfg || !packed || !aligned16(packed)) return DSVT_EINVAL;
+  int rc = check_pool(*cfg, false);
+  if (rc != DSVT_OK) return rc;
+  const PoolPacked pp = pool_packed(*cfg);
+  if (bytes < pp.total) return DSVT_ENOSPC;
+  hipStream_t st = (hipStream_t)stream;
+  char* pk = reinterpret_cast<char*>(packed);
+  const int C = cfg->C;
+  const size_t es = cfg->dtype == DSVT_BF16 ? 2 : 4;
+  const void* srcs[4] = {cfg->w_k, cfg->w_v, cfg->w_q, cfg->w_o};
+  char* dsts[4] = {pk + pp.off_kv, pk + pp.off_kv + (size_t)C * C * es, pk + pp.off_q, pk + pp.off_o};
+  for (int i = 0; i < 4; ++i) {
+    // [w_k; w_v] is the row-wise concatenation, so its fragment order is w_k's followed by w_v's
+    if (cfg->dtype == DSVT_BF16) pack_matrix<bf16_t>(srcs[i], dsts[i], C, C, st);
+    else pack_matrix<float>(srcs[i], dsts[i], C, C, st);
+  }
+  float* bkv = reinterpret_cast<float*>(pk + pp.off_bkv);
+  kp_copy_f32<<<(unsigned)dsvt_ceil_div(C, 256), 256, 0, st>>>(cfg->b_k, bkv, C);
+  kp_copy_f32<<<(unsigned)dsvt_ceil_div(C, 256), 256, 0, st>>>(cfg->b_v, bkv + C, C);
+  DSVT_HIP_TRY(hipGetLastError());
+  return DSVT_OK;
+}
 
 extern "C" int dsvt_attn_pool_workspace_size(const dsvt_pool_cfg* cfg, int32_t n_voxels, size_t* bytes) {
-  (void)cfg; (void)n_voxels; (void)bytes;
-  return DSVT_EUNSUPPORTED;
+  if (!bytes) return DSVT_EINVAL;
+  PoolPlan pl;
+  int rc = make_plan(cfg, n_voxels, &pl);
+  if (rc != DSVT_OK) return rc;
+  *bytes = pl.total;
+  return DSVT_OK;
 }
 
 extern "C" int dsvt_attn_pool(const dsvt_pool_cfg* cfg, const int32_t* coords, const void* x, int32_t n_voxels,
                               int32_t* out_coords, void* out, int32_t* n_out, void* ws, size_t ws_bytes,
                               int32_t* status, void* stream) {
-  (void)cfg; (void)coords; (void)x; (void)n_voxels; (void)out_coords; (void)out; (void)n_out; (void)ws;
-  (void)ws_bytes; (void)status; (void)stream;
-  return DSVT_EUNSUPPORTED;
+  PoolPlan pl;
+  int rc = make_plan(cfg, n_voxels, &pl);
+  if (rc != DSVT_OK) return rc;
+  rc = check_pool(*cfg, true);
+  if (rc != DSVT_OK) return rc;
+  if (!coords || !x || !out_coords || !out || !n_out || !ws || !status || x == out) return DSVT_EINVAL;
+  if (!aligned16(coords) || !aligned16(x) || !aligned16(out) || !aligned16(out_coords)) return DSVT_EINVAL;
+  if (ws_bytes < pl.total) return DSVT_ENOSPC;
+  hipStream_t st = (hipStream_t)stream;
+  char* base = reinterpret_cast<char*>(ws);
+  uint32_t* bitmap = reinterpret_cast<uint32_t*>(base + pl.off_bitmap);
+  int32_t* prefix = reinterpret_cast<int32_t*>(base + pl.off_prefix);
+  int32_t* inds = reinterpret_cast<int32_t*>(base + pl.off_inds);
+  const int tb = 256;
+  {
+    dsvt_prof_scope ps(DSVT_K_POOL_GROUP, st);
+    const int64_t n_inds = (int64_t)n_voxels * pl.g.P;
+    const int64_t n_clear = pl.n_words > n_inds ? pl.n_words : n_inds;
+    kp_clear<<<(unsigned)dsvt_ceil_div(n_clear, tb), tb, 0, st>>>(bitmap, pl.n_words, inds, n_inds);
+    kp_mark<<<(unsigned)dsvt_ceil_div(n_voxels, tb), tb, 0, st>>>(pl.g, reinterpret_cast<const int4*>(coords), n_voxels,
+                                                                  bitmap, status);
+    kp_scan<<<1, 1024, 0, st>>>(bitmap, prefix, pl.n_words, n_out);
+    kp_emit<<<(unsigned)dsvt_ceil_div(n_voxels, tb), tb, 0, st>>>(pl.g, reinterpret_cast<const int4*>(coords), n_voxels,
+                                                                  bitmap, prefix, inds, out_coords);
+  }
+  if (cfg->dtype == DSVT_BF16) {
+    if (cfg->C == 192) rc = launch_pool_attention<bf16_t, 192, 8, 3, 3>(*cfg, pl, inds, n_out, x, out, n_voxels, st);
+    else rc = launch_pool_attention<bf16_t, 64, 4, 2, 1>(*cfg, pl, inds, n_out, x, out, n_voxels, st);
+  } else {
+    rc = launch_pool_attention<float, 64, 4, 2, 1>(*cfg, pl, inds, n_out, x, out, n_voxels, st);
+  }
+  if (rc != DSVT_OK) return rc;
+  DSVT_HIP_TRY(hipGetLastError());
+  return DSVT_OK;
 }

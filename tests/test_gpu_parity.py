@@ -157,3 +157,53 @@ def test_layer_argument_errors():
     with pytest.raises(dsvt.DsvtError) as e:
         dsvt.dsvt_set_attention(lw, gm, cd, torch.zeros((300, 96), device="cuda"))
     assert e.value.rc == dsvt.binding.DSVT_EUNSUPPORTED
+
+
+# ------------------------------------------------------------------ attention-style pooling
+@pytest.mark.parametrize("cid,n,pool", [(1, None, (2, 2, 1)), (4, 20000, (1, 1, 4)), (4, 6000, (2, 2, 2)),
+                                        (4, None, (1, 1, 4))])
+@pytest.mark.parametrize("mask_empty", [1, 0])
+def test_attn_pool_parity(cid, n, pool, mask_empty):
+    cfg = synth.CONFIGS[cid]
+    coords = synth.make_frame(cid, n=n)
+    x = synth.make_features(35, len(coords), cfg["C"], cfg["dtype"])
+    w = synth.make_pool_weights(91, cfg["C"], cfg["heads"], cfg["dtype"])
+    _say(f"attn_pool cfg{cid} n={len(coords)} pool={pool} mask_empty={mask_empty}")
+    ref_c, ref = orc.attn_pool(w, coords, x, cfg["grid"], pool, mask_empty)
+    pw = dsvt.PoolWeights(w, cfg["grid"], pool, cfg["batch"], mask_empty)
+    oc, out, n_out, status = dsvt.dsvt_attn_pool(pw, dev_coords(coords), dev_feats(x, cfg["dtype"]))
+    torch.cuda.synchronize()
+    m = int(n_out.item())
+    assert int(status.item()) == 0 and m == len(ref_c) < len(coords)
+    assert np.array_equal(oc[:m].cpu().numpy(), ref_c)            # coordinates and order bit-exact
+    err = rel_err(out[:m], ref)
+    _say(f"  regions {m}, rel err {err:.3e}")
+    assert err < TOL[cfg["dtype"]]
+    assert torch.all(out[m:] == 0) and torch.all(oc[m:] == 0)     # rows past n_out untouched
+
+
+def test_attn_pool_then_block():
+    """The pooled voxels feed a rotated layer pair on the pooled grid (window 12 x 12 x 8, tau 48)."""
+    cfg = synth.CONFIGS[4]
+    coords = synth.make_frame(4, n=30000)
+    x = synth.make_features(36, len(coords), cfg["C"], cfg["dtype"])
+    w = synth.make_pool_weights(92, cfg["C"], cfg["heads"], cfg["dtype"])
+    ws = [synth.make_layer_weights(93 + a, cfg["C"], cfg["heads"], cfg["hidden"], cfg["win"], cfg["dtype"]) for a in (0, 1)]
+    pgrid = (468, 468, 8)
+    _say("attn_pool + block on the pooled grid")
+    ref_c, ref_p = orc.attn_pool(w, coords, x, cfg["grid"], cfg["pool"], 1)
+    ref_p16 = synth.round_bf16(ref_p.astype(np.float32))          # the GPU hands bf16 features to the block
+    oms = [orc.partition(ref_c, pgrid, cfg["win"], (0, 0, 0), cfg["tau"], a) for a in (0, 1)]
+    ref = orc.block(ws, oms, ref_c, ref_p16)
+    pw = dsvt.PoolWeights(w, cfg["grid"], cfg["pool"], 1, 1)
+    oc, out, n_out, _ = dsvt.dsvt_attn_pool(pw, dev_coords(coords), dev_feats(x, "bf16"))
+    m = int(n_out.item())
+    pc, px = oc[:m].contiguous(), out[:m].contiguous()
+    gms = [gpu_maps(pc, pgrid, cfg["win"], (0, 0, 0), cfg["tau"], 1, a) for a in (0, 1)]
+    for gm, om in zip(gms, oms):
+        assert_maps_equal(gm, om)
+    y = dsvt.dsvt_block([dsvt.LayerWeights(v) for v in ws], gms, pc, px)
+    torch.cuda.synchronize()
+    err = rel_err(y, ref)
+    _say(f"  rel err {err:.3e}")
+    assert err < TOL["bf16"]
