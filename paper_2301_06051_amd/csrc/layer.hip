@@ -19,6 +19,8 @@ constexpr int kMaxSets = kRowsMax / 4;           // every set takes at least 4 r
 constexpr int kRowsPad = kRowsMax + 16;          // per-row arrays are read 4 at a time up to 15 rows past a set's end
 constexpr int kMaxItems = 2 * (kRowsMax / 16 + kMaxSets);   // attention items: (set, query tile, half of the heads)
 constexpr int kFixedSets = kRowsMax / kTauMax;   // sets per workgroup when no tile list is given
+constexpr int kLayerWaves = 8;                   // two per SIMD: one workgroup per CU (LDS), the second wavefront hides the first one's waits
+constexpr int kHalfTiles = kRowTiles / 2;        // GEMM work items cover half of the row tiles
 
 struct LayerDev {
   const void *w_qkv, *w_o, *w_1, *w_2;       // packed (see mma.h)
@@ -208,13 +210,13 @@ __device__ __forceinline__ void attn_item(const LayerDev& p, T* Qs, const T* Ks,
 }
 
 template <typename T, int C, int HEADS, int HID, int NT_QKV, int NT_O, int NT_1, int NT_2>
-__global__ void __launch_bounds__(kWaves * 64)
+__global__ void __launch_bounds__(kLayerWaves * 64)
 k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* out, int full_layer) {
   // out may be x: a tile's rows are read, then written, by this workgroup only
   typedef LayerLds<T, C, HEADS, HID> L;
   typedef typename Mma<T>::Vec4 Vec4;
   constexpr int LDX = L::LDX, LDV = L::LDV, LDH = L::LDH;
-  constexpr int NW = kWaves, NTHREADS = NW * 64;
+  constexpr int NW = kLayerWaves, NTHREADS = NW * 64;
   static_assert(C / (16 * NT_O) == kStatGroups && C / (16 * NT_2) == kStatGroups, "LayerNorm phases: one item per wave");
   extern __shared__ __align__(16) unsigned char smem[];
   T* Xs = reinterpret_cast<T*>(smem + L::off_x);
@@ -235,7 +237,7 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
   // The first Q/K/V weight fragments are requested before anything else: their latency hides
   // behind the row bookkeeping and the gather.
   DSVT_CLK(0);
-  GemmPhase<T, NT_QKV, C, 3 * C, NW> qkv(reinterpret_cast<const T*>(p.w_qkv), wave);
+  GemmPhase<T, NT_QKV, C, 3 * C, NW, 2, false> qkv(reinterpret_cast<const T*>(p.w_qkv), wave);
   qkv.prefetch();
 
   int n_sets = *mp.n_sets;
@@ -339,9 +341,11 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
       }
     });
   }
-  GemmPhase<T, NT_O, C, C, NW> oproj(reinterpret_cast<const T*>(p.w_o), wave);
+  GemmPhase<T, NT_O, C, C, NW, 2> oproj(reinterpret_cast<const T*>(p.w_o), wave);
   oproj.prefetch();                              // in flight during the attention phase
-  const int o_own = wave * 16 * NT_O;            // this wavefront's features in the LayerNorm phases
+  const int og_own = wave % kStatGroups;         // LayerNorm phases: this wavefront's feature group ...
+  const int rt_own = (wave / kStatGroups) * (RTK >> 1), HC = RTK >> 1;   // ... and half of the row tiles
+  const int o_own = og_own * 16 * NT_O;
   f32x4 bo4[NT_O], g1[NT_O], be1[NT_O];
 #pragma unroll
   for (int nt = 0; nt < NT_O; ++nt) {
@@ -368,29 +372,29 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
   DSVT_CLK(4);
 
   // ---- 5. Y = O Wo^T + bo (+ x), then LayerNorm; result (or raw Y) replaces x in Xs
-  f32x4 keep[NT_O][kRowTiles];
-  if (RTK == 2) oproj.template run_keep<2>(Qs, LDX, bo4, keep);
-  else if (RTK == 4) oproj.template run_keep<4>(Qs, LDX, bo4, keep);
-  else oproj.template run_keep<6>(Qs, LDX, bo4, keep);
+  f32x4 keep[NT_O][kHalfTiles];
+  if (HC == 1) oproj.template run_keep<1>(Qs, LDX, rt_own, bo4, keep);
+  else if (HC == 2) oproj.template run_keep<2>(Qs, LDX, rt_own, bo4, keep);
+  else oproj.template run_keep<3>(Qs, LDX, rt_own, bo4, keep);
 #pragma unroll
   for (int nt = 0; nt < NT_O; ++nt) {
     const int o = o_own + 16 * nt + 4 * g;
 #pragma unroll
-    for (int r = 0; r < kRowTiles; ++r) {
-      if (r < RTK) {
+    for (int r = 0; r < kHalfTiles; ++r) {
+      if (r < HC) {
         if (full_layer) {
-          const Vec4 xr = *reinterpret_cast<const Vec4*>(Xs + (16 * r + m) * LDX + o);
+          const Vec4 xr = *reinterpret_cast<const Vec4*>(Xs + (16 * (rt_own + r) + m) * LDX + o);
           keep[nt][r] += f32x4{to_f32<T>(xr[0]), to_f32<T>(xr[1]), to_f32<T>(xr[2]), to_f32<T>(xr[3])};
         } else {
-          *reinterpret_cast<Vec4*>(Xs + (16 * r + m) * LDX + o) = pack4<T>(keep[nt][r]);
+          *reinterpret_cast<Vec4*>(Xs + (16 * (rt_own + r) + m) * LDX + o) = pack4<T>(keep[nt][r]);
         }
       }
     }
   }
   if (full_layer) {
-    GemmPhase<T, NT_1, C, HID, NW> ffn1(reinterpret_cast<const T*>(p.w_1), wave);
+    GemmPhase<T, NT_1, C, HID, NW, 2, false> ffn1(reinterpret_cast<const T*>(p.w_1), wave);
     ffn1.prefetch();                             // in flight during the LayerNorm exchange
-    layer_norm_tile<T, NT_O, C>(keep, o_own, wave, RTK, stat, g1, be1, p.ln_eps, Xs, LDX);
+    layer_norm_tile<T, NT_O, C, kHalfTiles>(keep, o_own, og_own, rt_own, HC, stat, g1, be1, p.ln_eps, Xs, LDX);
     __syncthreads();
     DSVT_CLK(5);
 
@@ -404,9 +408,9 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
         *reinterpret_cast<Vec4*>(Hs + (16 * r + m) * LDH + o) = pack4<T>(v);
       }
     });
-    GemmPhase<T, NT_2, HID, C, NW> ffn2(reinterpret_cast<const T*>(p.w_2), wave);
+    GemmPhase<T, NT_2, HID, C, NW, 2, true, (HID / Mma<T>::KC > 8 ? 2 : 1)> ffn2(reinterpret_cast<const T*>(p.w_2), wave);
     ffn2.prefetch();
-    const int o_own2 = wave * 16 * NT_2;
+    const int o_own2 = og_own * 16 * NT_2;
     f32x4 b24[NT_2], g2[NT_2], be2[NT_2];
 #pragma unroll
     for (int nt = 0; nt < NT_2; ++nt) {
@@ -416,22 +420,22 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
     }
     __syncthreads();
     DSVT_CLK(6);
-    f32x4 keep2[NT_2][kRowTiles];
-    if (RTK == 2) ffn2.template run_keep<2>(Hs, LDH, b24, keep2);
-    else if (RTK == 4) ffn2.template run_keep<4>(Hs, LDH, b24, keep2);
-    else ffn2.template run_keep<6>(Hs, LDH, b24, keep2);
+    f32x4 keep2[NT_2][kHalfTiles];
+    if (HC == 1) ffn2.template run_keep<1>(Hs, LDH, rt_own, b24, keep2);
+    else if (HC == 2) ffn2.template run_keep<2>(Hs, LDH, rt_own, b24, keep2);
+    else ffn2.template run_keep<3>(Hs, LDH, rt_own, b24, keep2);
 #pragma unroll
     for (int nt = 0; nt < NT_2; ++nt) {
       const int o = o_own2 + 16 * nt + 4 * g;
 #pragma unroll
-      for (int r = 0; r < kRowTiles; ++r) {
-        if (r < RTK) {
-          const Vec4 xr = *reinterpret_cast<const Vec4*>(Xs + (16 * r + m) * LDX + o);
+      for (int r = 0; r < kHalfTiles; ++r) {
+        if (r < HC) {
+          const Vec4 xr = *reinterpret_cast<const Vec4*>(Xs + (16 * (rt_own + r) + m) * LDX + o);
           keep2[nt][r] += f32x4{to_f32<T>(xr[0]), to_f32<T>(xr[1]), to_f32<T>(xr[2]), to_f32<T>(xr[3])};
         }
       }
     }
-    layer_norm_tile<T, NT_2, C>(keep2, o_own2, wave, RTK, stat, g2, be2, p.ln_eps, Xs, LDX);
+    layer_norm_tile<T, NT_2, C, kHalfTiles>(keep2, o_own2, og_own, rt_own, HC, stat, g2, be2, p.ln_eps, Xs, LDX);
   }
   __syncthreads();
   DSVT_CLK(7);
@@ -537,7 +541,7 @@ int launch_layer(const dsvt_layer_w& w, const dsvt_maps& mp, const int32_t* coor
   md.max_sets = mp.max_sets; md.tau = mp.tau; md.n_voxels = mp.n_voxels;
   const unsigned grid = mp.tile_first ? (unsigned)mp.max_tiles : (unsigned)dsvt_ceil_div(mp.max_sets, kFixedSets);
   dsvt_prof_scope ps(DSVT_K_LAYER, st);
-  kern<<<grid, kWaves * 64, lds, st>>>(to_dev(w), md, reinterpret_cast<const int4*>(coords),
+  kern<<<grid, kLayerWaves * 64, lds, st>>>(to_dev(w), md, reinterpret_cast<const int4*>(coords),
                                        reinterpret_cast<const T*>(x), reinterpret_cast<T*>(out), full);
   return DSVT_OK;
 }

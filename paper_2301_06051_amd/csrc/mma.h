@@ -76,24 +76,25 @@ template <typename T, int NT, int NKF> struct AFull { typename Mma<T>::Frag f[NK
 // B-operand fragments of one row tile (16 rows) over the whole K.
 template <typename T, int NKF> struct BRow { typename Mma<T>::Frag f[NKF]; };
 
-// Wp: packed matrix with NKF = K / KC fragments per tile; tiles tile0 .. tile0 + NT - 1.
-template <typename T, int NT, int NKF>
-__device__ __forceinline__ void load_a(AFull<T, NT, NKF>& a, const T* __restrict__ Wp, int tile0) {
+// Wp: packed matrix with NKF_ALL = K / KC fragments per tile; tiles tile0 .. tile0 + NT - 1,
+// k-fragments kf0 .. kf0 + NKF - 1.
+template <typename T, int NT, int NKF, int NKF_ALL = NKF>
+__device__ __forceinline__ void load_a(AFull<T, NT, NKF>& a, const T* __restrict__ Wp, int tile0, int kf0 = 0) {
   typedef typename Mma<T>::Frag Frag;
   const int lane = threadIdx.x & 63;
-  const Frag* fp = reinterpret_cast<const Frag*>(Wp) + (size_t)tile0 * NKF * 64 + lane;
+  const Frag* fp = reinterpret_cast<const Frag*>(Wp) + ((size_t)tile0 * NKF_ALL + kf0) * 64 + lane;
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-    for (int kf = 0; kf < NKF; ++kf) a.f[kf][nt] = fp[(nt * NKF + kf) * 64];
+    for (int kf = 0; kf < NKF; ++kf) a.f[kf][nt] = fp[(nt * NKF_ALL + kf) * 64];
 }
 
-// Xs: LDS [rows][ldx]; row tile r.
+// Xs: LDS [rows][ldx]; row tile r, k from k0.
 template <typename T, int NKF>
-__device__ __forceinline__ void load_b(BRow<T, NKF>& b, const T* Xs, int ldx, int r) {
+__device__ __forceinline__ void load_b(BRow<T, NKF>& b, const T* Xs, int ldx, int r, int k0 = 0) {
   typedef typename Mma<T>::Frag Frag;
   const int lane = threadIdx.x & 63, m = lane & 15, g = lane >> 4;
-  const T* xp = Xs + (16 * r + m) * ldx + g * Mma<T>::KL;
+  const T* xp = Xs + (16 * r + m) * ldx + k0 + g * Mma<T>::KL;
 #pragma unroll
   for (int kf = 0; kf < NKF; ++kf) b.f[kf] = *reinterpret_cast<const Frag*>(xp + kf * Mma<T>::KC);
 }
@@ -108,79 +109,98 @@ __device__ __forceinline__ void mma_row(f32x4 (&acc)[NT], const AFull<T, NT, NKF
 
 constexpr int kRowTiles = 6;                     // row tiles of a workgroup tile
 constexpr int kRowsMax = 16 * kRowTiles;         // 96 rows
-constexpr int kWaves = 4;                        // wavefronts per workgroup, one per SIMD: the LDS tile leaves room for one workgroup per CU
-constexpr int kStatGroups = kWaves;              // LayerNorm phases: every wavefront owns C / 4 features of all rows
+constexpr int kWaves = 4;                        // wavefronts of a pooling workgroup, one per SIMD
+constexpr int kStatGroups = 4;                   // LayerNorm phases: the C features are split over 4 groups of output tiles
 
 // One GEMM phase of a workgroup of NW wavefronts: Out^T[NOUT x rows] = W[NOUT x K] . X^T.
-// A work item is a group of NT output tiles over all row tiles; wavefront w takes items
+// A work item is a group of NT output tiles over all row tiles (RSPLIT = 1) or over one half of
+// them (RSPLIT = 2, for workgroups with two wavefronts per SIMD); wavefront w takes items
 // w, w + NW, ...  An item's weight fragments sit in registers for the whole item, the next item's
 // are requested before the current one is consumed, and inside an item the activations of row
-// tile r + 1 are read from LDS while row tile r is in the matrix cores.  Every weight fragment
-// is loaded by exactly one wavefront and every activation fragment feeds NT MFMAs.
-template <typename T, int NT, int K, int NOUT, int NW> struct GemmPhase {
+// tile r + 1 are read from LDS while row tile r is in the matrix cores.  Every activation
+// fragment read from LDS feeds NT MFMAs; a weight fragment is loaded by RSPLIT wavefronts.
+template <typename T, int NT, int K, int NOUT, int NW, int RSPLIT = 1, bool DOUBLE_A = true, int KSPLIT = 1>
+struct GemmPhase {
   static constexpr int KC = Mma<T>::KC;
-  static constexpr int NKF = K / KC;
-  static constexpr int N_ITEMS = NOUT / (16 * NT);
+  static constexpr int NKF_ALL = K / KC;
+  static constexpr int NKF = NKF_ALL / KSPLIT;          // fragments held at a time (KSPLIT > 1: run_keep only)
+  static constexpr int N_OG = NOUT / (16 * NT);
+  static constexpr int N_ITEMS = RSPLIT * N_OG;
   static constexpr int IPW = N_ITEMS / NW;
-  static_assert(N_ITEMS % NW == 0 && K % KC == 0 && NOUT % (16 * NT) == 0, "phase shape");
-  AFull<T, NT, NKF> a[IPW > 1 ? 2 : 1];
+  static constexpr int RH = kRowTiles / RSPLIT;          // row tiles an item can cover
+  static_assert(N_ITEMS % NW == 0 && K % KC == 0 && NOUT % (16 * NT) == 0 && (RSPLIT == 1 || RSPLIT == 2), "phase shape");
+  AFull<T, NT, NKF> a[(IPW > 1 && DOUBLE_A) ? 2 : 1];   // DOUBLE_A: the next item's weights load during the current item
   const T* Wp;
   int wave;
 
   __device__ __forceinline__ GemmPhase(const T* wp, int wave_) : Wp(wp), wave(wave_) {}
 
   // Request the weights of this wavefront's first item (may be called long before run()).
-  __device__ __forceinline__ void prefetch() { load_a<T, NT, NKF>(a[0], Wp, wave * NT); }
+  __device__ __forceinline__ void prefetch() { load_a<T, NT, NKF, NKF_ALL>(a[0], Wp, (wave % N_OG) * NT); }
 
   // Row tiles in a rolled loop, two per trip.  epi(o0, r, acc): acc[nt][i] is output feature
   // o0 + 16*nt + 4*g + i of row 16*r + m, bias included.  The bias is fetched before the next
   // item's weights are requested, so waiting for it never waits for them.
   template <typename Epi>
   __device__ __forceinline__ void run(const T* Xs, int ldx, int RT, const float* __restrict__ bias, Epi epi) {
+    static_assert(KSPLIT == 1, "run() holds the whole K");
     const int g4 = ((threadIdx.x & 63) >> 4) * 4;
+    const int h0 = RSPLIT == 1 ? RT : (RT + 1) >> 1;
 #pragma unroll
     for (int it = 0; it < IPW; ++it) {
       const int item = wave + it * NW;
+      const int og = item % N_OG, half = item / N_OG;
+      const int rt0 = half ? h0 : 0, cnt = half ? RT - h0 : h0;
       f32x4 b4[NT];
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt) b4[nt] = *reinterpret_cast<const f32x4*>(bias + item * 16 * NT + 16 * nt + g4);
-      if (it + 1 < IPW) load_a<T, NT, NKF>(a[(it + 1) & 1], Wp, (item + NW) * NT);
-      const AFull<T, NT, NKF>& A = a[it & 1];
+      for (int nt = 0; nt < NT; ++nt) b4[nt] = *reinterpret_cast<const f32x4*>(bias + og * 16 * NT + 16 * nt + g4);
+      if (DOUBLE_A && it + 1 < IPW) load_a<T, NT, NKF>(a[(it + 1) & 1], Wp, ((item + NW) % N_OG) * NT);
+      const AFull<T, NT, NKF>& A = a[DOUBLE_A ? (it & 1) : 0];
       BRow<T, NKF> b0, b1;
-      load_b<T, NKF>(b0, Xs, ldx, 0);
-      for (int r = 0; r < RT; r += 2) {
-        const bool two = r + 1 < RT;
-        if (two) load_b<T, NKF>(b1, Xs, ldx, r + 1);
+      if (cnt > 0) load_b<T, NKF>(b0, Xs, ldx, rt0);
+      for (int r = 0; r < cnt; r += 2) {
+        const bool two = r + 1 < cnt;
+        if (two) load_b<T, NKF>(b1, Xs, ldx, rt0 + r + 1);
         f32x4 acc0[NT], acc1[NT];                // the bias is the accumulators' initial value
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) { acc0[nt] = b4[nt]; acc1[nt] = b4[nt]; }
         mma_row<T, NT, NKF>(acc0, A, b0);
         if (two) {
-          if (r + 2 < RT) load_b<T, NKF>(b0, Xs, ldx, r + 2);
+          if (r + 2 < cnt) load_b<T, NKF>(b0, Xs, ldx, rt0 + r + 2);
           mma_row<T, NT, NKF>(acc1, A, b1);
         }
-        epi(item * 16 * NT, r, acc0);
-        if (two) epi(item * 16 * NT, r + 1, acc1);
+        epi(og * 16 * NT, rt0 + r, acc0);
+        if (two) epi(og * 16 * NT, rt0 + r + 1, acc1);
       }
+      if (!DOUBLE_A && it + 1 < IPW) load_a<T, NT, NKF>(a[0], Wp, ((item + NW) % N_OG) * NT);
     }
   }
 
-  // One item per wavefront, RTC row tiles unrolled, all accumulators returned (the LayerNorm
-  // phases need a row's values in registers across a workgroup barrier).
-  template <int RTC>
-  __device__ __forceinline__ void run_keep(const T* Xs, int ldx, const f32x4 (&b4)[NT], f32x4 (&acc)[NT][kRowTiles]) {
-    static_assert(IPW == 1, "one item per wavefront");
-    BRow<T, NKF> b[2];
-    load_b<T, NKF>(b[0], Xs, ldx, 0);
+  // One item per wavefront: row tiles rt0 .. rt0 + HC - 1 unrolled, all accumulators returned
+  // (the LayerNorm phases need a row's values in registers across a workgroup barrier).  With
+  // KSPLIT > 1 the weights pass through the registers one K-slice at a time.
+  template <int HC>
+  __device__ __forceinline__ void run_keep(const T* Xs, int ldx, int rt0, const f32x4 (&b4)[NT], f32x4 (&acc)[NT][RH]) {
+    static_assert(IPW == 1 && HC <= RH, "one item per wavefront");
 #pragma unroll
-    for (int r = 0; r < RTC; ++r) {
-      if (r + 1 < RTC) load_b<T, NKF>(b[(r + 1) & 1], Xs, ldx, r + 1);
-      f32x4 t[NT];
+    for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt) t[nt] = b4[nt];
-      mma_row<T, NT, NKF>(t, a[0], b[r & 1]);
+      for (int r = 0; r < HC; ++r) acc[nt][r] = b4[nt];
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt) acc[nt][r] = t[nt];
+    for (int ks = 0; ks < KSPLIT; ++ks) {
+      if (ks > 0) load_a<T, NT, NKF, NKF_ALL>(a[0], Wp, (wave % N_OG) * NT, ks * NKF);
+      BRow<T, NKF> b[2];
+      load_b<T, NKF>(b[0], Xs, ldx, rt0, ks * NKF * KC);
+#pragma unroll
+      for (int r = 0; r < HC; ++r) {
+        if (r + 1 < HC) load_b<T, NKF>(b[(r + 1) & 1], Xs, ldx, rt0 + r + 1, ks * NKF * KC);
+        f32x4 t[NT];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) t[nt] = acc[nt][r];
+        mma_row<T, NT, NKF>(t, a[0], b[r & 1]);
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) acc[nt][r] = t[nt];
+      }
     }
   }
 };
@@ -238,10 +258,10 @@ __device__ __forceinline__ float gelu_erf_fast(float x) {
 
 // LayerNorm over the C features of every row, for values spread over the workgroup in
 // accumulator layout: this wavefront holds features o0 .. o0 + 16*NT - 1 (group og of
-// kStatGroups) of rows 16*r + m, r < RT.  Per-group sums of x and x^2 (fp32) are exchanged
-// through LDS; variance = E[x^2] - mean^2.  Every thread of the workgroup must call it.
-template <typename T, int NT, int C>
-__device__ __forceinline__ void layer_norm_tile(f32x4 (&v)[NT][kRowTiles], int o0, int og, int RT, float* stat,
+// kStatGroups) of rows 16*(rt0 + r) + m, r < cnt.  Per-group sums of x and x^2 (fp32) are
+// exchanged through LDS; variance = E[x^2] - mean^2.  Every thread of the workgroup must call it.
+template <typename T, int NT, int C, int RH>
+__device__ __forceinline__ void layer_norm_tile(f32x4 (&v)[NT][RH], int o0, int og, int rt0, int cnt, float* stat,
                                                 const f32x4 (&ga)[NT], const f32x4 (&be)[NT], float eps, T* dst,
                                                 int ldd) {
   typedef typename Mma<T>::Vec4 Vec4;
@@ -249,8 +269,8 @@ __device__ __forceinline__ void layer_norm_tile(f32x4 (&v)[NT][kRowTiles], int o
   float* stat1 = stat;
   float* stat2 = stat + kStatGroups * kRowsMax;
 #pragma unroll
-  for (int r = 0; r < kRowTiles; ++r) {
-    if (r < RT) {
+  for (int r = 0; r < RH; ++r) {
+    if (r < cnt) {
       float s = 0.f, q = 0.f;
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) {
@@ -259,14 +279,14 @@ __device__ __forceinline__ void layer_norm_tile(f32x4 (&v)[NT][kRowTiles], int o
       }
       s = col_sum(s);
       q = col_sum(q);
-      if (g == 0) { stat1[og * kRowsMax + 16 * r + m] = s; stat2[og * kRowsMax + 16 * r + m] = q; }
+      if (g == 0) { stat1[og * kRowsMax + 16 * (rt0 + r) + m] = s; stat2[og * kRowsMax + 16 * (rt0 + r) + m] = q; }
     }
   }
   __syncthreads();
 #pragma unroll
-  for (int r = 0; r < kRowTiles; ++r) {
-    if (r < RT) {
-      const int row = 16 * r + m;
+  for (int r = 0; r < RH; ++r) {
+    if (r < cnt) {
+      const int row = 16 * (rt0 + r) + m;
       float s = 0.f, q = 0.f;
 #pragma unroll
       for (int k = 0; k < kStatGroups; ++k) { s += stat1[k * kRowsMax + row]; q += stat2[k * kRowsMax + row]; }

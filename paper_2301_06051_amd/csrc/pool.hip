@@ -229,7 +229,7 @@ kp_attention(PoolDev p, const int32_t* __restrict__ pool_inds, const int32_t* __
 
   // out = LN(P + O Wo^T + bo)
   f32x4 keep[NT_C][kRowTiles];
-  op.template run_keep<kQRows / 16>(Qs, LDX, bo4, keep);
+  op.template run_keep<kQRows / 16>(Qs, LDX, 0, bo4, keep);
 #pragma unroll
   for (int nt = 0; nt < NT_C; ++nt)
 #pragma unroll
@@ -237,7 +237,7 @@ kp_attention(PoolDev p, const int32_t* __restrict__ pool_inds, const int32_t* __
       const Vec4 xr = *reinterpret_cast<const Vec4*>(Ps + (16 * r + (lane & 15)) * LDX + o_own + 16 * nt + 4 * g);
       keep[nt][r] += f32x4{to_f32<T>(xr[0]), to_f32<T>(xr[1]), to_f32<T>(xr[2]), to_f32<T>(xr[3])};
     }
-  layer_norm_tile<T, NT_C, C>(keep, o_own, wave, kQRows / 16, stat, ga, be, p.ln_eps, Ps, LDX);
+  layer_norm_tile<T, NT_C, C, kRowTiles>(keep, o_own, wave, 0, kQRows / 16, stat, ga, be, p.ln_eps, Ps, LDX);
   __syncthreads();
   for (int idx = tid; idx < mr * CH; idx += NTHREADS) {
     const int r = idx / CH, c = idx - r * CH;
