@@ -50,13 +50,28 @@ def main():
     maps = {sh: [dsvt.SetMaps(pc, N) for pc in pcs] for sh, pcs in pcfgs.items()}
     ws = torch.empty((max(dsvt.dsvt_block_workspace_size(layers[0][0], N), 1),), dtype=torch.uint8, device="cuda")
 
+    # The four partitions are independent of each other and only the first pair is needed by
+    # block 0: each runs on its own stream (default priority) and joins the main stream where its
+    # maps are first used, so in the captured graph they are parallel branches.
+    order = [(sh, a) for sh in cfg["shifts"] for a in (0, 1)]
+    side_streams = [torch.cuda.Stream() for _ in order]
+
     def step():
-        for sh, pcs in pcfgs.items():
-            for a in (0, 1):
-                dsvt.dsvt_partition(pcs[a], cd, out=maps[sh][a])
+        main = torch.cuda.current_stream()
+        for st, (sh, a) in zip(side_streams, order):
+            st.wait_stream(main)
+            with torch.cuda.stream(st):
+                dsvt.dsvt_partition(pcfgs[sh][a], cd, out=maps[sh][a])
+        joined = set()
         src = x0
         for b, pair in enumerate(layers):
-            dsvt.dsvt_block(pair, maps[cfg["shifts"][b % len(cfg["shifts"])]], cd, src, x_out=buf, ws=ws)
+            sh = cfg["shifts"][b % len(cfg["shifts"])]
+            if sh not in joined:
+                for st, (s2, a) in zip(side_streams, order):
+                    if s2 == sh:
+                        main.wait_stream(st)
+                joined.add(sh)
+            dsvt.dsvt_block(pair, maps[sh], cd, src, x_out=buf, ws=ws)
             src = buf
 
     step()

@@ -67,6 +67,7 @@ int dsvt_partition_bound(const dsvt_part_cfg* cfg, int32_t n_voxels, int32_t* ma
  * tile_first [device] int32 [max_tiles+1]  out: work list for the layer kernels (see dsvt_maps): sets
  *                                               tile_first[t] .. tile_first[t+1]-1 form tile t; may be NULL
  * n_tiles    [device] int32 scalar         out: number of tiles; NULL iff tile_first is NULL
+ * tile_order [device] int32 [max_tiles]    out: tile indices in launch order (most rows first); may be NULL
  * ws         [device] scratch of at least the bytes dsvt_partition_bound reports
  * status     [device] int32 word, OR-ed with DSVT_ST_* bits (the caller zeroes it)
  * Errors: DSVT_EINVAL (NULL pointer, non-positive size, shift outside [0,win), axis not 0/1,
@@ -74,7 +75,7 @@ int dsvt_partition_bound(const dsvt_part_cfg* cfg, int32_t n_voxels, int32_t* ma
  * list asked for with tau > 48), DSVT_EHIP. */
 int dsvt_partition(const dsvt_part_cfg* cfg, const int32_t* coords, int32_t n_voxels,
                    int32_t* set_inds, int32_t* voxel_slot, int32_t* n_sets, int32_t max_sets,
-                   int32_t* set_win, int32_t* tile_first, int32_t* n_tiles, int32_t max_tiles,
+                   int32_t* set_win, int32_t* tile_first, int32_t* n_tiles, int32_t* tile_order, int32_t max_tiles,
                    void* ws, size_t ws_bytes, int32_t* status, void* stream);
 
 /* The maps one layer consumes (outputs of dsvt_partition, all [device]). */
@@ -90,6 +91,7 @@ typedef struct {
   int32_t max_tiles;         /* rows of tile_first minus one                            */
   const int32_t* tile_first; /* [max_tiles+1]                                           */
   const int32_t* n_tiles;    /* scalar, <= max_tiles                                    */
+  const int32_t* tile_order; /* [max_tiles] workgroup b takes tile tile_order[b]; NULL = tile b */
 } dsvt_maps;
 
 /* ---------------------------------------------------------------------------------------

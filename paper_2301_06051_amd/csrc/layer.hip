@@ -41,7 +41,7 @@ long long* g_phase_clocks = nullptr;
 #endif
 
 struct MapsDev {
-  const int32_t *set_inds, *n_sets, *tile_first, *n_tiles;
+  const int32_t *set_inds, *n_sets, *tile_first, *n_tiles, *tile_order;
   int32_t max_sets, tau, n_voxels;
 };
 
@@ -237,6 +237,9 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
   // The first Q/K/V weight fragments are requested before anything else: their latency hides
   // behind the row bookkeeping and the gather.
   DSVT_CLK(0);
+#ifdef DSVT_PHASE_CLOCKS
+  if (p.clk && threadIdx.x == 0) p.clk[blockIdx.x * 16 + 11] = wall_clock64();
+#endif
   GemmPhase<T, NT_QKV, C, 3 * C, NW, 2, false> qkv(reinterpret_cast<const T*>(p.w_qkv), wave);
   qkv.prefetch();
 
@@ -244,9 +247,12 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
   n_sets = n_sets < mp.max_sets ? n_sets : mp.max_sets;
   int s_begin, s_end;
   if (mp.tile_first != nullptr) {
-    if ((int)blockIdx.x >= *mp.n_tiles) return;
-    s_begin = mp.tile_first[blockIdx.x];
-    s_end = mp.tile_first[blockIdx.x + 1];
+    const int n_tiles = *mp.n_tiles;
+    if ((int)blockIdx.x >= n_tiles) return;
+    int t = mp.tile_order ? mp.tile_order[blockIdx.x] : (int)blockIdx.x;
+    t = t < 0 ? 0 : (t >= n_tiles ? n_tiles - 1 : t);
+    s_begin = mp.tile_first[t];
+    s_end = mp.tile_first[t + 1];
   } else {
     s_begin = blockIdx.x * kFixedSets;
     s_end = s_begin + kFixedSets;
@@ -453,7 +459,7 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
   }
   DSVT_CLK(8);
 #ifdef DSVT_PHASE_CLOCKS
-  if (p.clk && threadIdx.x == 0) { p.clk[blockIdx.x * 16 + 9] = R; p.clk[blockIdx.x * 16 + 10] = ns; }
+  if (p.clk && threadIdx.x == 0) { p.clk[blockIdx.x * 16 + 9] = R; p.clk[blockIdx.x * 16 + 10] = ns; p.clk[blockIdx.x * 16 + 12] = wall_clock64(); }
 #endif
 }
 
@@ -537,7 +543,7 @@ int launch_layer(const dsvt_layer_w& w, const dsvt_maps& mp, const int32_t* coor
   static int prepared = allow_lds(kern, lds);
   if (prepared != DSVT_OK) return prepared;
   MapsDev md;
-  md.set_inds = mp.set_inds; md.n_sets = mp.n_sets; md.tile_first = mp.tile_first; md.n_tiles = mp.n_tiles;
+  md.set_inds = mp.set_inds; md.n_sets = mp.n_sets; md.tile_first = mp.tile_first; md.n_tiles = mp.n_tiles; md.tile_order = mp.tile_first ? mp.tile_order : nullptr;
   md.max_sets = mp.max_sets; md.tau = mp.tau; md.n_voxels = mp.n_voxels;
   const unsigned grid = mp.tile_first ? (unsigned)mp.max_tiles : (unsigned)dsvt_ceil_div(mp.max_sets, kFixedSets);
   dsvt_prof_scope ps(DSVT_K_LAYER, st);

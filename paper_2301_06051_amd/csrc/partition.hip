@@ -157,9 +157,11 @@ __global__ void __launch_bounds__(1024) k_tiles(const int32_t* __restrict__ set_
                                                 const int32_t* __restrict__ win_soff, const int32_t* __restrict__ n_sets_ptr,
                                                 int32_t set_cap, int32_t tau, int32_t n_windows, int32_t rows_per_cut,
                                                 int32_t* __restrict__ tile_first, int32_t* __restrict__ n_tiles,
-                                                int32_t max_tiles) {
+                                                int32_t max_tiles, int32_t* __restrict__ tile_rows,
+                                                int32_t* __restrict__ tile_order) {
   __shared__ int32_t wave_tot[16];
   __shared__ int32_t carry_s;
+  __shared__ int32_t hist[32], running[32], wave_cnt[16][32];
   const int32_t tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   int32_t n_sets = *n_sets_ptr;
   n_sets = n_sets < set_cap ? n_sets : set_cap;
@@ -182,23 +184,74 @@ __global__ void __launch_bounds__(1024) k_tiles(const int32_t* __restrict__ set_
       const int32_t tile = P / rows_per_cut;
       bool first = s == 0;
       if (!first) first = (P - padded_rows(s - 1, set_win, win_count, win_soff, tau, n_windows)) / rows_per_cut != tile;
-      if (first && tile < max_tiles) tile_first[tile] = s;
+      if (first && tile < max_tiles) { tile_first[tile] = s; tile_rows[tile] = P; }
       if (s == n_sets - 1) {
         const int32_t nt = tile + 1 < max_tiles ? tile + 1 : max_tiles;
         *n_tiles = nt;
         tile_first[nt] = n_sets;
+        tile_rows[nt] = P + rows;
       }
     }
     __syncthreads();
     if (tid == 1023) carry_s = before + incl;
     __syncthreads();
   }
-  if (n_sets <= 0 && tid == 0) { *n_tiles = 0; tile_first[0] = 0; }
+  if (n_sets <= 0) {
+    if (tid == 0) { *n_tiles = 0; tile_first[0] = 0; }
+    return;
+  }
+  if (tile_order == nullptr) return;
+  // Launch order: tiles with more rows first (a stable counting sort on rows / 4), so that the
+  // short tiles fill the tail of the launch.  tile_rows[t] holds the rows before tile t.
+  __syncthreads();
+  const int32_t nt = *n_tiles;
+  if (tid < 32) hist[tid] = 0;
+  __syncthreads();
+  for (int32_t base = 0; base < nt; base += 1024) {
+    const int32_t t = base + tid;
+    if (t < nt) {
+      int32_t b = 24 - (tile_rows[t + 1] - tile_rows[t]) / 4;
+      b = b < 0 ? 0 : (b > 31 ? 31 : b);
+      atomicAdd(&hist[b], 1);
+    }
+  }
+  __syncthreads();
+  if (tid == 0) { int32_t acc = 0; for (int32_t b = 0; b < 32; ++b) { running[b] = acc; acc += hist[b]; } }
+  __syncthreads();
+  for (int32_t base = 0; base < nt; base += 1024) {
+    const int32_t t = base + tid;
+    int32_t b = -1;
+    if (t < nt) {
+      b = 24 - (tile_rows[t + 1] - tile_rows[t]) / 4;
+      b = b < 0 ? 0 : (b > 31 ? 31 : b);
+    }
+    for (int32_t k = lane; k < 32; k += 64) wave_cnt[wv][k] = 0;
+    // rank among this wavefront's lanes of the same bucket, in lane order
+    int32_t rank = 0;
+    unsigned long long todo = __ballot(b >= 0);
+    while (todo) {
+      const int32_t leader = __ffsll((long long)todo) - 1;
+      const int32_t lb = __shfl(b, leader, 64);
+      const unsigned long long same = __ballot(b == lb);
+      if (b == lb) rank = __popcll(same & ((1ull << lane) - 1ull));
+      if (lane == leader) wave_cnt[wv][lb] = __popcll(same);
+      todo &= ~same;
+    }
+    __syncthreads();
+    if (b >= 0) {
+      int32_t pos = running[b] + rank;
+      for (int32_t k = 0; k < wv; ++k) pos += wave_cnt[k][b];
+      tile_order[pos] = t;
+    }
+    __syncthreads();
+    if (tid < 32) { int32_t add = 0; for (int32_t k = 0; k < 16; ++k) add += wave_cnt[k][tid]; running[tid] += add; }
+    __syncthreads();
+  }
 }
 
 struct PartPlan {
   PartGeom g;
-  size_t off_bitmap, off_prefix, off_count, off_soff, off_keys, off_setwin, total;
+  size_t off_bitmap, off_prefix, off_count, off_soff, off_keys, off_setwin, off_tilerows, total;
   int64_t n_words;
   int32_t set_bound, tile_bound, rows_per_cut;
 };
@@ -236,6 +289,7 @@ int make_plan(const dsvt_part_cfg* cfg, int32_t n_voxels, PartPlan* p) {
   const int64_t pad_tau = (cfg->tau + 3) & ~3;
   p->rows_per_cut = (int32_t)(100 - pad_tau);
   p->tile_bound = p->rows_per_cut > 0 ? (int32_t)((n_voxels + 3 * bound) / p->rows_per_cut + 1) : 0;
+  p->off_tilerows = o; o = dsvt_align_up(o + (size_t)(p->tile_bound + 1) * 4, 256);
   p->total = o;
   return DSVT_OK;
 }
@@ -255,8 +309,8 @@ extern "C" int dsvt_partition_bound(const dsvt_part_cfg* cfg, int32_t n_voxels, 
 
 extern "C" int dsvt_partition(const dsvt_part_cfg* cfg, const int32_t* coords, int32_t n_voxels, int32_t* set_inds,
                               int32_t* voxel_slot, int32_t* n_sets, int32_t max_sets, int32_t* set_win,
-                              int32_t* tile_first, int32_t* n_tiles, int32_t max_tiles, void* ws, size_t ws_bytes,
-                              int32_t* status, void* stream) {
+                              int32_t* tile_first, int32_t* n_tiles, int32_t* tile_order, int32_t max_tiles, void* ws,
+                              size_t ws_bytes, int32_t* status, void* stream) {
   PartPlan p;
   int rc = make_plan(cfg, n_voxels, &p);
   if (rc != DSVT_OK) return rc;
@@ -265,6 +319,8 @@ extern "C" int dsvt_partition(const dsvt_part_cfg* cfg, const int32_t* coords, i
   if (ws_bytes < p.total) return DSVT_ENOSPC;
   if ((tile_first != nullptr) != (n_tiles != nullptr)) return DSVT_EINVAL;
   if (tile_first != nullptr && (max_tiles <= 0 || p.rows_per_cut < 48)) return max_tiles <= 0 ? DSVT_EINVAL : DSVT_EUNSUPPORTED;
+  if (tile_first == nullptr && tile_order != nullptr) return DSVT_EINVAL;
+  if (tile_first != nullptr && max_tiles > p.tile_bound) max_tiles = p.tile_bound;   // scratch is sized for the bound
   // window key of every set: the caller's array, or scratch when it is not wanted
   int32_t set_cap = max_sets;
   if (set_win == nullptr) {
@@ -308,7 +364,7 @@ extern "C" int dsvt_partition(const dsvt_part_cfg* cfg, const int32_t* coords, i
   if (tile_first != nullptr) {
     dsvt_prof_scope ps(DSVT_K_PART_TILES, st);
     k_tiles<<<1, 1024, 0, st>>>(set_win, count, soff, n_sets, set_cap, cfg->tau, p.g.n_windows, p.rows_per_cut, tile_first, n_tiles,
-                                max_tiles);
+                                max_tiles, (int32_t*)(base + p.off_tilerows), tile_order);
   }
   DSVT_HIP_TRY(hipGetLastError());
   return DSVT_OK;

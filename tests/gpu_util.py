@@ -41,6 +41,9 @@ def assert_tiles_valid(gm, om):
     uniq = 1 + (np.diff(si, axis=1) != 0).sum(1)
     rows = np.add.reduceat((uniq + 3) // 4 * 4, tf[:-1])
     assert rows.max() <= 96
+    order = gm.tile_order[:nt].cpu().numpy()
+    assert np.array_equal(np.sort(order), np.arange(nt))          # launch order is a permutation of the tiles ...
+    assert np.all(np.diff(rows[order] // 4) <= 0)                 # ... with the most rows first
 
 
 def assert_maps_equal(gm, om):
