@@ -54,6 +54,22 @@ typedef struct {
 int dsvt_partition_bound(const dsvt_part_cfg* cfg, int32_t n_voxels, int32_t* max_sets, int32_t* max_tiles,
                          size_t* ws_bytes);
 
+/* Work list for the layer kernels, written by dsvt_partition (all [device], caller-owned).  The sets
+ * are cut into tiles: runs of consecutive sets whose distinct voxels (every set padded to a multiple
+ * of 4 rows) fit one 96-row workgroup tile.
+ *   tile_first [max_tiles+1]     tile t covers sets tile_first[t] .. tile_first[t+1]-1
+ *   n_tiles    scalar            number of tiles (<= max_tiles)
+ *   tile_order [max_tiles]       tiles in launch order (most rows first)
+ *   tile_desc  [max_tiles][256]  per tile in launch order: [0] rows, [1] sets, [2+s] first row and
+ *                                [26+s] distinct voxels of its s-th set, [64+r] voxel of row r (-1 =
+ *                                padding), [160+r] (slots holding that voxel << 24) | position code
+ *                                (x*(2W-1) + y)*(2H-1) + z
+ * Needs tau <= 48 and grid[0]*(2W-1)*(2H-1) < 2^24. */
+typedef struct {
+  int32_t max_tiles;
+  int32_t *tile_first, *n_tiles, *tile_order, *tile_desc;
+} dsvt_tile_list;
+
 /* Builds the slot maps of one (window configuration, axis).
  *   window key  = ((b*nWx + (x+sx)/L)*nWy + (y+sy)/W)*nWz + (z+sz)/H, nW* = ceil((grid+shift)/win)
  *   per window with N voxels: S = ceil(N/tau) sets (Eq. 2); slot k of its j-th set holds the
@@ -64,34 +80,26 @@ int dsvt_partition_bound(const dsvt_part_cfg* cfg, int32_t n_voxels, int32_t* ma
  * voxel_slot [device] int32 [n_voxels]     out: smallest flat slot s*tau+k that holds the voxel
  * n_sets     [device] int32 scalar         out: total number of sets
  * set_win    [device] int32 [max_sets]     out: window key of every set; may be NULL
- * tile_first [device] int32 [max_tiles+1]  out: work list for the layer kernels (see dsvt_maps): sets
- *                                               tile_first[t] .. tile_first[t+1]-1 form tile t; may be NULL
- * n_tiles    [device] int32 scalar         out: number of tiles; NULL iff tile_first is NULL
- * tile_order [device] int32 [max_tiles]    out: tile indices in launch order (most rows first); may be NULL
+ * tiles      [host]   work list to fill (see dsvt_tile_list); may be NULL
  * ws         [device] scratch of at least the bytes dsvt_partition_bound reports
  * status     [device] int32 word, OR-ed with DSVT_ST_* bits (the caller zeroes it)
  * Errors: DSVT_EINVAL (NULL pointer, non-positive size, shift outside [0,win), axis not 0/1,
- * key space of 2^31 or more cells), DSVT_ENOSPC (ws_bytes too small), DSVT_EUNSUPPORTED (a tile
- * list asked for with tau > 48), DSVT_EHIP. */
+ * key space of 2^31 or more cells), DSVT_ENOSPC (ws_bytes too small), DSVT_EUNSUPPORTED (a work
+ * list asked for outside its limits), DSVT_EHIP. */
 int dsvt_partition(const dsvt_part_cfg* cfg, const int32_t* coords, int32_t n_voxels,
                    int32_t* set_inds, int32_t* voxel_slot, int32_t* n_sets, int32_t max_sets,
-                   int32_t* set_win, int32_t* tile_first, int32_t* n_tiles, int32_t* tile_order, int32_t max_tiles,
+                   int32_t* set_win, const dsvt_tile_list* tiles,
                    void* ws, size_t ws_bytes, int32_t* status, void* stream);
 
 /* The maps one layer consumes (outputs of dsvt_partition, all [device]). */
 typedef struct {
   int32_t n_voxels, max_sets, tau;
   const int32_t* set_inds;   /* [max_sets,tau]                                          */
-  const int32_t* voxel_slot; /* [n_voxels]; the attention kernels re-derive the first-occurrence
-                                rule from set_inds on chip and do not read it: may be NULL */
+  const int32_t* voxel_slot; /* [n_voxels]; not read by the layer kernels: may be NULL   */
   const int32_t* n_sets;     /* scalar, <= max_sets                                     */
-  /* Optional work list from dsvt_partition (both NULL or both set): tile t covers the sets
-   * tile_first[t] .. tile_first[t+1]-1, whose distinct voxels fit one 96-row workgroup tile.
-   * Without it a workgroup takes two consecutive sets. */
-  int32_t max_tiles;         /* rows of tile_first minus one                            */
-  const int32_t* tile_first; /* [max_tiles+1]                                           */
-  const int32_t* n_tiles;    /* scalar, <= max_tiles                                    */
-  const int32_t* tile_order; /* [max_tiles] workgroup b takes tile tile_order[b]; NULL = tile b */
+  dsvt_tile_list tiles;      /* the work list of the same dsvt_partition call, or all-NULL: the
+                                kernels then take two sets per workgroup and derive the rows
+                                from set_inds and coords on chip                         */
 } dsvt_maps;
 
 /* ---------------------------------------------------------------------------------------

@@ -26,10 +26,14 @@ class PartCfg(C.Structure):
                 ("axis", C.c_int32)]
 
 
+class TileList(C.Structure):
+    _fields_ = [("max_tiles", C.c_int32), ("tile_first", C.c_void_p), ("n_tiles", C.c_void_p),
+                ("tile_order", C.c_void_p), ("tile_desc", C.c_void_p)]
+
+
 class Maps(C.Structure):
     _fields_ = [("n_voxels", C.c_int32), ("max_sets", C.c_int32), ("tau", C.c_int32), ("set_inds", C.c_void_p),
-                ("voxel_slot", C.c_void_p), ("n_sets", C.c_void_p), ("max_tiles", C.c_int32),
-                ("tile_first", C.c_void_p), ("n_tiles", C.c_void_p), ("tile_order", C.c_void_p)]
+                ("voxel_slot", C.c_void_p), ("n_sets", C.c_void_p), ("tiles", TileList)]
 
 
 class LayerW(C.Structure):
@@ -62,7 +66,7 @@ def lib():
         L = C.CDLL(LIB_PATH)
         vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
         L.dsvt_partition_bound.argtypes = [C.POINTER(PartCfg), i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(sz)]
-        L.dsvt_partition.argtypes = [C.POINTER(PartCfg), vp, i32, vp, vp, vp, i32, vp, vp, vp, vp, i32, vp, sz, vp, vp]
+        L.dsvt_partition.argtypes = [C.POINTER(PartCfg), vp, i32, vp, vp, vp, i32, vp, C.POINTER(TileList), vp, sz, vp, vp]
         L.dsvt_layer_packed_size.argtypes = [C.POINTER(LayerW), C.POINTER(sz)]
         L.dsvt_layer_pack.argtypes = [C.POINTER(LayerW), vp, sz, vp]
         L.dsvt_block_workspace_size.argtypes = [C.POINTER(LayerW), i32, C.POINTER(sz)]
@@ -130,14 +134,18 @@ class SetMaps:
         self.status = torch.zeros((1,), **i32)
         self.ws = torch.empty((ws_bytes,), dtype=torch.uint8, device="cuda")
         self.max_tiles = tile_bound if (tiles and tile_bound > 0 and cfg.tau <= 48) else 0
-        self.tile_first = torch.full((self.max_tiles + 1,), -1, **i32) if self.max_tiles else None
-        self.n_tiles = torch.zeros((1,), **i32) if self.max_tiles else None
-        self.tile_order = torch.full((self.max_tiles,), -1, **i32) if self.max_tiles else None
+        if self.max_tiles:
+            self.tile_first = torch.full((self.max_tiles + 1,), -1, **i32)
+            self.n_tiles = torch.zeros((1,), **i32)
+            self.tile_order = torch.full((self.max_tiles,), -1, **i32)
+            self.tile_desc = torch.full((self.max_tiles, 256), -1, **i32)
+            self.tile_list = TileList(self.max_tiles, self.tile_first.data_ptr(), self.n_tiles.data_ptr(),
+                                      self.tile_order.data_ptr(), self.tile_desc.data_ptr())
+        else:
+            self.tile_first = self.n_tiles = self.tile_order = self.tile_desc = None
+            self.tile_list = TileList(0, None, None, None, None)
         self.struct = Maps(n_voxels, self.max_sets, cfg.tau, self.set_inds.data_ptr(), self.voxel_slot.data_ptr(),
-                           self.n_sets.data_ptr(), self.max_tiles,
-                           self.tile_first.data_ptr() if self.max_tiles else None,
-                           self.n_tiles.data_ptr() if self.max_tiles else None,
-                           self.tile_order.data_ptr() if self.max_tiles else None)
+                           self.n_sets.data_ptr(), self.tile_list)
 
 
 def dsvt_partition(cfg, coords, out=None, stream=None):
@@ -147,8 +155,8 @@ def dsvt_partition(cfg, coords, out=None, stream=None):
     out = SetMaps(cfg, n) if out is None else out
     assert out.n_voxels == n
     rc = lib().dsvt_partition(C.byref(cfg), _ptr(coords), n, _ptr(out.set_inds), _ptr(out.voxel_slot),
-                              _ptr(out.n_sets), out.max_sets, _ptr(out.set_win), _ptr(out.tile_first),
-                              _ptr(out.n_tiles), _ptr(out.tile_order), out.max_tiles, _ptr(out.ws), out.ws.numel(),
+                              _ptr(out.n_sets), out.max_sets, _ptr(out.set_win),
+                              C.byref(out.tile_list) if out.max_tiles else None, _ptr(out.ws), out.ws.numel(),
                               _ptr(out.status),
                               _stream(stream))
     _check("dsvt_partition", rc)

@@ -1,11 +1,12 @@
 // dsvt_set_attention / dsvt_block: one DSVT layer per kernel launch on gfx950 (Sec. 3.2 Eq. 4-5;
 // appendix "Network Architecture").
 //
-// k_layer: a workgroup owns a run of consecutive sets (a "tile" of at most 96 rows).  It reads
-// their slot rows of set_inds, keeps the first occurrence of every voxel (repeats are adjacent,
-// Eq. 3 is monotone), and gathers those voxels' features into an LDS tile -- the tau x C tiles of
-// Eq. (4) with the repeated rows squeezed out, since a masked repeat contributes nothing as a key
-// and its query row would be thrown away.  Q/K/V projection, per-(set, head) softmax(QK^T + PE)V,
+// k_layer: a workgroup owns a run of consecutive sets (a "tile" of at most 96 rows).  It takes the
+// sets' distinct voxels -- from the tile descriptor the partition wrote, or, without a work list, by
+// keeping the first occurrence of every voxel in the sets' slot rows (repeats are adjacent, Eq. 3 is
+// monotone) -- and gathers those voxels' features into an LDS tile: the tau x C tiles of Eq. (4)
+// with the repeated rows squeezed out, since a masked repeat contributes nothing as a key and its
+// query row would be thrown away.  Q/K/V projection, per-(set, head) softmax(QK^T + PE)V,
 // output projection, residual + LayerNorm, the MLP and the second residual + LayerNorm all run
 // on that tile in LDS and registers; the rows then go straight back to the voxels' rows of the
 // output (every voxel is in exactly one set, Thm A.2-A.3), so a layer reads and writes [N, C] once.
@@ -41,7 +42,7 @@ long long* g_phase_clocks = nullptr;
 #endif
 
 struct MapsDev {
-  const int32_t *set_inds, *n_sets, *tile_first, *n_tiles, *tile_order;
+  const int32_t *set_inds, *n_sets, *n_tiles, *tile_desc;
   int32_t max_sets, tau, n_voxels;
 };
 
@@ -243,71 +244,84 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
   GemmPhase<T, NT_QKV, C, 3 * C, NW, 2, false> qkv(reinterpret_cast<const T*>(p.w_qkv), wave);
   qkv.prefetch();
 
-  int n_sets = *mp.n_sets;
-  n_sets = n_sets < mp.max_sets ? n_sets : mp.max_sets;
-  int s_begin, s_end;
-  if (mp.tile_first != nullptr) {
+  int ns;
+  if (mp.tile_desc != nullptr) {
+    // ---- 1a. rows from the tile descriptor the partition wrote for this workgroup (1 KB, one load)
     const int n_tiles = *mp.n_tiles;
+    const int word = tid < 256 ? mp.tile_desc[(size_t)blockIdx.x * 256 + tid] : 0;
     if ((int)blockIdx.x >= n_tiles) return;
-    int t = mp.tile_order ? mp.tile_order[blockIdx.x] : (int)blockIdx.x;
-    t = t < 0 ? 0 : (t >= n_tiles ? n_tiles - 1 : t);
-    s_begin = mp.tile_first[t];
-    s_end = mp.tile_first[t + 1];
+    for (int r = kRowsMax + tid; r < kRowsPad; r += NTHREADS) { row_vox[r] = -1; row_lin[r] = 0; row_mult[r] = 0.f; }
+    if (wave == 0) {
+      int hdr_ns = __shfl(word, 1, 64), hdr_rows = __shfl(word, 0, 64);
+      hdr_ns = hdr_ns < 0 ? 0 : (hdr_ns > kMaxSets ? kMaxSets : hdr_ns);
+      hdr_rows = hdr_rows < 0 ? 0 : (hdr_rows > kRowsMax ? kRowsMax : hdr_rows);
+      if (lane == 0) { set_nu[kMaxSets] = hdr_ns; set_r0[hdr_ns] = hdr_rows; }
+      if (lane >= 2 && lane < 2 + kMaxSets && lane - 2 < hdr_ns) set_r0[lane - 2] = word < 0 ? 0 : (word > kRowsMax - 4 ? kRowsMax - 4 : word);
+      if (lane >= 2 + kMaxSets && lane < 2 + 2 * kMaxSets) set_nu[lane - 2 - kMaxSets] = word < 1 ? 1 : (word > kTauMax ? kTauMax : word);
+    } else if (tid >= 64 && tid < 64 + kRowsMax) {
+      row_vox[tid - 64] = (word >= 0 && word < mp.n_voxels) ? word : -1;
+    } else if (tid >= 160 && tid < 160 + kRowsMax) {
+      row_lin[tid - 160] = word & 0xFFFFFF;
+      row_mult[tid - 160] = (float)((unsigned)word >> 24);
+    }
+    __syncthreads();
+    ns = set_nu[kMaxSets];
+    if (ns <= 0) return;
+    if (tid == 0) {
+      int n = 0;                                 // attention items: (set, query tile, half of the heads)
+      for (int s = 0; s < ns; ++s) {
+        const int kts = (set_nu[s] + 15) >> 4;
+        for (int qt = 0; qt < kts; ++qt)
+          for (int hh = 0; hh < 2; ++hh) items[n++] = s | (qt << 8) | (hh << 12) | (kts << 16);
+      }
+      items[kMaxItems] = n;                      // published by the barrier after the gather
+    }
   } else {
-    s_begin = blockIdx.x * kFixedSets;
-    s_end = s_begin + kFixedSets;
-  }
-  s_end = s_end < n_sets ? s_end : n_sets;
-  int ns = s_end - s_begin;
-  if (ns <= 0 || s_begin < 0) return;
-  ns = ns < kMaxSets ? ns : kMaxSets;
-  const int tau = mp.tau;
-
-  // ---- 1. slots -> compact rows (first occurrences only; each set starts on a multiple of 4 rows)
-  for (int r = tid; r < kRowsPad; r += NTHREADS) { row_vox[r] = -1; row_lin[r] = 0; row_mult[r] = 0.f; }
-  for (int ls = wave; ls < ns; ls += NW) {
-    const int v = lane < tau ? mp.set_inds[(size_t)(s_begin + ls) * tau + lane] : -2;
-    const int prev = __shfl_up(v, 1, 64);
-    const bool first = lane < tau && (lane == 0 || v != prev);
-    const unsigned long long mask = __ballot(first);
-    if (lane == 0) set_nu[ls] = __popcll(mask);
-  }
-  __syncthreads();
-  if (tid == 0) {
-    int r = 0, keep = 0;
-    for (int s = 0; s < ns; ++s) {
-      const int padded = (set_nu[s] + 3) & ~3;
-      if (r + padded > kRowsMax) break;          // cannot happen with a tile list built for 96 rows
-      set_r0[s] = r; r += padded; keep = s + 1;
+    // ---- 1b. no work list: two sets per workgroup, rows derived from set_inds and coords
+    int n_sets = *mp.n_sets;
+    n_sets = n_sets < mp.max_sets ? n_sets : mp.max_sets;
+    const int s_begin = blockIdx.x * kFixedSets;
+    ns = (n_sets - s_begin) < kFixedSets ? (n_sets - s_begin) : kFixedSets;
+    if (ns <= 0) return;
+    const int tau = mp.tau;
+    for (int r = tid; r < kRowsPad; r += NTHREADS) { row_vox[r] = -1; row_lin[r] = 0; row_mult[r] = 0.f; }
+    for (int ls = wave; ls < ns; ls += NW) {
+      const int v = lane < tau ? mp.set_inds[(size_t)(s_begin + ls) * tau + lane] : -2;
+      const int prev = __shfl_up(v, 1, 64);
+      const bool first = lane < tau && (lane == 0 || v != prev);   // repeats are adjacent
+      const unsigned long long mask = __ballot(first);
+      if (lane == 0) set_nu[ls] = __popcll(mask);
     }
-    set_r0[keep] = r;
-    set_nu[kMaxSets] = keep;
-    int n = 0;                                   // attention items: (set, query tile, half of the heads)
-    for (int s = 0; s < keep; ++s) {
-      const int kts = (set_nu[s] + 15) >> 4;
-      for (int qt = 0; qt < kts; ++qt)
-        for (int hh = 0; hh < 2; ++hh) items[n++] = s | (qt << 8) | (hh << 12) | (kts << 16);
+    __syncthreads();
+    if (tid == 0) {
+      int r = 0, n = 0;
+      for (int s = 0; s < ns; ++s) {             // each set starts on a multiple of 4 rows
+        set_r0[s] = r; r += (set_nu[s] + 3) & ~3;
+        const int kts = (set_nu[s] + 15) >> 4;
+        for (int qt = 0; qt < kts; ++qt)
+          for (int hh = 0; hh < 2; ++hh) items[n++] = s | (qt << 8) | (hh << 12) | (kts << 16);
+      }
+      set_r0[ns] = r;
+      items[kMaxItems] = n;
     }
-    items[kMaxItems] = n;
-  }
-  __syncthreads();
-  ns = set_nu[kMaxSets];
-  for (int ls = wave; ls < ns; ls += NW) {
-    const int v = lane < tau ? mp.set_inds[(size_t)(s_begin + ls) * tau + lane] : -2;
-    const int prev = __shfl_up(v, 1, 64);
-    const bool first = lane < tau && (lane == 0 || v != prev);
-    const unsigned long long mask = __ballot(first);
-    if (first && v >= 0 && v < mp.n_voxels) {
-      const int r = set_r0[ls] + __popcll(mask & ((1ull << lane) - 1ull));
-      const unsigned long long later = mask >> (lane + 1);
-      const int run = later ? (__ffsll((long long)later)) : (tau - lane);   // slots holding this voxel
-      const int4 c = coords[v];
-      row_vox[r] = v;
-      row_mult[r] = (float)run;
-      row_lin[r] = (c.y * p.rel_my + c.z) * p.rel_mz + c.w;
+    __syncthreads();
+    for (int ls = wave; ls < ns; ls += NW) {
+      const int v = lane < tau ? mp.set_inds[(size_t)(s_begin + ls) * tau + lane] : -2;
+      const int prev = __shfl_up(v, 1, 64);
+      const bool first = lane < tau && (lane == 0 || v != prev);
+      const unsigned long long mask = __ballot(first);
+      if (first && v >= 0 && v < mp.n_voxels) {
+        const int r = set_r0[ls] + __popcll(mask & ((1ull << lane) - 1ull));
+        const unsigned long long later = mask >> (lane + 1);
+        const int run = later ? (__ffsll((long long)later)) : (tau - lane);   // slots holding this voxel
+        const int4 c = coords[v];
+        row_vox[r] = v;
+        row_mult[r] = (float)run;
+        row_lin[r] = (c.y * p.rel_my + c.z) * p.rel_mz + c.w;
+      }
     }
+    __syncthreads();
   }
-  __syncthreads();
   const int R = set_r0[ns];
   const int RT = (R + 15) >> 4;
   const int RTK = ((RT + 1) >> 1) << 1;          // the LayerNorm phases run on an even number of row tiles
@@ -524,8 +538,10 @@ int check_layer(const dsvt_layer_w& w, bool need_mlp, bool need_packed = true) {
 int check_maps(const dsvt_maps& mp) {
   if (!mp.set_inds || !mp.n_sets || mp.n_voxels <= 0 || mp.max_sets <= 0 || mp.tau <= 0) return DSVT_EINVAL;
   if (mp.tau > kTauMax) return DSVT_EUNSUPPORTED;
-  if ((mp.tile_first != nullptr) != (mp.n_tiles != nullptr)) return DSVT_EINVAL;
-  if (mp.tile_first != nullptr && mp.max_tiles <= 0) return DSVT_EINVAL;
+  const dsvt_tile_list& tl = mp.tiles;
+  const bool any = tl.tile_first || tl.n_tiles || tl.tile_order || tl.tile_desc;
+  const bool all = tl.tile_first && tl.n_tiles && tl.tile_order && tl.tile_desc;
+  if (any && (!all || tl.max_tiles <= 0)) return DSVT_EINVAL;
   return DSVT_OK;
 }
 
@@ -543,9 +559,9 @@ int launch_layer(const dsvt_layer_w& w, const dsvt_maps& mp, const int32_t* coor
   static int prepared = allow_lds(kern, lds);
   if (prepared != DSVT_OK) return prepared;
   MapsDev md;
-  md.set_inds = mp.set_inds; md.n_sets = mp.n_sets; md.tile_first = mp.tile_first; md.n_tiles = mp.n_tiles; md.tile_order = mp.tile_first ? mp.tile_order : nullptr;
+  md.set_inds = mp.set_inds; md.n_sets = mp.n_sets; md.n_tiles = mp.tiles.n_tiles; md.tile_desc = mp.tiles.tile_desc;
   md.max_sets = mp.max_sets; md.tau = mp.tau; md.n_voxels = mp.n_voxels;
-  const unsigned grid = mp.tile_first ? (unsigned)mp.max_tiles : (unsigned)dsvt_ceil_div(mp.max_sets, kFixedSets);
+  const unsigned grid = mp.tiles.tile_desc ? (unsigned)mp.tiles.max_tiles : (unsigned)dsvt_ceil_div(mp.max_sets, kFixedSets);
   dsvt_prof_scope ps(DSVT_K_LAYER, st);
   kern<<<grid, kLayerWaves * 64, lds, st>>>(to_dev(w), md, reinterpret_cast<const int4*>(coords),
                                        reinterpret_cast<const T*>(x), reinterpret_cast<T*>(out), full);

@@ -20,9 +20,10 @@ struct PartGeom {
   int32_t n_windows;       // batch * nw[0] * nw[1] * nw[2]
 };
 
-__global__ void k_clear(uint32_t* __restrict__ words, int64_t n) {
+__global__ void k_clear(uint32_t* __restrict__ words, int64_t n, int32_t* __restrict__ desc, int64_t n_desc) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) words[i] = 0u;
+  if (i < n_desc) desc[i] = -1;
 }
 
 // One thread per voxel: composite key = window key * (32*words_per_win) + inner key; set its bit.
@@ -79,7 +80,8 @@ __global__ void k_window_count(const uint32_t* __restrict__ bitmap, uint32_t* __
 __global__ void __launch_bounds__(1024) k_scan_windows(const int32_t* __restrict__ win_count,
                                                        int32_t* __restrict__ win_soff, int32_t n_windows,
                                                        int32_t tau, int32_t max_sets, int32_t* __restrict__ n_sets,
-                                                       int32_t* __restrict__ status) {
+                                                       int32_t* __restrict__ status, int32_t* __restrict__ set_w,
+                                                       int32_t set_cap) {
   __shared__ int32_t wave_tot[16];
   __shared__ int32_t carry_s;
   const int32_t tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
@@ -98,7 +100,11 @@ __global__ void __launch_bounds__(1024) k_scan_windows(const int32_t* __restrict
     __syncthreads();
     int32_t before = carry_s;
     for (int32_t k = 0; k < wv; ++k) before += wave_tot[k];
-    if (w < n_windows) win_soff[w] = before + incl - s;
+    if (w < n_windows) {
+      win_soff[w] = before + incl - s;
+      for (int32_t j = 0; j < s; ++j)                       // window of each of its sets, for k_tiles
+        if (before + incl - s + j < set_cap) set_w[before + incl - s + j] = w;
+    }
     __syncthreads();
     if (tid == 1023) carry_s = before + incl;
     __syncthreads();
@@ -109,67 +115,56 @@ __global__ void __launch_bounds__(1024) k_scan_windows(const int32_t* __restrict
   }
 }
 
-// One thread per voxel: rank d inside its window, then the slots t with floor(t*N/(S*tau)) == d.
-__global__ void k_emit(const uint32_t* __restrict__ keys, int32_t n, const uint32_t* __restrict__ bitmap,
-                       const uint32_t* __restrict__ word_prefix, const int32_t* __restrict__ win_count,
-                       const int32_t* __restrict__ win_soff, int32_t words_per_win, int32_t tau, int32_t max_sets,
-                       int32_t* __restrict__ set_inds, int32_t* __restrict__ voxel_slot,
-                       int32_t* __restrict__ set_win) {
-  int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= n) return;
-  uint32_t key = keys[i];
-  if (key == kBadKey) { voxel_slot[i] = -1; return; }
-  uint32_t word = key >> 5, bit = key & 31u;
-  int32_t w = (int32_t)(word / (uint32_t)words_per_win);
-  int64_t d = word_prefix[word] + (uint32_t)__popc(bitmap[word] & ((1u << bit) - 1u));
-  int64_t N = win_count[w];
-  int64_t S = (N + tau - 1) / tau, T = S * tau;
-  int64_t t_lo = (d * T + N - 1) / N, t_hi = ((d + 1) * T + N - 1) / N;
-  int64_t base = (int64_t)win_soff[w] * tau, cap = (int64_t)max_sets * tau;
-  voxel_slot[i] = (int32_t)(base + t_lo);
-  for (int64_t t = t_lo; t < t_hi; ++t) {
-    int64_t slot = base + t;
-    if (slot >= cap) break;
-    set_inds[slot] = i;
-    if (t % tau == 0) set_win[slot / tau] = w;
-  }
-}
+// Tile descriptor, one per workgroup tile of the layer kernels, in launch order (256 ints):
+//   [0] rows R (sets padded to multiples of 4)   [1] sets ns
+//   [2 + s] first row of set s                    [2 + 24 + s] distinct voxels of set s   (s < ns <= 24)
+//   [64 + r] voxel of row r, -1 for padding rows  [160 + r] (multiplicity << 24) | position code of row r
+constexpr int kDescInts = 256, kDescSets = 24, kDescR0 = 2, kDescNu = 2 + kDescSets, kDescVox = 64, kDescLin = 160;
+constexpr int kTileRows = 96;
 
-
-// Rows a set occupies in a layer workgroup's tile: its distinct voxels (closed form from Eq. 3),
-// rounded up to a multiple of 4.
-__device__ __forceinline__ int32_t padded_rows(int32_t s, const int32_t* __restrict__ set_win,
-                                               const int32_t* __restrict__ win_count,
-                                               const int32_t* __restrict__ win_soff, int32_t tau,
-                                               int32_t n_windows) {
-  const int32_t w = set_win[s];
-  if (w < 0 || w >= n_windows || win_count[w] <= 0) return 4;   // only reachable after a reported input error
-  const int64_t N = win_count[w], S = (N + tau - 1) / tau, j = s - win_soff[w];
+// Distinct voxels of the j-th set of a window with N voxels in S sets (closed form from Eq. 3).
+__device__ __forceinline__ int32_t set_distinct(int64_t N, int64_t S, int64_t j, int64_t tau) {
   const int64_t lo = (j * tau * N) / (S * tau), hi = ((j * tau + tau - 1) * N) / (S * tau);
-  return (int32_t)((hi - lo + 1 + 3) & ~3ll);
+  return (int32_t)(hi - lo + 1);
 }
 
-// One workgroup: cut the set sequence into tiles for the layer kernels.  With P(s) the running
-// sum of padded rows before set s, set s goes to tile P(s) / rows_per_cut; a tile then holds at
-// most rows_per_cut - 4 + pad4(tau) rows and no tile is empty.
-__global__ void __launch_bounds__(1024) k_tiles(const int32_t* __restrict__ set_win,
-                                                const int32_t* __restrict__ win_count,
+struct TileOut {                       // all null when the caller wants no work list
+  int32_t *tile_first, *n_tiles, *tile_order, *tile_desc;
+  int32_t max_tiles;
+};
+
+// One workgroup: cut the set sequence into tiles for the layer kernels, order the tiles for launch
+// and write the descriptor headers.  With P(s) the running sum of padded rows before set s, set s
+// goes to tile P(s) / rows_per_cut; a tile then holds at most rows_per_cut - 4 + pad4(tau) rows and
+// no tile is empty.  set_loc[s] = (descriptor slot << 7) | first row, for k_emit.
+__global__ void __launch_bounds__(1024) k_tiles(const int32_t* __restrict__ set_w, const int32_t* __restrict__ win_count,
                                                 const int32_t* __restrict__ win_soff, const int32_t* __restrict__ n_sets_ptr,
                                                 int32_t set_cap, int32_t tau, int32_t n_windows, int32_t rows_per_cut,
-                                                int32_t* __restrict__ tile_first, int32_t* __restrict__ n_tiles,
-                                                int32_t max_tiles, int32_t* __restrict__ tile_rows,
-                                                int32_t* __restrict__ tile_order) {
+                                                TileOut out, int32_t* __restrict__ tile_rows, int32_t* __restrict__ tile_pos,
+                                                int32_t* __restrict__ set_p, int32_t* __restrict__ set_loc) {
   __shared__ int32_t wave_tot[16];
   __shared__ int32_t carry_s;
   __shared__ int32_t hist[32], running[32], wave_cnt[16][32];
   const int32_t tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   int32_t n_sets = *n_sets_ptr;
   n_sets = n_sets < set_cap ? n_sets : set_cap;
+  if (n_sets <= 0) {
+    if (tid == 0) { *out.n_tiles = 0; out.tile_first[0] = 0; }
+    return;
+  }
   if (tid == 0) carry_s = 0;
   __syncthreads();
+  // pass 1: padded rows per set, their running sum, the tile of every set
   for (int32_t base = 0; base < n_sets; base += 1024) {
     const int32_t s = base + tid;
-    const int32_t rows = s < n_sets ? padded_rows(s, set_win, win_count, win_soff, tau, n_windows) : 0;
+    int32_t rows = 0;
+    if (s < n_sets) {
+      int32_t w = set_w[s];
+      w = w < 0 ? 0 : (w >= n_windows ? n_windows - 1 : w);
+      const int64_t N = win_count[w] > 0 ? win_count[w] : 1, S = (N + tau - 1) / tau;
+      rows = (set_distinct(N, S, s - win_soff[w], tau) + 3) & ~3;
+      rows = rows > kTileRows ? kTileRows : (rows < 4 ? 4 : rows);
+    }
     int32_t incl = rows;
     for (int32_t d = 1; d < 64; d <<= 1) {
       int32_t up = __shfl_up(incl, d, 64);
@@ -181,30 +176,33 @@ __global__ void __launch_bounds__(1024) k_tiles(const int32_t* __restrict__ set_
     for (int32_t k = 0; k < wv; ++k) before += wave_tot[k];
     const int32_t P = before + incl - rows;                 // rows before set s
     if (s < n_sets) {
-      const int32_t tile = P / rows_per_cut;
-      bool first = s == 0;
-      if (!first) first = (P - padded_rows(s - 1, set_win, win_count, win_soff, tau, n_windows)) / rows_per_cut != tile;
-      if (first && tile < max_tiles) { tile_first[tile] = s; tile_rows[tile] = P; }
-      if (s == n_sets - 1) {
-        const int32_t nt = tile + 1 < max_tiles ? tile + 1 : max_tiles;
-        *n_tiles = nt;
-        tile_first[nt] = n_sets;
-        tile_rows[nt] = P + rows;
-      }
+      set_p[s] = P;
+      set_loc[s] = -1;                                      // set in pass 4
+      if (s == n_sets - 1) set_p[n_sets] = P + rows;
     }
     __syncthreads();
     if (tid == 1023) carry_s = before + incl;
     __syncthreads();
   }
-  if (n_sets <= 0) {
-    if (tid == 0) { *n_tiles = 0; tile_first[0] = 0; }
-    return;
+  // pass 2: tile boundaries (a set starts a tile when its predecessor is in another one)
+  for (int32_t base = 0; base < n_sets; base += 1024) {
+    const int32_t s = base + tid;
+    if (s < n_sets) {
+      const int32_t tile = set_p[s] / rows_per_cut;
+      const bool first = s == 0 || set_p[s - 1] / rows_per_cut != tile;
+      if (first && tile < out.max_tiles) { out.tile_first[tile] = s; tile_rows[tile] = set_p[s]; }
+      if (s == n_sets - 1) {
+        const int32_t nt = tile + 1 < out.max_tiles ? tile + 1 : out.max_tiles;
+        *out.n_tiles = nt;
+        out.tile_first[nt] = n_sets;
+        tile_rows[nt] = set_p[n_sets];
+      }
+    }
   }
-  if (tile_order == nullptr) return;
-  // Launch order: tiles with more rows first (a stable counting sort on rows / 4), so that the
-  // short tiles fill the tail of the launch.  tile_rows[t] holds the rows before tile t.
   __syncthreads();
-  const int32_t nt = *n_tiles;
+  // pass 3: launch order = tiles with more rows first (a stable counting sort on rows / 4), so
+  // that the short tiles fill the tail of the launch
+  const int32_t nt = *out.n_tiles;
   if (tid < 32) hist[tid] = 0;
   __syncthreads();
   for (int32_t base = 0; base < nt; base += 1024) {
@@ -226,8 +224,7 @@ __global__ void __launch_bounds__(1024) k_tiles(const int32_t* __restrict__ set_
       b = b < 0 ? 0 : (b > 31 ? 31 : b);
     }
     for (int32_t k = lane; k < 32; k += 64) wave_cnt[wv][k] = 0;
-    // rank among this wavefront's lanes of the same bucket, in lane order
-    int32_t rank = 0;
+    int32_t rank = 0;                                       // among this wavefront's lanes of the same bucket
     unsigned long long todo = __ballot(b >= 0);
     while (todo) {
       const int32_t leader = __ffsll((long long)todo) - 1;
@@ -241,17 +238,83 @@ __global__ void __launch_bounds__(1024) k_tiles(const int32_t* __restrict__ set_
     if (b >= 0) {
       int32_t pos = running[b] + rank;
       for (int32_t k = 0; k < wv; ++k) pos += wave_cnt[k][b];
-      tile_order[pos] = t;
+      out.tile_order[pos] = t;
+      tile_pos[t] = pos;
+      int32_t* d = out.tile_desc + (int64_t)pos * kDescInts;    // descriptor header of launch slot pos
+      d[0] = tile_rows[t + 1] - tile_rows[t];
+      d[1] = out.tile_first[t + 1] - out.tile_first[t];
     }
     __syncthreads();
     if (tid < 32) { int32_t add = 0; for (int32_t k = 0; k < 16; ++k) add += wave_cnt[k][tid]; running[tid] += add; }
     __syncthreads();
   }
+  // pass 4: per set, its descriptor slot, first row and distinct count
+  for (int32_t base = 0; base < n_sets; base += 1024) {
+    const int32_t s = base + tid;
+    if (s < n_sets) {
+      const int32_t t = set_p[s] / rows_per_cut;
+      if (t < nt) {
+        const int32_t pos = tile_pos[t], ls = s - out.tile_first[t], r0 = set_p[s] - tile_rows[t];
+        int32_t w = set_w[s];
+        w = w < 0 ? 0 : (w >= n_windows ? n_windows - 1 : w);
+        const int64_t N = win_count[w] > 0 ? win_count[w] : 1, S = (N + tau - 1) / tau;
+        if (ls >= 0 && ls < kDescSets && r0 >= 0 && r0 <= kTileRows - 4) {
+          int32_t* d = out.tile_desc + (int64_t)pos * kDescInts;
+          d[kDescR0 + ls] = r0;
+          d[kDescNu + ls] = set_distinct(N, S, s - win_soff[w], tau);
+          set_loc[s] = (pos << 7) | r0;
+        }
+      }
+    }
+  }
+}
+
+// One thread per voxel: rank d inside its window, then the slots t with floor(t*N/(S*tau)) == d;
+// with a work list also the voxel's row of its tile descriptor.
+__global__ void k_emit(PartGeom g, const int4* __restrict__ coords, const uint32_t* __restrict__ keys, int32_t n,
+                       const uint32_t* __restrict__ bitmap, const uint32_t* __restrict__ word_prefix,
+                       const int32_t* __restrict__ win_count, const int32_t* __restrict__ win_soff, int32_t max_sets,
+                       int32_t* __restrict__ set_inds, int32_t* __restrict__ voxel_slot, int32_t* __restrict__ set_win,
+                       const int32_t* __restrict__ set_loc, int32_t* __restrict__ tile_desc, int32_t n_desc_slots) {
+  int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  uint32_t key = keys[i];
+  if (key == kBadKey) { voxel_slot[i] = -1; return; }
+  const int32_t tau = g.tau;
+  uint32_t word = key >> 5, bit = key & 31u;
+  int32_t w = (int32_t)(word / (uint32_t)g.words_per_win);
+  int64_t d = word_prefix[word] + (uint32_t)__popc(bitmap[word] & ((1u << bit) - 1u));
+  int64_t N = win_count[w];
+  int64_t S = (N + tau - 1) / tau, T = S * tau;
+  int64_t t_lo = (d * T + N - 1) / N, t_hi = ((d + 1) * T + N - 1) / N;
+  int64_t base = (int64_t)win_soff[w] * tau, cap = (int64_t)max_sets * tau;
+  voxel_slot[i] = (int32_t)(base + t_lo);
+  for (int64_t t = t_lo; t < t_hi; ++t) {
+    int64_t slot = base + t;
+    if (slot >= cap) break;
+    set_inds[slot] = i;
+    if (t % tau == 0) set_win[slot / tau] = w;
+  }
+  if (tile_desc != nullptr) {
+    const int64_t j = t_lo / tau, s = win_soff[w] + j;
+    if (s < max_sets) {
+      const int32_t loc = set_loc[s];
+      const int32_t slot = loc >> 7, row = (loc & 127) + (int32_t)(d - (j * tau * N) / T);
+      if (slot >= 0 && slot < n_desc_slots && row < kTileRows) {
+        const int4 c = coords[i];
+        const int32_t lin = (c.y * (2 * g.win[1] - 1) + c.z) * (2 * g.win[2] - 1) + c.w;
+        int32_t* dd = tile_desc + (int64_t)slot * kDescInts;
+        dd[kDescVox + row] = i;
+        dd[kDescLin + row] = (int32_t)((uint32_t)lin | ((uint32_t)(t_hi - t_lo) << 24));
+      }
+    }
+  }
 }
 
 struct PartPlan {
   PartGeom g;
-  size_t off_bitmap, off_prefix, off_count, off_soff, off_keys, off_setwin, off_tilerows, total;
+  size_t off_bitmap, off_prefix, off_count, off_soff, off_keys, off_setwin, off_tilerows, off_tilepos, off_setp, off_setloc, total;
+  bool desc_ok;
   int64_t n_words;
   int32_t set_bound, tile_bound, rows_per_cut;
 };
@@ -290,6 +353,12 @@ int make_plan(const dsvt_part_cfg* cfg, int32_t n_voxels, PartPlan* p) {
   p->rows_per_cut = (int32_t)(100 - pad_tau);
   p->tile_bound = p->rows_per_cut > 0 ? (int32_t)((n_voxels + 3 * bound) / p->rows_per_cut + 1) : 0;
   p->off_tilerows = o; o = dsvt_align_up(o + (size_t)(p->tile_bound + 1) * 4, 256);
+  p->off_tilepos = o;  o = dsvt_align_up(o + (size_t)(p->tile_bound + 1) * 4, 256);
+  p->off_setp = o;     o = dsvt_align_up(o + (size_t)(bound + 1) * 4, 256);
+  p->off_setloc = o;   o = dsvt_align_up(o + (size_t)(bound + 1) * 4, 256);
+  // a descriptor packs (slot << 7 | row) and (multiplicity << 24 | position code) into 32 bits
+  p->desc_ok = p->rows_per_cut >= 48 && p->tile_bound < (1 << 23) &&
+               (int64_t)cfg->grid[0] * (2 * cfg->win[1] - 1) * (2 * cfg->win[2] - 1) < (1 << 24) && cfg->tau < 128;
   p->total = o;
   return DSVT_OK;
 }
@@ -309,24 +378,24 @@ extern "C" int dsvt_partition_bound(const dsvt_part_cfg* cfg, int32_t n_voxels, 
 
 extern "C" int dsvt_partition(const dsvt_part_cfg* cfg, const int32_t* coords, int32_t n_voxels, int32_t* set_inds,
                               int32_t* voxel_slot, int32_t* n_sets, int32_t max_sets, int32_t* set_win,
-                              int32_t* tile_first, int32_t* n_tiles, int32_t* tile_order, int32_t max_tiles, void* ws,
-                              size_t ws_bytes, int32_t* status, void* stream) {
+                              const dsvt_tile_list* tiles, void* ws, size_t ws_bytes, int32_t* status, void* stream) {
   PartPlan p;
   int rc = make_plan(cfg, n_voxels, &p);
   if (rc != DSVT_OK) return rc;
   if (!coords || !set_inds || !voxel_slot || !n_sets || !ws || !status || max_sets <= 0) return DSVT_EINVAL;
   if ((int64_t)max_sets * cfg->tau >= (1ll << 31)) return DSVT_EINVAL;
   if (ws_bytes < p.total) return DSVT_ENOSPC;
-  if ((tile_first != nullptr) != (n_tiles != nullptr)) return DSVT_EINVAL;
-  if (tile_first != nullptr && (max_tiles <= 0 || p.rows_per_cut < 48)) return max_tiles <= 0 ? DSVT_EINVAL : DSVT_EUNSUPPORTED;
-  if (tile_first == nullptr && tile_order != nullptr) return DSVT_EINVAL;
-  if (tile_first != nullptr && max_tiles > p.tile_bound) max_tiles = p.tile_bound;   // scratch is sized for the bound
-  // window key of every set: the caller's array, or scratch when it is not wanted
-  int32_t set_cap = max_sets;
-  if (set_win == nullptr) {
-    set_win = (int32_t*)((char*)ws + p.off_setwin);
-    set_cap = max_sets < p.set_bound ? max_sets : p.set_bound;
+  TileOut tout = {nullptr, nullptr, nullptr, nullptr, 0};
+  if (tiles != nullptr) {
+    if (!tiles->tile_first || !tiles->n_tiles || !tiles->tile_order || !tiles->tile_desc || tiles->max_tiles <= 0) return DSVT_EINVAL;
+    if (!p.desc_ok) return DSVT_EUNSUPPORTED;
+    tout.tile_first = tiles->tile_first; tout.n_tiles = tiles->n_tiles; tout.tile_order = tiles->tile_order;
+    tout.tile_desc = tiles->tile_desc;
+    tout.max_tiles = tiles->max_tiles < p.tile_bound ? tiles->max_tiles : p.tile_bound;   // scratch is sized for the bound
   }
+  // window key of every set: the caller's array, or scratch when it is not wanted
+  int32_t set_cap = max_sets < p.set_bound ? max_sets : p.set_bound;
+  if (set_win == nullptr) set_win = (int32_t*)((char*)ws + p.off_setwin);   // k_emit rewrites the same values there
   hipStream_t st = (hipStream_t)stream;
   char* base = (char*)ws;
   uint32_t* bitmap = (uint32_t*)(base + p.off_bitmap);
@@ -334,10 +403,13 @@ extern "C" int dsvt_partition(const dsvt_part_cfg* cfg, const int32_t* coords, i
   int32_t* count = (int32_t*)(base + p.off_count);
   int32_t* soff = (int32_t*)(base + p.off_soff);
   uint32_t* keys = (uint32_t*)(base + p.off_keys);
+  int32_t* set_loc = (int32_t*)(base + p.off_setloc);
   const int tb = 256;
   {
     dsvt_prof_scope ps(DSVT_K_PART_CLEAR, st);
-    k_clear<<<(unsigned)dsvt_ceil_div(p.n_words, tb), tb, 0, st>>>(bitmap, p.n_words);
+    const int64_t n_desc = (int64_t)tout.max_tiles * kDescInts;
+    const int64_t n_clear = p.n_words > n_desc ? p.n_words : n_desc;
+    k_clear<<<(unsigned)dsvt_ceil_div(n_clear, tb), tb, 0, st>>>(bitmap, p.n_words, tout.tile_desc, n_desc);
   }
   {
     dsvt_prof_scope ps(DSVT_K_PART_MARK, st);
@@ -353,18 +425,20 @@ extern "C" int dsvt_partition(const dsvt_part_cfg* cfg, const int32_t* coords, i
   }
   {
     dsvt_prof_scope ps(DSVT_K_PART_SCAN, st);
-    k_scan_windows<<<1, 1024, 0, st>>>(count, soff, p.g.n_windows, cfg->tau, max_sets, n_sets, status);
+    k_scan_windows<<<1, 1024, 0, st>>>(count, soff, p.g.n_windows, cfg->tau, max_sets, n_sets, status,
+                                       (int32_t*)(base + p.off_setwin), p.set_bound);
+  }
+  if (tiles != nullptr) {
+    dsvt_prof_scope ps(DSVT_K_PART_TILES, st);
+    k_tiles<<<1, 1024, 0, st>>>((const int32_t*)(base + p.off_setwin), count, soff, n_sets, set_cap, cfg->tau,
+                                p.g.n_windows, p.rows_per_cut, tout, (int32_t*)(base + p.off_tilerows),
+                                (int32_t*)(base + p.off_tilepos), (int32_t*)(base + p.off_setp), set_loc);
   }
   {
     dsvt_prof_scope ps(DSVT_K_PART_EMIT, st);
-    k_emit<<<(unsigned)dsvt_ceil_div(n_voxels, tb), tb, 0, st>>>(keys, n_voxels, bitmap, prefix, count, soff,
-                                                                 p.g.words_per_win, cfg->tau, set_cap, set_inds,
-                                                                 voxel_slot, set_win);
-  }
-  if (tile_first != nullptr) {
-    dsvt_prof_scope ps(DSVT_K_PART_TILES, st);
-    k_tiles<<<1, 1024, 0, st>>>(set_win, count, soff, n_sets, set_cap, cfg->tau, p.g.n_windows, p.rows_per_cut, tile_first, n_tiles,
-                                max_tiles, (int32_t*)(base + p.off_tilerows), tile_order);
+    k_emit<<<(unsigned)dsvt_ceil_div(n_voxels, tb), tb, 0, st>>>(p.g, (const int4*)coords, keys, n_voxels, bitmap, prefix,
+                                                                 count, soff, set_cap, set_inds, voxel_slot, set_win, set_loc,
+                                                                 tout.tile_desc, tout.max_tiles);
   }
   DSVT_HIP_TRY(hipGetLastError());
   return DSVT_OK;

@@ -28,22 +28,40 @@ def gpu_maps(coords_d, grid, win, shift, tau, batch, axis, tiles=True):
     return dsvt.dsvt_partition(cfg, coords_d, out=dsvt.SetMaps(cfg, coords_d.shape[0], tiles=tiles))
 
 
-def assert_tiles_valid(gm, om):
-    """The workgroup tile list is a scheduling aid, not part of the method: check that it is a
-    partition of the set sequence into runs whose distinct voxels (each set padded to a multiple
-    of 4 rows) fit 96 rows."""
+def assert_tiles_valid(gm, om, coords=None, win=None):
+    """The work list is a scheduling aid, not part of the method: check that it is a partition of the
+    set sequence into runs whose distinct voxels (each set padded to a multiple of 4 rows) fit 96
+    rows, that the launch order is a permutation with the most rows first, and that every
+    descriptor lists exactly its sets' distinct voxels in slot order."""
     if not gm.max_tiles:
         return
     nt = int(gm.n_tiles.item())
     tf = gm.tile_first[:nt + 1].cpu().numpy()
     assert 0 < nt <= gm.max_tiles and tf[0] == 0 and tf[-1] == om["n_sets"] and np.all(np.diff(tf) > 0)
     si = om["set_inds"]
-    uniq = 1 + (np.diff(si, axis=1) != 0).sum(1)
+    first = np.ones(si.shape, bool)
+    first[:, 1:] = np.diff(si, axis=1) != 0
+    uniq = first.sum(1)
     rows = np.add.reduceat((uniq + 3) // 4 * 4, tf[:-1])
     assert rows.max() <= 96
     order = gm.tile_order[:nt].cpu().numpy()
     assert np.array_equal(np.sort(order), np.arange(nt))          # launch order is a permutation of the tiles ...
     assert np.all(np.diff(rows[order] // 4) <= 0)                 # ... with the most rows first
+    desc = gm.tile_desc[:nt].cpu().numpy()
+    assert np.array_equal(desc[:, 0], rows[order]) and np.array_equal(desc[:, 1], np.diff(tf)[order])
+    for pos in list(range(min(nt, 40))) + list(range(max(nt - 40, 0), nt)):
+        t = order[pos]
+        r = 0
+        for ls, s in enumerate(range(tf[t], tf[t + 1])):
+            members = si[s][first[s]]
+            assert desc[pos, 2 + ls] == r and desc[pos, 26 + ls] == len(members)
+            assert np.array_equal(desc[pos, 64 + r:64 + r + len(members)], members)
+            mult = np.diff(np.append(np.flatnonzero(first[s]), si.shape[1]))
+            assert np.array_equal((desc[pos, 160 + r:160 + r + len(members)].view(np.uint32) >> 24), mult)
+            pad = (len(members) + 3) // 4 * 4
+            assert np.all(desc[pos, 64 + r + len(members):64 + r + pad] == -1)
+            r += pad
+        assert np.all(desc[pos, 64 + r:160] == -1)
 
 
 def assert_maps_equal(gm, om):
