@@ -36,7 +36,7 @@ struct LayerDev {
 
 #ifdef DSVT_PHASE_CLOCKS
 long long* g_phase_clocks = nullptr;
-#define DSVT_CLK(k) do { if (p.clk && threadIdx.x == 0) p.clk[blockIdx.x * 16 + (k)] = clock64(); } while (0)
+#define DSVT_CLK(k) do { if (p.clk && threadIdx.x == 0) p.clk[blockIdx.x * 64 + (k)] = clock64(); } while (0)
 #else
 #define DSVT_CLK(k) do {} while (0)
 #endif
@@ -239,7 +239,7 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
   // behind the row bookkeeping and the gather.
   DSVT_CLK(0);
 #ifdef DSVT_PHASE_CLOCKS
-  if (p.clk && threadIdx.x == 0) p.clk[blockIdx.x * 16 + 11] = wall_clock64();
+  if (p.clk && threadIdx.x == 0) p.clk[blockIdx.x * 64 + 11] = wall_clock64();
 #endif
   GemmPhase<T, NT_QKV, C, 3 * C, NW, 2, false> qkv(reinterpret_cast<const T*>(p.w_qkv), wave);
   qkv.prefetch();
@@ -343,6 +343,9 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
 
   // ---- 3. Q, K, V = X W^T + b; V stored transposed
   {
+#ifdef DSVT_PHASE_CLOCKS
+    if (p.clk) qkv.dbg = p.clk + blockIdx.x * 64 + 16 + wave * 4;
+#endif
     qkv.run(Xs, LDX, RT, p.b_qkv, [&](int o0, int r, f32x4 (&acc)[NT_QKV]) {
       const int row = 16 * r + m;
 #pragma unroll
@@ -473,7 +476,7 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
   }
   DSVT_CLK(8);
 #ifdef DSVT_PHASE_CLOCKS
-  if (p.clk && threadIdx.x == 0) { p.clk[blockIdx.x * 16 + 9] = R; p.clk[blockIdx.x * 16 + 10] = ns; p.clk[blockIdx.x * 16 + 12] = wall_clock64(); }
+  if (p.clk && threadIdx.x == 0) { p.clk[blockIdx.x * 64 + 9] = R; p.clk[blockIdx.x * 64 + 10] = ns; p.clk[blockIdx.x * 64 + 12] = wall_clock64(); }
 #endif
 }
 

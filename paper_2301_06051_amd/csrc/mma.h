@@ -132,6 +132,12 @@ struct GemmPhase {
   AFull<T, NT, NKF> a[(IPW > 1 && DOUBLE_A) ? 2 : 1];   // DOUBLE_A: the next item's weights load during the current item
   const T* Wp;
   int wave;
+#ifdef DSVT_PHASE_CLOCKS
+  long long* dbg = nullptr;                               // per-wavefront stamps: start, then after every item
+#define DSVT_ITEM_CLK(k) do { if (dbg && (threadIdx.x & 63) == 0) dbg[k] = clock64(); } while (0)
+#else
+#define DSVT_ITEM_CLK(k) do {} while (0)
+#endif
 
   __device__ __forceinline__ GemmPhase(const T* wp, int wave_) : Wp(wp), wave(wave_) {}
 
@@ -146,6 +152,7 @@ struct GemmPhase {
     static_assert(KSPLIT == 1, "run() holds the whole K");
     const int g4 = ((threadIdx.x & 63) >> 4) * 4;
     const int h0 = RSPLIT == 1 ? RT : (RT + 1) >> 1;
+    DSVT_ITEM_CLK(0);
 #pragma unroll
     for (int it = 0; it < IPW; ++it) {
       const int item = wave + it * NW;
@@ -156,23 +163,38 @@ struct GemmPhase {
       for (int nt = 0; nt < NT; ++nt) b4[nt] = *reinterpret_cast<const f32x4*>(bias + og * 16 * NT + 16 * nt + g4);
       if (DOUBLE_A && it + 1 < IPW) load_a<T, NT, NKF>(a[(it + 1) & 1], Wp, ((item + NW) % N_OG) * NT);
       const AFull<T, NT, NKF>& A = a[DOUBLE_A ? (it & 1) : 0];
-      BRow<T, NKF> b0, b1;
-      if (cnt > 0) load_b<T, NKF>(b0, Xs, ldx, rt0);
-      for (int r = 0; r < cnt; r += 2) {
-        const bool two = r + 1 < cnt;
-        if (two) load_b<T, NKF>(b1, Xs, ldx, rt0 + r + 1);
-        f32x4 acc0[NT], acc1[NT];                // the bias is the accumulators' initial value
+      if constexpr (DOUBLE_A && RSPLIT == 2) {
+        // two wavefronts per SIMD: the other one covers the LDS latency, so one row tile at a
+        // time keeps the registers for the second weight buffer
+        for (int r = 0; r < cnt; ++r) {
+          BRow<T, NKF> b0;
+          load_b<T, NKF>(b0, Xs, ldx, rt0 + r);
+          f32x4 acc0[NT];
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) { acc0[nt] = b4[nt]; acc1[nt] = b4[nt]; }
-        mma_row<T, NT, NKF>(acc0, A, b0);
-        if (two) {
-          if (r + 2 < cnt) load_b<T, NKF>(b0, Xs, ldx, rt0 + r + 2);
-          mma_row<T, NT, NKF>(acc1, A, b1);
+          for (int nt = 0; nt < NT; ++nt) acc0[nt] = b4[nt];
+          mma_row<T, NT, NKF>(acc0, A, b0);
+          epi(og * 16 * NT, rt0 + r, acc0);
         }
-        epi(og * 16 * NT, rt0 + r, acc0);
-        if (two) epi(og * 16 * NT, rt0 + r + 1, acc1);
+      } else {
+        BRow<T, NKF> b0, b1;
+        if (cnt > 0) load_b<T, NKF>(b0, Xs, ldx, rt0);
+        for (int r = 0; r < cnt; r += 2) {
+          const bool two = r + 1 < cnt;
+          if (two) load_b<T, NKF>(b1, Xs, ldx, rt0 + r + 1);
+          f32x4 acc0[NT], acc1[NT];              // the bias is the accumulators' initial value
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt) { acc0[nt] = b4[nt]; acc1[nt] = b4[nt]; }
+          mma_row<T, NT, NKF>(acc0, A, b0);
+          if (two) {
+            if (r + 2 < cnt) load_b<T, NKF>(b0, Xs, ldx, rt0 + r + 2);
+            mma_row<T, NT, NKF>(acc1, A, b1);
+          }
+          epi(og * 16 * NT, rt0 + r, acc0);
+          if (two) epi(og * 16 * NT, rt0 + r + 1, acc1);
+        }
       }
       if (!DOUBLE_A && it + 1 < IPW) load_a<T, NT, NKF>(a[0], Wp, ((item + NW) % N_OG) * NT);
+      DSVT_ITEM_CLK(it + 1);
     }
   }
 

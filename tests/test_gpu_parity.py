@@ -207,3 +207,112 @@ def test_attn_pool_then_block():
     err = rel_err(y, ref)
     _say(f"  rel err {err:.3e}")
     assert err < TOL["bf16"]
+
+
+# ------------------------------------------------------------------ edge cases and wider shapes
+@pytest.mark.parametrize("n", [1, 2, 36, 37])
+def test_block_on_tiny_inputs(n):
+    """A lone voxel (softmax over one key), a pair, exactly tau and tau + 1 voxels in one window."""
+    cfg = synth.CONFIGS[1]
+    coords = np.concatenate([np.zeros((n, 1), np.int64), synth.frame_uniform(5, (12, 12, 1), n)], 1).astype(np.int32)
+    x = synth.make_features(51, n, cfg["C"], "f32")
+    ws = [synth.make_layer_weights(52 + a, cfg["C"], cfg["heads"], cfg["hidden"], cfg["win"], "f32") for a in (0, 1)]
+    _say(f"block on {n} voxels")
+    oms = [orc.partition(coords, (12, 12, 1), cfg["win"], (0, 0, 0), cfg["tau"], a) for a in (0, 1)]
+    ref = orc.block(ws, oms, coords, x)
+    cd = dev_coords(coords)
+    gms = [gpu_maps(cd, (12, 12, 1), cfg["win"], (0, 0, 0), cfg["tau"], 1, a) for a in (0, 1)]
+    for gm, om in zip(gms, oms):
+        assert_maps_equal(gm, om)
+    out = dsvt.dsvt_block([dsvt.LayerWeights(w) for w in ws], gms, cd, dev_feats(x, "f32"))
+    torch.cuda.synchronize()
+    assert rel_err(out, ref) < TOL["f32"]
+
+
+def test_crowded_window_many_sets():
+    """One 12x12x32 window holding 1,700 voxels: 48 sets from a single window, plus lone voxels elsewhere."""
+    cfg = synth.CONFIGS[5]
+    grid = (24, 24, 32)
+    dense = synth.frame_uniform(61, (12, 12, 32), 1700)
+    lone = np.array([[13, 2, 5], [20, 20, 31], [2, 23, 0]])
+    coords = np.concatenate([np.zeros((1703, 1), np.int64), np.concatenate([dense, lone])], 1).astype(np.int32)
+    coords = coords[np.random.Generator(np.random.Philox(3)).permutation(len(coords))]
+    x = synth.make_features(62, len(coords), cfg["C"], "bf16")
+    w = synth.make_layer_weights(63, cfg["C"], cfg["heads"], cfg["hidden"], cfg["win"], "bf16")
+    _say("crowded window: 1700 voxels, tau 36")
+    for dup_mode in (0, 1):
+        om = orc.partition(coords, grid, cfg["win"], (0, 0, 0), 36, 0)
+        assert om["n_sets"] == 48 + 3
+        ref = orc.set_attention(w, om, coords, x, dup_mode)
+        cd = dev_coords(coords)
+        gm = gpu_maps(cd, grid, cfg["win"], (0, 0, 0), 36, 1, 0)
+        assert_maps_equal(gm, om)
+        y = dsvt.dsvt_set_attention(dsvt.LayerWeights(w, dup_mode), gm, cd, dev_feats(x, "bf16"))
+        torch.cuda.synchronize()
+        assert rel_err(y, ref) < TOL["bf16"]
+
+
+def test_hybrid_window_sizes():
+    """Blocks alternating window (12,12,1) and the shifted (24,24,1) window of the paper's default
+    hybrid partition ("Hybrid window partition"; DSVT-P uses (12,12,1) and (24,24,1))."""
+    cfg = synth.CONFIGS[2]
+    coords = synth.make_frame(2, n=6000)
+    x = synth.make_features(71, len(coords), cfg["C"], "bf16")
+    wins = [((12, 12, 1), (0, 0, 0)), ((24, 24, 1), (12, 12, 0))]
+    ws = [[synth.make_layer_weights(72 + 2 * b + a, cfg["C"], cfg["heads"], cfg["hidden"], wins[b][0], "bf16")
+           for a in (0, 1)] for b in range(2)]
+    _say("hybrid window sizes 12x12 / shifted 24x24")
+    cd = dev_coords(coords)
+    ref, xd = x, dev_feats(x, "bf16")
+    for b, (win, shift) in enumerate(wins):
+        oms = [orc.partition(coords, cfg["grid"], win, shift, cfg["tau"], a) for a in (0, 1)]
+        ref = orc.block(ws[b], oms, coords, ref)
+        gms = [gpu_maps(cd, cfg["grid"], win, shift, cfg["tau"], 1, a) for a in (0, 1)]
+        for gm, om in zip(gms, oms):
+            assert_maps_equal(gm, om)
+        xd = dsvt.dsvt_block([dsvt.LayerWeights(w) for w in ws[b]], gms, cd, xd)
+    torch.cuda.synchronize()
+    err = rel_err(xd, ref)
+    _say(f"  rel err {err:.3e}")
+    assert err < TOL["bf16"]
+
+
+def test_gpu_path_is_permutation_invariant():
+    """Permuting the input voxels permutes the outputs, bit for bit (no arrival-order dependence)."""
+    cfg = synth.CONFIGS[2]
+    coords = synth.make_frame(2, n=5000)
+    x = synth.make_features(81, len(coords), cfg["C"], "bf16")
+    ws = [synth.make_layer_weights(82 + a, cfg["C"], cfg["heads"], cfg["hidden"], cfg["win"], "bf16") for a in (0, 1)]
+    perm = np.random.Generator(np.random.Philox(8)).permutation(len(coords))
+    outs = []
+    for c, f in ((coords, x), (coords[perm], x[perm])):
+        cd = dev_coords(c)
+        gms = [gpu_maps(cd, cfg["grid"], cfg["win"], (6, 6, 0), cfg["tau"], 1, a) for a in (0, 1)]
+        outs.append(dsvt.dsvt_block([dsvt.LayerWeights(w) for w in ws], gms, cd, dev_feats(f, "bf16")))
+    torch.cuda.synchronize()
+    assert torch.equal(outs[1], outs[0][torch.as_tensor(perm).cuda()])
+
+
+def test_full_size_skewed_batch_sampled():
+    """The 4 x 200,000-voxel skewed batch at full size: maps bit-exact, one layer checked on the voxels of
+    sampled sets (the oracle evaluates only the sets that hold them)."""
+    cfg = synth.CONFIGS[5]
+    coords = synth.make_frame(5)
+    x = synth.make_features(91, len(coords), cfg["C"], "bf16")
+    w = synth.make_layer_weights(92, cfg["C"], cfg["heads"], cfg["hidden"], cfg["win"], "bf16")
+    _say("skewed batch, full size, sampled sets")
+    om = orc.partition(coords, cfg["grid"], cfg["win"], (6, 6, 0), cfg["tau"], 1)
+    cd = dev_coords(coords)
+    gm = gpu_maps(cd, cfg["grid"], cfg["win"], (6, 6, 0), cfg["tau"], cfg["batch"], 1)
+    assert_maps_equal(gm, om)
+    y = dsvt.dsvt_set_attention(dsvt.LayerWeights(w), gm, cd, dev_feats(x, "bf16"))
+    torch.cuda.synchronize()
+    pick = np.random.Generator(np.random.Philox(9)).choice(om["n_sets"], 400, replace=False)
+    sub = dict(om, set_inds=om["set_inds"][pick], n_sets=len(pick))
+    members = np.unique(sub["set_inds"])
+    slot = {int(v): int(i) for i, v in reversed(list(enumerate(sub["set_inds"].reshape(-1))))}
+    sub["voxel_slot"] = np.array([slot[int(v)] for v in members], np.int32)
+    ref = orc.set_attention(w, sub, coords, x)
+    err = rel_err(y[torch.as_tensor(members).cuda()], ref)
+    _say(f"  {len(members)} sampled voxels, rel err {err:.3e}")
+    assert err < TOL["bf16"]
