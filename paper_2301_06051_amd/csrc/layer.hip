@@ -111,11 +111,10 @@ __device__ __forceinline__ void attn_item(const LayerDev& p, T* Qs, const T* Ks,
         const float* tp = p.rel_bias + (size_t)idx * HEADS + hh * HG;
         if constexpr (HG == 4) {
           const f32x4 t = *reinterpret_cast<const f32x4*>(tp);
-          bias[kt][i][0] = t[0] * kLog2e; bias[kt][i][1] = t[1] * kLog2e; bias[kt][i][2] = t[2] * kLog2e;
-          bias[kt][i][3] = t[3] * kLog2e;
+          bias[kt][i][0] = t[0]; bias[kt][i][1] = t[1]; bias[kt][i][2] = t[2]; bias[kt][i][3] = t[3];
         } else {
           const float2 t = *reinterpret_cast<const float2*>(tp);
-          bias[kt][i][0] = t.x * kLog2e; bias[kt][i][1] = t.y * kLog2e;
+          bias[kt][i][0] = t.x; bias[kt][i][1] = t.y;
         }
       }
     }
@@ -144,9 +143,8 @@ __device__ __forceinline__ void attn_item(const LayerDev& p, T* Qs, const T* Ks,
 #pragma unroll
       for (int kt = 0; kt < KTC; ++kt) {
         const int ki = 16 * kt + m;
-        Frag fa = *reinterpret_cast<const Frag*>(Ks + (r0 + (ki < nu ? ki : nu - 1)) * LDX + h * D + kkc);
-        fa = live ? fa : M::zero();
-        S[kt] = M::mma(fa, fb, S[kt]);
+        const Frag fa = *reinterpret_cast<const Frag*>(Ks + (r0 + (ki < nu ? ki : nu - 1)) * LDX + h * D + kkc);
+        S[kt] = M::mma(fa, fb, S[kt]);                  // dead k lanes: finite K times the zeroed Q
       }
     }
     // logits in units of log2(e): l = (q.k / sqrt(d) + PE) * log2(e), so exp is a bare exp2
@@ -155,7 +153,8 @@ __device__ __forceinline__ void attn_item(const LayerDev& p, T* Qs, const T* Ks,
     for (int kt = 0; kt < KTC; ++kt)
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const float l = (16 * kt + 4 * g + i < nu) ? fmaf(S[kt][i], scale2, bias[kt][i][hl]) : -INFINITY;
+        const float lv = fmaf(S[kt][i], scale2, bias[kt][i][hl]);
+        const float l = (kt < KTC - 1 || 16 * kt + 4 * g + i < nu) ? lv : -INFINITY;   // only the last key tile is ragged
         S[kt][i] = l;
         mx = fmaxf(mx, l);
       }
@@ -427,7 +426,7 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
       for (int nt = 0; nt < NT_1; ++nt) {
         const int o = o0 + 16 * nt + 4 * g;
         f32x4 v = acc[nt];
-        v = f32x4{gelu_erf_fast(v[0]), gelu_erf_fast(v[1]), gelu_erf_fast(v[2]), gelu_erf_fast(v[3])};
+        v = f32x4{gelu_erf_fast<T>(v[0]), gelu_erf_fast<T>(v[1]), gelu_erf_fast<T>(v[2]), gelu_erf_fast<T>(v[3])};
         *reinterpret_cast<Vec4*>(Hs + (16 * r + m) * LDH + o) = pack4<T>(v);
       }
     });
@@ -496,10 +495,10 @@ PackedLayout packed_layout(const dsvt_layer_w& w) {
   return pl;
 }
 
-// [heads][size] -> [size][heads]
+// [heads][size] -> [size][heads], in units of log2(e) (the softmax works with exp2)
 __global__ void k_pack_table(const float* __restrict__ src, float* __restrict__ dst, int heads, int size) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < heads * size) dst[(i % size) * heads + i / size] = src[i];
+  if (i < heads * size) dst[(i % size) * heads + i / size] = src[i] * 1.4426950408889634f;
 }
 
 LayerDev to_dev(const dsvt_layer_w& w) {

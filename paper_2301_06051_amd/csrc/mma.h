@@ -262,9 +262,12 @@ __device__ __forceinline__ float wave_sum(float v) {
 
 __device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
 
-// erf-GELU with erf from the rational approximation 1 - (1 + a1 z + ... + a6 z^6)^-16 of
-// Abramowitz & Stegun 7.1.28 (|error| <= 3e-7): x * Phi(x) = 0.5 x (1 + erf(x / sqrt 2)).
-__device__ __forceinline__ float gelu_erf_fast(float x) {
+// erf-GELU, x * Phi(x) = 0.5 x (1 + erf(x / sqrt 2)), with erf(z) = 1 - 1 / p(z)^(2^n) from
+// Abramowitz & Stegun: 7.1.28 (six coefficients, ^16, |error| <= 3e-7) for fp32 features, 7.1.27
+// (four coefficients, ^4, |error| <= 5e-4, below bf16 resolution) for bf16 features.
+// 0.5 x + 0.5 |x| erf(|x|/sqrt 2) = max(x, 0) - 0.5 |x| / p^(2^n).
+template <typename T> __device__ __forceinline__ float gelu_erf_fast(float x);
+template <> __device__ __forceinline__ float gelu_erf_fast<float>(float x) {
   const float z = fabsf(x) * 0.70710678118654752f;
   float p = 0.0000430638f;
   p = fmaf(p, z, 0.0002765672f);
@@ -273,9 +276,18 @@ __device__ __forceinline__ float gelu_erf_fast(float x) {
   p = fmaf(p, z, 0.0422820123f);
   p = fmaf(p, z, 0.0705230784f);
   p = fmaf(p, z, 1.0f);
-  p = p * p; p = p * p; p = p * p; p = p * p;          // ^16
-  const float e = 1.0f - __builtin_amdgcn_rcpf(p);                 // erf(|x| / sqrt 2)
-  return 0.5f * x + 0.5f * fabsf(x) * e;
+  p = p * p; p = p * p; p = p * p; p = p * p;
+  return fmaf(-0.70710678118654752f * z, __builtin_amdgcn_rcpf(p), fmaxf(x, 0.f));
+}
+template <> __device__ __forceinline__ float gelu_erf_fast<bf16_t>(float x) {
+  const float z = fabsf(x) * 0.70710678118654752f;
+  float p = 0.078108f;
+  p = fmaf(p, z, 0.000972f);
+  p = fmaf(p, z, 0.230389f);
+  p = fmaf(p, z, 0.278393f);
+  p = fmaf(p, z, 1.0f);
+  p = p * p; p = p * p;
+  return fmaf(-0.70710678118654752f * z, __builtin_amdgcn_rcpf(p), fmaxf(x, 0.f));
 }
 
 // LayerNorm over the C features of every row, for values spread over the workgroup in
