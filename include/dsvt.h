@@ -125,8 +125,8 @@ typedef struct {
                             dsvt_layer_pack; the layer kernels read the matrices only from here */
 } dsvt_layer_w;
 
-/* Supported shapes: (C,heads,hidden) = (64,4,128) in F32 or BF16 and (192,8,384) in BF16, tau <= 48;
- * anything else returns DSVT_EUNSUPPORTED. */
+/* Supported shapes: (C,heads,hidden) = (64,4,128) in F32 or BF16, (128,8,256) and (192,8,384) in BF16,
+ * tau <= 48; anything else returns DSVT_EUNSUPPORTED. */
 
 /* Weight preparation, once per layer (weights do not change between frames).
  * dsvt_layer_packed_size: host-only, bytes of the packed buffer for this layer's shape.
@@ -177,7 +177,7 @@ int dsvt_attn_pool_workspace_size(const dsvt_pool_cfg* cfg, int32_t n_voxels, si
  * out_coords [device] int32 [n_voxels,4] (first *n_out rows written: b, x/l, y/w, z/h)
  * out        [device] [n_voxels,C]       (first *n_out rows written)
  * n_out      [device] int32 scalar
- * Supported: (C,heads) = (64,4) in F32 or BF16, (192,8) in BF16; l*w*h <= 8; out must not alias x.
+ * Supported: (C,heads) = (64,4) in F32 or BF16, (128,8) and (192,8) in BF16; l*w*h <= 8; out must not alias x.
  * status gets DSVT_ST_COORD_RANGE for a coordinate outside the grid (that voxel is skipped). */
 int dsvt_attn_pool(const dsvt_pool_cfg* cfg, const int32_t* coords, const void* x, int32_t n_voxels,
                    int32_t* out_coords, void* out, int32_t* n_out,

@@ -529,9 +529,10 @@ int check_layer(const dsvt_layer_w& w, bool need_mlp, bool need_packed = true) {
   if (w.dtype != DSVT_F32 && w.dtype != DSVT_BF16) return DSVT_EINVAL;
   if (w.dup_mode != 0 && w.dup_mode != 1) return DSVT_EINVAL;
   for (int a = 0; a < 3; ++a) if (w.win[a] <= 0) return DSVT_EINVAL;
-  if (!((w.C == 64 && w.heads == 4 && w.hidden == 128) || (w.C == 192 && w.heads == 8 && w.hidden == 384)))
+  if (!((w.C == 64 && w.heads == 4 && w.hidden == 128) || (w.C == 128 && w.heads == 8 && w.hidden == 256) ||
+        (w.C == 192 && w.heads == 8 && w.hidden == 384)))
     return DSVT_EUNSUPPORTED;
-  if (w.dtype == DSVT_F32 && w.C != 64) return DSVT_EUNSUPPORTED;   // the fp32 C=192 tiles exceed the 160 KB LDS
+  if (w.dtype == DSVT_F32 && w.C != 64) return DSVT_EUNSUPPORTED;   // wider fp32 tiles exceed the 160 KB LDS
   const void* ptrs[] = {w.w_qkv, w.w_o, w.w_1, w.w_2, w.b_qkv, w.b_o, w.b_1, w.b_2, w.ln1_g, w.ln1_b, w.ln2_g, w.ln2_b};
   for (const void* q : ptrs) if (q && !aligned16(q)) return DSVT_EINVAL;
   return DSVT_OK;
@@ -574,6 +575,7 @@ int run_layer(const dsvt_layer_w& w, const dsvt_maps& mp, const int32_t* coords,
               hipStream_t st) {
   if (w.dtype == DSVT_BF16) {
     if (w.C == 192) return launch_layer<bf16_t, 192, 8, 384, 3, 3, 3, 3>(w, mp, coords, x, out, full, st);
+    if (w.C == 128) return launch_layer<bf16_t, 128, 8, 256, 3, 2, 2, 2>(w, mp, coords, x, out, full, st);
     return launch_layer<bf16_t, 64, 4, 128, 3, 1, 2, 1>(w, mp, coords, x, out, full, st);
   }
   return launch_layer<float, 64, 4, 128, 3, 1, 2, 1>(w, mp, coords, x, out, full, st);

@@ -280,7 +280,7 @@ int check_pool(const dsvt_pool_cfg& c, bool need_packed) {
   if (!c.w_q || !c.w_k || !c.w_v || !c.w_o || !c.b_q || !c.b_k || !c.b_v || !c.b_o || !c.ln_g || !c.ln_b) return DSVT_EINVAL;
   if (c.dtype != DSVT_F32 && c.dtype != DSVT_BF16) return DSVT_EINVAL;
   if (c.mask_empty != 0 && c.mask_empty != 1) return DSVT_EINVAL;
-  if (!((c.C == 64 && c.heads == 4) || (c.C == 192 && c.heads == 8))) return DSVT_EUNSUPPORTED;
+  if (!((c.C == 64 && c.heads == 4) || (c.C == 128 && c.heads == 8) || (c.C == 192 && c.heads == 8))) return DSVT_EUNSUPPORTED;
   if (c.dtype == DSVT_F32 && c.C != 64) return DSVT_EUNSUPPORTED;
   if (need_packed && (!c.packed || !aligned16(c.packed))) return DSVT_EINVAL;
   const void* ptrs[] = {c.w_q, c.w_k, c.w_v, c.w_o, c.b_q, c.b_k, c.b_v, c.b_o, c.ln_g, c.ln_b};
@@ -412,6 +412,7 @@ extern "C" int dsvt_attn_pool(const dsvt_pool_cfg* cfg, const int32_t* coords, c
   }
   if (cfg->dtype == DSVT_BF16) {
     if (cfg->C == 192) rc = launch_pool_attention<bf16_t, 192, 8, 3, 3>(*cfg, pl, inds, n_out, x, out, n_voxels, st);
+    else if (cfg->C == 128) rc = launch_pool_attention<bf16_t, 128, 8, 2, 2>(*cfg, pl, inds, n_out, x, out, n_voxels, st);
     else rc = launch_pool_attention<bf16_t, 64, 4, 2, 1>(*cfg, pl, inds, n_out, x, out, n_voxels, st);
   } else {
     rc = launch_pool_attention<float, 64, 4, 2, 1>(*cfg, pl, inds, n_out, x, out, n_voxels, st);

@@ -316,3 +316,28 @@ def test_full_size_skewed_batch_sampled():
     err = rel_err(y[torch.as_tensor(members).cuda()], ref)
     _say(f"  {len(members)} sampled voxels, rel err {err:.3e}")
     assert err < TOL["bf16"]
+
+
+def test_width_128_large_window():
+    """The nuScenes variant's widths (128 channels, 8 heads, hidden 256, window 30 x 30 x 1; appendix
+    "3D Perception on nuScenes") at the largest supported set size, tau = 48."""
+    C, heads, hidden, win, tau, grid = 128, 8, 256, (30, 30, 1), 48, (360, 360, 1)
+    coords = np.concatenate([np.zeros((9000, 1), np.int64), synth.frame_radial(95, grid, 9000)], 1).astype(np.int32)
+    x = synth.make_features(96, len(coords), C, "bf16")
+    ws = [synth.make_layer_weights(97 + a, C, heads, hidden, win, "bf16") for a in (0, 1)]
+    _say("C=128 window 30x30 tau=48")
+    oms = [orc.partition(coords, grid, win, (15, 15, 0), tau, a) for a in (0, 1)]
+    ref = orc.block(ws, oms, coords, x)
+    cd = dev_coords(coords)
+    gms = [gpu_maps(cd, grid, win, (15, 15, 0), tau, 1, a) for a in (0, 1)]
+    for gm, om in zip(gms, oms):
+        assert_maps_equal(gm, om)
+    out = dsvt.dsvt_block([dsvt.LayerWeights(w) for w in ws], gms, cd, dev_feats(x, "bf16"))
+    pw = synth.make_pool_weights(98, C, heads, "bf16")
+    rc_, rp = orc.attn_pool(pw, coords, x, grid, (2, 2, 1), 0)
+    oc, po, n_out, _ = dsvt.dsvt_attn_pool(dsvt.PoolWeights(pw, grid, (2, 2, 1), 1, 0), cd, dev_feats(x, "bf16"))
+    torch.cuda.synchronize()
+    err, m = rel_err(out, ref), int(n_out.item())
+    _say(f"  block rel err {err:.3e}")
+    assert err < TOL["bf16"]
+    assert m == len(rc_) and np.array_equal(oc[:m].cpu().numpy(), rc_) and rel_err(po[:m], rp) < TOL["bf16"]
