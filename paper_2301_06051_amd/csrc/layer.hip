@@ -20,8 +20,8 @@ constexpr int kMaxSets = kRowsMax / 4;           // every set takes at least 4 r
 constexpr int kRowsPad = kRowsMax + 16;          // per-row arrays are read 4 at a time up to 15 rows past a set's end
 constexpr int kMaxItems = 2 * (kRowsMax / 16 + kMaxSets);   // attention items: (set, query tile, half of the heads)
 constexpr int kFixedSets = kRowsMax / kTauMax;   // sets per workgroup when no tile list is given
+constexpr int kHalfTiles = kRowTiles / 2;        // the LayerNorm-phase work items cover half of the row tiles
 constexpr int kLayerWaves = 8;                   // two per SIMD: one workgroup per CU (LDS), the second wavefront hides the first one's waits
-constexpr int kHalfTiles = kRowTiles / 2;        // GEMM work items cover half of the row tiles
 
 struct LayerDev {
   const void *w_qkv, *w_o, *w_1, *w_2;       // packed (see mma.h)
@@ -232,7 +232,9 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
   float* stat = reinterpret_cast<float*>(set_nu + kMaxSets + 1);        // [2][kStatGroups][kRowsMax]
   int32_t* items = reinterpret_cast<int32_t*>(stat + 2 * kStatGroups * kRowsMax);   // [kMaxItems + 1]
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, m = lane & 15, g = lane >> 4;
+  // wave-uniform values are read back through readfirstlane so that the compiler keeps them in
+  // scalar registers: branches on them are scalar branches, not exec-mask divergence
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), m = lane & 15, g = lane >> 4;
 
   // The first Q/K/V weight fragments are requested before anything else: their latency hides
   // behind the row bookkeeping and the gather.
@@ -240,7 +242,7 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
 #ifdef DSVT_PHASE_CLOCKS
   if (p.clk && threadIdx.x == 0) p.clk[blockIdx.x * 64 + 11] = wall_clock64();
 #endif
-  GemmPhase<T, NT_QKV, C, 3 * C, NW, 2, false> qkv(reinterpret_cast<const T*>(p.w_qkv), wave);
+  GemmPhase<T, NT_QKV, C, 3 * C, NW, 1, false> qkv(reinterpret_cast<const T*>(p.w_qkv), wave);
   qkv.prefetch();
 
   int ns;
@@ -264,7 +266,7 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
       row_mult[tid - 160] = (float)((unsigned)word >> 24);
     }
     __syncthreads();
-    ns = set_nu[kMaxSets];
+    ns = __builtin_amdgcn_readfirstlane(set_nu[kMaxSets]);
     if (ns <= 0) return;
     if (tid == 0) {
       int n = 0;                                 // attention items: (set, query tile, half of the heads)
@@ -280,7 +282,7 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
     int n_sets = *mp.n_sets;
     n_sets = n_sets < mp.max_sets ? n_sets : mp.max_sets;
     const int s_begin = blockIdx.x * kFixedSets;
-    ns = (n_sets - s_begin) < kFixedSets ? (n_sets - s_begin) : kFixedSets;
+    ns = __builtin_amdgcn_readfirstlane((n_sets - s_begin) < kFixedSets ? (n_sets - s_begin) : kFixedSets);
     if (ns <= 0) return;
     const int tau = mp.tau;
     for (int r = tid; r < kRowsPad; r += NTHREADS) { row_vox[r] = -1; row_lin[r] = 0; row_mult[r] = 0.f; }
@@ -321,7 +323,7 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
     }
     __syncthreads();
   }
-  const int R = set_r0[ns];
+  const int R = __builtin_amdgcn_readfirstlane(set_r0[ns]);
   const int RT = (R + 15) >> 4;
   const int RTK = ((RT + 1) >> 1) << 1;          // the LayerNorm phases run on an even number of row tiles
   DSVT_CLK(1);
@@ -365,31 +367,30 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
   }
   GemmPhase<T, NT_O, C, C, NW, 2> oproj(reinterpret_cast<const T*>(p.w_o), wave);
   oproj.prefetch();                              // in flight during the attention phase
-  const int og_own = wave % kStatGroups;         // LayerNorm phases: this wavefront's feature group ...
-  const int rt_own = (wave / kStatGroups) * (RTK >> 1), HC = RTK >> 1;   // ... and half of the row tiles
+  // LayerNorm phases (small weight matrices): every wavefront owns C / 4 features of one half of
+  // the row tiles; the Q/K/V and first MLP projections (bandwidth-heavy) give a wavefront all rows
+  // of its output tiles instead, so that each of their weight fragments is loaded only once
+  const int og_own = wave % kStatGroups;
+  const int rt_own = (wave / kStatGroups) * (RTK >> 1), HC = RTK >> 1;
   const int o_own = og_own * 16 * NT_O;
-  f32x4 bo4[NT_O], g1[NT_O], be1[NT_O];
-#pragma unroll
-  for (int nt = 0; nt < NT_O; ++nt) {
-    bo4[nt] = *reinterpret_cast<const f32x4*>(p.b_o + o_own + 16 * nt + 4 * g);
-    g1[nt] = full_layer ? *reinterpret_cast<const f32x4*>(p.ln1_g + o_own + 16 * nt + 4 * g) : bo4[nt];
-    be1[nt] = full_layer ? *reinterpret_cast<const f32x4*>(p.ln1_b + o_own + 16 * nt + 4 * g) : bo4[nt];
-  }
   __syncthreads();
   DSVT_CLK(3);
 
   // ---- 4. attention inside every set; O overwrites Q
   {
-    const int n_items = items[kMaxItems];
+    const int n_items = __builtin_amdgcn_readfirstlane(items[kMaxItems]);
     for (int it = wave; it < n_items; it += NW) {
-      const int d = items[it];
+      const int d = __builtin_amdgcn_readfirstlane(items[it]);
       const int s = d & 255, qt = (d >> 8) & 15, hh = (d >> 12) & 1, kts = d >> 16;
-      const int r0 = set_r0[s], nu = set_nu[s];
+      const int r0 = __builtin_amdgcn_readfirstlane(set_r0[s]), nu = __builtin_amdgcn_readfirstlane(set_nu[s]);
       if (kts == 1) attn_item<T, C, HEADS, HID, 1>(p, Qs, Ks, Vt, row_lin, row_mult, r0, nu, qt, hh, RT * 16);
       else if (kts == 2) attn_item<T, C, HEADS, HID, 2>(p, Qs, Ks, Vt, row_lin, row_mult, r0, nu, qt, hh, RT * 16);
       else attn_item<T, C, HEADS, HID, 3>(p, Qs, Ks, Vt, row_lin, row_mult, r0, nu, qt, hh, RT * 16);
     }
   }
+  f32x4 bo4[NT_O];
+#pragma unroll
+  for (int nt = 0; nt < NT_O; ++nt) bo4[nt] = *reinterpret_cast<const f32x4*>(p.b_o + o_own + 16 * nt + 4 * g);
   __syncthreads();
   DSVT_CLK(4);
 
@@ -398,6 +399,12 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
   if (HC == 1) oproj.template run_keep<1>(Qs, LDX, rt_own, bo4, keep);
   else if (HC == 2) oproj.template run_keep<2>(Qs, LDX, rt_own, bo4, keep);
   else oproj.template run_keep<3>(Qs, LDX, rt_own, bo4, keep);
+  f32x4 g1[NT_O], be1[NT_O];                       // fetched while the MFMAs above drain
+#pragma unroll
+  for (int nt = 0; nt < NT_O; ++nt) {
+    g1[nt] = full_layer ? *reinterpret_cast<const f32x4*>(p.ln1_g + o_own + 16 * nt + 4 * g) : bo4[nt];
+    be1[nt] = full_layer ? *reinterpret_cast<const f32x4*>(p.ln1_b + o_own + 16 * nt + 4 * g) : bo4[nt];
+  }
 #pragma unroll
   for (int nt = 0; nt < NT_O; ++nt) {
     const int o = o_own + 16 * nt + 4 * g;
@@ -414,7 +421,7 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
     }
   }
   if (full_layer) {
-    GemmPhase<T, NT_1, C, HID, NW, 2, false> ffn1(reinterpret_cast<const T*>(p.w_1), wave);
+    GemmPhase<T, NT_1, C, HID, NW, 1, false> ffn1(reinterpret_cast<const T*>(p.w_1), wave);
     ffn1.prefetch();                             // in flight during the LayerNorm exchange
     layer_norm_tile<T, NT_O, C, kHalfTiles>(keep, o_own, og_own, rt_own, HC, stat, g1, be1, p.ln_eps, Xs, LDX);
     __syncthreads();
@@ -433,19 +440,21 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
     GemmPhase<T, NT_2, HID, C, NW, 2, true, (HID / Mma<T>::KC > 8 ? 2 : 1)> ffn2(reinterpret_cast<const T*>(p.w_2), wave);
     ffn2.prefetch();
     const int o_own2 = og_own * 16 * NT_2;
-    f32x4 b24[NT_2], g2[NT_2], be2[NT_2];
+    f32x4 b24[NT_2];
 #pragma unroll
-    for (int nt = 0; nt < NT_2; ++nt) {
-      b24[nt] = *reinterpret_cast<const f32x4*>(p.b_2 + o_own2 + 16 * nt + 4 * g);
-      g2[nt] = *reinterpret_cast<const f32x4*>(p.ln2_g + o_own2 + 16 * nt + 4 * g);
-      be2[nt] = *reinterpret_cast<const f32x4*>(p.ln2_b + o_own2 + 16 * nt + 4 * g);
-    }
+    for (int nt = 0; nt < NT_2; ++nt) b24[nt] = *reinterpret_cast<const f32x4*>(p.b_2 + o_own2 + 16 * nt + 4 * g);
     __syncthreads();
     DSVT_CLK(6);
     f32x4 keep2[NT_2][kHalfTiles];
     if (HC == 1) ffn2.template run_keep<1>(Hs, LDH, rt_own, b24, keep2);
     else if (HC == 2) ffn2.template run_keep<2>(Hs, LDH, rt_own, b24, keep2);
     else ffn2.template run_keep<3>(Hs, LDH, rt_own, b24, keep2);
+    f32x4 g2[NT_2], be2[NT_2];
+#pragma unroll
+    for (int nt = 0; nt < NT_2; ++nt) {
+      g2[nt] = *reinterpret_cast<const f32x4*>(p.ln2_g + o_own2 + 16 * nt + 4 * g);
+      be2[nt] = *reinterpret_cast<const f32x4*>(p.ln2_b + o_own2 + 16 * nt + 4 * g);
+    }
 #pragma unroll
     for (int nt = 0; nt < NT_2; ++nt) {
       const int o = o_own2 + 16 * nt + 4 * g;

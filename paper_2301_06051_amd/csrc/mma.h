@@ -11,6 +11,9 @@
 // the B operand of the next contraction without a transpose.
 #pragma once
 #include <hip/hip_runtime.h>
+#ifndef DSVT_EXP
+#define DSVT_EXP 0   // timing experiments of debug builds: 1 = GEMM phases without epilogues, 2 = without MFMAs
+#endif
 #include <stdint.h>
 
 typedef __bf16 bf16_t;
@@ -126,9 +129,9 @@ struct GemmPhase {
   static constexpr int NKF = NKF_ALL / KSPLIT;          // fragments held at a time (KSPLIT > 1: run_keep only)
   static constexpr int N_OG = NOUT / (16 * NT);
   static constexpr int N_ITEMS = RSPLIT * N_OG;
-  static constexpr int IPW = N_ITEMS / NW;
+  static constexpr int IPW = (N_ITEMS + NW - 1) / NW;   // items per wavefront (the last round may be partial)
   static constexpr int RH = kRowTiles / RSPLIT;          // row tiles an item can cover
-  static_assert(N_ITEMS % NW == 0 && K % KC == 0 && NOUT % (16 * NT) == 0 && (RSPLIT == 1 || RSPLIT == 2), "phase shape");
+  static_assert(K % KC == 0 && NOUT % (16 * NT) == 0 && (RSPLIT == 1 || RSPLIT == 2), "phase shape");
   AFull<T, NT, NKF> a[(IPW > 1 && DOUBLE_A) ? 2 : 1];   // DOUBLE_A: the next item's weights load during the current item
   const T* Wp;
   int wave;
@@ -142,7 +145,9 @@ struct GemmPhase {
   __device__ __forceinline__ GemmPhase(const T* wp, int wave_) : Wp(wp), wave(wave_) {}
 
   // Request the weights of this wavefront's first item (may be called long before run()).
-  __device__ __forceinline__ void prefetch() { load_a<T, NT, NKF, NKF_ALL>(a[0], Wp, (wave % N_OG) * NT); }
+  __device__ __forceinline__ void prefetch() {
+    if (wave < N_ITEMS) load_a<T, NT, NKF, NKF_ALL>(a[0], Wp, (wave % N_OG) * NT);
+  }
 
   // Row tiles in a rolled loop, two per trip.  epi(o0, r, acc): acc[nt][i] is output feature
   // o0 + 16*nt + 4*g + i of row 16*r + m, bias included.  The bias is fetched before the next
@@ -156,12 +161,13 @@ struct GemmPhase {
 #pragma unroll
     for (int it = 0; it < IPW; ++it) {
       const int item = wave + it * NW;
+      if (item >= N_ITEMS) break;
       const int og = item % N_OG, half = item / N_OG;
       const int rt0 = half ? h0 : 0, cnt = half ? RT - h0 : h0;
       f32x4 b4[NT];
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) b4[nt] = *reinterpret_cast<const f32x4*>(bias + og * 16 * NT + 16 * nt + g4);
-      if (DOUBLE_A && it + 1 < IPW) load_a<T, NT, NKF>(a[(it + 1) & 1], Wp, ((item + NW) % N_OG) * NT);
+      if (DOUBLE_A && it + 1 < IPW && item + NW < N_ITEMS) load_a<T, NT, NKF>(a[(it + 1) & 1], Wp, ((item + NW) % N_OG) * NT);
       const AFull<T, NT, NKF>& A = a[DOUBLE_A ? (it & 1) : 0];
       if constexpr (DOUBLE_A && RSPLIT == 2) {
         // two wavefronts per SIMD: the other one covers the LDS latency, so one row tile at a
@@ -184,16 +190,28 @@ struct GemmPhase {
           f32x4 acc0[NT], acc1[NT];              // the bias is the accumulators' initial value
 #pragma unroll
           for (int nt = 0; nt < NT; ++nt) { acc0[nt] = b4[nt]; acc1[nt] = b4[nt]; }
+#if DSVT_EXP != 2
           mma_row<T, NT, NKF>(acc0, A, b0);
+#else
+          for (int nt = 0; nt < NT; ++nt) acc0[nt] += f32x4{(float)b0.f[0][0], (float)b0.f[1][0], (float)A.f[0][nt][0], 0.f};
+#endif
           if (two) {
             if (r + 2 < cnt) load_b<T, NKF>(b0, Xs, ldx, rt0 + r + 2);
+#if DSVT_EXP != 2
             mma_row<T, NT, NKF>(acc1, A, b1);
+#else
+            for (int nt = 0; nt < NT; ++nt) acc1[nt] += f32x4{(float)b1.f[0][0], (float)b1.f[1][0], (float)A.f[1][nt][0], 0.f};
+#endif
           }
+#if DSVT_EXP != 1
           epi(og * 16 * NT, rt0 + r, acc0);
           if (two) epi(og * 16 * NT, rt0 + r + 1, acc1);
+#else
+          if (acc0[0][0] == 12345.678f || (two && acc1[0][0] == 12345.678f)) epi(og * 16 * NT, rt0 + r, acc0);
+#endif
         }
       }
-      if (!DOUBLE_A && it + 1 < IPW) load_a<T, NT, NKF>(a[0], Wp, ((item + NW) % N_OG) * NT);
+      if (!DOUBLE_A && it + 1 < IPW && item + NW < N_ITEMS) load_a<T, NT, NKF>(a[0], Wp, ((item + NW) % N_OG) * NT);
       DSVT_ITEM_CLK(it + 1);
     }
   }
@@ -204,6 +222,7 @@ struct GemmPhase {
   template <int HC>
   __device__ __forceinline__ void run_keep(const T* Xs, int ldx, int rt0, const f32x4 (&b4)[NT], f32x4 (&acc)[NT][RH]) {
     static_assert(IPW == 1 && HC <= RH, "one item per wavefront");
+    if (wave >= N_ITEMS) return;                       // wavefronts beyond the items only take part in the barriers
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt)
 #pragma unroll

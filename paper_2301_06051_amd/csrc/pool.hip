@@ -122,13 +122,13 @@ kp_attention(PoolDev p, const int32_t* __restrict__ pool_inds, const int32_t* __
   T* Qs = reinterpret_cast<T*>(smem + L::off_q);      // Q, then O
   int32_t* row_vox = reinterpret_cast<int32_t*>(smem + L::off_misc);
   float* stat = reinterpret_cast<float*>(row_vox + kRowsMax);
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 4;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), g = lane >> 4;
   const int P = p.P;
   const int MR = kRowsMax / P < kQRows ? kRowsMax / P : kQRows;     // regions per tile
 
   GemmPhase<T, NT_KV, C, 2 * C, NW> kv(reinterpret_cast<const T*>(p.w_kv), wave);
   kv.prefetch();
-  const int n_out = *n_out_ptr;
+  const int n_out = __builtin_amdgcn_readfirstlane(*n_out_ptr);
   const int m0 = blockIdx.x * MR;
   if (m0 >= n_out) return;
   const int mr = (n_out - m0) < MR ? (n_out - m0) : MR;
