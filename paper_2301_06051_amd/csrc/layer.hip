@@ -21,7 +21,7 @@ constexpr int kRowsPad = kRowsMax + 16;          // per-row arrays are read 4 at
 constexpr int kMaxItems = 2 * (kRowsMax / 16 + kMaxSets);   // attention items: (set, query tile, half of the heads)
 constexpr int kFixedSets = kRowsMax / kTauMax;   // sets per workgroup when no tile list is given
 constexpr int kHalfTiles = kRowTiles / 2;        // the LayerNorm-phase work items cover half of the row tiles
-constexpr int kLayerWaves = 8;                   // two per SIMD: one workgroup per CU (LDS), the second wavefront hides the first one's waits
+constexpr int kLayerWaves = 12;                  // three per SIMD: one workgroup per CU (LDS), the other wavefronts hide one's waits
 
 struct LayerDev {
   const void *w_qkv, *w_o, *w_1, *w_2;       // packed (see mma.h)
@@ -57,7 +57,7 @@ template <typename T, int C, int HEADS, int HID> struct LayerLds {
   static constexpr size_t kVt = (size_t)C * LDV * sizeof(T);
   static constexpr size_t off_h = off_q;         // hidden tile reuses Q and K once attention is done
   static constexpr size_t off_misc = off_v + kVt;
-  static constexpr size_t kMisc = (size_t)(3 * kRowsPad + 2 * kMaxSets + 2 + 2 * kStatGroups * kRowsMax + kMaxItems + 1) * 4;
+  static constexpr size_t kMisc = (size_t)(3 * kRowsPad + 2 * kMaxSets + 2 + 2 * kStatGroupsMax * kRowsMax + kMaxItems + 1) * 4;
   static constexpr size_t total = off_misc + kMisc;
   static_assert((size_t)kRowsMax * LDH * sizeof(T) <= 2 * kTile, "hidden tile must fit in Q + K");
   static_assert(C % 64 == 0 && D % Mma<T>::KL == 0 && D % 4 == 0, "shape");
@@ -87,7 +87,6 @@ __device__ __forceinline__ void attn_item(const LayerDev& p, T* Qs, const T* Ks,
 
   constexpr float kLog2e = 1.4426950408889634f;
   const float scale2 = rsqrtf((float)D) * kLog2e;
-  const bool dup = p.dup_mode != 0;
   float bias[KTC][4][HG];
   float mult[KTC][4];
 #pragma unroll
@@ -164,8 +163,7 @@ __device__ __forceinline__ void attn_item(const LayerDev& p, T* Qs, const T* Ks,
     for (int kt = 0; kt < KTC; ++kt)
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        float e = __builtin_amdgcn_exp2f(S[kt][i] - mx);                          // exp2(-inf) = 0 for masked keys
-        if (dup) e *= mult[kt][i];
+        const float e = __builtin_amdgcn_exp2f(S[kt][i] - mx) * mult[kt][i];     // exp2(-inf) = 0 for masked keys; mult = 1 unless repeats count
         S[kt][i] = e;
         sum += e;
       }
@@ -217,7 +215,8 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
   typedef typename Mma<T>::Vec4 Vec4;
   constexpr int LDX = L::LDX, LDV = L::LDV, LDH = L::LDH;
   constexpr int NW = kLayerWaves, NTHREADS = NW * 64;
-  static_assert(C / (16 * NT_O) == kStatGroups && C / (16 * NT_2) == kStatGroups, "LayerNorm phases: one item per wave");
+  constexpr int SG = C / (16 * NT_O);              // LayerNorm phases: SG feature groups x 2 halves of the row tiles, one item per wavefront
+  static_assert(NT_O == NT_2 && SG * 16 * NT_O == C && 2 * SG <= NW && SG <= kStatGroupsMax, "LayerNorm phases: one item per wavefront");
   extern __shared__ __align__(16) unsigned char smem[];
   T* Xs = reinterpret_cast<T*>(smem + L::off_x);
   T* Qs = reinterpret_cast<T*>(smem + L::off_q);
@@ -229,8 +228,8 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
   float* row_mult = reinterpret_cast<float*>(row_lin + kRowsPad);
   int32_t* set_r0 = reinterpret_cast<int32_t*>(row_mult + kRowsPad);   // [kMaxSets + 1]
   int32_t* set_nu = set_r0 + kMaxSets + 1;                              // [kMaxSets + 1]
-  float* stat = reinterpret_cast<float*>(set_nu + kMaxSets + 1);        // [2][kStatGroups][kRowsMax]
-  int32_t* items = reinterpret_cast<int32_t*>(stat + 2 * kStatGroups * kRowsMax);   // [kMaxItems + 1]
+  float* stat = reinterpret_cast<float*>(set_nu + kMaxSets + 1);        // [2][kStatGroupsMax][kRowsMax]
+  int32_t* items = reinterpret_cast<int32_t*>(stat + 2 * kStatGroupsMax * kRowsMax);   // [kMaxItems + 1]
 
   // wave-uniform values are read back through readfirstlane so that the compiler keeps them in
   // scalar registers: branches on them are scalar branches, not exec-mask divergence
@@ -243,7 +242,6 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
   if (p.clk && threadIdx.x == 0) p.clk[blockIdx.x * 64 + 11] = wall_clock64();
 #endif
   GemmPhase<T, NT_QKV, C, 3 * C, NW, 1, false> qkv(reinterpret_cast<const T*>(p.w_qkv), wave);
-  qkv.prefetch();
 
   int ns;
   if (mp.tile_desc != nullptr) {
@@ -258,7 +256,17 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
       hdr_rows = hdr_rows < 0 ? 0 : (hdr_rows > kRowsMax ? kRowsMax : hdr_rows);
       if (lane == 0) { set_nu[kMaxSets] = hdr_ns; set_r0[hdr_ns] = hdr_rows; }
       if (lane >= 2 && lane < 2 + kMaxSets && lane - 2 < hdr_ns) set_r0[lane - 2] = word < 0 ? 0 : (word > kRowsMax - 4 ? kRowsMax - 4 : word);
-      if (lane >= 2 + kMaxSets && lane < 2 + 2 * kMaxSets) set_nu[lane - 2 - kMaxSets] = word < 1 ? 1 : (word > kTauMax ? kTauMax : word);
+      const int nu_s = word < 1 ? 1 : (word > kTauMax ? kTauMax : word);
+      const int ls = lane - 2 - kMaxSets;        // the lanes holding the sets' sizes also list the sets' attention items
+      if (ls >= 0 && ls < kMaxSets) set_nu[ls] = nu_s;
+      const int kts = (ls >= 0 && ls < hdr_ns) ? (nu_s + 15) >> 4 : 0;
+      int incl = 2 * kts;                        // items: (set, query tile, half of the heads)
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) { const int t = __shfl_up(incl, o, 64); if (lane >= o) incl += t; }
+      int n = incl - 2 * kts;
+      for (int qt = 0; qt < kts; ++qt)
+        for (int hh = 0; hh < 2; ++hh) items[n++] = ls | (qt << 8) | (hh << 12) | (kts << 16);
+      if (lane == 63) items[kMaxItems] = incl;   // published by the barrier below
     } else if (tid >= 64 && tid < 64 + kRowsMax) {
       row_vox[tid - 64] = (word >= 0 && word < mp.n_voxels) ? word : -1;
     } else if (tid >= 160 && tid < 160 + kRowsMax) {
@@ -268,15 +276,6 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
     __syncthreads();
     ns = __builtin_amdgcn_readfirstlane(set_nu[kMaxSets]);
     if (ns <= 0) return;
-    if (tid == 0) {
-      int n = 0;                                 // attention items: (set, query tile, half of the heads)
-      for (int s = 0; s < ns; ++s) {
-        const int kts = (set_nu[s] + 15) >> 4;
-        for (int qt = 0; qt < kts; ++qt)
-          for (int hh = 0; hh < 2; ++hh) items[n++] = s | (qt << 8) | (hh << 12) | (kts << 16);
-      }
-      items[kMaxItems] = n;                      // published by the barrier after the gather
-    }
   } else {
     // ---- 1b. no work list: two sets per workgroup, rows derived from set_inds and coords
     int n_sets = *mp.n_sets;
@@ -328,15 +327,29 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
   const int RTK = ((RT + 1) >> 1) << 1;          // the LayerNorm phases run on an even number of row tiles
   DSVT_CLK(1);
 
-  // ---- 2. gather (Eq. 4): rows of x -> Xs, 16 bytes per thread, dead rows zero
+  // ---- 2. gather (Eq. 4): rows of x -> Xs, 16 bytes per thread, dead rows zero.  The loads are
+  // unconditional (clamped addresses) and issued ahead of the Q/K/V weights: a wavefront's loads
+  // return in order, so its rows do not wait for the 18 KB of weight fragments it requests.
   {
-    constexpr int CH = C * (int)sizeof(T) / 16;
-    for (int idx = tid; idx < RTK * 16 * CH; idx += NTHREADS) {
+    constexpr int CH = C * (int)sizeof(T) / 16, G = (kRowsMax * CH + NTHREADS - 1) / NTHREADS;
+    uint4 gv[G];
+    bool live[G];
+#pragma unroll
+    for (int k = 0; k < G; ++k) {
+      const int idx = tid + k * NTHREADS;
       const int r = idx / CH, c = idx - r * CH;
-      const int v = row_vox[r];
-      uint4 val = make_uint4(0u, 0u, 0u, 0u);
-      if (v >= 0) val = reinterpret_cast<const uint4*>(x + (size_t)v * C)[c];
-      *reinterpret_cast<uint4*>(reinterpret_cast<unsigned char*>(Xs) + (size_t)r * LDX * sizeof(T) + c * 16) = val;
+      const int v = r < RTK * 16 ? row_vox[r] : -1;
+      live[k] = v >= 0;
+      gv[k] = reinterpret_cast<const uint4*>(x + (size_t)(v >= 0 ? v : 0) * C)[c];
+    }
+    qkv.prefetch(p.b_qkv, 2 * C / (16 * NT_QKV));
+#pragma unroll
+    for (int k = 0; k < G; ++k) {
+      const int idx = tid + k * NTHREADS;
+      const int r = idx / CH, c = idx - r * CH;
+      if (idx < RTK * 16 * CH)
+        *reinterpret_cast<uint4*>(reinterpret_cast<unsigned char*>(Xs) + (size_t)r * LDX * sizeof(T) + c * 16) =
+            live[k] ? gv[k] : make_uint4(0u, 0u, 0u, 0u);
     }
   }
   __syncthreads();
@@ -347,31 +360,33 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
 #ifdef DSVT_PHASE_CLOCKS
     if (p.clk) qkv.dbg = p.clk + blockIdx.x * 64 + 16 + wave * 4;
 #endif
-    qkv.run(Xs, LDX, RT, p.b_qkv, [&](int o0, int r, f32x4 (&acc)[NT_QKV]) {
-      const int row = 16 * r + m;
+    // the V items run with exchanged MFMA operands: a lane then holds four consecutive rows of one
+    // feature, i.e. 8 contiguous bytes of V^T (a plain store instead of four 2-byte ones)
+    static_assert((C / 16) % NT_QKV == 0, "an item never straddles the Q/K/V boundary");
+    qkv.run(Xs, LDX, RT, p.b_qkv, [&](int o0, int r, f32x4 (&acc)[NT_QKV], bool swapped) {
+      if (swapped) {
 #pragma unroll
-      for (int nt = 0; nt < NT_QKV; ++nt) {
-        const int ot = o0 + 16 * nt;             // a tile never straddles the Q/K/V boundary (C % 16 == 0)
-        const int o = ot + 4 * g;
-        const f32x4 v = acc[nt];
-        if (ot < C) {
-          *reinterpret_cast<Vec4*>(Qs + row * LDX + o) = pack4<T>(v);
-        } else if (ot < 2 * C) {
-          *reinterpret_cast<Vec4*>(Ks + row * LDX + (o - C)) = pack4<T>(v);
-        } else {
+        for (int nt = 0; nt < NT_QKV; ++nt)
+          *reinterpret_cast<Vec4*>(Vt + (o0 - 2 * C + 16 * nt + m) * LDV + 16 * r + 4 * g) = pack4<T>(acc[nt]);
+      } else {
+        const int row = 16 * r + m;
 #pragma unroll
-          for (int i = 0; i < 4; ++i) Vt[(o - 2 * C + i) * LDV + row] = (T)v[i];
+        for (int nt = 0; nt < NT_QKV; ++nt) {
+          const int ot = o0 + 16 * nt;
+          const int o = ot + 4 * g;
+          if (ot < C) *reinterpret_cast<Vec4*>(Qs + row * LDX + o) = pack4<T>(acc[nt]);
+          else *reinterpret_cast<Vec4*>(Ks + row * LDX + (o - C)) = pack4<T>(acc[nt]);
         }
       }
-    });
+    }, 2 * C / (16 * NT_QKV));
   }
   GemmPhase<T, NT_O, C, C, NW, 2> oproj(reinterpret_cast<const T*>(p.w_o), wave);
   oproj.prefetch();                              // in flight during the attention phase
   // LayerNorm phases (small weight matrices): every wavefront owns C / 4 features of one half of
   // the row tiles; the Q/K/V and first MLP projections (bandwidth-heavy) give a wavefront all rows
   // of its output tiles instead, so that each of their weight fragments is loaded only once
-  const int og_own = wave % kStatGroups;
-  const int rt_own = (wave / kStatGroups) * (RTK >> 1), HC = RTK >> 1;
+  const int og_own = wave % SG;
+  const int rt_own = (wave / SG) * (RTK >> 1), HC = wave < 2 * SG ? RTK >> 1 : 0;   // HC = 0: a wavefront without an item
   const int o_own = og_own * 16 * NT_O;
   __syncthreads();
   DSVT_CLK(3);
@@ -398,7 +413,7 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
   f32x4 keep[NT_O][kHalfTiles];
   if (HC == 1) oproj.template run_keep<1>(Qs, LDX, rt_own, bo4, keep);
   else if (HC == 2) oproj.template run_keep<2>(Qs, LDX, rt_own, bo4, keep);
-  else oproj.template run_keep<3>(Qs, LDX, rt_own, bo4, keep);
+  else if (HC == 3) oproj.template run_keep<3>(Qs, LDX, rt_own, bo4, keep);
   f32x4 g1[NT_O], be1[NT_O];                       // fetched while the MFMAs above drain
 #pragma unroll
   for (int nt = 0; nt < NT_O; ++nt) {
@@ -428,7 +443,7 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
     DSVT_CLK(5);
 
     // ---- 6. MLP: H = gelu(x1 W1^T + b1) over the dead Q/K tiles; x2 = LN(x1 + H W2^T + b2)
-    ffn1.run(Xs, LDX, RT, p.b_1, [&](int o0, int r, f32x4 (&acc)[NT_1]) {
+    ffn1.run(Xs, LDX, RT, p.b_1, [&](int o0, int r, f32x4 (&acc)[NT_1], bool) {
 #pragma unroll
       for (int nt = 0; nt < NT_1; ++nt) {
         const int o = o0 + 16 * nt + 4 * g;
@@ -448,7 +463,7 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
     f32x4 keep2[NT_2][kHalfTiles];
     if (HC == 1) ffn2.template run_keep<1>(Hs, LDH, rt_own, b24, keep2);
     else if (HC == 2) ffn2.template run_keep<2>(Hs, LDH, rt_own, b24, keep2);
-    else ffn2.template run_keep<3>(Hs, LDH, rt_own, b24, keep2);
+    else if (HC == 3) ffn2.template run_keep<3>(Hs, LDH, rt_own, b24, keep2);
     f32x4 g2[NT_2], be2[NT_2];
 #pragma unroll
     for (int nt = 0; nt < NT_2; ++nt) {
@@ -583,11 +598,11 @@ int launch_layer(const dsvt_layer_w& w, const dsvt_maps& mp, const int32_t* coor
 int run_layer(const dsvt_layer_w& w, const dsvt_maps& mp, const int32_t* coords, const void* x, void* out, int full,
               hipStream_t st) {
   if (w.dtype == DSVT_BF16) {
-    if (w.C == 192) return launch_layer<bf16_t, 192, 8, 384, 3, 3, 3, 3>(w, mp, coords, x, out, full, st);
-    if (w.C == 128) return launch_layer<bf16_t, 128, 8, 256, 3, 2, 2, 2>(w, mp, coords, x, out, full, st);
-    return launch_layer<bf16_t, 64, 4, 128, 3, 1, 2, 1>(w, mp, coords, x, out, full, st);
+    if (w.C == 192) return launch_layer<bf16_t, 192, 8, 384, 3, 2, 2, 2>(w, mp, coords, x, out, full, st);
+    if (w.C == 128) return launch_layer<bf16_t, 128, 8, 256, 2, 2, 2, 2>(w, mp, coords, x, out, full, st);
+    return launch_layer<bf16_t, 64, 4, 128, 1, 1, 1, 1>(w, mp, coords, x, out, full, st);
   }
-  return launch_layer<float, 64, 4, 128, 3, 1, 2, 1>(w, mp, coords, x, out, full, st);
+  return launch_layer<float, 64, 4, 128, 1, 1, 1, 1>(w, mp, coords, x, out, full, st);
 }
 
 }  // namespace

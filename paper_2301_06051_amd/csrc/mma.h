@@ -110,10 +110,21 @@ __device__ __forceinline__ void mma_row(f32x4 (&acc)[NT], const AFull<T, NT, NKF
     for (int nt = 0; nt < NT; ++nt) acc[nt] = Mma<T>::mma(a.f[kf][nt], b.f[kf], acc[nt]);
 }
 
+// Operands exchanged: the activations are the MFMA "A" operand and the weights "B" (their fragment
+// layouts are identical), so acc[nt][i] = Out[row 4*g + i][feature 16*nt + m]: a lane holds four
+// consecutive ROWS of one feature -- what a transposed store of the result wants.
+template <typename T, int NT, int NKF>
+__device__ __forceinline__ void mma_row_swapped(f32x4 (&acc)[NT], const AFull<T, NT, NKF>& a, const BRow<T, NKF>& b) {
+#pragma unroll
+  for (int kf = 0; kf < NKF; ++kf)
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) acc[nt] = Mma<T>::mma(b.f[kf], a.f[kf][nt], acc[nt]);
+}
+
 constexpr int kRowTiles = 6;                     // row tiles of a workgroup tile
 constexpr int kRowsMax = 16 * kRowTiles;         // 96 rows
 constexpr int kWaves = 4;                        // wavefronts of a pooling workgroup, one per SIMD
-constexpr int kStatGroups = 4;                   // LayerNorm phases: the C features are split over 4 groups of output tiles
+constexpr int kStatGroupsMax = 6;                // LayerNorm phases: the C features are split over at most 6 groups of output tiles
 
 // One GEMM phase of a workgroup of NW wavefronts: Out^T[NOUT x rows] = W[NOUT x K] . X^T.
 // A work item is a group of NT output tiles over all row tiles (RSPLIT = 1) or over one half of
@@ -135,6 +146,9 @@ struct GemmPhase {
   AFull<T, NT, NKF> a[(IPW > 1 && DOUBLE_A) ? 2 : 1];   // DOUBLE_A: the next item's weights load during the current item
   const T* Wp;
   int wave;
+  struct Bias { f32x4 v[NT]; float s[NT]; };          // both forms of an item's bias, see load_bias()
+  Bias bias0;                                            // first item's bias when prefetch() fetched it
+  bool bias0_set = false;
 #ifdef DSVT_PHASE_CLOCKS
   long long* dbg = nullptr;                               // per-wavefront stamps: start, then after every item
 #define DSVT_ITEM_CLK(k) do { if (dbg && (threadIdx.x & 63) == 0) dbg[k] = clock64(); } while (0)
@@ -144,18 +158,39 @@ struct GemmPhase {
 
   __device__ __forceinline__ GemmPhase(const T* wp, int wave_) : Wp(wp), wave(wave_) {}
 
-  // Request the weights of this wavefront's first item (may be called long before run()).
-  __device__ __forceinline__ void prefetch() {
-    if (wave < N_ITEMS) load_a<T, NT, NKF, NKF_ALL>(a[0], Wp, (wave % N_OG) * NT);
+  // Request the weights of this wavefront's first item (may be called long before run()), and
+  // with them, if given, the bias run() starts that item from.
+  __device__ __forceinline__ void prefetch(const float* __restrict__ bias = nullptr, int swap_og = N_OG) {
+    if (N_ITEMS >= NW || wave < N_ITEMS) {
+      load_a<T, NT, NKF, NKF_ALL>(a[0], Wp, (wave % N_OG) * NT);
+      if (bias != nullptr) { load_bias(bias0, bias, wave % N_OG, swap_og < N_OG); bias0_set = true; }
+    }
   }
 
-  // Row tiles in a rolled loop, two per trip.  epi(o0, r, acc): acc[nt][i] is output feature
-  // o0 + 16*nt + 4*g + i of row 16*r + m, bias included.  The bias is fetched before the next
-  // item's weights are requested, so waiting for it never waits for them.
+  // Accumulator start values of output group og: feature 16*nt + 4*g + i for element i, or, with
+  // exchanged operands, feature 16*nt + m for all four.  Both forms are loaded (no branch, no
+  // wait at the point of the request) and select() picks one when the item starts.
+  __device__ __forceinline__ void load_bias(Bias& b, const float* __restrict__ bias, int og, bool need_s) const {
+    const int lane16 = threadIdx.x & 15, g4 = ((threadIdx.x & 63) >> 4) * 4;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      b.v[nt] = *reinterpret_cast<const f32x4*>(bias + og * 16 * NT + 16 * nt + g4);
+      b.s[nt] = need_s ? bias[og * 16 * NT + 16 * nt + lane16] : 0.f;
+    }
+  }
+  static __device__ __forceinline__ void select_bias(f32x4 (&b4)[NT], const Bias& b, bool sw) {
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) b4[nt] = sw ? f32x4{b.s[nt], b.s[nt], b.s[nt], b.s[nt]} : b.v[nt];
+  }
+
+  // Row tiles in a rolled loop, two per trip.  epi(o0, r, acc, swapped): acc[nt][i] is output
+  // feature o0 + 16*nt + 4*g + i of row 16*r + m, bias included -- or, for the items whose output
+  // group is >= swap_og ("swapped": operands exchanged), feature o0 + 16*nt + m of row
+  // 16*r + 4*g + i.  The bias is fetched before the next item's weights are requested, so waiting
+  // for it never waits for them.
   template <typename Epi>
-  __device__ __forceinline__ void run(const T* Xs, int ldx, int RT, const float* __restrict__ bias, Epi epi) {
+  __device__ __forceinline__ void run(const T* Xs, int ldx, int RT, const float* __restrict__ bias, Epi epi, int swap_og = N_OG) {
     static_assert(KSPLIT == 1, "run() holds the whole K");
-    const int g4 = ((threadIdx.x & 63) >> 4) * 4;
     const int h0 = RSPLIT == 1 ? RT : (RT + 1) >> 1;
     DSVT_ITEM_CLK(0);
 #pragma unroll
@@ -164,9 +199,15 @@ struct GemmPhase {
       if (item >= N_ITEMS) break;
       const int og = item % N_OG, half = item / N_OG;
       const int rt0 = half ? h0 : 0, cnt = half ? RT - h0 : h0;
+      const bool sw = og >= swap_og;                 // wave-uniform
       f32x4 b4[NT];
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt) b4[nt] = *reinterpret_cast<const f32x4*>(bias + og * 16 * NT + 16 * nt + g4);
+      if (it == 0 && bias0_set) {
+        select_bias(b4, bias0, sw);
+      } else {
+        Bias bl;
+        load_bias(bl, bias, og, swap_og < N_OG);
+        select_bias(b4, bl, sw);
+      }
       if (DOUBLE_A && it + 1 < IPW && item + NW < N_ITEMS) load_a<T, NT, NKF>(a[(it + 1) & 1], Wp, ((item + NW) % N_OG) * NT);
       const AFull<T, NT, NKF>& A = a[DOUBLE_A ? (it & 1) : 0];
       if constexpr (DOUBLE_A && RSPLIT == 2) {
@@ -178,8 +219,8 @@ struct GemmPhase {
           f32x4 acc0[NT];
 #pragma unroll
           for (int nt = 0; nt < NT; ++nt) acc0[nt] = b4[nt];
-          mma_row<T, NT, NKF>(acc0, A, b0);
-          epi(og * 16 * NT, rt0 + r, acc0);
+          if (sw) mma_row_swapped<T, NT, NKF>(acc0, A, b0); else mma_row<T, NT, NKF>(acc0, A, b0);
+          epi(og * 16 * NT, rt0 + r, acc0, sw);
         }
       } else {
         BRow<T, NKF> b0, b1;
@@ -191,23 +232,23 @@ struct GemmPhase {
 #pragma unroll
           for (int nt = 0; nt < NT; ++nt) { acc0[nt] = b4[nt]; acc1[nt] = b4[nt]; }
 #if DSVT_EXP != 2
-          mma_row<T, NT, NKF>(acc0, A, b0);
+          if (sw) mma_row_swapped<T, NT, NKF>(acc0, A, b0); else mma_row<T, NT, NKF>(acc0, A, b0);
 #else
           for (int nt = 0; nt < NT; ++nt) acc0[nt] += f32x4{(float)b0.f[0][0], (float)b0.f[1][0], (float)A.f[0][nt][0], 0.f};
 #endif
           if (two) {
             if (r + 2 < cnt) load_b<T, NKF>(b0, Xs, ldx, rt0 + r + 2);
 #if DSVT_EXP != 2
-            mma_row<T, NT, NKF>(acc1, A, b1);
+            if (sw) mma_row_swapped<T, NT, NKF>(acc1, A, b1); else mma_row<T, NT, NKF>(acc1, A, b1);
 #else
             for (int nt = 0; nt < NT; ++nt) acc1[nt] += f32x4{(float)b1.f[0][0], (float)b1.f[1][0], (float)A.f[1][nt][0], 0.f};
 #endif
           }
 #if DSVT_EXP != 1
-          epi(og * 16 * NT, rt0 + r, acc0);
-          if (two) epi(og * 16 * NT, rt0 + r + 1, acc1);
+          epi(og * 16 * NT, rt0 + r, acc0, sw);
+          if (two) epi(og * 16 * NT, rt0 + r + 1, acc1, sw);
 #else
-          if (acc0[0][0] == 12345.678f || (two && acc1[0][0] == 12345.678f)) epi(og * 16 * NT, rt0 + r, acc0);
+          if (acc0[0][0] == 12345.678f || (two && acc1[0][0] == 12345.678f)) epi(og * 16 * NT, rt0 + r, acc0, sw);
 #endif
         }
       }
@@ -284,43 +325,62 @@ __device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + e
 // erf-GELU, x * Phi(x) = 0.5 x (1 + erf(x / sqrt 2)), with erf(z) = 1 - 1 / p(z)^(2^n) from
 // Abramowitz & Stegun: 7.1.28 (six coefficients, ^16, |error| <= 3e-7) for fp32 features, 7.1.27
 // (four coefficients, ^4, |error| <= 5e-4, below bf16 resolution) for bf16 features.
-// 0.5 x + 0.5 |x| erf(|x|/sqrt 2) = max(x, 0) - 0.5 |x| / p^(2^n).
+// 0.5 x + 0.5 |x| erf(|x|/sqrt 2) = max(x, 0) - |x| / (2 p^(2^n)); the polynomial is taken in
+// a = |x| directly, q(a) = 2^(1/2^n) p(a / sqrt 2), so that q^(2^n) = 2 p^(2^n).
+template <int POW_LOG2> constexpr double gelu_coef(double c, int deg) {
+  double r = c;
+  for (int i = 0; i < deg; ++i) r *= 0.70710678118654752440;              // (1 / sqrt 2)^deg
+  double root = 2.0;                                                        // 2^(1 / 2^POW_LOG2)
+  for (int i = 0; i < POW_LOG2; ++i) {                                      // Newton square roots, constexpr-friendly
+    double y = root > 1.0 ? root : 1.0;
+    for (int k = 0; k < 60; ++k) y = 0.5 * (y + root / y);
+    root = y;
+  }
+  return r * root;
+}
 template <typename T> __device__ __forceinline__ float gelu_erf_fast(float x);
 template <> __device__ __forceinline__ float gelu_erf_fast<float>(float x) {
-  const float z = fabsf(x) * 0.70710678118654752f;
-  float p = 0.0000430638f;
-  p = fmaf(p, z, 0.0002765672f);
-  p = fmaf(p, z, 0.0001520143f);
-  p = fmaf(p, z, 0.0092705272f);
-  p = fmaf(p, z, 0.0422820123f);
-  p = fmaf(p, z, 0.0705230784f);
-  p = fmaf(p, z, 1.0f);
-  p = p * p; p = p * p; p = p * p; p = p * p;
-  return fmaf(-0.70710678118654752f * z, __builtin_amdgcn_rcpf(p), fmaxf(x, 0.f));
+  constexpr float k0 = (float)gelu_coef<4>(1.0, 0), k1 = (float)gelu_coef<4>(0.0705230784, 1),
+                  k2 = (float)gelu_coef<4>(0.0422820123, 2), k3 = (float)gelu_coef<4>(0.0092705272, 3),
+                  k4 = (float)gelu_coef<4>(0.0001520143, 4), k5 = (float)gelu_coef<4>(0.0002765672, 5),
+                  k6 = (float)gelu_coef<4>(0.0000430638, 6);
+  const float a = fabsf(x);
+  float q = fmaf(k6, a, k5);
+  q = fmaf(q, a, k4);
+  q = fmaf(q, a, k3);
+  q = fmaf(q, a, k2);
+  q = fmaf(q, a, k1);
+  q = fmaf(q, a, k0);
+  q = q * q; q = q * q; q = q * q; q = q * q;
+  return fmaf(-a, __builtin_amdgcn_rcpf(q), fmaxf(x, 0.f));
 }
 template <> __device__ __forceinline__ float gelu_erf_fast<bf16_t>(float x) {
-  const float z = fabsf(x) * 0.70710678118654752f;
-  float p = 0.078108f;
-  p = fmaf(p, z, 0.000972f);
-  p = fmaf(p, z, 0.230389f);
-  p = fmaf(p, z, 0.278393f);
-  p = fmaf(p, z, 1.0f);
-  p = p * p; p = p * p;
-  return fmaf(-0.70710678118654752f * z, __builtin_amdgcn_rcpf(p), fmaxf(x, 0.f));
+  constexpr float k0 = (float)gelu_coef<2>(1.0, 0), k1 = (float)gelu_coef<2>(0.278393, 1),
+                  k2 = (float)gelu_coef<2>(0.230389, 2), k3 = (float)gelu_coef<2>(0.000972, 3),
+                  k4 = (float)gelu_coef<2>(0.078108, 4);
+  const float a = fabsf(x);
+  float q = fmaf(k4, a, k3);
+  q = fmaf(q, a, k2);
+  q = fmaf(q, a, k1);
+  q = fmaf(q, a, k0);
+  q = q * q; q = q * q;
+  return fmaf(-a, __builtin_amdgcn_rcpf(q), fmaxf(x, 0.f));
 }
 
 // LayerNorm over the C features of every row, for values spread over the workgroup in
 // accumulator layout: this wavefront holds features o0 .. o0 + 16*NT - 1 (group og of
-// kStatGroups) of rows 16*(rt0 + r) + m, r < cnt.  Per-group sums of x and x^2 (fp32) are
+// SG = C / (16*NT)) of rows 16*(rt0 + r) + m, r < cnt (cnt = 0: only the barrier).  Per-group sums of x and x^2 (fp32) are
 // exchanged through LDS; variance = E[x^2] - mean^2.  Every thread of the workgroup must call it.
 template <typename T, int NT, int C, int RH>
 __device__ __forceinline__ void layer_norm_tile(f32x4 (&v)[NT][RH], int o0, int og, int rt0, int cnt, float* stat,
                                                 const f32x4 (&ga)[NT], const f32x4 (&be)[NT], float eps, T* dst,
                                                 int ldd) {
   typedef typename Mma<T>::Vec4 Vec4;
+  constexpr int SG = C / (16 * NT);
+  static_assert(SG * 16 * NT == C && SG <= kStatGroupsMax, "LayerNorm feature groups");
   const int lane = threadIdx.x & 63, m = lane & 15, g = lane >> 4;
   float* stat1 = stat;
-  float* stat2 = stat + kStatGroups * kRowsMax;
+  float* stat2 = stat + kStatGroupsMax * kRowsMax;
 #pragma unroll
   for (int r = 0; r < RH; ++r) {
     if (r < cnt) {
@@ -342,7 +402,7 @@ __device__ __forceinline__ void layer_norm_tile(f32x4 (&v)[NT][RH], int o0, int 
       const int row = 16 * (rt0 + r) + m;
       float s = 0.f, q = 0.f;
 #pragma unroll
-      for (int k = 0; k < kStatGroups; ++k) { s += stat1[k * kRowsMax + row]; q += stat2[k * kRowsMax + row]; }
+      for (int k = 0; k < SG; ++k) { s += stat1[k * kRowsMax + row]; q += stat2[k * kRowsMax + row]; }
       const float mean = s * (1.0f / C);
       const float rs = rsqrtf(fmaxf(fmaf(-mean, mean, q * (1.0f / C)), 0.f) + eps);
       const float sh = -mean * rs;

@@ -103,7 +103,7 @@ template <typename T, int C> struct PoolLds {
   static constexpr size_t kQTile = (size_t)kQRows * LDX * sizeof(T);
   static constexpr size_t off_x = 0, off_k = kTile, off_v = 2 * kTile, off_p = 3 * kTile, off_q = off_p + kQTile;
   static constexpr size_t off_misc = off_q + kQTile;
-  static constexpr size_t total = off_misc + (size_t)(kRowsMax + 2 * kStatGroups * kRowsMax) * 4;
+  static constexpr size_t total = off_misc + (size_t)(kRowsMax + 2 * kStatGroupsMax * kRowsMax) * 4;
 };
 
 template <typename T, int C, int HEADS, int NT_KV, int NT_C>
@@ -158,7 +158,7 @@ kp_attention(PoolDev p, const int32_t* __restrict__ pool_inds, const int32_t* __
   __syncthreads();
 
   // K, V of every slot; Q of the pooled rows
-  kv.run(Xs, LDX, RT, p.b_kv, [&](int o0, int r, f32x4 (&acc)[NT_KV]) {
+  kv.run(Xs, LDX, RT, p.b_kv, [&](int o0, int r, f32x4 (&acc)[NT_KV], bool) {
     const int row = 16 * r + (lane & 15);
 #pragma unroll
     for (int nt = 0; nt < NT_KV; ++nt) {
@@ -169,7 +169,7 @@ kp_attention(PoolDev p, const int32_t* __restrict__ pool_inds, const int32_t* __
   });
   GemmPhase<T, NT_C, C, C, NW> qp(reinterpret_cast<const T*>(p.w_q), wave);
   qp.prefetch();
-  qp.run(Ps, LDX, kQRows / 16, p.b_q, [&](int o0, int r, f32x4 (&acc)[NT_C]) {
+  qp.run(Ps, LDX, kQRows / 16, p.b_q, [&](int o0, int r, f32x4 (&acc)[NT_C], bool) {
     const int row = 16 * r + (lane & 15);
 #pragma unroll
     for (int nt = 0; nt < NT_C; ++nt) *reinterpret_cast<Vec4*>(Qs + row * LDX + o0 + 16 * nt + 4 * g) = pack4<T>(acc[nt]);
