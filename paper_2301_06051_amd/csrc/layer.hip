@@ -23,9 +23,34 @@ constexpr int kFixedSets = kRowsMax / kTauMax;   // sets per workgroup when no t
 constexpr int kHalfTiles = kRowTiles / 2;        // the LayerNorm-phase work items cover half of the row tiles
 constexpr int kLayerWaves = 12;                  // three per SIMD: one workgroup per CU (LDS), the other wavefronts hide one's waits
 
+// erf-GELU (appendix "Network Architecture": the MLP of a DSVT layer) for bf16 features by linear
+// interpolation: kGeluKnots intervals of width 1 / kGeluScale over [-4, 4), each with the slope
+// and intercept of the chord through the exact values at its ends; below -4 the result is 0, from
+// 4 on it is x (both within 1.4e-4 of the exact function; the chords are within 3.5e-5).  The
+// table (4 KB) sits in LDS during the MLP: a lookup and one fma replace a dozen ALU instructions.
+constexpr int kGeluKnots = 512;
+constexpr float kGeluScale = 64.f;
+__global__ void k_pack_gelu_table(float2* __restrict__ tab) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= kGeluKnots) return;
+  const double x0 = (i - kGeluKnots / 2) / (double)kGeluScale, x1 = x0 + 1.0 / kGeluScale;
+  const double g0 = 0.5 * x0 * (1.0 + erf(x0 * 0.70710678118654752440)), g1 = 0.5 * x1 * (1.0 + erf(x1 * 0.70710678118654752440));
+  const double sl = (g1 - g0) * kGeluScale;
+  float2 e = make_float2((float)sl, (float)(g0 - sl * x0));
+  if (i == 0) e = make_float2(0.f, 0.f);                      // x < -4 + 1/64 (and everything below)
+  if (i == kGeluKnots - 1) e = make_float2(1.f, 0.f);         // x >= 4 - 1/64 (and everything above)
+  tab[i] = e;
+}
+__device__ __forceinline__ float gelu_from_table(const float2* tab, float x) {
+  const float t = __builtin_amdgcn_fmed3f(fmaf(x, kGeluScale, 0.5f * kGeluKnots), 0.f, (float)(kGeluKnots - 1));
+  const float2 e = tab[(int)t];
+  return fmaf(e.x, x, e.y);
+}
+
 struct LayerDev {
   const void *w_qkv, *w_o, *w_1, *w_2;       // packed (see mma.h)
   const float *b_qkv, *b_o, *b_1, *b_2, *ln1_g, *ln1_b, *ln2_g, *ln2_b, *rel_bias;
+  const float2* gelu_tab;                    // kGeluKnots (slope, intercept) pairs, see k_pack_gelu_table
   float ln_eps;
   int rel_size, rel_const, rel_my, rel_mz;   // table entries per head; index = lin(q) - lin(k) + rel_const
   int dup_mode;
@@ -38,7 +63,11 @@ struct LayerDev {
 long long* g_phase_clocks = nullptr;
 #define DSVT_CLK(k) do { if (p.clk && threadIdx.x == 0) p.clk[blockIdx.x * 64 + (k)] = clock64(); } while (0)
 #else
+#ifdef DSVT_STOP
+#define DSVT_CLK(k) do { if ((k) == DSVT_STOP) return; } while (0)
+#else
 #define DSVT_CLK(k) do {} while (0)
+#endif
 #endif
 
 struct MapsDev {
@@ -50,17 +79,21 @@ template <typename T, int C, int HEADS, int HID> struct LayerLds {
   static constexpr int D = C / HEADS;
   static constexpr int PAD = lds_pad<T>();
   static constexpr int LDX = C + PAD;            // pitch of [row][feature] tiles, elements of T
-  static constexpr int LDV = kRowsMax + PAD;     // pitch of V^T [feature][row]
+  static constexpr int LDV = kRowsMax + 16 / (int)sizeof(T);   // pitch of V^T [feature][row]
   static constexpr int LDH = HID + PAD;          // pitch of the MLP hidden tile
   static constexpr size_t kTile = (size_t)kRowsMax * LDX * sizeof(T);
   static constexpr size_t off_x = 0, off_q = kTile, off_k = 2 * kTile, off_v = 3 * kTile;
   static constexpr size_t kVt = (size_t)C * LDV * sizeof(T);
   static constexpr size_t off_h = off_q;         // hidden tile reuses Q and K once attention is done
   static constexpr size_t off_misc = off_v + kVt;
-  static constexpr size_t kMisc = (size_t)(3 * kRowsPad + 2 * kMaxSets + 2 + 2 * kStatGroupsMax * kRowsMax + kMaxItems + 1) * 4;
+  static constexpr size_t kMisc = (size_t)(3 * kRowsPad + 2 * kMaxSets + 2 + kMaxItems + 1) * 4;
+  // after attention the V^T region holds the GELU table and the LayerNorm statistics
+  static constexpr size_t off_gelu = off_v, off_stat = off_v + 4096, kStat = (size_t)2 * kStatGroupsMax * kRowsMax * 4;
+  static_assert(off_stat + kStat <= off_misc, "GELU table and LayerNorm statistics must fit in the V^T region");
   static constexpr size_t total = off_misc + kMisc;
   static_assert((size_t)kRowsMax * LDH * sizeof(T) <= 2 * kTile, "hidden tile must fit in Q + K");
   static_assert(C % 64 == 0 && D % Mma<T>::KL == 0 && D % 4 == 0, "shape");
+  static_assert(total <= 160 * 1024, "LDS of one CU");
 };
 
 // Attention of one (set, query tile, half of the heads) item (Eq. 5): for each of its heads,
@@ -228,8 +261,8 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
   float* row_mult = reinterpret_cast<float*>(row_lin + kRowsPad);
   int32_t* set_r0 = reinterpret_cast<int32_t*>(row_mult + kRowsPad);   // [kMaxSets + 1]
   int32_t* set_nu = set_r0 + kMaxSets + 1;                              // [kMaxSets + 1]
-  float* stat = reinterpret_cast<float*>(set_nu + kMaxSets + 1);        // [2][kStatGroupsMax][kRowsMax]
-  int32_t* items = reinterpret_cast<int32_t*>(stat + 2 * kStatGroupsMax * kRowsMax);   // [kMaxItems + 1]
+  float* stat = reinterpret_cast<float*>(smem + L::off_stat);           // [2][kStatGroupsMax][kRowsMax], over V^T once attention is done
+  int32_t* items = set_nu + kMaxSets + 1;                               // [kMaxItems + 1]
 
   // wave-uniform values are read back through readfirstlane so that the compiler keeps them in
   // scalar registers: branches on them are scalar branches, not exec-mask divergence
@@ -408,6 +441,13 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
   for (int nt = 0; nt < NT_O; ++nt) bo4[nt] = *reinterpret_cast<const f32x4*>(p.b_o + o_own + 16 * nt + 4 * g);
   __syncthreads();
   DSVT_CLK(4);
+  // attention is done with V^T: the GELU table of the MLP takes its place (published by the
+  // barriers of the LayerNorm below)
+  constexpr bool kGeluTable = sizeof(T) == 2;
+  static_assert(kGeluKnots * sizeof(float2) <= 4096, "GELU table slot");
+  const float2* gelu_lds = reinterpret_cast<const float2*>(smem + L::off_gelu);
+  if (kGeluTable && full_layer && tid < kGeluKnots / 2)
+    reinterpret_cast<float4*>(smem + L::off_gelu)[tid] = reinterpret_cast<const float4*>(p.gelu_tab)[tid];
 
   // ---- 5. Y = O Wo^T + bo (+ x), then LayerNorm; result (or raw Y) replaces x in Xs
   f32x4 keep[NT_O][kHalfTiles];
@@ -448,7 +488,10 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
       for (int nt = 0; nt < NT_1; ++nt) {
         const int o = o0 + 16 * nt + 4 * g;
         f32x4 v = acc[nt];
-        v = f32x4{gelu_erf_fast<T>(v[0]), gelu_erf_fast<T>(v[1]), gelu_erf_fast<T>(v[2]), gelu_erf_fast<T>(v[3])};
+        if constexpr (kGeluTable)
+          v = f32x4{gelu_from_table(gelu_lds, v[0]), gelu_from_table(gelu_lds, v[1]), gelu_from_table(gelu_lds, v[2]), gelu_from_table(gelu_lds, v[3])};
+        else
+          v = f32x4{gelu_erf_fast<T>(v[0]), gelu_erf_fast<T>(v[1]), gelu_erf_fast<T>(v[2]), gelu_erf_fast<T>(v[3])};
         *reinterpret_cast<Vec4*>(Hs + (16 * r + m) * LDH + o) = pack4<T>(v);
       }
     });
@@ -505,7 +548,7 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
 
 // ------------------------------------------------------------------------------------------
 // Packed buffer of a layer: the four matrices in fragment order, each on a 256-byte boundary.
-struct PackedLayout { size_t off[5], total; int out[4], k[4]; int rel_size; };   // off[4]: position table [index][heads]
+struct PackedLayout { size_t off[6], total; int out[4], k[4]; int rel_size; };   // off[4]: position table [index][heads], off[5]: GELU table
 PackedLayout packed_layout(const dsvt_layer_w& w) {
   PackedLayout pl;
   const size_t es = w.dtype == DSVT_BF16 ? 2 : 4;
@@ -515,6 +558,8 @@ PackedLayout packed_layout(const dsvt_layer_w& w) {
   pl.rel_size = (2 * w.win[0] - 1) * (2 * w.win[1] - 1) * (2 * w.win[2] - 1);
   pl.off[4] = o;
   if (w.rel_bias != nullptr) o = dsvt_align_up(o + (size_t)pl.rel_size * w.heads * 4, 256);
+  pl.off[5] = o;
+  o = dsvt_align_up(o + (size_t)kGeluKnots * sizeof(float2), 256);
   pl.total = o;
   return pl;
 }
@@ -533,6 +578,7 @@ LayerDev to_dev(const dsvt_layer_w& w) {
   d.b_qkv = w.b_qkv; d.b_o = w.b_o; d.b_1 = w.b_1; d.b_2 = w.b_2;
   d.ln1_g = w.ln1_g; d.ln1_b = w.ln1_b; d.ln2_g = w.ln2_g; d.ln2_b = w.ln2_b;
   d.rel_bias = w.rel_bias ? reinterpret_cast<const float*>(pk + pl.off[4]) : nullptr;
+  d.gelu_tab = reinterpret_cast<const float2*>(pk + pl.off[5]);
   d.ln_eps = w.ln_eps; d.dup_mode = w.dup_mode;
   const int my = 2 * w.win[1] - 1, mz = 2 * w.win[2] - 1;
   d.rel_my = my; d.rel_mz = mz;
@@ -639,6 +685,8 @@ extern "C" int dsvt_layer_pack(const dsvt_layer_w* layer, void* packed, size_t b
                                                                        reinterpret_cast<float*>(dst), pl.out[i], pl.k[i]);
     }
   }
+  k_pack_gelu_table<<<(unsigned)dsvt_ceil_div(kGeluKnots, 256), 256, 0, st>>>(
+      reinterpret_cast<float2*>(reinterpret_cast<char*>(packed) + pl.off[5]));
   if (layer->rel_bias != nullptr) {
     const int n = pl.rel_size * layer->heads;
     k_pack_table<<<(unsigned)dsvt_ceil_div(n, 256), 256, 0, st>>>(
