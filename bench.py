@@ -15,6 +15,12 @@ import time
 import numpy as np
 
 
+# HBM bytes one launch of the layer kernel moves on this workload, from rocprofv3 FETCH_SIZE and
+# WRITE_SIZE (KiB per dispatch, each scaled by its reading for a plain 256 MiB copy); the
+# measurement and its commands are in profiles/hbm_traffic_pillar_frame.md.
+LAYER_HBM_BYTES_PER_LAUNCH = 33962 * 1024      # 19,253 KiB fetched + 14,709 KiB written
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -22,6 +28,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of a captured HIP graph")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run one plain 256 MiB device copy (a kernel of known traffic, to scale rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU by design (frames shard across GPUs with no communication); "
@@ -73,6 +82,13 @@ def main():
                 joined.add(sh)
             dsvt.dsvt_block(pair, maps[sh], cd, src, x_out=buf, ws=ws)
             src = buf
+
+    if args.pmc_calibration:
+        cal_src = torch.zeros(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
+        cal_dst = torch.empty_like(cal_src)
+        cal_dst.copy_(cal_src)
+        torch.cuda.synchronize()
+        del cal_src, cal_dst
 
     step()
     torch.cuda.synchronize()
@@ -129,7 +145,7 @@ def main():
     achieved = flops[dom] / (per_launch_us[dom] * 1e-6) / 1e12
     peak = 2500.0
     roofline = {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s",
-                "frac": round(achieved / peak, 5), "traffic": None,
+                "frac": round(achieved / peak, 5), "traffic": LAYER_HBM_BYTES_PER_LAUNCH,
                 "avg_launch_us": round(per_launch_us[dom], 2), "flops_per_launch": flops[dom]}
 
     cpu = None
