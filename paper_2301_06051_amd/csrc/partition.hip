@@ -12,6 +12,7 @@
 namespace {
 
 constexpr uint32_t kBadKey = 0xFFFFFFFFu;
+constexpr int64_t kFusedThreads = 32 * 1024;     // window-count work (windows x lanes per window) one workgroup takes on itself
 
 struct PartGeom {
   int32_t grid[3], win[3], shift[3], nw[3];
@@ -54,10 +55,9 @@ __global__ void k_mark(PartGeom g, const int4* __restrict__ coords, int32_t n, u
 
 // `group` lanes (a power of two <= 64) per window: pop-count the window's words, leave in
 // word_prefix[] the number of set bits in the window's earlier words, and the window total.
-__global__ void k_window_count(const uint32_t* __restrict__ bitmap, uint32_t* __restrict__ word_prefix,
-                               int32_t* __restrict__ win_count, int32_t n_windows, int32_t words_per_win,
-                               int32_t group) {
-  int32_t tid = blockIdx.x * blockDim.x + threadIdx.x;
+__device__ __forceinline__ void window_count(int32_t tid, const uint32_t* __restrict__ bitmap,
+                                             uint32_t* __restrict__ word_prefix, int32_t* __restrict__ win_count,
+                                             int32_t n_windows, int32_t words_per_win, int32_t group) {
   int32_t w = tid / group, lane = tid & (group - 1);
   if (w >= n_windows) return;               // whole groups leave together
   const int64_t base = (int64_t)w * words_per_win;
@@ -76,12 +76,17 @@ __global__ void k_window_count(const uint32_t* __restrict__ bitmap, uint32_t* __
   if (lane == 0) win_count[w] = (int32_t)running;
 }
 
+__global__ void k_window_count(const uint32_t* __restrict__ bitmap, uint32_t* __restrict__ word_prefix,
+                               int32_t* __restrict__ win_count, int32_t n_windows, int32_t words_per_win,
+                               int32_t group) {
+  window_count(blockIdx.x * blockDim.x + threadIdx.x, bitmap, word_prefix, win_count, n_windows, words_per_win, group);
+}
+
 // One workgroup: exclusive scans of voxels-per-window and sets-per-window (Eq. 2).
-__global__ void __launch_bounds__(1024) k_scan_windows(const int32_t* __restrict__ win_count,
-                                                       int32_t* __restrict__ win_soff, int32_t n_windows,
-                                                       int32_t tau, int32_t max_sets, int32_t* __restrict__ n_sets,
-                                                       int32_t* __restrict__ status, int32_t* __restrict__ set_w,
-                                                       int32_t set_cap) {
+__device__ __forceinline__ void scan_windows(const int32_t* __restrict__ win_count, int32_t* __restrict__ win_soff,
+                                             int32_t n_windows, int32_t tau, int32_t max_sets,
+                                             int32_t* __restrict__ n_sets, int32_t* __restrict__ status,
+                                             int32_t* __restrict__ set_w, int32_t set_cap) {
   __shared__ int32_t wave_tot[16];
   __shared__ int32_t carry_s;
   const int32_t tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
@@ -115,6 +120,14 @@ __global__ void __launch_bounds__(1024) k_scan_windows(const int32_t* __restrict
   }
 }
 
+__global__ void __launch_bounds__(1024) k_scan_windows(const int32_t* __restrict__ win_count,
+                                                       int32_t* __restrict__ win_soff, int32_t n_windows,
+                                                       int32_t tau, int32_t max_sets, int32_t* __restrict__ n_sets,
+                                                       int32_t* __restrict__ status, int32_t* __restrict__ set_w,
+                                                       int32_t set_cap) {
+  scan_windows(win_count, win_soff, n_windows, tau, max_sets, n_sets, status, set_w, set_cap);
+}
+
 // Tile descriptor, one per workgroup tile of the layer kernels, in launch order (256 ints):
 //   [0] rows R (sets padded to multiples of 4)   [1] sets ns
 //   [2 + s] first row of set s                    [2 + 24 + s] distinct voxels of set s   (s < ns <= 24)
@@ -124,6 +137,10 @@ constexpr int kTileRows = 96;
 
 // Distinct voxels of the j-th set of a window with N voxels in S sets (closed form from Eq. 3).
 __device__ __forceinline__ int32_t set_distinct(int64_t N, int64_t S, int64_t j, int64_t tau) {
+  if (N < 32768 && S * tau < 65536) {                       // the usual case: everything fits 32-bit division
+    const uint32_t n = (uint32_t)N, T = (uint32_t)(S * tau), a = (uint32_t)(j * tau);
+    return (int32_t)(((a + (uint32_t)tau - 1u) * n) / T - (a * n) / T + 1u);
+  }
   const int64_t lo = (j * tau * N) / (S * tau), hi = ((j * tau + tau - 1) * N) / (S * tau);
   return (int32_t)(hi - lo + 1);
 }
@@ -137,11 +154,10 @@ struct TileOut {                       // all null when the caller wants no work
 // and write the descriptor headers.  With P(s) the running sum of padded rows before set s, set s
 // goes to tile P(s) / rows_per_cut; a tile then holds at most rows_per_cut - 4 + pad4(tau) rows and
 // no tile is empty.  set_loc[s] = (descriptor slot << 7) | first row, for k_emit.
-__global__ void __launch_bounds__(1024) k_tiles(const int32_t* __restrict__ set_w, const int32_t* __restrict__ win_count,
-                                                const int32_t* __restrict__ win_soff, const int32_t* __restrict__ n_sets_ptr,
-                                                int32_t set_cap, int32_t tau, int32_t n_windows, int32_t rows_per_cut,
-                                                TileOut out, int32_t* __restrict__ tile_rows, int32_t* __restrict__ tile_pos,
-                                                int32_t* __restrict__ set_p, int32_t* __restrict__ set_loc) {
+__device__ __forceinline__ void build_tiles(const int32_t* set_w, const int32_t* win_count, const int32_t* win_soff,
+                                            const int32_t* n_sets_ptr, int32_t set_cap, int32_t tau, int32_t n_windows,
+                                            int32_t rows_per_cut, TileOut out, int32_t* tile_rows, int32_t* tile_pos,
+                                            int32_t* set_p, int32_t* set_loc) {
   __shared__ int32_t wave_tot[16];
   __shared__ int32_t carry_s;
   __shared__ int32_t hist[32], running[32], wave_cnt[16][32];
@@ -269,6 +285,54 @@ __global__ void __launch_bounds__(1024) k_tiles(const int32_t* __restrict__ set_
   }
 }
 
+__global__ void __launch_bounds__(1024) k_tiles(const int32_t* set_w, const int32_t* win_count, const int32_t* win_soff,
+                                                const int32_t* n_sets_ptr, int32_t set_cap, int32_t tau, int32_t n_windows,
+                                                int32_t rows_per_cut, TileOut out, int32_t* tile_rows, int32_t* tile_pos,
+                                                int32_t* set_p, int32_t* set_loc) {
+  build_tiles(set_w, win_count, win_soff, n_sets_ptr, set_cap, tau, n_windows, rows_per_cut, out, tile_rows, tile_pos, set_p,
+              set_loc);
+}
+
+// Small frames: the three steps between k_mark and k_emit in one workgroup and one launch (each is a
+// few microseconds of work; as separate launches their start-up and the gaps between them are most
+// of a partition's latency, which the first layer of a frame has to wait for).
+__global__ void __launch_bounds__(1024) k_count_scan_tiles(const uint32_t* bitmap, uint32_t* word_prefix, int32_t* win_count,
+                                                           int32_t* win_soff, int32_t n_windows, int32_t words_per_win,
+                                                           int32_t group, int32_t tau, int32_t max_sets, int32_t* n_sets,
+                                                           int32_t* status, int32_t* set_w, int32_t set_bound,
+                                                           int32_t set_cap, int32_t rows_per_cut, TileOut out,
+                                                           int32_t* tile_rows, int32_t* tile_pos, int32_t* set_p,
+                                                           int32_t* set_loc) {
+  if (words_per_win <= 8) {
+    // a thread per window: its few words are independent loads, the prefix a short serial sum
+    for (int32_t w = threadIdx.x; w < n_windows; w += 1024) {
+      const int64_t base = (int64_t)w * words_per_win;
+      uint32_t v[8];
+#pragma unroll
+      for (int32_t j = 0; j < 8; ++j) v[j] = j < words_per_win ? bitmap[base + j] : 0u;
+      uint32_t running = 0;
+#pragma unroll
+      for (int32_t j = 0; j < 8; ++j) {
+        if (j < words_per_win) word_prefix[base + j] = running;
+        running += (uint32_t)__popc(v[j]);
+      }
+      win_count[w] = (int32_t)running;
+    }
+  } else {
+    const int64_t n_threads = (int64_t)n_windows * group;
+    for (int64_t base = 0; base < n_threads; base += 1024)      // 1024 is a multiple of every group size
+      window_count((int32_t)(base + threadIdx.x), bitmap, word_prefix, win_count, n_windows, words_per_win, group);
+  }
+  __threadfence_block();
+  __syncthreads();
+  scan_windows(win_count, win_soff, n_windows, tau, max_sets, n_sets, status, set_w, set_bound);
+  __threadfence_block();
+  __syncthreads();
+  if (out.tile_desc != nullptr)
+    build_tiles(set_w, win_count, win_soff, n_sets, set_cap, tau, n_windows, rows_per_cut, out, tile_rows, tile_pos, set_p,
+                set_loc);
+}
+
 // One thread per voxel: rank d inside its window, then the slots t with floor(t*N/(S*tau)) == d;
 // with a work list also the voxel's row of its tile descriptor.
 __global__ void k_emit(PartGeom g, const int4* __restrict__ coords, const uint32_t* __restrict__ keys, int32_t n,
@@ -286,20 +350,31 @@ __global__ void k_emit(PartGeom g, const int4* __restrict__ coords, const uint32
   int64_t d = word_prefix[word] + (uint32_t)__popc(bitmap[word] & ((1u << bit) - 1u));
   int64_t N = win_count[w];
   int64_t S = (N + tau - 1) / tau, T = S * tau;
-  int64_t t_lo = (d * T + N - 1) / N, t_hi = ((d + 1) * T + N - 1) / N;
+  int64_t t_lo, t_hi, first_d;                               // first_d: rank of the first voxel of this voxel's first set
+  if (N > 0 && N < 32768 && T < 65536) {                     // the usual case: 32-bit division
+    const uint32_t n = (uint32_t)N, tt = (uint32_t)T, dd = (uint32_t)d;
+    const uint32_t lo = (dd * tt + n - 1u) / n, hi = ((dd + 1u) * tt + n - 1u) / n;
+    t_lo = lo; t_hi = hi;
+    first_d = ((lo / (uint32_t)tau) * (uint32_t)tau * n) / tt;
+  } else {
+    t_lo = (d * T + N - 1) / N; t_hi = ((d + 1) * T + N - 1) / N;
+    first_d = ((t_lo / tau) * tau * N) / T;
+  }
   int64_t base = (int64_t)win_soff[w] * tau, cap = (int64_t)max_sets * tau;
   voxel_slot[i] = (int32_t)(base + t_lo);
-  for (int64_t t = t_lo; t < t_hi; ++t) {
-    int64_t slot = base + t;
+  const int32_t j_first = (int32_t)t_lo / tau;               // (t < S * tau and slots < max_sets * tau fit 32 bits)
+  int32_t next_set_start = (int32_t)t_lo == j_first * tau ? (int32_t)t_lo : (j_first + 1) * tau;
+  for (int32_t t = (int32_t)t_lo; t < (int32_t)t_hi; ++t) {
+    const int64_t slot = base + t;
     if (slot >= cap) break;
     set_inds[slot] = i;
-    if (t % tau == 0) set_win[slot / tau] = w;
+    if (t == next_set_start) { set_win[win_soff[w] + t / tau] = w; next_set_start += tau; }
   }
   if (tile_desc != nullptr) {
-    const int64_t j = t_lo / tau, s = win_soff[w] + j;
+    const int64_t j = j_first, s = win_soff[w] + j;
     if (s < max_sets) {
       const int32_t loc = set_loc[s];
-      const int32_t slot = loc >> 7, row = (loc & 127) + (int32_t)(d - (j * tau * N) / T);
+      const int32_t slot = loc >> 7, row = (loc & 127) + (int32_t)(d - first_d);
       if (slot >= 0 && slot < n_desc_slots && row < kTileRows) {
         const int4 c = coords[i];
         const int32_t lin = (c.y * (2 * g.win[1] - 1) + c.z) * (2 * g.win[2] - 1) + c.w;
@@ -417,22 +492,30 @@ extern "C" int dsvt_partition(const dsvt_part_cfg* cfg, const int32_t* coords, i
   }
   int32_t group = 1;
   while (group < 64 && group < p.g.words_per_win) group <<= 1;
-  {
-    dsvt_prof_scope ps(DSVT_K_PART_COUNT, st);
-    int64_t threads = (int64_t)p.g.n_windows * group;
-    k_window_count<<<(unsigned)dsvt_ceil_div(threads, tb), tb, 0, st>>>(bitmap, prefix, count, p.g.n_windows,
-                                                                        p.g.words_per_win, group);
-  }
-  {
-    dsvt_prof_scope ps(DSVT_K_PART_SCAN, st);
-    k_scan_windows<<<1, 1024, 0, st>>>(count, soff, p.g.n_windows, cfg->tau, max_sets, n_sets, status,
-                                       (int32_t*)(base + p.off_setwin), p.set_bound);
-  }
-  if (tiles != nullptr) {
+  if ((int64_t)p.g.n_windows * group <= kFusedThreads) {
     dsvt_prof_scope ps(DSVT_K_PART_TILES, st);
-    k_tiles<<<1, 1024, 0, st>>>((const int32_t*)(base + p.off_setwin), count, soff, n_sets, set_cap, cfg->tau,
-                                p.g.n_windows, p.rows_per_cut, tout, (int32_t*)(base + p.off_tilerows),
-                                (int32_t*)(base + p.off_tilepos), (int32_t*)(base + p.off_setp), set_loc);
+    k_count_scan_tiles<<<1, 1024, 0, st>>>(bitmap, prefix, count, soff, p.g.n_windows, p.g.words_per_win, group, cfg->tau,
+                                           max_sets, n_sets, status, (int32_t*)(base + p.off_setwin), p.set_bound, set_cap,
+                                           p.rows_per_cut, tout, (int32_t*)(base + p.off_tilerows),
+                                           (int32_t*)(base + p.off_tilepos), (int32_t*)(base + p.off_setp), set_loc);
+  } else {
+    {
+      dsvt_prof_scope ps(DSVT_K_PART_COUNT, st);
+      int64_t threads = (int64_t)p.g.n_windows * group;
+      k_window_count<<<(unsigned)dsvt_ceil_div(threads, tb), tb, 0, st>>>(bitmap, prefix, count, p.g.n_windows,
+                                                                          p.g.words_per_win, group);
+    }
+    {
+      dsvt_prof_scope ps(DSVT_K_PART_SCAN, st);
+      k_scan_windows<<<1, 1024, 0, st>>>(count, soff, p.g.n_windows, cfg->tau, max_sets, n_sets, status,
+                                         (int32_t*)(base + p.off_setwin), p.set_bound);
+    }
+    if (tiles != nullptr) {
+      dsvt_prof_scope ps(DSVT_K_PART_TILES, st);
+      k_tiles<<<1, 1024, 0, st>>>((const int32_t*)(base + p.off_setwin), count, soff, n_sets, set_cap, cfg->tau,
+                                  p.g.n_windows, p.rows_per_cut, tout, (int32_t*)(base + p.off_tilerows),
+                                  (int32_t*)(base + p.off_tilepos), (int32_t*)(base + p.off_setp), set_loc);
+    }
   }
   {
     dsvt_prof_scope ps(DSVT_K_PART_EMIT, st);
