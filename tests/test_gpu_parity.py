@@ -341,3 +341,41 @@ def test_width_128_large_window():
     _say(f"  block rel err {err:.3e}")
     assert err < TOL["bf16"]
     assert m == len(rc_) and np.array_equal(oc[:m].cpu().numpy(), rc_) and rel_err(po[:m], rp) < TOL["bf16"]
+
+
+def test_dsvt_v_four_stages():
+    """The voxel variant's stage layout (appendix "Network Architecture": four stages, one block each here,
+    windows 12 x 12 x {32, 8, 2, 1}, tau = 48, attention-style pooling by {4, 4, 2} along z between stages),
+    chained end to end: every stage's maps and pooled coordinates bit-exact, the last stage's features in
+    tolerance.  The oracle rounds the features to bf16 where the GPU path stores them (after each call)."""
+    C, heads, hidden, tau = 192, 8, 384, 48
+    grid0 = (96, 96, 32)
+    coords = np.concatenate([np.zeros((5000, 1), np.int64), synth.frame_radial(311, grid0, 5000)], 1).astype(np.int32)
+    x = synth.make_features(312, len(coords), C, "bf16")
+    zs, strides = [32, 8, 2, 1], [4, 4, 2]
+    _say("DSVT-V stage chain: 4 blocks, 3 poolings")
+    ref_c, ref_x = coords, x
+    cd, xd = dev_coords(coords), dev_feats(x, "bf16")
+    for st, z in enumerate(zs):
+        grid, win, shift = (96, 96, z), (12, 12, z), ((0, 0, 0) if st % 2 == 0 else (6, 6, 0))
+        ws = [synth.make_layer_weights(320 + 2 * st + a, C, heads, hidden, win, "bf16") for a in (0, 1)]
+        oms = [orc.partition(ref_c, grid, win, shift, tau, a) for a in (0, 1)]
+        ref_x = synth.round_bf16(orc.block(ws, oms, ref_c, ref_x).astype(np.float32))
+        gms = [gpu_maps(cd, grid, win, shift, tau, 1, a) for a in (0, 1)]
+        for gm, om in zip(gms, oms):
+            assert_maps_equal(gm, om)
+        xd = dsvt.dsvt_block([dsvt.LayerWeights(w) for w in ws], gms, cd, xd)
+        torch.cuda.synchronize()
+        err = rel_err(xd, ref_x)
+        _say(f"  stage {st} (z = {z}, {len(ref_c)} voxels): block rel err {err:.3e}")
+        assert err < TOL["bf16"]
+        if st < len(strides):
+            pool = (1, 1, strides[st])
+            pw = synth.make_pool_weights(340 + st, C, heads, "bf16")
+            ref_c, ref_p = orc.attn_pool(pw, ref_c, ref_x, grid, pool, 1)
+            ref_x = synth.round_bf16(ref_p.astype(np.float32))
+            oc, po, n_out, _ = dsvt.dsvt_attn_pool(dsvt.PoolWeights(pw, grid, pool, 1, 1), cd, xd)
+            m = int(n_out.item())
+            assert m == len(ref_c) and np.array_equal(oc[:m].cpu().numpy(), ref_c)
+            cd, xd = oc[:m].contiguous(), po[:m].contiguous()
+            assert rel_err(xd, ref_x) < TOL["bf16"]
