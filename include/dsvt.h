@@ -64,7 +64,7 @@ int dsvt_partition_bound(const dsvt_part_cfg* cfg, int32_t n_voxels, int32_t* ma
  *                                [26+s] distinct voxels of its s-th set, [64+r] voxel of row r (-1 =
  *                                padding), [160+r] (slots holding that voxel << 24) | position code
  *                                (x*(2W-1) + y)*(2H-1) + z
- * Needs tau <= 48 and grid[0]*(2W-1)*(2H-1) < 2^24. */
+ * Needs tau <= 96 and grid[0]*(2W-1)*(2H-1) < 2^24. */
 typedef struct {
   int32_t max_tiles;
   int32_t *tile_first, *n_tiles, *tile_order, *tile_desc;
@@ -126,7 +126,7 @@ typedef struct {
 } dsvt_layer_w;
 
 /* Supported shapes: (C,heads,hidden) = (64,4,128) in F32 or BF16, (128,8,256) and (192,8,384) in BF16,
- * tau <= 48; anything else returns DSVT_EUNSUPPORTED. */
+ * tau <= 96 (<= 64 for maps without a tile list); anything else returns DSVT_EUNSUPPORTED. */
 
 /* Weight preparation, once per layer (weights do not change between frames).
  * dsvt_layer_packed_size: host-only, bytes of the packed buffer for this layer's shape.

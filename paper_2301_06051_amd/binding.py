@@ -133,7 +133,7 @@ class SetMaps:
         self.n_sets = torch.zeros((1,), **i32)
         self.status = torch.zeros((1,), **i32)
         self.ws = torch.empty((ws_bytes,), dtype=torch.uint8, device="cuda")
-        self.max_tiles = tile_bound if (tiles and tile_bound > 0 and cfg.tau <= 48) else 0
+        self.max_tiles = tile_bound if (tiles and tile_bound > 0 and cfg.tau <= 96) else 0
         if self.max_tiles:
             self.tile_first = torch.full((self.max_tiles + 1,), -1, **i32)
             self.n_tiles = torch.zeros((1,), **i32)

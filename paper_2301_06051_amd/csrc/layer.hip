@@ -15,11 +15,16 @@
 
 namespace {
 
-constexpr int kTauMax = 48;
+constexpr int kTauMax = 96;                     // a set's distinct voxels must fit one tile
 constexpr int kMaxSets = kRowsMax / 4;           // every set takes at least 4 rows of a tile
 constexpr int kRowsPad = kRowsMax + 16;          // per-row arrays are read 4 at a time up to 15 rows past a set's end
-constexpr int kMaxItems = 2 * (kRowsMax / 16 + kMaxSets);   // attention items: (set, query tile, half of the heads)
-constexpr int kFixedSets = kRowsMax / kTauMax;   // sets per workgroup when no tile list is given
+constexpr int kMaxItems = 128;                  // attention items: (set, query tile, group of heads); see item_groups()
+// Sets per workgroup when no tile list is given.
+__host__ __device__ constexpr int fixed_sets(int tau) { return tau <= kRowsMax / 2 ? 2 : 1; }
+// A set of up to 3 key tiles (48 voxels) is split into items of half of the heads each; a larger one
+// (its logits take more registers) into one item per head.  At most one set of a tile is that large,
+// so a tile has at most 8 * 6 + 2 * (3 + 11) = 76 items.
+__host__ __device__ constexpr int item_groups(int kts, int heads) { return kts <= 3 ? 2 : heads; }
 constexpr int kHalfTiles = kRowTiles / 2;        // the LayerNorm-phase work items cover half of the row tiles
 constexpr int kLayerWaves = 12;                  // three per SIMD: one workgroup per CU (LDS), the other wavefronts hide one's waits
 
@@ -103,17 +108,17 @@ template <typename T, int C, int HEADS, int HID> struct LayerLds {
 // softmax reductions are in-lane plus two cross-lane steps, and P^T is already laid out as the B
 // operand of O^T = V^T P^T.  The positional term depends on (query, key) only through the
 // coordinate difference, i.e. one table row [idx][heads] per pair, fetched once for all heads.
-template <typename T, int C, int HEADS, int HID, int KTC>
+template <typename T, int C, int HEADS, int HID, int KTC, int HG>
 __device__ __forceinline__ void attn_item(const LayerDev& p, T* Qs, const T* Ks, const T* Vt, const int32_t* row_lin,
                                           const float* row_mult, int r0, int nu, int qt, int hh, int rows_ready) {
   typedef LayerLds<T, C, HEADS, HID> L;
   typedef Mma<T> M;
   typedef typename M::Frag Frag;
   typedef typename M::Vec4 Vec4;
-  constexpr int D = L::D, LDX = L::LDX, LDV = L::LDV, KC = M::KC, KL = M::KL, HG = HEADS / 2;
+  constexpr int D = L::D, LDX = L::LDX, LDV = L::LDV, KC = M::KC, KL = M::KL;
   constexpr int TPC = KC / 16;                    // key tiles per PV fragment: 2 (bf16) or 1 (fp32)
   constexpr int NCH = (KTC + TPC - 1) / TPC;
-  static_assert(HG == 2 || HG == 4, "heads per item");
+  static_assert(HG == 1 || HG == 2 || HG == 4, "heads per item");
   const int lane = threadIdx.x & 63, m = lane & 15, g = lane >> 4;
   const int qi = 16 * qt + m;
   const int qrow = r0 + (qi < nu ? qi : nu - 1);
@@ -144,9 +149,11 @@ __device__ __forceinline__ void attn_item(const LayerDev& p, T* Qs, const T* Ks,
         if constexpr (HG == 4) {
           const f32x4 t = *reinterpret_cast<const f32x4*>(tp);
           bias[kt][i][0] = t[0]; bias[kt][i][1] = t[1]; bias[kt][i][2] = t[2]; bias[kt][i][3] = t[3];
-        } else {
+        } else if constexpr (HG == 2) {
           const float2 t = *reinterpret_cast<const float2*>(tp);
           bias[kt][i][0] = t.x; bias[kt][i][1] = t.y;
+        } else {
+          bias[kt][i][0] = *tp;
         }
       }
     }
@@ -240,7 +247,8 @@ __device__ __forceinline__ void attn_item(const LayerDev& p, T* Qs, const T* Ks,
   }
 }
 
-template <typename T, int C, int HEADS, int HID, int NT_QKV, int NT_O, int NT_1, int NT_2>
+// BIG: the instantiation for tau > 48 (sets of four to six key tiles); the common one does not carry that code.
+template <typename T, int C, int HEADS, int HID, int NT_QKV, int NT_O, int NT_1, int NT_2, bool BIG>
 __global__ void __launch_bounds__(kLayerWaves * 64)
 k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* out, int full_layer) {
   // out may be x: a tile's rows are read, then written, by this workgroup only
@@ -289,17 +297,20 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
       hdr_rows = hdr_rows < 0 ? 0 : (hdr_rows > kRowsMax ? kRowsMax : hdr_rows);
       if (lane == 0) { set_nu[kMaxSets] = hdr_ns; set_r0[hdr_ns] = hdr_rows; }
       if (lane >= 2 && lane < 2 + kMaxSets && lane - 2 < hdr_ns) set_r0[lane - 2] = word < 0 ? 0 : (word > kRowsMax - 4 ? kRowsMax - 4 : word);
-      const int nu_s = word < 1 ? 1 : (word > kTauMax ? kTauMax : word);
+      constexpr int kNuMax = BIG ? kTauMax : 48;
+      const int nu_s = word < 1 ? 1 : (word > kNuMax ? kNuMax : word);
       const int ls = lane - 2 - kMaxSets;        // the lanes holding the sets' sizes also list the sets' attention items
       if (ls >= 0 && ls < kMaxSets) set_nu[ls] = nu_s;
       const int kts = (ls >= 0 && ls < hdr_ns) ? (nu_s + 15) >> 4 : 0;
-      int incl = 2 * kts;                        // items: (set, query tile, half of the heads)
+      const int ngr = item_groups(kts, HEADS);
+      int incl = ngr * kts;                      // items: (set, query tile, group of heads)
 #pragma unroll
       for (int o = 1; o < 64; o <<= 1) { const int t = __shfl_up(incl, o, 64); if (lane >= o) incl += t; }
-      int n = incl - 2 * kts;
+      int n = incl - ngr * kts;
       for (int qt = 0; qt < kts; ++qt)
-        for (int hh = 0; hh < 2; ++hh) items[n++] = ls | (qt << 8) | (hh << 12) | (kts << 16);
-      if (lane == 63) items[kMaxItems] = incl;   // published by the barrier below
+        for (int hh = 0; hh < ngr; ++hh)
+          if (n < kMaxItems) items[n++] = ls | (qt << 8) | (hh << 12) | (kts << 16);
+      if (lane == 63) items[kMaxItems] = incl < kMaxItems ? incl : kMaxItems;   // published by the barrier below
     } else if (tid >= 64 && tid < 64 + kRowsMax) {
       row_vox[tid - 64] = (word >= 0 && word < mp.n_voxels) ? word : -1;
     } else if (tid >= 160 && tid < 160 + kRowsMax) {
@@ -313,8 +324,9 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
     // ---- 1b. no work list: two sets per workgroup, rows derived from set_inds and coords
     int n_sets = *mp.n_sets;
     n_sets = n_sets < mp.max_sets ? n_sets : mp.max_sets;
-    const int s_begin = blockIdx.x * kFixedSets;
-    ns = __builtin_amdgcn_readfirstlane((n_sets - s_begin) < kFixedSets ? (n_sets - s_begin) : kFixedSets);
+    const int per_wg = fixed_sets(mp.tau);
+    const int s_begin = blockIdx.x * per_wg;
+    ns = __builtin_amdgcn_readfirstlane((n_sets - s_begin) < per_wg ? (n_sets - s_begin) : per_wg);
     if (ns <= 0) return;
     const int tau = mp.tau;
     for (int r = tid; r < kRowsPad; r += NTHREADS) { row_vox[r] = -1; row_lin[r] = 0; row_mult[r] = 0.f; }
@@ -332,7 +344,8 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
         set_r0[s] = r; r += (set_nu[s] + 3) & ~3;
         const int kts = (set_nu[s] + 15) >> 4;
         for (int qt = 0; qt < kts; ++qt)
-          for (int hh = 0; hh < 2; ++hh) items[n++] = s | (qt << 8) | (hh << 12) | (kts << 16);
+          for (int hh = 0; hh < item_groups(kts, HEADS); ++hh)
+            if (n < kMaxItems) items[n++] = s | (qt << 8) | (hh << 12) | (kts << 16);
       }
       set_r0[ns] = r;
       items[kMaxItems] = n;
@@ -429,11 +442,17 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
     const int n_items = __builtin_amdgcn_readfirstlane(items[kMaxItems]);
     for (int it = wave; it < n_items; it += NW) {
       const int d = __builtin_amdgcn_readfirstlane(items[it]);
-      const int s = d & 255, qt = (d >> 8) & 15, hh = (d >> 12) & 1, kts = d >> 16;
+      const int s = d & 255, qt = (d >> 8) & 15, hh = (d >> 12) & 15, kts = d >> 16;
+      constexpr int HG2 = HEADS / 2;
       const int r0 = __builtin_amdgcn_readfirstlane(set_r0[s]), nu = __builtin_amdgcn_readfirstlane(set_nu[s]);
-      if (kts == 1) attn_item<T, C, HEADS, HID, 1>(p, Qs, Ks, Vt, row_lin, row_mult, r0, nu, qt, hh, RT * 16);
-      else if (kts == 2) attn_item<T, C, HEADS, HID, 2>(p, Qs, Ks, Vt, row_lin, row_mult, r0, nu, qt, hh, RT * 16);
-      else attn_item<T, C, HEADS, HID, 3>(p, Qs, Ks, Vt, row_lin, row_mult, r0, nu, qt, hh, RT * 16);
+      if (kts == 1) attn_item<T, C, HEADS, HID, 1, HG2>(p, Qs, Ks, Vt, row_lin, row_mult, r0, nu, qt, hh, RT * 16);
+      else if (kts == 2) attn_item<T, C, HEADS, HID, 2, HG2>(p, Qs, Ks, Vt, row_lin, row_mult, r0, nu, qt, hh, RT * 16);
+      else if (!BIG || kts == 3) attn_item<T, C, HEADS, HID, 3, HG2>(p, Qs, Ks, Vt, row_lin, row_mult, r0, nu, qt, hh, RT * 16);
+      else if constexpr (BIG) {
+        if (kts == 4) attn_item<T, C, HEADS, HID, 4, 1>(p, Qs, Ks, Vt, row_lin, row_mult, r0, nu, qt, hh, RT * 16);
+        else if (kts == 5) attn_item<T, C, HEADS, HID, 5, 1>(p, Qs, Ks, Vt, row_lin, row_mult, r0, nu, qt, hh, RT * 16);
+        else attn_item<T, C, HEADS, HID, 6, 1>(p, Qs, Ks, Vt, row_lin, row_mult, r0, nu, qt, hh, RT * 16);
+      }
     }
   }
   f32x4 bo4[NT_O];
@@ -611,6 +630,7 @@ int check_layer(const dsvt_layer_w& w, bool need_mlp, bool need_packed = true) {
 int check_maps(const dsvt_maps& mp) {
   if (!mp.set_inds || !mp.n_sets || mp.n_voxels <= 0 || mp.max_sets <= 0 || mp.tau <= 0) return DSVT_EINVAL;
   if (mp.tau > kTauMax) return DSVT_EUNSUPPORTED;
+  if (mp.tiles.tile_desc == nullptr && mp.tau > 64) return DSVT_EUNSUPPORTED;   // without a work list a wavefront scans a set's tau slots
   const dsvt_tile_list& tl = mp.tiles;
   const bool any = tl.tile_first || tl.n_tiles || tl.tile_order || tl.tile_desc;
   const bool all = tl.tile_first && tl.n_tiles && tl.tile_order && tl.tile_desc;
@@ -624,21 +644,28 @@ template <typename K> int allow_lds(K kernel, size_t bytes) {
   return DSVT_OK;
 }
 
-template <typename T, int C, int HEADS, int HID, int NT_QKV, int NT_O, int NT_1, int NT_2>
-int launch_layer(const dsvt_layer_w& w, const dsvt_maps& mp, const int32_t* coords, const void* x, void* out, int full,
-                 hipStream_t st) {
-  auto kern = k_layer<T, C, HEADS, HID, NT_QKV, NT_O, NT_1, NT_2>;
+template <typename T, int C, int HEADS, int HID, int NT_QKV, int NT_O, int NT_1, int NT_2, bool BIG>
+int launch_layer_v(const dsvt_layer_w& w, const dsvt_maps& mp, const int32_t* coords, const void* x, void* out, int full,
+                   hipStream_t st) {
+  auto kern = k_layer<T, C, HEADS, HID, NT_QKV, NT_O, NT_1, NT_2, BIG>;
   constexpr size_t lds = LayerLds<T, C, HEADS, HID>::total;
   static int prepared = allow_lds(kern, lds);
   if (prepared != DSVT_OK) return prepared;
   MapsDev md;
   md.set_inds = mp.set_inds; md.n_sets = mp.n_sets; md.n_tiles = mp.tiles.n_tiles; md.tile_desc = mp.tiles.tile_desc;
   md.max_sets = mp.max_sets; md.tau = mp.tau; md.n_voxels = mp.n_voxels;
-  const unsigned grid = mp.tiles.tile_desc ? (unsigned)mp.tiles.max_tiles : (unsigned)dsvt_ceil_div(mp.max_sets, kFixedSets);
+  const unsigned grid = mp.tiles.tile_desc ? (unsigned)mp.tiles.max_tiles : (unsigned)dsvt_ceil_div(mp.max_sets, fixed_sets(mp.tau));
   dsvt_prof_scope ps(DSVT_K_LAYER, st);
   kern<<<grid, kLayerWaves * 64, lds, st>>>(to_dev(w), md, reinterpret_cast<const int4*>(coords),
                                        reinterpret_cast<const T*>(x), reinterpret_cast<T*>(out), full);
   return DSVT_OK;
+}
+
+template <typename T, int C, int HEADS, int HID, int NT_QKV, int NT_O, int NT_1, int NT_2>
+int launch_layer(const dsvt_layer_w& w, const dsvt_maps& mp, const int32_t* coords, const void* x, void* out, int full,
+                 hipStream_t st) {
+  if (mp.tau > 48) return launch_layer_v<T, C, HEADS, HID, NT_QKV, NT_O, NT_1, NT_2, true>(w, mp, coords, x, out, full, st);
+  return launch_layer_v<T, C, HEADS, HID, NT_QKV, NT_O, NT_1, NT_2, false>(w, mp, coords, x, out, full, st);
 }
 
 int run_layer(const dsvt_layer_w& w, const dsvt_maps& mp, const int32_t* coords, const void* x, void* out, int full,

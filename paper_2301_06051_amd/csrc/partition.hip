@@ -152,8 +152,8 @@ struct TileOut {                       // all null when the caller wants no work
 
 // One workgroup: cut the set sequence into tiles for the layer kernels, order the tiles for launch
 // and write the descriptor headers.  With P(s) the running sum of padded rows before set s, set s
-// goes to tile P(s) / rows_per_cut; a tile then holds at most rows_per_cut - 4 + pad4(tau) rows and
-// no tile is empty.  set_loc[s] = (descriptor slot << 7) | first row, for k_emit.
+// starts a tile when P crosses a multiple of rows_per_cut; a tile then holds at most
+// rows_per_cut - 4 + pad4(tau) rows.  set_loc[s] = (descriptor slot << 7) | first row, for k_emit.
 __device__ __forceinline__ void build_tiles(const int32_t* set_w, const int32_t* win_count, const int32_t* win_soff,
                                             const int32_t* n_sets_ptr, int32_t set_cap, int32_t tau, int32_t n_windows,
                                             int32_t rows_per_cut, TileOut out, int32_t* tile_rows, int32_t* tile_pos,
@@ -200,12 +200,27 @@ __device__ __forceinline__ void build_tiles(const int32_t* set_w, const int32_t*
     if (tid == 1023) carry_s = before + incl;
     __syncthreads();
   }
-  // pass 2: tile boundaries (a set starts a tile when its predecessor is in another one)
+  // pass 2: tile boundaries.  A set starts a tile when the running row count crosses a multiple of
+  // rows_per_cut between its predecessor's start and its own; tiles are numbered by counting these
+  // starts (a scan), so none is empty even when one set is longer than rows_per_cut.  A tile then
+  // holds at most rows_per_cut - 4 + pad4(tau) <= 96 rows.
+  if (tid == 0) carry_s = 0;
+  __syncthreads();
   for (int32_t base = 0; base < n_sets; base += 1024) {
     const int32_t s = base + tid;
+    const bool first = s < n_sets && (s == 0 || set_p[s - 1] / rows_per_cut != set_p[s] / rows_per_cut);
+    int32_t incl = first ? 1 : 0;
+    for (int32_t d = 1; d < 64; d <<= 1) {
+      int32_t up = __shfl_up(incl, d, 64);
+      if (lane >= d) incl += up;
+    }
+    if (lane == 63) wave_tot[wv] = incl;
+    __syncthreads();
+    int32_t before = carry_s;
+    for (int32_t k = 0; k < wv; ++k) before += wave_tot[k];
+    const int32_t tile = before + incl - 1;                   // tile of set s
     if (s < n_sets) {
-      const int32_t tile = set_p[s] / rows_per_cut;
-      const bool first = s == 0 || set_p[s - 1] / rows_per_cut != tile;
+      set_loc[s] = tile;                                      // until pass 4 replaces it
       if (first && tile < out.max_tiles) { out.tile_first[tile] = s; tile_rows[tile] = set_p[s]; }
       if (s == n_sets - 1) {
         const int32_t nt = tile + 1 < out.max_tiles ? tile + 1 : out.max_tiles;
@@ -214,7 +229,11 @@ __device__ __forceinline__ void build_tiles(const int32_t* set_w, const int32_t*
         tile_rows[nt] = set_p[n_sets];
       }
     }
+    __syncthreads();
+    if (tid == 1023) carry_s = before + incl;
+    __syncthreads();
   }
+  __threadfence_block();
   __syncthreads();
   // pass 3: launch order = tiles with more rows first (a stable counting sort on rows / 4), so
   // that the short tiles fill the tail of the launch
@@ -268,8 +287,9 @@ __device__ __forceinline__ void build_tiles(const int32_t* set_w, const int32_t*
   for (int32_t base = 0; base < n_sets; base += 1024) {
     const int32_t s = base + tid;
     if (s < n_sets) {
-      const int32_t t = set_p[s] / rows_per_cut;
-      if (t < nt) {
+      const int32_t t = set_loc[s];
+      int32_t loc = -1;
+      if (t >= 0 && t < nt) {
         const int32_t pos = tile_pos[t], ls = s - out.tile_first[t], r0 = set_p[s] - tile_rows[t];
         int32_t w = set_w[s];
         w = w < 0 ? 0 : (w >= n_windows ? n_windows - 1 : w);
@@ -278,9 +298,10 @@ __device__ __forceinline__ void build_tiles(const int32_t* set_w, const int32_t*
           int32_t* d = out.tile_desc + (int64_t)pos * kDescInts;
           d[kDescR0 + ls] = r0;
           d[kDescNu + ls] = set_distinct(N, S, s - win_soff[w], tau);
-          set_loc[s] = (pos << 7) | r0;
+          loc = (pos << 7) | r0;
         }
       }
+      set_loc[s] = loc;
     }
   }
 }
@@ -432,7 +453,7 @@ int make_plan(const dsvt_part_cfg* cfg, int32_t n_voxels, PartPlan* p) {
   p->off_setp = o;     o = dsvt_align_up(o + (size_t)(bound + 1) * 4, 256);
   p->off_setloc = o;   o = dsvt_align_up(o + (size_t)(bound + 1) * 4, 256);
   // a descriptor packs (slot << 7 | row) and (multiplicity << 24 | position code) into 32 bits
-  p->desc_ok = p->rows_per_cut >= 48 && p->tile_bound < (1 << 23) &&
+  p->desc_ok = p->rows_per_cut >= 4 && p->tile_bound < (1 << 23) &&
                (int64_t)cfg->grid[0] * (2 * cfg->win[1] - 1) * (2 * cfg->win[2] - 1) < (1 << 24) && cfg->tau < 128;
   p->total = o;
   return DSVT_OK;

@@ -379,3 +379,29 @@ def test_dsvt_v_four_stages():
             assert m == len(ref_c) and np.array_equal(oc[:m].cpu().numpy(), ref_c)
             cd, xd = oc[:m].contiguous(), po[:m].contiguous()
             assert rel_err(xd, ref_x) < TOL["bf16"]
+
+
+@pytest.mark.parametrize("C,heads,hidden,win,tau,n", [(128, 8, 256, (30, 30, 1), 90, 9000), (192, 8, 384, (12, 12, 1), 60, 9000),
+                                                      (64, 4, 128, (12, 12, 1), 96, 9000)])
+def test_large_sets(C, heads, hidden, win, tau, n):
+    """Sets of more than 48 voxels (the nuScenes variant uses tau = 90 with 30 x 30 windows, appendix "3D
+    Perception on nuScenes"; the ablation on set size goes up to 60): a set then spans four to six key
+    tiles and is attended one head per work item."""
+    grid = (360, 360, 1) if win[0] == 30 else (96, 96, 1)
+    shift = (win[0] // 2, win[1] // 2, 0)
+    coords = np.concatenate([np.zeros((n, 1), np.int64), synth.frame_radial(400 + tau, grid, n)], 1).astype(np.int32)
+    x = synth.make_features(401 + tau, len(coords), C, "bf16")
+    ws = [synth.make_layer_weights(402 + a, C, heads, hidden, win, "bf16") for a in (0, 1)]
+    _say(f"C={C} window {win} tau={tau}")
+    oms = [orc.partition(coords, grid, win, shift, tau, a) for a in (0, 1)]
+    ref = orc.block(ws, oms, coords, x)
+    cd = dev_coords(coords)
+    gms = [gpu_maps(cd, grid, win, shift, tau, 1, a) for a in (0, 1)]
+    for gm, om in zip(gms, oms):
+        assert_maps_equal(gm, om)
+    out = dsvt.dsvt_block([dsvt.LayerWeights(w) for w in ws], gms, cd, dev_feats(x, "bf16"))
+    torch.cuda.synchronize()
+    err = rel_err(out, ref)
+    nu_max = max(int((np.diff(np.r_[om["set_inds"][s], -7]) != 0).sum()) for om in oms for s in range(0, om["n_sets"], 7))
+    _say(f"  rel err {err:.3e}; largest sampled set {nu_max} voxels")
+    assert err < TOL["bf16"]
