@@ -317,7 +317,7 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
       row_lin[tid - 160] = word & 0xFFFFFF;
       row_mult[tid - 160] = (float)((unsigned)word >> 24);
     }
-    __syncthreads();
+    lds_barrier();
     ns = __builtin_amdgcn_readfirstlane(set_nu[kMaxSets]);
     if (ns <= 0) return;
   } else {
@@ -337,7 +337,7 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
       const unsigned long long mask = __ballot(first);
       if (lane == 0) set_nu[ls] = __popcll(mask);
     }
-    __syncthreads();
+    lds_barrier();
     if (tid == 0) {
       int r = 0, n = 0;
       for (int s = 0; s < ns; ++s) {             // each set starts on a multiple of 4 rows
@@ -350,7 +350,7 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
       set_r0[ns] = r;
       items[kMaxItems] = n;
     }
-    __syncthreads();
+    lds_barrier();
     for (int ls = wave; ls < ns; ls += NW) {
       const int v = lane < tau ? mp.set_inds[(size_t)(s_begin + ls) * tau + lane] : -2;
       const int prev = __shfl_up(v, 1, 64);
@@ -366,7 +366,7 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
         row_lin[r] = (c.y * p.rel_my + c.z) * p.rel_mz + c.w;
       }
     }
-    __syncthreads();
+    lds_barrier();
   }
   const int R = __builtin_amdgcn_readfirstlane(set_r0[ns]);
   const int RT = (R + 15) >> 4;
@@ -398,7 +398,7 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
             live[k] ? gv[k] : make_uint4(0u, 0u, 0u, 0u);
     }
   }
-  __syncthreads();
+  lds_barrier();
   DSVT_CLK(2);
 
   // ---- 3. Q, K, V = X W^T + b; V stored transposed
@@ -434,7 +434,7 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
   const int og_own = wave % SG;
   const int rt_own = (wave / SG) * (RTK >> 1), HC = wave < 2 * SG ? RTK >> 1 : 0;   // HC = 0: a wavefront without an item
   const int o_own = og_own * 16 * NT_O;
-  __syncthreads();
+  lds_barrier();
   DSVT_CLK(3);
 
   // ---- 4. attention inside every set; O overwrites Q
@@ -458,7 +458,7 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
   f32x4 bo4[NT_O];
 #pragma unroll
   for (int nt = 0; nt < NT_O; ++nt) bo4[nt] = *reinterpret_cast<const f32x4*>(p.b_o + o_own + 16 * nt + 4 * g);
-  __syncthreads();
+  lds_barrier();
   DSVT_CLK(4);
   // attention is done with V^T: the GELU table of the MLP takes its place (published by the
   // barriers of the LayerNorm below)
@@ -469,10 +469,19 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
     reinterpret_cast<float4*>(smem + L::off_gelu)[tid] = reinterpret_cast<const float4*>(p.gelu_tab)[tid];
 
   // ---- 5. Y = O Wo^T + bo (+ x), then LayerNorm; result (or raw Y) replaces x in Xs
+  // The first MLP matrix is requested during this phase, by a third of the wavefronts at a time
+  // (before the projection, after it, after the residual): a CU takes a 16-byte load per
+  // wavefront every ~16 cycles, a wavefront waits until its requests are taken, and twelve
+  // wavefronts asking at once would all stand still for 3 k cycles.
+  GemmPhase<T, NT_1, C, HID, NW, 1, false> ffn1(reinterpret_cast<const T*>(p.w_1), wave);
+  const int pf_turn = full_layer ? wave / (NW / 3) : -1;
+  if (pf_turn == 0) ffn1.prefetch();
   f32x4 keep[NT_O][kHalfTiles];
   if (HC == 1) oproj.template run_keep<1>(Qs, LDX, rt_own, bo4, keep);
   else if (HC == 2) oproj.template run_keep<2>(Qs, LDX, rt_own, bo4, keep);
   else if (HC == 3) oproj.template run_keep<3>(Qs, LDX, rt_own, bo4, keep);
+  if (pf_turn == 1) ffn1.prefetch();
+  DSVT_CLK(13);
   f32x4 g1[NT_O], be1[NT_O];                       // fetched while the MFMAs above drain
 #pragma unroll
   for (int nt = 0; nt < NT_O; ++nt) {
@@ -495,10 +504,11 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
     }
   }
   if (full_layer) {
-    GemmPhase<T, NT_1, C, HID, NW, 1, false> ffn1(reinterpret_cast<const T*>(p.w_1), wave);
-    ffn1.prefetch();                             // in flight during the LayerNorm exchange
+    if (pf_turn == 2) ffn1.prefetch();
+    DSVT_CLK(14);
     layer_norm_tile<T, NT_O, C, kHalfTiles>(keep, o_own, og_own, rt_own, HC, stat, g1, be1, p.ln_eps, Xs, LDX);
-    __syncthreads();
+    DSVT_CLK(15);
+    lds_barrier();
     DSVT_CLK(5);
 
     // ---- 6. MLP: H = gelu(x1 W1^T + b1) over the dead Q/K tiles; x2 = LN(x1 + H W2^T + b2)
@@ -520,7 +530,7 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
     f32x4 b24[NT_2];
 #pragma unroll
     for (int nt = 0; nt < NT_2; ++nt) b24[nt] = *reinterpret_cast<const f32x4*>(p.b_2 + o_own2 + 16 * nt + 4 * g);
-    __syncthreads();
+    lds_barrier();
     DSVT_CLK(6);
     f32x4 keep2[NT_2][kHalfTiles];
     if (HC == 1) ffn2.template run_keep<1>(Hs, LDH, rt_own, b24, keep2);
@@ -545,7 +555,7 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
     }
     layer_norm_tile<T, NT_2, C, kHalfTiles>(keep2, o_own2, og_own, rt_own, HC, stat, g2, be2, p.ln_eps, Xs, LDX);
   }
-  __syncthreads();
+  lds_barrier();
   DSVT_CLK(7);
 
   // ---- 7. scatter: rows of Xs -> the voxels' rows of out, 16 bytes per thread

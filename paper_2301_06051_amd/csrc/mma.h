@@ -75,6 +75,14 @@ template <typename T> constexpr int lds_pad() { return 32 / (int)sizeof(T); }
 // of 64 bytes each, which the L1/L2 path serves about 3x slower).
 template <typename T> __host__ __device__ constexpr size_t packed_elems(int out, int k) { return (size_t)out * k; }
 
+// Workgroup barrier for data exchanged through LDS: waits for this wavefront's LDS operations
+// only.  __syncthreads() also drains the outstanding global loads (on this target loads and
+// stores share one counter, and its release fence waits for stores), which would turn every
+// barrier into a wait for the weight fragments requested ahead for the following phase.
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 // A-operand fragments of NT output tiles over the whole K, kept in registers: every weight
 // fragment is loaded from memory once per workgroup tile and reused for all its rows.
 template <typename T, int NT, int NKF> struct AFull { typename Mma<T>::Frag f[NKF][NT]; };
@@ -397,7 +405,7 @@ __device__ __forceinline__ void layer_norm_tile(f32x4 (&v)[NT][RH], int o0, int 
       if (g == 0) { stat1[og * kRowsMax + 16 * (rt0 + r) + m] = s; stat2[og * kRowsMax + 16 * (rt0 + r) + m] = q; }
     }
   }
-  __syncthreads();
+  lds_barrier();
 #pragma unroll
   for (int r = 0; r < RH; ++r) {
     if (r < cnt) {
