@@ -184,6 +184,19 @@ int dsvt_attn_pool(const dsvt_pool_cfg* cfg, const int32_t* coords, const void* 
                    void* ws, size_t ws_bytes, int32_t* status, void* stream);
 
 /* ---------------------------------------------------------------------------------------
+ * Bird's-eye-view map (Sec. 3.1, overview: after the last block "voxel features ... are then
+ * projected to a bird's eye view (BEV) feature map" for the 2D backbone).
+ * out [device] [batch, X, Y, Z, C] of dtype, channels last (Z = 1 for pillars and for the voxel
+ * variant after its last pooling: a [batch, X, Y, C] image); the whole of it is written: the
+ * voxel's row at its cell, zeros elsewhere.  coords [device] int32 [n_voxels,4] = (b, x, y, z),
+ * unique; x [device] [n_voxels, C].  C * sizeof(dtype) must be a multiple of 16, all three
+ * pointers 16-byte aligned, out must not alias x.  A coordinate outside the grid sets
+ * DSVT_ST_COORD_RANGE in *status [device] and that voxel is skipped.  Asynchronous on stream.
+ * ------------------------------------------------------------------------------------ */
+int dsvt_bev_scatter(const int32_t* coords, const void* x, int32_t n_voxels, int32_t C, int32_t dtype,
+                     int32_t batch, const int32_t grid[3], void* out, int32_t* status, void* stream);
+
+/* ---------------------------------------------------------------------------------------
  * Instrumentation for benchmarks (not part of the method): per-kernel time from hipEvent pairs
  * recorded around every launch while enabled.  Host-only; not thread-safe.
  * dsvt_prof_enable creates events for up to max_launches launches (later ones go unrecorded);

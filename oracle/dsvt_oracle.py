@@ -17,6 +17,8 @@ What each function follows:
                  an X-axis layer followed by a Y-axis layer (Eq. 5, Fig. 3).
   attn_pool      Sec. 3.3, Eq. (6) max-pool query and Eq. (7) attention over
                  the densified pooling region.
+  bev_scatter    Sec. 3.1 overview: the voxel features projected to a dense
+                 bird's-eye-view map (a definition: out[cell of voxel i] = x[i]).
 
 Readings taken where the paper is silent (each listed in the design notes):
 0-based ranks; Eq. (3) evaluated as an exact integer floor; x (resp. y) most
@@ -217,3 +219,18 @@ def attn_pool(w, coords, x, grid, pool, mask_empty=1):
     out = layer_norm(pooled + o @ g("w_o").T + g("b_o"), g("ln_g"), g("ln_b"), w["ln_eps"])
     out_coords = np.stack([ukeys // (Xp * Yp * Zp), (ukeys // (Yp * Zp)) % Xp, (ukeys // Zp) % Yp, ukeys % Zp], 1)
     return out_coords.astype(np.int32), out
+
+
+# ----------------------------------------------------------------------------
+# Bird's-eye-view map (Sec. 3.1, overview)
+# ----------------------------------------------------------------------------
+def bev_scatter(coords, x, batch, grid):
+    """Dense [batch, X, Y, Z, C] map: voxel i's feature row at cell coords[i] = (b, x, y, z), zeros at
+    every empty cell.  One voxel at a time, as the definition reads."""
+    coords = np.asarray(coords)
+    x = np.asarray(x)
+    out = np.zeros((batch, grid[0], grid[1], grid[2], x.shape[1]), dtype=x.dtype)
+    for i in range(len(coords)):
+        b, cx, cy, cz = (int(v) for v in coords[i])
+        out[b, cx, cy, cz, :] = x[i]
+    return out

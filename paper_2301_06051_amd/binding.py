@@ -76,6 +76,7 @@ def lib():
         L.dsvt_pool_pack.argtypes = [C.POINTER(PoolCfg), vp, sz, vp]
         L.dsvt_attn_pool_workspace_size.argtypes = [C.POINTER(PoolCfg), i32, C.POINTER(sz)]
         L.dsvt_attn_pool.argtypes = [C.POINTER(PoolCfg), vp, vp, i32, vp, vp, vp, vp, sz, vp, vp]
+        L.dsvt_bev_scatter.argtypes = [vp, vp, i32, i32, i32, i32, C.POINTER(I32x3), vp, vp, vp]
         L.dsvt_prof_enable.argtypes = [i32]
         L.dsvt_prof_collect.argtypes = [C.POINTER(C.c_float), C.POINTER(i32), i32]
         L.dsvt_prof_kernel_count.restype = i32
@@ -254,6 +255,20 @@ def dsvt_attn_pool(pool, coords, x, out=None, ws=None, stream=None):
                               _ptr(ws), ws.numel(), _ptr(out[3]), _stream(stream))
     _check("dsvt_attn_pool", rc)
     return out
+
+
+def dsvt_bev_scatter(coords, x, batch, grid, out=None, stream=None):
+    """Dense channels-last map [batch, X, Y, Z, C] with every voxel's row at its cell, zeros elsewhere.
+    Returns (out, status)."""
+    n, c = x.shape
+    assert x.is_cuda and x.is_contiguous() and coords.shape == (n, 4) and x.dtype in (torch.float32, torch.bfloat16)
+    if out is None:
+        out = torch.empty((batch, *grid, c), dtype=x.dtype, device="cuda")
+    status = torch.zeros((1,), dtype=torch.int32, device="cuda")
+    rc = lib().dsvt_bev_scatter(_ptr(coords), _ptr(x), n, c, DSVT_F32 if x.dtype == torch.float32 else DSVT_BF16, batch,
+                                C.byref(I32x3(*grid)), _ptr(out), _ptr(status), _stream(stream))
+    _check("dsvt_bev_scatter", rc)
+    return out, status
 
 
 def prof_enable(max_launches):

@@ -405,3 +405,24 @@ def test_large_sets(C, heads, hidden, win, tau, n):
     nu_max = max(int((np.diff(np.r_[om["set_inds"][s], -7]) != 0).sum()) for om in oms for s in range(0, om["n_sets"], 7))
     _say(f"  rel err {err:.3e}; largest sampled set {nu_max} voxels")
     assert err < TOL["bf16"]
+
+
+@pytest.mark.parametrize("dt,C,grid,batch,n", [("bf16", 192, (468, 468, 1), 1, 30000), ("f32", 64, (48, 48, 1), 1, 2000),
+                                               ("bf16", 128, (37, 29, 3), 2, 1500)])
+def test_bev_scatter_bit_exact(dt, C, grid, batch, n):
+    """Sec. 3.1 overview: sparse voxel rows -> dense channels-last bird's-eye-view map; a copy, so bit-exact."""
+    coords = np.concatenate([np.concatenate([np.full((n, 1), b, np.int64), synth.frame_uniform(500 + b, grid, n)], 1)
+                             for b in range(batch)]).astype(np.int32)
+    x = synth.make_features(501, len(coords), C, dt)
+    _say(f"bev scatter {dt} C={C} grid={grid} batch={batch}")
+    ref = orc.bev_scatter(coords, x, batch, grid)
+    out, status = dsvt.dsvt_bev_scatter(dev_coords(coords), dev_feats(x, dt), batch, grid)
+    torch.cuda.synchronize()
+    assert int(status.item()) == 0
+    assert np.array_equal(out.float().cpu().numpy(), ref.astype(np.float32))
+    bad = coords.copy(); bad[3, 1] = grid[0]                     # out of range: reported, skipped, nothing else disturbed
+    out2, status2 = dsvt.dsvt_bev_scatter(dev_coords(bad), dev_feats(x, dt), batch, grid)
+    torch.cuda.synchronize()
+    assert int(status2.item()) & 1
+    ref2 = ref.copy(); ref2[tuple(coords[3])] = 0
+    assert np.array_equal(out2.float().cpu().numpy(), ref2.astype(np.float32))

@@ -207,3 +207,19 @@ def test_pool_single_voxel_region_is_value_path():
         r = p + g("w_o") @ (g("w_v") @ p + g("b_v")) + g("b_o")
         want = TF.layer_norm(torch.tensor(r), (C,), torch.tensor(g("ln_g")), torch.tensor(g("ln_b")), w["ln_eps"])
         np.testing.assert_allclose(out[i], want.numpy(), rtol=1e-11, atol=1e-12)
+
+
+def test_bev_scatter_definition():
+    """Sec. 3.1 overview (BEV projection): the dense map holds every voxel's row at its cell and zeros
+    elsewhere -- checked against an independent gather: reading the map back at the voxels' cells returns
+    the rows, the number of non-zero cells equals the number of voxels, and the map's sum is the rows' sum."""
+    import synth
+    from oracle import dsvt_oracle as orc
+    grid = (9, 7, 2)
+    coords = np.concatenate([np.repeat(np.arange(2), 20)[:, None], np.concatenate([synth.frame_uniform(5 + b, grid, 20) for b in range(2)])], 1)
+    x = synth.make_features(6, len(coords), 8, "f32") + 3.0      # no zero rows
+    m = orc.bev_scatter(coords, x, 2, grid)
+    assert m.shape == (2, 9, 7, 2, 8)
+    assert np.array_equal(m[coords[:, 0], coords[:, 1], coords[:, 2], coords[:, 3]], x)
+    assert int((np.abs(m).sum(-1) > 0).sum()) == len(coords)
+    assert np.isclose(m.sum(dtype=np.float64), x.sum(dtype=np.float64))
