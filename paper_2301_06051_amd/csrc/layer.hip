@@ -119,7 +119,7 @@ __device__ __forceinline__ void attn_item(const LayerDev& p, T* Qs, const T* Ks,
   constexpr int TPC = KC / 16;                    // key tiles per PV fragment: 2 (bf16) or 1 (fp32)
   constexpr int NCH = (KTC + TPC - 1) / TPC;
   static_assert(HG == 1 || HG == 2 || HG == 4, "heads per item");
-  const int lane = threadIdx.x & 63, m = lane & 15, g = lane >> 4;
+  const int lane = opaque_tid() & 63, m = lane & 15, g = lane >> 4;
   const int qi = 16 * qt + m;
   const int qrow = r0 + (qi < nu ? qi : nu - 1);
 
@@ -274,7 +274,9 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
 
   // wave-uniform values are read back through readfirstlane so that the compiler keeps them in
   // scalar registers: branches on them are scalar branches, not exec-mask divergence
-  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), m = lane & 15, g = lane >> 4;
+  int tid = threadIdx.x, lane = tid & 63, m = lane & 15, g = lane >> 4;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+#define DSVT_REFRESH_LANE() do { tid = opaque_tid(); lane = tid & 63; m = lane & 15; g = lane >> 4; } while (0)
 
   // The first Q/K/V weight fragments are requested before anything else: their latency hides
   // behind the row bookkeeping and the gather.
@@ -400,6 +402,7 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
   }
   lds_barrier();
   DSVT_CLK(2);
+  DSVT_REFRESH_LANE();
 
   // ---- 3. Q, K, V = X W^T + b; V stored transposed
   {
@@ -436,6 +439,7 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
   const int o_own = og_own * 16 * NT_O;
   lds_barrier();
   DSVT_CLK(3);
+  DSVT_REFRESH_LANE();
 
   // ---- 4. attention inside every set; O overwrites Q
   {
@@ -460,6 +464,7 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
   for (int nt = 0; nt < NT_O; ++nt) bo4[nt] = *reinterpret_cast<const f32x4*>(p.b_o + o_own + 16 * nt + 4 * g);
   lds_barrier();
   DSVT_CLK(4);
+  DSVT_REFRESH_LANE();
   // attention is done with V^T: the GELU table of the MLP takes its place (published by the
   // barriers of the LayerNorm below)
   constexpr bool kGeluTable = sizeof(T) == 2;
@@ -510,6 +515,7 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
     DSVT_CLK(15);
     lds_barrier();
     DSVT_CLK(5);
+    DSVT_REFRESH_LANE();
 
     // ---- 6. MLP: H = gelu(x1 W1^T + b1) over the dead Q/K tiles; x2 = LN(x1 + H W2^T + b2)
     ffn1.run(Xs, LDX, RT, p.b_1, [&](int o0, int r, f32x4 (&acc)[NT_1], bool) {
@@ -532,6 +538,7 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
     for (int nt = 0; nt < NT_2; ++nt) b24[nt] = *reinterpret_cast<const f32x4*>(p.b_2 + o_own2 + 16 * nt + 4 * g);
     lds_barrier();
     DSVT_CLK(6);
+    DSVT_REFRESH_LANE();
     f32x4 keep2[NT_2][kHalfTiles];
     if (HC == 1) ffn2.template run_keep<1>(Hs, LDH, rt_own, b24, keep2);
     else if (HC == 2) ffn2.template run_keep<2>(Hs, LDH, rt_own, b24, keep2);
@@ -557,6 +564,7 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
   }
   lds_barrier();
   DSVT_CLK(7);
+  DSVT_REFRESH_LANE();
 
   // ---- 7. scatter: rows of Xs -> the voxels' rows of out, 16 bytes per thread
   {

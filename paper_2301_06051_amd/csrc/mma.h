@@ -62,6 +62,16 @@ template <> __device__ __forceinline__ f32x4 pack4<float>(f32x4 v) { return v; }
 
 template <typename T> __device__ __forceinline__ float to_f32(T v) { return (float)v; }
 
+// threadIdx.x behind an empty asm: values derived from it (lane, row and feature offsets) are
+// recomputed where they are used -- a couple of ALU instructions -- instead of being kept in
+// registers from the top of a long kernel, where they end up spilled to scratch memory (and a
+// reload from scratch waits for every outstanding global load, the weights requested ahead).
+__device__ __forceinline__ int opaque_tid() {
+  int t = threadIdx.x;
+  asm volatile("" : "+v"(t));
+  return t;
+}
+
 // Elements of T that pad every LDS row by 32 bytes.  Rows of K elements (K * sizeof(T) a multiple
 // of 64 bytes) then have a pitch that is an odd multiple of 32 bytes, the one pitch at which the
 // 16-byte fragment loads of a wavefront (16 rows x 4 k-slices) run at the full LDS rate; measured
@@ -94,7 +104,7 @@ template <typename T, int NKF> struct BRow { typename Mma<T>::Frag f[NKF]; };
 template <typename T, int NT, int NKF, int NKF_ALL = NKF>
 __device__ __forceinline__ void load_a(AFull<T, NT, NKF>& a, const T* __restrict__ Wp, int tile0, int kf0 = 0) {
   typedef typename Mma<T>::Frag Frag;
-  const int lane = threadIdx.x & 63;
+  const int lane = opaque_tid() & 63;
   const Frag* fp = reinterpret_cast<const Frag*>(Wp) + ((size_t)tile0 * NKF_ALL + kf0) * 64 + lane;
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt)
@@ -106,7 +116,7 @@ __device__ __forceinline__ void load_a(AFull<T, NT, NKF>& a, const T* __restrict
 template <typename T, int NKF>
 __device__ __forceinline__ void load_b(BRow<T, NKF>& b, const T* Xs, int ldx, int r, int k0 = 0) {
   typedef typename Mma<T>::Frag Frag;
-  const int lane = threadIdx.x & 63, m = lane & 15, g = lane >> 4;
+  const int lane = opaque_tid() & 63, m = lane & 15, g = lane >> 4;
   const T* xp = Xs + (16 * r + m) * ldx + k0 + g * Mma<T>::KL;
 #pragma unroll
   for (int kf = 0; kf < NKF; ++kf) b.f[kf] = *reinterpret_cast<const Frag*>(xp + kf * Mma<T>::KC);
@@ -181,7 +191,7 @@ struct GemmPhase {
   // exchanged operands, feature 16*nt + m for all four.  Both forms are loaded (no branch, no
   // wait at the point of the request) and select() picks one when the item starts.
   __device__ __forceinline__ void load_bias(Bias& b, const float* __restrict__ bias, int og, bool need_s) const {
-    const int lane16 = threadIdx.x & 15, g4 = ((threadIdx.x & 63) >> 4) * 4;
+    const int tl = opaque_tid(), lane16 = tl & 15, g4 = ((tl & 63) >> 4) * 4;
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
       b.v[nt] = *reinterpret_cast<const f32x4*>(bias + og * 16 * NT + 16 * nt + g4);
@@ -388,7 +398,7 @@ __device__ __forceinline__ void layer_norm_tile(f32x4 (&v)[NT][RH], int o0, int 
   typedef typename Mma<T>::Vec4 Vec4;
   constexpr int SG = C / (16 * NT);
   static_assert(SG * 16 * NT == C && SG <= kStatGroupsMax, "LayerNorm feature groups");
-  const int lane = threadIdx.x & 63, m = lane & 15, g = lane >> 4;
+  const int lane = opaque_tid() & 63, m = lane & 15, g = lane >> 4;
   float* stat1 = stat;
   float* stat2 = stat + kStatGroupsMax * kRowsMax;
 #pragma unroll
