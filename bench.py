@@ -54,31 +54,30 @@ def main():
     x0 = torch.as_tensor(x_np).cuda().to(torch.bfloat16).contiguous()
     buf = torch.empty_like(x0)
     layers = [[dsvt.LayerWeights(w) for w in pair] for pair in w_np]
-    pcfgs = {sh: [dsvt.part_cfg(cfg["grid"], cfg["win"], sh, tau, cfg["batch"], a) for a in (0, 1)]
-             for sh in cfg["shifts"]}
-    maps = {sh: [dsvt.SetMaps(pc, N) for pc in pcs] for sh, pcs in pcfgs.items()}
+    pcfgs = {sh: dsvt.part_cfg(cfg["grid"], cfg["win"], sh, tau, cfg["batch"], 0) for sh in cfg["shifts"]}
+    maps = {sh: dsvt.SetMapsXY(pc, N) for sh, pc in pcfgs.items()}       # X- and Y-axis maps of each window shift
     ws = torch.empty((max(dsvt.dsvt_block_workspace_size(layers[0][0], N), 1),), dtype=torch.uint8, device="cuda")
 
-    # The four partitions are independent of each other and only the first pair is needed by
-    # block 0: each runs on its own stream (default priority) and joins the main stream where its
-    # maps are first used, so in the captured graph they are parallel branches.
-    order = [(sh, a) for sh in cfg["shifts"] for a in (0, 1)]
-    side_streams = [torch.cuda.Stream() for _ in order]
+    # The partitions of the two window shifts (each both axes at once) are independent of each other
+    # and only the first is needed by block 0: it runs on the main stream, the other on a stream of
+    # its own (default priority) that joins the main stream where its maps are first used, so in the
+    # captured graph it is a parallel branch.
+    first = cfg["shifts"][0]
+    side_streams = {sh: torch.cuda.Stream() for sh in cfg["shifts"][1:]}
 
     def step():
         main = torch.cuda.current_stream()
-        for st, (sh, a) in zip(side_streams, order):
+        for sh, st in side_streams.items():
             st.wait_stream(main)
             with torch.cuda.stream(st):
-                dsvt.dsvt_partition(pcfgs[sh][a], cd, out=maps[sh][a])
-        joined = set()
+                dsvt.dsvt_partition_xy(pcfgs[sh], cd, out=maps[sh])
+        dsvt.dsvt_partition_xy(pcfgs[first], cd, out=maps[first])
+        joined = {first}
         src = x0
         for b, pair in enumerate(layers):
             sh = cfg["shifts"][b % len(cfg["shifts"])]
             if sh not in joined:
-                for st, (s2, a) in zip(side_streams, order):
-                    if s2 == sh:
-                        main.wait_stream(st)
+                main.wait_stream(side_streams[sh])
                 joined.add(sh)
             dsvt.dsvt_block(pair, maps[sh], cd, src, x_out=buf, ws=ws)
             src = buf
@@ -127,7 +126,7 @@ def main():
     ms_per_step = dt / args.steps * 1e3
 
     # Per-kernel time: the same steps again, eagerly, with an event pair around every launch.
-    launches_per_step = 4 * 6 + 4 * 2
+    launches_per_step = 2 * 6 + 4 * 2
     prof_steps = min(args.steps, 50)
     dsvt.prof_enable(launches_per_step * prof_steps)
     for _ in range(prof_steps):

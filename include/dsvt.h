@@ -49,8 +49,8 @@ typedef struct {
 } dsvt_part_cfg;
 
 /* Host-only.  Upper bound on the number of sets, floor(N/tau) + min(N, #windows), on the number
- * of workgroup tiles (see dsvt_maps), and the bytes of scratch dsvt_partition needs for n_voxels
- * voxels.  Any output may be NULL. */
+ * of workgroup tiles (see dsvt_maps), and the bytes of scratch dsvt_partition or dsvt_partition_xy
+ * needs for n_voxels voxels.  Any output may be NULL. */
 int dsvt_partition_bound(const dsvt_part_cfg* cfg, int32_t n_voxels, int32_t* max_sets, int32_t* max_tiles,
                          size_t* ws_bytes);
 
@@ -90,6 +90,21 @@ int dsvt_partition(const dsvt_part_cfg* cfg, const int32_t* coords, int32_t n_vo
                    int32_t* set_inds, int32_t* voxel_slot, int32_t* n_sets, int32_t max_sets,
                    int32_t* set_win, const dsvt_tile_list* tiles,
                    void* ws, size_t ws_bytes, int32_t* status, void* stream);
+
+/* Both rotated partitions of one window configuration (Sec. 3.2: a block's first layer takes the sets
+ * in X-axis inner order, its second in Y-axis order) in one pass over the voxels.  The windows, the
+ * number of sets per window (Eq. 2) and hence n_sets, set_win and the tile boundaries are the same for
+ * both; only the order of the voxels inside a window differs.  cfg->axis is ignored.  Arguments as for
+ * dsvt_partition, with one set_inds and voxel_slot per axis; `tiles` receives the common tile_first,
+ * n_tiles and tile_order and the X-axis descriptors, tile_desc_y [device, max_tiles*256 int32] the
+ * Y-axis descriptors (required when tiles is given).  The maps of the Y-axis layer are then
+ * {set_inds_y, voxel_slot_y, n_sets, {max_tiles, tile_first, n_tiles, tile_order, tile_desc_y}}.
+ * Results are identical to two dsvt_partition calls with axis 0 and 1.  Same errors. */
+int dsvt_partition_xy(const dsvt_part_cfg* cfg, const int32_t* coords, int32_t n_voxels,
+                      int32_t* set_inds_x, int32_t* set_inds_y, int32_t* voxel_slot_x, int32_t* voxel_slot_y,
+                      int32_t* n_sets, int32_t max_sets, int32_t* set_win,
+                      const dsvt_tile_list* tiles, int32_t* tile_desc_y,
+                      void* ws, size_t ws_bytes, int32_t* status, void* stream);
 
 /* The maps one layer consumes (outputs of dsvt_partition, all [device]). */
 typedef struct {

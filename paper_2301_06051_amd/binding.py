@@ -67,6 +67,8 @@ def lib():
         vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
         L.dsvt_partition_bound.argtypes = [C.POINTER(PartCfg), i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(sz)]
         L.dsvt_partition.argtypes = [C.POINTER(PartCfg), vp, i32, vp, vp, vp, i32, vp, C.POINTER(TileList), vp, sz, vp, vp]
+        L.dsvt_partition_xy.argtypes = [C.POINTER(PartCfg), vp, i32, vp, vp, vp, vp, vp, i32, vp, C.POINTER(TileList), vp,
+                                        vp, sz, vp, vp]
         L.dsvt_layer_packed_size.argtypes = [C.POINTER(LayerW), C.POINTER(sz)]
         L.dsvt_layer_pack.argtypes = [C.POINTER(LayerW), vp, sz, vp]
         L.dsvt_block_workspace_size.argtypes = [C.POINTER(LayerW), i32, C.POINTER(sz)]
@@ -123,22 +125,31 @@ def dsvt_partition_bound(cfg, n_voxels):
 class SetMaps:
     """Device buffers of one (window configuration, axis) and the struct the kernels read."""
 
-    def __init__(self, cfg, n_voxels, max_sets=None, tiles=True):
+    def __init__(self, cfg, n_voxels, max_sets=None, tiles=True, common=None):
+        """common: the SetMaps of the other axis of the same dsvt_partition_xy call, whose n_sets, set_win,
+        status, scratch and tile boundaries this one shares."""
         bound, tile_bound, ws_bytes = dsvt_partition_bound(cfg, n_voxels)
         self.cfg, self.n_voxels, self.tau = cfg, n_voxels, cfg.tau
         self.max_sets = bound if max_sets is None else max_sets
         i32 = dict(dtype=torch.int32, device="cuda")
         self.set_inds = torch.full((self.max_sets, cfg.tau), -1, **i32)
         self.voxel_slot = torch.full((n_voxels,), -1, **i32)
-        self.set_win = torch.full((self.max_sets,), -1, **i32)
-        self.n_sets = torch.zeros((1,), **i32)
-        self.status = torch.zeros((1,), **i32)
-        self.ws = torch.empty((ws_bytes,), dtype=torch.uint8, device="cuda")
+        if common is None:
+            self.set_win = torch.full((self.max_sets,), -1, **i32)
+            self.n_sets = torch.zeros((1,), **i32)
+            self.status = torch.zeros((1,), **i32)
+            self.ws = torch.empty((ws_bytes,), dtype=torch.uint8, device="cuda")
+        else:
+            assert common.max_sets == self.max_sets and common.n_voxels == n_voxels
+            self.set_win, self.n_sets, self.status, self.ws = common.set_win, common.n_sets, common.status, common.ws
         self.max_tiles = tile_bound if (tiles and tile_bound > 0 and cfg.tau <= 96) else 0
         if self.max_tiles:
-            self.tile_first = torch.full((self.max_tiles + 1,), -1, **i32)
-            self.n_tiles = torch.zeros((1,), **i32)
-            self.tile_order = torch.full((self.max_tiles,), -1, **i32)
+            if common is None:
+                self.tile_first = torch.full((self.max_tiles + 1,), -1, **i32)
+                self.n_tiles = torch.zeros((1,), **i32)
+                self.tile_order = torch.full((self.max_tiles,), -1, **i32)
+            else:
+                self.tile_first, self.n_tiles, self.tile_order = common.tile_first, common.n_tiles, common.tile_order
             self.tile_desc = torch.full((self.max_tiles, 256), -1, **i32)
             self.tile_list = TileList(self.max_tiles, self.tile_first.data_ptr(), self.n_tiles.data_ptr(),
                                       self.tile_order.data_ptr(), self.tile_desc.data_ptr())
@@ -161,6 +172,40 @@ def dsvt_partition(cfg, coords, out=None, stream=None):
                               _ptr(out.status),
                               _stream(stream))
     _check("dsvt_partition", rc)
+    return out
+
+
+class SetMapsXY:
+    """The maps of both axes of one window configuration, filled by one dsvt_partition_xy call; indexes
+    and iterates like the pair [X-axis maps, Y-axis maps]."""
+
+    def __init__(self, cfg, n_voxels, max_sets=None, tiles=True):
+        self.x = SetMaps(cfg, n_voxels, max_sets, tiles)
+        self.y = SetMaps(cfg, n_voxels, max_sets, tiles, common=self.x)
+        self.n_voxels = n_voxels
+
+    def __getitem__(self, k):
+        return (self.x, self.y)[k]
+
+    def __iter__(self):
+        return iter((self.x, self.y))
+
+    def __len__(self):
+        return 2
+
+
+def dsvt_partition_xy(cfg, coords, out=None, stream=None):
+    """Both rotated partitions of one window configuration.  Returns the SetMapsXY it filled."""
+    assert coords.is_cuda and coords.dtype == torch.int32 and coords.is_contiguous() and coords.shape[1] == 4
+    n = coords.shape[0]
+    out = SetMapsXY(cfg, n) if out is None else out
+    assert out.n_voxels == n
+    x, y = out.x, out.y
+    rc = lib().dsvt_partition_xy(C.byref(cfg), _ptr(coords), n, _ptr(x.set_inds), _ptr(y.set_inds), _ptr(x.voxel_slot),
+                                 _ptr(y.voxel_slot), _ptr(x.n_sets), x.max_sets, _ptr(x.set_win),
+                                 C.byref(x.tile_list) if x.max_tiles else None, _ptr(y.tile_desc) if x.max_tiles else None,
+                                 _ptr(x.ws), x.ws.numel(), _ptr(x.status), _stream(stream))
+    _check("dsvt_partition_xy", rc)
     return out
 
 

@@ -11,46 +11,85 @@
 
 namespace {
 
-constexpr uint32_t kBadKey = 0xFFFFFFFFu;
-constexpr int64_t kFusedThreads = 32 * 1024;     // window-count work (windows x lanes per window) one workgroup takes on itself
+constexpr int32_t kFrontVoxels = 64 * 1024;      // frames up to this size go through k_front (one workgroup marks them all)
+constexpr size_t kFrontLds = 152 * 1024;         // LDS k_front may ask for
 
 struct PartGeom {
   int32_t grid[3], win[3], shift[3], nw[3];
-  int32_t batch, tau, axis;
+  int32_t batch, tau;
+  uint32_t magic[3];       // ceil(2^32 / win[a]) when that divides every x + shift exactly (see div_win), else 0
+  uint32_t magic_tau, magic_cut;   // the same for tau (dividends up to a window's volume + tau) and for the rows of a
+                                   // tile cut (dividends up to all padded rows), 0 when not exact; used by k_front
+  uint32_t mul24[3], shr24[3];     // x / win[a] = (x * mul24) >> shr24 in 24-bit arithmetic (k_front), see small_div
   int32_t words_per_win;   // 32-bit bitmap words per window (window volume rounded up to 32)
   int32_t n_windows;       // batch * nw[0] * nw[1] * nw[2]
 };
 
-__global__ void k_clear(uint32_t* __restrict__ words, int64_t n, int32_t* __restrict__ desc, int64_t n_desc) {
+// What differs between the two rotated partitions of one window configuration (Sec. 3.2): the order
+// of the voxels inside a window, hence the occupancy bitmap, its prefix and the slot maps.  Windows,
+// set counts and tile boundaries are common.  a[k] belongs to inner order axis0 + k.
+struct AxisBufs {
+  uint32_t *bitmap, *prefix;                 // [n_words] each
+  int32_t *set_inds, *voxel_slot, *tile_desc;
+};
+struct AxisSet {
+  AxisBufs a[2];
+  int32_t n, axis0;
+};
+
+__global__ void k_clear(uint32_t* __restrict__ words, int64_t n) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) words[i] = 0u;
-  if (i < n_desc) desc[i] = -1;
 }
 
-// One thread per voxel: composite key = window key * (32*words_per_win) + inner key; set its bit.
-__global__ void k_mark(PartGeom g, const int4* __restrict__ coords, int32_t n, uint32_t* __restrict__ bitmap,
-                       uint32_t* __restrict__ keys, int32_t* __restrict__ status) {
+// x / win[a] for 0 <= x < grid + shift.  With m = ceil(2^32 / d) the high word of x * m is floor(x / d)
+// whenever x * (m * d - 2^32) < 2^32, which x < 2^16 and d < 2^15 guarantee (the host sets magic only then).
+__device__ __forceinline__ int32_t div_win(const PartGeom& g, int32_t a, int32_t x) {
+  if (g.win[a] == 1) return x;
+  if (g.magic[a] != 0u) return (int32_t)__umulhi((uint32_t)x, g.magic[a]);
+  return x / g.win[a];
+}
+
+// Full-rate integer arithmetic for k_front, whose operands all stay below 2^24.
+__device__ __forceinline__ uint32_t mul24(uint32_t a, uint32_t b) { return __umul24(a, b); }
+
+// x / d by the high word of x * magic (magic = ceil(2^32 / d), exact for the dividends the host checked).
+__device__ __forceinline__ uint32_t div_magic(uint32_t x, uint32_t magic) { return __umulhi(x, magic); }
+
+// Window key and in-window cell of a voxel (b, x, y, z); false when it lies outside the grid.
+__device__ __forceinline__ bool voxel_cell(const PartGeom& g, int4 c, uint32_t& wkey, int32_t& xi, int32_t& yi, int32_t& zi) {
+  const bool ok = (uint32_t)c.x < (uint32_t)g.batch && (uint32_t)c.y < (uint32_t)g.grid[0] &&
+                  (uint32_t)c.z < (uint32_t)g.grid[1] && (uint32_t)c.w < (uint32_t)g.grid[2];
+  if (!ok) return false;
+  const int32_t x = c.y + g.shift[0], y = c.z + g.shift[1], z = c.w + g.shift[2];
+  const int32_t wx = div_win(g, 0, x), wy = div_win(g, 1, y), wz = div_win(g, 2, z);
+  xi = x - wx * g.win[0]; yi = y - wy * g.win[1]; zi = z - wz * g.win[2];
+  wkey = (uint32_t)(((c.x * g.nw[0] + wx) * g.nw[1] + wy) * g.nw[2] + wz);
+  return true;
+}
+
+// Composite key = window key * (32*words_per_win) + inner key; the inner key runs x-major for the
+// X-axis partition and y-major for the Y-axis one.
+__device__ __forceinline__ uint32_t voxel_key(const PartGeom& g, int32_t axis, uint32_t wkey, int32_t xi, int32_t yi, int32_t zi) {
+  const uint32_t inner = axis == 0 ? (uint32_t)((xi * g.win[1] + yi) * g.win[2] + zi)
+                                   : (uint32_t)((yi * g.win[0] + xi) * g.win[2] + zi);
+  return wkey * (uint32_t)(g.words_per_win * 32) + inner;
+}
+
+// One thread per voxel: set its bit in the bitmap of every axis.
+__global__ void k_mark(PartGeom g, const int4* __restrict__ coords, int32_t n, AxisSet ax, int32_t* __restrict__ status) {
   int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= n) return;
-  int4 c = coords[i];                       // (b, x, y, z)
-  bool ok = c.x >= 0 && c.x < g.batch && c.y >= 0 && c.y < g.grid[0] && c.z >= 0 && c.z < g.grid[1] &&
-            c.w >= 0 && c.w < g.grid[2];
-  if (!ok) {
-    keys[i] = kBadKey;
+  uint32_t wkey; int32_t xi, yi, zi;
+  if (!voxel_cell(g, coords[i], wkey, xi, yi, zi)) {
     atomicOr(status, DSVT_ST_COORD_RANGE);
     return;
   }
-  int32_t x = c.y + g.shift[0], y = c.z + g.shift[1], z = c.w + g.shift[2];
-  int32_t wx = x / g.win[0], wy = y / g.win[1], wz = z / g.win[2];
-  int32_t xi = x - wx * g.win[0], yi = y - wy * g.win[1], zi = z - wz * g.win[2];
-  uint32_t wkey = (uint32_t)(((c.x * g.nw[0] + wx) * g.nw[1] + wy) * g.nw[2] + wz);
-  uint32_t inner = g.axis == 0 ? (uint32_t)((xi * g.win[1] + yi) * g.win[2] + zi)
-                               : (uint32_t)((yi * g.win[0] + xi) * g.win[2] + zi);
-  uint32_t key = wkey * (uint32_t)(g.words_per_win * 32) + inner;
-  uint32_t bit = 1u << (key & 31u);
-  uint32_t old = atomicOr(&bitmap[key >> 5], bit);
-  if (old & bit) atomicOr(status, DSVT_ST_COORD_REPEAT);
-  keys[i] = key;
+  for (int32_t k = 0; k < ax.n; ++k) {
+    const uint32_t key = voxel_key(g, ax.axis0 + k, wkey, xi, yi, zi), bit = 1u << (key & 31u);
+    const uint32_t old = atomicOr(&ax.a[k].bitmap[key >> 5], bit);
+    if (old & bit) atomicOr(status, DSVT_ST_COORD_REPEAT);
+  }
 }
 
 // `group` lanes (a power of two <= 64) per window: pop-count the window's words, leave in
@@ -76,10 +115,10 @@ __device__ __forceinline__ void window_count(int32_t tid, const uint32_t* __rest
   if (lane == 0) win_count[w] = (int32_t)running;
 }
 
-__global__ void k_window_count(const uint32_t* __restrict__ bitmap, uint32_t* __restrict__ word_prefix,
-                               int32_t* __restrict__ win_count, int32_t n_windows, int32_t words_per_win,
-                               int32_t group) {
-  window_count(blockIdx.x * blockDim.x + threadIdx.x, bitmap, word_prefix, win_count, n_windows, words_per_win, group);
+__global__ void k_window_count(AxisSet ax, int32_t* __restrict__ win_count, int32_t n_windows, int32_t words_per_win,
+                               int32_t group) {       // blockIdx.y = axis; every axis leaves the same counts
+  window_count(blockIdx.x * blockDim.x + threadIdx.x, ax.a[blockIdx.y].bitmap, ax.a[blockIdx.y].prefix, win_count, n_windows,
+               words_per_win, group);
 }
 
 // One workgroup: exclusive scans of voxels-per-window and sets-per-window (Eq. 2).
@@ -145,10 +184,64 @@ __device__ __forceinline__ int32_t set_distinct(int64_t N, int64_t S, int64_t j,
   return (int32_t)(hi - lo + 1);
 }
 
+// The same counts for j = 0, 1, 2, ... in turn, with one division per window: floor(j*tau*N / (S*tau)) =
+// floor(j*N/S) =: q_j with remainder r_j, both stepped by N/S and N mod S; and the last voxel of set j,
+// floor(((j+1)*N - N/tau) / S), is q_{j+1} less one exactly when r_{j+1} * tau < N.
+struct SetWalk {
+  uint32_t N, S, tau, dq, dr, q, r;
+  bool small;                                                // N < 2^16: float division and 24-bit products are exact
+  // N < 2^16: the quotient of (N + 0.5) / S in float arithmetic (errors of a few 2^-24 of a quotient below
+  // 2^16 / S, against a distance of at least 0.5 / S to the next integer) truncates to floor(N / S)
+  __device__ __forceinline__ SetWalk(int32_t n, int32_t s, int32_t t) : N((uint32_t)n), S((uint32_t)s), tau((uint32_t)t), q(0u), r(0u) {
+    small = N < 65536u;
+    dq = s > 0 ? (small ? (uint32_t)(((float)N + 0.5f) * __frcp_rn((float)S)) : N / S) : 0u;
+    dr = small ? N - __umul24(dq, S) : N - dq * S;
+  }
+  __device__ __forceinline__ void restart() { q = 0u; r = 0u; }
+  __device__ __forceinline__ int32_t next() {               // distinct voxels of the next set
+    uint32_t q2 = q + dq, r2 = r + dr;
+    if (r2 >= S) { r2 -= S; ++q2; }
+    const uint32_t nu = q2 - (small ? (__umul24(r2, tau) < N ? 1u : 0u) : (r2 * tau < N ? 1u : 0u)) - q + 1u;
+    q = q2; r = r2;
+    return (int32_t)nu;
+  }
+};
+
 struct TileOut {                       // all null when the caller wants no work list
-  int32_t *tile_first, *n_tiles, *tile_order, *tile_desc;
+  int32_t *tile_first, *n_tiles, *tile_order;
+  int32_t* tile_desc[2];               // one descriptor array per axis (second null for a single partition)
   int32_t max_tiles;
 };
+
+// Padded rows of a set with nu distinct voxels.
+__device__ __forceinline__ int32_t set_rows(int32_t nu) {
+  const int32_t rows = (nu + 3) & ~3;
+  return rows > kTileRows ? kTileRows : (rows < 4 ? 4 : rows);
+}
+
+// Header of launch slot pos, in every axis's descriptor array.
+__device__ __forceinline__ void desc_header(const TileOut& out, int32_t pos, int32_t rows, int32_t sets) {
+#pragma unroll
+  for (int32_t k = 0; k < 2; ++k)
+    if (out.tile_desc[k] != nullptr) {
+      int32_t* d = out.tile_desc[k] + (int64_t)pos * kDescInts;
+      d[0] = rows;
+      d[1] = sets;
+    }
+}
+
+// Set ls of launch slot pos: first row, distinct voxels, and -1 in the rows that pad it to a multiple of 4.
+__device__ __forceinline__ void desc_set(const TileOut& out, int32_t pos, int32_t ls, int32_t r0, int32_t nu) {
+  const int32_t r1 = r0 + set_rows(nu) < kTileRows ? r0 + set_rows(nu) : kTileRows;
+#pragma unroll
+  for (int32_t k = 0; k < 2; ++k)
+    if (out.tile_desc[k] != nullptr) {
+      int32_t* d = out.tile_desc[k] + (int64_t)pos * kDescInts;
+      d[kDescR0 + ls] = r0;
+      d[kDescNu + ls] = nu;
+      for (int32_t r = r0 + nu; r < r1; ++r) { d[kDescVox + r] = -1; d[kDescLin + r] = -1; }
+    }
+}
 
 // One workgroup: cut the set sequence into tiles for the layer kernels, order the tiles for launch
 // and write the descriptor headers.  With P(s) the running sum of padded rows before set s, set s
@@ -178,8 +271,7 @@ __device__ __forceinline__ void build_tiles(const int32_t* set_w, const int32_t*
       int32_t w = set_w[s];
       w = w < 0 ? 0 : (w >= n_windows ? n_windows - 1 : w);
       const int64_t N = win_count[w] > 0 ? win_count[w] : 1, S = (N + tau - 1) / tau;
-      rows = (set_distinct(N, S, s - win_soff[w], tau) + 3) & ~3;
-      rows = rows > kTileRows ? kTileRows : (rows < 4 ? 4 : rows);
+      rows = set_rows(set_distinct(N, S, s - win_soff[w], tau));
     }
     int32_t incl = rows;
     for (int32_t d = 1; d < 64; d <<= 1) {
@@ -275,9 +367,7 @@ __device__ __forceinline__ void build_tiles(const int32_t* set_w, const int32_t*
       for (int32_t k = 0; k < wv; ++k) pos += wave_cnt[k][b];
       out.tile_order[pos] = t;
       tile_pos[t] = pos;
-      int32_t* d = out.tile_desc + (int64_t)pos * kDescInts;    // descriptor header of launch slot pos
-      d[0] = tile_rows[t + 1] - tile_rows[t];
-      d[1] = out.tile_first[t + 1] - out.tile_first[t];
+      desc_header(out, pos, tile_rows[t + 1] - tile_rows[t], out.tile_first[t + 1] - out.tile_first[t]);
     }
     __syncthreads();
     if (tid < 32) { int32_t add = 0; for (int32_t k = 0; k < 16; ++k) add += wave_cnt[k][tid]; running[tid] += add; }
@@ -295,9 +385,7 @@ __device__ __forceinline__ void build_tiles(const int32_t* set_w, const int32_t*
         w = w < 0 ? 0 : (w >= n_windows ? n_windows - 1 : w);
         const int64_t N = win_count[w] > 0 ? win_count[w] : 1, S = (N + tau - 1) / tau;
         if (ls >= 0 && ls < kDescSets && r0 >= 0 && r0 <= kTileRows - 4) {
-          int32_t* d = out.tile_desc + (int64_t)pos * kDescInts;
-          d[kDescR0 + ls] = r0;
-          d[kDescNu + ls] = set_distinct(N, S, s - win_soff[w], tau);
+          desc_set(out, pos, ls, r0, set_distinct(N, S, s - win_soff[w], tau));
           loc = (pos << 7) | r0;
         }
       }
@@ -314,82 +402,391 @@ __global__ void __launch_bounds__(1024) k_tiles(const int32_t* set_w, const int3
               set_loc);
 }
 
-// Small frames: the three steps between k_mark and k_emit in one workgroup and one launch (each is a
-// few microseconds of work; as separate launches their start-up and the gaps between them are most
-// of a partition's latency, which the first layer of a frame has to wait for).
-__global__ void __launch_bounds__(1024) k_count_scan_tiles(const uint32_t* bitmap, uint32_t* word_prefix, int32_t* win_count,
-                                                           int32_t* win_soff, int32_t n_windows, int32_t words_per_win,
-                                                           int32_t group, int32_t tau, int32_t max_sets, int32_t* n_sets,
-                                                           int32_t* status, int32_t* set_w, int32_t set_bound,
-                                                           int32_t set_cap, int32_t rows_per_cut, TileOut out,
-                                                           int32_t* tile_rows, int32_t* tile_pos, int32_t* set_p,
-                                                           int32_t* set_loc) {
-  if (words_per_win <= 8) {
-    // a thread per window: its few words are independent loads, the prefix a short serial sum
-    for (int32_t w = threadIdx.x; w < n_windows; w += 1024) {
-      const int64_t base = (int64_t)w * words_per_win;
-      uint32_t v[8];
-#pragma unroll
-      for (int32_t j = 0; j < 8; ++j) v[j] = j < words_per_win ? bitmap[base + j] : 0u;
-      uint32_t running = 0;
-#pragma unroll
-      for (int32_t j = 0; j < 8; ++j) {
-        if (j < words_per_win) word_prefix[base + j] = running;
-        running += (uint32_t)__popc(v[j]);
-      }
-      win_count[w] = (int32_t)running;
-    }
-  } else {
-    const int64_t n_threads = (int64_t)n_windows * group;
-    for (int64_t base = 0; base < n_threads; base += 1024)      // 1024 is a multiple of every group size
-      window_count((int32_t)(base + threadIdx.x), bitmap, word_prefix, win_count, n_windows, words_per_win, group);
-  }
-  __threadfence_block();
-  __syncthreads();
-  scan_windows(win_count, win_soff, n_windows, tau, max_sets, n_sets, status, set_w, set_bound);
-  __threadfence_block();
-  __syncthreads();
-  if (out.tile_desc != nullptr)
-    build_tiles(set_w, win_count, win_soff, n_sets, set_cap, tau, n_windows, rows_per_cut, out, tile_rows, tile_pos, set_p,
-                set_loc);
+#ifdef DSVT_PHASE_CLOCKS
+long long* g_front_clocks = nullptr;       // [16] shader-clock stamps of thread 0 of k_front (debug builds)
+#define DSVT_FCLK(k) do { if (clk && threadIdx.x == 0) clk[k] = clock64(); } while (0)
+#else
+#define DSVT_FCLK(k) do {} while (0)
+#endif
+
+// Scan over the 1024 threads of a workgroup, continued from one call to the next through `carry`:
+// inclusive sums of a and b, and in xm the maximum of m over the threads before this one (and over
+// earlier calls).  Every thread of the workgroup calls it; two barriers inside.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int32_t dpp_or(int32_t identity, int32_t v) {       // v of the lane CTRL names, identity where there is none
+  return __builtin_amdgcn_update_dpp(identity, v, CTRL, ROW_MASK, 0xF, false);
+}
+// Inclusive scans over a wavefront by data-parallel-primitive moves: shifts by 1, 2, 4, 8 inside rows of
+// 16 lanes, then lane 15 of rows 0 and 2 into rows 1 and 3, then lane 31 into rows 2 and 3.
+__device__ __forceinline__ int32_t wave_scan_add(int32_t v) {
+  v += dpp_or<0x111, 0xF>(0, v);
+  v += dpp_or<0x112, 0xF>(0, v);
+  v += dpp_or<0x114, 0xF>(0, v);
+  v += dpp_or<0x118, 0xF>(0, v);
+  v += dpp_or<0x142, 0xA>(0, v);
+  v += dpp_or<0x143, 0xC>(0, v);
+  return v;
+}
+__device__ __forceinline__ int32_t wave_scan_max(int32_t v, int32_t lowest) {
+  int32_t t;
+  t = dpp_or<0x111, 0xF>(lowest, v); v = t > v ? t : v;
+  t = dpp_or<0x112, 0xF>(lowest, v); v = t > v ? t : v;
+  t = dpp_or<0x114, 0xF>(lowest, v); v = t > v ? t : v;
+  t = dpp_or<0x118, 0xF>(lowest, v); v = t > v ? t : v;
+  t = dpp_or<0x142, 0xA>(lowest, v); v = t > v ? t : v;
+  t = dpp_or<0x143, 0xC>(lowest, v); v = t > v ? t : v;
+  return v;
 }
 
-// One thread per voxel: rank d inside its window, then the slots t with floor(t*N/(S*tau)) == d;
-// with a work list also the voxel's row of its tile descriptor.
-__global__ void k_emit(PartGeom g, const int4* __restrict__ coords, const uint32_t* __restrict__ keys, int32_t n,
-                       const uint32_t* __restrict__ bitmap, const uint32_t* __restrict__ word_prefix,
+struct Scan3 { int32_t a, b, m, xm; };
+__device__ __forceinline__ Scan3 block_scan3(Scan3 v, int32_t (*wave_tot)[16], int32_t* carry) {
+  const int32_t tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  v.a = wave_scan_add(v.a);
+  v.b = wave_scan_add(v.b);
+  v.m = wave_scan_max(v.m, -1);                         // (every m is at least -1)
+  const int32_t below = __shfl_up(v.m, 1, 64);
+  if (lane == 63) { wave_tot[0][wv] = v.a; wave_tot[1][wv] = v.b; wave_tot[2][wv] = v.m; }
+  __syncthreads();
+  int32_t pa = carry[0], pb = carry[1], pm = carry[2];
+  for (int32_t k = 0; k < wv; ++k) {
+    pa += wave_tot[0][k]; pb += wave_tot[1][k];
+    pm = wave_tot[2][k] > pm ? wave_tot[2][k] : pm;
+  }
+  v.a += pa; v.b += pb;
+  v.xm = lane == 0 ? pm : (below > pm ? below : pm);
+  v.m = pm > v.m ? pm : v.m;
+  __syncthreads();
+  if (tid == 1023) { carry[0] = v.a; carry[1] = v.b; carry[2] = v.m; }
+  return v;                                 // the new carry is visible after the caller's next barrier
+}
+
+// Small frames: everything before k_emit in one workgroup and one launch.  The bitmaps live in LDS
+// while the voxels are marked, so nothing has to be cleared in memory beforehand, and the per-window
+// and per-tile tables stay in LDS between the steps: the kernel reads the coordinates and writes its
+// results, with no trip through memory in between.  (Each step is a few microseconds of work; as
+// separate launches their start-up and the gaps between them are most of a partition's latency,
+// which the first layer of a frame has to wait for.)
+// Dynamic LDS, in 32-bit words: bitmaps [ax.n * n_words] | per window: voxels, first set, rows before
+// it, tiles started before it [4 * n_windows] | per tile: first set, rows before it [2 * (tile_cap + 1)],
+// launch slot [tile_cap].
+template <int NAX>
+__global__ void __launch_bounds__(1024) k_front(PartGeom g, const int4* __restrict__ coords, int32_t n, AxisSet ax,
+                                                int32_t n_words, int32_t* __restrict__ win_count,
+                                                int32_t* __restrict__ win_soff, int32_t max_sets,
+                                                int32_t* __restrict__ n_sets, int32_t* __restrict__ status, int32_t set_cap,
+                                                int32_t rows_per_cut, TileOut out, int32_t tile_cap,
+                                                int32_t* __restrict__ set_loc
+#ifdef DSVT_PHASE_CLOCKS
+                                                , long long* clk
+#endif
+                                                ) {
+  extern __shared__ uint32_t smem[];
+  DSVT_FCLK(0);
+  __shared__ int32_t wave_tot[3][16], carry1[3], carry2[3];
+  __shared__ int32_t p_cap, ok_seen, bits_seen, over_s, over_p;
+  __shared__ int32_t hist[32], running[32], wave_cnt[16][32];
+  const int32_t tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int32_t nw = g.n_windows, wpw = g.words_per_win, tau = g.tau;
+  const bool want_tiles = out.tile_desc[0] != nullptr;
+  const int32_t tile_lim = out.max_tiles < tile_cap ? out.max_tiles : tile_cap;
+  uint32_t* bm = smem;
+  int32_t* wN = (int32_t*)(smem + (size_t)ax.n * n_words);
+  int32_t *wSoff = wN + nw, *wP0 = wSoff + nw, *wT0 = wP0 + nw;
+  int32_t *tFirst = wT0 + nw, *tRows = tFirst + tile_cap + 1, *tPos = tRows + tile_cap + 1;
+
+  for (int32_t i = tid; i < ax.n * n_words; i += 1024) bm[i] = 0u;
+  if (tid == 0) {
+    carry1[0] = carry1[1] = 0; carry1[2] = -1;
+    carry2[0] = carry2[1] = 0; carry2[2] = -1;
+    p_cap = 0; ok_seen = 0; bits_seen = 0; over_s = -1; over_p = 0;
+  }
+  __syncthreads();
+  DSVT_FCLK(1);
+
+  // ---- mark: a bit per voxel and axis, straight-line code (a voxel outside the grid ORs a zero into
+  // word 0); the next eight coordinate loads of a thread are in flight while it handles the last eight.
+  // Divisions by the window sizes are 24-bit multiplications and shifts (the host takes this kernel only
+  // when they are exact).  Repeated cells are found afterwards: they leave fewer bits than there are
+  // voxels inside the grid.
+  uint32_t sx[2], sy[2];                                      // inner key = xi * sx + yi * sy + zi
+#pragma unroll
+  for (int32_t k = 0; k < 2; ++k) {
+    const bool x_major = ax.axis0 + k == 0;
+    sx[k] = (uint32_t)(x_major ? g.win[1] * g.win[2] : g.win[2]);
+    sy[k] = (uint32_t)(x_major ? g.win[2] : g.win[0] * g.win[2]);
+  }
+  int32_t n_ok = 0;
+  constexpr int32_t kB = 8;
+  int4 cn[kB];
+#pragma unroll
+  for (int32_t u = 0; u < kB; ++u) {
+    const int32_t i = tid + u * 1024;
+    cn[u] = coords[i < n ? i : n - 1];
+  }
+  for (int32_t i0 = tid; i0 < n; i0 += kB * 1024) {
+    int4 c[kB];
+#pragma unroll
+    for (int32_t u = 0; u < kB; ++u) c[u] = cn[u];
+    if (i0 + kB * 1024 < n) {
+#pragma unroll
+      for (int32_t u = 0; u < kB; ++u) {
+        const int32_t i = i0 + (kB + u) * 1024;
+        cn[u] = coords[i < n ? i : n - 1];
+      }
+    }
+#pragma unroll
+    for (int32_t u = 0; u < kB; ++u) {
+      const bool ok = i0 + u * 1024 < n && (uint32_t)c[u].x < (uint32_t)g.batch && (uint32_t)c[u].y < (uint32_t)g.grid[0] &&
+                      (uint32_t)c[u].z < (uint32_t)g.grid[1] && (uint32_t)c[u].w < (uint32_t)g.grid[2];
+      n_ok += ok ? 1 : 0;
+      const uint32_t x = (uint32_t)(c[u].y + g.shift[0]), y = (uint32_t)(c[u].z + g.shift[1]), z = (uint32_t)(c[u].w + g.shift[2]);
+      const uint32_t wx = mul24(x, g.mul24[0]) >> g.shr24[0], wy = mul24(y, g.mul24[1]) >> g.shr24[1],
+                     wz = mul24(z, g.mul24[2]) >> g.shr24[2];
+      const uint32_t xi = x - mul24(wx, (uint32_t)g.win[0]), yi = y - mul24(wy, (uint32_t)g.win[1]),
+                     zi = z - mul24(wz, (uint32_t)g.win[2]);
+      const uint32_t wkey = mul24(mul24(mul24((uint32_t)c[u].x, (uint32_t)g.nw[0]) + wx, (uint32_t)g.nw[1]) + wy, (uint32_t)g.nw[2]) + wz;
+      const uint32_t wword = mul24(wkey, (uint32_t)wpw);
+#pragma unroll
+      for (int32_t k = 0; k < NAX; ++k) {
+        const uint32_t inner = mul24(xi, sx[k]) + mul24(yi, sy[k]) + zi;
+        const uint32_t word = wword + (inner >> 5) + (uint32_t)(k * n_words);
+#if defined(DSVT_EXP) && DSVT_EXP == 1
+        n_ok += (int32_t)((word ^ inner) & 1u);
+#else
+        atomicOr(&bm[ok ? word : 0u], ok ? 1u << (inner & 31u) : 0u);
+#endif
+      }
+    }
+  }
+  if (n_ok != 0) atomicAdd(&ok_seen, n_ok);
+  __syncthreads();
+  DSVT_FCLK(2);
+
+  // ---- a thread per window: count, word prefixes, then scans over the windows of (sets, padded rows,
+  // last set's rows of the latest non-empty window) and of the tiles its sets start
+  int32_t my_bits = 0;
+  for (int32_t base = 0; base < nw; base += 1024) {
+    const int32_t w = base + tid;
+    int32_t N = 0;
+    if (w < nw) {
+#pragma unroll
+      for (int32_t k = 0; k < NAX; ++k) {
+        const uint32_t w0 = mul24((uint32_t)w, (uint32_t)wpw);
+        const uint32_t* src = bm + (uint32_t)(k * n_words) + w0;
+        uint32_t* dst_b = ax.a[k].bitmap + w0;
+        uint32_t* dst_p = ax.a[k].prefix + w0;
+        uint32_t run = 0;
+        for (int32_t j = 0; j < wpw; ++j) {
+          const uint32_t v = src[j];
+          dst_b[j] = v;
+          dst_p[j] = run;
+          run += (uint32_t)__popc(v);
+        }
+        N = (int32_t)run;                                     // the same for every axis
+      }
+      win_count[w] = N;
+      my_bits += N;
+    }
+    const int32_t S = (int32_t)div_magic((uint32_t)(N + tau - 1), g.magic_tau);
+    SetWalk walk(N, S, tau);
+    int32_t R = 0, last_rows = 0;
+    for (int32_t j = 0; j < S; ++j) { last_rows = set_rows(walk.next()); R += last_rows; }
+    Scan3 v = {S, R, S > 0 ? (w << 7) | last_rows : -1, -1};
+    v = block_scan3(v, wave_tot, carry1);
+    const int32_t soff = v.a - S, P0 = v.b - R;
+    const int32_t prev = v.xm;                  // (window << 7 | rows of its last set) of the latest non-empty window before
+    int32_t F = 0;
+    if (w < nw) {
+      win_soff[w] = soff;
+      wN[w] = N; wSoff[w] = soff; wP0[w] = P0;
+    }
+    // Set s starts a tile when a multiple of rows_per_cut lies in (rows before set s - 1, rows before set s],
+    // that is when (rows before set s - 1) mod rows_per_cut plus the rows of set s - 1 reach rows_per_cut.
+    const int32_t prev_rows0 = prev >= 0 ? (prev & 127) : 0;
+    const int32_t d0 = P0 - prev_rows0;                       // rows before the previous set
+    const int32_t m0 = d0 - (int32_t)div_magic((uint32_t)d0, g.magic_cut) * rows_per_cut;
+    auto for_each_set = [&](auto&& fn) {
+      int32_t P = P0, pr = prev_rows0, m = m0;
+      walk.restart();
+      for (int32_t j = 0; j < S; ++j) {
+        const int32_t s = soff + j;
+        if (s == set_cap) p_cap = P;
+        if (s >= set_cap) break;
+        const bool first = s == 0 || m + pr >= rows_per_cut;
+        m += pr;
+        while (m >= rows_per_cut) m -= rows_per_cut;
+        fn(s, P, first);
+        pr = set_rows(walk.next());
+        P += pr;
+      }
+    };
+    if (want_tiles) for_each_set([&](int32_t, int32_t, bool first) { F += first ? 1 : 0; });
+    Scan3 f = {F, 0, -1, -1};
+    f = block_scan3(f, wave_tot, carry2);
+    if (want_tiles && w < nw) {
+      int32_t t = f.a - F;                                    // tiles started before this window
+      wT0[w] = t;
+      for_each_set([&](int32_t s, int32_t P, bool first) {
+        if (!first) return;
+        if (t < tile_lim) { tFirst[t] = s; tRows[t] = P; out.tile_first[t] = s; }
+        else if (t == tile_lim) { over_s = s; over_p = P; }        // first set that no tile is left for
+        ++t;
+      });
+    }
+  }
+  if (my_bits != 0) atomicAdd(&bits_seen, my_bits);
+  __syncthreads();
+  DSVT_FCLK(3);
+  const int32_t n_tot = carry1[0];
+  if (tid == 0) {
+    *n_sets = n_tot;
+    int32_t bad = n_tot > max_sets ? DSVT_ST_SET_OVERFLOW : 0;
+    if (ok_seen < n) bad |= DSVT_ST_COORD_RANGE;
+    if (bits_seen < ok_seen) bad |= DSVT_ST_COORD_REPEAT;     // fewer bits than voxels inside the grid
+    if (bad) atomicOr(status, bad);
+  }
+  if (!want_tiles) return;
+  const bool tiles_short = carry2[0] > tile_lim;          // the caller's list is shorter than the frame needs: later sets get no tile
+  const int32_t n_eff = tiles_short ? over_s : (n_tot < set_cap ? n_tot : set_cap);
+  const int32_t nt = tiles_short ? tile_lim : carry2[0];
+  if (n_eff <= 0) {
+    if (tid == 0) { *out.n_tiles = 0; out.tile_first[0] = 0; }
+    return;
+  }
+  if (tid == 0) {
+    *out.n_tiles = nt;
+    out.tile_first[nt] = n_eff;
+    tFirst[nt] = n_eff;
+    tRows[nt] = tiles_short ? over_p : (n_tot <= set_cap ? carry1[1] : p_cap);
+  }
+  if (tid < 32) hist[tid] = 0;
+  __syncthreads();
+
+  // ---- launch order = tiles with more rows first (a stable counting sort on rows / 4), so that the
+  // short tiles fill the tail of the launch
+  for (int32_t base = 0; base < nt; base += 1024) {
+    const int32_t t = base + tid;
+    if (t < nt) {
+      int32_t b = 24 - (tRows[t + 1] - tRows[t]) / 4;
+      b = b < 0 ? 0 : (b > 31 ? 31 : b);
+      atomicAdd(&hist[b], 1);
+    }
+  }
+  __syncthreads();
+  if (tid == 0) { int32_t acc = 0; for (int32_t b = 0; b < 32; ++b) { running[b] = acc; acc += hist[b]; } }
+  __syncthreads();
+  for (int32_t base = 0; base < nt; base += 1024) {
+    const int32_t t = base + tid;
+    int32_t b = -1;
+    if (t < nt) {
+      b = 24 - (tRows[t + 1] - tRows[t]) / 4;
+      b = b < 0 ? 0 : (b > 31 ? 31 : b);
+    }
+    for (int32_t k = lane; k < 32; k += 64) wave_cnt[wv][k] = 0;
+    int32_t rank = 0;                                         // among this wavefront's lanes of the same bucket
+    unsigned long long todo = __ballot(b >= 0);
+    while (todo) {
+      const int32_t leader = __ffsll((long long)todo) - 1;
+      const int32_t lb = __shfl(b, leader, 64);
+      const unsigned long long same = __ballot(b == lb);
+      if (b == lb) rank = __popcll(same & ((1ull << lane) - 1ull));
+      if (lane == leader) wave_cnt[wv][lb] = __popcll(same);
+      todo &= ~same;
+    }
+    __syncthreads();
+    if (b >= 0) {
+      int32_t pos = running[b] + rank;
+      for (int32_t k = 0; k < wv; ++k) pos += wave_cnt[k][b];
+      out.tile_order[pos] = t;
+      tPos[t] = pos;
+      desc_header(out, pos, tRows[t + 1] - tRows[t], tFirst[t + 1] - tFirst[t]);
+    }
+    __syncthreads();
+    if (tid < 32) { int32_t add = 0; for (int32_t k = 0; k < 16; ++k) add += wave_cnt[k][tid]; running[tid] += add; }
+    __syncthreads();
+  }
+
+  DSVT_FCLK(4);
+  // ---- per set: its descriptor slot, first row and distinct count; set_loc[s] for k_emit
+  for (int32_t w = tid; w < nw; w += 1024) {
+    const int32_t N = wN[w], S = (int32_t)div_magic((uint32_t)(N + tau - 1), g.magic_tau), soff = wSoff[w];
+    int32_t P = wP0[w], t = wT0[w] - 1;
+    SetWalk walk(N, S, tau);
+    for (int32_t j = 0; j < S; ++j) {
+      const int32_t s = soff + j;
+      if (s >= set_cap) break;
+      const int32_t nu = walk.next();
+      if (t + 1 < nt && tFirst[t + 1] == s) ++t;
+      int32_t loc = -1;
+      if (t >= 0 && t < nt && s < n_eff) {
+        const int32_t pos = tPos[t], ls = s - tFirst[t], r0 = P - tRows[t];
+        if (ls >= 0 && ls < kDescSets && r0 >= 0 && r0 <= kTileRows - 4) {
+          desc_set(out, pos, ls, r0, nu);
+          loc = (pos << 7) | r0;
+        }
+      }
+      set_loc[s] = loc;
+      P += set_rows(nu);
+    }
+  }
+  DSVT_FCLK(5);
+}
+
+// One thread per voxel and axis (blockIdx.y): rank d inside its window, then the slots t with
+// floor(t*N/(S*tau)) == d; with a work list also the voxel's row of its tile descriptor.  The blocks
+// after the voxels' (blockIdx.x >= vox_blocks) put -1 into the descriptor rows past each tile's last.
+__global__ void k_emit(PartGeom g, const int4* __restrict__ coords, int32_t n, AxisSet ax, int32_t vox_blocks,
                        const int32_t* __restrict__ win_count, const int32_t* __restrict__ win_soff, int32_t max_sets,
-                       int32_t* __restrict__ set_inds, int32_t* __restrict__ voxel_slot, int32_t* __restrict__ set_win,
-                       const int32_t* __restrict__ set_loc, int32_t* __restrict__ tile_desc, int32_t n_desc_slots) {
+                       int32_t* __restrict__ set_win, const int32_t* __restrict__ set_loc,
+                       const int32_t* __restrict__ n_tiles, int32_t n_desc_slots) {
+  const AxisBufs& me = ax.a[blockIdx.y];
+  int32_t* __restrict__ tile_desc = me.tile_desc;
+  if ((int32_t)blockIdx.x >= vox_blocks) {
+    if (tile_desc == nullptr) return;
+    const int32_t idx = ((int32_t)blockIdx.x - vox_blocks) * blockDim.x + threadIdx.x;
+    const int32_t pos = idx / kTileRows, r = idx - pos * kTileRows;
+    int32_t nt = *n_tiles;
+    nt = nt < n_desc_slots ? nt : n_desc_slots;
+    if (pos >= nt) return;
+    int32_t* dd = tile_desc + (int64_t)pos * kDescInts;
+    if (r >= dd[0]) { dd[kDescVox + r] = -1; dd[kDescLin + r] = -1; }
+    return;
+  }
   int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= n) return;
-  uint32_t key = keys[i];
-  if (key == kBadKey) { voxel_slot[i] = -1; return; }
+  const int4 c = coords[i];
+  uint32_t wkey; int32_t xi, yi, zi;
+  if (!voxel_cell(g, c, wkey, xi, yi, zi)) { me.voxel_slot[i] = -1; return; }
+  const uint32_t key = voxel_key(g, ax.axis0 + (int32_t)blockIdx.y, wkey, xi, yi, zi);
   const int32_t tau = g.tau;
   uint32_t word = key >> 5, bit = key & 31u;
-  int32_t w = (int32_t)(word / (uint32_t)g.words_per_win);
-  int64_t d = word_prefix[word] + (uint32_t)__popc(bitmap[word] & ((1u << bit) - 1u));
+  const int32_t w = (int32_t)wkey;
+  int64_t d = me.prefix[word] + (uint32_t)__popc(me.bitmap[word] & ((1u << bit) - 1u));
   int64_t N = win_count[w];
   int64_t S = (N + tau - 1) / tau, T = S * tau;
   int64_t t_lo, t_hi, first_d;                               // first_d: rank of the first voxel of this voxel's first set
   if (N > 0 && N < 32768 && T < 65536) {                     // the usual case: 32-bit division
-    const uint32_t n = (uint32_t)N, tt = (uint32_t)T, dd = (uint32_t)d;
-    const uint32_t lo = (dd * tt + n - 1u) / n, hi = ((dd + 1u) * tt + n - 1u) / n;
+    const uint32_t nn = (uint32_t)N, tt = (uint32_t)T, dd = (uint32_t)d;
+    const uint32_t lo = (dd * tt + nn - 1u) / nn, hi = ((dd + 1u) * tt + nn - 1u) / nn;
     t_lo = lo; t_hi = hi;
-    first_d = ((lo / (uint32_t)tau) * (uint32_t)tau * n) / tt;
+    first_d = ((lo / (uint32_t)tau) * (uint32_t)tau * nn) / tt;
   } else {
     t_lo = (d * T + N - 1) / N; t_hi = ((d + 1) * T + N - 1) / N;
     first_d = ((t_lo / tau) * tau * N) / T;
   }
   int64_t base = (int64_t)win_soff[w] * tau, cap = (int64_t)max_sets * tau;
-  voxel_slot[i] = (int32_t)(base + t_lo);
+  me.voxel_slot[i] = (int32_t)(base + t_lo);
   const int32_t j_first = (int32_t)t_lo / tau;               // (t < S * tau and slots < max_sets * tau fit 32 bits)
   int32_t next_set_start = (int32_t)t_lo == j_first * tau ? (int32_t)t_lo : (j_first + 1) * tau;
+  const bool names_sets = blockIdx.y == 0;                   // the window of a set is the same for every axis
   for (int32_t t = (int32_t)t_lo; t < (int32_t)t_hi; ++t) {
     const int64_t slot = base + t;
     if (slot >= cap) break;
-    set_inds[slot] = i;
-    if (t == next_set_start) { set_win[win_soff[w] + t / tau] = w; next_set_start += tau; }
+    me.set_inds[slot] = i;
+    if (t == next_set_start) {
+      if (names_sets) set_win[win_soff[w] + t / tau] = w;
+      next_set_start += tau;
+    }
   }
   if (tile_desc != nullptr) {
     const int64_t j = j_first, s = win_soff[w] + j;
@@ -397,7 +794,6 @@ __global__ void k_emit(PartGeom g, const int4* __restrict__ coords, const uint32
       const int32_t loc = set_loc[s];
       const int32_t slot = loc >> 7, row = (loc & 127) + (int32_t)(d - first_d);
       if (slot >= 0 && slot < n_desc_slots && row < kTileRows) {
-        const int4 c = coords[i];
         const int32_t lin = (c.y * (2 * g.win[1] - 1) + c.z) * (2 * g.win[2] - 1) + c.w;
         int32_t* dd = tile_desc + (int64_t)slot * kDescInts;
         dd[kDescVox + row] = i;
@@ -409,7 +805,7 @@ __global__ void k_emit(PartGeom g, const int4* __restrict__ coords, const uint32
 
 struct PartPlan {
   PartGeom g;
-  size_t off_bitmap, off_prefix, off_count, off_soff, off_keys, off_setwin, off_tilerows, off_tilepos, off_setp, off_setloc, total;
+  size_t off_bitmap, off_prefix, off_count, off_soff, off_setwin, off_tilerows, off_tilepos, off_setp, off_setloc, total;
   bool desc_ok;
   int64_t n_words;
   int32_t set_bound, tile_bound, rows_per_cut;
@@ -424,30 +820,34 @@ int make_plan(const dsvt_part_cfg* cfg, int32_t n_voxels, PartPlan* p) {
     if (cfg->grid[a] <= 0 || cfg->win[a] <= 0 || cfg->shift[a] < 0 || cfg->shift[a] >= cfg->win[a]) return DSVT_EINVAL;
     g.grid[a] = cfg->grid[a]; g.win[a] = cfg->win[a]; g.shift[a] = cfg->shift[a];
     g.nw[a] = (int32_t)dsvt_ceil_div((int64_t)cfg->grid[a] + cfg->shift[a], cfg->win[a]);
+    g.magic[a] = (cfg->win[a] > 1 && cfg->win[a] < (1 << 15) && (int64_t)cfg->grid[a] + cfg->shift[a] < (1 << 16))
+                     ? (uint32_t)(((1ull << 32) + (uint64_t)cfg->win[a] - 1) / (uint64_t)cfg->win[a]) : 0u;
     vol *= cfg->win[a];
     nwin *= g.nw[a];
     if (vol >= (1ll << 31) || nwin >= (1ll << 31)) return DSVT_EINVAL;
   }
-  g.batch = cfg->batch; g.tau = cfg->tau; g.axis = cfg->axis;
+  g.batch = cfg->batch; g.tau = cfg->tau;
+  g.magic_tau = g.magic_cut = 0u;
   int64_t wpw = dsvt_ceil_div(vol, 32);
   if (nwin * wpw * 32 >= (1ll << 31)) return DSVT_EINVAL;   // composite keys are 32-bit
   g.words_per_win = (int32_t)wpw;
   g.n_windows = (int32_t)nwin;
   p->n_words = nwin * wpw;
-  size_t o = 0;
-  p->off_bitmap = o; o = dsvt_align_up(o + (size_t)p->n_words * 4, 256);
-  p->off_prefix = o; o = dsvt_align_up(o + (size_t)p->n_words * 4, 256);
+  size_t o = 0;                                             // bitmaps and prefixes: room for both axes, back to back
+  p->off_bitmap = o; o = dsvt_align_up(o + (size_t)p->n_words * 8, 256);
+  p->off_prefix = o; o = dsvt_align_up(o + (size_t)p->n_words * 8, 256);
   p->off_count = o;  o = dsvt_align_up(o + (size_t)nwin * 4, 256);
   p->off_soff = o;   o = dsvt_align_up(o + (size_t)nwin * 4, 256);
-  p->off_keys = o;   o = dsvt_align_up(o + (size_t)n_voxels * 4, 256);
   const int64_t bound = n_voxels / cfg->tau + (n_voxels < nwin ? n_voxels : nwin);
   if (bound * cfg->tau >= (1ll << 31)) return DSVT_EINVAL;
   p->set_bound = (int32_t)bound;
   p->off_setwin = o; o = dsvt_align_up(o + (size_t)bound * 4, 256);
-  // tiles of the layer kernels: 96 rows, every set padded to a multiple of 4 rows
+  // tiles of the layer kernels: 96 rows, every set padded to a multiple of 4 rows.  The sets of a window
+  // with N voxels list at most N + S - 1 distinct voxels (neighbours may share one), so all sets
+  // together have at most n + 4 * bound rows, and every rows_per_cut of them start at most one tile.
   const int64_t pad_tau = (cfg->tau + 3) & ~3;
   p->rows_per_cut = (int32_t)(100 - pad_tau);
-  p->tile_bound = p->rows_per_cut > 0 ? (int32_t)((n_voxels + 3 * bound) / p->rows_per_cut + 1) : 0;
+  p->tile_bound = p->rows_per_cut > 0 ? (int32_t)((n_voxels + 4 * bound) / p->rows_per_cut + 1) : 0;
   p->off_tilerows = o; o = dsvt_align_up(o + (size_t)(p->tile_bound + 1) * 4, 256);
   p->off_tilepos = o;  o = dsvt_align_up(o + (size_t)(p->tile_bound + 1) * 4, 256);
   p->off_setp = o;     o = dsvt_align_up(o + (size_t)(bound + 1) * 4, 256);
@@ -459,34 +859,27 @@ int make_plan(const dsvt_part_cfg* cfg, int32_t n_voxels, PartPlan* p) {
   return DSVT_OK;
 }
 
-}  // namespace
-
-extern "C" int dsvt_partition_bound(const dsvt_part_cfg* cfg, int32_t n_voxels, int32_t* max_sets, int32_t* max_tiles,
-                                    size_t* ws_bytes) {
+// The partition of n_axes inner orders (axis0, axis0 + 1) of one window configuration.
+int run_partition(const dsvt_part_cfg* cfg, int32_t n_axes, int32_t axis0, const int32_t* coords, int32_t n_voxels,
+                  int32_t* const* set_inds, int32_t* const* voxel_slot, int32_t* n_sets, int32_t max_sets, int32_t* set_win,
+                  const dsvt_tile_list* tiles, int32_t* tile_desc_2, void* ws, size_t ws_bytes, int32_t* status,
+                  void* stream) {
   PartPlan p;
   int rc = make_plan(cfg, n_voxels, &p);
   if (rc != DSVT_OK) return rc;
-  if (max_sets) *max_sets = p.set_bound;
-  if (max_tiles) *max_tiles = p.tile_bound;
-  if (ws_bytes) *ws_bytes = p.total;
-  return DSVT_OK;
-}
-
-extern "C" int dsvt_partition(const dsvt_part_cfg* cfg, const int32_t* coords, int32_t n_voxels, int32_t* set_inds,
-                              int32_t* voxel_slot, int32_t* n_sets, int32_t max_sets, int32_t* set_win,
-                              const dsvt_tile_list* tiles, void* ws, size_t ws_bytes, int32_t* status, void* stream) {
-  PartPlan p;
-  int rc = make_plan(cfg, n_voxels, &p);
-  if (rc != DSVT_OK) return rc;
-  if (!coords || !set_inds || !voxel_slot || !n_sets || !ws || !status || max_sets <= 0) return DSVT_EINVAL;
+  if (!coords || !n_sets || !ws || !status || max_sets <= 0) return DSVT_EINVAL;
+  for (int32_t k = 0; k < n_axes; ++k)
+    if (!set_inds[k] || !voxel_slot[k]) return DSVT_EINVAL;
   if ((int64_t)max_sets * cfg->tau >= (1ll << 31)) return DSVT_EINVAL;
   if (ws_bytes < p.total) return DSVT_ENOSPC;
-  TileOut tout = {nullptr, nullptr, nullptr, nullptr, 0};
+  TileOut tout = {nullptr, nullptr, nullptr, {nullptr, nullptr}, 0};
   if (tiles != nullptr) {
     if (!tiles->tile_first || !tiles->n_tiles || !tiles->tile_order || !tiles->tile_desc || tiles->max_tiles <= 0) return DSVT_EINVAL;
+    if (n_axes == 2 && !tile_desc_2) return DSVT_EINVAL;
     if (!p.desc_ok) return DSVT_EUNSUPPORTED;
     tout.tile_first = tiles->tile_first; tout.n_tiles = tiles->n_tiles; tout.tile_order = tiles->tile_order;
-    tout.tile_desc = tiles->tile_desc;
+    tout.tile_desc[0] = tiles->tile_desc;
+    tout.tile_desc[1] = n_axes == 2 ? tile_desc_2 : nullptr;
     tout.max_tiles = tiles->max_tiles < p.tile_bound ? tiles->max_tiles : p.tile_bound;   // scratch is sized for the bound
   }
   // window key of every set: the caller's array, or scratch when it is not wanted
@@ -494,37 +887,72 @@ extern "C" int dsvt_partition(const dsvt_part_cfg* cfg, const int32_t* coords, i
   if (set_win == nullptr) set_win = (int32_t*)((char*)ws + p.off_setwin);   // k_emit rewrites the same values there
   hipStream_t st = (hipStream_t)stream;
   char* base = (char*)ws;
-  uint32_t* bitmap = (uint32_t*)(base + p.off_bitmap);
-  uint32_t* prefix = (uint32_t*)(base + p.off_prefix);
   int32_t* count = (int32_t*)(base + p.off_count);
   int32_t* soff = (int32_t*)(base + p.off_soff);
-  uint32_t* keys = (uint32_t*)(base + p.off_keys);
   int32_t* set_loc = (int32_t*)(base + p.off_setloc);
+  AxisSet ax = {};
+  ax.n = n_axes; ax.axis0 = axis0;
+  for (int32_t k = 0; k < n_axes; ++k) {
+    ax.a[k].bitmap = (uint32_t*)(base + p.off_bitmap) + (size_t)k * p.n_words;
+    ax.a[k].prefix = (uint32_t*)(base + p.off_prefix) + (size_t)k * p.n_words;
+    ax.a[k].set_inds = set_inds[k]; ax.a[k].voxel_slot = voxel_slot[k];
+    ax.a[k].tile_desc = tout.tile_desc[k];
+  }
   const int tb = 256;
-  {
-    dsvt_prof_scope ps(DSVT_K_PART_CLEAR, st);
-    const int64_t n_desc = (int64_t)tout.max_tiles * kDescInts;
-    const int64_t n_clear = p.n_words > n_desc ? p.n_words : n_desc;
-    k_clear<<<(unsigned)dsvt_ceil_div(n_clear, tb), tb, 0, st>>>(bitmap, p.n_words, tout.tile_desc, n_desc);
+  // k_front divides by multiplying: exact for x < 2^16 and d < 2^15 (window sizes, and tau against a window's
+  // volume + tau), and for x < 2^25 and d <= 128 (rows of a tile cut against all padded rows)
+  bool front_ok = n_voxels <= kFrontVoxels && (int64_t)p.g.words_per_win * 32 + cfg->tau < (1 << 16) && cfg->tau < (1 << 15);
+  for (int a = 0; a < 3; ++a) {
+    // x / d = (x * m) >> k with m = ceil(2^k / d) whenever x * (m * d - 2^k) < 2^k; x * d <= 2^k suffices.  With
+    // x < X <= 2^15 and 2^k the first power of two >= X * d: m <= 2 X, so x * m fits 32 bits and m fits 24.
+    const int64_t X = (int64_t)cfg->grid[a] + cfg->shift[a], d = cfg->win[a];
+    int k = 0;
+    while ((1ll << k) < X * d) ++k;
+    front_ok = front_ok && X <= (1 << 15) && k <= 30;
+    p.g.mul24[a] = front_ok ? (uint32_t)(((1ll << k) + d - 1) / d) : 0u;
+    p.g.shr24[a] = (uint32_t)k;
   }
-  {
-    dsvt_prof_scope ps(DSVT_K_PART_MARK, st);
-    k_mark<<<(unsigned)dsvt_ceil_div(n_voxels, tb), tb, 0, st>>>(p.g, (const int4*)coords, n_voxels, bitmap, keys, status);
+  front_ok = front_ok && p.g.n_windows < (1 << 22) && p.n_words * n_axes < (1 << 22);
+  if (front_ok) {
+    p.g.magic_tau = (uint32_t)(((1ull << 32) + (uint64_t)cfg->tau - 1) / (uint64_t)cfg->tau);
+    if (cfg->tau == 1) front_ok = false;                      // (2^32 does not fit the multiplier)
+    const int32_t cut = p.rows_per_cut > 1 ? p.rows_per_cut : 2;
+    p.g.magic_cut = (uint32_t)(((1ull << 32) + (uint64_t)cut - 1) / (uint64_t)cut);
+    if (tiles != nullptr && p.rows_per_cut < 2) front_ok = false;
   }
-  int32_t group = 1;
-  while (group < 64 && group < p.g.words_per_win) group <<= 1;
-  if ((int64_t)p.g.n_windows * group <= kFusedThreads) {
+  const size_t front_lds = ((size_t)n_axes * p.n_words + 4 * (size_t)p.g.n_windows + 3 * (size_t)(p.tile_bound + 1)) * 4;
+  if (front_ok && front_lds <= kFrontLds) {
+    static bool lds_raised = false;                          // (the same value every time: a benign race)
+    if (!lds_raised) {
+      DSVT_HIP_TRY(hipFuncSetAttribute((const void*)k_front<1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFrontLds));
+      DSVT_HIP_TRY(hipFuncSetAttribute((const void*)k_front<2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFrontLds));
+      lds_raised = true;
+    }
     dsvt_prof_scope ps(DSVT_K_PART_TILES, st);
-    k_count_scan_tiles<<<1, 1024, 0, st>>>(bitmap, prefix, count, soff, p.g.n_windows, p.g.words_per_win, group, cfg->tau,
-                                           max_sets, n_sets, status, (int32_t*)(base + p.off_setwin), p.set_bound, set_cap,
-                                           p.rows_per_cut, tout, (int32_t*)(base + p.off_tilerows),
-                                           (int32_t*)(base + p.off_tilepos), (int32_t*)(base + p.off_setp), set_loc);
+    auto* front = n_axes == 2 ? k_front<2> : k_front<1>;
+    front<<<1, 1024, front_lds, st>>>(p.g, (const int4*)coords, n_voxels, ax, (int32_t)p.n_words, count, soff, max_sets,
+                                        n_sets, status, set_cap, p.rows_per_cut, tout, p.tile_bound, set_loc
+#ifdef DSVT_PHASE_CLOCKS
+                                        , g_front_clocks
+#endif
+                                        );
   } else {
+    {
+      dsvt_prof_scope ps(DSVT_K_PART_CLEAR, st);
+      const int64_t n_clear = p.n_words * n_axes;
+      k_clear<<<(unsigned)dsvt_ceil_div(n_clear, tb), tb, 0, st>>>(ax.a[0].bitmap, n_clear);
+    }
+    {
+      dsvt_prof_scope ps(DSVT_K_PART_MARK, st);
+      k_mark<<<(unsigned)dsvt_ceil_div(n_voxels, tb), tb, 0, st>>>(p.g, (const int4*)coords, n_voxels, ax, status);
+    }
+    int32_t group = 1;
+    while (group < 64 && group < p.g.words_per_win) group <<= 1;
     {
       dsvt_prof_scope ps(DSVT_K_PART_COUNT, st);
       int64_t threads = (int64_t)p.g.n_windows * group;
-      k_window_count<<<(unsigned)dsvt_ceil_div(threads, tb), tb, 0, st>>>(bitmap, prefix, count, p.g.n_windows,
-                                                                          p.g.words_per_win, group);
+      k_window_count<<<dim3((unsigned)dsvt_ceil_div(threads, tb), n_axes), tb, 0, st>>>(ax, count, p.g.n_windows,
+                                                                                       p.g.words_per_win, group);
     }
     {
       dsvt_prof_scope ps(DSVT_K_PART_SCAN, st);
@@ -540,10 +968,48 @@ extern "C" int dsvt_partition(const dsvt_part_cfg* cfg, const int32_t* coords, i
   }
   {
     dsvt_prof_scope ps(DSVT_K_PART_EMIT, st);
-    k_emit<<<(unsigned)dsvt_ceil_div(n_voxels, tb), tb, 0, st>>>(p.g, (const int4*)coords, keys, n_voxels, bitmap, prefix,
-                                                                 count, soff, set_cap, set_inds, voxel_slot, set_win, set_loc,
-                                                                 tout.tile_desc, tout.max_tiles);
+    const int32_t vox_blocks = (int32_t)dsvt_ceil_div(n_voxels, tb);
+    const int32_t tail_blocks = (int32_t)dsvt_ceil_div((int64_t)tout.max_tiles * kTileRows, tb);
+    k_emit<<<dim3((unsigned)(vox_blocks + tail_blocks), n_axes), tb, 0, st>>>(p.g, (const int4*)coords, n_voxels, ax, vox_blocks,
+                                                                            count, soff, set_cap, set_win, set_loc,
+                                                                            tout.n_tiles, tout.max_tiles);
   }
   DSVT_HIP_TRY(hipGetLastError());
   return DSVT_OK;
+}
+
+}  // namespace
+
+#ifdef DSVT_PHASE_CLOCKS
+extern "C" void dsvt_debug_front_clocks(long long* dev_buf) { g_front_clocks = dev_buf; }
+#endif
+
+extern "C" int dsvt_partition_bound(const dsvt_part_cfg* cfg, int32_t n_voxels, int32_t* max_sets, int32_t* max_tiles,
+                                    size_t* ws_bytes) {
+  PartPlan p;
+  int rc = make_plan(cfg, n_voxels, &p);
+  if (rc != DSVT_OK) return rc;
+  if (max_sets) *max_sets = p.set_bound;
+  if (max_tiles) *max_tiles = p.tile_bound;
+  if (ws_bytes) *ws_bytes = p.total;
+  return DSVT_OK;
+}
+
+extern "C" int dsvt_partition(const dsvt_part_cfg* cfg, const int32_t* coords, int32_t n_voxels, int32_t* set_inds,
+                              int32_t* voxel_slot, int32_t* n_sets, int32_t max_sets, int32_t* set_win,
+                              const dsvt_tile_list* tiles, void* ws, size_t ws_bytes, int32_t* status, void* stream) {
+  if (cfg == nullptr) return DSVT_EINVAL;
+  return run_partition(cfg, 1, cfg->axis, coords, n_voxels, &set_inds, &voxel_slot, n_sets, max_sets, set_win, tiles, nullptr,
+                       ws, ws_bytes, status, stream);
+}
+
+extern "C" int dsvt_partition_xy(const dsvt_part_cfg* cfg, const int32_t* coords, int32_t n_voxels, int32_t* set_inds_x,
+                                 int32_t* set_inds_y, int32_t* voxel_slot_x, int32_t* voxel_slot_y, int32_t* n_sets,
+                                 int32_t max_sets, int32_t* set_win, const dsvt_tile_list* tiles, int32_t* tile_desc_y,
+                                 void* ws, size_t ws_bytes, int32_t* status, void* stream) {
+  if (cfg == nullptr) return DSVT_EINVAL;
+  int32_t* const si[2] = {set_inds_x, set_inds_y};
+  int32_t* const vs[2] = {voxel_slot_x, voxel_slot_y};
+  return run_partition(cfg, 2, 0, coords, n_voxels, si, vs, n_sets, max_sets, set_win, tiles, tile_desc_y, ws, ws_bytes,
+                       status, stream);
 }

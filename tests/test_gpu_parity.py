@@ -13,7 +13,7 @@ from oracle import dsvt_oracle as orc
 pytestmark = pytest.mark.gpu
 
 dsvt = pytest.importorskip("paper_2301_06051_amd")
-from gpu_util import TOL, assert_maps_equal, dev_coords, dev_feats, gpu_maps, rel_err  # noqa: E402
+from gpu_util import TOL, assert_maps_equal, assert_tiles_valid, dev_coords, dev_feats, gpu_maps, rel_err  # noqa: E402
 
 
 def _say(msg):
@@ -31,6 +31,45 @@ def test_partition_bit_exact(cid, n, axis):
     om = orc.partition(coords, cfg["grid"], cfg["win"], shift, cfg["tau"], axis)
     gm = gpu_maps(dev_coords(coords), cfg["grid"], cfg["win"], shift, cfg["tau"], cfg["batch"], axis)
     assert_maps_equal(gm, om)
+
+
+@pytest.mark.parametrize("cid,n", [(1, None), (2, None), (3, None), (2, 777), (3, 5000), (5, 30000)])
+def test_partition_xy_bit_exact(cid, n):
+    """Both rotated partitions from one call: each equals the oracle's partition of its axis, and the
+    Y-axis maps share the set counts, window keys and tile boundaries of the X-axis maps."""
+    cfg = synth.CONFIGS[cid]
+    coords = synth.make_frame(cid, n=n)
+    shift = cfg["shifts"][-1]
+    _say(f"partition_xy cfg{cid} n={len(coords)} shift={shift}")
+    pc = dsvt.part_cfg(cfg["grid"], cfg["win"], shift, cfg["tau"], cfg["batch"], 0)
+    pair = dsvt.dsvt_partition_xy(pc, dev_coords(coords))
+    for axis in (0, 1):
+        assert_maps_equal(pair[axis], orc.partition(coords, cfg["grid"], cfg["win"], shift, cfg["tau"], axis))
+    assert pair[1].n_sets.data_ptr() == pair[0].n_sets.data_ptr()
+    # a second call into the same buffers (nothing left over from the first may matter)
+    coords2 = synth.make_frame(cid, n=max(len(coords) // 2, 1))
+    pair2 = dsvt.SetMapsXY(pc, len(coords2))
+    for m in (pair2.x, pair2.y):
+        m.tile_desc.fill_(12345)                      # descriptors are not cleared by the caller
+    dsvt.dsvt_partition_xy(pc, dev_coords(coords2), out=pair2)
+    dsvt.dsvt_partition_xy(pc, dev_coords(coords2), out=pair2)
+    for axis in (0, 1):
+        om = orc.partition(coords2, cfg["grid"], cfg["win"], shift, cfg["tau"], axis)
+        torch.cuda.synchronize()
+        n_sets = int(pair2[axis].n_sets.item())
+        assert n_sets == om["n_sets"]
+        assert np.array_equal(pair2[axis].set_inds[:n_sets].cpu().numpy(), om["set_inds"])
+        assert_tiles_valid(pair2[axis], om)
+
+
+def test_partition_xy_odd_geometry_and_batch():
+    grid, win, shift, tau = (29, 17, 9), (5, 7, 3), (2, 6, 1), 11
+    coords = np.concatenate([np.concatenate([np.full((900, 1), b), synth.frame_uniform(60 + b, grid, 900)], 1)
+                             for b in range(3)]).astype(np.int32)
+    _say("partition_xy odd geometry")
+    pair = dsvt.dsvt_partition_xy(dsvt.part_cfg(grid, win, shift, tau, 3, 0), dev_coords(coords))
+    for axis in (0, 1):
+        assert_maps_equal(pair[axis], orc.partition(coords, grid, win, shift, tau, axis))
 
 
 @pytest.mark.parametrize("n", [1, 35, 36, 37, 72, 73])
