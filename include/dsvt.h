@@ -32,7 +32,7 @@ extern "C" {
 enum { DSVT_OK = 0, DSVT_EINVAL = -1, DSVT_ENOSPC = -2, DSVT_EHIP = -3, DSVT_EUNSUPPORTED = -4 };
 enum { DSVT_F32 = 0, DSVT_BF16 = 1 };
 /* bits of the device status word */
-enum { DSVT_ST_COORD_RANGE = 1, DSVT_ST_COORD_REPEAT = 2, DSVT_ST_SET_OVERFLOW = 4 };
+enum { DSVT_ST_COORD_RANGE = 1, DSVT_ST_COORD_REPEAT = 2, DSVT_ST_SET_OVERFLOW = 4, DSVT_ST_WS_STATE = 8 };
 
 /* ---------------------------------------------------------------------------------------
  * Set partition (Sec. 3.2 "Dynamic set partition", Eq. 2-4; "Rotated set attention";
@@ -81,7 +81,12 @@ typedef struct {
  * n_sets     [device] int32 scalar         out: total number of sets
  * set_win    [device] int32 [max_sets]     out: window key of every set; may be NULL
  * tiles      [host]   work list to fill (see dsvt_tile_list); may be NULL
- * ws         [device] scratch of at least the bytes dsvt_partition_bound reports
+ * ws         [device] at least the bytes dsvt_partition_bound reports, prepared by dsvt_partition_ws_init.
+ *            Not plain scratch: part of it is an occupancy bitmap that every call finds zero and leaves
+ *            zero (clearing it per call would put one more launch in front of every frame), so the
+ *            buffer must stay untouched between calls; calls that share a ws must not overlap.  A
+ *            call on a ws that was not prepared for this geometry marks nothing, reports *n_sets = 0
+ *            and sets DSVT_ST_WS_STATE in *status.
  * status     [device] int32 word, OR-ed with DSVT_ST_* bits (the caller zeroes it)
  * Errors: DSVT_EINVAL (NULL pointer, non-positive size, shift outside [0,win), axis not 0/1,
  * key space of 2^31 or more cells), DSVT_ENOSPC (ws_bytes too small), DSVT_EUNSUPPORTED (a work
@@ -90,6 +95,12 @@ int dsvt_partition(const dsvt_part_cfg* cfg, const int32_t* coords, int32_t n_vo
                    int32_t* set_inds, int32_t* voxel_slot, int32_t* n_sets, int32_t max_sets,
                    int32_t* set_win, const dsvt_tile_list* tiles,
                    void* ws, size_t ws_bytes, int32_t* status, void* stream);
+
+/* Prepares ws for dsvt_partition / dsvt_partition_xy calls with this cfg geometry (grid, window,
+ * batch; shift, tau and axis may change freely) and n_voxels: zeroes the occupancy bitmap and writes
+ * the header the kernels check.  Once per buffer, again only if the geometry changes or something
+ * else wrote to the buffer.  Asynchronous on stream.  Errors: DSVT_EINVAL, DSVT_ENOSPC, DSVT_EHIP. */
+int dsvt_partition_ws_init(const dsvt_part_cfg* cfg, int32_t n_voxels, void* ws, size_t ws_bytes, void* stream);
 
 /* Both rotated partitions of one window configuration (Sec. 3.2: a block's first layer takes the sets
  * in X-axis inner order, its second in Y-axis order) in one pass over the voxels.  The windows, the

@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(_PKG, "libdsvt.so")
 
 DSVT_OK, DSVT_EINVAL, DSVT_ENOSPC, DSVT_EHIP, DSVT_EUNSUPPORTED = 0, -1, -2, -3, -4
 DSVT_F32, DSVT_BF16 = 0, 1
-ST_COORD_RANGE, ST_COORD_REPEAT, ST_SET_OVERFLOW = 1, 2, 4
+ST_COORD_RANGE, ST_COORD_REPEAT, ST_SET_OVERFLOW, ST_WS_STATE = 1, 2, 4, 8
 _ERR = {-1: "DSVT_EINVAL", -2: "DSVT_ENOSPC", -3: "DSVT_EHIP", -4: "DSVT_EUNSUPPORTED"}
 _DT = {"f32": (DSVT_F32, torch.float32), "bf16": (DSVT_BF16, torch.bfloat16)}
 
@@ -67,6 +67,7 @@ def lib():
         vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
         L.dsvt_partition_bound.argtypes = [C.POINTER(PartCfg), i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(sz)]
         L.dsvt_partition.argtypes = [C.POINTER(PartCfg), vp, i32, vp, vp, vp, i32, vp, C.POINTER(TileList), vp, sz, vp, vp]
+        L.dsvt_partition_ws_init.argtypes = [C.POINTER(PartCfg), i32, vp, sz, vp]
         L.dsvt_partition_xy.argtypes = [C.POINTER(PartCfg), vp, i32, vp, vp, vp, vp, vp, i32, vp, C.POINTER(TileList), vp,
                                         vp, sz, vp, vp]
         L.dsvt_layer_packed_size.argtypes = [C.POINTER(LayerW), C.POINTER(sz)]
@@ -139,6 +140,9 @@ class SetMaps:
             self.n_sets = torch.zeros((1,), **i32)
             self.status = torch.zeros((1,), **i32)
             self.ws = torch.empty((ws_bytes,), dtype=torch.uint8, device="cuda")
+            _check("dsvt_partition_ws_init",
+                   lib().dsvt_partition_ws_init(C.byref(cfg), n_voxels, _ptr(self.ws), ws_bytes, _stream(None)))
+            torch.cuda.current_stream().synchronize()     # the maps may first be used on any stream
         else:
             assert common.max_sets == self.max_sets and common.n_voxels == n_voxels
             self.set_win, self.n_sets, self.status, self.ws = common.set_win, common.n_sets, common.status, common.ws

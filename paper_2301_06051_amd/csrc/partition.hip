@@ -11,8 +11,10 @@
 
 namespace {
 
-constexpr int32_t kFrontVoxels = 64 * 1024;      // frames up to this size go through k_front (one workgroup marks them all)
 constexpr size_t kFrontLds = 152 * 1024;         // LDS k_front may ask for
+constexpr uint64_t kWsMagic = 0x44535654504152ull;   // scratch header: "the mark bitmap of n_words words is all zero"
+constexpr size_t kWsHeader = 256;
+constexpr int32_t kRankWords = 8;                 // windows of up to this many bitmap words need no prefix array
 
 struct PartGeom {
   int32_t grid[3], win[3], shift[3], nw[3];
@@ -20,7 +22,6 @@ struct PartGeom {
   uint32_t magic[3];       // ceil(2^32 / win[a]) when that divides every x + shift exactly (see div_win), else 0
   uint32_t magic_tau, magic_cut;   // the same for tau (dividends up to a window's volume + tau) and for the rows of a
                                    // tile cut (dividends up to all padded rows), 0 when not exact; used by k_front
-  uint32_t mul24[3], shr24[3];     // x / win[a] = (x * mul24) >> shr24 in 24-bit arithmetic (k_front), see small_div
   int32_t words_per_win;   // 32-bit bitmap words per window (window volume rounded up to 32)
   int32_t n_windows;       // batch * nw[0] * nw[1] * nw[2]
 };
@@ -29,17 +30,23 @@ struct PartGeom {
 // of the voxels inside a window, hence the occupancy bitmap, its prefix and the slot maps.  Windows,
 // set counts and tile boundaries are common.  a[k] belongs to inner order axis0 + k.
 struct AxisBufs {
-  uint32_t *bitmap, *prefix;                 // [n_words] each
+  uint32_t* mark;                            // [n_words] bits set by k_mark; zero before and after every call
+  uint32_t *bitmap, *prefix;                 // [n_words] each: the call's own copy of the bits, and their running count
   int32_t *set_inds, *voxel_slot, *tile_desc;
 };
 struct AxisSet {
   AxisBufs a[2];
   int32_t n, axis0;
+  const uint64_t* ws_token;                  // scratch header, equal to `token` when the mark bitmaps are known to be zero
+  uint64_t token;
 };
 
-__global__ void k_clear(uint32_t* __restrict__ words, int64_t n) {
+__device__ __forceinline__ bool ws_ready(const AxisSet& ax) { return *ax.ws_token == ax.token; }
+
+__global__ void k_ws_init(uint32_t* __restrict__ words, int64_t n, uint64_t* __restrict__ ws_token, uint64_t token) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) words[i] = 0u;
+  if (i == 0) *ws_token = token;     // (kernels of later calls start after this one has ended)
 }
 
 // x / win[a] for 0 <= x < grid + shift.  With m = ceil(2^32 / d) the high word of x * m is floor(x / d)
@@ -49,9 +56,6 @@ __device__ __forceinline__ int32_t div_win(const PartGeom& g, int32_t a, int32_t
   if (g.magic[a] != 0u) return (int32_t)__umulhi((uint32_t)x, g.magic[a]);
   return x / g.win[a];
 }
-
-// Full-rate integer arithmetic for k_front, whose operands all stay below 2^24.
-__device__ __forceinline__ uint32_t mul24(uint32_t a, uint32_t b) { return __umul24(a, b); }
 
 // x / d by the high word of x * magic (magic = ceil(2^32 / d), exact for the dividends the host checked).
 __device__ __forceinline__ uint32_t div_magic(uint32_t x, uint32_t magic) { return __umulhi(x, magic); }
@@ -76,10 +80,14 @@ __device__ __forceinline__ uint32_t voxel_key(const PartGeom& g, int32_t axis, u
   return wkey * (uint32_t)(g.words_per_win * 32) + inner;
 }
 
-// One thread per voxel: set its bit in the bitmap of every axis.
+// One thread per voxel: set its bit in the mark bitmap of every axis.
 __global__ void k_mark(PartGeom g, const int4* __restrict__ coords, int32_t n, AxisSet ax, int32_t* __restrict__ status) {
   int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= n) return;
+  if (!ws_ready(ax)) {                       // scratch not prepared: mark nothing, the later kernels report no sets
+    if (i == 0) atomicOr(status, DSVT_ST_WS_STATE);
+    return;
+  }
   uint32_t wkey; int32_t xi, yi, zi;
   if (!voxel_cell(g, coords[i], wkey, xi, yi, zi)) {
     atomicOr(status, DSVT_ST_COORD_RANGE);
@@ -87,14 +95,14 @@ __global__ void k_mark(PartGeom g, const int4* __restrict__ coords, int32_t n, A
   }
   for (int32_t k = 0; k < ax.n; ++k) {
     const uint32_t key = voxel_key(g, ax.axis0 + k, wkey, xi, yi, zi), bit = 1u << (key & 31u);
-    const uint32_t old = atomicOr(&ax.a[k].bitmap[key >> 5], bit);
+    const uint32_t old = atomicOr(&ax.a[k].mark[key >> 5], bit);
     if (old & bit) atomicOr(status, DSVT_ST_COORD_REPEAT);
   }
 }
 
 // `group` lanes (a power of two <= 64) per window: pop-count the window's words, leave in
 // word_prefix[] the number of set bits in the window's earlier words, and the window total.
-__device__ __forceinline__ void window_count(int32_t tid, const uint32_t* __restrict__ bitmap,
+__device__ __forceinline__ void window_count(int32_t tid, uint32_t* __restrict__ mark, uint32_t* __restrict__ bitmap,
                                              uint32_t* __restrict__ word_prefix, int32_t* __restrict__ win_count,
                                              int32_t n_windows, int32_t words_per_win, int32_t group) {
   int32_t w = tid / group, lane = tid & (group - 1);
@@ -103,7 +111,13 @@ __device__ __forceinline__ void window_count(int32_t tid, const uint32_t* __rest
   uint32_t running = 0;
   for (int32_t w0 = 0; w0 < words_per_win; w0 += group) {
     int32_t j = w0 + lane;
-    uint32_t v = j < words_per_win ? (uint32_t)__popc(bitmap[base + j]) : 0u;
+    uint32_t v = 0u;
+    if (j < words_per_win) {                 // the word moves from the mark bitmap (left zero) to this call's copy
+      const uint32_t bits = mark[base + j];
+      mark[base + j] = 0u;
+      bitmap[base + j] = bits;
+      v = (uint32_t)__popc(bits);
+    }
     uint32_t incl = v;
     for (int32_t d = 1; d < group; d <<= 1) {
       uint32_t up = __shfl_up(incl, d, group);
@@ -117,8 +131,13 @@ __device__ __forceinline__ void window_count(int32_t tid, const uint32_t* __rest
 
 __global__ void k_window_count(AxisSet ax, int32_t* __restrict__ win_count, int32_t n_windows, int32_t words_per_win,
                                int32_t group) {       // blockIdx.y = axis; every axis leaves the same counts
-  window_count(blockIdx.x * blockDim.x + threadIdx.x, ax.a[blockIdx.y].bitmap, ax.a[blockIdx.y].prefix, win_count, n_windows,
-               words_per_win, group);
+  if (!ws_ready(ax)) {
+    const int32_t w = (blockIdx.x * blockDim.x + threadIdx.x) / group;
+    if (w < n_windows && blockIdx.y == 0) win_count[w] = 0;
+    return;
+  }
+  window_count(blockIdx.x * blockDim.x + threadIdx.x, ax.a[blockIdx.y].mark, ax.a[blockIdx.y].bitmap, ax.a[blockIdx.y].prefix,
+               win_count, n_windows, words_per_win, group);
 }
 
 // One workgroup: exclusive scans of voxels-per-window and sets-per-window (Eq. 2).
@@ -230,23 +249,21 @@ __device__ __forceinline__ void desc_header(const TileOut& out, int32_t pos, int
     }
 }
 
-// Set ls of launch slot pos: first row, distinct voxels, and -1 in the rows that pad it to a multiple of 4.
-__device__ __forceinline__ void desc_set(const TileOut& out, int32_t pos, int32_t ls, int32_t r0, int32_t nu) {
+// Set ls of the descriptor d: first row, distinct voxels, and -1 in the rows that pad it to a multiple of 4.
+__device__ __forceinline__ void desc_set(int32_t* d, int32_t ls, int32_t r0, int32_t nu) {
   const int32_t r1 = r0 + set_rows(nu) < kTileRows ? r0 + set_rows(nu) : kTileRows;
-#pragma unroll
-  for (int32_t k = 0; k < 2; ++k)
-    if (out.tile_desc[k] != nullptr) {
-      int32_t* d = out.tile_desc[k] + (int64_t)pos * kDescInts;
-      d[kDescR0 + ls] = r0;
-      d[kDescNu + ls] = nu;
-      for (int32_t r = r0 + nu; r < r1; ++r) { d[kDescVox + r] = -1; d[kDescLin + r] = -1; }
-    }
+  d[kDescR0 + ls] = r0;
+  d[kDescNu + ls] = nu;
+  for (int32_t r = r0 + nu; r < r1; ++r) { d[kDescVox + r] = -1; d[kDescLin + r] = -1; }
 }
+
+// What k_emit needs to know about a set with a tile: descriptor slot, place among the tile's sets, first row.
+__device__ __forceinline__ int32_t set_loc_code(int32_t pos, int32_t ls, int32_t r0) { return (pos << 12) | (ls << 7) | r0; }
 
 // One workgroup: cut the set sequence into tiles for the layer kernels, order the tiles for launch
 // and write the descriptor headers.  With P(s) the running sum of padded rows before set s, set s
 // starts a tile when P crosses a multiple of rows_per_cut; a tile then holds at most
-// rows_per_cut - 4 + pad4(tau) rows.  set_loc[s] = (descriptor slot << 7) | first row, for k_emit.
+// rows_per_cut - 4 + pad4(tau) rows.  set_loc[s] = set_loc_code(descriptor slot, place in the tile, first row), for k_emit.
 __device__ __forceinline__ void build_tiles(const int32_t* set_w, const int32_t* win_count, const int32_t* win_soff,
                                             const int32_t* n_sets_ptr, int32_t set_cap, int32_t tau, int32_t n_windows,
                                             int32_t rows_per_cut, TileOut out, int32_t* tile_rows, int32_t* tile_pos,
@@ -373,7 +390,7 @@ __device__ __forceinline__ void build_tiles(const int32_t* set_w, const int32_t*
     if (tid < 32) { int32_t add = 0; for (int32_t k = 0; k < 16; ++k) add += wave_cnt[k][tid]; running[tid] += add; }
     __syncthreads();
   }
-  // pass 4: per set, its descriptor slot, first row and distinct count
+  // pass 4: per set, its descriptor slot, its place among the tile's sets and its first row
   for (int32_t base = 0; base < n_sets; base += 1024) {
     const int32_t s = base + tid;
     if (s < n_sets) {
@@ -381,13 +398,7 @@ __device__ __forceinline__ void build_tiles(const int32_t* set_w, const int32_t*
       int32_t loc = -1;
       if (t >= 0 && t < nt) {
         const int32_t pos = tile_pos[t], ls = s - out.tile_first[t], r0 = set_p[s] - tile_rows[t];
-        int32_t w = set_w[s];
-        w = w < 0 ? 0 : (w >= n_windows ? n_windows - 1 : w);
-        const int64_t N = win_count[w] > 0 ? win_count[w] : 1, S = (N + tau - 1) / tau;
-        if (ls >= 0 && ls < kDescSets && r0 >= 0 && r0 <= kTileRows - 4) {
-          desc_set(out, pos, ls, r0, set_distinct(N, S, s - win_soff[w], tau));
-          loc = (pos << 7) | r0;
-        }
+        if (ls >= 0 && ls < kDescSets && r0 >= 0 && r0 <= kTileRows - 4) loc = set_loc_code(pos, ls, r0);
       }
       set_loc[s] = loc;
     }
@@ -412,6 +423,10 @@ long long* g_front_clocks = nullptr;       // [16] shader-clock stamps of thread
 // Scan over the 1024 threads of a workgroup, continued from one call to the next through `carry`:
 // inclusive sums of a and b, and in xm the maximum of m over the threads before this one (and over
 // earlier calls).  Every thread of the workgroup calls it; two barriers inside.
+// Workgroup barrier that waits for this wavefront's LDS traffic only.  __syncthreads() also waits for its
+// outstanding stores to memory (a microsecond each time); k_front never reads back what it wrote there.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 template <int CTRL, int ROW_MASK>
 __device__ __forceinline__ int32_t dpp_or(int32_t identity, int32_t v) {       // v of the lane CTRL names, identity where there is none
   return __builtin_amdgcn_update_dpp(identity, v, CTRL, ROW_MASK, 0xF, false);
@@ -446,32 +461,36 @@ __device__ __forceinline__ Scan3 block_scan3(Scan3 v, int32_t (*wave_tot)[16], i
   v.m = wave_scan_max(v.m, -1);                         // (every m is at least -1)
   const int32_t below = __shfl_up(v.m, 1, 64);
   if (lane == 63) { wave_tot[0][wv] = v.a; wave_tot[1][wv] = v.b; wave_tot[2][wv] = v.m; }
-  __syncthreads();
+  lds_barrier();
+  // totals of the wavefronts before this one: a scan of the 16 totals in the first row of lanes
+  const int32_t ta = wave_scan_add(lane < 16 ? wave_tot[0][lane] : 0), tb = wave_scan_add(lane < 16 ? wave_tot[1][lane] : 0),
+                tm = wave_scan_max(lane < 16 ? wave_tot[2][lane] : -1, -1);
   int32_t pa = carry[0], pb = carry[1], pm = carry[2];
-  for (int32_t k = 0; k < wv; ++k) {
-    pa += wave_tot[0][k]; pb += wave_tot[1][k];
-    pm = wave_tot[2][k] > pm ? wave_tot[2][k] : pm;
+  if (wv > 0) {
+    pa += __builtin_amdgcn_readlane(ta, wv - 1);
+    pb += __builtin_amdgcn_readlane(tb, wv - 1);
+    const int32_t m = __builtin_amdgcn_readlane(tm, wv - 1);
+    pm = m > pm ? m : pm;
   }
   v.a += pa; v.b += pb;
   v.xm = lane == 0 ? pm : (below > pm ? below : pm);
   v.m = pm > v.m ? pm : v.m;
-  __syncthreads();
+  lds_barrier();
   if (tid == 1023) { carry[0] = v.a; carry[1] = v.b; carry[2] = v.m; }
   return v;                                 // the new carry is visible after the caller's next barrier
 }
 
-// Small frames: everything before k_emit in one workgroup and one launch.  The bitmaps live in LDS
-// while the voxels are marked, so nothing has to be cleared in memory beforehand, and the per-window
-// and per-tile tables stay in LDS between the steps: the kernel reads the coordinates and writes its
-// results, with no trip through memory in between.  (Each step is a few microseconds of work; as
-// separate launches their start-up and the gaps between them are most of a partition's latency,
-// which the first layer of a frame has to wait for.)
+// Small frames: everything between k_mark and k_emit in one workgroup and one launch.  The marked bits
+// are staged in LDS (and the mark bitmap left zero for the next call), and the per-window and per-tile
+// tables stay in LDS between the steps: the kernel reads the bitmaps and writes its results, with no
+// trip through memory in between.  (Each step is a few microseconds of work; as separate launches their
+// start-up and the gaps between them are most of a partition's latency, which the first layer of a
+// frame has to wait for.)
 // Dynamic LDS, in 32-bit words: bitmaps [ax.n * n_words] | per window: voxels, first set, rows before
 // it, tiles started before it [4 * n_windows] | per tile: first set, rows before it [2 * (tile_cap + 1)],
 // launch slot [tile_cap].
 template <int NAX>
-__global__ void __launch_bounds__(1024) k_front(PartGeom g, const int4* __restrict__ coords, int32_t n, AxisSet ax,
-                                                int32_t n_words, int32_t* __restrict__ win_count,
+__global__ void __launch_bounds__(1024) k_front(PartGeom g, AxisSet ax, int32_t n_words, int32_t* __restrict__ win_count,
                                                 int32_t* __restrict__ win_soff, int32_t max_sets,
                                                 int32_t* __restrict__ n_sets, int32_t* __restrict__ status, int32_t set_cap,
                                                 int32_t rows_per_cut, TileOut out, int32_t tile_cap,
@@ -483,114 +502,88 @@ __global__ void __launch_bounds__(1024) k_front(PartGeom g, const int4* __restri
   extern __shared__ uint32_t smem[];
   DSVT_FCLK(0);
   __shared__ int32_t wave_tot[3][16], carry1[3], carry2[3];
-  __shared__ int32_t p_cap, ok_seen, bits_seen, over_s, over_p;
+  __shared__ int32_t p_cap, over_s, over_p;
   __shared__ int32_t hist[32], running[32], wave_cnt[16][32];
   const int32_t tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int32_t nw = g.n_windows, wpw = g.words_per_win, tau = g.tau;
   const bool want_tiles = out.tile_desc[0] != nullptr;
   const int32_t tile_lim = out.max_tiles < tile_cap ? out.max_tiles : tile_cap;
   uint32_t* bm = smem;
-  int32_t* wN = (int32_t*)(smem + (size_t)ax.n * n_words);
+  int32_t* wN = (int32_t*)(smem + (size_t)NAX * n_words);
   int32_t *wSoff = wN + nw, *wP0 = wSoff + nw, *wT0 = wP0 + nw;
   int32_t *tFirst = wT0 + nw, *tRows = tFirst + tile_cap + 1, *tPos = tRows + tile_cap + 1;
 
-  for (int32_t i = tid; i < ax.n * n_words; i += 1024) bm[i] = 0u;
+  if (!ws_ready(ax)) {                       // (k_mark has raised DSVT_ST_WS_STATE)
+    if (tid == 0) {
+      *n_sets = 0;
+      if (want_tiles) { *out.n_tiles = 0; out.tile_first[0] = 0; }
+    }
+    return;
+  }
   if (tid == 0) {
     carry1[0] = carry1[1] = 0; carry1[2] = -1;
     carry2[0] = carry2[1] = 0; carry2[2] = -1;
-    p_cap = 0; ok_seen = 0; bits_seen = 0; over_s = -1; over_p = 0;
+    p_cap = 0; over_s = -1; over_p = 0;
   }
-  __syncthreads();
+  // ---- the marked bits: into LDS and into this call's copy for k_emit; the mark bitmap is left zero
+  constexpr int32_t kStage = 8;                               // loads in flight per thread and axis
+  for (int32_t i0 = tid; i0 < n_words; i0 += kStage * 1024) {
+    uint32_t v[NAX][kStage];
+#pragma unroll
+    for (int32_t k = 0; k < NAX; ++k)
+#pragma unroll
+      for (int32_t u = 0; u < kStage; ++u) v[k][u] = i0 + u * 1024 < n_words ? ax.a[k].mark[i0 + u * 1024] : 0u;
+#pragma unroll
+    for (int32_t k = 0; k < NAX; ++k)
+#pragma unroll
+      for (int32_t u = 0; u < kStage; ++u) {
+        const int32_t i = i0 + u * 1024;
+        if (i < n_words) { bm[k * n_words + i] = v[k][u]; ax.a[k].mark[i] = 0u; ax.a[k].bitmap[i] = v[k][u]; }
+      }
+  }
+  lds_barrier();
   DSVT_FCLK(1);
-
-  // ---- mark: a bit per voxel and axis, straight-line code (a voxel outside the grid ORs a zero into
-  // word 0); the next eight coordinate loads of a thread are in flight while it handles the last eight.
-  // Divisions by the window sizes are 24-bit multiplications and shifts (the host takes this kernel only
-  // when they are exact).  Repeated cells are found afterwards: they leave fewer bits than there are
-  // voxels inside the grid.
-  uint32_t sx[2], sy[2];                                      // inner key = xi * sx + yi * sy + zi
-#pragma unroll
-  for (int32_t k = 0; k < 2; ++k) {
-    const bool x_major = ax.axis0 + k == 0;
-    sx[k] = (uint32_t)(x_major ? g.win[1] * g.win[2] : g.win[2]);
-    sy[k] = (uint32_t)(x_major ? g.win[2] : g.win[0] * g.win[2]);
-  }
-  int32_t n_ok = 0;
-  constexpr int32_t kB = 8;
-  int4 cn[kB];
-#pragma unroll
-  for (int32_t u = 0; u < kB; ++u) {
-    const int32_t i = tid + u * 1024;
-    cn[u] = coords[i < n ? i : n - 1];
-  }
-  for (int32_t i0 = tid; i0 < n; i0 += kB * 1024) {
-    int4 c[kB];
-#pragma unroll
-    for (int32_t u = 0; u < kB; ++u) c[u] = cn[u];
-    if (i0 + kB * 1024 < n) {
-#pragma unroll
-      for (int32_t u = 0; u < kB; ++u) {
-        const int32_t i = i0 + (kB + u) * 1024;
-        cn[u] = coords[i < n ? i : n - 1];
-      }
-    }
-#pragma unroll
-    for (int32_t u = 0; u < kB; ++u) {
-      const bool ok = i0 + u * 1024 < n && (uint32_t)c[u].x < (uint32_t)g.batch && (uint32_t)c[u].y < (uint32_t)g.grid[0] &&
-                      (uint32_t)c[u].z < (uint32_t)g.grid[1] && (uint32_t)c[u].w < (uint32_t)g.grid[2];
-      n_ok += ok ? 1 : 0;
-      const uint32_t x = (uint32_t)(c[u].y + g.shift[0]), y = (uint32_t)(c[u].z + g.shift[1]), z = (uint32_t)(c[u].w + g.shift[2]);
-      const uint32_t wx = mul24(x, g.mul24[0]) >> g.shr24[0], wy = mul24(y, g.mul24[1]) >> g.shr24[1],
-                     wz = mul24(z, g.mul24[2]) >> g.shr24[2];
-      const uint32_t xi = x - mul24(wx, (uint32_t)g.win[0]), yi = y - mul24(wy, (uint32_t)g.win[1]),
-                     zi = z - mul24(wz, (uint32_t)g.win[2]);
-      const uint32_t wkey = mul24(mul24(mul24((uint32_t)c[u].x, (uint32_t)g.nw[0]) + wx, (uint32_t)g.nw[1]) + wy, (uint32_t)g.nw[2]) + wz;
-      const uint32_t wword = mul24(wkey, (uint32_t)wpw);
-#pragma unroll
-      for (int32_t k = 0; k < NAX; ++k) {
-        const uint32_t inner = mul24(xi, sx[k]) + mul24(yi, sy[k]) + zi;
-        const uint32_t word = wword + (inner >> 5) + (uint32_t)(k * n_words);
-#if defined(DSVT_EXP) && DSVT_EXP == 1
-        n_ok += (int32_t)((word ^ inner) & 1u);
-#else
-        atomicOr(&bm[ok ? word : 0u], ok ? 1u << (inner & 31u) : 0u);
-#endif
-      }
-    }
-  }
-  if (n_ok != 0) atomicAdd(&ok_seen, n_ok);
-  __syncthreads();
   DSVT_FCLK(2);
-
   // ---- a thread per window: count, word prefixes, then scans over the windows of (sets, padded rows,
   // last set's rows of the latest non-empty window) and of the tiles its sets start
-  int32_t my_bits = 0;
   for (int32_t base = 0; base < nw; base += 1024) {
     const int32_t w = base + tid;
     int32_t N = 0;
     if (w < nw) {
+      const uint32_t w0 = __umul24((uint32_t)w, (uint32_t)wpw);        // (n_words < 2^22)
+      if (wpw <= kRankWords) {                                // k_emit ranks a voxel from the bitmap words themselves
+        uint32_t v[kRankWords];
 #pragma unroll
-      for (int32_t k = 0; k < NAX; ++k) {
-        const uint32_t w0 = mul24((uint32_t)w, (uint32_t)wpw);
-        const uint32_t* src = bm + (uint32_t)(k * n_words) + w0;
-        uint32_t* dst_b = ax.a[k].bitmap + w0;
-        uint32_t* dst_p = ax.a[k].prefix + w0;
-        uint32_t run = 0;
-        for (int32_t j = 0; j < wpw; ++j) {
-          const uint32_t v = src[j];
-          dst_b[j] = v;
-          dst_p[j] = run;
-          run += (uint32_t)__popc(v);
+        for (int32_t j = 0; j < kRankWords; ++j) v[j] = j < wpw ? bm[w0 + j] : 0u;
+#pragma unroll
+        for (int32_t j = 0; j < kRankWords; ++j) N += __popc(v[j]);
+      } else {
+#pragma unroll
+        for (int32_t k = 0; k < NAX; ++k) {
+          uint32_t* dst_p = ax.a[k].prefix + w0;
+          uint32_t run = 0;
+          for (int32_t j = 0; j < wpw; ++j) {
+            dst_p[j] = run;
+            run += (uint32_t)__popc(bm[k * n_words + w0 + j]);
+          }
+          N = (int32_t)run;                                   // the same for every axis
         }
-        N = (int32_t)run;                                     // the same for every axis
       }
       win_count[w] = N;
-      my_bits += N;
     }
     const int32_t S = (int32_t)div_magic((uint32_t)(N + tau - 1), g.magic_tau);
+    // distinct voxels of the window's sets, 7 bits each, for the passes below (windows of more than 9 sets
+    // walk through them again instead)
     SetWalk walk(N, S, tau);
+    const bool packed = S <= 9;
+    uint64_t nu_bits = 0;
     int32_t R = 0, last_rows = 0;
-    for (int32_t j = 0; j < S; ++j) { last_rows = set_rows(walk.next()); R += last_rows; }
+    for (int32_t j = 0; j < S; ++j) {
+      const int32_t nu = walk.next();
+      if (packed) nu_bits |= (uint64_t)nu << (7 * j);
+      last_rows = set_rows(nu);
+      R += last_rows;
+    }
     Scan3 v = {S, R, S > 0 ? (w << 7) | last_rows : -1, -1};
     v = block_scan3(v, wave_tot, carry1);
     const int32_t soff = v.a - S, P0 = v.b - R;
@@ -616,7 +609,7 @@ __global__ void __launch_bounds__(1024) k_front(PartGeom g, const int4* __restri
         m += pr;
         while (m >= rows_per_cut) m -= rows_per_cut;
         fn(s, P, first);
-        pr = set_rows(walk.next());
+        pr = set_rows(packed ? (int32_t)((nu_bits >> (7 * j)) & 127u) : walk.next());
         P += pr;
       }
     };
@@ -634,16 +627,12 @@ __global__ void __launch_bounds__(1024) k_front(PartGeom g, const int4* __restri
       });
     }
   }
-  if (my_bits != 0) atomicAdd(&bits_seen, my_bits);
-  __syncthreads();
+  lds_barrier();
   DSVT_FCLK(3);
   const int32_t n_tot = carry1[0];
   if (tid == 0) {
     *n_sets = n_tot;
-    int32_t bad = n_tot > max_sets ? DSVT_ST_SET_OVERFLOW : 0;
-    if (ok_seen < n) bad |= DSVT_ST_COORD_RANGE;
-    if (bits_seen < ok_seen) bad |= DSVT_ST_COORD_REPEAT;     // fewer bits than voxels inside the grid
-    if (bad) atomicOr(status, bad);
+    if (n_tot > max_sets) atomicOr(status, DSVT_ST_SET_OVERFLOW);
   }
   if (!want_tiles) return;
   const bool tiles_short = carry2[0] > tile_lim;          // the caller's list is shorter than the frame needs: later sets get no tile
@@ -660,7 +649,7 @@ __global__ void __launch_bounds__(1024) k_front(PartGeom g, const int4* __restri
     tRows[nt] = tiles_short ? over_p : (n_tot <= set_cap ? carry1[1] : p_cap);
   }
   if (tid < 32) hist[tid] = 0;
-  __syncthreads();
+  lds_barrier();
 
   // ---- launch order = tiles with more rows first (a stable counting sort on rows / 4), so that the
   // short tiles fill the tail of the launch
@@ -672,9 +661,12 @@ __global__ void __launch_bounds__(1024) k_front(PartGeom g, const int4* __restri
       atomicAdd(&hist[b], 1);
     }
   }
-  __syncthreads();
-  if (tid == 0) { int32_t acc = 0; for (int32_t b = 0; b < 32; ++b) { running[b] = acc; acc += hist[b]; } }
-  __syncthreads();
+  lds_barrier();
+  if (wv == 0) {
+    const int32_t h = lane < 32 ? hist[lane] : 0, incl = wave_scan_add(h);
+    if (lane < 32) running[lane] = incl - h;
+  }
+  lds_barrier();
   for (int32_t base = 0; base < nt; base += 1024) {
     const int32_t t = base + tid;
     int32_t b = -1;
@@ -693,21 +685,31 @@ __global__ void __launch_bounds__(1024) k_front(PartGeom g, const int4* __restri
       if (lane == leader) wave_cnt[wv][lb] = __popcll(same);
       todo &= ~same;
     }
-    __syncthreads();
+    lds_barrier();
+    if (tid < 512) {                                          // a row of 16 lanes per bucket, a lane per wavefront:
+      const int32_t bb = tid >> 4, k = tid & 15;              // counts of the wavefronts -> first position of each
+      const int32_t cnt = wave_cnt[k][bb];
+      int32_t incl = cnt;
+      incl += dpp_or<0x111, 0xF>(0, incl);
+      incl += dpp_or<0x112, 0xF>(0, incl);
+      incl += dpp_or<0x114, 0xF>(0, incl);
+      incl += dpp_or<0x118, 0xF>(0, incl);
+      const int32_t first = running[bb];
+      wave_cnt[k][bb] = first + incl - cnt;
+      if (k == 15) running[bb] = first + incl;                // (read by this row only, all of it before this write)
+    }
+    lds_barrier();
     if (b >= 0) {
-      int32_t pos = running[b] + rank;
-      for (int32_t k = 0; k < wv; ++k) pos += wave_cnt[k][b];
+      const int32_t pos = wave_cnt[wv][b] + rank;
       out.tile_order[pos] = t;
       tPos[t] = pos;
       desc_header(out, pos, tRows[t + 1] - tRows[t], tFirst[t + 1] - tFirst[t]);
     }
-    __syncthreads();
-    if (tid < 32) { int32_t add = 0; for (int32_t k = 0; k < 16; ++k) add += wave_cnt[k][tid]; running[tid] += add; }
-    __syncthreads();
+    lds_barrier();
   }
 
   DSVT_FCLK(4);
-  // ---- per set: its descriptor slot, first row and distinct count; set_loc[s] for k_emit
+  // ---- per set: its descriptor slot, its place among the tile's sets and its first row, for k_emit
   for (int32_t w = tid; w < nw; w += 1024) {
     const int32_t N = wN[w], S = (int32_t)div_magic((uint32_t)(N + tau - 1), g.magic_tau), soff = wSoff[w];
     int32_t P = wP0[w], t = wT0[w] - 1;
@@ -720,10 +722,7 @@ __global__ void __launch_bounds__(1024) k_front(PartGeom g, const int4* __restri
       int32_t loc = -1;
       if (t >= 0 && t < nt && s < n_eff) {
         const int32_t pos = tPos[t], ls = s - tFirst[t], r0 = P - tRows[t];
-        if (ls >= 0 && ls < kDescSets && r0 >= 0 && r0 <= kTileRows - 4) {
-          desc_set(out, pos, ls, r0, nu);
-          loc = (pos << 7) | r0;
-        }
+        if (ls >= 0 && ls < kDescSets && r0 >= 0 && r0 <= kTileRows - 4) loc = set_loc_code(pos, ls, r0);
       }
       set_loc[s] = loc;
       P += set_rows(nu);
@@ -742,7 +741,7 @@ __global__ void k_emit(PartGeom g, const int4* __restrict__ coords, int32_t n, A
   const AxisBufs& me = ax.a[blockIdx.y];
   int32_t* __restrict__ tile_desc = me.tile_desc;
   if ((int32_t)blockIdx.x >= vox_blocks) {
-    if (tile_desc == nullptr) return;
+    if (tile_desc == nullptr || !ws_ready(ax)) return;
     const int32_t idx = ((int32_t)blockIdx.x - vox_blocks) * blockDim.x + threadIdx.x;
     const int32_t pos = idx / kTileRows, r = idx - pos * kTileRows;
     int32_t nt = *n_tiles;
@@ -756,12 +755,22 @@ __global__ void k_emit(PartGeom g, const int4* __restrict__ coords, int32_t n, A
   if (i >= n) return;
   const int4 c = coords[i];
   uint32_t wkey; int32_t xi, yi, zi;
-  if (!voxel_cell(g, c, wkey, xi, yi, zi)) { me.voxel_slot[i] = -1; return; }
+  if (!ws_ready(ax) || !voxel_cell(g, c, wkey, xi, yi, zi)) { me.voxel_slot[i] = -1; return; }
   const uint32_t key = voxel_key(g, ax.axis0 + (int32_t)blockIdx.y, wkey, xi, yi, zi);
   const int32_t tau = g.tau;
   uint32_t word = key >> 5, bit = key & 31u;
   const int32_t w = (int32_t)wkey;
-  int64_t d = me.prefix[word] + (uint32_t)__popc(me.bitmap[word] & ((1u << bit) - 1u));
+  int64_t d = (uint32_t)__popc(me.bitmap[word] & ((1u << bit) - 1u));          // set bits before its own inside its window
+  if (g.words_per_win <= kRankWords) {
+    const uint32_t w0 = wkey * (uint32_t)g.words_per_win;
+    uint32_t v[kRankWords];
+#pragma unroll
+    for (int32_t j = 0; j < kRankWords; ++j) v[j] = w0 + j < word ? me.bitmap[w0 + j] : 0u;
+#pragma unroll
+    for (int32_t j = 0; j < kRankWords; ++j) d += __popc(v[j]);
+  } else {
+    d += me.prefix[word];
+  }
   int64_t N = win_count[w];
   int64_t S = (N + tau - 1) / tau, T = S * tau;
   int64_t t_lo, t_hi, first_d;                               // first_d: rank of the first voxel of this voxel's first set
@@ -783,8 +792,14 @@ __global__ void k_emit(PartGeom g, const int4* __restrict__ coords, int32_t n, A
     const int64_t slot = base + t;
     if (slot >= cap) break;
     me.set_inds[slot] = i;
-    if (t == next_set_start) {
-      if (names_sets) set_win[win_soff[w] + t / tau] = w;
+    if (t == next_set_start) {                               // the first slot of a set: this thread describes the set
+      const int32_t j = t / tau, s = win_soff[w] + j;
+      if (names_sets) set_win[s] = w;
+      if (tile_desc != nullptr) {
+        const int32_t loc = set_loc[s];
+        if (loc >= 0 && (loc >> 12) < n_desc_slots)
+          desc_set(tile_desc + (int64_t)(loc >> 12) * kDescInts, (loc >> 7) & 31, loc & 127, set_distinct(N, S, j, tau));
+      }
       next_set_start += tau;
     }
   }
@@ -792,7 +807,7 @@ __global__ void k_emit(PartGeom g, const int4* __restrict__ coords, int32_t n, A
     const int64_t j = j_first, s = win_soff[w] + j;
     if (s < max_sets) {
       const int32_t loc = set_loc[s];
-      const int32_t slot = loc >> 7, row = (loc & 127) + (int32_t)(d - first_d);
+      const int32_t slot = loc >> 12, row = (loc & 127) + (int32_t)(d - first_d);
       if (slot >= 0 && slot < n_desc_slots && row < kTileRows) {
         const int32_t lin = (c.y * (2 * g.win[1] - 1) + c.z) * (2 * g.win[2] - 1) + c.w;
         int32_t* dd = tile_desc + (int64_t)slot * kDescInts;
@@ -805,7 +820,7 @@ __global__ void k_emit(PartGeom g, const int4* __restrict__ coords, int32_t n, A
 
 struct PartPlan {
   PartGeom g;
-  size_t off_bitmap, off_prefix, off_count, off_soff, off_setwin, off_tilerows, off_tilepos, off_setp, off_setloc, total;
+  size_t off_mark, off_bitmap, off_prefix, off_count, off_soff, off_setwin, off_tilerows, off_tilepos, off_setp, off_setloc, total;
   bool desc_ok;
   int64_t n_words;
   int32_t set_bound, tile_bound, rows_per_cut;
@@ -833,7 +848,8 @@ int make_plan(const dsvt_part_cfg* cfg, int32_t n_voxels, PartPlan* p) {
   g.words_per_win = (int32_t)wpw;
   g.n_windows = (int32_t)nwin;
   p->n_words = nwin * wpw;
-  size_t o = 0;                                             // bitmaps and prefixes: room for both axes, back to back
+  size_t o = kWsHeader;                                     // bitmaps and prefixes: room for both axes, back to back
+  p->off_mark = o;   o = dsvt_align_up(o + (size_t)p->n_words * 8, 256);
   p->off_bitmap = o; o = dsvt_align_up(o + (size_t)p->n_words * 8, 256);
   p->off_prefix = o; o = dsvt_align_up(o + (size_t)p->n_words * 8, 256);
   p->off_count = o;  o = dsvt_align_up(o + (size_t)nwin * 4, 256);
@@ -852,12 +868,15 @@ int make_plan(const dsvt_part_cfg* cfg, int32_t n_voxels, PartPlan* p) {
   p->off_tilepos = o;  o = dsvt_align_up(o + (size_t)(p->tile_bound + 1) * 4, 256);
   p->off_setp = o;     o = dsvt_align_up(o + (size_t)(bound + 1) * 4, 256);
   p->off_setloc = o;   o = dsvt_align_up(o + (size_t)(bound + 1) * 4, 256);
-  // a descriptor packs (slot << 7 | row) and (multiplicity << 24 | position code) into 32 bits
-  p->desc_ok = p->rows_per_cut >= 4 && p->tile_bound < (1 << 23) &&
+  // set_loc packs (slot << 12 | place << 7 | row), a descriptor (multiplicity << 24 | position code) into 32 bits
+  p->desc_ok = p->rows_per_cut >= 4 && p->tile_bound < (1 << 19) &&
                (int64_t)cfg->grid[0] * (2 * cfg->win[1] - 1) * (2 * cfg->win[2] - 1) < (1 << 24) && cfg->tau < 128;
   p->total = o;
   return DSVT_OK;
 }
+
+// Header value of a scratch buffer whose mark bitmaps (room for both axes) are zero for this geometry.
+uint64_t ws_token(const PartPlan& p) { return kWsMagic ^ ((uint64_t)p.n_words * 0x9E3779B97F4A7C15ull); }
 
 // The partition of n_axes inner orders (axis0, axis0 + 1) of one window configuration.
 int run_partition(const dsvt_part_cfg* cfg, int32_t n_axes, int32_t axis0, const int32_t* coords, int32_t n_voxels,
@@ -893,32 +912,28 @@ int run_partition(const dsvt_part_cfg* cfg, int32_t n_axes, int32_t axis0, const
   AxisSet ax = {};
   ax.n = n_axes; ax.axis0 = axis0;
   for (int32_t k = 0; k < n_axes; ++k) {
+    ax.a[k].mark = (uint32_t*)(base + p.off_mark) + (size_t)k * p.n_words;
     ax.a[k].bitmap = (uint32_t*)(base + p.off_bitmap) + (size_t)k * p.n_words;
     ax.a[k].prefix = (uint32_t*)(base + p.off_prefix) + (size_t)k * p.n_words;
     ax.a[k].set_inds = set_inds[k]; ax.a[k].voxel_slot = voxel_slot[k];
     ax.a[k].tile_desc = tout.tile_desc[k];
   }
   const int tb = 256;
-  // k_front divides by multiplying: exact for x < 2^16 and d < 2^15 (window sizes, and tau against a window's
-  // volume + tau), and for x < 2^25 and d <= 128 (rows of a tile cut against all padded rows)
-  bool front_ok = n_voxels <= kFrontVoxels && (int64_t)p.g.words_per_win * 32 + cfg->tau < (1 << 16) && cfg->tau < (1 << 15);
-  for (int a = 0; a < 3; ++a) {
-    // x / d = (x * m) >> k with m = ceil(2^k / d) whenever x * (m * d - 2^k) < 2^k; x * d <= 2^k suffices.  With
-    // x < X <= 2^15 and 2^k the first power of two >= X * d: m <= 2 X, so x * m fits 32 bits and m fits 24.
-    const int64_t X = (int64_t)cfg->grid[a] + cfg->shift[a], d = cfg->win[a];
-    int k = 0;
-    while ((1ll << k) < X * d) ++k;
-    front_ok = front_ok && X <= (1 << 15) && k <= 30;
-    p.g.mul24[a] = front_ok ? (uint32_t)(((1ll << k) + d - 1) / d) : 0u;
-    p.g.shr24[a] = (uint32_t)k;
+  ax.ws_token = (const uint64_t*)base;
+  ax.token = ws_token(p);
+  {
+    dsvt_prof_scope ps(DSVT_K_PART_MARK, st);
+    k_mark<<<(unsigned)dsvt_ceil_div(n_voxels, tb), tb, 0, st>>>(p.g, (const int4*)coords, n_voxels, ax, status);
   }
-  front_ok = front_ok && p.g.n_windows < (1 << 22) && p.n_words * n_axes < (1 << 22);
+  // k_front divides by multiplying: exact for x < 2^16 and d < 2^15 (tau against a window's volume + tau),
+  // and for x < 2^25 and d <= 128 (rows of a tile cut against all padded rows)
+  bool front_ok = (int64_t)p.g.words_per_win * 32 + cfg->tau < (1 << 16) && cfg->tau < (1 << 15) && cfg->tau > 1 &&
+                  (int64_t)n_voxels + 4 * (int64_t)p.set_bound < (1 << 25) && p.g.n_windows < (1 << 22) &&
+                  p.n_words * n_axes < (1 << 22) && (tiles == nullptr || p.rows_per_cut >= 2);
   if (front_ok) {
     p.g.magic_tau = (uint32_t)(((1ull << 32) + (uint64_t)cfg->tau - 1) / (uint64_t)cfg->tau);
-    if (cfg->tau == 1) front_ok = false;                      // (2^32 does not fit the multiplier)
     const int32_t cut = p.rows_per_cut > 1 ? p.rows_per_cut : 2;
     p.g.magic_cut = (uint32_t)(((1ull << 32) + (uint64_t)cut - 1) / (uint64_t)cut);
-    if (tiles != nullptr && p.rows_per_cut < 2) front_ok = false;
   }
   const size_t front_lds = ((size_t)n_axes * p.n_words + 4 * (size_t)p.g.n_windows + 3 * (size_t)(p.tile_bound + 1)) * 4;
   if (front_ok && front_lds <= kFrontLds) {
@@ -930,22 +945,13 @@ int run_partition(const dsvt_part_cfg* cfg, int32_t n_axes, int32_t axis0, const
     }
     dsvt_prof_scope ps(DSVT_K_PART_TILES, st);
     auto* front = n_axes == 2 ? k_front<2> : k_front<1>;
-    front<<<1, 1024, front_lds, st>>>(p.g, (const int4*)coords, n_voxels, ax, (int32_t)p.n_words, count, soff, max_sets,
-                                        n_sets, status, set_cap, p.rows_per_cut, tout, p.tile_bound, set_loc
+    front<<<1, 1024, front_lds, st>>>(p.g, ax, (int32_t)p.n_words, count, soff, max_sets, n_sets, status, set_cap,
+                                      p.rows_per_cut, tout, p.tile_bound, set_loc
 #ifdef DSVT_PHASE_CLOCKS
-                                        , g_front_clocks
+                                      , g_front_clocks
 #endif
-                                        );
+                                      );
   } else {
-    {
-      dsvt_prof_scope ps(DSVT_K_PART_CLEAR, st);
-      const int64_t n_clear = p.n_words * n_axes;
-      k_clear<<<(unsigned)dsvt_ceil_div(n_clear, tb), tb, 0, st>>>(ax.a[0].bitmap, n_clear);
-    }
-    {
-      dsvt_prof_scope ps(DSVT_K_PART_MARK, st);
-      k_mark<<<(unsigned)dsvt_ceil_div(n_voxels, tb), tb, 0, st>>>(p.g, (const int4*)coords, n_voxels, ax, status);
-    }
     int32_t group = 1;
     while (group < 64 && group < p.g.words_per_win) group <<= 1;
     {
@@ -992,6 +998,19 @@ extern "C" int dsvt_partition_bound(const dsvt_part_cfg* cfg, int32_t n_voxels, 
   if (max_sets) *max_sets = p.set_bound;
   if (max_tiles) *max_tiles = p.tile_bound;
   if (ws_bytes) *ws_bytes = p.total;
+  return DSVT_OK;
+}
+
+extern "C" int dsvt_partition_ws_init(const dsvt_part_cfg* cfg, int32_t n_voxels, void* ws, size_t ws_bytes, void* stream) {
+  PartPlan p;
+  int rc = make_plan(cfg, n_voxels, &p);
+  if (rc != DSVT_OK) return rc;
+  if (!ws) return DSVT_EINVAL;
+  if (ws_bytes < p.total) return DSVT_ENOSPC;
+  const int64_t n_clear = p.n_words * 2;
+  k_ws_init<<<(unsigned)dsvt_ceil_div(n_clear, 256), 256, 0, (hipStream_t)stream>>>(
+      (uint32_t*)((char*)ws + p.off_mark), n_clear, (uint64_t*)ws, ws_token(p));
+  DSVT_HIP_TRY(hipGetLastError());
   return DSVT_OK;
 }
 

@@ -114,6 +114,14 @@ def test_partition_reports_bad_input_without_faulting():
     with pytest.raises(dsvt.DsvtError) as e:
         dsvt.dsvt_partition(dsvt.part_cfg(grid, win, (12, 0, 0), tau, 1, 0), dev_coords(coords), out=gm)
     assert e.value.rc == dsvt.binding.DSVT_EINVAL
+    # a scratch buffer that dsvt_partition_ws_init has not prepared: no sets, and the status says why
+    for maker, call in ((dsvt.SetMaps, dsvt.dsvt_partition), (dsvt.SetMapsXY, dsvt.dsvt_partition_xy)):
+        raw = maker(cfg, 200)
+        first = raw if maker is dsvt.SetMaps else raw.x
+        first.ws[:64].fill_(0x5A)
+        call(cfg, dev_coords(coords), out=raw); torch.cuda.synchronize()
+        assert int(first.status.item()) & dsvt.binding.ST_WS_STATE and int(first.n_sets.item()) == 0
+        assert torch.all(first.voxel_slot == -1)
 
 
 # ------------------------------------------------------------------ set attention / block
