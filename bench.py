@@ -2,7 +2,7 @@
 """Benchmark of the DSVT hot path on one MI355X.
 
 A step = the whole hot path on one synthetic 30,000-pillar frame (468 x 468 x 1 grid, bf16,
-C = 192, 8 heads, tau = 36, windows 12 x 12 x 1): four set partitions (2 window shifts x 2 axes)
+C = 192, 8 heads, tau = 36, windows 12 x 12 x 1): four set partitions (2 window shifts x 2 axes, one call)
 and four DSVT blocks (8 layers).  Inputs are resident in HBM before the timed region.  Prints one
 JSON line: voxels/s, ms/frame, the roofline of the dominant kernel (per-kernel time from hipEvent
 pairs around every launch) and the CPU oracle timed on the host cores on one frame.
@@ -58,27 +58,15 @@ def main():
     maps = {sh: dsvt.SetMapsXY(pc, N) for sh, pc in pcfgs.items()}       # X- and Y-axis maps of each window shift
     ws = torch.empty((max(dsvt.dsvt_block_workspace_size(layers[0][0], N), 1),), dtype=torch.uint8, device="cuda")
 
-    # The partitions of the two window shifts (each both axes at once) are independent of each other
-    # and only the first is needed by block 0: it runs on the main stream, the other on a stream of
-    # its own (default priority) that joins the main stream where its maps are first used, so in the
-    # captured graph it is a parallel branch.
-    first = cfg["shifts"][0]
-    side_streams = {sh: torch.cuda.Stream() for sh in cfg["shifts"][1:]}
+    # The partitions of both window shifts, each in both axes, go through one chain of three launches
+    # ahead of the blocks; everything is on one stream.
+    shifts = list(cfg["shifts"])
 
     def step():
-        main = torch.cuda.current_stream()
-        for sh, st in side_streams.items():
-            st.wait_stream(main)
-            with torch.cuda.stream(st):
-                dsvt.dsvt_partition_xy(pcfgs[sh], cd, out=maps[sh])
-        dsvt.dsvt_partition_xy(pcfgs[first], cd, out=maps[first])
-        joined = {first}
+        dsvt.dsvt_partition_xy_multi([pcfgs[sh] for sh in shifts], cd, [maps[sh] for sh in shifts])
         src = x0
         for b, pair in enumerate(layers):
-            sh = cfg["shifts"][b % len(cfg["shifts"])]
-            if sh not in joined:
-                main.wait_stream(side_streams[sh])
-                joined.add(sh)
+            sh = shifts[b % len(shifts)]
             dsvt.dsvt_block(pair, maps[sh], cd, src, x_out=buf, ws=ws)
             src = buf
 
@@ -126,7 +114,7 @@ def main():
     ms_per_step = dt / args.steps * 1e3
 
     # Per-kernel time: the same steps again, eagerly, with an event pair around every launch.
-    launches_per_step = 2 * 6 + 4 * 2
+    launches_per_step = 3 + 4 * 2
     prof_steps = min(args.steps, 50)
     dsvt.prof_enable(launches_per_step * prof_steps)
     for _ in range(prof_steps):

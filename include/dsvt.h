@@ -117,6 +117,26 @@ int dsvt_partition_xy(const dsvt_part_cfg* cfg, const int32_t* coords, int32_t n
                       const dsvt_tile_list* tiles, int32_t* tile_desc_y,
                       void* ws, size_t ws_bytes, int32_t* status, void* stream);
 
+/* The partitions of several window configurations over the same voxels in one pass: a stage computes
+ * its unshifted and its shifted windows once per frame and its blocks alternate between them
+ * (Sec. 3.2, window shift between consecutive blocks), so every launch handles all configurations
+ * side by side and the frame waits for one chain of launches instead of one per configuration.
+ * Each job is the argument list of one dsvt_partition_xy call (every job its own ws, status and
+ * outputs; tiles [host] may be NULL).  At most 4 jobs.  Results are identical to n_jobs
+ * dsvt_partition_xy calls.  Errors as there; DSVT_EINVAL for n_jobs outside 1..4. */
+typedef struct {
+  dsvt_part_cfg cfg;                        /* axis ignored */
+  int32_t *set_inds_x, *set_inds_y, *voxel_slot_x, *voxel_slot_y, *n_sets, *set_win;
+  int32_t max_sets;
+  const dsvt_tile_list* tiles;
+  int32_t* tile_desc_y;
+  void* ws;
+  size_t ws_bytes;
+  int32_t* status;
+} dsvt_xy_job;
+int dsvt_partition_xy_multi(const dsvt_xy_job* jobs, int32_t n_jobs, const int32_t* coords, int32_t n_voxels,
+                            void* stream);
+
 /* The maps one layer consumes (outputs of dsvt_partition, all [device]). */
 typedef struct {
   int32_t n_voxels, max_sets, tau;

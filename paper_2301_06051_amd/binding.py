@@ -31,6 +31,13 @@ class TileList(C.Structure):
                 ("tile_order", C.c_void_p), ("tile_desc", C.c_void_p)]
 
 
+class XyJob(C.Structure):
+    _fields_ = [("cfg", PartCfg), ("set_inds_x", C.c_void_p), ("set_inds_y", C.c_void_p), ("voxel_slot_x", C.c_void_p),
+                ("voxel_slot_y", C.c_void_p), ("n_sets", C.c_void_p), ("set_win", C.c_void_p), ("max_sets", C.c_int32),
+                ("tiles", C.POINTER(TileList)), ("tile_desc_y", C.c_void_p), ("ws", C.c_void_p), ("ws_bytes", C.c_size_t),
+                ("status", C.c_void_p)]
+
+
 class Maps(C.Structure):
     _fields_ = [("n_voxels", C.c_int32), ("max_sets", C.c_int32), ("tau", C.c_int32), ("set_inds", C.c_void_p),
                 ("voxel_slot", C.c_void_p), ("n_sets", C.c_void_p), ("tiles", TileList)]
@@ -70,6 +77,7 @@ def lib():
         L.dsvt_partition_ws_init.argtypes = [C.POINTER(PartCfg), i32, vp, sz, vp]
         L.dsvt_partition_xy.argtypes = [C.POINTER(PartCfg), vp, i32, vp, vp, vp, vp, vp, i32, vp, C.POINTER(TileList), vp,
                                         vp, sz, vp, vp]
+        L.dsvt_partition_xy_multi.argtypes = [C.POINTER(XyJob), i32, vp, i32, vp]
         L.dsvt_layer_packed_size.argtypes = [C.POINTER(LayerW), C.POINTER(sz)]
         L.dsvt_layer_pack.argtypes = [C.POINTER(LayerW), vp, sz, vp]
         L.dsvt_block_workspace_size.argtypes = [C.POINTER(LayerW), i32, C.POINTER(sz)]
@@ -211,6 +219,25 @@ def dsvt_partition_xy(cfg, coords, out=None, stream=None):
                                  _ptr(x.ws), x.ws.numel(), _ptr(x.status), _stream(stream))
     _check("dsvt_partition_xy", rc)
     return out
+
+
+def dsvt_partition_xy_multi(cfgs, coords, outs, stream=None):
+    """The partitions of several window configurations (cfgs[k] into the SetMapsXY outs[k]) in one pass."""
+    assert coords.is_cuda and coords.dtype == torch.int32 and coords.is_contiguous() and coords.shape[1] == 4
+    n = coords.shape[0]
+    assert len(cfgs) == len(outs) and all(o.n_voxels == n for o in outs)
+    jobs = (XyJob * len(cfgs))()
+    for j, cfg, o in zip(jobs, cfgs, outs):
+        x, y = o.x, o.y
+        j.cfg = cfg
+        j.set_inds_x, j.set_inds_y = x.set_inds.data_ptr(), y.set_inds.data_ptr()
+        j.voxel_slot_x, j.voxel_slot_y = x.voxel_slot.data_ptr(), y.voxel_slot.data_ptr()
+        j.n_sets, j.set_win, j.max_sets = x.n_sets.data_ptr(), x.set_win.data_ptr(), x.max_sets
+        j.tiles = C.pointer(x.tile_list) if x.max_tiles else None
+        j.tile_desc_y = y.tile_desc.data_ptr() if x.max_tiles else None
+        j.ws, j.ws_bytes, j.status = x.ws.data_ptr(), x.ws.numel(), x.status.data_ptr()
+    _check("dsvt_partition_xy_multi", lib().dsvt_partition_xy_multi(jobs, len(cfgs), _ptr(coords), n, _stream(stream)))
+    return outs
 
 
 class LayerWeights:

@@ -80,26 +80,6 @@ __device__ __forceinline__ uint32_t voxel_key(const PartGeom& g, int32_t axis, u
   return wkey * (uint32_t)(g.words_per_win * 32) + inner;
 }
 
-// One thread per voxel: set its bit in the mark bitmap of every axis.
-__global__ void k_mark(PartGeom g, const int4* __restrict__ coords, int32_t n, AxisSet ax, int32_t* __restrict__ status) {
-  int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= n) return;
-  if (!ws_ready(ax)) {                       // scratch not prepared: mark nothing, the later kernels report no sets
-    if (i == 0) atomicOr(status, DSVT_ST_WS_STATE);
-    return;
-  }
-  uint32_t wkey; int32_t xi, yi, zi;
-  if (!voxel_cell(g, coords[i], wkey, xi, yi, zi)) {
-    atomicOr(status, DSVT_ST_COORD_RANGE);
-    return;
-  }
-  for (int32_t k = 0; k < ax.n; ++k) {
-    const uint32_t key = voxel_key(g, ax.axis0 + k, wkey, xi, yi, zi), bit = 1u << (key & 31u);
-    const uint32_t old = atomicOr(&ax.a[k].mark[key >> 5], bit);
-    if (old & bit) atomicOr(status, DSVT_ST_COORD_REPEAT);
-  }
-}
-
 // `group` lanes (a power of two <= 64) per window: pop-count the window's words, leave in
 // word_prefix[] the number of set bits in the window's earlier words, and the window total.
 __device__ __forceinline__ void window_count(int32_t tid, uint32_t* __restrict__ mark, uint32_t* __restrict__ bitmap,
@@ -231,6 +211,39 @@ struct TileOut {                       // all null when the caller wants no work
   int32_t* tile_desc[2];               // one descriptor array per axis (second null for a single partition)
   int32_t max_tiles;
 };
+
+// Everything the kernels need for one window configuration.  Several configurations over the same voxels
+// (a stage's unshifted and shifted windows) go through the same launches, one grid slice each.
+struct Job {
+  PartGeom g;
+  AxisSet ax;
+  TileOut out;
+  int32_t *win_count, *win_soff, *n_sets, *status, *set_win, *set_loc;
+  int32_t n_words, max_sets, set_cap, rows_per_cut, tile_cap;
+};
+constexpr int32_t kMaxJobs = 4;
+struct Jobs { Job j[kMaxJobs]; };
+
+// One thread per voxel and job (blockIdx.y): set its bit in the mark bitmap of every axis.
+__global__ void k_mark(Jobs jobs, const int4* __restrict__ coords, int32_t n) {
+  const Job& J = jobs.j[blockIdx.y];
+  int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  if (!ws_ready(J.ax)) {                     // scratch not prepared: mark nothing, the later kernels report no sets
+    if (i == 0) atomicOr(J.status, DSVT_ST_WS_STATE);
+    return;
+  }
+  uint32_t wkey; int32_t xi, yi, zi;
+  if (!voxel_cell(J.g, coords[i], wkey, xi, yi, zi)) {
+    atomicOr(J.status, DSVT_ST_COORD_RANGE);
+    return;
+  }
+  for (int32_t k = 0; k < J.ax.n; ++k) {
+    const uint32_t key = voxel_key(J.g, J.ax.axis0 + k, wkey, xi, yi, zi), bit = 1u << (key & 31u);
+    const uint32_t old = atomicOr(&J.ax.a[k].mark[key >> 5], bit);
+    if (old & bit) atomicOr(J.status, DSVT_ST_COORD_REPEAT);
+  }
+}
 
 // Padded rows of a set with nu distinct voxels.
 __device__ __forceinline__ int32_t set_rows(int32_t nu) {
@@ -490,15 +503,22 @@ __device__ __forceinline__ Scan3 block_scan3(Scan3 v, int32_t (*wave_tot)[16], i
 // it, tiles started before it [4 * n_windows] | per tile: first set, rows before it [2 * (tile_cap + 1)],
 // launch slot [tile_cap].
 template <int NAX>
-__global__ void __launch_bounds__(1024) k_front(PartGeom g, AxisSet ax, int32_t n_words, int32_t* __restrict__ win_count,
-                                                int32_t* __restrict__ win_soff, int32_t max_sets,
-                                                int32_t* __restrict__ n_sets, int32_t* __restrict__ status, int32_t set_cap,
-                                                int32_t rows_per_cut, TileOut out, int32_t tile_cap,
-                                                int32_t* __restrict__ set_loc
+__global__ void __launch_bounds__(1024) k_front(Jobs jobs
 #ifdef DSVT_PHASE_CLOCKS
                                                 , long long* clk
 #endif
                                                 ) {
+  const Job& J = jobs.j[blockIdx.x];
+  const PartGeom& g = J.g;
+  const AxisSet& ax = J.ax;
+  const TileOut& out = J.out;
+  int32_t* __restrict__ win_count = J.win_count;
+  int32_t* __restrict__ win_soff = J.win_soff;
+  int32_t* __restrict__ n_sets = J.n_sets;
+  int32_t* __restrict__ status = J.status;
+  int32_t* __restrict__ set_loc = J.set_loc;
+  const int32_t n_words = J.n_words, max_sets = J.max_sets, set_cap = J.set_cap, rows_per_cut = J.rows_per_cut,
+                tile_cap = J.tile_cap;
   extern __shared__ uint32_t smem[];
   DSVT_FCLK(0);
   __shared__ int32_t wave_tot[3][16], carry1[3], carry2[3];
@@ -731,13 +751,20 @@ __global__ void __launch_bounds__(1024) k_front(PartGeom g, AxisSet ax, int32_t 
   DSVT_FCLK(5);
 }
 
-// One thread per voxel and axis (blockIdx.y): rank d inside its window, then the slots t with
+// One thread per voxel, axis (blockIdx.y) and job (blockIdx.z): rank d inside its window, then the slots t with
 // floor(t*N/(S*tau)) == d; with a work list also the voxel's row of its tile descriptor.  The blocks
 // after the voxels' (blockIdx.x >= vox_blocks) put -1 into the descriptor rows past each tile's last.
-__global__ void k_emit(PartGeom g, const int4* __restrict__ coords, int32_t n, AxisSet ax, int32_t vox_blocks,
-                       const int32_t* __restrict__ win_count, const int32_t* __restrict__ win_soff, int32_t max_sets,
-                       int32_t* __restrict__ set_win, const int32_t* __restrict__ set_loc,
-                       const int32_t* __restrict__ n_tiles, int32_t n_desc_slots) {
+__global__ void k_emit(Jobs jobs, const int4* __restrict__ coords, int32_t n, int32_t vox_blocks) {
+  const Job& J = jobs.j[blockIdx.z];
+  const PartGeom& g = J.g;
+  const AxisSet& ax = J.ax;
+  if ((int32_t)blockIdx.y >= ax.n) return;
+  const int32_t* __restrict__ win_count = J.win_count;
+  const int32_t* __restrict__ win_soff = J.win_soff;
+  int32_t* __restrict__ set_win = J.set_win;
+  const int32_t* __restrict__ set_loc = J.set_loc;
+  const int32_t* __restrict__ n_tiles = J.out.n_tiles;
+  const int32_t max_sets = J.set_cap, n_desc_slots = J.out.max_tiles;
   const AxisBufs& me = ax.a[blockIdx.y];
   int32_t* __restrict__ tile_desc = me.tile_desc;
   if ((int32_t)blockIdx.x >= vox_blocks) {
@@ -878,107 +905,167 @@ int make_plan(const dsvt_part_cfg* cfg, int32_t n_voxels, PartPlan* p) {
 // Header value of a scratch buffer whose mark bitmaps (room for both axes) are zero for this geometry.
 uint64_t ws_token(const PartPlan& p) { return kWsMagic ^ ((uint64_t)p.n_words * 0x9E3779B97F4A7C15ull); }
 
-// The partition of n_axes inner orders (axis0, axis0 + 1) of one window configuration.
-int run_partition(const dsvt_part_cfg* cfg, int32_t n_axes, int32_t axis0, const int32_t* coords, int32_t n_voxels,
-                  int32_t* const* set_inds, int32_t* const* voxel_slot, int32_t* n_sets, int32_t max_sets, int32_t* set_win,
-                  const dsvt_tile_list* tiles, int32_t* tile_desc_2, void* ws, size_t ws_bytes, int32_t* status,
-                  void* stream) {
+// What one window configuration asks for (host side).
+struct PartRequest {
+  const dsvt_part_cfg* cfg;
+  int32_t n_axes, axis0;
+  int32_t* set_inds[2];
+  int32_t* voxel_slot[2];
+  int32_t *n_sets, *set_win;
+  int32_t max_sets;
+  const dsvt_tile_list* tiles;
+  int32_t* tile_desc_2;
+  void* ws;
+  size_t ws_bytes;
+  int32_t* status;
+};
+
+struct Prepared {
   PartPlan p;
-  int rc = make_plan(cfg, n_voxels, &p);
+  Job job;
+  bool want_tiles, front_ok;
+  size_t front_lds;
+};
+
+// Checks one request and lays out its job.
+int prepare(const PartRequest& r, int32_t n_voxels, Prepared* out) {
+  PartPlan& p = out->p;
+  int rc = make_plan(r.cfg, n_voxels, &p);
   if (rc != DSVT_OK) return rc;
-  if (!coords || !n_sets || !ws || !status || max_sets <= 0) return DSVT_EINVAL;
-  for (int32_t k = 0; k < n_axes; ++k)
-    if (!set_inds[k] || !voxel_slot[k]) return DSVT_EINVAL;
-  if ((int64_t)max_sets * cfg->tau >= (1ll << 31)) return DSVT_EINVAL;
-  if (ws_bytes < p.total) return DSVT_ENOSPC;
-  TileOut tout = {nullptr, nullptr, nullptr, {nullptr, nullptr}, 0};
-  if (tiles != nullptr) {
-    if (!tiles->tile_first || !tiles->n_tiles || !tiles->tile_order || !tiles->tile_desc || tiles->max_tiles <= 0) return DSVT_EINVAL;
-    if (n_axes == 2 && !tile_desc_2) return DSVT_EINVAL;
+  if (!r.n_sets || !r.ws || !r.status || r.max_sets <= 0) return DSVT_EINVAL;
+  for (int32_t k = 0; k < r.n_axes; ++k)
+    if (!r.set_inds[k] || !r.voxel_slot[k]) return DSVT_EINVAL;
+  if ((int64_t)r.max_sets * r.cfg->tau >= (1ll << 31)) return DSVT_EINVAL;
+  if (r.ws_bytes < p.total) return DSVT_ENOSPC;
+  Job& J = out->job;
+  J = Job{};
+  TileOut& tout = J.out;
+  out->want_tiles = r.tiles != nullptr;
+  if (r.tiles != nullptr) {
+    const dsvt_tile_list* t = r.tiles;
+    if (!t->tile_first || !t->n_tiles || !t->tile_order || !t->tile_desc || t->max_tiles <= 0) return DSVT_EINVAL;
+    if (r.n_axes == 2 && !r.tile_desc_2) return DSVT_EINVAL;
     if (!p.desc_ok) return DSVT_EUNSUPPORTED;
-    tout.tile_first = tiles->tile_first; tout.n_tiles = tiles->n_tiles; tout.tile_order = tiles->tile_order;
-    tout.tile_desc[0] = tiles->tile_desc;
-    tout.tile_desc[1] = n_axes == 2 ? tile_desc_2 : nullptr;
-    tout.max_tiles = tiles->max_tiles < p.tile_bound ? tiles->max_tiles : p.tile_bound;   // scratch is sized for the bound
+    tout.tile_first = t->tile_first; tout.n_tiles = t->n_tiles; tout.tile_order = t->tile_order;
+    tout.tile_desc[0] = t->tile_desc;
+    tout.tile_desc[1] = r.n_axes == 2 ? r.tile_desc_2 : nullptr;
+    tout.max_tiles = t->max_tiles < p.tile_bound ? t->max_tiles : p.tile_bound;   // scratch is sized for the bound
   }
-  // window key of every set: the caller's array, or scratch when it is not wanted
-  int32_t set_cap = max_sets < p.set_bound ? max_sets : p.set_bound;
-  if (set_win == nullptr) set_win = (int32_t*)((char*)ws + p.off_setwin);   // k_emit rewrites the same values there
-  hipStream_t st = (hipStream_t)stream;
-  char* base = (char*)ws;
-  int32_t* count = (int32_t*)(base + p.off_count);
-  int32_t* soff = (int32_t*)(base + p.off_soff);
-  int32_t* set_loc = (int32_t*)(base + p.off_setloc);
-  AxisSet ax = {};
-  ax.n = n_axes; ax.axis0 = axis0;
-  for (int32_t k = 0; k < n_axes; ++k) {
+  char* base = (char*)r.ws;
+  J.win_count = (int32_t*)(base + p.off_count);
+  J.win_soff = (int32_t*)(base + p.off_soff);
+  J.set_loc = (int32_t*)(base + p.off_setloc);
+  J.n_sets = r.n_sets;
+  J.status = r.status;
+  // window key of every set: the caller's array, or scratch when it is not wanted (k_emit rewrites the same values there)
+  J.set_win = r.set_win != nullptr ? r.set_win : (int32_t*)(base + p.off_setwin);
+  J.n_words = (int32_t)p.n_words;
+  J.max_sets = r.max_sets;
+  J.set_cap = r.max_sets < p.set_bound ? r.max_sets : p.set_bound;
+  J.rows_per_cut = p.rows_per_cut;
+  J.tile_cap = p.tile_bound;
+  AxisSet& ax = J.ax;
+  ax.n = r.n_axes; ax.axis0 = r.axis0;
+  for (int32_t k = 0; k < r.n_axes; ++k) {
     ax.a[k].mark = (uint32_t*)(base + p.off_mark) + (size_t)k * p.n_words;
     ax.a[k].bitmap = (uint32_t*)(base + p.off_bitmap) + (size_t)k * p.n_words;
     ax.a[k].prefix = (uint32_t*)(base + p.off_prefix) + (size_t)k * p.n_words;
-    ax.a[k].set_inds = set_inds[k]; ax.a[k].voxel_slot = voxel_slot[k];
+    ax.a[k].set_inds = r.set_inds[k]; ax.a[k].voxel_slot = r.voxel_slot[k];
     ax.a[k].tile_desc = tout.tile_desc[k];
   }
-  const int tb = 256;
   ax.ws_token = (const uint64_t*)base;
   ax.token = ws_token(p);
-  {
-    dsvt_prof_scope ps(DSVT_K_PART_MARK, st);
-    k_mark<<<(unsigned)dsvt_ceil_div(n_voxels, tb), tb, 0, st>>>(p.g, (const int4*)coords, n_voxels, ax, status);
-  }
   // k_front divides by multiplying: exact for x < 2^16 and d < 2^15 (tau against a window's volume + tau),
   // and for x < 2^25 and d <= 128 (rows of a tile cut against all padded rows)
-  bool front_ok = (int64_t)p.g.words_per_win * 32 + cfg->tau < (1 << 16) && cfg->tau < (1 << 15) && cfg->tau > 1 &&
+  const int32_t tau = r.cfg->tau;
+  out->front_ok = (int64_t)p.g.words_per_win * 32 + tau < (1 << 16) && tau < (1 << 15) && tau > 1 &&
                   (int64_t)n_voxels + 4 * (int64_t)p.set_bound < (1 << 25) && p.g.n_windows < (1 << 22) &&
-                  p.n_words * n_axes < (1 << 22) && (tiles == nullptr || p.rows_per_cut >= 2);
-  if (front_ok) {
-    p.g.magic_tau = (uint32_t)(((1ull << 32) + (uint64_t)cfg->tau - 1) / (uint64_t)cfg->tau);
+                  p.n_words * r.n_axes < (1 << 22) && (r.tiles == nullptr || p.rows_per_cut >= 2);
+  if (out->front_ok) {
+    p.g.magic_tau = (uint32_t)(((1ull << 32) + (uint64_t)tau - 1) / (uint64_t)tau);
     const int32_t cut = p.rows_per_cut > 1 ? p.rows_per_cut : 2;
     p.g.magic_cut = (uint32_t)(((1ull << 32) + (uint64_t)cut - 1) / (uint64_t)cut);
   }
-  const size_t front_lds = ((size_t)n_axes * p.n_words + 4 * (size_t)p.g.n_windows + 3 * (size_t)(p.tile_bound + 1)) * 4;
-  if (front_ok && front_lds <= kFrontLds) {
-    static bool lds_raised = false;                          // (the same value every time: a benign race)
-    if (!lds_raised) {
-      DSVT_HIP_TRY(hipFuncSetAttribute((const void*)k_front<1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFrontLds));
-      DSVT_HIP_TRY(hipFuncSetAttribute((const void*)k_front<2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFrontLds));
-      lds_raised = true;
-    }
-    dsvt_prof_scope ps(DSVT_K_PART_TILES, st);
-    auto* front = n_axes == 2 ? k_front<2> : k_front<1>;
-    front<<<1, 1024, front_lds, st>>>(p.g, ax, (int32_t)p.n_words, count, soff, max_sets, n_sets, status, set_cap,
-                                      p.rows_per_cut, tout, p.tile_bound, set_loc
-#ifdef DSVT_PHASE_CLOCKS
-                                      , g_front_clocks
-#endif
-                                      );
-  } else {
-    int32_t group = 1;
-    while (group < 64 && group < p.g.words_per_win) group <<= 1;
-    {
-      dsvt_prof_scope ps(DSVT_K_PART_COUNT, st);
-      int64_t threads = (int64_t)p.g.n_windows * group;
-      k_window_count<<<dim3((unsigned)dsvt_ceil_div(threads, tb), n_axes), tb, 0, st>>>(ax, count, p.g.n_windows,
-                                                                                       p.g.words_per_win, group);
-    }
-    {
-      dsvt_prof_scope ps(DSVT_K_PART_SCAN, st);
-      k_scan_windows<<<1, 1024, 0, st>>>(count, soff, p.g.n_windows, cfg->tau, max_sets, n_sets, status,
-                                         (int32_t*)(base + p.off_setwin), p.set_bound);
-    }
-    if (tiles != nullptr) {
-      dsvt_prof_scope ps(DSVT_K_PART_TILES, st);
-      k_tiles<<<1, 1024, 0, st>>>((const int32_t*)(base + p.off_setwin), count, soff, n_sets, set_cap, cfg->tau,
-                                  p.g.n_windows, p.rows_per_cut, tout, (int32_t*)(base + p.off_tilerows),
-                                  (int32_t*)(base + p.off_tilepos), (int32_t*)(base + p.off_setp), set_loc);
-    }
+  out->front_lds = ((size_t)r.n_axes * p.n_words + 4 * (size_t)p.g.n_windows + 3 * (size_t)(p.tile_bound + 1)) * 4;
+  out->front_ok = out->front_ok && out->front_lds <= kFrontLds;
+  J.g = p.g;
+  return DSVT_OK;
+}
+
+// The partitions of n window configurations over the same voxels (n_axes inner orders each): one
+// launch per step when every configuration fits k_front, else one configuration after the other.
+int run_partitions(const PartRequest* reqs, int32_t n, const int32_t* coords, int32_t n_voxels, void* stream) {
+  if (n <= 0 || n > kMaxJobs || !reqs || !coords) return DSVT_EINVAL;
+  Prepared prep[kMaxJobs];
+  bool all_front = true;
+  for (int32_t q = 0; q < n; ++q) {
+    if (reqs[q].cfg == nullptr || reqs[q].n_axes != reqs[0].n_axes) return DSVT_EINVAL;
+    int rc = prepare(reqs[q], n_voxels, &prep[q]);
+    if (rc != DSVT_OK) return rc;
+    all_front = all_front && prep[q].front_ok;
   }
-  {
-    dsvt_prof_scope ps(DSVT_K_PART_EMIT, st);
-    const int32_t vox_blocks = (int32_t)dsvt_ceil_div(n_voxels, tb);
-    const int32_t tail_blocks = (int32_t)dsvt_ceil_div((int64_t)tout.max_tiles * kTileRows, tb);
-    k_emit<<<dim3((unsigned)(vox_blocks + tail_blocks), n_axes), tb, 0, st>>>(p.g, (const int4*)coords, n_voxels, ax, vox_blocks,
-                                                                            count, soff, set_cap, set_win, set_loc,
-                                                                            tout.n_tiles, tout.max_tiles);
+  hipStream_t st = (hipStream_t)stream;
+  const int tb = 256;
+  const int32_t n_axes = reqs[0].n_axes;
+  const int32_t vox_blocks = (int32_t)dsvt_ceil_div(n_voxels, tb);
+  for (int32_t q0 = 0; q0 < n; q0 += all_front ? n : 1) {
+    const int32_t nq = all_front ? n : 1;
+    Jobs jobs = {};
+    size_t lds = 0;
+    int32_t max_tiles = 0;
+    for (int32_t q = 0; q < nq; ++q) {
+      jobs.j[q] = prep[q0 + q].job;
+      lds = prep[q0 + q].front_lds > lds ? prep[q0 + q].front_lds : lds;
+      max_tiles = jobs.j[q].out.max_tiles > max_tiles ? jobs.j[q].out.max_tiles : max_tiles;
+    }
+    {
+      dsvt_prof_scope ps(DSVT_K_PART_MARK, st);
+      k_mark<<<dim3((unsigned)vox_blocks, nq), tb, 0, st>>>(jobs, (const int4*)coords, n_voxels);
+    }
+    if (all_front) {
+      static bool lds_raised = false;                        // (the same value every time: a benign race)
+      if (!lds_raised) {
+        DSVT_HIP_TRY(hipFuncSetAttribute((const void*)k_front<1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFrontLds));
+        DSVT_HIP_TRY(hipFuncSetAttribute((const void*)k_front<2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFrontLds));
+        lds_raised = true;
+      }
+      dsvt_prof_scope ps(DSVT_K_PART_TILES, st);
+      auto* front = n_axes == 2 ? k_front<2> : k_front<1>;
+      front<<<nq, 1024, lds, st>>>(jobs
+#ifdef DSVT_PHASE_CLOCKS
+                                   , g_front_clocks
+#endif
+                                   );
+    } else {
+      const Prepared& P = prep[q0];
+      const PartPlan& p = P.p;
+      const Job& J = P.job;
+      char* base = (char*)reqs[q0].ws;
+      int32_t group = 1;
+      while (group < 64 && group < p.g.words_per_win) group <<= 1;
+      {
+        dsvt_prof_scope ps(DSVT_K_PART_COUNT, st);
+        int64_t threads = (int64_t)p.g.n_windows * group;
+        k_window_count<<<dim3((unsigned)dsvt_ceil_div(threads, tb), n_axes), tb, 0, st>>>(J.ax, J.win_count, p.g.n_windows,
+                                                                                         p.g.words_per_win, group);
+      }
+      {
+        dsvt_prof_scope ps(DSVT_K_PART_SCAN, st);
+        k_scan_windows<<<1, 1024, 0, st>>>(J.win_count, J.win_soff, p.g.n_windows, p.g.tau, J.max_sets, J.n_sets, J.status,
+                                           (int32_t*)(base + p.off_setwin), p.set_bound);
+      }
+      if (P.want_tiles) {
+        dsvt_prof_scope ps(DSVT_K_PART_TILES, st);
+        k_tiles<<<1, 1024, 0, st>>>((const int32_t*)(base + p.off_setwin), J.win_count, J.win_soff, J.n_sets, J.set_cap,
+                                    p.g.tau, p.g.n_windows, p.rows_per_cut, J.out, (int32_t*)(base + p.off_tilerows),
+                                    (int32_t*)(base + p.off_tilepos), (int32_t*)(base + p.off_setp), J.set_loc);
+      }
+    }
+    {
+      dsvt_prof_scope ps(DSVT_K_PART_EMIT, st);
+      const int32_t tail_blocks = (int32_t)dsvt_ceil_div((int64_t)max_tiles * kTileRows, tb);
+      k_emit<<<dim3((unsigned)(vox_blocks + tail_blocks), n_axes, nq), tb, 0, st>>>(jobs, (const int4*)coords, n_voxels, vox_blocks);
+    }
   }
   DSVT_HIP_TRY(hipGetLastError());
   return DSVT_OK;
@@ -1018,8 +1105,9 @@ extern "C" int dsvt_partition(const dsvt_part_cfg* cfg, const int32_t* coords, i
                               int32_t* voxel_slot, int32_t* n_sets, int32_t max_sets, int32_t* set_win,
                               const dsvt_tile_list* tiles, void* ws, size_t ws_bytes, int32_t* status, void* stream) {
   if (cfg == nullptr) return DSVT_EINVAL;
-  return run_partition(cfg, 1, cfg->axis, coords, n_voxels, &set_inds, &voxel_slot, n_sets, max_sets, set_win, tiles, nullptr,
-                       ws, ws_bytes, status, stream);
+  const PartRequest r = {cfg, 1, cfg->axis, {set_inds, nullptr}, {voxel_slot, nullptr}, n_sets, set_win, max_sets, tiles,
+                         nullptr, ws, ws_bytes, status};
+  return run_partitions(&r, 1, coords, n_voxels, stream);
 }
 
 extern "C" int dsvt_partition_xy(const dsvt_part_cfg* cfg, const int32_t* coords, int32_t n_voxels, int32_t* set_inds_x,
@@ -1027,8 +1115,19 @@ extern "C" int dsvt_partition_xy(const dsvt_part_cfg* cfg, const int32_t* coords
                                  int32_t max_sets, int32_t* set_win, const dsvt_tile_list* tiles, int32_t* tile_desc_y,
                                  void* ws, size_t ws_bytes, int32_t* status, void* stream) {
   if (cfg == nullptr) return DSVT_EINVAL;
-  int32_t* const si[2] = {set_inds_x, set_inds_y};
-  int32_t* const vs[2] = {voxel_slot_x, voxel_slot_y};
-  return run_partition(cfg, 2, 0, coords, n_voxels, si, vs, n_sets, max_sets, set_win, tiles, tile_desc_y, ws, ws_bytes,
-                       status, stream);
+  const PartRequest r = {cfg, 2, 0, {set_inds_x, set_inds_y}, {voxel_slot_x, voxel_slot_y}, n_sets, set_win, max_sets, tiles,
+                         tile_desc_y, ws, ws_bytes, status};
+  return run_partitions(&r, 1, coords, n_voxels, stream);
+}
+
+extern "C" int dsvt_partition_xy_multi(const dsvt_xy_job* jobs, int32_t n_jobs, const int32_t* coords, int32_t n_voxels,
+                                       void* stream) {
+  if (jobs == nullptr || n_jobs <= 0 || n_jobs > kMaxJobs) return DSVT_EINVAL;
+  PartRequest r[kMaxJobs];
+  for (int32_t q = 0; q < n_jobs; ++q) {
+    const dsvt_xy_job& j = jobs[q];
+    r[q] = PartRequest{&j.cfg, 2, 0, {j.set_inds_x, j.set_inds_y}, {j.voxel_slot_x, j.voxel_slot_y}, j.n_sets, j.set_win,
+                       j.max_sets, j.tiles, j.tile_desc_y, j.ws, j.ws_bytes, j.status};
+  }
+  return run_partitions(r, n_jobs, coords, n_voxels, stream);
 }

@@ -62,6 +62,24 @@ def test_partition_xy_bit_exact(cid, n):
         assert_tiles_valid(pair2[axis], om)
 
 
+@pytest.mark.parametrize("cid,n", [(2, None), (1, None), (3, 20000)])
+def test_partition_xy_multi_bit_exact(cid, n):
+    """A stage's window configurations (unshifted, shifted, and a second tau) partitioned by one call."""
+    cfg = synth.CONFIGS[cid]
+    coords = synth.make_frame(cid, n=n)
+    half = tuple(w // 2 for w in cfg["win"][:2]) + (0,)
+    variants = [((0, 0, 0), cfg["tau"]), (half, cfg["tau"]), (half, cfg["tau"] // 2 + 1)]
+    _say(f"partition_xy_multi cfg{cid} n={len(coords)}")
+    pcs = [dsvt.part_cfg(cfg["grid"], cfg["win"], sh, tau, cfg["batch"], 0) for sh, tau in variants]
+    outs = [dsvt.SetMapsXY(pc, len(coords)) for pc in pcs]
+    cd = dev_coords(coords)
+    for _ in range(2):                                 # twice: the second call finds what the first left behind
+        dsvt.dsvt_partition_xy_multi(pcs, cd, outs)
+    for (sh, tau), out in zip(variants, outs):
+        for axis in (0, 1):
+            assert_maps_equal(out[axis], orc.partition(coords, cfg["grid"], cfg["win"], sh, tau, axis))
+
+
 def test_partition_xy_odd_geometry_and_batch():
     grid, win, shift, tau = (29, 17, 9), (5, 7, 3), (2, 6, 1), 11
     coords = np.concatenate([np.concatenate([np.full((900, 1), b), synth.frame_uniform(60 + b, grid, 900)], 1)
