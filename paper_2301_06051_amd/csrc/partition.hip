@@ -493,6 +493,19 @@ __device__ __forceinline__ Scan3 block_scan3(Scan3 v, int32_t (*wave_tot)[16], i
   return v;                                 // the new carry is visible after the caller's next barrier
 }
 
+// The same for one sum.
+__device__ __forceinline__ int32_t block_scan1(int32_t v, int32_t* wave_tot, int32_t* carry) {
+  const int32_t tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  v = wave_scan_add(v);
+  if (lane == 63) wave_tot[wv] = v;
+  lds_barrier();
+  const int32_t t = wave_scan_add(lane < 16 ? wave_tot[lane] : 0);
+  v += *carry + (wv > 0 ? __builtin_amdgcn_readlane(t, wv - 1) : 0);
+  lds_barrier();
+  if (tid == 1023) *carry = v;
+  return v;
+}
+
 // Small frames: everything between k_mark and k_emit in one workgroup and one launch.  The marked bits
 // are staged in LDS (and the mark bitmap left zero for the next call), and the per-window and per-tile
 // tables stay in LDS between the steps: the kernel reads the bitmaps and writes its results, with no
@@ -634,10 +647,9 @@ __global__ void __launch_bounds__(1024) k_front(Jobs jobs
       }
     };
     if (want_tiles) for_each_set([&](int32_t, int32_t, bool first) { F += first ? 1 : 0; });
-    Scan3 f = {F, 0, -1, -1};
-    f = block_scan3(f, wave_tot, carry2);
+    const int32_t f_incl = block_scan1(F, wave_tot[0], carry2);
     if (want_tiles && w < nw) {
-      int32_t t = f.a - F;                                    // tiles started before this window
+      int32_t t = f_incl - F;                                 // tiles started before this window
       wT0[w] = t;
       for_each_set([&](int32_t s, int32_t P, bool first) {
         if (!first) return;
@@ -695,16 +707,17 @@ __global__ void __launch_bounds__(1024) k_front(Jobs jobs
       b = b < 0 ? 0 : (b > 31 ? 31 : b);
     }
     for (int32_t k = lane; k < 32; k += 64) wave_cnt[wv][k] = 0;
-    int32_t rank = 0;                                         // among this wavefront's lanes of the same bucket
-    unsigned long long todo = __ballot(b >= 0);
-    while (todo) {
-      const int32_t leader = __ffsll((long long)todo) - 1;
-      const int32_t lb = __shfl(b, leader, 64);
-      const unsigned long long same = __ballot(b == lb);
-      if (b == lb) rank = __popcll(same & ((1ull << lane) - 1ull));
-      if (lane == leader) wave_cnt[wv][lb] = __popcll(same);
-      todo &= ~same;
+    // lanes of this wavefront with the same bucket: those that agree with this lane in each of its 5 bits
+    unsigned long long same = __ballot(b >= 0);
+#pragma unroll
+    for (int32_t bit = 0; bit < 5; ++bit) {
+      const bool one = (b >> bit) & 1;
+      const unsigned long long ones = __ballot(one);
+      same &= one ? ones : ~ones;
     }
+    const unsigned long long below = same & ((1ull << lane) - 1ull);
+    const int32_t rank = __popcll(below);                     // among this wavefront's lanes of the same bucket
+    if (b >= 0 && below == 0ull) wave_cnt[wv][b] = __popcll(same);
     lds_barrier();
     if (tid < 512) {                                          // a row of 16 lanes per bucket, a lane per wavefront:
       const int32_t bb = tid >> 4, k = tid & 15;              // counts of the wavefronts -> first position of each
