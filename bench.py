@@ -6,6 +6,11 @@ C = 192, 8 heads, tau = 36, windows 12 x 12 x 1): four set partitions (2 window 
 and four DSVT blocks (8 layers).  Inputs are resident in HBM before the timed region.  Prints one
 JSON line: voxels/s, ms/frame, the roofline of the dominant kernel (per-kernel time from hipEvent
 pairs around every launch) and the CPU oracle timed on the host cores on one frame.
+
+--workload names another of the synthetic workloads instead (the same JSON line, no CPU baseline):
+voxel = the 120,000-voxel frame (2 blocks), skewed = the 4-frame batch of 200,000 voxels each
+(4 blocks), pool = attention-style 3D pooling of the voxel frame, bev = bird's-eye-view scatter of
+the pillar frame.
 """
 import argparse
 import json
@@ -15,37 +20,64 @@ import time
 import numpy as np
 
 
-# HBM bytes one launch of the layer kernel moves on this workload, from rocprofv3 FETCH_SIZE and
-# WRITE_SIZE (KiB per dispatch, each scaled by its reading for a plain 256 MiB copy); the
+# HBM bytes one launch of the layer kernel moves on the default workload, from rocprofv3 FETCH_SIZE
+# and WRITE_SIZE (KiB per dispatch, each scaled by its reading for a plain 256 MiB copy); the
 # measurement and its commands are in profiles/hbm_traffic_pillar_frame.md.
-LAYER_HBM_BYTES_PER_LAUNCH = 33962 * 1024      # 19,253 KiB fetched + 14,709 KiB written
+LAYER_HBM_BYTES_PER_LAUNCH = 28470 * 1024      # 17,220 KiB fetched + 11,250 KiB written
+
+STACKS = {"frame": 2, "voxel": 3, "skewed": 5}  # workload -> synth config id
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
-    ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of a captured HIP graph")
-    ap.add_argument("--pmc-calibration", action="store_true",
-                    help="also run one plain 256 MiB device copy (a kernel of known traffic, to scale rocprofv3's "
-                         "FETCH_SIZE / WRITE_SIZE readings)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build is single-GPU by design (frames shard across GPUs with no communication); "
-              "run with --gpus 1", file=sys.stderr)
-        sys.exit(2)
+def timed(run, steps, warmup):
+    import torch
+    for _ in range(warmup):
+        run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        run()
+    torch.cuda.synchronize()
+    return time.perf_counter() - t0
 
+
+def capture(step, check):
+    """step() captured into a HIP graph; three replays must pass check()."""
+    import torch
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for _ in range(3):
+        check(graph.replay)
+    return graph.replay
+
+
+def per_kernel(step, launches_per_step, steps):
+    """The same steps again, eagerly, with an event pair around every launch."""
+    import torch
+    import paper_2301_06051_amd as dsvt
+    dsvt.prof_enable(launches_per_step * steps)
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    prof = dsvt.prof_collect()
+    return ({k: 1e3 * ms / n for k, (ms, n) in prof.items() if n}, {k: ms / steps for k, (ms, n) in prof.items() if n})
+
+
+def stack_workload(args, name):
     import torch
     import synth
     import paper_2301_06051_amd as dsvt
-
-    torch.cuda.set_device(0)
-    cid = 2
+    cid = STACKS[name]
     cfg = synth.CONFIGS[cid]
-    C, tau, N = cfg["C"], cfg["tau"], cfg["n"]
+    C, tau = cfg["C"], cfg["tau"]
     coords = synth.make_frame(cid)
+    N = len(coords)
     x_np = synth.make_features(33, N, C, cfg["dtype"])
     w_np = [[synth.make_layer_weights(200 + 2 * b + a, C, cfg["heads"], cfg["hidden"], cfg["win"], cfg["dtype"])
              for a in (0, 1)] for b in range(cfg["blocks"])]
@@ -58,7 +90,7 @@ def main():
     maps = {sh: dsvt.SetMapsXY(pc, N) for sh, pc in pcfgs.items()}       # X- and Y-axis maps of each window shift
     ws = torch.empty((max(dsvt.dsvt_block_workspace_size(layers[0][0], N), 1),), dtype=torch.uint8, device="cuda")
 
-    # The partitions of both window shifts, each in both axes, go through one chain of three launches
+    # The partitions of both window shifts, each in both axes, go through one chain of launches
     # ahead of the blocks; everything is on one stream.
     shifts = list(cfg["shifts"])
 
@@ -84,59 +116,29 @@ def main():
     status = max(int(m.status.item()) for ms in maps.values() for m in ms)
     assert status == 0, f"partition status {status}"
 
-    use_graph = not args.no_graph
-    run = step
-    if use_graph:
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        with torch.cuda.stream(side):
-            step()
-        torch.cuda.current_stream().wait_stream(side)
+    def check(replay):                           # replays must reproduce the eager result bit for bit
+        buf.zero_()
+        replay()
         torch.cuda.synchronize()
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            step()
-        for _ in range(3):                       # replays must reproduce the eager result bit for bit
-            buf.zero_()
-            graph.replay()
-            torch.cuda.synchronize()
-            assert torch.equal(buf, eager_out), "graph replay differs from eager launches"
-        run = graph.replay
+        assert torch.equal(buf, eager_out), "graph replay differs from eager launches"
 
-    for _ in range(args.warmup):
-        run()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        run()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ms_per_step = dt / args.steps * 1e3
-
-    # Per-kernel time: the same steps again, eagerly, with an event pair around every launch.
-    launches_per_step = 3 + 4 * 2
-    prof_steps = min(args.steps, 50)
-    dsvt.prof_enable(launches_per_step * prof_steps)
-    for _ in range(prof_steps):
-        step()
-    torch.cuda.synchronize()
-    prof = dsvt.prof_collect()
-    per_launch_us = {k: 1e3 * ms / n for k, (ms, n) in prof.items() if n}
-    per_step_ms = {k: ms / prof_steps for k, (ms, n) in prof.items() if n}
+    use_graph = not args.no_graph
+    run = capture(step, check) if use_graph else step
+    dt = timed(run, args.steps, args.warmup)
+    launches = 6 * len(shifts) + 2 * cfg["blocks"]          # (an upper bound: small frames take 3 partition launches)
+    per_launch_us, per_step_ms = per_kernel(step, launches, min(args.steps, 50))
 
     # Roofline of the dominant kernel, the fused layer.  Algorithmic flops per voxel per layer
     # (duplicate-row and tile-padding work not counted): 16 C^2 + 4 tau C rho.
-    rho = np.mean([n_sets[cfg["shifts"][b % len(cfg["shifts"])]] for b in range(cfg["blocks"])]) * tau / N
-    flops = {"layer": N * (16 * C * C + 4 * tau * C * rho)}
-    dom = "layer"
-    achieved = flops[dom] / (per_launch_us[dom] * 1e-6) / 1e12
-    peak = 2500.0
-    roofline = {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s",
-                "frac": round(achieved / peak, 5), "traffic": LAYER_HBM_BYTES_PER_LAUNCH,
-                "avg_launch_us": round(per_launch_us[dom], 2), "flops_per_launch": flops[dom]}
+    rho = np.mean([n_sets[shifts[b % len(shifts)]] for b in range(cfg["blocks"])]) * tau / N
+    flops = N * (16 * C * C + 4 * tau * C * rho)
+    achieved = flops / (per_launch_us["layer"] * 1e-6) / 1e12
+    roofline = {"bound": "mfma", "kernel": "layer", "achieved": round(achieved, 2), "peak": 2500.0, "unit": "TFLOP/s",
+                "frac": round(achieved / 2500.0, 5), "traffic": LAYER_HBM_BYTES_PER_LAUNCH if name == "frame" else None,
+                "avg_launch_us": round(per_launch_us["layer"], 2), "flops_per_launch": flops}
 
     cpu = None
-    if not args.no_cpu_baseline:
+    if name == "frame" and not args.no_cpu_baseline:
         from threadpoolctl import threadpool_info
         from oracle import dsvt_oracle as orc
         t0 = time.perf_counter()
@@ -146,19 +148,143 @@ def main():
         cpu = {"value": round(N / cdt, 1), "unit": "voxels/s", "cores": cores, "kind": "oracle",
                "sample": f"one full frame of the same workload ({N} voxels, 8 layers, 4 partitions), {cdt:.1f} s"}
 
-    line = {
-        "metric": "voxels/sec through the 4-block DSVT stack (partition + set attention); ms/frame 4-block",
-        "value": round(N / (dt / args.steps), 1), "unit": "voxels/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "configs[1]: 468x468x1 pillar frame, 30000 voxels, C=192, 8 heads, tau=36, "
-                               "win 12x12x1, 4 blocks x 2 layers, shift (6,6,0) on odd blocks",
-                   "launch": "hip_graph" if use_graph else "eager", "n_sets": {"shift" + "_".join(map(str, k)): v for k, v in n_sets.items()}, "rho": round(float(rho), 4)},
-        "ms_per_frame": round(ms_per_step, 4),
+    g, w, nb = cfg["grid"], cfg["win"], cfg["blocks"]
+    workload = (f"configs[{cid - 1}]: {g[0]}x{g[1]}x{g[2]} {'pillar' if g[2] == 1 else 'voxel'} frame"
+                f"{'s, batch ' + str(cfg['batch']) if cfg['batch'] > 1 else ''}, {N} voxels, C={C}, {cfg['heads']} heads, "
+                f"tau={tau}, win {w[0]}x{w[1]}x{w[2]}, {nb} blocks x 2 layers, shift (6,6,0) on odd blocks")
+    return {
+        "metric": f"voxels/sec through the {nb}-block DSVT stack (partition + set attention); ms/frame {nb}-block",
+        "value": round(N / (dt / args.steps), 1), "unit": "voxels/s", "dtype": "bf16",
+        "config": {"workload": workload, "launch": "hip_graph" if use_graph else "eager",
+                   "n_sets": {"shift" + "_".join(map(str, k)): v for k, v in n_sets.items()}, "rho": round(float(rho), 4)},
+        "ms_per_frame": round(dt / args.steps * 1e3, 4),
         "kernel_ms_per_step": {k: round(v, 4) for k, v in per_step_ms.items()},
         "kernel_us_per_launch": {k: round(v, 2) for k, v in per_launch_us.items()},
         "roofline": roofline, "cpu_baseline": cpu,
-    }
+    }, dt
+
+
+def pool_workload(args):
+    """Sec. 3.3: attention-style 3D pooling of the 120,000-voxel frame over 1 x 1 x 4 regions."""
+    import torch
+    import synth
+    import paper_2301_06051_amd as dsvt
+    cid = 4
+    cfg = synth.CONFIGS[cid]
+    C, pool = cfg["C"], cfg["pool"]
+    coords = synth.make_frame(cid)
+    N = len(coords)
+    cd = torch.as_tensor(coords).cuda()
+    x = torch.as_tensor(synth.make_features(35, N, C, cfg["dtype"])).cuda().to(torch.bfloat16).contiguous()
+    pw = dsvt.PoolWeights(synth.make_pool_weights(91, C, cfg["heads"], cfg["dtype"]), cfg["grid"], pool, cfg["batch"], 0)
+    ws = torch.empty((max(dsvt.dsvt_attn_pool_workspace_size(pw, N), 1),), dtype=torch.uint8, device="cuda")
+    out = (torch.zeros((N, 4), dtype=torch.int32, device="cuda"), torch.zeros_like(x),
+           torch.zeros((1,), dtype=torch.int32, device="cuda"), torch.zeros((1,), dtype=torch.int32, device="cuda"))
+
+    def step():
+        dsvt.dsvt_attn_pool(pw, cd, x, out=out, ws=ws)
+
+    step()
+    torch.cuda.synchronize()
+    assert int(out[3].item()) == 0
+    M = int(out[2].item())
+    ref = out[1].clone()
+
+    def check(replay):
+        out[1].zero_()
+        replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out[1], ref), "graph replay differs from eager launches"
+
+    use_graph = not args.no_graph
+    run = capture(step, check) if use_graph else step
+    dt = timed(run, args.steps, args.warmup)
+    per_launch_us, per_step_ms = per_kernel(step, 8, min(args.steps, 50))
+    # K and V projections of the N occupied cells, Q and output projection of the M regions, 2 C^2 flops each
+    flops = 2 * C * C * (2 * N + 2 * M)
+    us = per_launch_us["pool_attention"]
+    roofline = {"bound": "mfma", "kernel": "pool_attention", "achieved": round(flops / (us * 1e-6) / 1e12, 2), "peak": 2500.0,
+                "unit": "TFLOP/s", "frac": round(flops / (us * 1e-6) / 2.5e15, 5), "traffic": None, "avg_launch_us": round(us, 2),
+                "flops_per_launch": flops, "hbm_bytes_algorithmic": (N + M) * C * 2,
+                "hbm_gbps_algorithmic": round((N + M) * C * 2 / (us * 1e-6) / 1e9, 1)}
+    return {
+        "metric": "input voxels/sec through attention-style 3D pooling (grouping + pooling attention)",
+        "value": round(N / (dt / args.steps), 1), "unit": "voxels/s", "dtype": "bf16",
+        "config": {"workload": f"configs[3]: 468x468x32 voxel frame, {N} voxels -> {M} regions of {pool[0]}x{pool[1]}x{pool[2]} "
+                               f"cells, C={C}, {cfg['heads']} heads, empty cells kept as keys",
+                   "launch": "hip_graph" if use_graph else "eager"},
+        "ms_per_frame": round(dt / args.steps * 1e3, 4),
+        "kernel_ms_per_step": {k: round(v, 4) for k, v in per_step_ms.items()},
+        "kernel_us_per_launch": {k: round(v, 2) for k, v in per_launch_us.items()},
+        "roofline": roofline, "cpu_baseline": None,
+    }, dt
+
+
+def bev_workload(args):
+    """Sec. 3.1: the pillar frame's rows scattered into the dense channels-last bird's-eye-view map."""
+    import torch
+    import synth
+    import paper_2301_06051_amd as dsvt
+    cfg = synth.CONFIGS[2]
+    C = cfg["C"]
+    coords = synth.make_frame(2)
+    N = len(coords)
+    cd = torch.as_tensor(coords).cuda()
+    x = torch.as_tensor(synth.make_features(33, N, C, cfg["dtype"])).cuda().to(torch.bfloat16).contiguous()
+    out = torch.empty((cfg["batch"], *cfg["grid"], C), dtype=torch.bfloat16, device="cuda")
+
+    def step():
+        dsvt.dsvt_bev_scatter(cd, x, cfg["batch"], cfg["grid"], out=out)
+
+    step()                                       # (eager: the binding allocates the status word per call)
+    torch.cuda.synchronize()
+    dt = timed(step, args.steps, args.warmup)
+    per_launch_us, per_step_ms = per_kernel(step, 2, min(args.steps, 50))
+    nbytes = out.numel() * 2 + 2 * N * C * 2 + N * 16      # map zero-filled, rows read and written, coords read
+    us = per_launch_us["bev_clear"] + per_launch_us["bev_scatter"]
+    roofline = {"bound": "hbm", "kernel": "bev_clear + bev_scatter", "achieved": round(nbytes / (us * 1e-6) / 1e9, 1), "peak": 8000.0,
+                "unit": "GB/s", "frac": round(nbytes / (us * 1e-6) / 8e12, 5), "traffic": None, "avg_launch_us": round(us, 2),
+                "bytes_per_launch": nbytes}
+    return {
+        "metric": "voxels/sec scattered into the dense bird's-eye-view map", "value": round(N / (dt / args.steps), 1),
+        "unit": "voxels/s", "dtype": "bf16",
+        "config": {"workload": f"configs[1]: {N} voxel rows of C={C} into a 468x468x1 channels-last map", "launch": "eager"},
+        "ms_per_frame": round(dt / args.steps * 1e3, 4),
+        "kernel_ms_per_step": {k: round(v, 4) for k, v in per_step_ms.items()},
+        "kernel_us_per_launch": {k: round(v, 2) for k, v in per_launch_us.items()},
+        "roofline": roofline, "cpu_baseline": None,
+    }, dt
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", choices=["frame", "voxel", "skewed", "pool", "bev"], default="frame")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
+    ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of a captured HIP graph")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run one plain 256 MiB device copy (a kernel of known traffic, to scale rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE readings)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU by design (frames shard across GPUs with no communication); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    torch.cuda.set_device(0)
+    if args.workload in STACKS:
+        body, dt = stack_workload(args, args.workload)
+    elif args.workload == "pool":
+        body, dt = pool_workload(args)
+    else:
+        body, dt = bev_workload(args)
+    line = {"metric": body.pop("metric"), "value": body.pop("value"), "unit": body.pop("unit"), "n_gpus": 1,
+            "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(dt / args.steps * 1e3, 4),
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": body.pop("dtype"), "data": "synthetic"}
+    line.update(body)
     print(json.dumps(line))
 
 

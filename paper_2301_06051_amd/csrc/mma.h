@@ -143,7 +143,7 @@ __device__ __forceinline__ void mma_row_swapped(f32x4 (&acc)[NT], const AFull<T,
 
 constexpr int kRowTiles = 6;                     // row tiles of a workgroup tile
 constexpr int kRowsMax = 16 * kRowTiles;         // 96 rows
-constexpr int kWaves = 4;                        // wavefronts of a pooling workgroup, one per SIMD
+constexpr int kWaves = 8;                        // wavefronts of a pooling workgroup, two per SIMD
 constexpr int kStatGroupsMax = 6;                // LayerNorm phases: the C features are split over at most 6 groups of output tiles
 
 // One GEMM phase of a workgroup of NW wavefronts: Out^T[NOUT x rows] = W[NOUT x K] . X^T.

@@ -4,17 +4,20 @@
 // output order (ascending region key) comes from an occupancy bitmap and a pop-count prefix, with
 // no sort.  Every voxel then writes its index into the dense slot table of its region
 // ("convert the sparse region into dense").
-// Attention: a workgroup takes kRowsMax / P consecutive regions; their dense slots (holes = zero
-// rows) are one <=96-row LDS tile.  Max-pool over the occupied slots gives the query row (Eq. 6);
-// K/V of all slots and Q of the pooled rows are MFMA projections; the P-key softmax per head is
-// plain ALU work; output projection, residual and LayerNorm follow the layer kernels (Eq. 7).
+// Attention: a workgroup takes 48 consecutive regions.  Only their occupied slots become rows of the
+// <=96-row LDS tile that the K/V projection runs on (an empty slot's key and value are the two bias
+// vectors, whatever the weights); regions whose occupied slots do not fit one tile are taken in
+// several passes.  Max-pool over the occupied slots gives the query row (Eq. 6); K/V of the occupied
+// slots and Q of the pooled rows are MFMA projections; the P-key softmax per head is plain ALU
+// work; output projection, residual and LayerNorm follow the layer kernels (Eq. 7).
 #include "common.h"
 #include "mma.h"
 
 namespace {
 
 constexpr int kMaxPool = 8;                       // slots of a pooling region
-constexpr int kQRows = 32;                        // pooled rows of a tile, padded to two MFMA row tiles
+constexpr int kRegs = 48;                         // regions (pooled rows) of a workgroup: three MFMA row tiles
+constexpr int kSlots = kRegs * kMaxPool;          // their dense slots at most
 
 struct PoolGeom {
   int32_t grid[3], pool[3], pg[3];                // cells, region size, pooled cells per axis
@@ -47,6 +50,9 @@ __global__ void kp_mark(PoolGeom g, const int4* __restrict__ coords, int32_t n, 
 }
 
 // One workgroup: exclusive pop-count scan over the bitmap words; the total is the output count.
+// A thread takes 16 consecutive words per round (four 16-byte loads), so a round covers 16,384 words
+// with one block scan of the threads' totals.
+constexpr int kScanWords = 16;
 __global__ void __launch_bounds__(1024) kp_scan(const uint32_t* __restrict__ bitmap, int32_t* __restrict__ word_prefix,
                                                 int64_t n_words, int32_t* __restrict__ n_out) {
   __shared__ int32_t wave_tot[16];
@@ -54,10 +60,23 @@ __global__ void __launch_bounds__(1024) kp_scan(const uint32_t* __restrict__ bit
   const int32_t tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   if (tid == 0) carry_s = 0;
   __syncthreads();
-  for (int64_t base = 0; base < n_words; base += 1024) {
-    const int64_t w = base + tid;
-    const int32_t v = w < n_words ? __popc(bitmap[w]) : 0;
-    int32_t incl = v;
+  for (int64_t base = 0; base < n_words; base += 1024 * kScanWords) {
+    const int64_t w0 = base + (int64_t)tid * kScanWords;
+    uint32_t v[kScanWords];
+    if (w0 + kScanWords <= n_words) {            // (the bitmap is 256-byte aligned and w0 a multiple of 16)
+#pragma unroll
+      for (int32_t q = 0; q < kScanWords / 4; ++q) {
+        const uint4 t = reinterpret_cast<const uint4*>(bitmap + w0)[q];
+        v[4 * q] = t.x; v[4 * q + 1] = t.y; v[4 * q + 2] = t.z; v[4 * q + 3] = t.w;
+      }
+    } else {
+#pragma unroll
+      for (int32_t j = 0; j < kScanWords; ++j) v[j] = w0 + j < n_words ? bitmap[w0 + j] : 0u;
+    }
+    int32_t pre[kScanWords], mine = 0;
+#pragma unroll
+    for (int32_t j = 0; j < kScanWords; ++j) { pre[j] = mine; mine += __popc(v[j]); }
+    int32_t incl = mine;
     for (int32_t d = 1; d < 64; d <<= 1) {
       const int32_t up = __shfl_up(incl, d, 64);
       if (lane >= d) incl += up;
@@ -66,7 +85,17 @@ __global__ void __launch_bounds__(1024) kp_scan(const uint32_t* __restrict__ bit
     __syncthreads();
     int32_t before = carry_s;
     for (int32_t k = 0; k < wv; ++k) before += wave_tot[k];
-    if (w < n_words) word_prefix[w] = before + incl - v;
+    const int32_t first = before + incl - mine;
+    if (w0 + kScanWords <= n_words) {
+#pragma unroll
+      for (int32_t q = 0; q < kScanWords / 4; ++q)
+        reinterpret_cast<int4*>(word_prefix + w0)[q] =
+            make_int4(first + pre[4 * q], first + pre[4 * q + 1], first + pre[4 * q + 2], first + pre[4 * q + 3]);
+    } else {
+#pragma unroll
+      for (int32_t j = 0; j < kScanWords; ++j)
+        if (w0 + j < n_words) word_prefix[w0 + j] = first + pre[j];
+    }
     __syncthreads();
     if (tid == 1023) carry_s = before + incl;
     __syncthreads();
@@ -96,14 +125,46 @@ struct PoolDev {
   int32_t P, mask_empty;
 };
 
+// D consecutive elements of an LDS row as floats (16-byte reads when the head width allows).
+template <typename T, int D>
+__device__ __forceinline__ void load_row(float (&dst)[D], const T* src) {
+  constexpr int EPC = 16 / (int)sizeof(T);
+  if constexpr (D % EPC == 0) {
+#pragma unroll
+    for (int c = 0; c < D / EPC; ++c) {
+      const uint4 raw = reinterpret_cast<const uint4*>(src)[c];
+      const T* e = reinterpret_cast<const T*>(&raw);
+#pragma unroll
+      for (int j = 0; j < EPC; ++j) dst[c * EPC + j] = to_f32<T>(e[j]);
+    }
+  } else {
+#pragma unroll
+    for (int j = 0; j < D; ++j) dst[j] = to_f32<T>(src[j]);
+  }
+}
+
+#ifdef DSVT_PHASE_CLOCKS
+__device__ long long g_pool_clk[16];       // shader-clock stamps of thread 0 of workgroup 0 (debug builds)
+#define DSVT_PCLK(k) do { if (blockIdx.x == 0 && threadIdx.x == 0) g_pool_clk[k] = clock64(); } while (0)
+#else
+#define DSVT_PCLK(k) do {} while (0)
+#endif
+
 template <typename T, int C> struct PoolLds {
   static constexpr int PAD = lds_pad<T>();
   static constexpr int LDX = C + PAD;
   static constexpr size_t kTile = (size_t)kRowsMax * LDX * sizeof(T);
-  static constexpr size_t kQTile = (size_t)kQRows * LDX * sizeof(T);
+  static constexpr size_t kQTile = (size_t)kRegs * LDX * sizeof(T);
+  static constexpr size_t kStat = (size_t)2 * kStatGroupsMax * kRowsMax * 4;      // LayerNorm partial sums: over Xs, dead by then
   static constexpr size_t off_x = 0, off_k = kTile, off_v = 2 * kTile, off_p = 3 * kTile, off_q = off_p + kQTile;
   static constexpr size_t off_misc = off_q + kQTile;
-  static constexpr size_t total = off_misc + (size_t)(kRowsMax + 2 * kStatGroupsMax * kRowsMax) * 4;
+  // misc: voxel of every slot, occupied slots before it (16 bit), occupied slots before every region, first
+  // region of every pass, voxel of every tile row, the bias rows b_k and b_v, per-wavefront counts
+  static constexpr size_t off_svox = off_misc, off_scum = off_svox + kSlots * 4, off_rcum = off_scum + kSlots * 2,
+                          off_pass = off_rcum + (kRegs + 1) * 4, off_rvox = off_pass + (kMaxPool + 2) * 4,
+                          off_bias = (off_rvox + kRowsMax * 4 + 15) / 16 * 16, off_wcnt = off_bias + 2 * C * sizeof(T);
+  static constexpr size_t total = off_wcnt + 16 * 4;
+  static_assert(kStat <= kTile && total <= 160 * 1024 && off_bias % 16 == 0, "pooling tile does not fit the LDS");
 };
 
 template <typename T, int C, int HEADS, int NT_KV, int NT_C>
@@ -113,70 +174,202 @@ kp_attention(PoolDev p, const int32_t* __restrict__ pool_inds, const int32_t* __
   typedef PoolLds<T, C> L;
   typedef typename Mma<T>::Vec4 Vec4;
   constexpr int LDX = L::LDX, D = C / HEADS, NW = kWaves, NTHREADS = NW * 64;
-  constexpr int CH = C * (int)sizeof(T) / 16;
+  constexpr int CH = C * (int)sizeof(T) / 16, EPC = 16 / (int)sizeof(T);     // 16-byte chunks of a row, elements per chunk
   extern __shared__ __align__(16) unsigned char smem[];
-  T* Xs = reinterpret_cast<T*>(smem + L::off_x);      // dense slot rows (holes zero)
+  T* Xs = reinterpret_cast<T*>(smem + L::off_x);      // occupied slots of the pass, one row each
   T* Ks = reinterpret_cast<T*>(smem + L::off_k);
   T* Vs = reinterpret_cast<T*>(smem + L::off_v);
   T* Ps = reinterpret_cast<T*>(smem + L::off_p);      // pooled rows: query input, residual, finally the output
   T* Qs = reinterpret_cast<T*>(smem + L::off_q);      // Q, then O
-  int32_t* row_vox = reinterpret_cast<int32_t*>(smem + L::off_misc);
-  float* stat = reinterpret_cast<float*>(row_vox + kRowsMax);
+  float* stat = reinterpret_cast<float*>(smem + L::off_x);
+  int32_t* slot_vox = reinterpret_cast<int32_t*>(smem + L::off_svox);
+  uint16_t* slot_cum = reinterpret_cast<uint16_t*>(smem + L::off_scum);
+  int32_t* reg_cum = reinterpret_cast<int32_t*>(smem + L::off_rcum);
+  int32_t* pass_first = reinterpret_cast<int32_t*>(smem + L::off_pass);
+  int32_t* row_vox = reinterpret_cast<int32_t*>(smem + L::off_rvox);
+  T* Kb = reinterpret_cast<T*>(smem + L::off_bias);   // key and value of an empty slot
+  T* Vb = Kb + C;
+  int32_t* wcnt = reinterpret_cast<int32_t*>(smem + L::off_wcnt);
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), g = lane >> 4;
   const int P = p.P;
-  const int MR = kRowsMax / P < kQRows ? kRowsMax / P : kQRows;     // regions per tile
 
-  GemmPhase<T, NT_KV, C, 2 * C, NW> kv(reinterpret_cast<const T*>(p.w_kv), wave);
-  kv.prefetch();
+  DSVT_PCLK(0);
+  // (a wavefront's loads return in order: the weights are requested after the loads whose results are needed first;
+  // the barriers wait for LDS traffic only, so none of them waits for weights still on their way)
+  GemmPhase<T, NT_C, C, C, NW, 2> qp(reinterpret_cast<const T*>(p.w_q), wave);   // C x C phases: 4 feature groups x 2 halves of the row tiles
   const int n_out = __builtin_amdgcn_readfirstlane(*n_out_ptr);
-  const int m0 = blockIdx.x * MR;
+  const int m0 = blockIdx.x * kRegs;
   if (m0 >= n_out) return;
-  const int mr = (n_out - m0) < MR ? (n_out - m0) : MR;
-  const int rows = mr * P;
-  const int RT = (rows + 15) >> 4;
+  const int mr = (n_out - m0) < kRegs ? (n_out - m0) : kRegs;
+  const int slots = mr * P;
+  const int W = kRowsMax + 1 - P;                  // a pass takes the regions whose first occupied slot number lies in one
+                                                   // run of W: together at most W - 1 + P = 96 rows
 
-  for (int r = tid; r < kRowsMax; r += NTHREADS) row_vox[r] = r < rows ? pool_inds[(size_t)m0 * P + r] : -1;
-  __syncthreads();
-  for (int idx = tid; idx < RT * 16 * CH; idx += NTHREADS) {
-    const int r = idx / CH, c = idx - r * CH;
-    const int v = row_vox[r];
-    uint4 val = make_uint4(0u, 0u, 0u, 0u);
-    if (v >= 0) val = reinterpret_cast<const uint4*>(x + (size_t)v * C)[c];
-    *reinterpret_cast<uint4*>(reinterpret_cast<unsigned char*>(Xs) + (size_t)r * LDX * sizeof(T) + c * 16) = val;
+  // ---- slots: voxel and number of occupied slots before it
+  int carry = 0;
+  for (int s0 = 0; s0 < slots; s0 += NTHREADS) {
+    const int sl = s0 + tid;
+    const int v = sl < slots ? pool_inds[(size_t)m0 * P + sl] : -1;
+    const unsigned long long occ = __ballot(v >= 0);
+    if (lane == 0) wcnt[wave] = __popcll(occ);
+    lds_barrier();
+    int before = carry;
+    for (int k = 0; k < wave; ++k) before += wcnt[k];
+    int all = carry;
+    for (int k = 0; k < NW; ++k) all += wcnt[k];
+    const int cum = before + __popcll(occ & ((1ull << lane) - 1ull));
+    if (sl < slots) { slot_vox[sl] = v; slot_cum[sl] = (uint16_t)cum; }
+    carry = all;
+    lds_barrier();
   }
-  __syncthreads();
-  // Eq. (6): channel-wise max over the region's occupied slots -> Ps (rows >= mr zero)
-  for (int idx = tid; idx < kQRows * C; idx += NTHREADS) {
-    const int mm = idx / C, c = idx - mm * C;
-    float best = -INFINITY;
-    bool any = false;
-    if (mm < mr)
-      for (int s = 0; s < P; ++s)
-        if (row_vox[mm * P + s] >= 0) { best = fmaxf(best, to_f32<T>(Xs[(mm * P + s) * LDX + c])); any = true; }
-    Ps[mm * LDX + c] = (T)(any ? best : 0.f);
-  }
-  __syncthreads();
-
-  // K, V of every slot; Q of the pooled rows
-  kv.run(Xs, LDX, RT, p.b_kv, [&](int o0, int r, f32x4 (&acc)[NT_KV], bool) {
-    const int row = 16 * r + (lane & 15);
-#pragma unroll
-    for (int nt = 0; nt < NT_KV; ++nt) {
-      const int ot = o0 + 16 * nt, o = ot + 4 * g;
-      if (ot < C) *reinterpret_cast<Vec4*>(Ks + row * LDX + o) = pack4<T>(acc[nt]);
-      else *reinterpret_cast<Vec4*>(Vs + row * LDX + (o - C)) = pack4<T>(acc[nt]);
-    }
-  });
-  GemmPhase<T, NT_C, C, C, NW> qp(reinterpret_cast<const T*>(p.w_q), wave);
+  DSVT_PCLK(1);
+  for (int c = tid; c < 2 * C; c += NTHREADS) Kb[c] = (T)p.b_kv[c];
   qp.prefetch();
-  qp.run(Ps, LDX, kQRows / 16, p.b_q, [&](int o0, int r, f32x4 (&acc)[NT_C], bool) {
-    const int row = 16 * r + (lane & 15);
+  for (int mm = tid; mm <= mr; mm += NTHREADS) {
+    const int cum = mm < mr ? slot_cum[mm * P] : carry;
+    reg_cum[mm] = cum;
+    if (mm == mr) pass_first[(slot_cum[(mr - 1) * P] / W) + 1] = mr;
+    else if (mm == 0 || slot_cum[(mm - 1) * P] / W != cum / W) pass_first[cum / W] = mm;
+  }
+  lds_barrier();
+  const int n_pass = reg_cum[mr - 1] / W + 1;
+
+  DSVT_PCLK(2);
+  for (int idx = tid; idx < kRegs * CH; idx += NTHREADS)     // pooled rows past the last region stay zero
+    if (idx / CH >= mr)
+      *reinterpret_cast<uint4*>(reinterpret_cast<unsigned char*>(Ps) + (size_t)(idx / CH) * LDX * sizeof(T) + (idx % CH) * 16) =
+          make_uint4(0u, 0u, 0u, 0u);
+  DSVT_PCLK(3);
+  GemmPhase<T, NT_KV, C, 2 * C, NW> kv(reinterpret_cast<const T*>(p.w_kv), wave);
+
+  // ---- passes: K, V of the occupied slots, then Eq. (7) per (region, head): softmax over the region's slots;
+  // O replaces the head's Q entries
+  const float scale = rsqrtf((float)D);
+  DSVT_PCLK(4);
+  for (int ps = 0; ps < n_pass; ++ps) {
+    const int ma = pass_first[ps], mb = pass_first[ps + 1];
+    const int base = reg_cum[ma], rows = reg_cum[mb] - base;
+    const int RT = (rows + 15) >> 4;
+    for (int r = rows + tid; r < RT * 16; r += NTHREADS) row_vox[r] = -1;
+    for (int sl = ma * P + tid; sl < mb * P; sl += NTHREADS) {
+      const int v = slot_vox[sl];
+      if (v >= 0) row_vox[slot_cum[sl] - base] = v;
+    }
+    lds_barrier();
+    {
+      constexpr int G = (kRowsMax * CH + NTHREADS - 1) / NTHREADS;      // gather: every load requested before the first store
+      uint4 val[G];
 #pragma unroll
-    for (int nt = 0; nt < NT_C; ++nt) *reinterpret_cast<Vec4*>(Qs + row * LDX + o0 + 16 * nt + 4 * g) = pack4<T>(acc[nt]);
-  });
-  GemmPhase<T, NT_C, C, C, NW> op(reinterpret_cast<const T*>(p.w_o), wave);
+      for (int k = 0; k < G; ++k) {
+        const int idx = tid + k * NTHREADS, r = idx / CH, c = idx - r * CH;
+        const int v = idx < RT * 16 * CH ? row_vox[r] : -1;
+        val[k] = make_uint4(0u, 0u, 0u, 0u);
+        if (v >= 0) val[k] = reinterpret_cast<const uint4*>(x + (size_t)v * C)[c];
+      }
+      if (ps == 0) kv.prefetch();
+#pragma unroll
+      for (int k = 0; k < G; ++k) {
+        const int idx = tid + k * NTHREADS, r = idx / CH, c = idx - r * CH;
+        if (idx < RT * 16 * CH)
+          *reinterpret_cast<uint4*>(reinterpret_cast<unsigned char*>(Xs) + (size_t)r * LDX * sizeof(T) + c * 16) = val[k];
+      }
+    }
+    lds_barrier();
+    DSVT_PCLK(5);
+    // Eq. (6): channel-wise max over a region's occupied slots, which are consecutive rows of the tile
+    for (int idx = tid; idx < (mb - ma) * CH; idx += NTHREADS) {
+      const int mm = ma + idx / CH, c = idx % CH;
+      const int r0 = reg_cum[mm] - base, cnt = reg_cum[mm + 1] - reg_cum[mm];
+      float best[EPC];
+#pragma unroll
+      for (int e = 0; e < EPC; ++e) best[e] = -INFINITY;
+      for (int r = r0; r < r0 + cnt; ++r) {
+        const uint4 raw = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(Xs) + (size_t)r * LDX * sizeof(T) + c * 16);
+        const T* e4 = reinterpret_cast<const T*>(&raw);
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) best[e] = fmaxf(best[e], to_f32<T>(e4[e]));
+      }
+      uint4 packed;
+      T* o4 = reinterpret_cast<T*>(&packed);
+#pragma unroll
+      for (int e = 0; e < EPC; ++e) o4[e] = (T)best[e];
+      *reinterpret_cast<uint4*>(reinterpret_cast<unsigned char*>(Ps) + (size_t)mm * LDX * sizeof(T) + c * 16) = packed;
+    }
+    kv.run(Xs, LDX, RT, p.b_kv, [&](int o0, int r, f32x4 (&acc)[NT_KV], bool) {
+      const int row = 16 * r + (lane & 15);
+#pragma unroll
+      for (int nt = 0; nt < NT_KV; ++nt) {
+        const int ot = o0 + 16 * nt, o = ot + 4 * g;
+        if (ot < C) *reinterpret_cast<Vec4*>(Ks + row * LDX + o) = pack4<T>(acc[nt]);
+        else *reinterpret_cast<Vec4*>(Vs + row * LDX + (o - C)) = pack4<T>(acc[nt]);
+      }
+    });
+    lds_barrier();
+    // Q of the pooled rows of this pass (the rows of earlier passes hold their results already)
+    qp.run(Ps, LDX, kRegs / 16, p.b_q, [&](int o0, int r, f32x4 (&acc)[NT_C], bool) {
+      const int row = 16 * r + (lane & 15);
+      if (row >= ma && row < mb) {
+#pragma unroll
+        for (int nt = 0; nt < NT_C; ++nt) *reinterpret_cast<Vec4*>(Qs + row * LDX + o0 + 16 * nt + 4 * g) = pack4<T>(acc[nt]);
+      }
+    });
+    lds_barrier();
+    DSVT_PCLK(6);
+    // Eq. (7) per (region, head): softmax over the region's slots; O replaces the head's Q entries.  The
+    // occupied slots are rows r0 .. r0 + cnt - 1; the P - cnt empty ones all have the bias vectors as key and
+    // value, so they enter as one key of that weight (or not at all when empty slots are masked).
+    for (int it = tid; it < (mb - ma) * HEADS; it += NTHREADS) {
+      const int mm = ma + it / HEADS, h = it % HEADS;
+      const int r0 = reg_cum[mm] - base, cnt = reg_cum[mm + 1] - reg_cum[mm];
+      const float holes = p.mask_empty ? 0.f : (float)(P - cnt);
+      T* q = Qs + mm * LDX + h * D;
+      float qv[D], o[D], logit[kMaxPool + 1];
+      load_row<T, D>(qv, q);
+      float mx = -INFINITY;
+#pragma unroll
+      for (int s = 0; s <= kMaxPool; ++s) {
+        logit[s] = -INFINITY;
+        const bool real = s < cnt, hole = s == kMaxPool && holes > 0.f;
+        if (real || hole) {
+          float kvv[D];
+          load_row<T, D>(kvv, real ? Ks + (r0 + s) * LDX + h * D : Kb + h * D);
+          float acc = 0.f;
+#pragma unroll
+          for (int j = 0; j < D; ++j) acc = fmaf(qv[j], kvv[j], acc);
+          logit[s] = acc * scale;
+          mx = fmaxf(mx, logit[s]);
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < D; ++j) o[j] = 0.f;
+      float sum = 0.f;
+#pragma unroll
+      for (int s = 0; s <= kMaxPool; ++s) {
+        const bool real = s < cnt, hole = s == kMaxPool && holes > 0.f;
+        if (real || hole) {
+          const float e = __expf(logit[s] - mx) * (hole ? holes : 1.f);
+          sum += e;
+          float kvv[D];
+          load_row<T, D>(kvv, real ? Vs + (r0 + s) * LDX + h * D : Vb + h * D);
+#pragma unroll
+          for (int j = 0; j < D; ++j) o[j] = fmaf(e, kvv[j], o[j]);
+        }
+      }
+      const float inv = 1.0f / sum;
+#pragma unroll
+      for (int j = 0; j < D; ++j) q[j] = (T)(o[j] * inv);
+    }
+    lds_barrier();
+  }
+
+  DSVT_PCLK(7);
+  // ---- out = LN(P + O Wo^T + bo)
+  GemmPhase<T, NT_C, C, C, NW, 2> op(reinterpret_cast<const T*>(p.w_o), wave);
   op.prefetch();
-  const int o_own = wave * 16 * NT_C;
+  constexpr int N_OG = C / (16 * NT_C), RH = kRowTiles / 2;
+  static_assert(2 * N_OG == NW && kRegs / 16 <= 2 * RH - 1, "one output-projection item per wavefront");
+  const int og_own = wave % N_OG, half = wave / N_OG;
+  const int o_own = og_own * 16 * NT_C, rt_own = half ? 2 : 0, HC = half ? kRegs / 16 - 2 : 2;
   f32x4 bo4[NT_C], ga[NT_C], be[NT_C];
 #pragma unroll
   for (int nt = 0; nt < NT_C; ++nt) {
@@ -184,61 +377,20 @@ kp_attention(PoolDev p, const int32_t* __restrict__ pool_inds, const int32_t* __
     ga[nt] = *reinterpret_cast<const f32x4*>(p.ln_g + o_own + 16 * nt + 4 * g);
     be[nt] = *reinterpret_cast<const f32x4*>(p.ln_b + o_own + 16 * nt + 4 * g);
   }
-  __syncthreads();
-
-  // Eq. (7): per (region, head) softmax over its slots; O replaces the head's Q entries
-  {
-    const float scale = rsqrtf((float)D);
-    for (int it = tid; it < mr * HEADS; it += NTHREADS) {
-      const int mm = it / HEADS, h = it - mm * HEADS;
-      T* q = Qs + mm * LDX + h * D;
-      float qv[D], logit[kMaxPool], o[D];
-#pragma unroll
-      for (int j = 0; j < D; ++j) { qv[j] = to_f32<T>(q[j]); o[j] = 0.f; }
-      float mx = -INFINITY;
-#pragma unroll
-      for (int s = 0; s < kMaxPool; ++s) {
-        logit[s] = -INFINITY;
-        if (s < P) {
-          const bool live = !p.mask_empty || row_vox[mm * P + s] >= 0;
-          const T* k = Ks + (mm * P + s) * LDX + h * D;
-          float acc = 0.f;
-#pragma unroll
-          for (int j = 0; j < D; ++j) acc = fmaf(qv[j], to_f32<T>(k[j]), acc);
-          logit[s] = live ? acc * scale : -INFINITY;
-          mx = fmaxf(mx, logit[s]);
-        }
-      }
-      float sum = 0.f;
-#pragma unroll
-      for (int s = 0; s < kMaxPool; ++s) {
-        if (s < P) {
-          const float e = __expf(logit[s] - mx);
-          sum += e;
-          const T* v = Vs + (mm * P + s) * LDX + h * D;
-#pragma unroll
-          for (int j = 0; j < D; ++j) o[j] = fmaf(e, to_f32<T>(v[j]), o[j]);
-        }
-      }
-      const float inv = 1.0f / sum;
-#pragma unroll
-      for (int j = 0; j < D; ++j) q[j] = (T)(o[j] * inv);
-    }
-  }
-  __syncthreads();
-
-  // out = LN(P + O Wo^T + bo)
-  f32x4 keep[NT_C][kRowTiles];
-  op.template run_keep<kQRows / 16>(Qs, LDX, 0, bo4, keep);
+  f32x4 keep[NT_C][RH];
+  if (HC == 1) op.template run_keep<1>(Qs, LDX, rt_own, bo4, keep);
+  else op.template run_keep<2>(Qs, LDX, rt_own, bo4, keep);
 #pragma unroll
   for (int nt = 0; nt < NT_C; ++nt)
 #pragma unroll
-    for (int r = 0; r < kQRows / 16; ++r) {
-      const Vec4 xr = *reinterpret_cast<const Vec4*>(Ps + (16 * r + (lane & 15)) * LDX + o_own + 16 * nt + 4 * g);
-      keep[nt][r] += f32x4{to_f32<T>(xr[0]), to_f32<T>(xr[1]), to_f32<T>(xr[2]), to_f32<T>(xr[3])};
-    }
-  layer_norm_tile<T, NT_C, C, kRowTiles>(keep, o_own, wave, 0, kQRows / 16, stat, ga, be, p.ln_eps, Ps, LDX);
-  __syncthreads();
+    for (int r = 0; r < RH; ++r)
+      if (r < HC) {
+        const Vec4 xr = *reinterpret_cast<const Vec4*>(Ps + (16 * (rt_own + r) + (lane & 15)) * LDX + o_own + 16 * nt + 4 * g);
+        keep[nt][r] += f32x4{to_f32<T>(xr[0]), to_f32<T>(xr[1]), to_f32<T>(xr[2]), to_f32<T>(xr[3])};
+      }
+  layer_norm_tile<T, NT_C, C, RH>(keep, o_own, og_own, rt_own, HC, stat, ga, be, p.ln_eps, Ps, LDX);
+  lds_barrier();
+  DSVT_PCLK(8);
   for (int idx = tid; idx < mr * CH; idx += NTHREADS) {
     const int r = idx / CH, c = idx - r * CH;
     reinterpret_cast<uint4*>(out + (size_t)(m0 + r) * C)[c] =
@@ -332,14 +484,19 @@ int launch_pool_attention(const dsvt_pool_cfg& c, const PoolPlan& pl, const int3
   d.b_kv = reinterpret_cast<const float*>(pk + pp.off_bkv);
   d.b_q = c.b_q; d.b_o = c.b_o; d.ln_g = c.ln_g; d.ln_b = c.ln_b; d.ln_eps = c.ln_eps;
   d.P = pl.g.P; d.mask_empty = c.mask_empty;
-  const int mr = kRowsMax / pl.g.P < kQRows ? kRowsMax / pl.g.P : kQRows;
   dsvt_prof_scope ps(DSVT_K_POOL_ATTN, st);
-  kern<<<(unsigned)dsvt_ceil_div(n_voxels, mr), kWaves * 64, lds, st>>>(d, pool_inds, n_out, reinterpret_cast<const T*>(x),
+  kern<<<(unsigned)dsvt_ceil_div(n_voxels, kRegs), kWaves * 64, lds, st>>>(d, pool_inds, n_out, reinterpret_cast<const T*>(x),
                                                                         reinterpret_cast<T*>(out));
   return DSVT_OK;
 }
 
 }  // namespace
+
+#ifdef DSVT_PHASE_CLOCKS
+extern "C" int dsvt_debug_pool_clocks(long long* host16) {
+  return hipMemcpyFromSymbol(host16, HIP_SYMBOL(g_pool_clk), 16 * sizeof(long long)) == hipSuccess ? 0 : -1;
+}
+#endif
 
 extern "C" int dsvt_pool_packed_size(const dsvt_pool_cfg* cfg, size_t* bytes) {
   if (!cfg || !bytes) return DSVT_EINVAL;
@@ -413,9 +570,9 @@ extern "C" int dsvt_attn_pool(const dsvt_pool_cfg* cfg, const int32_t* coords, c
   if (cfg->dtype == DSVT_BF16) {
     if (cfg->C == 192) rc = launch_pool_attention<bf16_t, 192, 8, 3, 3>(*cfg, pl, inds, n_out, x, out, n_voxels, st);
     else if (cfg->C == 128) rc = launch_pool_attention<bf16_t, 128, 8, 2, 2>(*cfg, pl, inds, n_out, x, out, n_voxels, st);
-    else rc = launch_pool_attention<bf16_t, 64, 4, 2, 1>(*cfg, pl, inds, n_out, x, out, n_voxels, st);
+    else rc = launch_pool_attention<bf16_t, 64, 4, 1, 1>(*cfg, pl, inds, n_out, x, out, n_voxels, st);
   } else {
-    rc = launch_pool_attention<float, 64, 4, 2, 1>(*cfg, pl, inds, n_out, x, out, n_voxels, st);
+    rc = launch_pool_attention<float, 64, 4, 1, 1>(*cfg, pl, inds, n_out, x, out, n_voxels, st);
   }
   if (rc != DSVT_OK) return rc;
   DSVT_HIP_TRY(hipGetLastError());

@@ -247,6 +247,31 @@ def test_attn_pool_parity(cid, n, pool, mask_empty):
     assert torch.all(out[m:] == 0) and torch.all(oc[m:] == 0)     # rows past n_out untouched
 
 
+@pytest.mark.parametrize("pool,fill", [((2, 2, 2), 1.0), ((2, 2, 2), 0.7), ((1, 1, 4), 1.0), ((2, 1, 1), 0.9)])
+def test_attn_pool_dense_regions(pool, fill):
+    """Regions that are (nearly) full: a workgroup's 48 regions then hold several 96-row tiles of occupied cells
+    and are processed in several passes."""
+    grid, C, heads = (16, 16, 8), 64, 4
+    rng = np.random.Generator(np.random.Philox(77))
+    cells = np.argwhere(rng.random(grid) < fill)
+    coords = np.concatenate([np.zeros((len(cells), 1), np.int64), cells], 1).astype(np.int32)
+    coords = coords[rng.permutation(len(coords))]
+    x = synth.make_features(36, len(coords), C, "f32")
+    w = synth.make_pool_weights(92, C, heads, "f32")
+    _say(f"attn_pool dense pool={pool} fill={fill} n={len(coords)}")
+    for mask_empty in (0, 1):
+        ref_c, ref = orc.attn_pool(w, coords, x, grid, pool, mask_empty)
+        pw = dsvt.PoolWeights(w, grid, pool, 1, mask_empty)
+        oc, out, n_out, status = dsvt.dsvt_attn_pool(pw, dev_coords(coords), dev_feats(x, "f32"))
+        torch.cuda.synchronize()
+        m = int(n_out.item())
+        assert int(status.item()) == 0 and m == len(ref_c)
+        assert np.array_equal(oc[:m].cpu().numpy(), ref_c)
+        err = rel_err(out[:m], ref)
+        _say(f"  mask_empty {mask_empty}: regions {m}, rel err {err:.3e}")
+        assert err < TOL["f32"]
+
+
 def test_attn_pool_then_block():
     """The pooled voxels feed a rotated layer pair on the pooled grid (window 12 x 12 x 8, tau 48)."""
     cfg = synth.CONFIGS[4]
