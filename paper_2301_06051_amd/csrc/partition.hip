@@ -20,8 +20,7 @@ struct PartGeom {
   int32_t grid[3], win[3], shift[3], nw[3];
   int32_t batch, tau;
   uint32_t magic[3];       // ceil(2^32 / win[a]) when that divides every x + shift exactly (see div_win), else 0
-  uint32_t magic_tau, magic_cut;   // the same for tau (dividends up to a window's volume + tau) and for the rows of a
-                                   // tile cut (dividends up to all padded rows), 0 when not exact; used by k_front
+  uint32_t magic_tau;      // the same for tau (dividends up to a window's volume + tau), 0 when not exact; used by k_front
   int32_t words_per_win;   // 32-bit bitmap words per window (window volume rounded up to 32)
   int32_t n_windows;       // batch * nw[0] * nw[1] * nw[2]
 };
@@ -251,6 +250,18 @@ __device__ __forceinline__ int32_t set_rows(int32_t nu) {
   return rows > kTileRows ? kTileRows : (rows < 4 ? 4 : rows);
 }
 
+// Rows between two tile cuts: at most rpc_max = 100 - pad4(tau), so that a tile never exceeds 96 rows.  A frame
+// whose tiles would not fill the GPU's compute units once gets a smaller cut, i.e. more and shorter tiles on
+// more units (measured: a 3,000-voxel frame 28 -> 22 us per layer, 8,000 voxels 29 -> 26 us).  Larger frames keep
+// rpc_max: a tile's cost is mostly fixed (weights, barriers), so more tiles per unit buy nothing there.
+constexpr int32_t kComputeUnits = 256;            // MI355X
+__device__ __forceinline__ int32_t tile_cut(int32_t total_rows, int32_t rpc_max) {
+  if (rpc_max < 16 || total_rows <= 0 || total_rows > rpc_max * kComputeUnits) return rpc_max;
+  int32_t rpc = ((total_rows + kComputeUnits - 1) / kComputeUnits + 3) & ~3;     // at most 256 tiles
+  rpc = rpc < 16 ? 16 : rpc;
+  return rpc < rpc_max ? rpc : rpc_max;
+}
+
 // Header of launch slot pos, in every axis's descriptor array.
 __device__ __forceinline__ void desc_header(const TileOut& out, int32_t pos, int32_t rows, int32_t sets) {
 #pragma unroll
@@ -322,6 +333,9 @@ __device__ __forceinline__ void build_tiles(const int32_t* set_w, const int32_t*
     if (tid == 1023) carry_s = before + incl;
     __syncthreads();
   }
+  __threadfence_block();
+  __syncthreads();
+  rows_per_cut = tile_cut(set_p[n_sets], rows_per_cut);
   // pass 2: tile boundaries.  A set starts a tile when the running row count crosses a multiple of
   // rows_per_cut between its predecessor's start and its own; tiles are numbered by counting these
   // starts (a scan), so none is empty even when one set is longer than rows_per_cut.  A tile then
@@ -513,7 +527,7 @@ __device__ __forceinline__ int32_t block_scan1(int32_t v, int32_t* wave_tot, int
 // start-up and the gaps between them are most of a partition's latency, which the first layer of a
 // frame has to wait for.)
 // Dynamic LDS, in 32-bit words: bitmaps [ax.n * n_words] | per window: voxels, first set, rows before
-// it, tiles started before it [4 * n_windows] | per tile: first set, rows before it [2 * (tile_cap + 1)],
+// it, tiles started before it, last rows before it [5 * n_windows] | per tile: first set, rows before it [2 * (tile_cap + 1)],
 // launch slot [tile_cap].
 template <int NAX>
 __global__ void __launch_bounds__(1024) k_front(Jobs jobs
@@ -530,8 +544,7 @@ __global__ void __launch_bounds__(1024) k_front(Jobs jobs
   int32_t* __restrict__ n_sets = J.n_sets;
   int32_t* __restrict__ status = J.status;
   int32_t* __restrict__ set_loc = J.set_loc;
-  const int32_t n_words = J.n_words, max_sets = J.max_sets, set_cap = J.set_cap, rows_per_cut = J.rows_per_cut,
-                tile_cap = J.tile_cap;
+  const int32_t n_words = J.n_words, max_sets = J.max_sets, set_cap = J.set_cap, tile_cap = J.tile_cap;
   extern __shared__ uint32_t smem[];
   DSVT_FCLK(0);
   __shared__ int32_t wave_tot[3][16], carry1[3], carry2[3];
@@ -543,8 +556,8 @@ __global__ void __launch_bounds__(1024) k_front(Jobs jobs
   const int32_t tile_lim = out.max_tiles < tile_cap ? out.max_tiles : tile_cap;
   uint32_t* bm = smem;
   int32_t* wN = (int32_t*)(smem + (size_t)NAX * n_words);
-  int32_t *wSoff = wN + nw, *wP0 = wSoff + nw, *wT0 = wP0 + nw;
-  int32_t *tFirst = wT0 + nw, *tRows = tFirst + tile_cap + 1, *tPos = tRows + tile_cap + 1;
+  int32_t *wSoff = wN + nw, *wP0 = wSoff + nw, *wT0 = wP0 + nw, *wPrev = wT0 + nw;
+  int32_t *tFirst = wPrev + nw, *tRows = tFirst + tile_cap + 1, *tPos = tRows + tile_cap + 1;
 
   if (!ws_ready(ax)) {                       // (k_mark has raised DSVT_ST_WS_STATE)
     if (tid == 0) {
@@ -605,32 +618,31 @@ __global__ void __launch_bounds__(1024) k_front(Jobs jobs
       win_count[w] = N;
     }
     const int32_t S = (int32_t)div_magic((uint32_t)(N + tau - 1), g.magic_tau);
-    // distinct voxels of the window's sets, 7 bits each, for the passes below (windows of more than 9 sets
-    // walk through them again instead)
     SetWalk walk(N, S, tau);
-    const bool packed = S <= 9;
-    uint64_t nu_bits = 0;
     int32_t R = 0, last_rows = 0;
-    for (int32_t j = 0; j < S; ++j) {
-      const int32_t nu = walk.next();
-      if (packed) nu_bits |= (uint64_t)nu << (7 * j);
-      last_rows = set_rows(nu);
-      R += last_rows;
-    }
+    for (int32_t j = 0; j < S; ++j) { last_rows = set_rows(walk.next()); R += last_rows; }
     Scan3 v = {S, R, S > 0 ? (w << 7) | last_rows : -1, -1};
     v = block_scan3(v, wave_tot, carry1);
-    const int32_t soff = v.a - S, P0 = v.b - R;
-    const int32_t prev = v.xm;                  // (window << 7 | rows of its last set) of the latest non-empty window before
-    int32_t F = 0;
     if (w < nw) {
-      win_soff[w] = soff;
-      wN[w] = N; wSoff[w] = soff; wP0[w] = P0;
+      win_soff[w] = v.a - S;
+      wN[w] = N; wSoff[w] = v.a - S; wP0[w] = v.b - R;
+      wPrev[w] = v.xm;                          // (window << 7 | rows of its last set) of the latest non-empty window before
     }
+  }
+  lds_barrier();
+  const int32_t rows_per_cut = tile_cut(carry1[1], J.rows_per_cut);
+
+  // ---- the tiles every window's sets start, and a scan of their number
+  for (int32_t base = 0; want_tiles && base < nw; base += 1024) {
+    const int32_t w = base + tid;
+    const int32_t N = w < nw ? wN[w] : 0, soff = w < nw ? wSoff[w] : 0, P0 = w < nw ? wP0[w] : 0, prev = w < nw ? wPrev[w] : -1;
+    const int32_t S = (int32_t)div_magic((uint32_t)(N + tau - 1), g.magic_tau);
+    SetWalk walk(N, S, tau);
     // Set s starts a tile when a multiple of rows_per_cut lies in (rows before set s - 1, rows before set s],
     // that is when (rows before set s - 1) mod rows_per_cut plus the rows of set s - 1 reach rows_per_cut.
     const int32_t prev_rows0 = prev >= 0 ? (prev & 127) : 0;
-    const int32_t d0 = P0 - prev_rows0;                       // rows before the previous set
-    const int32_t m0 = d0 - (int32_t)div_magic((uint32_t)d0, g.magic_cut) * rows_per_cut;
+    const uint32_t d0 = (uint32_t)(P0 - prev_rows0);          // rows before the previous set
+    const int32_t m0 = (int32_t)(d0 % (uint32_t)rows_per_cut);
     auto for_each_set = [&](auto&& fn) {
       int32_t P = P0, pr = prev_rows0, m = m0;
       walk.restart();
@@ -642,13 +654,14 @@ __global__ void __launch_bounds__(1024) k_front(Jobs jobs
         m += pr;
         while (m >= rows_per_cut) m -= rows_per_cut;
         fn(s, P, first);
-        pr = set_rows(packed ? (int32_t)((nu_bits >> (7 * j)) & 127u) : walk.next());
+        pr = set_rows(walk.next());
         P += pr;
       }
     };
-    if (want_tiles) for_each_set([&](int32_t, int32_t, bool first) { F += first ? 1 : 0; });
+    int32_t F = 0;
+    for_each_set([&](int32_t, int32_t, bool first) { F += first ? 1 : 0; });
     const int32_t f_incl = block_scan1(F, wave_tot[0], carry2);
-    if (want_tiles && w < nw) {
+    if (w < nw) {
       int32_t t = f_incl - F;                                 // tiles started before this window
       wT0[w] = t;
       for_each_set([&](int32_t s, int32_t P, bool first) {
@@ -882,7 +895,7 @@ int make_plan(const dsvt_part_cfg* cfg, int32_t n_voxels, PartPlan* p) {
     if (vol >= (1ll << 31) || nwin >= (1ll << 31)) return DSVT_EINVAL;
   }
   g.batch = cfg->batch; g.tau = cfg->tau;
-  g.magic_tau = g.magic_cut = 0u;
+  g.magic_tau = 0u;
   int64_t wpw = dsvt_ceil_div(vol, 32);
   if (nwin * wpw * 32 >= (1ll << 31)) return DSVT_EINVAL;   // composite keys are 32-bit
   g.words_per_win = (int32_t)wpw;
@@ -903,7 +916,7 @@ int make_plan(const dsvt_part_cfg* cfg, int32_t n_voxels, PartPlan* p) {
   // together have at most n + 4 * bound rows, and every rows_per_cut of them start at most one tile.
   const int64_t pad_tau = (cfg->tau + 3) & ~3;
   p->rows_per_cut = (int32_t)(100 - pad_tau);
-  p->tile_bound = p->rows_per_cut > 0 ? (int32_t)((n_voxels + 4 * bound) / p->rows_per_cut + 1) : 0;
+  p->tile_bound = p->rows_per_cut > 0 ? (int32_t)((n_voxels + 4 * bound) / p->rows_per_cut + 1 + kComputeUnits) : 0;   // (see tile_cut)
   p->off_tilerows = o; o = dsvt_align_up(o + (size_t)(p->tile_bound + 1) * 4, 256);
   p->off_tilepos = o;  o = dsvt_align_up(o + (size_t)(p->tile_bound + 1) * 4, 256);
   p->off_setp = o;     o = dsvt_align_up(o + (size_t)(bound + 1) * 4, 256);
@@ -988,18 +1001,15 @@ int prepare(const PartRequest& r, int32_t n_voxels, Prepared* out) {
   }
   ax.ws_token = (const uint64_t*)base;
   ax.token = ws_token(p);
-  // k_front divides by multiplying: exact for x < 2^16 and d < 2^15 (tau against a window's volume + tau),
-  // and for x < 2^25 and d <= 128 (rows of a tile cut against all padded rows)
+  // k_front divides by tau by multiplying: exact for x < 2^16 and d < 2^15 (tau against a window's volume + tau)
   const int32_t tau = r.cfg->tau;
   out->front_ok = (int64_t)p.g.words_per_win * 32 + tau < (1 << 16) && tau < (1 << 15) && tau > 1 &&
                   (int64_t)n_voxels + 4 * (int64_t)p.set_bound < (1 << 25) && p.g.n_windows < (1 << 22) &&
                   p.n_words * r.n_axes < (1 << 22) && (r.tiles == nullptr || p.rows_per_cut >= 2);
   if (out->front_ok) {
     p.g.magic_tau = (uint32_t)(((1ull << 32) + (uint64_t)tau - 1) / (uint64_t)tau);
-    const int32_t cut = p.rows_per_cut > 1 ? p.rows_per_cut : 2;
-    p.g.magic_cut = (uint32_t)(((1ull << 32) + (uint64_t)cut - 1) / (uint64_t)cut);
   }
-  out->front_lds = ((size_t)r.n_axes * p.n_words + 4 * (size_t)p.g.n_windows + 3 * (size_t)(p.tile_bound + 1)) * 4;
+  out->front_lds = ((size_t)r.n_axes * p.n_words + 5 * (size_t)p.g.n_windows + 3 * (size_t)(p.tile_bound + 1)) * 4;
   out->front_ok = out->front_ok && out->front_lds <= kFrontLds;
   J.g = p.g;
   return DSVT_OK;

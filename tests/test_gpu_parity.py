@@ -80,6 +80,29 @@ def test_partition_xy_multi_bit_exact(cid, n):
             assert_maps_equal(out[axis], orc.partition(coords, cfg["grid"], cfg["win"], sh, tau, axis))
 
 
+@pytest.mark.parametrize("n", [300, 3000, 12000, 20000])
+def test_small_frames_spread_over_the_compute_units(n):
+    """A frame whose 64-row tiles would not fill the 256 compute units once is cut into more, shorter tiles (at
+    most 256, of 16 rows or more between cuts); larger frames keep the 64-row cut.  The work list stays valid."""
+    cfg = synth.CONFIGS[2]
+    coords = synth.make_frame(2, n=n)
+    _say(f"tile spread n={len(coords)}")
+    om = orc.partition(coords, cfg["grid"], cfg["win"], (0, 0, 0), cfg["tau"], 0)
+    pair = dsvt.dsvt_partition_xy(dsvt.part_cfg(cfg["grid"], cfg["win"], (0, 0, 0), cfg["tau"], 1, 0), dev_coords(coords))
+    assert_maps_equal(pair[0], om)
+    si = om["set_inds"]
+    first = np.ones(si.shape, bool)
+    first[:, 1:] = np.diff(si, axis=1) != 0
+    rows = int(((first.sum(1) + 3) // 4 * 4).sum())
+    nt = int(pair[0].n_tiles.item())
+    _say(f"  rows {rows}, tiles {nt}")
+    if rows <= 64 * 256:
+        cut = min(max((-(-rows // 256) + 3) // 4 * 4, 16), 64)
+        assert nt <= min(256, rows // cut + 1) and nt >= 0.8 * min(256, rows // cut)
+    else:
+        assert abs(nt - rows / 64) <= 2
+
+
 def test_partition_xy_odd_geometry_and_batch():
     grid, win, shift, tau = (29, 17, 9), (5, 7, 3), (2, 6, 1), 11
     coords = np.concatenate([np.concatenate([np.full((900, 1), b), synth.frame_uniform(60 + b, grid, 900)], 1)

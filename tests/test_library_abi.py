@@ -38,7 +38,7 @@ def test_host_only_calls_work_without_a_gpu():
     cfg = b.part_cfg((468, 468, 1), (12, 12, 1), (6, 6, 0), 36, 1, 0)
     max_sets, max_tiles, ws = b.dsvt_partition_bound(cfg, 30000)
     assert max_sets == 30000 // 36 + 40 * 40 and ws > 0
-    assert max_tiles == (30000 + 4 * max_sets) // 64 + 1
+    assert max_tiles == (30000 + 4 * max_sets) // 64 + 1 + 256
     with pytest.raises(b.DsvtError):
         b.dsvt_partition_bound(b.part_cfg((468, 468, 1), (12, 12, 1), (12, 0, 0), 36, 1, 0), 30000)
     with pytest.raises(b.DsvtError):
