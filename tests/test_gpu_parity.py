@@ -155,6 +155,32 @@ def test_partition_reports_bad_input_without_faulting():
     with pytest.raises(dsvt.DsvtError) as e:
         dsvt.dsvt_partition(dsvt.part_cfg(grid, win, (12, 0, 0), tau, 1, 0), dev_coords(coords), out=gm)
     assert e.value.rc == dsvt.binding.DSVT_EINVAL
+    # host-side argument errors of the paired and the multi-configuration entry points
+    pair = dsvt.SetMapsXY(cfg, 200)
+    with pytest.raises(dsvt.DsvtError) as e:
+        dsvt.dsvt_partition_xy_multi([cfg] * 5, dev_coords(coords), [pair] * 5)
+    assert e.value.rc == dsvt.binding.DSVT_EINVAL
+    lib, C = dsvt.lib(), dsvt.binding.C
+    cd = dev_coords(coords)
+    ptr = lambda t: C.c_void_p(t.data_ptr())
+    rc = lib.dsvt_partition_xy(C.byref(cfg), ptr(cd), 200, ptr(pair.x.set_inds), ptr(pair.y.set_inds), ptr(pair.x.voxel_slot),
+                               ptr(pair.y.voxel_slot), ptr(pair.x.n_sets), pair.x.max_sets, None, None, None, ptr(pair.x.ws), 64,
+                               ptr(pair.x.status), None)
+    assert rc == dsvt.binding.DSVT_ENOSPC                          # scratch too small
+    rc = lib.dsvt_partition_xy(C.byref(cfg), ptr(cd), 200, ptr(pair.x.set_inds), None, ptr(pair.x.voxel_slot),
+                               ptr(pair.y.voxel_slot), ptr(pair.x.n_sets), pair.x.max_sets, None, None, None, ptr(pair.x.ws),
+                               pair.x.ws.numel(), ptr(pair.x.status), None)
+    assert rc == dsvt.binding.DSVT_EINVAL                          # an output of the second axis missing
+    rc = lib.dsvt_partition_xy(C.byref(cfg), ptr(cd), 200, ptr(pair.x.set_inds), ptr(pair.y.set_inds), ptr(pair.x.voxel_slot),
+                               ptr(pair.y.voxel_slot), ptr(pair.x.n_sets), pair.x.max_sets, None, C.byref(pair.x.tile_list), None,
+                               ptr(pair.x.ws), pair.x.ws.numel(), ptr(pair.x.status), None)
+    assert rc == dsvt.binding.DSVT_EINVAL                          # a work list without the second axis's descriptors
+    assert lib.dsvt_partition_ws_init(C.byref(cfg), 200, ptr(pair.x.ws), 64, None) == dsvt.binding.DSVT_ENOSPC
+    # no work list and no set_win: the maps alone
+    plain = dsvt.SetMapsXY(cfg, 200, tiles=False)
+    dsvt.dsvt_partition_xy(cfg, cd, out=plain)
+    for axis in (0, 1):
+        assert_maps_equal(plain[axis], orc.partition(coords, grid, win, (0, 0, 0), tau, axis))
     # a scratch buffer that dsvt_partition_ws_init has not prepared: no sets, and the status says why
     for maker, call in ((dsvt.SetMaps, dsvt.dsvt_partition), (dsvt.SetMapsXY, dsvt.dsvt_partition_xy)):
         raw = maker(cfg, 200)
