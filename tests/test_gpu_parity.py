@@ -546,6 +546,29 @@ def test_large_sets(C, heads, hidden, win, tau, n):
     assert err < TOL["bf16"]
 
 
+@pytest.mark.parametrize("tau", [24, 36, 48, 60])
+def test_set_size_sweep(tau):
+    """The set sizes of the paper's set-size ablation (24, 36, 48 for pillars; 36, 48, 60 for voxels) on the pillar
+    shape, maps from the paired partition call."""
+    C, heads, hidden, grid, win, n = 192, 8, 384, (144, 144, 1), (12, 12, 1), 7000
+    shift = (6, 6, 0)
+    coords = np.concatenate([np.zeros((n, 1), np.int64), synth.frame_radial(500 + tau, grid, n)], 1).astype(np.int32)
+    x = synth.make_features(501 + tau, len(coords), C, "bf16")
+    ws = [synth.make_layer_weights(502 + a, C, heads, hidden, win, "bf16") for a in (0, 1)]
+    _say(f"set size tau={tau}")
+    oms = [orc.partition(coords, grid, win, shift, tau, a) for a in (0, 1)]
+    ref = orc.block(ws, oms, coords, x)
+    cd = dev_coords(coords)
+    gms = dsvt.dsvt_partition_xy(dsvt.part_cfg(grid, win, shift, tau, 1, 0), cd)
+    for gm, om in zip(gms, oms):
+        assert_maps_equal(gm, om)
+    out = dsvt.dsvt_block([dsvt.LayerWeights(w) for w in ws], gms, cd, dev_feats(x, "bf16"))
+    torch.cuda.synchronize()
+    err = rel_err(out, ref)
+    _say(f"  sets {oms[0]['n_sets']}, rel err {err:.3e}")
+    assert err < TOL["bf16"]
+
+
 @pytest.mark.parametrize("dt,C,grid,batch,n", [("bf16", 192, (468, 468, 1), 1, 30000), ("f32", 64, (48, 48, 1), 1, 2000),
                                                ("bf16", 128, (37, 29, 3), 2, 1500)])
 def test_bev_scatter_bit_exact(dt, C, grid, batch, n):
