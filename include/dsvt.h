@@ -4,6 +4,7 @@
  *
  * Conventions for every entry point
  *   - Plain C, one shared object.  No entry point allocates, frees or keeps any pointer.
+ *     (One buffer carries state from call to call: the partition's `ws`, see dsvt_partition.)
  *   - Pointers marked [device] are device memory owned by the caller; pointers marked
  *     [host] are ordinary host memory.  Structs themselves are read on the host.
  *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the null
@@ -14,7 +15,8 @@
  *   - Return value: DSVT_OK, or a negative code for what the host can see (bad argument,
  *     unsupported shape, workspace too small, launch failure).  Nothing is enqueued when a
  *     negative code is returned.  Errors only a kernel can see (a coordinate outside the
- *     grid, a repeated coordinate, more sets than `max_sets`) OR bits into the caller's
+ *     grid, a repeated coordinate, more sets than `max_sets`, a partition buffer that was
+ *     not prepared) OR bits into the caller's
  *     [device] `status` word; outputs are then unspecified but no access leaves the
  *     caller's buffers.
  *   - Voxel coordinates are int32 rows (b, x, y, z), 0 <= b < batch, unique per call.
@@ -63,8 +65,13 @@ int dsvt_partition_bound(const dsvt_part_cfg* cfg, int32_t n_voxels, int32_t* ma
  *   tile_desc  [max_tiles][256]  per tile in launch order: [0] rows, [1] sets, [2+s] first row and
  *                                [26+s] distinct voxels of its s-th set, [64+r] voxel of row r (-1 =
  *                                padding), [160+r] (slots holding that voxel << 24) | position code
- *                                (x*(2W-1) + y)*(2H-1) + z
- * Needs tau <= 96 and grid[0]*(2W-1)*(2H-1) < 2^24. */
+ *                                (x*(2W-1) + y)*(2H-1) + z.  The arrays need no clearing: every
+ *                                entry of the first n_tiles descriptors that a kernel reads is
+ *                                written by the call; the rest keeps what it held.
+ * Needs tau <= 96, grid[0]*(2W-1)*(2H-1) < 2^24 and max_tiles of at least the bound dsvt_partition_bound
+ * reports (with fewer, the sets past the last tile get none and their voxels are not processed by a layer).
+ * Tiles hold 100 - 4*ceil(tau/4) rows on average; a frame whose tiles would not occupy the 256 compute
+ * units once is cut into more, shorter tiles. */
 typedef struct {
   int32_t max_tiles;
   int32_t *tile_first, *n_tiles, *tile_order, *tile_desc;
