@@ -291,7 +291,8 @@ __device__ __forceinline__ int32_t set_loc_code(int32_t pos, int32_t ls, int32_t
 __device__ __forceinline__ void build_tiles(const int32_t* set_w, const int32_t* win_count, const int32_t* win_soff,
                                             const int32_t* n_sets_ptr, int32_t set_cap, int32_t tau, int32_t n_windows,
                                             int32_t rows_per_cut, TileOut out, int32_t* tile_rows, int32_t* tile_pos,
-                                            int32_t* set_p, int32_t* set_loc) {
+                                            int32_t* set_p, int32_t* set_loc, int32_t fill_sets) {
+  extern __shared__ uint32_t fill_lds[];                     // filled tiles: rows before every set, two jump tables, marks
   __shared__ int32_t wave_tot[16];
   __shared__ int32_t carry_s;
   __shared__ int32_t hist[32], running[32], wave_cnt[16][32];
@@ -336,6 +337,51 @@ __device__ __forceinline__ void build_tiles(const int32_t* set_w, const int32_t*
   __threadfence_block();
   __syncthreads();
   rows_per_cut = tile_cut(set_p[n_sets], rows_per_cut);
+  // Frames of many rounds over the compute units: a tile costs a fixed amount plus its rows, so tiles are filled
+  // as far as they go -- a set starts a tile when it no longer fits the 96 rows of the one before (84 rows per tile
+  // on average instead of rows_per_cut).  The boundaries depend on each other: jump[s] = the set that starts the
+  // next tile if s starts one (a binary search over the row prefix), and the sets reachable from set 0 are found
+  // by doubling the jumps, log2(tiles) rounds over tables in LDS.
+  const bool filled = rows_per_cut >= 4 && n_sets <= fill_sets && n_sets < 65535 &&
+                      set_p[n_sets] > 4 * kComputeUnits * rows_per_cut;
+  if (filled) {
+    int32_t* P = reinterpret_cast<int32_t*>(fill_lds);                       // [fill_sets + 1]
+    uint16_t* jump = reinterpret_cast<uint16_t*>(P + fill_sets + 1);         // [2][fill_sets + 1]
+    uint16_t* jump2 = jump + fill_sets + 1;
+    uint8_t* mark = reinterpret_cast<uint8_t*>(jump2 + fill_sets + 1);       // [fill_sets + 1]
+    for (int32_t s = tid; s <= n_sets; s += 1024) { P[s] = set_p[s]; mark[s] = s == 0; }
+    __syncthreads();
+    for (int32_t s = tid; s <= n_sets; s += 1024) {
+      int32_t lo = s + 1, hi = n_sets;                       // smallest t in (s, n_sets] with P[t + 1] - P[s] > 96; n_sets = none
+      if (s < n_sets) {
+        const int32_t lim = P[s] + kTileRows;
+        while (lo < hi) {
+          const int32_t mid = (lo + hi) >> 1;
+          if (P[mid + 1] > lim) hi = mid; else lo = mid + 1;
+        }
+      } else {
+        lo = n_sets;
+      }
+      jump[s] = (uint16_t)lo;
+    }
+    __syncthreads();
+    for (int32_t round = 0; round < 17; ++round) {
+      if (jump[0] == n_sets) break;                          // (uniform) every tile start has been reached
+      for (int32_t s = tid; s < n_sets; s += 1024)
+        if (mark[s]) mark[jump[s]] = 1;                      // (mark[n_sets] is a dummy)
+      for (int32_t s = tid; s <= n_sets; s += 1024) jump2[s] = jump[jump[s]];
+      __syncthreads();
+      uint16_t* t = jump; jump = jump2; jump2 = t;
+    }
+    // the last partial round of marks
+    for (int32_t s = tid; s < n_sets; s += 1024)
+      if (mark[s]) mark[jump[s]] = 1;
+    __syncthreads();
+    for (int32_t s = tid; s < n_sets; s += 1024)
+      if (mark[s]) set_loc[s] = -2;
+  }
+  __threadfence_block();
+  __syncthreads();
   // pass 2: tile boundaries.  A set starts a tile when the running row count crosses a multiple of
   // rows_per_cut between its predecessor's start and its own; tiles are numbered by counting these
   // starts (a scan), so none is empty even when one set is longer than rows_per_cut.  A tile then
@@ -344,7 +390,8 @@ __device__ __forceinline__ void build_tiles(const int32_t* set_w, const int32_t*
   __syncthreads();
   for (int32_t base = 0; base < n_sets; base += 1024) {
     const int32_t s = base + tid;
-    const bool first = s < n_sets && (s == 0 || set_p[s - 1] / rows_per_cut != set_p[s] / rows_per_cut);
+    const bool first = s < n_sets && (filled ? set_loc[s] == -2
+                                             : (s == 0 || set_p[s - 1] / rows_per_cut != set_p[s] / rows_per_cut));
     int32_t incl = first ? 1 : 0;
     for (int32_t d = 1; d < 64; d <<= 1) {
       int32_t up = __shfl_up(incl, d, 64);
@@ -435,9 +482,9 @@ __device__ __forceinline__ void build_tiles(const int32_t* set_w, const int32_t*
 __global__ void __launch_bounds__(1024) k_tiles(const int32_t* set_w, const int32_t* win_count, const int32_t* win_soff,
                                                 const int32_t* n_sets_ptr, int32_t set_cap, int32_t tau, int32_t n_windows,
                                                 int32_t rows_per_cut, TileOut out, int32_t* tile_rows, int32_t* tile_pos,
-                                                int32_t* set_p, int32_t* set_loc) {
+                                                int32_t* set_p, int32_t* set_loc, int32_t fill_sets) {
   build_tiles(set_w, win_count, win_soff, n_sets_ptr, set_cap, tau, n_windows, rows_per_cut, out, tile_rows, tile_pos, set_p,
-              set_loc);
+              set_loc, fill_sets);
 }
 
 #ifdef DSVT_PHASE_CLOCKS
@@ -1079,9 +1126,18 @@ int run_partitions(const PartRequest* reqs, int32_t n, const int32_t* coords, in
       }
       if (P.want_tiles) {
         dsvt_prof_scope ps(DSVT_K_PART_TILES, st);
-        k_tiles<<<1, 1024, 0, st>>>((const int32_t*)(base + p.off_setwin), J.win_count, J.win_soff, J.n_sets, J.set_cap,
+        // tables of the tile filling (see build_tiles), when this frame's sets fit the LDS
+        const size_t fill_lds = ((size_t)p.set_bound + 1) * 9 + 16;
+        const bool fill_ok = fill_lds <= kFrontLds;
+        static bool tiles_lds_raised = false;                  // (the same value every time: a benign race)
+        if (fill_ok && !tiles_lds_raised) {
+          DSVT_HIP_TRY(hipFuncSetAttribute((const void*)k_tiles, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFrontLds));
+          tiles_lds_raised = true;
+        }
+        k_tiles<<<1, 1024, fill_ok ? fill_lds : 0, st>>>((const int32_t*)(base + p.off_setwin), J.win_count, J.win_soff, J.n_sets, J.set_cap,
                                     p.g.tau, p.g.n_windows, p.rows_per_cut, J.out, (int32_t*)(base + p.off_tilerows),
-                                    (int32_t*)(base + p.off_tilepos), (int32_t*)(base + p.off_setp), J.set_loc);
+                                    (int32_t*)(base + p.off_tilepos), (int32_t*)(base + p.off_setp), J.set_loc,
+                                    fill_ok ? p.set_bound : 0);
       }
     }
     {
