@@ -842,13 +842,15 @@ __global__ void k_emit(Jobs jobs, const int4* __restrict__ coords, int32_t n, in
   int32_t* __restrict__ tile_desc = me.tile_desc;
   if ((int32_t)blockIdx.x >= vox_blocks) {
     if (tile_desc == nullptr || !ws_ready(ax)) return;
+    // 16 threads per descriptor share the rows past the tile's last
     const int32_t idx = ((int32_t)blockIdx.x - vox_blocks) * blockDim.x + threadIdx.x;
-    const int32_t pos = idx / kTileRows, r = idx - pos * kTileRows;
+    const int32_t pos = idx >> 4, part = idx & 15;
     int32_t nt = *n_tiles;
     nt = nt < n_desc_slots ? nt : n_desc_slots;
     if (pos >= nt) return;
     int32_t* dd = tile_desc + (int64_t)pos * kDescInts;
-    if (r >= dd[0]) { dd[kDescVox + r] = -1; dd[kDescLin + r] = -1; }
+    const int32_t rows = dd[0];
+    for (int32_t r = rows + part; r < kTileRows; r += 16) { dd[kDescVox + r] = -1; dd[kDescLin + r] = -1; }
     return;
   }
   int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -1142,7 +1144,7 @@ int run_partitions(const PartRequest* reqs, int32_t n, const int32_t* coords, in
     }
     {
       dsvt_prof_scope ps(DSVT_K_PART_EMIT, st);
-      const int32_t tail_blocks = (int32_t)dsvt_ceil_div((int64_t)max_tiles * kTileRows, tb);
+      const int32_t tail_blocks = (int32_t)dsvt_ceil_div((int64_t)max_tiles * 16, tb);
       k_emit<<<dim3((unsigned)(vox_blocks + tail_blocks), n_axes, nq), tb, 0, st>>>(jobs, (const int4*)coords, n_voxels, vox_blocks);
     }
   }
