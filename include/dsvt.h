@@ -91,7 +91,8 @@ typedef struct {
  * ws         [device] at least the bytes dsvt_partition_bound reports, prepared by dsvt_partition_ws_init.
  *            Not plain scratch: part of it is an occupancy bitmap that every call finds zero and leaves
  *            zero (clearing it per call would put one more launch in front of every frame), so the
- *            buffer must stay untouched between calls; calls that share a ws must not overlap.  A
+ *            buffer must stay untouched between calls; calls that share a ws must not overlap
+ *            (n_voxels may change from call to call, up to the count the buffer was sized for).  A
  *            call on a ws that was not prepared for this geometry marks nothing, reports *n_sets = 0
  *            and sets DSVT_ST_WS_STATE in *status.
  * status     [device] int32 word, OR-ed with DSVT_ST_* bits (the caller zeroes it)

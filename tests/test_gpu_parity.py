@@ -103,6 +103,38 @@ def test_small_frames_spread_over_the_compute_units(n):
         assert abs(nt - rows / 64) <= 2
 
 
+def test_partition_buffers_reused_across_frame_sizes():
+    """A stream of frames with different voxel counts through one set of buffers (sized for the largest): the
+    scratch buffer's bitmap is left clean by every call whatever the frame's size."""
+    cfg = synth.CONFIGS[2]
+    grid, win, tau, shift = cfg["grid"], cfg["win"], cfg["tau"], (6, 6, 0)
+    pc = dsvt.part_cfg(grid, win, shift, tau, 1, 0)
+    cap = 30000
+    pair = dsvt.SetMapsXY(pc, cap)
+    lib, C = dsvt.lib(), dsvt.binding.C
+    ptr = lambda t: C.c_void_p(t.data_ptr())
+    for n in (30000, 9000, 21000, 500):
+        coords = synth.make_frame(2, n=n)
+        _say(f"partition_xy stream n={len(coords)}")
+        cd = dev_coords(coords)
+        for m in (pair.x, pair.y):
+            m.set_inds.fill_(-1)
+        rc = lib.dsvt_partition_xy(C.byref(pc), ptr(cd), len(coords), ptr(pair.x.set_inds), ptr(pair.y.set_inds),
+                                   ptr(pair.x.voxel_slot), ptr(pair.y.voxel_slot), ptr(pair.x.n_sets), pair.x.max_sets,
+                                   ptr(pair.x.set_win), C.byref(pair.x.tile_list), ptr(pair.y.tile_desc), ptr(pair.x.ws),
+                                   pair.x.ws.numel(), ptr(pair.x.status), None)
+        assert rc == 0
+        torch.cuda.synchronize()
+        assert int(pair.x.status.item()) == 0
+        for axis in (0, 1):
+            om = orc.partition(coords, grid, win, shift, tau, axis)
+            k = int(pair[axis].n_sets.item())
+            assert k == om["n_sets"]
+            assert np.array_equal(pair[axis].set_inds[:k].cpu().numpy(), om["set_inds"])
+            assert np.array_equal(pair[axis].voxel_slot[:len(coords)].cpu().numpy(), om["voxel_slot"])
+            assert_tiles_valid(pair[axis], om)
+
+
 def test_partition_xy_odd_geometry_and_batch():
     grid, win, shift, tau = (29, 17, 9), (5, 7, 3), (2, 6, 1), 11
     coords = np.concatenate([np.concatenate([np.full((900, 1), b), synth.frame_uniform(60 + b, grid, 900)], 1)
