@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stddef.h>
 #include <stdint.h>
+#include <atomic>
+
 #include "dsvt.h"
 
 #define DSVT_HIP_TRY(expr)                    \
@@ -12,6 +14,18 @@
       return DSVT_EHIP;                       \
     }                                         \
   } while (0)
+
+// Lets `kernel` ask for `bytes` of dynamic LDS (more than the 64 KB default), once per device: `done` holds one
+// bit per device id.  Called on every launch path; after the first time it is one atomic load.
+inline int dsvt_allow_lds(const void* kernel, size_t bytes, std::atomic<uint64_t>& done) {
+  int dev = 0;
+  DSVT_HIP_TRY(hipGetDevice(&dev));
+  const uint64_t bit = 1ull << (dev & 63);
+  if (done.load(std::memory_order_acquire) & bit) return DSVT_OK;
+  DSVT_HIP_TRY(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
+  done.fetch_or(bit, std::memory_order_release);
+  return DSVT_OK;
+}
 
 static inline size_t dsvt_align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 static inline int64_t dsvt_ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }

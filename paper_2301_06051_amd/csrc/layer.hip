@@ -656,19 +656,13 @@ int check_maps(const dsvt_maps& mp) {
   return DSVT_OK;
 }
 
-template <typename K> int allow_lds(K kernel, size_t bytes) {
-  DSVT_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                   (int)bytes));
-  return DSVT_OK;
-}
-
 template <typename T, int C, int HEADS, int HID, int NT_QKV, int NT_O, int NT_1, int NT_2, bool BIG>
 int launch_layer_v(const dsvt_layer_w& w, const dsvt_maps& mp, const int32_t* coords, const void* x, void* out, int full,
                    hipStream_t st) {
   auto kern = k_layer<T, C, HEADS, HID, NT_QKV, NT_O, NT_1, NT_2, BIG>;
   constexpr size_t lds = LayerLds<T, C, HEADS, HID>::total;
-  static int prepared = allow_lds(kern, lds);
-  if (prepared != DSVT_OK) return prepared;
+  static std::atomic<uint64_t> lds_allowed{0};
+  if (int rc = dsvt_allow_lds(reinterpret_cast<const void*>(kern), lds, lds_allowed)) return rc;
   MapsDev md;
   md.set_inds = mp.set_inds; md.n_sets = mp.n_sets; md.n_tiles = mp.tiles.n_tiles; md.tile_desc = mp.tiles.tile_desc;
   md.max_sets = mp.max_sets; md.tau = mp.tau; md.n_voxels = mp.n_voxels;

@@ -1095,14 +1095,10 @@ int run_partitions(const PartRequest* reqs, int32_t n, const int32_t* coords, in
       k_mark<<<dim3((unsigned)vox_blocks, nq), tb, 0, st>>>(jobs, (const int4*)coords, n_voxels);
     }
     if (all_front) {
-      static bool lds_raised = false;                        // (the same value every time: a benign race)
-      if (!lds_raised) {
-        DSVT_HIP_TRY(hipFuncSetAttribute((const void*)k_front<1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFrontLds));
-        DSVT_HIP_TRY(hipFuncSetAttribute((const void*)k_front<2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFrontLds));
-        lds_raised = true;
-      }
-      dsvt_prof_scope ps(DSVT_K_PART_TILES, st);
+      static std::atomic<uint64_t> front_allowed[2];
       auto* front = n_axes == 2 ? k_front<2> : k_front<1>;
+      if (int rc = dsvt_allow_lds((const void*)front, kFrontLds, front_allowed[n_axes - 1])) return rc;
+      dsvt_prof_scope ps(DSVT_K_PART_TILES, st);
       front<<<nq, 1024, lds, st>>>(jobs
 #ifdef DSVT_PHASE_CLOCKS
                                    , g_front_clocks
@@ -1131,11 +1127,9 @@ int run_partitions(const PartRequest* reqs, int32_t n, const int32_t* coords, in
         // tables of the tile filling (see build_tiles), when this frame's sets fit the LDS
         const size_t fill_lds = ((size_t)p.set_bound + 1) * 9 + 16;
         const bool fill_ok = fill_lds <= kFrontLds;
-        static bool tiles_lds_raised = false;                  // (the same value every time: a benign race)
-        if (fill_ok && !tiles_lds_raised) {
-          DSVT_HIP_TRY(hipFuncSetAttribute((const void*)k_tiles, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFrontLds));
-          tiles_lds_raised = true;
-        }
+        static std::atomic<uint64_t> tiles_allowed{0};
+        if (fill_ok)
+          if (int rc = dsvt_allow_lds((const void*)k_tiles, kFrontLds, tiles_allowed)) return rc;
         k_tiles<<<1, 1024, fill_ok ? fill_lds : 0, st>>>((const int32_t*)(base + p.off_setwin), J.win_count, J.win_soff, J.n_sets, J.set_cap,
                                     p.g.tau, p.g.n_windows, p.rows_per_cut, J.out, (int32_t*)(base + p.off_tilerows),
                                     (int32_t*)(base + p.off_tilepos), (int32_t*)(base + p.off_setp), J.set_loc,

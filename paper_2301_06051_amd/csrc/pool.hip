@@ -464,19 +464,13 @@ template <typename T> void pack_matrix(const void* src, void* dst, int out, int 
   k_pack<T><<<(unsigned)dsvt_ceil_div(slots, 256), 256, 0, st>>>(reinterpret_cast<const T*>(src), reinterpret_cast<T*>(dst), out, k);
 }
 
-template <typename K> int allow_lds(K kernel, size_t bytes) {
-  DSVT_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                   (int)bytes));
-  return DSVT_OK;
-}
-
 template <typename T, int C, int HEADS, int NT_KV, int NT_C>
 int launch_pool_attention(const dsvt_pool_cfg& c, const PoolPlan& pl, const int32_t* pool_inds, const int32_t* n_out,
                           const void* x, void* out, int32_t n_voxels, hipStream_t st) {
   auto kern = kp_attention<T, C, HEADS, NT_KV, NT_C>;
   constexpr size_t lds = PoolLds<T, C>::total;
-  static int prepared = allow_lds(kern, lds);
-  if (prepared != DSVT_OK) return prepared;
+  static std::atomic<uint64_t> lds_allowed{0};
+  if (int rc = dsvt_allow_lds(reinterpret_cast<const void*>(kern), lds, lds_allowed)) return rc;
   const PoolPacked pp = pool_packed(c);
   const char* pk = reinterpret_cast<const char*>(c.packed);
   PoolDev d;
