@@ -68,11 +68,7 @@ struct LayerDev {
 long long* g_phase_clocks = nullptr;
 #define DSVT_CLK(k) do { if (p.clk && threadIdx.x == 0) p.clk[blockIdx.x * 64 + (k)] = clock64(); } while (0)
 #else
-#ifdef DSVT_STOP
-#define DSVT_CLK(k) do { if ((k) == DSVT_STOP) return; } while (0)
-#else
 #define DSVT_CLK(k) do {} while (0)
-#endif
 #endif
 
 struct MapsDev {

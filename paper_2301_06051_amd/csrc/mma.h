@@ -11,9 +11,6 @@
 // the B operand of the next contraction without a transpose.
 #pragma once
 #include <hip/hip_runtime.h>
-#ifndef DSVT_EXP
-#define DSVT_EXP 0   // timing experiments of debug builds: 1 = GEMM phases without epilogues, 2 = without MFMAs
-#endif
 #include <stdint.h>
 
 typedef __bf16 bf16_t;
@@ -251,25 +248,13 @@ struct GemmPhase {
           f32x4 acc0[NT], acc1[NT];              // the bias is the accumulators' initial value
 #pragma unroll
           for (int nt = 0; nt < NT; ++nt) { acc0[nt] = b4[nt]; acc1[nt] = b4[nt]; }
-#if DSVT_EXP != 2
           if (sw) mma_row_swapped<T, NT, NKF>(acc0, A, b0); else mma_row<T, NT, NKF>(acc0, A, b0);
-#else
-          for (int nt = 0; nt < NT; ++nt) acc0[nt] += f32x4{(float)b0.f[0][0], (float)b0.f[1][0], (float)A.f[0][nt][0], 0.f};
-#endif
           if (two) {
             if (r + 2 < cnt) load_b<T, NKF>(b0, Xs, ldx, rt0 + r + 2);
-#if DSVT_EXP != 2
             if (sw) mma_row_swapped<T, NT, NKF>(acc1, A, b1); else mma_row<T, NT, NKF>(acc1, A, b1);
-#else
-            for (int nt = 0; nt < NT; ++nt) acc1[nt] += f32x4{(float)b1.f[0][0], (float)b1.f[1][0], (float)A.f[1][nt][0], 0.f};
-#endif
           }
-#if DSVT_EXP != 1
           epi(og * 16 * NT, rt0 + r, acc0, sw);
           if (two) epi(og * 16 * NT, rt0 + r + 1, acc1, sw);
-#else
-          if (acc0[0][0] == 12345.678f || (two && acc1[0][0] == 12345.678f)) epi(og * 16 * NT, rt0 + r, acc0, sw);
-#endif
         }
       }
       if (!DOUBLE_A && it + 1 < IPW && item + NW < N_ITEMS) load_a<T, NT, NKF>(a[0], Wp, ((item + NW) % N_OG) * NT);
