@@ -273,20 +273,51 @@ def test_block_parity(cid, n, tiles):
     assert again.data_ptr() == xd.data_ptr() and torch.equal(again, out)
 
 
-def test_stack_parity_full_pillar_frame():
-    """The benchmark workload: 30,000-pillar frame, 4 blocks x 2 layers, windows shifted on odd blocks."""
+@pytest.mark.parametrize("launch", ["eager", "hip_graph"])
+def test_stack_parity_full_pillar_frame(launch):
+    """The benchmark workload in the launch configuration the benchmark times: 30,000-pillar frame, both window
+    shifts partitioned by one call, 4 blocks x 2 layers on one stream, eagerly and as a replayed HIP graph."""
     cfg, coords, x, _, _ = _layer_case(2, None, 33)
     ws = [[synth.make_layer_weights(200 + 2 * b + a, cfg["C"], cfg["heads"], cfg["hidden"], cfg["win"], cfg["dtype"])
            for a in (0, 1)] for b in range(cfg["blocks"])]
-    _say("stack cfg2 full frame")
+    _say(f"stack cfg2 full frame, {launch}")
     ref = orc.stack(ws, coords, x, cfg["grid"], cfg["win"], cfg["shifts"], cfg["tau"])
     cd = dev_coords(coords)
-    maps = {sh: [gpu_maps(cd, cfg["grid"], cfg["win"], sh, cfg["tau"], 1, a) for a in (0, 1)] for sh in cfg["shifts"]}
-    xd = dev_feats(x, cfg["dtype"])
-    for b, pair in enumerate(ws):
-        xd = dsvt.dsvt_block([dsvt.LayerWeights(w) for w in pair], maps[cfg["shifts"][b % 2]], cd, xd)
+    shifts = list(cfg["shifts"])
+    pcs = [dsvt.part_cfg(cfg["grid"], cfg["win"], sh, cfg["tau"], 1, 0) for sh in shifts]
+    maps = [dsvt.SetMapsXY(pc, len(coords)) for pc in pcs]
+    layers = [[dsvt.LayerWeights(w) for w in pair] for pair in ws]
+    x0 = dev_feats(x, cfg["dtype"])
+    buf = torch.empty_like(x0)
+    wsb = torch.empty((max(dsvt.dsvt_block_workspace_size(layers[0][0], len(coords)), 1),), dtype=torch.uint8, device="cuda")
+
+    def step():
+        dsvt.dsvt_partition_xy_multi(pcs, cd, maps)
+        src = x0
+        for b, pair in enumerate(layers):
+            dsvt.dsvt_block(pair, maps[b % len(shifts)], cd, src, x_out=buf, ws=wsb)
+            src = buf
+
+    if launch == "eager":
+        step()
+    else:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        for _ in range(3):
+            buf.zero_()
+            graph.replay()
     torch.cuda.synchronize()
-    err = rel_err(xd, ref)
+    for m, sh in zip(maps, shifts):
+        for axis in (0, 1):
+            assert_maps_equal(m[axis], orc.partition(coords, cfg["grid"], cfg["win"], sh, cfg["tau"], axis))
+    err = rel_err(buf, ref)
     _say(f"  rel err after 8 layers {err:.3e}")
     assert err < TOL["bf16"]
 
