@@ -171,6 +171,93 @@ __global__ void __launch_bounds__(1024) k_scan_windows(const int32_t* __restrict
 //   [64 + r] voxel of row r, -1 for padding rows  [160 + r] (multiplicity << 24) | position code of row r
 constexpr int kDescInts = 256, kDescSets = 24, kDescR0 = 2, kDescNu = 2 + kDescSets, kDescVox = 64, kDescLin = 160;
 constexpr int kTileRows = 96;
+constexpr int32_t kComputeUnits = 256;            // MI355X
+
+// Workgroup barrier that waits for this wavefront's LDS traffic only.  __syncthreads() also waits for its
+// outstanding stores to memory (a microsecond each time); the kernels that use it never read back what they wrote there.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+// Filled tiles: a set starts a tile when it no longer fits the `cap` (at most 96) rows of the tile before.  These boundaries depend
+// on each other, so: jump[s] = the set that starts the next tile if s starts one (a binary search over P, the rows
+// before every set), and the sets reachable from set 0 are marked by doubling the jumps, log2(tiles) rounds.
+// All in LDS, 1,024 threads; P[0 .. n_sets] is ready on entry, mark[s] = 1 for the tile starts on return.
+__device__ __forceinline__ void fill_tile_starts(const int32_t* P, uint16_t* jump, uint16_t* jump2, uint8_t* mark,
+                                                 int32_t n_sets, int32_t cap) {
+  const int32_t tid = threadIdx.x;
+  for (int32_t s = tid; s <= n_sets; s += 1024) {
+    int32_t lo = s + 1, hi = n_sets;                         // smallest t in (s, n_sets] with P[t + 1] - P[s] > cap; n_sets = none
+    if (s < n_sets) {
+      const int32_t lim = P[s] + cap;                         // (a set has at most 96 rows; one longer than cap gets a tile of its own)
+      while (lo < hi) {
+        const int32_t mid = (lo + hi) >> 1;
+        if (P[mid + 1] > lim) hi = mid; else lo = mid + 1;
+      }
+    } else {
+      lo = n_sets;
+    }
+    jump[s] = (uint16_t)lo;
+    mark[s] = s == 0;
+  }
+  lds_barrier();
+  for (int32_t round = 0; round < 17; ++round) {
+    if (jump[0] == n_sets) break;                            // (uniform) every tile start has been reached
+    for (int32_t s = tid; s < n_sets; s += 1024)
+      if (mark[s]) mark[jump[s]] = 1;                        // (mark[n_sets] is a dummy)
+    for (int32_t s = tid; s <= n_sets; s += 1024) jump2[s] = jump[jump[s]];
+    lds_barrier();
+    uint16_t* t = jump; jump = jump2; jump2 = t;
+  }
+  for (int32_t s = tid; s < n_sets; s += 1024)               // the last, partial round of marks
+    if (mark[s]) mark[jump[s]] = 1;
+  lds_barrier();
+}
+
+// Whether a frame's tiles are filled rather than cut every rpc_max rows, and if so their starts (mark[], as
+// fill_tile_starts leaves them).  A tile filled up to `cap` rows holds about cap - (mean set rows) / 2.  Filling pays
+// when it saves a whole round over the compute units, or when the frame takes more than two rounds anyway.  A frame
+// of a few rounds gets the capacity that puts its tile count just under a whole number of rounds (a last round of a
+// few full-size tiles costs as much as a full round); should the count still come out above it, the next number of
+// rounds is tried.  Frames of more than four rounds get the whole 96 rows (measured at seven rounds: fewer, fuller
+// tiles beat a full last round, 167 against 185 us per layer).  Same arguments as fill_tile_starts; every thread returns
+// the same answer.
+constexpr int32_t kTunedRounds = 4;
+__device__ __forceinline__ bool fill_wanted(int32_t total_rows, int32_t n_sets, int32_t rpc_max) {   // fill_tiles' first test
+  if (n_sets <= 0 || rpc_max < 4) return false;
+  const int32_t rounds_cut = (total_rows + kComputeUnits * rpc_max - 1) / (kComputeUnits * rpc_max);
+  const int32_t rounds = (int32_t)ceilf((float)total_rows / (256.f * ((float)kTileRows - 0.5f * (float)total_rows / (float)n_sets)));
+  return rounds_cut > 1 && (rounds < rounds_cut || rounds_cut > 2);
+}
+__device__ __forceinline__ bool fill_tiles(const int32_t* P, uint16_t* jump, uint16_t* jump2, uint8_t* mark, int32_t n_sets,
+                                           int32_t rpc_max) {
+  __shared__ int32_t n_starts;
+  if (n_sets <= 0 || rpc_max < 4) return false;
+  const int32_t total_rows = P[n_sets];
+  const float half_set = 0.5f * (float)total_rows / (float)n_sets;
+  const float best_fill = (float)kTileRows - half_set;
+  const int32_t rounds_cut = (total_rows + kComputeUnits * rpc_max - 1) / (kComputeUnits * rpc_max);
+  int32_t rounds = (int32_t)ceilf((float)total_rows / (256.f * best_fill));
+  if (rounds_cut <= 1) return false;                         // (tile_cut spreads frames of less than a round)
+  for (int32_t attempt = 0; attempt < 2; ++attempt, ++rounds) {
+    if (!(rounds < rounds_cut || rounds_cut > 2)) return false;
+    int32_t cap = kTileRows;
+    if (rounds <= kTunedRounds) {
+      const float fill = (float)total_rows / (0.97f * 256.f * (float)rounds);
+      const int32_t c = ((int32_t)ceilf(fill + half_set) + 3) & ~3;
+      cap = c > kTileRows ? kTileRows : c;
+    }
+    if (threadIdx.x == 0) n_starts = 0;
+    fill_tile_starts(P, jump, jump2, mark, n_sets, cap);      // (barriers inside: n_starts is zero for everybody after)
+    if (rounds > kTunedRounds) return true;
+    int32_t mine = 0;
+    for (int32_t s = threadIdx.x; s < n_sets; s += 1024) mine += mark[s];
+    if (mine) atomicAdd(&n_starts, mine);
+    lds_barrier();
+    const int32_t tiles = n_starts;
+    lds_barrier();
+    if (tiles <= rounds * kComputeUnits) return true;
+  }
+  return false;
+}
 
 // Distinct voxels of the j-th set of a window with N voxels in S sets (closed form from Eq. 3).
 __device__ __forceinline__ int32_t set_distinct(int64_t N, int64_t S, int64_t j, int64_t tau) {
@@ -219,6 +306,7 @@ struct Job {
   TileOut out;
   int32_t *win_count, *win_soff, *n_sets, *status, *set_win, *set_loc;
   int32_t n_words, max_sets, set_cap, rows_per_cut, tile_cap;
+  int32_t fill_sets;                         // k_front: sets its LDS has tables for (filled tiles), 0 = none
 };
 constexpr int32_t kMaxJobs = 4;
 struct Jobs { Job j[kMaxJobs]; };
@@ -254,7 +342,6 @@ __device__ __forceinline__ int32_t set_rows(int32_t nu) {
 // whose tiles would not fill the GPU's compute units once gets a smaller cut, i.e. more and shorter tiles on
 // more units (measured: a 3,000-voxel frame 28 -> 22 us per layer, 8,000 voxels 29 -> 26 us).  Larger frames keep
 // rpc_max: a tile's cost is mostly fixed (weights, barriers), so more tiles per unit buy nothing there.
-constexpr int32_t kComputeUnits = 256;            // MI355X
 __device__ __forceinline__ int32_t tile_cut(int32_t total_rows, int32_t rpc_max) {
   if (rpc_max < 16 || total_rows <= 0 || total_rows > rpc_max * kComputeUnits) return rpc_max;
   int32_t rpc = ((total_rows + kComputeUnits - 1) / kComputeUnits + 3) & ~3;     // at most 256 tiles
@@ -338,47 +425,19 @@ __device__ __forceinline__ void build_tiles(const int32_t* set_w, const int32_t*
   __syncthreads();
   rows_per_cut = tile_cut(set_p[n_sets], rows_per_cut);
   // Frames of many rounds over the compute units: a tile costs a fixed amount plus its rows, so tiles are filled
-  // as far as they go -- a set starts a tile when it no longer fits the 96 rows of the one before (84 rows per tile
-  // on average instead of rows_per_cut).  The boundaries depend on each other: jump[s] = the set that starts the
-  // next tile if s starts one (a binary search over the row prefix), and the sets reachable from set 0 are found
-  // by doubling the jumps, log2(tiles) rounds over tables in LDS.
-  const bool filled = rows_per_cut >= 4 && n_sets <= fill_sets && n_sets < 65535 &&
-                      set_p[n_sets] > 4 * kComputeUnits * rows_per_cut;
-  if (filled) {
+  // as far as they go (84 rows per tile on average instead of rows_per_cut), see fill_tile_starts.
+  bool filled = false;
+  if (n_sets <= fill_sets && n_sets < 65535 && fill_wanted(set_p[n_sets], n_sets, rows_per_cut)) {
     int32_t* P = reinterpret_cast<int32_t*>(fill_lds);                       // [fill_sets + 1]
     uint16_t* jump = reinterpret_cast<uint16_t*>(P + fill_sets + 1);         // [2][fill_sets + 1]
     uint16_t* jump2 = jump + fill_sets + 1;
     uint8_t* mark = reinterpret_cast<uint8_t*>(jump2 + fill_sets + 1);       // [fill_sets + 1]
-    for (int32_t s = tid; s <= n_sets; s += 1024) { P[s] = set_p[s]; mark[s] = s == 0; }
+    for (int32_t s = tid; s <= n_sets; s += 1024) P[s] = set_p[s];
     __syncthreads();
-    for (int32_t s = tid; s <= n_sets; s += 1024) {
-      int32_t lo = s + 1, hi = n_sets;                       // smallest t in (s, n_sets] with P[t + 1] - P[s] > 96; n_sets = none
-      if (s < n_sets) {
-        const int32_t lim = P[s] + kTileRows;
-        while (lo < hi) {
-          const int32_t mid = (lo + hi) >> 1;
-          if (P[mid + 1] > lim) hi = mid; else lo = mid + 1;
-        }
-      } else {
-        lo = n_sets;
-      }
-      jump[s] = (uint16_t)lo;
-    }
-    __syncthreads();
-    for (int32_t round = 0; round < 17; ++round) {
-      if (jump[0] == n_sets) break;                          // (uniform) every tile start has been reached
+    filled = fill_tiles(P, jump, jump2, mark, n_sets, rows_per_cut);
+    if (filled)
       for (int32_t s = tid; s < n_sets; s += 1024)
-        if (mark[s]) mark[jump[s]] = 1;                      // (mark[n_sets] is a dummy)
-      for (int32_t s = tid; s <= n_sets; s += 1024) jump2[s] = jump[jump[s]];
-      __syncthreads();
-      uint16_t* t = jump; jump = jump2; jump2 = t;
-    }
-    // the last partial round of marks
-    for (int32_t s = tid; s < n_sets; s += 1024)
-      if (mark[s]) mark[jump[s]] = 1;
-    __syncthreads();
-    for (int32_t s = tid; s < n_sets; s += 1024)
-      if (mark[s]) set_loc[s] = -2;
+        if (mark[s]) set_loc[s] = -2;
   }
   __threadfence_block();
   __syncthreads();
@@ -497,10 +556,6 @@ long long* g_front_clocks = nullptr;       // [16] shader-clock stamps of thread
 // Scan over the 1024 threads of a workgroup, continued from one call to the next through `carry`:
 // inclusive sums of a and b, and in xm the maximum of m over the threads before this one (and over
 // earlier calls).  Every thread of the workgroup calls it; two barriers inside.
-// Workgroup barrier that waits for this wavefront's LDS traffic only.  __syncthreads() also waits for its
-// outstanding stores to memory (a microsecond each time); k_front never reads back what it wrote there.
-__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
-
 template <int CTRL, int ROW_MASK>
 __device__ __forceinline__ int32_t dpp_or(int32_t identity, int32_t v) {       // v of the lane CTRL names, identity where there is none
   return __builtin_amdgcn_update_dpp(identity, v, CTRL, ROW_MASK, 0xF, false);
@@ -575,7 +630,7 @@ __device__ __forceinline__ int32_t block_scan1(int32_t v, int32_t* wave_tot, int
 // frame has to wait for.)
 // Dynamic LDS, in 32-bit words: bitmaps [ax.n * n_words] | per window: voxels, first set, rows before
 // it, tiles started before it, last rows before it [5 * n_windows] | per tile: first set, rows before it [2 * (tile_cap + 1)],
-// launch slot [tile_cap].
+// launch slot [tile_cap] | when there is room, 9 bytes per set for the filled tiles.
 template <int NAX>
 __global__ void __launch_bounds__(1024) k_front(Jobs jobs
 #ifdef DSVT_PHASE_CLOCKS
@@ -605,6 +660,11 @@ __global__ void __launch_bounds__(1024) k_front(Jobs jobs
   int32_t* wN = (int32_t*)(smem + (size_t)NAX * n_words);
   int32_t *wSoff = wN + nw, *wP0 = wSoff + nw, *wT0 = wP0 + nw, *wPrev = wT0 + nw;
   int32_t *tFirst = wPrev + nw, *tRows = tFirst + tile_cap + 1, *tPos = tRows + tile_cap + 1;
+  const int32_t fill_sets = J.fill_sets;                    // tables of the filled tiles (see fill_tile_starts)
+  int32_t* setP = tPos + tile_cap;                           // [fill_sets + 1] rows before every set
+  uint16_t* jump = reinterpret_cast<uint16_t*>(setP + fill_sets + 1);
+  uint16_t* jump2 = jump + fill_sets + 1;
+  uint8_t* mark = reinterpret_cast<uint8_t*>(jump2 + fill_sets + 1);
 
   if (!ws_ready(ax)) {                       // (k_mark has raised DSVT_ST_WS_STATE)
     if (tid == 0) {
@@ -678,6 +738,22 @@ __global__ void __launch_bounds__(1024) k_front(Jobs jobs
   }
   lds_barrier();
   const int32_t rows_per_cut = tile_cut(carry1[1], J.rows_per_cut);
+  bool filled = false;
+  if (want_tiles && fill_sets > 0 && carry1[0] <= fill_sets && carry1[0] <= set_cap && carry1[0] < 65535 &&
+      fill_wanted(carry1[1], carry1[0], J.rows_per_cut)) {
+    for (int32_t w = tid; w < nw; w += 1024) {               // rows before every set
+      const int32_t N = wN[w], S = (int32_t)div_magic((uint32_t)(N + tau - 1), g.magic_tau), soff = wSoff[w];
+      SetWalk walk(N, S, tau);
+      int32_t P = wP0[w];
+      for (int32_t j = 0; j < S; ++j) {
+        setP[soff + j] = P;
+        P += set_rows(walk.next());
+      }
+    }
+    if (tid == 0) setP[carry1[0]] = carry1[1];
+    lds_barrier();
+    filled = fill_tiles(setP, jump, jump2, mark, carry1[0], J.rows_per_cut);
+  }
 
   // ---- the tiles every window's sets start, and a scan of their number
   for (int32_t base = 0; want_tiles && base < nw; base += 1024) {
@@ -697,7 +773,7 @@ __global__ void __launch_bounds__(1024) k_front(Jobs jobs
         const int32_t s = soff + j;
         if (s == set_cap) p_cap = P;
         if (s >= set_cap) break;
-        const bool first = s == 0 || m + pr >= rows_per_cut;
+        const bool first = filled ? mark[s] != 0 : (s == 0 || m + pr >= rows_per_cut);
         m += pr;
         while (m >= rows_per_cut) m -= rows_per_cut;
         fn(s, P, first);
@@ -1060,6 +1136,12 @@ int prepare(const PartRequest& r, int32_t n_voxels, Prepared* out) {
   }
   out->front_lds = ((size_t)r.n_axes * p.n_words + 5 * (size_t)p.g.n_windows + 3 * (size_t)(p.tile_bound + 1)) * 4;
   out->front_ok = out->front_ok && out->front_lds <= kFrontLds;
+  const size_t fill_lds = ((size_t)p.set_bound + 1) * 9 + 16;    // rows before every set, two jump tables, marks
+  J.fill_sets = 0;
+  if (r.tiles != nullptr && p.set_bound < 65535 && out->front_lds + fill_lds <= kFrontLds) {
+    J.fill_sets = p.set_bound;
+    out->front_lds += fill_lds;
+  }
   J.g = p.g;
   return DSVT_OK;
 }

@@ -83,7 +83,8 @@ def test_partition_xy_multi_bit_exact(cid, n):
 @pytest.mark.parametrize("n", [300, 3000, 12000, 20000])
 def test_small_frames_spread_over_the_compute_units(n):
     """A frame whose 64-row tiles would not fill the 256 compute units once is cut into more, shorter tiles (at
-    most 256, of 16 rows or more between cuts); larger frames keep the 64-row cut.  The work list stays valid."""
+    most 256, of 16 rows or more between cuts); larger frames keep the 64-row cut or get filled tiles when that saves
+    a round.  The work list stays valid."""
     cfg = synth.CONFIGS[2]
     coords = synth.make_frame(2, n=n)
     _say(f"tile spread n={len(coords)}")
@@ -100,7 +101,33 @@ def test_small_frames_spread_over_the_compute_units(n):
         cut = min(max((-(-rows // 256) + 3) // 4 * 4, 16), 64)
         assert nt <= min(256, rows // cut + 1) and nt >= 0.8 * min(256, rows // cut)
     else:
-        assert abs(nt - rows / 64) <= 2
+        assert nt <= rows / 64 + 2                         # (20,000 voxels: filled tiles, one round instead of two)
+        if n == 20000:
+            assert nt <= 256
+
+
+@pytest.mark.parametrize("cid,n", [(2, 45000), (2, 64000), (3, None)])
+def test_large_frames_get_filled_tiles(cid, n):
+    """Frames of several rounds over the compute units: a set starts a tile only when it no longer fits the tile before,
+    so tiles hold more than the 64 rows a fixed cut gives; for a frame of a few rounds the tile count ends just under a
+    whole number of rounds.  The work list stays valid (both kernels' paths)."""
+    cfg = synth.CONFIGS[cid]
+    coords = synth.make_frame(cid, n=n)
+    _say(f"filled tiles cfg{cid} n={len(coords)}")
+    om = orc.partition(coords, cfg["grid"], cfg["win"], (0, 0, 0), cfg["tau"], 0)
+    pair = dsvt.dsvt_partition_xy(dsvt.part_cfg(cfg["grid"], cfg["win"], (0, 0, 0), cfg["tau"], cfg["batch"], 0), dev_coords(coords))
+    assert_maps_equal(pair[0], om)
+    assert_maps_equal(pair[1], orc.partition(coords, cfg["grid"], cfg["win"], (0, 0, 0), cfg["tau"], 1))
+    si = om["set_inds"]
+    first = np.ones(si.shape, bool)
+    first[:, 1:] = np.diff(si, axis=1) != 0
+    rows = int(((first.sum(1) + 3) // 4 * 4).sum())
+    nt = int(pair[0].n_tiles.item())
+    _say(f"  rows {rows}, tiles {nt}, rows per tile {rows / nt:.1f}")
+    if nt > 8 * 256:
+        assert rows / nt > 76
+    else:
+        assert rows / nt > 66 and 0.88 < (nt / 256) / np.ceil(nt / 256) <= 1.0
 
 
 def test_partition_buffers_reused_across_frame_sizes():
