@@ -19,6 +19,11 @@ What each function follows:
                  the densified pooling region.
   bev_scatter    Sec. 3.1 overview: the voxel features projected to a dense
                  bird's-eye-view map (a definition: out[cell of voxel i] = x[i]).
+  voxel_max_vfe  Sec. 3.1 overview: points become sparse voxels through a voxel
+                 feature encoding module.  The paper names the step and cites
+                 earlier pillar encoders for it; the reading taken is the
+                 simplest member of that family: an optional per-point linear
+                 map, then the channel-wise maximum over a voxel's points.
 
 Readings taken where the paper is silent (each listed in the design notes):
 0-based ranks; Eq. (3) evaluated as an exact integer floor; x (resp. y) most
@@ -26,7 +31,9 @@ significant in the inner-window order, z least; windows shifted without wrap,
 windows and sets numbered in ascending window key; PE = a learned relative
 position bias table per head indexed by the coordinate difference query-key;
 LN eps 1e-5, exact (erf) GELU, logit scale 1/sqrt(d); pooling output =
-LN(P + Attn(P, region)).
+LN(P + Attn(P, region)); voxel feature encoding = max over the voxel's points
+of (W f + b), voxels in ascending cell key, the cell of a point decided in
+float32 (subtract, divide, compare) so that both sides take the same decision.
 Parity unpinned by the paper itself: the PE form, the pooling wrapper
 (residual + LN) and LN eps / GELU form -- they are pinned only to the stated
 reading (library LN / GELU / MHSA routines and brute force).
@@ -234,3 +241,56 @@ def bev_scatter(coords, x, batch, grid):
         b, cx, cy, cz = (int(v) for v in coords[i])
         out[b, cx, cy, cz, :] = x[i]
     return out
+
+
+# ----------------------------------------------------------------------------
+# Voxel feature encoding (Sec. 3.1, overview: point cloud -> sparse voxels)
+# ----------------------------------------------------------------------------
+def point_cells(points, point_batch, range_min, voxel_size, grid, batch):
+    """Cell (b, x, y, z) of every point and whether it lies inside the grid.  The decision is taken in
+    float32, one operation at a time: t = (p - range_min) / voxel_size, inside iff 0 <= t < cells,
+    cell = t truncated.  Points with a NaN coordinate or a batch index outside [0, batch) are outside."""
+    p = np.asarray(points, dtype=np.float32)
+    lo = np.asarray(range_min, dtype=np.float32)
+    sz = np.asarray(voxel_size, dtype=np.float32)
+    n = len(p)
+    b = np.zeros(n, dtype=np.int64) if point_batch is None else np.asarray(point_batch, dtype=np.int64)
+    inside = (b >= 0) & (b < batch)
+    cell = np.zeros((n, 4), dtype=np.int64)
+    cell[:, 0] = b
+    for a in range(3):
+        with np.errstate(invalid="ignore"):
+            t = ((p[:, a] - lo[a]).astype(np.float32) / sz[a]).astype(np.float32)
+            ok = (t >= np.float32(0)) & (t < np.float32(grid[a]))      # False for NaN
+        inside &= ok
+        cell[:, 1 + a] = np.where(ok, t, 0).astype(np.int64)            # truncation = floor for t >= 0
+    return cell, inside
+
+
+def voxel_max_vfe(points, point_batch, range_min, voxel_size, grid, batch, w=None, b=None, relu=False):
+    """Non-empty voxels in ascending key ((b*X + x)*Y + y)*Z + z and, for each, the channel-wise maximum
+    over its points of h = W f + b (f = the point's feature row, its first three entries the position;
+    w None: h = f), followed by max(., 0) if relu.  One voxel at a time, one point at a time."""
+    pts = np.asarray(points, dtype=np.float32)
+    cell, inside = point_cells(pts, point_batch, range_min, voxel_size, grid, batch)
+    X, Y, Z = (int(g) for g in grid)
+    members = {}
+    for i in range(len(pts)):
+        if inside[i]:
+            bb, cx, cy, cz = (int(v) for v in cell[i])
+            members.setdefault(((bb * X + cx) * Y + cy) * Z + cz, []).append(i)
+    keys = sorted(members)
+    C = pts.shape[1] if w is None else np.shape(w)[0]
+    coords = np.zeros((len(keys), 4), dtype=np.int32)
+    out = np.zeros((len(keys), C), dtype=F64)
+    W = None if w is None else np.asarray(w, dtype=F64)
+    B = np.zeros(C, dtype=F64) if b is None else np.asarray(b, dtype=F64)
+    for v, key in enumerate(keys):
+        coords[v] = (key // (X * Y * Z), (key // (Y * Z)) % X, (key // Z) % Y, key % Z)
+        best = np.full(C, -np.inf, dtype=F64)
+        for i in members[key]:
+            f = pts[i].astype(F64)
+            h = f + B if W is None else W @ f + B
+            best = np.maximum(best, h)
+        out[v] = np.maximum(best, 0.0) if relu else best
+    return coords, out

@@ -159,3 +159,24 @@ def make_features(seed, n, C, dtype):
     """N(0,1) features, fp32; rounded to bf16-representable values when dtype == 'bf16'."""
     x = _rng(seed).standard_normal((n, C)).astype(np.float32)
     return round_bf16(x) if dtype == "bf16" else x
+
+
+def make_points(seed, n_points, range_min, range_max, f_in=5, batch=1, outside=0.05):
+    """LiDAR-shaped point rows [n_points, f_in] float32 (x, y, z in metres, then f_in - 3 attributes
+    in [0, 1)) and a batch index per point: ranges uniform from the sensor (area density ~ 1/r, many
+    points per near cell, single points far out), heights near the ground, a share `outside` of the
+    points beyond the range on purpose, and a few points exactly on cell-like boundaries."""
+    rng = _rng(seed)
+    lo, hi = np.asarray(range_min, dtype=np.float64), np.asarray(range_max, dtype=np.float64)
+    centre, half = (lo + hi) / 2.0, (hi - lo) / 2.0
+    r = rng.uniform(0.5, min(half[0], half[1]) * (1.0 + 2.0 * outside), n_points)
+    th = rng.uniform(0.0, 2.0 * np.pi, n_points)
+    pts = np.empty((n_points, f_in), dtype=np.float64)
+    pts[:, 0] = centre[0] + r * np.cos(th)
+    pts[:, 1] = centre[1] + r * np.sin(th)
+    pts[:, 2] = lo[2] + np.abs(rng.normal(0.25, 0.2, n_points)) * (hi[2] - lo[2])
+    pts[:, 3:] = rng.random((n_points, f_in - 3))
+    m = min(n_points, 64)                                  # exact range corners and edges
+    pts[:m, 0] = np.where(rng.random(m) < 0.5, lo[0], hi[0])
+    pb = rng.integers(0, batch, n_points).astype(np.int32)
+    return pts.astype(np.float32), pb
