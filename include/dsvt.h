@@ -16,7 +16,7 @@
  *     unsupported shape, workspace too small, launch failure).  Nothing is enqueued when a
  *     negative code is returned.  Errors only a kernel can see (a coordinate outside the
  *     grid, a repeated coordinate, more sets than `max_sets`, a partition buffer that was
- *     not prepared) OR bits into the caller's
+ *     not prepared, more voxels than `max_voxels`) OR bits into the caller's
  *     [device] `status` word; outputs are then unspecified but no access leaves the
  *     caller's buffers.
  *   - Voxel coordinates are int32 rows (b, x, y, z), 0 <= b < batch, unique per call.
@@ -34,7 +34,8 @@ extern "C" {
 enum { DSVT_OK = 0, DSVT_EINVAL = -1, DSVT_ENOSPC = -2, DSVT_EHIP = -3, DSVT_EUNSUPPORTED = -4 };
 enum { DSVT_F32 = 0, DSVT_BF16 = 1 };
 /* bits of the device status word */
-enum { DSVT_ST_COORD_RANGE = 1, DSVT_ST_COORD_REPEAT = 2, DSVT_ST_SET_OVERFLOW = 4, DSVT_ST_WS_STATE = 8 };
+enum { DSVT_ST_COORD_RANGE = 1, DSVT_ST_COORD_REPEAT = 2, DSVT_ST_SET_OVERFLOW = 4, DSVT_ST_WS_STATE = 8,
+       DSVT_ST_VOXEL_OVERFLOW = 16 };
 
 /* ---------------------------------------------------------------------------------------
  * Set partition (Sec. 3.2 "Dynamic set partition", Eq. 2-4; "Rotated set attention";
@@ -249,6 +250,45 @@ int dsvt_attn_pool(const dsvt_pool_cfg* cfg, const int32_t* coords, const void* 
  * ------------------------------------------------------------------------------------ */
 int dsvt_bev_scatter(const int32_t* coords, const void* x, int32_t n_voxels, int32_t C, int32_t dtype,
                      int32_t batch, const int32_t grid[3], void* out, int32_t* status, void* stream);
+
+/* ---------------------------------------------------------------------------------------
+ * Voxel feature encoding (Sec. 3.1, overview: the input points are first converted into sparse
+ * voxels by a voxel feature encoding module, each voxel then being one token).  The paper names
+ * the step and cites earlier pillar encoders; built here is the plain member of that family:
+ *   x[v] = max over the points p of voxel v of (w f_p + b), channel by channel, then max(., 0)
+ *   if relu; w == NULL: x[v] = max over p of f_p (C == f_in).
+ * A point's cell along an axis is t = (p - range_min) / voxel_size evaluated in float32, one
+ * rounded operation each; the point lies in the grid iff 0 <= t < grid (a NaN does not), its cell
+ * is t truncated.  Points outside the grid, or with a batch index outside [0, batch), are ignored.
+ * ------------------------------------------------------------------------------------ */
+typedef struct {
+  int32_t grid[3];      /* cells along X, Y, Z                                             */
+  int32_t batch;        /* frames in the call                                              */
+  float range_min[3];   /* position of the corner of cell (0,0,0)                          */
+  float voxel_size[3];  /* cell edge lengths, > 0                                          */
+  int32_t f_in;         /* floats per point, 3 <= f_in <= 16; the first three are x, y, z   */
+  int32_t C;            /* output channels                                                 */
+  int32_t dtype;        /* element type of the output rows x                               */
+  const float* w;       /* [C, f_in] [device] or NULL                                      */
+  const float* b;       /* [C] [device] or NULL                                            */
+  int32_t relu;
+} dsvt_vfe_cfg;
+
+int dsvt_vfe_workspace_size(const dsvt_vfe_cfg* cfg, int32_t n_points, int32_t max_voxels, size_t* bytes);
+
+/* points      [device] float [n_points, f_in]
+ * point_batch [device] int32 [n_points] frame of each point; may be NULL when batch == 1
+ * coords      [device] int32 [max_voxels,4], 16-byte aligned: (b, x, y, z) of the non-empty voxels in
+ *             ascending key ((b*X + x)*Y + y)*Z + z -- the rows dsvt_partition and dsvt_block take
+ * x           [device] [max_voxels, C] of dtype: their features
+ * n_voxels    [device] int32 scalar: the number of non-empty voxels (may exceed max_voxels, see below)
+ * ws          [device] scratch of dsvt_vfe_workspace_size bytes, 16-byte aligned; no state is kept in it
+ * status gets DSVT_ST_VOXEL_OVERFLOW when there are more than max_voxels non-empty voxels: the first
+ * max_voxels rows are then complete and the rest is dropped.  batch*X*Y*Z must be below 2^31.
+ * Asynchronous on stream.  The result does not depend on the order of the points. */
+int dsvt_vfe(const dsvt_vfe_cfg* cfg, const float* points, const int32_t* point_batch, int32_t n_points,
+             int32_t* coords, void* x, int32_t* n_voxels, int32_t max_voxels, void* ws, size_t ws_bytes,
+             int32_t* status, void* stream);
 
 /* ---------------------------------------------------------------------------------------
  * Instrumentation for benchmarks (not part of the method): per-kernel time from hipEvent pairs

@@ -14,11 +14,12 @@ LIB_PATH = os.path.join(_PKG, "libdsvt.so")
 
 DSVT_OK, DSVT_EINVAL, DSVT_ENOSPC, DSVT_EHIP, DSVT_EUNSUPPORTED = 0, -1, -2, -3, -4
 DSVT_F32, DSVT_BF16 = 0, 1
-ST_COORD_RANGE, ST_COORD_REPEAT, ST_SET_OVERFLOW, ST_WS_STATE = 1, 2, 4, 8
+ST_COORD_RANGE, ST_COORD_REPEAT, ST_SET_OVERFLOW, ST_WS_STATE, ST_VOXEL_OVERFLOW = 1, 2, 4, 8, 16
 _ERR = {-1: "DSVT_EINVAL", -2: "DSVT_ENOSPC", -3: "DSVT_EHIP", -4: "DSVT_EUNSUPPORTED"}
 _DT = {"f32": (DSVT_F32, torch.float32), "bf16": (DSVT_BF16, torch.bfloat16)}
 
 I32x3 = C.c_int32 * 3
+F32x3 = C.c_float * 3
 
 
 class PartCfg(C.Structure):
@@ -50,6 +51,11 @@ class LayerW(C.Structure):
                 ("ln1_g", C.c_void_p), ("ln1_b", C.c_void_p), ("ln2_g", C.c_void_p), ("ln2_b", C.c_void_p),
                 ("ln_eps", C.c_float), ("rel_bias", C.c_void_p), ("win", I32x3), ("dup_mode", C.c_int32),
                 ("packed", C.c_void_p)]
+
+
+class VfeCfg(C.Structure):
+    _fields_ = [("grid", I32x3), ("batch", C.c_int32), ("range_min", F32x3), ("voxel_size", F32x3), ("f_in", C.c_int32),
+                ("C", C.c_int32), ("dtype", C.c_int32), ("w", C.c_void_p), ("b", C.c_void_p), ("relu", C.c_int32)]
 
 
 class PoolCfg(C.Structure):
@@ -88,6 +94,8 @@ def lib():
         L.dsvt_attn_pool_workspace_size.argtypes = [C.POINTER(PoolCfg), i32, C.POINTER(sz)]
         L.dsvt_attn_pool.argtypes = [C.POINTER(PoolCfg), vp, vp, i32, vp, vp, vp, vp, sz, vp, vp]
         L.dsvt_bev_scatter.argtypes = [vp, vp, i32, i32, i32, i32, C.POINTER(I32x3), vp, vp, vp]
+        L.dsvt_vfe_workspace_size.argtypes = [C.POINTER(VfeCfg), i32, i32, C.POINTER(sz)]
+        L.dsvt_vfe.argtypes = [C.POINTER(VfeCfg), vp, vp, i32, vp, vp, vp, i32, vp, sz, vp, vp]
         L.dsvt_prof_enable.argtypes = [i32]
         L.dsvt_prof_collect.argtypes = [C.POINTER(C.c_float), C.POINTER(i32), i32]
         L.dsvt_prof_kernel_count.restype = i32
@@ -345,6 +353,42 @@ def dsvt_bev_scatter(coords, x, batch, grid, out=None, stream=None):
                                 C.byref(I32x3(*grid)), _ptr(out), _ptr(status), _stream(stream))
     _check("dsvt_bev_scatter", rc)
     return out, status
+
+
+def dsvt_vfe_workspace_size(cfg, n_points, max_voxels):
+    b = C.c_size_t(0)
+    _check("dsvt_vfe_workspace_size", lib().dsvt_vfe_workspace_size(C.byref(cfg), n_points, max_voxels, C.byref(b)))
+    return b.value
+
+
+class Vfe:
+    """Configuration, weights and buffers of one dsvt_vfe call site: `max_points` points in, at most
+    `max_voxels` voxels out.  w [C, f_in] and b [C] are float32 device tensors or None."""
+
+    def __init__(self, grid, batch, range_min, voxel_size, f_in, C_out, dtype, max_points, max_voxels, w=None, b=None,
+                 relu=False):
+        self.w, self.b = w, b
+        self.cfg = VfeCfg(I32x3(*grid), batch, F32x3(*range_min), F32x3(*voxel_size), f_in, C_out, _DT[dtype][0],
+                          None if w is None else w.data_ptr(), None if b is None else b.data_ptr(), int(relu))
+        self.max_points, self.max_voxels = max_points, max_voxels
+        self.ws = torch.empty((dsvt_vfe_workspace_size(self.cfg, max_points, max_voxels),), dtype=torch.uint8, device="cuda")
+        self.coords = torch.empty((max_voxels, 4), dtype=torch.int32, device="cuda")
+        self.x = torch.empty((max_voxels, C_out), dtype=_DT[dtype][1], device="cuda")
+        self.n_voxels = torch.zeros((1,), dtype=torch.int32, device="cuda")
+        self.status = torch.zeros((1,), dtype=torch.int32, device="cuda")
+
+
+def dsvt_vfe(vfe, points, point_batch=None, stream=None):
+    """Encodes `points` [P, f_in] float32 (device) into vfe.coords / vfe.x / vfe.n_voxels."""
+    n = points.shape[0]
+    assert points.is_cuda and points.is_contiguous() and points.dtype == torch.float32 and n <= vfe.max_points
+    assert points.shape[1] == vfe.cfg.f_in
+    assert point_batch is None or (point_batch.is_cuda and point_batch.dtype == torch.int32 and point_batch.shape == (n,))
+    rc = lib().dsvt_vfe(C.byref(vfe.cfg), _ptr(points), None if point_batch is None else _ptr(point_batch), n,
+                        _ptr(vfe.coords), _ptr(vfe.x), _ptr(vfe.n_voxels), vfe.max_voxels, _ptr(vfe.ws), vfe.ws.numel(),
+                        _ptr(vfe.status), _stream(stream))
+    _check("dsvt_vfe", rc)
+    return vfe
 
 
 def prof_enable(max_launches):

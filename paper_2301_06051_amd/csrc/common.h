@@ -35,7 +35,8 @@ void dsvt_prof_mark_begin(int kernel_id, hipStream_t stream);
 void dsvt_prof_mark_end(int kernel_id, hipStream_t stream);
 enum {
   DSVT_K_PART_MARK = 0, DSVT_K_PART_COUNT, DSVT_K_PART_SCAN, DSVT_K_PART_EMIT, DSVT_K_PART_CLEAR,
-  DSVT_K_PART_TILES, DSVT_K_LAYER, DSVT_K_POOL_GROUP, DSVT_K_POOL_ATTN, DSVT_K_BEV_CLEAR, DSVT_K_BEV_SCATTER, DSVT_K_COUNT
+  DSVT_K_PART_TILES, DSVT_K_LAYER, DSVT_K_POOL_GROUP, DSVT_K_POOL_ATTN, DSVT_K_BEV_CLEAR, DSVT_K_BEV_SCATTER,
+  DSVT_K_VFE_GROUP, DSVT_K_VFE_REDUCE, DSVT_K_COUNT
 };
 struct dsvt_prof_scope {
   int id; hipStream_t s;

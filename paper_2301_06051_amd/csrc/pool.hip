@@ -11,6 +11,7 @@
 // slots and Q of the pooled rows are MFMA projections; the P-key softmax per head is plain ALU
 // work; output projection, residual and LayerNorm follow the layer kernels (Eq. 7).
 #include "common.h"
+#include "block_scan.h"
 #include "mma.h"
 
 namespace {
@@ -47,60 +48,6 @@ __global__ void kp_mark(PoolGeom g, const int4* __restrict__ coords, int32_t n, 
   uint32_t key; int32_t slot;
   if (!pool_key(g, coords[i], &key, &slot)) { atomicOr(status, DSVT_ST_COORD_RANGE); return; }
   atomicOr(&bitmap[key >> 5], 1u << (key & 31u));
-}
-
-// One workgroup: exclusive pop-count scan over the bitmap words; the total is the output count.
-// A thread takes 16 consecutive words per round (four 16-byte loads), so a round covers 16,384 words
-// with one block scan of the threads' totals.
-constexpr int kScanWords = 16;
-__global__ void __launch_bounds__(1024) kp_scan(const uint32_t* __restrict__ bitmap, int32_t* __restrict__ word_prefix,
-                                                int64_t n_words, int32_t* __restrict__ n_out) {
-  __shared__ int32_t wave_tot[16];
-  __shared__ int32_t carry_s;
-  const int32_t tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-  if (tid == 0) carry_s = 0;
-  __syncthreads();
-  for (int64_t base = 0; base < n_words; base += 1024 * kScanWords) {
-    const int64_t w0 = base + (int64_t)tid * kScanWords;
-    uint32_t v[kScanWords];
-    if (w0 + kScanWords <= n_words) {            // (the bitmap is 256-byte aligned and w0 a multiple of 16)
-#pragma unroll
-      for (int32_t q = 0; q < kScanWords / 4; ++q) {
-        const uint4 t = reinterpret_cast<const uint4*>(bitmap + w0)[q];
-        v[4 * q] = t.x; v[4 * q + 1] = t.y; v[4 * q + 2] = t.z; v[4 * q + 3] = t.w;
-      }
-    } else {
-#pragma unroll
-      for (int32_t j = 0; j < kScanWords; ++j) v[j] = w0 + j < n_words ? bitmap[w0 + j] : 0u;
-    }
-    int32_t pre[kScanWords], mine = 0;
-#pragma unroll
-    for (int32_t j = 0; j < kScanWords; ++j) { pre[j] = mine; mine += __popc(v[j]); }
-    int32_t incl = mine;
-    for (int32_t d = 1; d < 64; d <<= 1) {
-      const int32_t up = __shfl_up(incl, d, 64);
-      if (lane >= d) incl += up;
-    }
-    if (lane == 63) wave_tot[wv] = incl;
-    __syncthreads();
-    int32_t before = carry_s;
-    for (int32_t k = 0; k < wv; ++k) before += wave_tot[k];
-    const int32_t first = before + incl - mine;
-    if (w0 + kScanWords <= n_words) {
-#pragma unroll
-      for (int32_t q = 0; q < kScanWords / 4; ++q)
-        reinterpret_cast<int4*>(word_prefix + w0)[q] =
-            make_int4(first + pre[4 * q], first + pre[4 * q + 1], first + pre[4 * q + 2], first + pre[4 * q + 3]);
-    } else {
-#pragma unroll
-      for (int32_t j = 0; j < kScanWords; ++j)
-        if (w0 + j < n_words) word_prefix[w0 + j] = first + pre[j];
-    }
-    __syncthreads();
-    if (tid == 1023) carry_s = before + incl;
-    __syncthreads();
-  }
-  if (tid == 0) *n_out = carry_s;
 }
 
 __global__ void kp_emit(PoolGeom g, const int4* __restrict__ coords, int32_t n, const uint32_t* __restrict__ bitmap,
@@ -557,7 +504,7 @@ extern "C" int dsvt_attn_pool(const dsvt_pool_cfg* cfg, const int32_t* coords, c
     kp_clear<<<(unsigned)dsvt_ceil_div(n_clear, tb), tb, 0, st>>>(bitmap, pl.n_words, inds, n_inds);
     kp_mark<<<(unsigned)dsvt_ceil_div(n_voxels, tb), tb, 0, st>>>(pl.g, reinterpret_cast<const int4*>(coords), n_voxels,
                                                                   bitmap, status);
-    kp_scan<<<1, 1024, 0, st>>>(bitmap, prefix, pl.n_words, n_out);
+    k_block_scan<true><<<1, 1024, 0, st>>>(bitmap, prefix, pl.n_words, nullptr, n_out);
     kp_emit<<<(unsigned)dsvt_ceil_div(n_voxels, tb), tb, 0, st>>>(pl.g, reinterpret_cast<const int4*>(coords), n_voxels,
                                                                   bitmap, prefix, inds, out_coords);
   }

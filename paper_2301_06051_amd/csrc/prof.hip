@@ -11,7 +11,7 @@ std::vector<int> g_ids;
 size_t g_used = 0;
 const char* const kNames[DSVT_K_COUNT] = {
     "part_mark", "part_window_count", "part_scan_windows", "part_emit", "part_clear",
-    "part_tiles", "layer", "pool_group", "pool_attention", "bev_clear", "bev_scatter"};
+    "part_tiles", "layer", "pool_group", "pool_attention", "bev_clear", "bev_scatter", "vfe_group", "vfe_reduce"};
 }  // namespace
 
 void dsvt_prof_mark_begin(int id, hipStream_t s) {

@@ -161,22 +161,30 @@ def make_features(seed, n, C, dtype):
     return round_bf16(x) if dtype == "bf16" else x
 
 
-def make_points(seed, n_points, range_min, range_max, f_in=5, batch=1, outside=0.05):
-    """LiDAR-shaped point rows [n_points, f_in] float32 (x, y, z in metres, then f_in - 3 attributes
-    in [0, 1)) and a batch index per point: ranges uniform from the sensor (area density ~ 1/r, many
-    points per near cell, single points far out), heights near the ground, a share `outside` of the
-    points beyond the range on purpose, and a few points exactly on cell-like boundaries."""
+def make_points(seed, n_points, range_min, range_max, f_in=5, batch=1, clusters=600, share=0.95, sigma=0.45):
+    """LiDAR-shaped point rows [n_points, f_in] float32 (x, y, z in metres, then f_in - 3 attributes in
+    [0, 1)) and a frame index per point.  A share of the points falls into Gaussian blobs (objects and
+    ground patches, centres at uniform range from the sensor, so dense near it), the rest is spread with
+    an area density ~ 1/r out to 7 % beyond the range, so that some points lie outside on purpose: at
+    180,000 points over 150 m x 150 m and 0.32 m pillars about 30,000 pillars are hit, from single points
+    to several dozen per pillar.  The first 64 rows are put exactly on the range's x edges.  sigma scales
+    with the x extent (0.45 at 150 m)."""
     rng = _rng(seed)
     lo, hi = np.asarray(range_min, dtype=np.float64), np.asarray(range_max, dtype=np.float64)
     centre, half = (lo + hi) / 2.0, (hi - lo) / 2.0
-    r = rng.uniform(0.5, min(half[0], half[1]) * (1.0 + 2.0 * outside), n_points)
-    th = rng.uniform(0.0, 2.0 * np.pi, n_points)
+    R = min(half[0], half[1])
+    sig = sigma * (hi[0] - lo[0]) / 149.76
+    cr, cth = rng.uniform(0.0, R, clusters), rng.uniform(0.0, 2.0 * np.pi, clusters)
+    cx, cy = centre[0] + cr * np.cos(cth), centre[1] + cr * np.sin(cth)
+    pick = rng.integers(0, clusters, n_points)
+    blob = rng.random(n_points) < share
+    r, th = rng.uniform(0.0, 1.07 * R, n_points), rng.uniform(0.0, 2.0 * np.pi, n_points)
     pts = np.empty((n_points, f_in), dtype=np.float64)
-    pts[:, 0] = centre[0] + r * np.cos(th)
-    pts[:, 1] = centre[1] + r * np.sin(th)
+    pts[:, 0] = np.where(blob, cx[pick] + rng.normal(0.0, sig, n_points), centre[0] + r * np.cos(th))
+    pts[:, 1] = np.where(blob, cy[pick] + rng.normal(0.0, sig, n_points), centre[1] + r * np.sin(th))
     pts[:, 2] = lo[2] + np.abs(rng.normal(0.25, 0.2, n_points)) * (hi[2] - lo[2])
     pts[:, 3:] = rng.random((n_points, f_in - 3))
-    m = min(n_points, 64)                                  # exact range corners and edges
+    m = min(n_points, 64)
     pts[:m, 0] = np.where(rng.random(m) < 0.5, lo[0], hi[0])
     pb = rng.integers(0, batch, n_points).astype(np.int32)
     return pts.astype(np.float32), pb

@@ -44,3 +44,9 @@ def make_pool_weights(seed, C, heads, dtype):
                 w_q=_xavier(rng, C, C, dtype), b_q=_vec(rng, C), w_k=_xavier(rng, C, C, dtype), b_k=_vec(rng, C),
                 w_v=_xavier(rng, C, C, dtype), b_v=_vec(rng, C), w_o=_xavier(rng, C, C, dtype), b_o=_vec(rng, C),
                 ln_g=_vec(rng, C, 1.0), ln_b=_vec(rng, C))
+
+
+def make_vfe_weights(seed, C, f_in):
+    """Per-point linear map of the voxel feature encoder: w [C, f_in] Xavier-uniform, b [C] U(+-0.1), float32."""
+    rng = _rng(seed)
+    return _xavier(rng, C, f_in, "f32"), _vec(rng, C)
