@@ -256,12 +256,58 @@ def bev_workload(args):
     }, dt
 
 
+def vfe_workload(args):
+    """Sec. 3.1: a LiDAR-shaped point frame encoded into the pillar rows the first DSVT block takes."""
+    import torch
+    import synth
+    import paper_2301_06051_amd as dsvt
+    grid, lo, hi, size, C, f_in, P = (468, 468, 1), (-74.88, -74.88, -2.0), (74.88, 74.88, 4.0), (0.32, 0.32, 6.0), 192, 5, 180000
+    pts, _ = synth.make_points(24, P, lo, hi, f_in=f_in)
+    w, b = synth.make_vfe_weights(25, C, f_in)
+    pd, wd, bd = torch.as_tensor(pts).cuda(), torch.as_tensor(w).cuda(), torch.as_tensor(b).cuda()
+    vfe = dsvt.Vfe(grid, 1, lo, size, f_in, C, "bf16", P, 65536, wd, bd, True)
+
+    def step():
+        dsvt.dsvt_vfe(vfe, pd)
+
+    step()
+    torch.cuda.synchronize()
+    N = int(vfe.n_voxels.item())
+    assert int(vfe.status.item()) == 0
+    ref_x, ref_c = vfe.x[:N].clone(), vfe.coords[:N].clone()
+
+    def check(run):                                       # every replay must reproduce the eager result
+        vfe.x.zero_(); vfe.coords.zero_(); vfe.n_voxels.zero_()
+        run()
+        torch.cuda.synchronize()
+        assert int(vfe.n_voxels.item()) == N and torch.equal(vfe.x[:N], ref_x) and torch.equal(vfe.coords[:N], ref_c)
+
+    graph = None if args.no_graph else capture(step, check)
+    run = step if graph is None else graph
+    dt = timed(run, args.steps, args.warmup)
+    per_launch_us, per_step_ms = per_kernel(step, 2, min(args.steps, 50))
+    nbytes = P * f_in * 4 + N * (C * 2 + 16)               # points read once, rows and coordinates written once
+    us = per_launch_us["vfe_group"] + per_launch_us["vfe_reduce"]
+    roofline = {"bound": "hbm", "kernel": "vfe_group (7 launches) + vfe_reduce", "achieved": round(nbytes / (us * 1e-6) / 1e9, 1),
+                "peak": 8000.0, "unit": "GB/s", "frac": round(nbytes / (us * 1e-6) / 8e12, 5), "traffic": None,
+                "avg_launch_us": round(us, 2), "bytes_per_launch": nbytes}
+    return {
+        "metric": "points/sec encoded into pillar rows", "value": round(P / (dt / args.steps), 1), "unit": "points/s", "dtype": "f32",
+        "config": {"workload": f"{P} points ({f_in} floats each) over 468x468x1 pillars of 0.32 m -> {N} rows of C={C} bf16 "
+                               "(linear map + ReLU + max)", "launch": "eager" if graph is None else "hip_graph"},
+        "ms_per_frame": round(dt / args.steps * 1e3, 4),
+        "kernel_ms_per_step": {k: round(v, 4) for k, v in per_step_ms.items()},
+        "kernel_us_per_launch": {k: round(v, 2) for k, v in per_launch_us.items()},
+        "roofline": roofline, "cpu_baseline": None,
+    }, dt
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", choices=["frame", "voxel", "skewed", "pool", "bev"], default="frame")
+    ap.add_argument("--workload", choices=["frame", "voxel", "skewed", "pool", "bev", "vfe"], default="frame")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of a captured HIP graph")
     ap.add_argument("--pmc-calibration", action="store_true",
@@ -279,6 +325,8 @@ def main():
         body, dt = stack_workload(args, args.workload)
     elif args.workload == "pool":
         body, dt = pool_workload(args)
+    elif args.workload == "vfe":
+        body, dt = vfe_workload(args)
     else:
         body, dt = bev_workload(args)
     line = {"metric": body.pop("metric"), "value": body.pop("value"), "unit": body.pop("unit"), "n_gpus": 1,

@@ -267,7 +267,7 @@ typedef struct {
   float range_min[3];   /* position of the corner of cell (0,0,0)                          */
   float voxel_size[3];  /* cell edge lengths, > 0                                          */
   int32_t f_in;         /* floats per point, 3 <= f_in <= 16; the first three are x, y, z   */
-  int32_t C;            /* output channels                                                 */
+  int32_t C;            /* output channels, <= 512                                         */
   int32_t dtype;        /* element type of the output rows x                               */
   const float* w;       /* [C, f_in] [device] or NULL                                      */
   const float* b;       /* [C] [device] or NULL                                            */
