@@ -40,6 +40,19 @@ def timed(run, steps, warmup):
     return time.perf_counter() - t0
 
 
+def percentiles(run, steps):
+    """Per-step time from an event pair around every step (steps still queue back to back): p10 / p50 / p90 in ms."""
+    import torch
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    for a, b in ev:
+        a.record()
+        run()
+        b.record()
+    torch.cuda.synchronize()
+    ms = np.sort([a.elapsed_time(b) for a, b in ev])
+    return {k: round(float(ms[min(int(q * steps), steps - 1)]), 4) for k, q in (("p10", 0.1), ("p50", 0.5), ("p90", 0.9))}
+
+
 def capture(step, check):
     """step() captured into a HIP graph; three replays must pass check()."""
     import torch
@@ -125,6 +138,32 @@ def stack_workload(args, name):
     use_graph = not args.no_graph
     run = capture(step, check) if use_graph else step
     dt = timed(run, args.steps, args.warmup)
+    step_ms = percentiles(run, min(args.steps, 100))
+
+    # One DSVT block on its own (the paper's per-block latency): both rotated partitions of one window
+    # configuration plus the block's two layers, and the block alone with the maps reused.
+    def one_block():
+        dsvt.dsvt_partition_xy(pcfgs[shifts[0]], cd, out=maps[shifts[0]])
+        dsvt.dsvt_block(layers[0], maps[shifts[0]], cd, x0, x_out=buf, ws=ws)
+
+    def block_only():
+        dsvt.dsvt_block(layers[0], maps[shifts[0]], cd, x0, x_out=buf, ws=ws)
+
+    one = {}
+    for key, fn in (("partition_and_block", one_block), ("block_maps_reused", block_only)):
+        fn()
+        torch.cuda.synchronize()
+        ref = buf.clone()
+
+        def check_one(replay):
+            buf.zero_()
+            replay()
+            torch.cuda.synchronize()
+            assert torch.equal(buf, ref), "graph replay differs from eager launches"
+
+        t = timed(capture(fn, check_one) if use_graph else fn, args.steps, args.warmup) / args.steps
+        one[key] = {"ms": round(t * 1e3, 4), "voxels_per_s": round(N / t, 1)}
+    step()                                                   # (the maps of the first shift back to the frame's own)
     launches = 6 * len(shifts) + 2 * cfg["blocks"]          # (an upper bound: small frames take 3 partition launches)
     per_launch_us, per_step_ms = per_kernel(step, launches, min(args.steps, 50))
 
@@ -157,7 +196,7 @@ def stack_workload(args, name):
         "value": round(N / (dt / args.steps), 1), "unit": "voxels/s", "dtype": "bf16",
         "config": {"workload": workload, "launch": "hip_graph" if use_graph else "eager",
                    "n_sets": {"shift" + "_".join(map(str, k)): v for k, v in n_sets.items()}, "rho": round(float(rho), 4)},
-        "ms_per_frame": round(dt / args.steps * 1e3, 4),
+        "ms_per_frame": round(dt / args.steps * 1e3, 4), "step_ms": step_ms, "one_block": one,
         "kernel_ms_per_step": {k: round(v, 4) for k, v in per_step_ms.items()},
         "kernel_us_per_launch": {k: round(v, 2) for k, v in per_launch_us.items()},
         "roofline": roofline, "cpu_baseline": cpu,

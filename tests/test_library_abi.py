@@ -43,3 +43,12 @@ def test_host_only_calls_work_without_a_gpu():
         b.dsvt_partition_bound(b.part_cfg((468, 468, 1), (12, 12, 1), (12, 0, 0), 36, 1, 0), 30000)
     with pytest.raises(b.DsvtError):
         b.dsvt_partition_bound(b.part_cfg((468, 468, 1), (12, 12, 1), (0, 0, 0), 36, 1, 2), 30000)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py is single-GPU by design: any other --gpus value exits with a message before touching a device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2 and "single-GPU" in r.stderr and r.stdout.strip() == ""
