@@ -9,7 +9,10 @@ What each function follows:
   partition      Sec. 3.2 "Dynamic set partition": window split, Eq. (2) set
                  count, Eq. (3) slot index, Eq. (4) INDEX; "Rotated set
                  attention": X-/Y-axis main order; "Hybrid window partition":
-                 window shift.
+                 window shift.  axis 2-5: the Random and Sparse baselines of
+                 the set-partition ablation (Sec. 4.4), made "by controlling
+                 the inner-window voxel ID" as the paper says they are; the
+                 Regional baseline is axis 0 in both layers of a block.
   set_attention  Eq. (5): MHSA over every set in one batch, PE added to the
                  logits, duplicated slots masked as keys (sentence after Eq. 3).
   layer / block  Appendix "Network Architecture", DSVT-P paragraph: MHSA,
@@ -60,11 +63,25 @@ def window_and_inner_keys(coords, grid, win, shift, axis):
     nwx, nwy, nwz = windows_per_axis(grid, win, shift)
     win_key = ((b * nwx + x // L) * nwy + y // W) * nwz + z // H
     xi, yi, zi = x % L, y % W, z % H
-    if axis == 0:                       # X-axis main order: x, then y, then z
+    if axis % 2 == 0:                   # X-axis main order: x, then y, then z
         inner = (xi * W + yi) * H + zi
     else:                               # Y-axis main order: y, then x, then z
         inner = (yi * L + xi) * H + zi
+    if axis in (2, 3):                  # "Random" baseline of the set-partition ablation: a fixed shuffle of the cells
+        mul, add = shuffle_constants(L * W * H, axis)
+        inner = (inner * mul + add) % (L * W * H)
     return win_key, inner
+
+
+def shuffle_constants(volume, axis):
+    """The inner-window voxel ID of the 'Random' partition baseline is taken as a fixed shuffle of the window's
+    V cells, key -> (key * mul + add) mod V: mul = the smallest integer >= floor(0.618 V) + (axis odd) that has
+    no common factor with V (so the map is one-to-one), add = floor(V / 3) + (axis odd)."""
+    odd = axis % 2
+    mul = max(int(0.618 * volume), 1) + odd
+    while np.gcd(mul, volume) != 1:
+        mul += 1
+    return mul, volume // 3 + odd
 
 
 def partition(coords, grid, win, shift, tau, axis):
@@ -87,7 +104,11 @@ def partition(coords, grid, win, shift, tau, axis):
         S = N // tau + (1 if N % tau > 0 else 0)                    # Eq. (2)
         t = np.arange(S * tau, dtype=np.int64)                      # t = j*tau + k
         q = (t * N) // (S * tau)                                    # Eq. (3), exact floor
-        rows.append(order[base + q].reshape(S, tau))                # Eq. (4): INDEX by inner-window rank
+        members = order[base:base + N]
+        if axis in (4, 5):              # "Sparse" baseline: every subset spread over the whole window -- the voxel
+            d = np.arange(N)            # of rank d goes behind all voxels of a smaller rank residue d mod S
+            members = members[np.lexsort((d // S, d % S))]
+        rows.append(members[q].reshape(S, tau))                     # Eq. (4): INDEX by inner-window rank
         set_win += [wk] * S
     set_inds = np.concatenate(rows, 0) if rows else np.zeros((0, tau), np.int64)
     flat = set_inds.reshape(-1)

@@ -144,3 +144,78 @@ def test_float_evaluation_of_eq3_is_not_exact():
         lit = np.floor(t.astype(np.float64) / (S * tau) * N).astype(np.int64)
         bad += int(np.any(lit != (t * N) // (S * tau)))
     assert bad > 0
+
+
+# ---------------------------------------------------------------- Random / Sparse / Regional baselines (Sec. 4.4)
+def _brute_variant(coords, grid, win, shift, tau, axis):
+    """The variants written out in plain Python: an explicit shuffle table for axis 2/3, an explicit
+    round-robin deal of the ranked voxels for axis 4/5."""
+    L, W, H = win
+    V = L * W * H
+    mul, add = orc.shuffle_constants(V, axis)
+    table = [(k * mul + add) % V for k in range(V)]
+    per_window = {}
+    for i, (b, x, y, z) in enumerate(coords.tolist()):
+        x, y, z = x + shift[0], y + shift[1], z + shift[2]
+        xi, yi, zi = x % L, y % W, z % H
+        inner = (xi * W + yi) * H + zi if axis % 2 == 0 else (yi * L + xi) * H + zi
+        if axis in (2, 3):
+            inner = table[inner]
+        per_window.setdefault((b, x // L, y // W, z // H), []).append((inner, i))
+    set_inds = []
+    for wkey in sorted(per_window):
+        ranked = [i for _, i in sorted(per_window[wkey])]
+        N = len(ranked)
+        S = N // tau + (1 if N % tau else 0)
+        if axis in (4, 5):
+            piles = [[] for _ in range(S)]
+            for d, i in enumerate(ranked):            # deal the ranked voxels round-robin onto S piles ...
+                piles[d % S].append(i)
+            ranked = [i for pile in piles for i in pile]   # ... and lay the piles end to end
+        for j in range(S):
+            set_inds.append([ranked[floor(Fraction(j * tau + k, S * tau) * N)] for k in range(tau)])
+    return set_inds
+
+
+@pytest.mark.parametrize("volume", [1, 2, 7, 36, 144, 1152, 4608, 900])
+def test_shuffle_is_one_to_one(volume):
+    for axis in (2, 3):
+        mul, add = orc.shuffle_constants(volume, axis)
+        image = sorted((k * mul + add) % volume for k in range(volume))
+        assert image == list(range(volume))
+    if volume > 7:
+        assert orc.shuffle_constants(volume, 2) != orc.shuffle_constants(volume, 3)
+
+
+@pytest.mark.parametrize("axis", [2, 3, 4, 5])
+def test_partition_variants_match_brute_force(axis):
+    grid, win, tau, shift = (13, 11, 5), (4, 6, 2), 5, (2, 3, 1)
+    coords = np.concatenate([np.concatenate([np.full((150, 1), b), synth.frame_uniform(7 + b, grid, 150)], 1)
+                             for b in range(2)]).astype(np.int32)
+    m = orc.partition(coords, grid, win, shift, tau, axis)
+    assert m["set_inds"].tolist() == _brute_variant(coords, grid, win, shift, tau, axis)
+    base = orc.partition(coords, grid, win, shift, tau, axis % 2)
+    # the same windows, set counts and voxels per window as the rotated partition; another order inside
+    assert m["n_sets"] == base["n_sets"] and np.array_equal(m["set_win"], base["set_win"])
+    assert not np.array_equal(m["set_inds"], base["set_inds"])
+    assert np.array_equal(m["set_inds"].reshape(-1)[m["voxel_slot"]], np.arange(len(coords)))
+    # Thm A.2-A.4 still hold (they only use the ranks): per window every voxel in exactly one set, sizes within 1
+    for wk in np.unique(m["set_win"]):
+        rows = m["set_inds"][m["set_win"] == wk]
+        members = [set(r.tolist()) for r in rows]
+        assert sum(len(s) for s in members) == len(set().union(*members))
+        assert max(len(s) for s in members) - min(len(s) for s in members) <= 1
+
+
+def test_sparse_sets_span_the_window_and_regional_sets_do_not():
+    """What the names say: along the main axis a Sparse subset reaches across (nearly) the whole window's voxels,
+    a Regional one (the rotated partition's X-axis order) covers a slab."""
+    cfg = synth.CONFIGS[2]
+    coords = synth.make_frame(2, n=20000)
+    reg = orc.partition(coords, cfg["grid"], cfg["win"], (0, 0, 0), cfg["tau"], 0)
+    spr = orc.partition(coords, cfg["grid"], cfg["win"], (0, 0, 0), cfg["tau"], 4)
+    counts = dict(zip(reg["win_keys"].tolist(), reg["win_counts"].tolist()))
+    big = np.array([counts[int(w)] >= 2 * cfg["tau"] for w in reg["set_win"]])          # windows of three sets or more
+    assert big.sum() > 20
+    span = lambda m: np.ptp(coords[m["set_inds"][big], 1], axis=1)          # extent in x of every set
+    assert np.median(span(spr)) >= 9 and np.median(span(reg)) <= 5
