@@ -48,7 +48,16 @@ typedef struct {
   int32_t tau;      /* set size: slots per set                                         */
   int32_t batch;    /* frames in the call; b is the top digit of the window key        */
   int32_t axis;     /* inner-window order: 0 = x,y,z most-to-least significant (X-axis
-                       main order), 1 = y,x,z (Y-axis main order)                       */
+                       main order), 1 = y,x,z (Y-axis main order).  2..5: the baselines of
+                       the set-partition ablation (Sec. 4.4), made by controlling the
+                       inner-window voxel ID: 2, 3 "Random" = order 0, 1 with the window's V
+                       cells shuffled, key -> (key*mul + add) mod V, mul = the smallest integer
+                       >= floor(0.618 V) + (axis odd) coprime to V, add = V/3 + (axis odd)
+                       (V <= 65536); 4, 5 "Sparse" = order 0, 1 with the ranks re-dealt: the
+                       voxel of rank d goes behind all voxels of a smaller d mod S, so every
+                       subset spreads over the whole window.  ("Regional" is order 0 in both
+                       layers of a block.)  dsvt_partition_xy and _xy_multi take an even
+                       value and produce the pair (axis, axis + 1).                       */
 } dsvt_part_cfg;
 
 /* Host-only.  Upper bound on the number of sets, floor(N/tau) + min(N, #windows), on the number

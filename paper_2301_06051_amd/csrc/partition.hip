@@ -23,6 +23,8 @@ struct PartGeom {
   uint32_t magic_tau;      // the same for tau (dividends up to a window's volume + tau), 0 when not exact; used by k_front
   int32_t words_per_win;   // 32-bit bitmap words per window (window volume rounded up to 32)
   int32_t n_windows;       // batch * nw[0] * nw[1] * nw[2]
+  uint32_t vol;            // cells of a window
+  uint32_t shuf_mul[2], shuf_add[2];   // the cell shuffle of inner orders 2 and 3 (see voxel_key)
 };
 
 // What differs between the two rotated partitions of one window configuration (Sec. 3.2): the order
@@ -72,10 +74,14 @@ __device__ __forceinline__ bool voxel_cell(const PartGeom& g, int4 c, uint32_t& 
 }
 
 // Composite key = window key * (32*words_per_win) + inner key; the inner key runs x-major for the
-// X-axis partition and y-major for the Y-axis one.
+// X-axis partition (even inner orders) and y-major for the Y-axis one (odd).  Inner orders 2 and 3 are the
+// "Random" baseline of the paper's set-partition ablation (Sec. 4.4), made by controlling the inner-window voxel
+// ID as the paper says: the window's cells in a fixed shuffle, key -> (key * mul + add) mod volume with mul
+// coprime to the volume.  (4 and 5, "Sparse", re-deal the ranks instead: see k_emit.)
 __device__ __forceinline__ uint32_t voxel_key(const PartGeom& g, int32_t axis, uint32_t wkey, int32_t xi, int32_t yi, int32_t zi) {
-  const uint32_t inner = axis == 0 ? (uint32_t)((xi * g.win[1] + yi) * g.win[2] + zi)
+  uint32_t inner = (axis & 1) == 0 ? (uint32_t)((xi * g.win[1] + yi) * g.win[2] + zi)
                                    : (uint32_t)((yi * g.win[0] + xi) * g.win[2] + zi);
+  if ((axis >> 1) == 1) inner = (inner * g.shuf_mul[axis & 1] + g.shuf_add[axis & 1]) % g.vol;   // (volume <= 2^16)
   return wkey * (uint32_t)(g.words_per_win * 32) + inner;
 }
 
@@ -951,6 +957,12 @@ __global__ void k_emit(Jobs jobs, const int4* __restrict__ coords, int32_t n, in
   }
   int64_t N = win_count[w];
   int64_t S = (N + tau - 1) / tau, T = S * tau;
+  if (((ax.axis0 + (int32_t)blockIdx.y) >> 1) == 2 && S > 1) {
+    // "Sparse" baseline (Sec. 4.4): every subset spread over the whole window.  The voxel of rank d goes behind
+    // all voxels of a smaller residue d mod S (residues below N mod S hold one voxel more), then Eq. 3 as usual.
+    const int64_t q = N / S, rem = N - q * S, r = d % S;
+    d = r * q + (r < rem ? r : rem) + d / S;
+  }
   int64_t t_lo, t_hi, first_d;                               // first_d: rank of the first voxel of this voxel's first set
   if (N > 0 && N < 32768 && T < 65536) {                     // the usual case: 32-bit division
     const uint32_t nn = (uint32_t)N, tt = (uint32_t)T, dd = (uint32_t)d;
@@ -1005,7 +1017,7 @@ struct PartPlan {
 };
 
 int make_plan(const dsvt_part_cfg* cfg, int32_t n_voxels, PartPlan* p) {
-  if (cfg == nullptr || n_voxels <= 0 || cfg->tau <= 0 || cfg->batch <= 0 || (cfg->axis != 0 && cfg->axis != 1))
+  if (cfg == nullptr || n_voxels <= 0 || cfg->tau <= 0 || cfg->batch <= 0 || cfg->axis < 0 || cfg->axis > 5)
     return DSVT_EINVAL;
   PartGeom& g = p->g;
   int64_t vol = 1, nwin = cfg->batch;
@@ -1021,6 +1033,16 @@ int make_plan(const dsvt_part_cfg* cfg, int32_t n_voxels, PartPlan* p) {
   }
   g.batch = cfg->batch; g.tau = cfg->tau;
   g.magic_tau = 0u;
+  g.vol = (uint32_t)vol;
+  if ((cfg->axis >> 1) == 1 && vol > (1 << 16)) return DSVT_EUNSUPPORTED;   // key * mul must fit 32 bits
+  for (int odd = 0; odd < 2; ++odd) {
+    int64_t mul = (int64_t)(0.618 * (double)vol);
+    mul = (mul < 1 ? 1 : mul) + odd;
+    auto gcd = [](int64_t a, int64_t b) { while (b) { const int64_t t = a % b; a = b; b = t; } return a; };
+    while (gcd(mul, vol) != 1) ++mul;
+    g.shuf_mul[odd] = (uint32_t)(mul % vol);
+    g.shuf_add[odd] = (uint32_t)((vol / 3 + odd) % vol);
+  }
   int64_t wpw = dsvt_ceil_div(vol, 32);
   if (nwin * wpw * 32 >= (1ll << 31)) return DSVT_EINVAL;   // composite keys are 32-bit
   g.words_per_win = (int32_t)wpw;
@@ -1272,8 +1294,9 @@ extern "C" int dsvt_partition_xy(const dsvt_part_cfg* cfg, const int32_t* coords
                                  int32_t max_sets, int32_t* set_win, const dsvt_tile_list* tiles, int32_t* tile_desc_y,
                                  void* ws, size_t ws_bytes, int32_t* status, void* stream) {
   if (cfg == nullptr) return DSVT_EINVAL;
-  const PartRequest r = {cfg, 2, 0, {set_inds_x, set_inds_y}, {voxel_slot_x, voxel_slot_y}, n_sets, set_win, max_sets, tiles,
-                         tile_desc_y, ws, ws_bytes, status};
+  if (cfg->axis & 1) return DSVT_EINVAL;                      // the pair is (axis, axis + 1)
+  const PartRequest r = {cfg, 2, cfg->axis, {set_inds_x, set_inds_y}, {voxel_slot_x, voxel_slot_y}, n_sets, set_win, max_sets,
+                         tiles, tile_desc_y, ws, ws_bytes, status};
   return run_partitions(&r, 1, coords, n_voxels, stream);
 }
 
@@ -1283,8 +1306,9 @@ extern "C" int dsvt_partition_xy_multi(const dsvt_xy_job* jobs, int32_t n_jobs, 
   PartRequest r[kMaxJobs];
   for (int32_t q = 0; q < n_jobs; ++q) {
     const dsvt_xy_job& j = jobs[q];
-    r[q] = PartRequest{&j.cfg, 2, 0, {j.set_inds_x, j.set_inds_y}, {j.voxel_slot_x, j.voxel_slot_y}, j.n_sets, j.set_win,
-                       j.max_sets, j.tiles, j.tile_desc_y, j.ws, j.ws_bytes, j.status};
+    if (j.cfg.axis & 1) return DSVT_EINVAL;
+    r[q] = PartRequest{&j.cfg, 2, j.cfg.axis, {j.set_inds_x, j.set_inds_y}, {j.voxel_slot_x, j.voxel_slot_y}, j.n_sets,
+                       j.set_win, j.max_sets, j.tiles, j.tile_desc_y, j.ws, j.ws_bytes, j.status};
   }
   return run_partitions(r, n_jobs, coords, n_voxels, stream);
 }

@@ -678,3 +678,49 @@ def test_bev_scatter_bit_exact(dt, C, grid, batch, n):
     assert int(status2.item()) & 1
     ref2 = ref.copy(); ref2[tuple(coords[3])] = 0
     assert np.array_equal(out2.float().cpu().numpy(), ref2.astype(np.float32))
+
+
+# ------------------------------------------------- set-partition baselines of the ablation (Sec. 4.4)
+@pytest.mark.parametrize("cid,n", [(1, None), (2, 9000), (3, 20000), (5, 30000)])
+@pytest.mark.parametrize("axis", [2, 3, 4, 5])
+def test_partition_variants_bit_exact(cid, n, axis):
+    """Random (2, 3) and Sparse (4, 5) inner-window orders: single-map call, through the small-frame and the
+    general front end (cfg 5's windows hold up to 1,800 voxels)."""
+    cfg = synth.CONFIGS[cid]
+    coords = synth.make_frame(cid, n=n)
+    shift = cfg["shifts"][-1]
+    _say(f"partition variant axis={axis} cfg{cid} n={len(coords)}")
+    om = orc.partition(coords, cfg["grid"], cfg["win"], shift, cfg["tau"], axis)
+    assert_maps_equal(gpu_maps(dev_coords(coords), cfg["grid"], cfg["win"], shift, cfg["tau"], cfg["batch"], axis), om)
+
+
+@pytest.mark.parametrize("axis0", [2, 4])
+def test_partition_variant_pairs_and_block(axis0):
+    """The pair call yields (axis0, axis0 + 1); a block run on those maps matches the oracle's block on its own.
+    Regional = the X-axis order in both layers."""
+    cfg = synth.CONFIGS[2]
+    coords = synth.make_frame(2, n=6000)
+    x = synth.make_features(91, len(coords), cfg["C"], "bf16")
+    ws = [synth.make_layer_weights(92 + a, cfg["C"], cfg["heads"], cfg["hidden"], cfg["win"], "bf16") for a in (0, 1)]
+    _say(f"variant pair axis0={axis0} + block; regional block")
+    cd = dev_coords(coords)
+    pair = dsvt.dsvt_partition_xy(dsvt.part_cfg(cfg["grid"], cfg["win"], (6, 6, 0), cfg["tau"], 1, axis0), cd)
+    oms = [orc.partition(coords, cfg["grid"], cfg["win"], (6, 6, 0), cfg["tau"], axis0 + k) for k in (0, 1)]
+    for k in (0, 1):
+        assert_maps_equal(pair[k], oms[k])
+    lw = [dsvt.LayerWeights(w) for w in ws]
+    out = dsvt.dsvt_block(lw, pair, cd, dev_feats(x, "bf16"))
+    err = rel_err(out, orc.block(ws, oms, coords, x))
+    _say(f"  rel err {err:.3e}")
+    assert err < TOL["bf16"]
+    if axis0 == 2:
+        om0 = orc.partition(coords, cfg["grid"], cfg["win"], (6, 6, 0), cfg["tau"], 0)
+        gm0 = gpu_maps(cd, cfg["grid"], cfg["win"], (6, 6, 0), cfg["tau"], 1, 0)
+        err = rel_err(dsvt.dsvt_block(lw, [gm0, gm0], cd, dev_feats(x, "bf16")), orc.block(ws, [om0, om0], coords, x))
+        _say(f"  regional rel err {err:.3e}")
+        assert err < TOL["bf16"]
+    # an odd first order has no pair
+    import ctypes as C
+    bad = dsvt.part_cfg(cfg["grid"], cfg["win"], (6, 6, 0), cfg["tau"], 1, 1)
+    with pytest.raises(dsvt.DsvtError):
+        dsvt.dsvt_partition_xy(bad, cd)

@@ -42,7 +42,9 @@ def test_host_only_calls_work_without_a_gpu():
     with pytest.raises(b.DsvtError):
         b.dsvt_partition_bound(b.part_cfg((468, 468, 1), (12, 12, 1), (12, 0, 0), 36, 1, 0), 30000)
     with pytest.raises(b.DsvtError):
-        b.dsvt_partition_bound(b.part_cfg((468, 468, 1), (12, 12, 1), (0, 0, 0), 36, 1, 2), 30000)
+        b.dsvt_partition_bound(b.part_cfg((468, 468, 1), (12, 12, 1), (0, 0, 0), 36, 1, 6), 30000)      # inner orders are 0..5
+    with pytest.raises(b.DsvtError):
+        b.dsvt_partition_bound(b.part_cfg((468, 468, 32), (48, 48, 32), (0, 0, 0), 36, 1, 2), 30000)   # shuffled order: window volume <= 65536
 
 
 def test_bench_refuses_more_than_one_gpu():
