@@ -25,7 +25,7 @@ import numpy as np
 # measurement and its commands are in profiles/hbm_traffic_pillar_frame.md.
 LAYER_HBM_BYTES_PER_LAUNCH = 28470 * 1024      # 17,220 KiB fetched + 11,250 KiB written
 
-STACKS = {"frame": 2, "voxel": 3, "skewed": 5}  # workload -> synth config id
+STACKS = {"frame": 2, "voxel": 3, "skewed": 5, "nuscenes": 6}  # workload -> synth config id
 
 
 def timed(run, steps, warmup):
@@ -188,9 +188,9 @@ def stack_workload(args, name):
                "sample": f"one full frame of the same workload ({N} voxels, 8 layers, 4 partitions), {cdt:.1f} s"}
 
     g, w, nb = cfg["grid"], cfg["win"], cfg["blocks"]
-    workload = (f"configs[{cid - 1}]: {g[0]}x{g[1]}x{g[2]} {'pillar' if g[2] == 1 else 'voxel'} frame"
+    workload = (f"{'configs[' + str(cid - 1) + ']' if cid <= 5 else 'nuScenes shape'}: {g[0]}x{g[1]}x{g[2]} {'pillar' if g[2] == 1 else 'voxel'} frame"
                 f"{'s, batch ' + str(cfg['batch']) if cfg['batch'] > 1 else ''}, {N} voxels, C={C}, {cfg['heads']} heads, "
-                f"tau={tau}, win {w[0]}x{w[1]}x{w[2]}, {nb} blocks x 2 layers, shift (6,6,0) on odd blocks")
+                f"tau={tau}, win {w[0]}x{w[1]}x{w[2]}, {nb} blocks x 2 layers, shift ({w[0] // 2},{w[1] // 2},0) on odd blocks")
     return {
         "metric": f"voxels/sec through the {nb}-block DSVT stack (partition + set attention); ms/frame {nb}-block",
         "value": round(N / (dt / args.steps), 1), "unit": "voxels/s", "dtype": "bf16",
@@ -346,7 +346,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", choices=["frame", "voxel", "skewed", "pool", "bev", "vfe"], default="frame")
+    ap.add_argument("--workload", choices=["frame", "voxel", "skewed", "nuscenes", "pool", "bev", "vfe"], default="frame")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of a captured HIP graph")
     ap.add_argument("--pmc-calibration", action="store_true",

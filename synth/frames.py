@@ -25,6 +25,10 @@ CONFIGS = {
             pool=(1, 1, 4)),
     5: dict(name="skewed_batch", grid=(468, 468, 32), n=200000, C=192, heads=8, hidden=384, tau=36,
             win=(12, 12, 32), shifts=((0, 0, 0), (6, 6, 0)), blocks=4, dtype="bf16", batch=4, kind="skewed"),
+    # the nuScenes variant's shape (appendix "3D Perception on nuScenes": 0.3 m pillars over +-54 m, windows of
+    # 30 x 30 pillars, set size 90, 128 channels)
+    6: dict(name="nuscenes_pillar_frame", grid=(360, 360, 1), n=20000, C=128, heads=8, hidden=256, tau=90,
+            win=(30, 30, 1), shifts=((0, 0, 0), (15, 15, 0)), blocks=4, dtype="bf16", batch=1, kind="radial"),
 }
 
 
