@@ -3,10 +3,11 @@
 // optional per-point linear map followed by the channel-wise maximum over each voxel's points.
 //
 // Voxels are found without a sort: an occupancy map over the grid's cells, in key order (a byte per cell while
-// the points mark it, then packed to bits), and a pop-count scan number the non-empty cells in ascending key; a counting sort by voxel (one returning atomic per point)
-// then copies each voxel's points into one run of rows, and workgroups of equal point counts take the maxima from LDS.
-// The order of a voxel's points in its run varies from call to call, the maximum does not.  Pure bandwidth:
-// points are read twice and copied once (20 bytes each), the feature rows written once.
+// the points mark it, then packed to bits), and a pop-count scan number the non-empty cells in ascending key; a
+// counting sort by voxel (one returning atomic per point) then copies each voxel's points into one run of rows,
+// and wavefronts with equal shares of those rows take the maxima from LDS.  The order of a voxel's points in its
+// run varies from call to call, the maximum does not.  Pure bandwidth: points are read twice and copied once,
+// the feature rows written once.
 #include "common.h"
 #include "block_scan.h"
 
