@@ -114,17 +114,6 @@ __device__ __forceinline__ void window_count(int32_t tid, uint32_t* __restrict__
   if (lane == 0) win_count[w] = (int32_t)running;
 }
 
-__global__ void k_window_count(AxisSet ax, int32_t* __restrict__ win_count, int32_t n_windows, int32_t words_per_win,
-                               int32_t group) {       // blockIdx.y = axis; every axis leaves the same counts
-  if (!ws_ready(ax)) {
-    const int32_t w = (blockIdx.x * blockDim.x + threadIdx.x) / group;
-    if (w < n_windows && blockIdx.y == 0) win_count[w] = 0;
-    return;
-  }
-  window_count(blockIdx.x * blockDim.x + threadIdx.x, ax.a[blockIdx.y].mark, ax.a[blockIdx.y].bitmap, ax.a[blockIdx.y].prefix,
-               win_count, n_windows, words_per_win, group);
-}
-
 // One workgroup: exclusive scans of voxels-per-window and sets-per-window (Eq. 2).
 __device__ __forceinline__ void scan_windows(const int32_t* __restrict__ win_count, int32_t* __restrict__ win_soff,
                                              int32_t n_windows, int32_t tau, int32_t max_sets,
@@ -161,14 +150,6 @@ __device__ __forceinline__ void scan_windows(const int32_t* __restrict__ win_cou
     *n_sets = carry_s;
     if (carry_s > max_sets) atomicOr(status, DSVT_ST_SET_OVERFLOW);
   }
-}
-
-__global__ void __launch_bounds__(1024) k_scan_windows(const int32_t* __restrict__ win_count,
-                                                       int32_t* __restrict__ win_soff, int32_t n_windows,
-                                                       int32_t tau, int32_t max_sets, int32_t* __restrict__ n_sets,
-                                                       int32_t* __restrict__ status, int32_t* __restrict__ set_w,
-                                                       int32_t set_cap) {
-  scan_windows(win_count, win_soff, n_windows, tau, max_sets, n_sets, status, set_w, set_cap);
 }
 
 // Tile descriptor, one per workgroup tile of the layer kernels, in launch order (256 ints):
@@ -544,12 +525,46 @@ __device__ __forceinline__ void build_tiles(const int32_t* set_w, const int32_t*
   }
 }
 
-__global__ void __launch_bounds__(1024) k_tiles(const int32_t* set_w, const int32_t* win_count, const int32_t* win_soff,
-                                                const int32_t* n_sets_ptr, int32_t set_cap, int32_t tau, int32_t n_windows,
-                                                int32_t rows_per_cut, TileOut out, int32_t* tile_rows, int32_t* tile_pos,
-                                                int32_t* set_p, int32_t* set_loc, int32_t fill_sets) {
-  build_tiles(set_w, win_count, win_soff, n_sets_ptr, set_cap, tau, n_windows, rows_per_cut, out, tile_rows, tile_pos, set_p,
-              set_loc, fill_sets);
+// The general front end's own arguments for one window configuration (frames too large for k_front).
+struct GenJob {
+  int32_t *ws_setwin, *tile_rows, *tile_pos, *set_p;
+  int32_t set_bound, want_tiles, fill_sets;
+};
+struct GenJobs { GenJob j[kMaxJobs]; };
+
+// A slice of a wavefront per window: zero the mark words, copy them, count them (blockIdx.y = axis, every axis
+// leaves the same counts; blockIdx.z = job).
+__global__ void k_window_count(Jobs jobs) {
+  const Job& J = jobs.j[blockIdx.z];
+  const AxisSet& ax = J.ax;
+  if ((int32_t)blockIdx.y >= ax.n) return;
+  const int32_t n_windows = J.g.n_windows, words_per_win = J.g.words_per_win;
+  int32_t group = 1;
+  while (group < 64 && group < words_per_win) group <<= 1;
+  const int32_t tid = blockIdx.x * blockDim.x + threadIdx.x;
+  if (!ws_ready(ax)) {
+    const int32_t w = tid / group;
+    if (w < n_windows && blockIdx.y == 0 && (tid & (group - 1)) == 0) J.win_count[w] = 0;
+    return;
+  }
+  window_count(tid, ax.a[blockIdx.y].mark, ax.a[blockIdx.y].bitmap, ax.a[blockIdx.y].prefix, J.win_count, n_windows,
+               words_per_win, group);
+}
+
+// One workgroup per job.
+__global__ void __launch_bounds__(1024) k_scan_windows(Jobs jobs, GenJobs gen) {
+  const Job& J = jobs.j[blockIdx.x];
+  const GenJob& G = gen.j[blockIdx.x];
+  scan_windows(J.win_count, J.win_soff, J.g.n_windows, J.g.tau, J.max_sets, J.n_sets, J.status, G.ws_setwin, G.set_bound);
+}
+
+// One workgroup per job that wants a work list.
+__global__ void __launch_bounds__(1024) k_tiles(Jobs jobs, GenJobs gen) {
+  const Job& J = jobs.j[blockIdx.x];
+  const GenJob& G = gen.j[blockIdx.x];
+  if (!G.want_tiles) return;
+  build_tiles(G.ws_setwin, J.win_count, J.win_soff, J.n_sets, J.set_cap, J.g.tau, J.g.n_windows, J.rows_per_cut, J.out,
+              G.tile_rows, G.tile_pos, G.set_p, J.set_loc, G.fill_sets);
 }
 
 #ifdef DSVT_PHASE_CLOCKS
@@ -1173,78 +1188,87 @@ int prepare(const PartRequest& r, int32_t n_voxels, Prepared* out) {
 int run_partitions(const PartRequest* reqs, int32_t n, const int32_t* coords, int32_t n_voxels, void* stream) {
   if (n <= 0 || n > kMaxJobs || !reqs || !coords) return DSVT_EINVAL;
   Prepared prep[kMaxJobs];
-  bool all_front = true;
   for (int32_t q = 0; q < n; ++q) {
     if (reqs[q].cfg == nullptr || reqs[q].n_axes != reqs[0].n_axes) return DSVT_EINVAL;
     int rc = prepare(reqs[q], n_voxels, &prep[q]);
     if (rc != DSVT_OK) return rc;
-    all_front = all_front && prep[q].front_ok;
   }
   hipStream_t st = (hipStream_t)stream;
   const int tb = 256;
   const int32_t n_axes = reqs[0].n_axes;
   const int32_t vox_blocks = (int32_t)dsvt_ceil_div(n_voxels, tb);
-  for (int32_t q0 = 0; q0 < n; q0 += all_front ? n : 1) {
-    const int32_t nq = all_front ? n : 1;
-    Jobs jobs = {};
-    size_t lds = 0;
-    int32_t max_tiles = 0;
-    for (int32_t q = 0; q < nq; ++q) {
-      jobs.j[q] = prep[q0 + q].job;
-      lds = prep[q0 + q].front_lds > lds ? prep[q0 + q].front_lds : lds;
-      max_tiles = jobs.j[q].out.max_tiles > max_tiles ? jobs.j[q].out.max_tiles : max_tiles;
-    }
-    {
-      dsvt_prof_scope ps(DSVT_K_PART_MARK, st);
-      k_mark<<<dim3((unsigned)vox_blocks, nq), tb, 0, st>>>(jobs, (const int4*)coords, n_voxels);
-    }
-    if (all_front) {
-      static std::atomic<uint64_t> front_allowed[2];
-      auto* front = n_axes == 2 ? k_front<2> : k_front<1>;
-      if (int rc = dsvt_allow_lds((const void*)front, kFrontLds, front_allowed[n_axes - 1])) return rc;
-      dsvt_prof_scope ps(DSVT_K_PART_TILES, st);
-      front<<<nq, 1024, lds, st>>>(jobs
-#ifdef DSVT_PHASE_CLOCKS
-                                   , g_front_clocks
-#endif
-                                   );
+  // One chain of launches for all jobs: mark, then the single-workgroup front end for the jobs it can hold and
+  // the general one (three launches) for the others, then emit.
+  Jobs jobs = {}, front_jobs = {}, gen_jobs = {};
+  GenJobs gen = {};
+  int32_t n_front = 0, n_gen = 0, max_tiles = 0, any_tiles = 0;
+  size_t front_lds = 0, fill_lds = 0;
+  int64_t count_threads = 0;
+  for (int32_t q = 0; q < n; ++q) {
+    const Prepared& P = prep[q];
+    jobs.j[q] = P.job;
+    max_tiles = P.job.out.max_tiles > max_tiles ? P.job.out.max_tiles : max_tiles;
+    if (P.front_ok) {
+      front_jobs.j[n_front++] = P.job;
+      front_lds = P.front_lds > front_lds ? P.front_lds : front_lds;
     } else {
-      const Prepared& P = prep[q0];
       const PartPlan& p = P.p;
-      const Job& J = P.job;
-      char* base = (char*)reqs[q0].ws;
+      char* base = (char*)reqs[q].ws;
+      GenJob& G = gen.j[n_gen];
+      G.ws_setwin = (int32_t*)(base + p.off_setwin);
+      G.tile_rows = (int32_t*)(base + p.off_tilerows);
+      G.tile_pos = (int32_t*)(base + p.off_tilepos);
+      G.set_p = (int32_t*)(base + p.off_setp);
+      G.set_bound = p.set_bound;
+      G.want_tiles = P.want_tiles ? 1 : 0;
+      // tables of the tile filling (see build_tiles), when this frame's sets fit the LDS
+      const size_t need = ((size_t)p.set_bound + 1) * 9 + 16;
+      G.fill_sets = (P.want_tiles && need <= kFrontLds) ? p.set_bound : 0;
+      if (G.fill_sets) fill_lds = need > fill_lds ? need : fill_lds;
+      any_tiles |= G.want_tiles;
       int32_t group = 1;
       while (group < 64 && group < p.g.words_per_win) group <<= 1;
-      {
-        dsvt_prof_scope ps(DSVT_K_PART_COUNT, st);
-        int64_t threads = (int64_t)p.g.n_windows * group;
-        k_window_count<<<dim3((unsigned)dsvt_ceil_div(threads, tb), n_axes), tb, 0, st>>>(J.ax, J.win_count, p.g.n_windows,
-                                                                                         p.g.words_per_win, group);
-      }
-      {
-        dsvt_prof_scope ps(DSVT_K_PART_SCAN, st);
-        k_scan_windows<<<1, 1024, 0, st>>>(J.win_count, J.win_soff, p.g.n_windows, p.g.tau, J.max_sets, J.n_sets, J.status,
-                                           (int32_t*)(base + p.off_setwin), p.set_bound);
-      }
-      if (P.want_tiles) {
-        dsvt_prof_scope ps(DSVT_K_PART_TILES, st);
-        // tables of the tile filling (see build_tiles), when this frame's sets fit the LDS
-        const size_t fill_lds = ((size_t)p.set_bound + 1) * 9 + 16;
-        const bool fill_ok = fill_lds <= kFrontLds;
-        static std::atomic<uint64_t> tiles_allowed{0};
-        if (fill_ok)
-          if (int rc = dsvt_allow_lds((const void*)k_tiles, kFrontLds, tiles_allowed)) return rc;
-        k_tiles<<<1, 1024, fill_ok ? fill_lds : 0, st>>>((const int32_t*)(base + p.off_setwin), J.win_count, J.win_soff, J.n_sets, J.set_cap,
-                                    p.g.tau, p.g.n_windows, p.rows_per_cut, J.out, (int32_t*)(base + p.off_tilerows),
-                                    (int32_t*)(base + p.off_tilepos), (int32_t*)(base + p.off_setp), J.set_loc,
-                                    fill_ok ? p.set_bound : 0);
-      }
+      const int64_t threads = (int64_t)p.g.n_windows * group;
+      count_threads = threads > count_threads ? threads : count_threads;
+      gen_jobs.j[n_gen++] = P.job;
+    }
+  }
+  {
+    dsvt_prof_scope ps(DSVT_K_PART_MARK, st);
+    k_mark<<<dim3((unsigned)vox_blocks, n), tb, 0, st>>>(jobs, (const int4*)coords, n_voxels);
+  }
+  if (n_front) {
+    static std::atomic<uint64_t> front_allowed[2];
+    auto* front = n_axes == 2 ? k_front<2> : k_front<1>;
+    if (int rc = dsvt_allow_lds((const void*)front, kFrontLds, front_allowed[n_axes - 1])) return rc;
+    dsvt_prof_scope ps(DSVT_K_PART_TILES, st);
+    front<<<n_front, 1024, front_lds, st>>>(front_jobs
+#ifdef DSVT_PHASE_CLOCKS
+                                            , g_front_clocks
+#endif
+                                            );
+  }
+  if (n_gen) {
+    {
+      dsvt_prof_scope ps(DSVT_K_PART_COUNT, st);
+      k_window_count<<<dim3((unsigned)dsvt_ceil_div(count_threads, tb), n_axes, n_gen), tb, 0, st>>>(gen_jobs);
     }
     {
-      dsvt_prof_scope ps(DSVT_K_PART_EMIT, st);
-      const int32_t tail_blocks = (int32_t)dsvt_ceil_div((int64_t)max_tiles * 16, tb);
-      k_emit<<<dim3((unsigned)(vox_blocks + tail_blocks), n_axes, nq), tb, 0, st>>>(jobs, (const int4*)coords, n_voxels, vox_blocks);
+      dsvt_prof_scope ps(DSVT_K_PART_SCAN, st);
+      k_scan_windows<<<n_gen, 1024, 0, st>>>(gen_jobs, gen);
     }
+    if (any_tiles) {
+      dsvt_prof_scope ps(DSVT_K_PART_TILES, st);
+      static std::atomic<uint64_t> tiles_allowed{0};
+      if (fill_lds)
+        if (int rc = dsvt_allow_lds((const void*)k_tiles, kFrontLds, tiles_allowed)) return rc;
+      k_tiles<<<n_gen, 1024, fill_lds, st>>>(gen_jobs, gen);
+    }
+  }
+  {
+    dsvt_prof_scope ps(DSVT_K_PART_EMIT, st);
+    const int32_t tail_blocks = (int32_t)dsvt_ceil_div((int64_t)max_tiles * 16, tb);
+    k_emit<<<dim3((unsigned)(vox_blocks + tail_blocks), n_axes, n), tb, 0, st>>>(jobs, (const int4*)coords, n_voxels, vox_blocks);
   }
   DSVT_HIP_TRY(hipGetLastError());
   return DSVT_OK;
