@@ -79,6 +79,22 @@ def test_partition_xy_multi_bit_exact(cid, n):
         for axis in (0, 1):
             assert_maps_equal(out[axis], orc.partition(coords, cfg["grid"], cfg["win"], sh, tau, axis))
 
+def test_partition_xy_multi_mixed_front_ends():
+    """One call whose window configurations take different front ends: 12 x 12 windows (a frame's tables fit one
+    workgroup's LDS), 3 x 3 windows (24,000 windows: the general chain), and 24 x 24 windows with a large set."""
+    cfg = synth.CONFIGS[2]
+    coords = synth.make_frame(2, n=20000)
+    variants = [((12, 12, 1), (6, 6, 0), 36), ((3, 3, 1), (1, 2, 0), 4), ((24, 24, 1), (12, 12, 0), 90), ((3, 3, 1), (0, 0, 0), 5)]
+    _say("partition_xy_multi with mixed front ends")
+    pcs = [dsvt.part_cfg(cfg["grid"], win, sh, tau, 1, 0) for win, sh, tau in variants]
+    outs = [dsvt.SetMapsXY(pc, len(coords)) for pc in pcs]
+    cd = dev_coords(coords)
+    for _ in range(2):
+        dsvt.dsvt_partition_xy_multi(pcs, cd, outs)
+    for (win, sh, tau), out in zip(variants, outs):
+        for axis in (0, 1):
+            assert_maps_equal(out[axis], orc.partition(coords, cfg["grid"], win, sh, tau, axis))
+
 
 @pytest.mark.parametrize("n", [300, 3000, 12000, 20000])
 def test_small_frames_spread_over_the_compute_units(n):
