@@ -140,6 +140,52 @@ def stack_workload(args, name):
     dt = timed(run, args.steps, args.warmup)
     step_ms = percentiles(run, min(args.steps, 100))
 
+    # Optional: a serving loop keeps two frames in flight, each with its own maps and feature buffer on a stream of
+    # its own, so that one frame's partition and the ramp and tail of its launches are filled by the other's tiles.
+    # Every step is still one whole frame; steps that share buffers are on the same stream.  Reported beside the
+    # single-stream figures, never instead of them.
+    in_flight = None
+    if args.frames_in_flight == 2 and use_graph:
+        maps_b = {sh: dsvt.SetMapsXY(pc, N) for sh, pc in pcfgs.items()}
+        buf_b = torch.empty_like(x0)
+
+        def step_b():
+            dsvt.dsvt_partition_xy_multi([pcfgs[sh] for sh in shifts], cd, [maps_b[sh] for sh in shifts])
+            src = x0
+            for b, pair in enumerate(layers):
+                dsvt.dsvt_block(pair, maps_b[shifts[b % len(shifts)]], cd, src, x_out=buf_b, ws=ws)
+                src = buf_b
+
+        def check_b(replay):
+            buf_b.zero_()
+            replay()
+            torch.cuda.synchronize()
+            assert torch.equal(buf_b, eager_out), "graph replay differs from eager launches"
+
+        streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+        with torch.cuda.stream(streams[1]):
+            run_b = capture(step_b, check_b)
+        torch.cuda.synchronize()
+        runs = (run, run_b)
+
+        def pump(k):
+            with torch.cuda.stream(streams[k % 2]):
+                runs[k % 2]()
+
+        for k in range(args.warmup):
+            pump(k)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(args.steps):
+            pump(k)
+        torch.cuda.synchronize()
+        t2 = (time.perf_counter() - t0) / args.steps
+        buf.zero_(); buf_b.zero_()
+        pump(0); pump(1)
+        torch.cuda.synchronize()
+        assert torch.equal(buf, eager_out) and torch.equal(buf_b, eager_out), "pipelined frames differ from eager launches"
+        in_flight = {"frames": 2, "ms_per_frame": round(t2 * 1e3, 4), "voxels_per_s": round(N / t2, 1)}
+
     # One DSVT block on its own (the paper's per-block latency): both rotated partitions of one window
     # configuration plus the block's two layers, and the block alone with the maps reused.
     def one_block():
@@ -196,7 +242,7 @@ def stack_workload(args, name):
         "value": round(N / (dt / args.steps), 1), "unit": "voxels/s", "dtype": "bf16",
         "config": {"workload": workload, "launch": "hip_graph" if use_graph else "eager",
                    "n_sets": {"shift" + "_".join(map(str, k)): v for k, v in n_sets.items()}, "rho": round(float(rho), 4)},
-        "ms_per_frame": round(dt / args.steps * 1e3, 4), "step_ms": step_ms, "one_block": one,
+        "ms_per_frame": round(dt / args.steps * 1e3, 4), "step_ms": step_ms, "one_block": one, "two_frames_in_flight": in_flight,
         "kernel_ms_per_step": {k: round(v, 4) for k, v in per_step_ms.items()},
         "kernel_us_per_launch": {k: round(v, 2) for k, v in per_launch_us.items()},
         "roofline": roofline, "cpu_baseline": cpu,
@@ -349,6 +395,9 @@ def main():
     ap.add_argument("--workload", choices=["frame", "voxel", "skewed", "nuscenes", "pool", "bev", "vfe"], default="frame")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of a captured HIP graph")
+    ap.add_argument("--frames-in-flight", type=int, choices=[1, 2], default=2,
+                    help="2: also time a loop that keeps two frames in flight on two streams (an extra field of the JSON "
+                         "line; `value` and `ms_per_step` are always the single-stream figures)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one plain 256 MiB device copy (a kernel of known traffic, to scale rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE readings)")
