@@ -273,7 +273,7 @@ struct SetWalk {
   __device__ __forceinline__ int32_t next() {               // distinct voxels of the next set
     uint32_t q2 = q + dq, r2 = r + dr;
     if (r2 >= S) { r2 -= S; ++q2; }
-    const uint32_t nu = q2 - (small ? (__umul24(r2, tau) < N ? 1u : 0u) : (r2 * tau < N ? 1u : 0u)) - q + 1u;
+    const uint32_t nu = q2 - (small ? ((uint32_t)__umul24(r2, tau) < N ? 1u : 0u) : (r2 * tau < N ? 1u : 0u)) - q + 1u;
     q = q2; r = r2;
     return (int32_t)nu;
   }

@@ -11,7 +11,7 @@ from oracle import dsvt_oracle as orc
 pytestmark = pytest.mark.gpu
 
 dsvt = pytest.importorskip("paper_2301_06051_amd")
-from gpu_util import TOL, assert_maps_equal, rel_err  # noqa: E402
+from gpu_util import assert_maps_equal, rel_err  # noqa: E402
 
 WAYMO_LO, WAYMO_HI = (-74.88, -74.88, -2.0), (74.88, 74.88, 4.0)
 
