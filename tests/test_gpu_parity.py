@@ -742,3 +742,28 @@ def test_partition_variant_pairs_and_block(axis0):
     bad = dsvt.part_cfg(cfg["grid"], cfg["win"], (6, 6, 0), cfg["tau"], 1, 1)
     with pytest.raises(dsvt.DsvtError):
         dsvt.dsvt_partition_xy(bad, cd)
+
+
+@pytest.mark.parametrize("seed", list(range(16)))
+def test_partition_seeded_random_geometries(seed):
+    """Seeded draws of grid, window, shift, set size, frame count and voxel count (all valid inputs): the paired
+    call's maps equal the oracle's bit for bit and the work list is a valid tiling, whatever front end and tile
+    policy the sizes select."""
+    rng = np.random.Generator(np.random.Philox(7000 + seed))
+    win = (int(rng.integers(2, 25)), int(rng.integers(2, 25)), int(rng.choice([1, 1, 2, 4, 8])))
+    grid = (int(rng.integers(win[0], 300)), int(rng.integers(win[1], 300)), int(win[2] * rng.integers(1, 4)))
+    shift = tuple(int(rng.integers(0, w)) for w in win)
+    tau = int(rng.choice([4, 7, 12, 24, 36, 48, 60, 90]))
+    batch = int(rng.choice([1, 1, 2, 3]))
+    cells = grid[0] * grid[1] * grid[2]
+    n = int(min(rng.integers(1, 40000), max(cells // 3, 1)))
+    kind = int(rng.integers(0, 2))
+    frames = []
+    for b in range(batch):
+        c = synth.frame_radial(7100 + 16 * seed + b, grid, n) if kind else synth.frame_uniform(7100 + 16 * seed + b, grid, n)
+        frames.append(np.concatenate([np.full((len(c), 1), b, np.int64), c], 1))
+    coords = np.concatenate(frames).astype(np.int32)
+    _say(f"random geometry seed={seed} grid={grid} win={win} shift={shift} tau={tau} batch={batch} n={len(coords)}")
+    pair = dsvt.dsvt_partition_xy(dsvt.part_cfg(grid, win, shift, tau, batch, 0), dev_coords(coords))
+    for axis in (0, 1):
+        assert_maps_equal(pair[axis], orc.partition(coords, grid, win, shift, tau, axis))
