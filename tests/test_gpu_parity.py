@@ -767,3 +767,31 @@ def test_partition_seeded_random_geometries(seed):
     pair = dsvt.dsvt_partition_xy(dsvt.part_cfg(grid, win, shift, tau, batch, 0), dev_coords(coords))
     for axis in (0, 1):
         assert_maps_equal(pair[axis], orc.partition(coords, grid, win, shift, tau, axis))
+
+
+@pytest.mark.parametrize("seed", list(range(10)))
+def test_block_seeded_random_shapes(seed):
+    """Seeded draws of channel width, set size, window, shift and voxel count among the supported shapes: one block
+    (paired partition call, both layers) against the oracle."""
+    rng = np.random.Generator(np.random.Philox(7500 + seed))
+    C, heads, hidden, dt = [(64, 4, 128, "f32"), (64, 4, 128, "bf16"), (128, 8, 256, "bf16"), (192, 8, 384, "bf16")][int(rng.integers(0, 4))]
+    win = (int(rng.integers(3, 20)), int(rng.integers(3, 20)), int(rng.choice([1, 1, 2, 4])))
+    grid = (int(rng.integers(win[0], 160)), int(rng.integers(win[1], 160)), int(win[2] * rng.integers(1, 3)))
+    shift = tuple(int(rng.integers(0, w)) for w in win)
+    tau = int(rng.choice([8, 20, 36, 48, 64, 90]))
+    n = int(min(rng.integers(50, 9000), max(grid[0] * grid[1] * grid[2] // 3, 1)))
+    coords = np.concatenate([np.zeros((n, 1), np.int64), synth.frame_radial(7600 + seed, grid, n)], 1).astype(np.int32)
+    x = synth.make_features(7700 + seed, len(coords), C, dt)
+    ws = [synth.make_layer_weights(7800 + 2 * seed + a, C, heads, hidden, win, dt) for a in (0, 1)]
+    _say(f"random block seed={seed} C={C} {dt} grid={grid} win={win} shift={shift} tau={tau} n={n}")
+    oms = [orc.partition(coords, grid, win, shift, tau, a) for a in (0, 1)]
+    ref = orc.block(ws, oms, coords, x)
+    cd = dev_coords(coords)
+    gms = dsvt.dsvt_partition_xy(dsvt.part_cfg(grid, win, shift, tau, 1, 0), cd)
+    for gm, om in zip(gms, oms):
+        assert_maps_equal(gm, om)
+    out = dsvt.dsvt_block([dsvt.LayerWeights(w) for w in ws], gms, cd, dev_feats(x, dt))
+    torch.cuda.synchronize()
+    err = rel_err(out, ref)
+    _say(f"  rel err {err:.3e}")
+    assert err < TOL[dt]
