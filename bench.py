@@ -195,17 +195,21 @@ def stack_workload(args, name):
     def block_only():
         dsvt.dsvt_block(layers[0], maps[shifts[0]], cd, x0, x_out=buf, ws=ws)
 
+    def partition_only():
+        dsvt.dsvt_partition_xy(pcfgs[shifts[0]], cd, out=maps[shifts[0]])
+
     one = {}
-    for key, fn in (("partition_and_block", one_block), ("block_maps_reused", block_only)):
+    for key, fn in (("partition_and_block", one_block), ("block_maps_reused", block_only), ("partition_xy_only", partition_only)):
         fn()
         torch.cuda.synchronize()
-        ref = buf.clone()
+        watched = maps[shifts[0]].y.voxel_slot if key == "partition_xy_only" else buf
+        ref = watched.clone()
 
-        def check_one(replay):
-            buf.zero_()
+        def check_one(replay, watched=watched, ref=ref):
+            watched.zero_()
             replay()
             torch.cuda.synchronize()
-            assert torch.equal(buf, ref), "graph replay differs from eager launches"
+            assert torch.equal(watched, ref), "graph replay differs from eager launches"
 
         t = timed(capture(fn, check_one) if use_graph else fn, args.steps, args.warmup) / args.steps
         one[key] = {"ms": round(t * 1e3, 4), "voxels_per_s": round(N / t, 1)}
