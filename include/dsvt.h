@@ -199,7 +199,8 @@ typedef struct {
 int dsvt_layer_packed_size(const dsvt_layer_w* layer, size_t* bytes);
 int dsvt_layer_pack(const dsvt_layer_w* layer, void* packed, size_t bytes, void* stream);
 
-/* Host-only: scratch bytes the two calls below need (currently 0; callers must still ask). */
+/* Host-only: scratch bytes the two calls below need (currently 0 for both; callers must still ask). */
+int dsvt_set_attention_workspace_size(const dsvt_layer_w* layer, int32_t n_voxels, size_t* bytes);
 int dsvt_block_workspace_size(const dsvt_layer_w* layer, int32_t n_voxels, size_t* bytes);
 
 /* y = MHSA over every set (Eq. 5, first two lines: INDEX, then attention with PE), out-projected

@@ -87,6 +87,7 @@ def lib():
         L.dsvt_layer_packed_size.argtypes = [C.POINTER(LayerW), C.POINTER(sz)]
         L.dsvt_layer_pack.argtypes = [C.POINTER(LayerW), vp, sz, vp]
         L.dsvt_block_workspace_size.argtypes = [C.POINTER(LayerW), i32, C.POINTER(sz)]
+        L.dsvt_set_attention_workspace_size.argtypes = [C.POINTER(LayerW), i32, C.POINTER(sz)]
         L.dsvt_set_attention.argtypes = [C.POINTER(LayerW), C.POINTER(Maps), vp, vp, vp, vp, sz, vp]
         L.dsvt_block.argtypes = [C.POINTER(LayerW), C.POINTER(Maps), vp, vp, vp, vp, sz, vp]
         L.dsvt_pool_packed_size.argtypes = [C.POINTER(PoolCfg), C.POINTER(sz)]
@@ -267,6 +268,13 @@ class LayerWeights:
         self.packed = torch.empty((nbytes.value,), dtype=torch.uint8, device="cuda")
         _check("dsvt_layer_pack", lib().dsvt_layer_pack(C.byref(self.struct), _ptr(self.packed), nbytes.value, _stream(None)))
         self.struct.packed = self.packed.data_ptr()
+
+
+def dsvt_set_attention_workspace_size(layer, n_voxels):
+    sz = C.c_size_t(0)
+    _check("dsvt_set_attention_workspace_size",
+           lib().dsvt_set_attention_workspace_size(C.byref(layer.struct), n_voxels, C.byref(sz)))
+    return sz.value
 
 
 def dsvt_block_workspace_size(layer, n_voxels):

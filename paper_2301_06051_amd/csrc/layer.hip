@@ -731,6 +731,12 @@ extern "C" int dsvt_layer_pack(const dsvt_layer_w* layer, void* packed, size_t b
   return DSVT_OK;
 }
 
+extern "C" int dsvt_set_attention_workspace_size(const dsvt_layer_w* layer, int32_t n_voxels, size_t* bytes) {
+  if (!layer || !bytes || n_voxels <= 0) return DSVT_EINVAL;
+  *bytes = 0;
+  return DSVT_OK;
+}
+
 extern "C" int dsvt_block_workspace_size(const dsvt_layer_w* layer, int32_t n_voxels, size_t* bytes) {
   if (!layer || !bytes || n_voxels <= 0) return DSVT_EINVAL;
   *bytes = 0;
