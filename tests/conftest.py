@@ -15,3 +15,23 @@ def pytest_configure(config):
 @pytest.fixture(scope="session")
 def golden_dir():
     return os.path.join(ROOT, "tests", "golden")
+
+
+def pytest_collection_modifyitems(config, items):
+    """Without a GPU the tests marked `gpu` are skipped rather than failed in a plain `pytest tests` on a CPU machine.
+    A run that asks for them (`-m gpu`) gets them whatever the machine says, so that a GPU machine without a visible
+    GPU fails loudly instead of skipping."""
+    markexpr = config.getoption("markexpr", "") or ""
+    if "gpu" in markexpr and "not gpu" not in markexpr:
+        return
+    try:
+        import torch
+        have_gpu = torch.cuda.is_available()
+    except Exception:
+        have_gpu = False
+    if have_gpu:
+        return
+    skip = pytest.mark.skip(reason="needs a GPU")
+    for item in items:
+        if "gpu" in item.keywords:
+            item.add_marker(skip)
