@@ -38,8 +38,10 @@ LN(P + Attn(P, region)); voxel feature encoding = max over the voxel's points
 of (W f + b), voxels in ascending cell key, the cell of a point decided in
 float32 (subtract, divide, compare) so that both sides take the same decision.
 Parity unpinned by the paper itself: the PE form, the pooling wrapper
-(residual + LN) and LN eps / GELU form -- they are pinned only to the stated
-reading (library LN / GELU / MHSA routines and brute force).
+(residual + LN), LN eps / GELU form, the voxel feature encoder's form and the
+Random / Sparse partition baselines (one sentence each in the paper) -- they
+are pinned only to the stated reading (library LN / GELU / MHSA routines,
+numpy's segmented maximum, brute force).
 """
 import numpy as np
 from scipy.special import erf
