@@ -265,30 +265,46 @@ def pool_workload(args):
     N = len(coords)
     cd = torch.as_tensor(coords).cuda()
     x = torch.as_tensor(synth.make_features(35, N, C, cfg["dtype"])).cuda().to(torch.bfloat16).contiguous()
-    pw = dsvt.PoolWeights(synth.make_pool_weights(91, C, cfg["heads"], cfg["dtype"]), cfg["grid"], pool, cfg["batch"], 0)
+    # keys / values = the region's occupied voxels, as the workload is worded (the paper's best variant, which keeps
+    # the empty cells as keys, is --pool-keep-empty)
+    mask_empty = 0 if args.pool_keep_empty else 1
+    pw = dsvt.PoolWeights(synth.make_pool_weights(91, C, cfg["heads"], cfg["dtype"]), cfg["grid"], pool, cfg["batch"], mask_empty)
     ws = torch.empty((max(dsvt.dsvt_attn_pool_workspace_size(pw, N), 1),), dtype=torch.uint8, device="cuda")
     out = (torch.zeros((N, 4), dtype=torch.int32, device="cuda"), torch.zeros_like(x),
            torch.zeros((1,), dtype=torch.int32, device="cuda"), torch.zeros((1,), dtype=torch.int32, device="cuda"))
 
+    dsvt.dsvt_attn_pool(pw, cd, x, out=out, ws=ws)
+    torch.cuda.synchronize()
+    assert int(out[3].item()) == 0
+    M = int(out[2].item())                       # the host sizes the block on the pooled voxels with it (fixed input)
+    # the rotated layer pair that follows on the pooled grid
+    pgrid = tuple(g // p for g, p in zip(cfg["grid"], pool))
+    pc = dsvt.part_cfg(pgrid, cfg["win"], (0, 0, 0), cfg["tau"], cfg["batch"], 0)
+    pmaps = dsvt.SetMapsXY(pc, M)
+    layers = [dsvt.LayerWeights(synth.make_layer_weights(92 + a, C, cfg["heads"], cfg["hidden"], cfg["win"], cfg["dtype"]))
+              for a in (0, 1)]
+    y = torch.empty((M, C), dtype=torch.bfloat16, device="cuda")
+
     def step():
         dsvt.dsvt_attn_pool(pw, cd, x, out=out, ws=ws)
+        dsvt.dsvt_partition_xy(pc, out[0][:M], out=pmaps)
+        dsvt.dsvt_block(layers, pmaps, out[0][:M], out[1][:M], x_out=y)
 
     step()
     torch.cuda.synchronize()
-    assert int(out[3].item()) == 0
-    M = int(out[2].item())
-    ref = out[1].clone()
+    assert int(out[3].item()) == 0 and int(pmaps.x.status.item()) == 0
+    ref, ref_y = out[1].clone(), y.clone()
 
     def check(replay):
-        out[1].zero_()
+        out[1].zero_(); y.zero_()
         replay()
         torch.cuda.synchronize()
-        assert torch.equal(out[1], ref), "graph replay differs from eager launches"
+        assert torch.equal(out[1], ref) and torch.equal(y, ref_y), "graph replay differs from eager launches"
 
     use_graph = not args.no_graph
     run = capture(step, check) if use_graph else step
     dt = timed(run, args.steps, args.warmup)
-    per_launch_us, per_step_ms = per_kernel(step, 8, min(args.steps, 50))
+    per_launch_us, per_step_ms = per_kernel(step, 16, min(args.steps, 50))
     # K and V projections of the N occupied cells, Q and output projection of the M regions, 2 C^2 flops each
     flops = 2 * C * C * (2 * N + 2 * M)
     us = per_launch_us["pool_attention"]
@@ -297,10 +313,11 @@ def pool_workload(args):
                 "flops_per_launch": flops, "hbm_bytes_algorithmic": (N + M) * C * 2,
                 "hbm_gbps_algorithmic": round((N + M) * C * 2 / (us * 1e-6) / 1e9, 1)}
     return {
-        "metric": "input voxels/sec through attention-style 3D pooling (grouping + pooling attention)",
+        "metric": "input voxels/sec through attention-style 3D pooling and the rotated layer pair on the pooled grid",
         "value": round(N / (dt / args.steps), 1), "unit": "voxels/s", "dtype": "bf16",
         "config": {"workload": f"configs[3]: 468x468x32 voxel frame, {N} voxels -> {M} regions of {pool[0]}x{pool[1]}x{pool[2]} "
-                               f"cells, C={C}, {cfg['heads']} heads, empty cells kept as keys",
+                               f"cells, C={C}, {cfg['heads']} heads, keys = {'all cells (empty ones as bias keys)' if mask_empty == 0 else 'occupied voxels'}; "
+                               f"then one block (win 12x12x8, tau={cfg['tau']}) on the {M} pooled voxels",
                    "launch": "hip_graph" if use_graph else "eager"},
         "ms_per_frame": round(dt / args.steps * 1e3, 4),
         "kernel_ms_per_step": {k: round(v, 4) for k, v in per_step_ms.items()},
@@ -399,6 +416,7 @@ def main():
     ap.add_argument("--workload", choices=["frame", "voxel", "skewed", "nuscenes", "pool", "bev", "vfe"], default="frame")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of a captured HIP graph")
+    ap.add_argument("--pool-keep-empty", action="store_true", help="pool workload: empty cells of a region stay keys (zero features)")
     ap.add_argument("--frames-in-flight", type=int, choices=[1, 2], default=2,
                     help="2: also time a loop that keeps two frames in flight on two streams (an extra field of the JSON "
                          "line; `value` and `ms_per_step` are always the single-stream figures)")
