@@ -171,26 +171,55 @@ __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(
 __device__ __forceinline__ void fill_tile_starts(const int32_t* P, uint16_t* jump, uint16_t* jump2, uint8_t* mark,
                                                  int32_t n_sets, int32_t cap) {
   const int32_t tid = threadIdx.x;
-  for (int32_t s = tid; s <= n_sets; s += 1024) {
-    int32_t lo = s + 1, hi = n_sets;                         // smallest t in (s, n_sets] with P[t + 1] - P[s] > cap; n_sets = none
-    if (s < n_sets) {
-      const int32_t lim = P[s] + cap;                         // (a set has at most 96 rows; one longer than cap gets a tile of its own)
-      while (lo < hi) {
-        const int32_t mid = (lo + hi) >> 1;
-        if (P[mid + 1] > lim) hi = mid; else lo = mid + 1;
-      }
-    } else {
-      lo = n_sets;
+  constexpr int32_t kB = 8;                                  // sets a thread works on side by side: their LDS reads overlap
+  for (int32_t base = 0; base <= n_sets; base += 1024 * kB) {
+    // smallest t in (s, n_sets] with P[t + 1] - P[s] > cap (n_sets = none).  A set has at least 4 rows, so t is at most
+    // s + cap / 4 + 1: five or six halvings, taken in step for the kB sets.  (A set longer than cap gets a tile of its own.)
+    int32_t lo[kB], hi[kB], lim[kB];
+#pragma unroll
+    for (int32_t k = 0; k < kB; ++k) {
+      const int32_t s = base + tid + k * 1024;
+      lo[k] = s + 1;
+      hi[k] = min(n_sets, s + cap / 4 + 2);
+      lim[k] = s < n_sets ? P[s] + cap : 0;
+      if (s >= n_sets) { lo[k] = n_sets; hi[k] = n_sets; }
     }
-    jump[s] = (uint16_t)lo;
-    mark[s] = s == 0;
+    for (int32_t step = 0; step < 7; ++step) {               // 2^7 > 96 / 4 + 2
+#pragma unroll
+      for (int32_t k = 0; k < kB; ++k) {
+        if (lo[k] < hi[k]) {
+          const int32_t mid = (lo[k] + hi[k]) >> 1;
+          if (P[mid + 1] > lim[k]) hi[k] = mid; else lo[k] = mid + 1;
+        }
+      }
+    }
+#pragma unroll
+    for (int32_t k = 0; k < kB; ++k) {
+      const int32_t s = base + tid + k * 1024;
+      if (s <= n_sets) { jump[s] = (uint16_t)lo[k]; mark[s] = s == 0; }
+    }
   }
   lds_barrier();
   for (int32_t round = 0; round < 17; ++round) {
     if (jump[0] == n_sets) break;                            // (uniform) every tile start has been reached
-    for (int32_t s = tid; s < n_sets; s += 1024)
-      if (mark[s]) mark[jump[s]] = 1;                        // (mark[n_sets] is a dummy)
-    for (int32_t s = tid; s <= n_sets; s += 1024) jump2[s] = jump[jump[s]];
+    for (int32_t base = 0; base <= n_sets; base += 1024 * kB) {
+      uint16_t j1[kB], j2[kB];
+      bool m[kB];
+#pragma unroll
+      for (int32_t k = 0; k < kB; ++k) {
+        const int32_t s = base + tid + k * 1024;
+        j1[k] = s <= n_sets ? jump[s] : (uint16_t)n_sets;
+        m[k] = s < n_sets && mark[s];
+      }
+#pragma unroll
+      for (int32_t k = 0; k < kB; ++k) j2[k] = jump[j1[k]];
+#pragma unroll
+      for (int32_t k = 0; k < kB; ++k) {
+        const int32_t s = base + tid + k * 1024;
+        if (m[k]) mark[j1[k]] = 1;                           // (mark[n_sets] is a dummy)
+        if (s <= n_sets) jump2[s] = j2[k];
+      }
+    }
     lds_barrier();
     uint16_t* t = jump; jump = jump2; jump2 = t;
   }
