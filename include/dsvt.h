@@ -81,7 +81,8 @@ int dsvt_partition_bound(const dsvt_part_cfg* cfg, int32_t n_voxels, int32_t* ma
  * Needs tau <= 96, grid[0]*(2W-1)*(2H-1) < 2^24 and max_tiles of at least the bound dsvt_partition_bound
  * reports (with fewer, the sets past the last tile get none and their voxels are not processed by a layer).
  * Tiles hold 100 - 4*ceil(tau/4) rows on average; a frame whose tiles would not occupy the 256 compute
- * units once is cut into more, shorter tiles. */
+ * units once is cut into more, shorter tiles, and a frame of several rounds over the compute units gets tiles
+ * filled as far as their sets go (up to 96 rows) when that saves a round or the frame has many rounds. */
 typedef struct {
   int32_t max_tiles;
   int32_t *tile_first, *n_tiles, *tile_order, *tile_desc;
@@ -106,7 +107,7 @@ typedef struct {
  *            call on a ws that was not prepared for this geometry marks nothing, reports *n_sets = 0
  *            and sets DSVT_ST_WS_STATE in *status.
  * status     [device] int32 word, OR-ed with DSVT_ST_* bits (the caller zeroes it)
- * Errors: DSVT_EINVAL (NULL pointer, non-positive size, shift outside [0,win), axis not 0/1,
+ * Errors: DSVT_EINVAL (NULL pointer, non-positive size, shift outside [0,win), axis outside 0..5,
  * key space of 2^31 or more cells), DSVT_ENOSPC (ws_bytes too small), DSVT_EUNSUPPORTED (a work
  * list asked for outside its limits), DSVT_EHIP. */
 int dsvt_partition(const dsvt_part_cfg* cfg, const int32_t* coords, int32_t n_voxels,
@@ -123,12 +124,13 @@ int dsvt_partition_ws_init(const dsvt_part_cfg* cfg, int32_t n_voxels, void* ws,
 /* Both rotated partitions of one window configuration (Sec. 3.2: a block's first layer takes the sets
  * in X-axis inner order, its second in Y-axis order) in one pass over the voxels.  The windows, the
  * number of sets per window (Eq. 2) and hence n_sets, set_win and the tile boundaries are the same for
- * both; only the order of the voxels inside a window differs.  cfg->axis is ignored.  Arguments as for
+ * both; only the order of the voxels inside a window differs.  cfg->axis is the first order of the pair and must be
+ * even: 0 for the X-/Y-axis pair, 2 or 4 for the pairs of the ablation's baselines (DSVT_EINVAL otherwise).  Arguments as for
  * dsvt_partition, with one set_inds and voxel_slot per axis; `tiles` receives the common tile_first,
  * n_tiles and tile_order and the X-axis descriptors, tile_desc_y [device, max_tiles*256 int32] the
  * Y-axis descriptors (required when tiles is given).  The maps of the Y-axis layer are then
  * {set_inds_y, voxel_slot_y, n_sets, {max_tiles, tile_first, n_tiles, tile_order, tile_desc_y}}.
- * Results are identical to two dsvt_partition calls with axis 0 and 1.  Same errors. */
+ * Results are identical to two dsvt_partition calls with axis cfg->axis and cfg->axis + 1.  Same errors. */
 int dsvt_partition_xy(const dsvt_part_cfg* cfg, const int32_t* coords, int32_t n_voxels,
                       int32_t* set_inds_x, int32_t* set_inds_y, int32_t* voxel_slot_x, int32_t* voxel_slot_y,
                       int32_t* n_sets, int32_t max_sets, int32_t* set_win,
@@ -143,7 +145,7 @@ int dsvt_partition_xy(const dsvt_part_cfg* cfg, const int32_t* coords, int32_t n
  * outputs; tiles [host] may be NULL).  At most 4 jobs.  Results are identical to n_jobs
  * dsvt_partition_xy calls.  Errors as there; DSVT_EINVAL for n_jobs outside 1..4. */
 typedef struct {
-  dsvt_part_cfg cfg;                        /* axis ignored */
+  dsvt_part_cfg cfg;                        /* axis: even, as for dsvt_partition_xy */
   int32_t *set_inds_x, *set_inds_y, *voxel_slot_x, *voxel_slot_y, *n_sets, *set_win;
   int32_t max_sets;
   const dsvt_tile_list* tiles;
