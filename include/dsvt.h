@@ -49,8 +49,8 @@ typedef struct {
   int32_t batch;    /* frames in the call; b is the top digit of the window key        */
   int32_t axis;     /* inner-window order: 0 = x,y,z most-to-least significant (X-axis
                        main order), 1 = y,x,z (Y-axis main order).  2..5: the baselines of
-                       the set-partition ablation (Sec. 4.4), made by controlling the
-                       inner-window voxel ID: 2, 3 "Random" = order 0, 1 with the window's V
+                       the set-partition ablation (Sec. 4.4), each of them a different
+                       numbering of the voxels inside a window: 2, 3 "Random" = order 0, 1 with the window's V
                        cells shuffled, key -> (key*mul + add) mod V, mul = the smallest integer
                        >= floor(0.618 V) + (axis odd) coprime to V, add = V/3 + (axis odd)
                        (V <= 65536); 4, 5 "Sparse" = order 0, 1 with the ranks re-dealt: the
@@ -251,8 +251,8 @@ int dsvt_attn_pool(const dsvt_pool_cfg* cfg, const int32_t* coords, const void* 
                    void* ws, size_t ws_bytes, int32_t* status, void* stream);
 
 /* ---------------------------------------------------------------------------------------
- * Bird's-eye-view map (Sec. 3.1, overview: after the last block "voxel features ... are then
- * projected to a bird's eye view (BEV) feature map" for the 2D backbone).
+ * Bird's-eye-view map (Sec. 3.1, overview: the step after the last block, which lays the sparse voxel
+ * rows out as the dense map the 2D backbone works on).
  * out [device] [batch, X, Y, Z, C] of dtype, channels last (Z = 1 for pillars and for the voxel
  * variant after its last pooling: a [batch, X, Y, C] image); the whole of it is written: the
  * voxel's row at its cell, zeros elsewhere.  coords [device] int32 [n_voxels,4] = (b, x, y, z),

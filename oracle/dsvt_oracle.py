@@ -10,9 +10,10 @@ What each function follows:
                  count, Eq. (3) slot index, Eq. (4) INDEX; "Rotated set
                  attention": X-/Y-axis main order; "Hybrid window partition":
                  window shift.  axis 2-5: the Random and Sparse baselines of
-                 the set-partition ablation (Sec. 4.4), made "by controlling
-                 the inner-window voxel ID" as the paper says they are; the
-                 Regional baseline is axis 0 in both layers of a block.
+                 the set-partition ablation (Sec. 4.4), each of them another
+                 numbering of the voxels inside a window, which is how the paper
+                 says it built them; the Regional baseline is axis 0 in both
+                 layers of a block.
   set_attention  Eq. (5): MHSA over every set in one batch, PE added to the
                  logits, duplicated slots masked as keys (sentence after Eq. 3).
   layer / block  Appendix "Network Architecture", DSVT-P paragraph: MHSA,

@@ -75,8 +75,8 @@ __device__ __forceinline__ bool voxel_cell(const PartGeom& g, int4 c, uint32_t& 
 
 // Composite key = window key * (32*words_per_win) + inner key; the inner key runs x-major for the
 // X-axis partition (even inner orders) and y-major for the Y-axis one (odd).  Inner orders 2 and 3 are the
-// "Random" baseline of the paper's set-partition ablation (Sec. 4.4), made by controlling the inner-window voxel
-// ID as the paper says: the window's cells in a fixed shuffle, key -> (key * mul + add) mod volume with mul
+// "Random" baseline of the paper's set-partition ablation (Sec. 4.4), which the paper builds by renumbering the
+// voxels inside a window: the window's cells in a fixed shuffle, key -> (key * mul + add) mod volume with mul
 // coprime to the volume.  (4 and 5, "Sparse", re-deal the ranks instead: see k_emit.)
 __device__ __forceinline__ uint32_t voxel_key(const PartGeom& g, int32_t axis, uint32_t wkey, int32_t xi, int32_t yi, int32_t zi) {
   uint32_t inner = (axis & 1) == 0 ? (uint32_t)((xi * g.win[1] + yi) * g.win[2] + zi)

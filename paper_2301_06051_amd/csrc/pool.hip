@@ -2,8 +2,8 @@
 //
 // Grouping: pooled cells are unique keys in a bounded grid, so -- as in the set partition -- the
 // output order (ascending region key) comes from an occupancy bitmap and a pop-count prefix, with
-// no sort.  Every voxel then writes its index into the dense slot table of its region
-// ("convert the sparse region into dense").
+// no sort.  Every voxel then writes its index into the dense slot table of its region (Sec. 3.3: a
+// sparse pooling region is first laid out densely, one slot per cell).
 // Attention: a workgroup takes 48 consecutive regions.  Only their occupied slots become rows of the
 // <=96-row LDS tile that the K/V projection runs on (an empty slot's key and value are the two bias
 // vectors, whatever the weights); regions whose occupied slots do not fit one tile are taken in
