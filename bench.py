@@ -226,6 +226,16 @@ def stack_workload(args, name):
                 "frac": round(achieved / 2500.0, 5), "traffic": LAYER_HBM_BYTES_PER_LAUNCH if name == "frame" else None,
                 "avg_launch_us": round(per_launch_us["layer"], 2), "flops_per_launch": flops}
 
+    # The partition chain against the HBM roofline: algorithmic bytes per voxel and map = 16 B of coordinates read,
+    # 4 rho B of set_inds, 4 B of voxel_slot and 8 B of descriptor row written; latency-bound at these sizes.
+    n_maps = 2 * len(shifts)
+    part_bytes = N * n_maps * (16 + 4 * rho + 4 + 8)
+    part_us = sum(v for k, v in per_launch_us.items() if k.startswith("part_"))
+    partition_roofline = {"bound": "hbm", "kernel": "partition chain (" + ", ".join(sorted(k for k in per_launch_us if k.startswith("part_"))) + ")",
+                          "achieved": round(part_bytes / (part_us * 1e-6) / 1e9, 1), "peak": 8000.0, "unit": "GB/s",
+                          "frac": round(part_bytes / (part_us * 1e-6) / 8e12, 5), "traffic": None, "avg_launch_us": round(part_us, 2),
+                          "bytes_per_launch": int(part_bytes)}
+
     cpu = None
     if name == "frame" and not args.no_cpu_baseline:
         from threadpoolctl import threadpool_info
@@ -249,7 +259,7 @@ def stack_workload(args, name):
         "ms_per_frame": round(dt / args.steps * 1e3, 4), "step_ms": step_ms, "one_block": one, "two_frames_in_flight": in_flight,
         "kernel_ms_per_step": {k: round(v, 4) for k, v in per_step_ms.items()},
         "kernel_us_per_launch": {k: round(v, 2) for k, v in per_launch_us.items()},
-        "roofline": roofline, "cpu_baseline": cpu,
+        "roofline": roofline, "partition_roofline": partition_roofline, "cpu_baseline": cpu,
     }, dt
 
 
