@@ -153,6 +153,30 @@ def test_block_and_stack_invariances():
     assert np.abs(one - orc.block(ws[0], [my, mx], coords, x)).max() > 1e-6
 
 
+def test_stack_alternates_the_window_shifts():
+    """A backbone's blocks take the window shifts in turn ("Hybrid window partition": the shift changes between
+    consecutive blocks): stack() must equal the composition written out block by block with shifts 0, 1, 0, and
+    must not equal the composition that keeps the first shift throughout, nor the one that starts with the second."""
+    coords, x, _ = _tiny(n=96)
+    ws = [[synth.make_layer_weights(60 + 2 * b + a, C, HEADS, HIDDEN, WIN, "f32") for a in (0, 1)] for b in range(3)]
+    shifts = ((0, 0, 0), (3, 2, 1))
+    got = orc.stack(ws, coords, x, GRID, WIN, shifts, TAU)
+
+    def compose(order):
+        y = x
+        for w_pair, k in zip(ws, order):
+            maps = [orc.partition(coords, GRID, WIN, shifts[k], TAU, axis) for axis in (0, 1)]
+            y = orc.layer(w_pair[1], maps[1], coords, orc.layer(w_pair[0], maps[0], coords, y))
+        return y
+
+    np.testing.assert_allclose(got, compose((0, 1, 0)), rtol=1e-12, atol=1e-13)
+    for wrong in ((0, 0, 0), (1, 0, 1), (0, 1, 1)):
+        assert np.abs(got - compose(wrong)).max() > 1e-6, wrong
+    # a single shift in the list: every block uses it
+    one = orc.stack(ws, coords, x, GRID, WIN, (shifts[1],), TAU)
+    np.testing.assert_allclose(one, compose((1, 1, 1)), rtol=1e-12, atol=1e-13)
+
+
 # ------------------------------ pooling (Sec. 3.3) ------------------------------
 def _brute_pool(w, coords, x, grid, pool, mask_empty):
     d = C // HEADS

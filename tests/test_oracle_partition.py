@@ -6,6 +6,7 @@ brute-force loops over tiny inputs.
 """
 from fractions import Fraction
 from math import floor
+import math
 import os
 
 import numpy as np
@@ -147,12 +148,36 @@ def test_float_evaluation_of_eq3_is_not_exact():
 
 
 # ---------------------------------------------------------------- Random / Sparse / Regional baselines (Sec. 4.4)
+def _golden_shuffle_constants():
+    """{(V, axis): (mul, add)} worked by hand from the stated rule (tests/golden/shuffle_constants.txt)."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "shuffle_constants.txt")
+    table = {}
+    for line in open(path):
+        body = line.split("#")[0].split()
+        if body:
+            V, axis, mul, add = map(int, body)
+            table[(V, axis)] = (mul, add)
+    return table
+
+
+def test_shuffle_constants_match_hand_worked_values():
+    """The constants of the Random baseline's cell shuffle against values worked by hand from the rule, for the
+    window volumes of the workloads (12x12x1, 12x12x8, 12x12x32, 30x30x1) and of the brute-force case below."""
+    golden = _golden_shuffle_constants()
+    assert {v for v, _ in golden} >= {48, 144, 900, 1152, 4608}
+    for (V, axis), want in golden.items():
+        assert orc.shuffle_constants(V, axis) == want, (V, axis)
+        mul, add = want                                  # what the rule promises, checked on the literals themselves
+        assert math.gcd(mul, V) == 1 and mul >= int(0.618 * V) + axis % 2 and add == V // 3 + axis % 2
+        assert all(math.gcd(m, V) != 1 for m in range(int(0.618 * V) + axis % 2, mul))   # no smaller candidate
+
+
 def _brute_variant(coords, grid, win, shift, tau, axis):
-    """The variants written out in plain Python: an explicit shuffle table for axis 2/3, an explicit
-    round-robin deal of the ranked voxels for axis 4/5."""
+    """The variants written out in plain Python: an explicit shuffle table for axis 2/3 (its constants are the
+    hand-worked literals, not the oracle's), an explicit round-robin deal of the ranked voxels for axis 4/5."""
     L, W, H = win
     V = L * W * H
-    mul, add = orc.shuffle_constants(V, axis)
+    mul, add = _golden_shuffle_constants()[(V, 2 + axis % 2)]
     table = [(k * mul + add) % V for k in range(V)]
     per_window = {}
     for i, (b, x, y, z) in enumerate(coords.tolist()):
