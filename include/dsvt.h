@@ -14,7 +14,8 @@
  *     parameters and the relative-position table are always float.
  *   - Return value: DSVT_OK, or a negative code for what the host can see (bad argument,
  *     unsupported shape, workspace too small, launch failure).  Nothing is enqueued when a
- *     negative code is returned.  Errors only a kernel can see (a coordinate outside the
+ *     negative code is returned (one exception: DSVT_EHIP from a launch that fails in the middle
+ *     of a partition's chain of kernels, after which that call's `ws` is marked unprepared).  Errors only a kernel can see (a coordinate outside the
  *     grid, a repeated coordinate, more sets than `max_sets`, a partition buffer that was
  *     not prepared, more voxels than `max_voxels`) OR bits into the caller's
  *     [device] `status` word; outputs are then unspecified but no access leaves the
@@ -35,7 +36,7 @@ enum { DSVT_OK = 0, DSVT_EINVAL = -1, DSVT_ENOSPC = -2, DSVT_EHIP = -3, DSVT_EUN
 enum { DSVT_F32 = 0, DSVT_BF16 = 1 };
 /* bits of the device status word */
 enum { DSVT_ST_COORD_RANGE = 1, DSVT_ST_COORD_REPEAT = 2, DSVT_ST_SET_OVERFLOW = 4, DSVT_ST_WS_STATE = 8,
-       DSVT_ST_VOXEL_OVERFLOW = 16 };
+       DSVT_ST_VOXEL_OVERFLOW = 16, DSVT_ST_TILE_OVERFLOW = 32 };
 
 /* ---------------------------------------------------------------------------------------
  * Set partition (Sec. 3.2 "Dynamic set partition", Eq. 2-4; "Rotated set attention";
@@ -79,7 +80,8 @@ int dsvt_partition_bound(const dsvt_part_cfg* cfg, int32_t n_voxels, int32_t* ma
  *                                entry of the first n_tiles descriptors that a kernel reads is
  *                                written by the call; the rest keeps what it held.
  * Needs tau <= 96, grid[0]*(2W-1)*(2H-1) < 2^24 and max_tiles of at least the bound dsvt_partition_bound
- * reports (with fewer, the sets past the last tile get none and their voxels are not processed by a layer).
+ * reports (with fewer, the sets past the last tile get none, their voxels are not processed by a layer, and
+ * the partition sets DSVT_ST_TILE_OVERFLOW in *status).
  * Tiles hold 100 - 4*ceil(tau/4) rows on average; a frame whose tiles would not occupy the 256 compute
  * units once is cut into more, shorter tiles, and a frame of several rounds over the compute units gets tiles
  * filled as far as their sets go (up to 96 rows) when that saves a round or the frame has many rounds. */

@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(_PKG, "libdsvt.so")
 
 DSVT_OK, DSVT_EINVAL, DSVT_ENOSPC, DSVT_EHIP, DSVT_EUNSUPPORTED = 0, -1, -2, -3, -4
 DSVT_F32, DSVT_BF16 = 0, 1
-ST_COORD_RANGE, ST_COORD_REPEAT, ST_SET_OVERFLOW, ST_WS_STATE, ST_VOXEL_OVERFLOW = 1, 2, 4, 8, 16
+ST_COORD_RANGE, ST_COORD_REPEAT, ST_SET_OVERFLOW, ST_WS_STATE, ST_VOXEL_OVERFLOW, ST_TILE_OVERFLOW = 1, 2, 4, 8, 16, 32
 _ERR = {-1: "DSVT_EINVAL", -2: "DSVT_ENOSPC", -3: "DSVT_EHIP", -4: "DSVT_EUNSUPPORTED"}
 _DT = {"f32": (DSVT_F32, torch.float32), "bf16": (DSVT_BF16, torch.bfloat16)}
 
@@ -143,9 +143,9 @@ def dsvt_partition_bound(cfg, n_voxels):
 class SetMaps:
     """Device buffers of one (window configuration, axis) and the struct the kernels read."""
 
-    def __init__(self, cfg, n_voxels, max_sets=None, tiles=True, common=None):
+    def __init__(self, cfg, n_voxels, max_sets=None, tiles=True, common=None, max_tiles=None):
         """common: the SetMaps of the other axis of the same dsvt_partition_xy call, whose n_sets, set_win,
-        status, scratch and tile boundaries this one shares."""
+        status, scratch and tile boundaries this one shares.  max_tiles: a work list shorter than the bound."""
         bound, tile_bound, ws_bytes = dsvt_partition_bound(cfg, n_voxels)
         self.cfg, self.n_voxels, self.tau = cfg, n_voxels, cfg.tau
         self.max_sets = bound if max_sets is None else max_sets
@@ -164,6 +164,8 @@ class SetMaps:
             assert common.max_sets == self.max_sets and common.n_voxels == n_voxels
             self.set_win, self.n_sets, self.status, self.ws = common.set_win, common.n_sets, common.status, common.ws
         self.max_tiles = tile_bound if (tiles and tile_bound > 0 and cfg.tau <= 96) else 0
+        if self.max_tiles and max_tiles is not None:
+            self.max_tiles = min(self.max_tiles, max_tiles)
         if self.max_tiles:
             if common is None:
                 self.tile_first = torch.full((self.max_tiles + 1,), -1, **i32)
@@ -200,9 +202,9 @@ class SetMapsXY:
     """The maps of both axes of one window configuration, filled by one dsvt_partition_xy call; indexes
     and iterates like the pair [X-axis maps, Y-axis maps]."""
 
-    def __init__(self, cfg, n_voxels, max_sets=None, tiles=True):
-        self.x = SetMaps(cfg, n_voxels, max_sets, tiles)
-        self.y = SetMaps(cfg, n_voxels, max_sets, tiles, common=self.x)
+    def __init__(self, cfg, n_voxels, max_sets=None, tiles=True, max_tiles=None):
+        self.x = SetMaps(cfg, n_voxels, max_sets, tiles, max_tiles=max_tiles)
+        self.y = SetMaps(cfg, n_voxels, max_sets, tiles, common=self.x, max_tiles=max_tiles)
         self.n_voxels = n_voxels
 
     def __getitem__(self, k):

@@ -50,6 +50,10 @@ __global__ void k_ws_init(uint32_t* __restrict__ words, int64_t n, uint64_t* __r
   if (i == 0) *ws_token = token;     // (kernels of later calls start after this one has ended)
 }
 
+__global__ void k_ws_revoke(uint64_t* __restrict__ ws_token) {
+  if (threadIdx.x == 0) *ws_token = 0ull;
+}
+
 // x / win[a] for 0 <= x < grid + shift.  With m = ceil(2^32 / d) the high word of x * m is floor(x / d)
 // whenever x * (m * d - 2^32) < 2^32, which x < 2^16 and d < 2^15 guarantee (the host sets magic only then).
 __device__ __forceinline__ int32_t div_win(const PartGeom& g, int32_t a, int32_t x) {
@@ -394,7 +398,7 @@ __device__ __forceinline__ int32_t set_loc_code(int32_t pos, int32_t ls, int32_t
 __device__ __forceinline__ void build_tiles(const int32_t* set_w, const int32_t* win_count, const int32_t* win_soff,
                                             const int32_t* n_sets_ptr, int32_t set_cap, int32_t tau, int32_t n_windows,
                                             int32_t rows_per_cut, TileOut out, int32_t* tile_rows, int32_t* tile_pos,
-                                            int32_t* set_p, int32_t* set_loc, int32_t fill_sets) {
+                                            int32_t* set_p, int32_t* set_loc, int32_t fill_sets, int32_t* status) {
   extern __shared__ uint32_t fill_lds[];                     // filled tiles: rows before every set, two jump tables, marks
   __shared__ int32_t wave_tot[16];
   __shared__ int32_t carry_s;
@@ -519,6 +523,7 @@ __device__ __forceinline__ void build_tiles(const int32_t* set_w, const int32_t*
         if (first[j] && tile < out.max_tiles) { out.tile_first[tile] = s; tile_rows[tile] = pv[j + 1]; }
         if (s == n_sets - 1) {
           const int32_t nt = tile + 1 < out.max_tiles ? tile + 1 : out.max_tiles;
+          if (tile + 1 > out.max_tiles) atomicOr(status, DSVT_ST_TILE_OVERFLOW);   // the sets past the last tile get none
           *out.n_tiles = nt;
           out.tile_first[nt] = n_sets;
           tile_rows[nt] = set_p[n_sets];
@@ -648,7 +653,7 @@ __global__ void __launch_bounds__(1024) k_tiles(Jobs jobs, GenJobs gen) {
   const GenJob& G = gen.j[blockIdx.x];
   if (!G.want_tiles) return;
   build_tiles(G.ws_setwin, J.win_count, J.win_soff, J.n_sets, J.set_cap, J.g.tau, J.g.n_windows, J.rows_per_cut, J.out,
-              G.tile_rows, G.tile_pos, G.set_p, J.set_loc, G.fill_sets);
+              G.tile_rows, G.tile_pos, G.set_p, J.set_loc, G.fill_sets, J.status);
 }
 
 #ifdef DSVT_PHASE_CLOCKS
@@ -911,6 +916,7 @@ __global__ void __launch_bounds__(1024) k_front(Jobs jobs
   const bool tiles_short = carry2[0] > tile_lim;          // the caller's list is shorter than the frame needs: later sets get no tile
   const int32_t n_eff = tiles_short ? over_s : (n_tot < set_cap ? n_tot : set_cap);
   const int32_t nt = tiles_short ? tile_lim : carry2[0];
+  if (tiles_short && tid == 0) atomicOr(status, DSVT_ST_TILE_OVERFLOW);
   if (n_eff <= 0) {
     if (tid == 0) { *out.n_tiles = 0; out.tile_first[0] = 0; }
     return;
@@ -1317,14 +1323,24 @@ int run_partitions(const PartRequest* reqs, int32_t n, const int32_t* coords, in
       gen_jobs.j[n_gen++] = P.job;
     }
   }
+  // Everything that can fail on the host comes before the first launch: once k_mark has run, the mark bitmap
+  // holds bits that only the rest of the chain takes out again.
+  auto* front = n_axes == 2 ? k_front<2> : k_front<1>;
+  if (n_front) {
+    static std::atomic<uint64_t> front_allowed[2];
+    if (int rc = dsvt_allow_lds((const void*)front, kFrontLds, front_allowed[n_axes - 1])) return rc;
+  }
+  if (n_gen && any_tiles && fill_lds) {
+    static std::atomic<uint64_t> tiles_allowed{0};
+    if (int rc = dsvt_allow_lds((const void*)k_tiles, kFrontLds, tiles_allowed)) return rc;
+  }
+  DSVT_HIP_TRY(hipGetLastError());                            // (an error left by an earlier call is not this chain's)
   {
     dsvt_prof_scope ps(DSVT_K_PART_MARK, st);
     k_mark<<<dim3((unsigned)vox_blocks, n), tb, 0, st>>>(jobs, (const int4*)coords, n_voxels);
   }
+  if (hipGetLastError() != hipSuccess) return DSVT_EHIP;      // nothing was enqueued
   if (n_front) {
-    static std::atomic<uint64_t> front_allowed[2];
-    auto* front = n_axes == 2 ? k_front<2> : k_front<1>;
-    if (int rc = dsvt_allow_lds((const void*)front, kFrontLds, front_allowed[n_axes - 1])) return rc;
     dsvt_prof_scope ps(DSVT_K_PART_TILES, st);
     front<<<n_front, 1024, front_lds, st>>>(front_jobs
 #ifdef DSVT_PHASE_CLOCKS
@@ -1343,9 +1359,6 @@ int run_partitions(const PartRequest* reqs, int32_t n, const int32_t* coords, in
     }
     if (any_tiles) {
       dsvt_prof_scope ps(DSVT_K_PART_TILES, st);
-      static std::atomic<uint64_t> tiles_allowed{0};
-      if (fill_lds)
-        if (int rc = dsvt_allow_lds((const void*)k_tiles, kFrontLds, tiles_allowed)) return rc;
       k_tiles<<<n_gen, 1024, fill_lds, st>>>(gen_jobs, gen);
     }
   }
@@ -1354,7 +1367,13 @@ int run_partitions(const PartRequest* reqs, int32_t n, const int32_t* coords, in
     const int32_t tail_blocks = (int32_t)dsvt_ceil_div((int64_t)max_tiles * 16, tb);
     k_emit<<<dim3((unsigned)(vox_blocks + tail_blocks), n_axes, n), tb, 0, st>>>(jobs, (const int4*)coords, n_voxels, vox_blocks);
   }
-  DSVT_HIP_TRY(hipGetLastError());
+  if (hipGetLastError() != hipSuccess) {
+    // A launch after k_mark failed: the marked bits may still be there.  The buffers' headers are taken back,
+    // so that the next call on them reports DSVT_ST_WS_STATE instead of ranking voxels over stale bits.
+    for (int32_t q = 0; q < n; ++q) k_ws_revoke<<<1, 64, 0, st>>>((uint64_t*)reqs[q].ws);
+    (void)hipGetLastError();
+    return DSVT_EHIP;
+  }
   return DSVT_OK;
 }
 

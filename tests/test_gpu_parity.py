@@ -266,6 +266,50 @@ def test_partition_reports_bad_input_without_faulting():
         assert torch.all(first.voxel_slot == -1)
 
 
+@pytest.mark.parametrize("cid,n", [(2, 5000), (3, 20000)])
+def test_partition_buffer_survives_calls_that_report_errors(cid, n):
+    """The partition's scratch buffer carries an occupancy bitmap from call to call (every call finds it zero and
+    leaves it zero).  One buffer through: a good frame, a frame with a voxel outside the grid, a frame with a
+    repeated cell, a call with too few set rows, a call with too short a work list -- each reports its status bit
+    -- and then the good frame again, whose maps must be bit-exact with status 0.  Both front ends (the
+    single-workgroup one for the pillar frame, the general chain for the voxel grid)."""
+    cfg = synth.CONFIGS[cid]
+    coords = synth.make_frame(cid, n=n)
+    shift = cfg["shifts"][-1]
+    B = dsvt.binding
+    pc = dsvt.part_cfg(cfg["grid"], cfg["win"], shift, cfg["tau"], cfg["batch"], 0)
+    pair = dsvt.SetMapsXY(pc, len(coords))
+    oms = [orc.partition(coords, cfg["grid"], cfg["win"], shift, cfg["tau"], a) for a in (0, 1)]
+
+    def share_ws(other):
+        other.x.ws = other.y.ws = pair.x.ws
+        return other
+
+    def call(c, out, want_bit):
+        out.x.status.zero_()
+        dsvt.dsvt_partition_xy(pc, dev_coords(c), out=out)
+        torch.cuda.synchronize()
+        st = int(out.x.status.item())
+        _say(f"  status {st} (expected bit {want_bit})")
+        assert (st & want_bit) == want_bit and (want_bit != 0 or st == 0)
+
+    _say(f"partition buffer through error-reporting calls, cfg{cid} n={len(coords)}")
+    call(coords, pair, 0)
+    for axis in (0, 1):
+        assert_maps_equal(pair[axis], oms[axis])
+    bad = coords.copy(); bad[5, 1] = cfg["grid"][0]; bad[9, 0] = cfg["batch"]     # outside the grid, outside the batch
+    call(bad, pair, B.ST_COORD_RANGE)
+    rep = coords.copy(); rep[7] = rep[8]; rep[100] = rep[8]                      # one cell three times
+    call(rep, pair, B.ST_COORD_REPEAT)
+    call(coords, share_ws(dsvt.SetMapsXY(pc, len(coords), max_sets=3)), B.ST_SET_OVERFLOW)
+    call(coords, share_ws(dsvt.SetMapsXY(pc, len(coords), max_tiles=2)), B.ST_TILE_OVERFLOW)
+    for m in (pair.x, pair.y):
+        m.set_inds.fill_(-1); m.voxel_slot.fill_(-1)
+    call(coords, pair, 0)
+    for axis in (0, 1):
+        assert_maps_equal(pair[axis], oms[axis])
+
+
 # ------------------------------------------------------------------ set attention / block
 def _layer_case(cid, n, seed, rel_bias=True, shift=None):
     cfg = synth.CONFIGS[cid]
@@ -295,7 +339,7 @@ def test_set_attention_parity(cid, n, dup_mode, rel_bias):
 
 
 @pytest.mark.parametrize("tiles", [True, False])
-@pytest.mark.parametrize("cid,n", [(1, None), (2, 5000), (3, 8000)])
+@pytest.mark.parametrize("cid,n", [(1, None), (2, 5000), (3, 8000), (5, 30000)])
 def test_block_parity(cid, n, tiles):
     cfg, coords, x, shift, mk = _layer_case(cid, n, 32)
     ws = [mk(71), mk(72)]
@@ -367,6 +411,71 @@ def test_stack_parity_full_pillar_frame(cid, launch):
     assert err < TOL["bf16"]
 
 
+@pytest.mark.timeout(900)
+def test_stack_parity_full_skewed_batch(capsys):
+    """The 4 x 200,000-voxel skewed batch (windows 12 x 12 x 32 holding 1 to ~1,850 voxels, tau 36) through the full
+    4-block rotated stack at full size, in the launch configuration the benchmark times: both window shifts
+    partitioned by one dsvt_partition_xy_multi call, four dsvt_block calls on one stream, eagerly and as a replayed
+    HIP graph.  All four maps bit-exact, all 800,000 rows of the output against the oracle.  The oracle takes about
+    two minutes here; it reports after every block so that the run is seen to be alive."""
+    cfg, coords, x, _, _ = _layer_case(5, None, 33)
+    ws = [[synth.make_layer_weights(200 + 2 * b + a, cfg["C"], cfg["heads"], cfg["hidden"], cfg["win"], cfg["dtype"])
+           for a in (0, 1)] for b in range(cfg["blocks"])]
+
+    def progress(msg):
+        with capsys.disabled():
+            print(f"[case] {msg}", flush=True)
+
+    progress(f"stack cfg5 full batch: {len(coords)} voxels, {cfg['blocks']} blocks")
+    cd = dev_coords(coords)
+    shifts = list(cfg["shifts"])
+    pcs = [dsvt.part_cfg(cfg["grid"], cfg["win"], sh, cfg["tau"], cfg["batch"], 0) for sh in shifts]
+    maps = [dsvt.SetMapsXY(pc, len(coords)) for pc in pcs]
+    layers = [[dsvt.LayerWeights(w) for w in pair] for pair in ws]
+    x0 = dev_feats(x, cfg["dtype"])
+    buf = torch.empty_like(x0)
+
+    def step():
+        dsvt.dsvt_partition_xy_multi(pcs, cd, maps)
+        src = x0
+        for b, pair in enumerate(layers):
+            dsvt.dsvt_block(pair, maps[b % len(shifts)], cd, src, x_out=buf)
+            src = buf
+
+    step()
+    torch.cuda.synchronize()
+    eager = buf.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for _ in range(3):
+        buf.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(buf, eager)
+    progress("  GPU: eager and three graph replays agree bit for bit")
+    omaps = []
+    for m, sh in zip(maps, shifts):
+        oms = [orc.partition(coords, cfg["grid"], cfg["win"], sh, cfg["tau"], axis) for axis in (0, 1)]
+        for axis in (0, 1):
+            assert_maps_equal(m[axis], oms[axis])
+        omaps.append(oms)
+        progress(f"  maps of shift {sh} bit-exact ({oms[0]['n_sets']} sets, largest window {int(oms[0]['win_counts'].max())} voxels)")
+    ref = x
+    for b, pair in enumerate(ws):                 # blocks alternate between the shifts (orc.stack does the same; pinned on the CPU)
+        ref = orc.block(pair, omaps[b % len(shifts)], coords, ref)
+        progress(f"  oracle block {b} done")
+    err = rel_err(eager, ref)
+    progress(f"  rel err after {2 * cfg['blocks']} layers {err:.3e}")
+    assert err < TOL["bf16"]
+
+
 def test_layer_argument_errors():
     cfg, coords, x, shift, mk = _layer_case(1, 300, 34)
     cd = dev_coords(coords)
@@ -429,15 +538,18 @@ def test_attn_pool_dense_regions(pool, fill):
         assert err < TOL["f32"]
 
 
-def test_attn_pool_then_block():
-    """The pooled voxels feed a rotated layer pair on the pooled grid (window 12 x 12 x 8, tau 48)."""
+@pytest.mark.timeout(400)
+@pytest.mark.parametrize("n", [30000, None])
+def test_attn_pool_then_block(n):
+    """The pooled voxels feed a rotated layer pair on the pooled grid (window 12 x 12 x 8, tau 48); n = None is the
+    workload's full 120,000-voxel frame (107,564 pooled voxels)."""
     cfg = synth.CONFIGS[4]
-    coords = synth.make_frame(4, n=30000)
+    coords = synth.make_frame(4, n=n)
     x = synth.make_features(36, len(coords), cfg["C"], cfg["dtype"])
     w = synth.make_pool_weights(92, cfg["C"], cfg["heads"], cfg["dtype"])
     ws = [synth.make_layer_weights(93 + a, cfg["C"], cfg["heads"], cfg["hidden"], cfg["win"], cfg["dtype"]) for a in (0, 1)]
     pgrid = (468, 468, 8)
-    _say("attn_pool + block on the pooled grid")
+    _say(f"attn_pool + block on the pooled grid, {len(coords)} voxels")
     ref_c, ref_p = orc.attn_pool(w, coords, x, cfg["grid"], cfg["pool"], 1)
     ref_p16 = synth.round_bf16(ref_p.astype(np.float32))          # the GPU hands bf16 features to the block
     oms = [orc.partition(ref_c, pgrid, cfg["win"], (0, 0, 0), cfg["tau"], a) for a in (0, 1)]
@@ -499,16 +611,18 @@ def test_crowded_window_many_sets():
         assert rel_err(y, ref) < TOL["bf16"]
 
 
-def test_hybrid_window_sizes():
-    """Blocks alternating window (12,12,1) and the shifted (24,24,1) window of the paper's default
-    hybrid partition ("Hybrid window partition"; DSVT-P uses (12,12,1) and (24,24,1))."""
+@pytest.mark.parametrize("second", [24, 36])
+def test_hybrid_window_sizes(second):
+    """Blocks alternating window (12,12,1) and a shifted larger window: (24,24,1), the paper's default
+    hybrid partition ("Hybrid window partition"; DSVT-P uses (12,12,1) and (24,24,1)), and (36,36,1), the
+    third row of its hybrid-window ablation."""
     cfg = synth.CONFIGS[2]
     coords = synth.make_frame(2, n=6000)
     x = synth.make_features(71, len(coords), cfg["C"], "bf16")
-    wins = [((12, 12, 1), (0, 0, 0)), ((24, 24, 1), (12, 12, 0))]
+    wins = [((12, 12, 1), (0, 0, 0)), ((second, second, 1), (second // 2, second // 2, 0))]
     ws = [[synth.make_layer_weights(72 + 2 * b + a, cfg["C"], cfg["heads"], cfg["hidden"], wins[b][0], "bf16")
            for a in (0, 1)] for b in range(2)]
-    _say("hybrid window sizes 12x12 / shifted 24x24")
+    _say(f"hybrid window sizes 12x12 / shifted {second}x{second}")
     cd = dev_coords(coords)
     ref, xd = x, dev_feats(x, "bf16")
     for b, (win, shift) in enumerate(wins):
@@ -590,21 +704,24 @@ def test_width_128_large_window():
     assert m == len(rc_) and np.array_equal(oc[:m].cpu().numpy(), rc_) and rel_err(po[:m], rp) < TOL["bf16"]
 
 
-def test_dsvt_v_four_stages():
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("xy,n", [(96, 5000), (468, 120000)])
+def test_dsvt_v_four_stages(xy, n):
     """The voxel variant's stage layout (appendix "Network Architecture": four stages, one block each here,
     windows 12 x 12 x {32, 8, 2, 1}, tau = 48, attention-style pooling by {4, 4, 2} along z between stages),
     chained end to end: every stage's maps and pooled coordinates bit-exact, the last stage's features in
-    tolerance.  The oracle rounds the features to bf16 where the GPU path stores them (after each call)."""
+    tolerance.  The oracle rounds the features to bf16 where the GPU path stores them (after each call).  Once on a
+    small grid, once at frame size (468 x 468 x 32, 120,000 voxels)."""
     C, heads, hidden, tau = 192, 8, 384, 48
-    grid0 = (96, 96, 32)
-    coords = np.concatenate([np.zeros((5000, 1), np.int64), synth.frame_radial(311, grid0, 5000)], 1).astype(np.int32)
+    grid0 = (xy, xy, 32)
+    coords = np.concatenate([np.zeros((n, 1), np.int64), synth.frame_radial(311, grid0, n)], 1).astype(np.int32)
     x = synth.make_features(312, len(coords), C, "bf16")
     zs, strides = [32, 8, 2, 1], [4, 4, 2]
-    _say("DSVT-V stage chain: 4 blocks, 3 poolings")
+    _say(f"DSVT-V stage chain: 4 blocks, 3 poolings, {n} voxels on {grid0}")
     ref_c, ref_x = coords, x
     cd, xd = dev_coords(coords), dev_feats(x, "bf16")
     for st, z in enumerate(zs):
-        grid, win, shift = (96, 96, z), (12, 12, z), ((0, 0, 0) if st % 2 == 0 else (6, 6, 0))
+        grid, win, shift = (xy, xy, z), (12, 12, z), ((0, 0, 0) if st % 2 == 0 else (6, 6, 0))
         ws = [synth.make_layer_weights(320 + 2 * st + a, C, heads, hidden, win, "bf16") for a in (0, 1)]
         oms = [orc.partition(ref_c, grid, win, shift, tau, a) for a in (0, 1)]
         ref_x = synth.round_bf16(orc.block(ws, oms, ref_c, ref_x).astype(np.float32))
