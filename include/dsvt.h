@@ -252,6 +252,20 @@ int dsvt_attn_pool(const dsvt_pool_cfg* cfg, const int32_t* coords, const void* 
                    int32_t* out_coords, void* out, int32_t* n_out,
                    void* ws, size_t ws_bytes, int32_t* status, void* stream);
 
+/* dsvt_attn_pool for callers that cannot allocate device memory or carry a workspace around: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * results and errors as dsvt_attn_pool, without `ws`: the scratch (occupancy bitmap, its prefix, the
+ * dense slot table) is an array of DSVT_POOL_STATIC_SCRATCH_BYTES built into the library, one copy per
+ * GPU, held from the moment the library is loaded until the process ends.  The call allocates and
+ * frees nothing.  DSVT_ENOSPC when dsvt_attn_pool_workspace_size(cfg, n_voxels) exceeds that size
+ * (8 MiB: e.g. 300,000 voxels in regions of 4 cells on a 468 x 468 x 32 grid).  Every call on a GPU uses
+ * that GPU's one array: calls on different streams of one GPU must not overlap (they would race on
+ * it); what the array held before does not matter (each call clears what it reads).  The first call
+ * on a device looks the array's address up (no allocation; make it outside graph capture). */
+#define DSVT_POOL_STATIC_SCRATCH_BYTES (8u << 20)
+int dsvt_attn_pool_static(const dsvt_pool_cfg* cfg, const int32_t* coords, const void* x, int32_t n_voxels,
+                          int32_t* out_coords, void* out, int32_t* n_out, int32_t* status, void* stream);
+
 /* ---------------------------------------------------------------------------------------
  * Bird's-eye-view map (Sec. 3.1, overview: the step after the last block, which lays the sparse voxel
  * rows out as the dense map the 2D backbone works on).

@@ -94,6 +94,7 @@ def lib():
         L.dsvt_pool_pack.argtypes = [C.POINTER(PoolCfg), vp, sz, vp]
         L.dsvt_attn_pool_workspace_size.argtypes = [C.POINTER(PoolCfg), i32, C.POINTER(sz)]
         L.dsvt_attn_pool.argtypes = [C.POINTER(PoolCfg), vp, vp, i32, vp, vp, vp, vp, sz, vp, vp]
+        L.dsvt_attn_pool_static.argtypes = [C.POINTER(PoolCfg), vp, vp, i32, vp, vp, vp, vp, vp]
         L.dsvt_bev_scatter.argtypes = [vp, vp, i32, i32, i32, i32, C.POINTER(I32x3), vp, vp, vp]
         L.dsvt_vfe_workspace_size.argtypes = [C.POINTER(VfeCfg), i32, i32, C.POINTER(sz)]
         L.dsvt_vfe.argtypes = [C.POINTER(VfeCfg), vp, vp, i32, vp, vp, vp, i32, vp, sz, vp, vp]
@@ -348,6 +349,17 @@ def dsvt_attn_pool(pool, coords, x, out=None, ws=None, stream=None):
     rc = lib().dsvt_attn_pool(C.byref(pool.struct), _ptr(coords), _ptr(x), n, _ptr(out[0]), _ptr(out[1]), _ptr(out[2]),
                               _ptr(ws), ws.numel(), _ptr(out[3]), _stream(stream))
     _check("dsvt_attn_pool", rc)
+    return out
+
+
+def dsvt_attn_pool_static(pool, coords, x, out, stream=None):
+    """dsvt_attn_pool on the library's built-in scratch: no workspace, nothing allocated.  `out` = the caller's
+    (out_coords [N,4] int32, out [N,C], n_out, status) tensors."""
+    n = coords.shape[0]
+    assert x.is_cuda and x.dtype == pool.dtype and x.is_contiguous() and x.shape == (n, pool.C)
+    rc = lib().dsvt_attn_pool_static(C.byref(pool.struct), _ptr(coords), _ptr(x), n, _ptr(out[0]), _ptr(out[1]), _ptr(out[2]),
+                                     _ptr(out[3]), _stream(stream))
+    _check("dsvt_attn_pool_static", rc)
     return out
 
 

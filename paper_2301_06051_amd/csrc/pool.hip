@@ -480,18 +480,11 @@ extern "C" int dsvt_attn_pool_workspace_size(const dsvt_pool_cfg* cfg, int32_t n
   return DSVT_OK;
 }
 
-extern "C" int dsvt_attn_pool(const dsvt_pool_cfg* cfg, const int32_t* coords, const void* x, int32_t n_voxels,
-                              int32_t* out_coords, void* out, int32_t* n_out, void* ws, size_t ws_bytes,
-                              int32_t* status, void* stream) {
-  PoolPlan pl;
-  int rc = make_plan(cfg, n_voxels, &pl);
-  if (rc != DSVT_OK) return rc;
-  rc = check_pool(*cfg, true);
-  if (rc != DSVT_OK) return rc;
-  if (!coords || !x || !out_coords || !out || !n_out || !ws || !status || x == out) return DSVT_EINVAL;
-  if (!aligned16(coords) || !aligned16(x) || !aligned16(out) || !aligned16(out_coords)) return DSVT_EINVAL;
-  if (ws_bytes < pl.total) return DSVT_ENOSPC;
-  hipStream_t st = (hipStream_t)stream;
+namespace {
+
+// The whole call on scratch memory `ws` of at least pl.total bytes (checked by the callers).
+int run_attn_pool(const dsvt_pool_cfg* cfg, const PoolPlan& pl, const int32_t* coords, const void* x, int32_t n_voxels,
+                  int32_t* out_coords, void* out, int32_t* n_out, void* ws, int32_t* status, hipStream_t st) {
   char* base = reinterpret_cast<char*>(ws);
   uint32_t* bitmap = reinterpret_cast<uint32_t*>(base + pl.off_bitmap);
   int32_t* prefix = reinterpret_cast<int32_t*>(base + pl.off_prefix);
@@ -508,6 +501,7 @@ extern "C" int dsvt_attn_pool(const dsvt_pool_cfg* cfg, const int32_t* coords, c
     kp_emit<<<(unsigned)dsvt_ceil_div(n_voxels, tb), tb, 0, st>>>(pl.g, reinterpret_cast<const int4*>(coords), n_voxels,
                                                                   bitmap, prefix, inds, out_coords);
   }
+  int rc;
   if (cfg->dtype == DSVT_BF16) {
     if (cfg->C == 192) rc = launch_pool_attention<bf16_t, 192, 8, 3, 3>(*cfg, pl, inds, n_out, x, out, n_voxels, st);
     else if (cfg->C == 128) rc = launch_pool_attention<bf16_t, 128, 8, 2, 2>(*cfg, pl, inds, n_out, x, out, n_voxels, st);
@@ -518,4 +512,62 @@ extern "C" int dsvt_attn_pool(const dsvt_pool_cfg* cfg, const int32_t* coords, c
   if (rc != DSVT_OK) return rc;
   DSVT_HIP_TRY(hipGetLastError());
   return DSVT_OK;
+}
+
+int check_pool_call(const dsvt_pool_cfg* cfg, const int32_t* coords, const void* x, int32_t n_voxels, int32_t* out_coords,
+                    void* out, int32_t* n_out, int32_t* status, PoolPlan* pl) {
+  int rc = make_plan(cfg, n_voxels, pl);
+  if (rc != DSVT_OK) return rc;
+  rc = check_pool(*cfg, true);
+  if (rc != DSVT_OK) return rc;
+  if (!coords || !x || !out_coords || !out || !n_out || !status || x == out) return DSVT_EINVAL;
+  if (!aligned16(coords) || !aligned16(x) || !aligned16(out) || !aligned16(out_coords)) return DSVT_EINVAL;
+  return DSVT_OK;
+}
+
+// Scratch of dsvt_attn_pool_static: one array per GPU, part of the loaded code object (never allocated, never
+// freed).  In host code `scratch` is only a handle for hipGetSymbolAddress; the kernels get the device address
+// that call returns, looked up once per device and kept in g_scratch.
+constexpr size_t kStaticScratchBytes = DSVT_POOL_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch[kMaxDevices];
+
+int static_scratch(void** ptr) {
+  int dev = 0;
+  DSVT_HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return DSVT_EUNSUPPORTED;
+  void* p = g_scratch[dev].load(std::memory_order_acquire);
+  if (p == nullptr) {                                          // first call on this device (it is the current one)
+    DSVT_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (p == nullptr) return DSVT_EHIP;
+    g_scratch[dev].store(p, std::memory_order_release);        // (two threads racing here store the same address)
+  }
+  *ptr = p;
+  return DSVT_OK;
+}
+
+}  // namespace
+
+extern "C" int dsvt_attn_pool(const dsvt_pool_cfg* cfg, const int32_t* coords, const void* x, int32_t n_voxels,
+                              int32_t* out_coords, void* out, int32_t* n_out, void* ws, size_t ws_bytes,
+                              int32_t* status, void* stream) {
+  PoolPlan pl;
+  int rc = check_pool_call(cfg, coords, x, n_voxels, out_coords, out, n_out, status, &pl);
+  if (rc != DSVT_OK) return rc;
+  if (!ws) return DSVT_EINVAL;
+  if (ws_bytes < pl.total) return DSVT_ENOSPC;
+  return run_attn_pool(cfg, pl, coords, x, n_voxels, out_coords, out, n_out, ws, status, (hipStream_t)stream);
+}
+
+extern "C" int dsvt_attn_pool_static(const dsvt_pool_cfg* cfg, const int32_t* coords, const void* x, int32_t n_voxels,
+                                     int32_t* out_coords, void* out, int32_t* n_out, int32_t* status, void* stream) {
+  PoolPlan pl;
+  int rc = check_pool_call(cfg, coords, x, n_voxels, out_coords, out, n_out, status, &pl);
+  if (rc != DSVT_OK) return rc;
+  if (pl.total > kStaticScratchBytes) return DSVT_ENOSPC;      // grid or voxel count beyond the built-in scratch
+  void* ws = nullptr;
+  rc = static_scratch(&ws);
+  if (rc != DSVT_OK) return rc;
+  return run_attn_pool(cfg, pl, coords, x, n_voxels, out_coords, out, n_out, ws, status, (hipStream_t)stream);
 }
