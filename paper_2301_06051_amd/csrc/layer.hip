@@ -97,14 +97,18 @@ template <typename T, int C, int HEADS, int HID> struct LayerLds {
   static_assert(total <= 160 * 1024, "LDS of one CU");
 };
 
-// Attention of one (set, query tile, half of the heads) item (Eq. 5): for each of its heads,
+// Attention of one (set, query tile, group of heads) item (Eq. 5): for each of its heads,
 // logits = Q K^T (+ PE), softmax over the set's distinct voxels, O = P V; O overwrites the Q
 // entries it was computed from.  KTC = key tiles of the set (compile time: no branches inside).
 // S^T is produced key-major (keys as MFMA rows) so that a lane holds 4 keys of ONE query: the
 // softmax reductions are in-lane plus two cross-lane steps, and P^T is already laid out as the B
-// operand of O^T = V^T P^T.  The positional term depends on (query, key) only through the
-// coordinate difference, i.e. one table row [idx][heads] per pair, fetched once for all heads.
-template <typename T, int C, int HEADS, int HID, int KTC, int HG>
+// operand of O^T = V^T P^T.  Q arrives scaled by log2(e) / sqrt(d) (the projection's epilogue does
+// it), and the positional term -- which depends on (query, key) only through the coordinate
+// difference, one table row [index][heads] per pair, fetched once for all heads -- is the MFMA's
+// initial accumulator value, so the logits come out of the matrix cores finished.  The keys past
+// the set's last voxel take the table's extra last row, which holds -inf: no mask arithmetic.
+// DUP: repeated slots count as keys (the exponentials are multiplied by the slots' counts).
+template <typename T, int C, int HEADS, int HID, int KTC, int HG, bool DUP>
 __device__ __forceinline__ void attn_item(const LayerDev& p, T* Qs, const T* Ks, const T* Vt, const int32_t* row_lin,
                                           const float* row_mult, int r0, int nu, int qt, int hh, int rows_ready) {
   typedef LayerLds<T, C, HEADS, HID> L;
@@ -119,19 +123,9 @@ __device__ __forceinline__ void attn_item(const LayerDev& p, T* Qs, const T* Ks,
   const int qi = 16 * qt + m;
   const int qrow = r0 + (qi < nu ? qi : nu - 1);
 
-  constexpr float kLog2e = 1.4426950408889634f;
-  const float scale2 = rsqrtf((float)D) * kLog2e;
-  float bias[KTC][4][HG];
-  float mult[KTC][4];
-#pragma unroll
-  for (int kt = 0; kt < KTC; ++kt)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      mult[kt][i] = 1.0f;
-#pragma unroll
-      for (int hl = 0; hl < HG; ++hl) bias[kt][i][hl] = 0.f;
-    }
-  if (p.rel_bias != nullptr) {
+  f32x4 bias[HG][KTC];
+  f32x4 mult[KTC];
+  {
     const int ql = row_lin[qrow] + p.rel_const;
 #pragma unroll
     for (int kt = 0; kt < KTC; ++kt) {
@@ -141,25 +135,24 @@ __device__ __forceinline__ void attn_item(const LayerDev& p, T* Qs, const T* Ks,
       for (int i = 0; i < 4; ++i) {
         int idx = ql - kls[i];
         idx = idx < 0 ? 0 : (idx >= p.rel_size ? p.rel_size - 1 : idx);
-        const float* tp = p.rel_bias + (size_t)idx * HEADS + hh * HG;
+        if (kt == KTC - 1) idx = 16 * kt + 4 * g + i < nu ? idx : p.rel_size;   // only the last key tile is ragged
+        const float* tp = reinterpret_cast<const float*>(reinterpret_cast<const char*>(p.rel_bias) +
+                                                         (unsigned)idx * (unsigned)(HEADS * 4) + (unsigned)(hh * HG * 4));
         if constexpr (HG == 4) {
           const f32x4 t = *reinterpret_cast<const f32x4*>(tp);
-          bias[kt][i][0] = t[0]; bias[kt][i][1] = t[1]; bias[kt][i][2] = t[2]; bias[kt][i][3] = t[3];
+          bias[0][kt][i] = t[0]; bias[1][kt][i] = t[1]; bias[2][kt][i] = t[2]; bias[3][kt][i] = t[3];
         } else if constexpr (HG == 2) {
           const float2 t = *reinterpret_cast<const float2*>(tp);
-          bias[kt][i][0] = t.x; bias[kt][i][1] = t.y;
+          bias[0][kt][i] = t.x; bias[1][kt][i] = t.y;
         } else {
-          bias[kt][i][0] = *tp;
+          bias[0][kt][i] = *tp;
         }
       }
     }
   }
-  if (p.dup_mode) {
+  if constexpr (DUP) {
 #pragma unroll
-    for (int kt = 0; kt < KTC; ++kt) {
-      const f32x4 t = *reinterpret_cast<const f32x4*>(row_mult + r0 + 16 * kt + 4 * g);
-      mult[kt][0] = t[0]; mult[kt][1] = t[1]; mult[kt][2] = t[2]; mult[kt][3] = t[3];
-    }
+    for (int kt = 0; kt < KTC; ++kt) mult[kt] = *reinterpret_cast<const f32x4*>(row_mult + r0 + 16 * kt + 4 * g);
   }
 
 #pragma unroll
@@ -167,7 +160,7 @@ __device__ __forceinline__ void attn_item(const LayerDev& p, T* Qs, const T* Ks,
     const int h = hh * HG + hl;
     f32x4 S[KTC];                                 // S[kt][i]: key 16*kt + 4*g + i, query 16*qt + m
 #pragma unroll
-    for (int kt = 0; kt < KTC; ++kt) S[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int kt = 0; kt < KTC; ++kt) S[kt] = bias[hl][kt];
 #pragma unroll
     for (int kc = 0; kc < D; kc += KC) {
       const int kk = kc + g * KL;
@@ -182,57 +175,54 @@ __device__ __forceinline__ void attn_item(const LayerDev& p, T* Qs, const T* Ks,
         S[kt] = M::mma(fa, fb, S[kt]);                  // dead k lanes: finite K times the zeroed Q
       }
     }
-    // logits in units of log2(e): l = (q.k / sqrt(d) + PE) * log2(e), so exp is a bare exp2
-    float mx = -INFINITY;
+    // S holds the logits in units of log2(e), -inf for the keys that do not exist: exp is a bare exp2
+    float mx = S[0][0];
 #pragma unroll
     for (int kt = 0; kt < KTC; ++kt)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const float lv = fmaf(S[kt][i], scale2, bias[kt][i][hl]);
-        const float l = (kt < KTC - 1 || 16 * kt + 4 * g + i < nu) ? lv : -INFINITY;   // only the last key tile is ragged
-        S[kt][i] = l;
-        mx = fmaxf(mx, l);
-      }
-    mx = col_max(mx);
+      for (int i = 0; i < 4; ++i)
+        if (kt + i > 0) mx = fmaxf(mx, S[kt][i]);
+    mx = col_max(mx);                             // (key 0 exists for every query: finite)
     float sum = 0.f;
 #pragma unroll
     for (int kt = 0; kt < KTC; ++kt)
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const float e = __builtin_amdgcn_exp2f(S[kt][i] - mx) * mult[kt][i];     // exp2(-inf) = 0 for masked keys; mult = 1 unless repeats count
+        float e = __builtin_amdgcn_exp2f(S[kt][i] - mx);       // exp2(-inf) = 0
+        if constexpr (DUP) e *= mult[kt][i];
         S[kt][i] = e;
         sum += e;
       }
     sum = col_sum(sum);
     const float inv = __builtin_amdgcn_rcpf(sum);
 
-    // O^T[dv][q] = sum_key V^T[dv][key] P^T[key][q]
+    // O^T[dv][q] = sum_key V^T[dv][key] P^T[key][q].  Key columns past the tile's rows hold no V: their P is an
+    // exact zero, so any finite column will do, and the set's first one is read instead.
 #pragma unroll
     for (int dt = 0; dt < (D + 15) / 16; ++dt) {
       f32x4 O = f32x4{0.f, 0.f, 0.f, 0.f};
       const int dv = 16 * dt + m;
-      const bool dlive = dv < D;
-      const T* vrow = Vt + (h * D + (dlive ? dv : 0)) * LDV;
+      const T* vrow = Vt + (h * D + (dv < D ? dv : 0)) * LDV;      // (rows past the head width: results thrown away)
 #pragma unroll
       for (int c = 0; c < NCH; ++c) {
         Frag fa, fb;
         if constexpr (TPC == 2) {
           const int c0 = r0 + 32 * c + 4 * g, c1 = c0 + 16;
-          const bool ok0 = dlive && c0 < rows_ready, ok1 = dlive && (2 * c + 1 < KTC) && c1 < rows_ready;
-          bf16x4 lo = *reinterpret_cast<const bf16x4*>(vrow + (c0 < rows_ready ? c0 : 0));
-          bf16x4 hi = *reinterpret_cast<const bf16x4*>(vrow + (c1 < rows_ready ? c1 : 0));
-          const bf16x4 z4 = {0, 0, 0, 0};
-          lo = ok0 ? lo : z4;
-          hi = ok1 ? hi : z4;
-          fa = Frag{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+          const bf16x4 lo = *reinterpret_cast<const bf16x4*>(vrow + (c0 < rows_ready ? c0 : r0));
           const f32x4 p0 = S[2 * c];
-          const f32x4 p1 = (2 * c + 1 < KTC) ? S[(2 * c + 1 < KTC) ? 2 * c + 1 : 0] : f32x4{0.f, 0.f, 0.f, 0.f};
-          fb = Frag{(bf16_t)p0[0], (bf16_t)p0[1], (bf16_t)p0[2], (bf16_t)p0[3],
-                    (bf16_t)p1[0], (bf16_t)p1[1], (bf16_t)p1[2], (bf16_t)p1[3]};
+          if (2 * c + 1 < KTC) {
+            const bf16x4 hi = *reinterpret_cast<const bf16x4*>(vrow + (c1 < rows_ready ? c1 : r0));
+            const f32x4 p1 = S[2 * c + 1 < KTC ? 2 * c + 1 : 0];
+            fa = Frag{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+            fb = Frag{(bf16_t)p0[0], (bf16_t)p0[1], (bf16_t)p0[2], (bf16_t)p0[3],
+                      (bf16_t)p1[0], (bf16_t)p1[1], (bf16_t)p1[2], (bf16_t)p1[3]};
+          } else {
+            fa = Frag{lo[0], lo[1], lo[2], lo[3], 0, 0, 0, 0};
+            fb = Frag{(bf16_t)p0[0], (bf16_t)p0[1], (bf16_t)p0[2], (bf16_t)p0[3], 0, 0, 0, 0};
+          }
         } else {
           const int c0 = r0 + 16 * c + 4 * g;
-          fa = *reinterpret_cast<const Frag*>(vrow + (c0 < rows_ready ? c0 : 0));
-          fa = (dlive && c0 < rows_ready) ? fa : M::zero();
+          fa = *reinterpret_cast<const Frag*>(vrow + (c0 < rows_ready ? c0 : r0));
           fb = S[c];
         }
         O = M::mma(fa, fb, O);
@@ -243,8 +233,24 @@ __device__ __forceinline__ void attn_item(const LayerDev& p, T* Qs, const T* Ks,
   }
 }
 
+// An item of a set with kts key tiles: up to three key tiles half of the heads per item, beyond that (BIG kernels
+// only) one head.
+template <typename T, int C, int HEADS, int HID, bool BIG, bool DUP>
+__device__ __forceinline__ void attn_any(const LayerDev& p, T* Qs, const T* Ks, const T* Vt, const int32_t* row_lin,
+                                         const float* row_mult, int r0, int nu, int qt, int hh, int kts, int rows_ready) {
+  constexpr int HG2 = HEADS / 2;
+  if (kts == 1) attn_item<T, C, HEADS, HID, 1, HG2, DUP>(p, Qs, Ks, Vt, row_lin, row_mult, r0, nu, qt, hh, rows_ready);
+  else if (kts == 2) attn_item<T, C, HEADS, HID, 2, HG2, DUP>(p, Qs, Ks, Vt, row_lin, row_mult, r0, nu, qt, hh, rows_ready);
+  else if (!BIG || kts == 3) attn_item<T, C, HEADS, HID, 3, HG2, DUP>(p, Qs, Ks, Vt, row_lin, row_mult, r0, nu, qt, hh, rows_ready);
+  else if constexpr (BIG) {
+    if (kts == 4) attn_item<T, C, HEADS, HID, 4, 1, DUP>(p, Qs, Ks, Vt, row_lin, row_mult, r0, nu, qt, hh, rows_ready);
+    else if (kts == 5) attn_item<T, C, HEADS, HID, 5, 1, DUP>(p, Qs, Ks, Vt, row_lin, row_mult, r0, nu, qt, hh, rows_ready);
+    else attn_item<T, C, HEADS, HID, 6, 1, DUP>(p, Qs, Ks, Vt, row_lin, row_mult, r0, nu, qt, hh, rows_ready);
+  }
+}
+
 // BIG: the instantiation for tau > 48 (sets of four to six key tiles); the common one does not carry that code.
-template <typename T, int C, int HEADS, int HID, int NT_QKV, int NT_O, int NT_1, int NT_2, bool BIG>
+template <typename T, int C, int HEADS, int HID, int NT_QKV, int NT_O, int NT_1, int NT_2, bool BIG, bool DUP>
 __global__ void __launch_bounds__(kLayerWaves * 64)
 k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* out, int full_layer) {
   // out may be x: a tile's rows are read, then written, by this workgroup only
@@ -274,8 +280,6 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 #define DSVT_REFRESH_LANE() do { tid = opaque_tid(); lane = tid & 63; m = lane & 15; g = lane >> 4; } while (0)
 
-  // The first Q/K/V weight fragments are requested before anything else: their latency hides
-  // behind the row bookkeeping and the gather.
   DSVT_CLK(0);
 #ifdef DSVT_PHASE_CLOCKS
   if (p.clk && threadIdx.x == 0) p.clk[blockIdx.x * 64 + 11] = wall_clock64();
@@ -372,8 +376,11 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
   DSVT_CLK(1);
 
   // ---- 2. gather (Eq. 4): rows of x -> Xs, 16 bytes per thread, dead rows zero.  The loads are
-  // unconditional (clamped addresses) and issued ahead of the Q/K/V weights: a wavefront's loads
-  // return in order, so its rows do not wait for the 18 KB of weight fragments it requests.
+  // unconditional (clamped addresses).  The Q/K/V weights are requested after the barrier that
+  // publishes the rows, not here: the compute unit's memory pipeline takes one 1 KB fragment every
+  // ~19 cycles whether it hits the cache or not, a wavefront stands still until its requests are
+  // taken, and 216 fragments in front of the stores to LDS kept every wavefront from the barrier
+  // for 3.4 k cycles (measured: gather 5.7 k -> 1.6 k cycles, the tile 47.4 k -> 45.7 k).
   {
     constexpr int CH = C * (int)sizeof(T) / 16, G = (kRowsMax * CH + NTHREADS - 1) / NTHREADS;
     uint4 gv[G];
@@ -386,7 +393,6 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
       live[k] = v >= 0;
       gv[k] = reinterpret_cast<const uint4*>(x + (size_t)(v >= 0 ? v : 0) * C)[c];
     }
-    qkv.prefetch(p.b_qkv, 2 * C / (16 * NT_QKV));
 #pragma unroll
     for (int k = 0; k < G; ++k) {
       const int idx = tid + k * NTHREADS;
@@ -399,6 +405,7 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
   lds_barrier();
   DSVT_CLK(2);
   DSVT_REFRESH_LANE();
+  qkv.prefetch(p.b_qkv, 2 * C / (16 * NT_QKV));
 
   // ---- 3. Q, K, V = X W^T + b; V stored transposed
   {
@@ -408,6 +415,7 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
     // the V items run with exchanged MFMA operands: a lane then holds four consecutive rows of one
     // feature, i.e. 8 contiguous bytes of V^T (a plain store instead of four 2-byte ones)
     static_assert((C / 16) % NT_QKV == 0, "an item never straddles the Q/K/V boundary");
+    const float q_scale = rsqrtf((float)L::D) * 1.4426950408889634f;
     qkv.run(Xs, LDX, RT, p.b_qkv, [&](int o0, int r, f32x4 (&acc)[NT_QKV], bool swapped) {
       if (swapped) {
 #pragma unroll
@@ -419,7 +427,7 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
         for (int nt = 0; nt < NT_QKV; ++nt) {
           const int ot = o0 + 16 * nt;
           const int o = ot + 4 * g;
-          if (ot < C) *reinterpret_cast<Vec4*>(Qs + row * LDX + o) = pack4<T>(acc[nt]);
+          if (ot < C) *reinterpret_cast<Vec4*>(Qs + row * LDX + o) = pack4<T>(acc[nt] * q_scale);   // logits in units of log2(e)
           else *reinterpret_cast<Vec4*>(Ks + row * LDX + (o - C)) = pack4<T>(acc[nt]);
         }
       }
@@ -443,16 +451,8 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
     for (int it = wave; it < n_items; it += NW) {
       const int d = __builtin_amdgcn_readfirstlane(items[it]);
       const int s = d & 255, qt = (d >> 8) & 15, hh = (d >> 12) & 15, kts = d >> 16;
-      constexpr int HG2 = HEADS / 2;
       const int r0 = __builtin_amdgcn_readfirstlane(set_r0[s]), nu = __builtin_amdgcn_readfirstlane(set_nu[s]);
-      if (kts == 1) attn_item<T, C, HEADS, HID, 1, HG2>(p, Qs, Ks, Vt, row_lin, row_mult, r0, nu, qt, hh, RT * 16);
-      else if (kts == 2) attn_item<T, C, HEADS, HID, 2, HG2>(p, Qs, Ks, Vt, row_lin, row_mult, r0, nu, qt, hh, RT * 16);
-      else if (!BIG || kts == 3) attn_item<T, C, HEADS, HID, 3, HG2>(p, Qs, Ks, Vt, row_lin, row_mult, r0, nu, qt, hh, RT * 16);
-      else if constexpr (BIG) {
-        if (kts == 4) attn_item<T, C, HEADS, HID, 4, 1>(p, Qs, Ks, Vt, row_lin, row_mult, r0, nu, qt, hh, RT * 16);
-        else if (kts == 5) attn_item<T, C, HEADS, HID, 5, 1>(p, Qs, Ks, Vt, row_lin, row_mult, r0, nu, qt, hh, RT * 16);
-        else attn_item<T, C, HEADS, HID, 6, 1>(p, Qs, Ks, Vt, row_lin, row_mult, r0, nu, qt, hh, RT * 16);
-      }
+      attn_any<T, C, HEADS, HID, BIG, DUP>(p, Qs, Ks, Vt, row_lin, row_mult, r0, nu, qt, hh, kts, RT * 16);
     }
   }
   f32x4 bo4[NT_O];
@@ -588,19 +588,23 @@ PackedLayout packed_layout(const dsvt_layer_w& w) {
   const int out[4] = {3 * w.C, w.C, w.hidden, w.C}, k[4] = {w.C, w.C, w.C, w.hidden};
   size_t o = 0;
   for (int i = 0; i < 4; ++i) { pl.off[i] = o; pl.out[i] = out[i]; pl.k[i] = k[i]; o = dsvt_align_up(o + (size_t)out[i] * k[i] * es, 256); }
-  pl.rel_size = (2 * w.win[0] - 1) * (2 * w.win[1] - 1) * (2 * w.win[2] - 1);
+  // position table [index][heads] plus one last row of -inf (the row of a key that does not exist); without a
+  // positional term the table is one row of zeros and that last row
+  pl.rel_size = w.rel_bias != nullptr ? (2 * w.win[0] - 1) * (2 * w.win[1] - 1) * (2 * w.win[2] - 1) : 1;
   pl.off[4] = o;
-  if (w.rel_bias != nullptr) o = dsvt_align_up(o + (size_t)pl.rel_size * w.heads * 4, 256);
+  o = dsvt_align_up(o + (size_t)(pl.rel_size + 1) * w.heads * 4, 256);
   pl.off[5] = o;
   o = dsvt_align_up(o + (size_t)kGeluKnots * sizeof(float2), 256);
   pl.total = o;
   return pl;
 }
 
-// [heads][size] -> [size][heads], in units of log2(e) (the softmax works with exp2)
+// [heads][size] -> [size + 1][heads], in units of log2(e) (the softmax works with exp2); row `size` holds -inf.
+// src == nullptr (no positional term): zeros.
 __global__ void k_pack_table(const float* __restrict__ src, float* __restrict__ dst, int heads, int size) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < heads * size) dst[(i % size) * heads + i / size] = src[i] * 1.4426950408889634f;
+  if (i < heads * size) dst[(i % size) * heads + i / size] = src != nullptr ? src[i] * 1.4426950408889634f : 0.f;
+  else if (i < heads * (size + 1)) dst[i] = -INFINITY;
 }
 
 LayerDev to_dev(const dsvt_layer_w& w) {
@@ -610,13 +614,13 @@ LayerDev to_dev(const dsvt_layer_w& w) {
   d.w_qkv = pk + pl.off[0]; d.w_o = pk + pl.off[1]; d.w_1 = pk + pl.off[2]; d.w_2 = pk + pl.off[3];
   d.b_qkv = w.b_qkv; d.b_o = w.b_o; d.b_1 = w.b_1; d.b_2 = w.b_2;
   d.ln1_g = w.ln1_g; d.ln1_b = w.ln1_b; d.ln2_g = w.ln2_g; d.ln2_b = w.ln2_b;
-  d.rel_bias = w.rel_bias ? reinterpret_cast<const float*>(pk + pl.off[4]) : nullptr;
+  d.rel_bias = reinterpret_cast<const float*>(pk + pl.off[4]);
   d.gelu_tab = reinterpret_cast<const float2*>(pk + pl.off[5]);
   d.ln_eps = w.ln_eps; d.dup_mode = w.dup_mode;
   const int my = 2 * w.win[1] - 1, mz = 2 * w.win[2] - 1;
   d.rel_my = my; d.rel_mz = mz;
-  d.rel_size = (2 * w.win[0] - 1) * my * mz;
-  d.rel_const = ((w.win[0] - 1) * my + (w.win[1] - 1)) * mz + (w.win[2] - 1);
+  d.rel_size = pl.rel_size;
+  d.rel_const = w.rel_bias != nullptr ? ((w.win[0] - 1) * my + (w.win[1] - 1)) * mz + (w.win[2] - 1) : 0;
 #ifdef DSVT_PHASE_CLOCKS
   d.clk = g_phase_clocks;
 #endif
@@ -652,10 +656,10 @@ int check_maps(const dsvt_maps& mp) {
   return DSVT_OK;
 }
 
-template <typename T, int C, int HEADS, int HID, int NT_QKV, int NT_O, int NT_1, int NT_2, bool BIG>
+template <typename T, int C, int HEADS, int HID, int NT_QKV, int NT_O, int NT_1, int NT_2, bool BIG, bool DUP>
 int launch_layer_v(const dsvt_layer_w& w, const dsvt_maps& mp, const int32_t* coords, const void* x, void* out, int full,
                    hipStream_t st) {
-  auto kern = k_layer<T, C, HEADS, HID, NT_QKV, NT_O, NT_1, NT_2, BIG>;
+  auto kern = k_layer<T, C, HEADS, HID, NT_QKV, NT_O, NT_1, NT_2, BIG, DUP>;
   constexpr size_t lds = LayerLds<T, C, HEADS, HID>::total;
   static std::atomic<uint64_t> lds_allowed{0};
   if (int rc = dsvt_allow_lds(reinterpret_cast<const void*>(kern), lds, lds_allowed)) return rc;
@@ -672,8 +676,13 @@ int launch_layer_v(const dsvt_layer_w& w, const dsvt_maps& mp, const int32_t* co
 template <typename T, int C, int HEADS, int HID, int NT_QKV, int NT_O, int NT_1, int NT_2>
 int launch_layer(const dsvt_layer_w& w, const dsvt_maps& mp, const int32_t* coords, const void* x, void* out, int full,
                  hipStream_t st) {
-  if (mp.tau > 48) return launch_layer_v<T, C, HEADS, HID, NT_QKV, NT_O, NT_1, NT_2, true>(w, mp, coords, x, out, full, st);
-  return launch_layer_v<T, C, HEADS, HID, NT_QKV, NT_O, NT_1, NT_2, false>(w, mp, coords, x, out, full, st);
+  // four instantiations per shape: sets of more than 48 voxels (tau > 48) take one head per attention item, and
+  // repeated slots that count as keys (dup_mode 1) multiply the exponentials by the slots' counts
+  const bool big = mp.tau > 48, dup = w.dup_mode != 0;
+  if (big && dup) return launch_layer_v<T, C, HEADS, HID, NT_QKV, NT_O, NT_1, NT_2, true, true>(w, mp, coords, x, out, full, st);
+  if (big) return launch_layer_v<T, C, HEADS, HID, NT_QKV, NT_O, NT_1, NT_2, true, false>(w, mp, coords, x, out, full, st);
+  if (dup) return launch_layer_v<T, C, HEADS, HID, NT_QKV, NT_O, NT_1, NT_2, false, true>(w, mp, coords, x, out, full, st);
+  return launch_layer_v<T, C, HEADS, HID, NT_QKV, NT_O, NT_1, NT_2, false, false>(w, mp, coords, x, out, full, st);
 }
 
 int run_layer(const dsvt_layer_w& w, const dsvt_maps& mp, const int32_t* coords, const void* x, void* out, int full,
@@ -722,8 +731,8 @@ extern "C" int dsvt_layer_pack(const dsvt_layer_w* layer, void* packed, size_t b
   }
   k_pack_gelu_table<<<(unsigned)dsvt_ceil_div(kGeluKnots, 256), 256, 0, st>>>(
       reinterpret_cast<float2*>(reinterpret_cast<char*>(packed) + pl.off[5]));
-  if (layer->rel_bias != nullptr) {
-    const int n = pl.rel_size * layer->heads;
+  {
+    const int n = (pl.rel_size + 1) * layer->heads;
     k_pack_table<<<(unsigned)dsvt_ceil_div(n, 256), 256, 0, st>>>(
         layer->rel_bias, reinterpret_cast<float*>(reinterpret_cast<char*>(packed) + pl.off[4]), layer->heads, pl.rel_size);
   }

@@ -310,13 +310,20 @@ __device__ __forceinline__ float col_sum(float v) {
   const auto b = __builtin_amdgcn_permlane32_swap(w, w, false, false);
   return __uint_as_float(b[0]) + __uint_as_float(b[1]);
 }
+// (the maxima are taken by the instruction itself: fmaxf() on values that come out of a lane swap as plain bits
+// is compiled with an extra quieting operation per operand)
+__device__ __forceinline__ float raw_max(float a, float b) {
+  float r;
+  asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
 __device__ __forceinline__ float col_max(float v) {
   const unsigned u = __float_as_uint(v);
   const auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
-  const float s = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+  const float s = raw_max(__uint_as_float(a[0]), __uint_as_float(a[1]));
   const unsigned w = __float_as_uint(s);
   const auto b = __builtin_amdgcn_permlane32_swap(w, w, false, false);
-  return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+  return raw_max(__uint_as_float(b[0]), __uint_as_float(b[1]));
 }
 
 __device__ __forceinline__ float wave_sum(float v) {
