@@ -59,17 +59,8 @@ struct LayerDev {
   float ln_eps;
   int rel_size, rel_const, rel_my, rel_mz;   // table entries per head; index = lin(q) - lin(k) + rel_const
   int dup_mode;
-#ifdef DSVT_PHASE_CLOCKS
-  long long* clk;                            // [blocks][16] shader-clock stamps of wavefront 0 (debug builds)
-#endif
 };
 
-#ifdef DSVT_PHASE_CLOCKS
-long long* g_phase_clocks = nullptr;
-#define DSVT_CLK(k) do { if (p.clk && threadIdx.x == 0) p.clk[blockIdx.x * 64 + (k)] = clock64(); } while (0)
-#else
-#define DSVT_CLK(k) do {} while (0)
-#endif
 
 struct MapsDev {
   const int32_t *set_inds, *n_sets, *n_tiles, *tile_desc;
@@ -279,11 +270,6 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
   int tid = threadIdx.x, lane = tid & 63, m = lane & 15, g = lane >> 4;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 #define DSVT_REFRESH_LANE() do { tid = opaque_tid(); lane = tid & 63; m = lane & 15; g = lane >> 4; } while (0)
-
-  DSVT_CLK(0);
-#ifdef DSVT_PHASE_CLOCKS
-  if (p.clk && threadIdx.x == 0) p.clk[blockIdx.x * 64 + 11] = wall_clock64();
-#endif
   GemmPhase<T, NT_QKV, C, 3 * C, NW, 1, false> qkv(reinterpret_cast<const T*>(p.w_qkv), wave);
 
   int ns;
@@ -373,7 +359,6 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
   const int R = __builtin_amdgcn_readfirstlane(set_r0[ns]);
   const int RT = (R + 15) >> 4;
   const int RTK = ((RT + 1) >> 1) << 1;          // the LayerNorm phases run on an even number of row tiles
-  DSVT_CLK(1);
 
   // ---- 2. gather (Eq. 4): rows of x -> Xs, 16 bytes per thread, dead rows zero.  The loads are
   // unconditional (clamped addresses).  The Q/K/V weights are requested after the barrier that
@@ -403,15 +388,11 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
     }
   }
   lds_barrier();
-  DSVT_CLK(2);
   DSVT_REFRESH_LANE();
   qkv.prefetch(p.b_qkv, 2 * C / (16 * NT_QKV));
 
   // ---- 3. Q, K, V = X W^T + b; V stored transposed
   {
-#ifdef DSVT_PHASE_CLOCKS
-    if (p.clk) qkv.dbg = p.clk + blockIdx.x * 64 + 16 + wave * 4;
-#endif
     // the V items run with exchanged MFMA operands: a lane then holds four consecutive rows of one
     // feature, i.e. 8 contiguous bytes of V^T (a plain store instead of four 2-byte ones)
     static_assert((C / 16) % NT_QKV == 0, "an item never straddles the Q/K/V boundary");
@@ -442,7 +423,6 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
   const int rt_own = (wave / SG) * (RTK >> 1), HC = wave < 2 * SG ? RTK >> 1 : 0;   // HC = 0: a wavefront without an item
   const int o_own = og_own * 16 * NT_O;
   lds_barrier();
-  DSVT_CLK(3);
   DSVT_REFRESH_LANE();
 
   // ---- 4. attention inside every set; O overwrites Q
@@ -459,7 +439,6 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
 #pragma unroll
   for (int nt = 0; nt < NT_O; ++nt) bo4[nt] = *reinterpret_cast<const f32x4*>(p.b_o + o_own + 16 * nt + 4 * g);
   lds_barrier();
-  DSVT_CLK(4);
   DSVT_REFRESH_LANE();
   // attention is done with V^T: the GELU table of the MLP takes its place (published by the
   // barriers of the LayerNorm below)
@@ -482,7 +461,6 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
   else if (HC == 2) oproj.template run_keep<2>(Qs, LDX, rt_own, bo4, keep);
   else if (HC == 3) oproj.template run_keep<3>(Qs, LDX, rt_own, bo4, keep);
   if (pf_turn == 1) ffn1.prefetch();
-  DSVT_CLK(13);
   f32x4 g1[NT_O], be1[NT_O];                       // fetched while the MFMAs above drain
 #pragma unroll
   for (int nt = 0; nt < NT_O; ++nt) {
@@ -506,11 +484,8 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
   }
   if (full_layer) {
     if (pf_turn == 2) ffn1.prefetch();
-    DSVT_CLK(14);
     layer_norm_tile<T, NT_O, C, kHalfTiles>(keep, o_own, og_own, rt_own, HC, stat, g1, be1, p.ln_eps, Xs, LDX);
-    DSVT_CLK(15);
     lds_barrier();
-    DSVT_CLK(5);
     DSVT_REFRESH_LANE();
 
     // ---- 6. MLP: H = gelu(x1 W1^T + b1) over the dead Q/K tiles; x2 = LN(x1 + H W2^T + b2)
@@ -533,7 +508,6 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
 #pragma unroll
     for (int nt = 0; nt < NT_2; ++nt) b24[nt] = *reinterpret_cast<const f32x4*>(p.b_2 + o_own2 + 16 * nt + 4 * g);
     lds_barrier();
-    DSVT_CLK(6);
     DSVT_REFRESH_LANE();
     f32x4 keep2[NT_2][kHalfTiles];
     if (HC == 1) ffn2.template run_keep<1>(Hs, LDH, rt_own, b24, keep2);
@@ -559,7 +533,6 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
     layer_norm_tile<T, NT_2, C, kHalfTiles>(keep2, o_own2, og_own, rt_own, HC, stat, g2, be2, p.ln_eps, Xs, LDX);
   }
   lds_barrier();
-  DSVT_CLK(7);
   DSVT_REFRESH_LANE();
 
   // ---- 7. scatter: rows of Xs -> the voxels' rows of out, 16 bytes per thread
@@ -573,10 +546,6 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
             *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(Xs) + (size_t)r * LDX * sizeof(T) + c * 16);
     }
   }
-  DSVT_CLK(8);
-#ifdef DSVT_PHASE_CLOCKS
-  if (p.clk && threadIdx.x == 0) { p.clk[blockIdx.x * 64 + 9] = R; p.clk[blockIdx.x * 64 + 10] = ns; p.clk[blockIdx.x * 64 + 12] = wall_clock64(); }
-#endif
 }
 
 // ------------------------------------------------------------------------------------------
@@ -621,9 +590,6 @@ LayerDev to_dev(const dsvt_layer_w& w) {
   d.rel_my = my; d.rel_mz = mz;
   d.rel_size = pl.rel_size;
   d.rel_const = w.rel_bias != nullptr ? ((w.win[0] - 1) * my + (w.win[1] - 1)) * mz + (w.win[2] - 1) : 0;
-#ifdef DSVT_PHASE_CLOCKS
-  d.clk = g_phase_clocks;
-#endif
   return d;
 }
 
@@ -697,9 +663,6 @@ int run_layer(const dsvt_layer_w& w, const dsvt_maps& mp, const int32_t* coords,
 
 }  // namespace
 
-#ifdef DSVT_PHASE_CLOCKS
-extern "C" void dsvt_debug_phase_clocks(long long* dev_buf) { g_phase_clocks = dev_buf; }
-#endif
 
 extern "C" int dsvt_layer_packed_size(const dsvt_layer_w* layer, size_t* bytes) {
   if (!layer || !bytes) return DSVT_EINVAL;

@@ -166,12 +166,6 @@ struct GemmPhase {
   struct Bias { f32x4 v[NT]; float s[NT]; };          // both forms of an item's bias, see load_bias()
   Bias bias0;                                            // first item's bias when prefetch() fetched it
   bool bias0_set = false;
-#ifdef DSVT_PHASE_CLOCKS
-  long long* dbg = nullptr;                               // per-wavefront stamps: start, then after every item
-#define DSVT_ITEM_CLK(k) do { if (dbg && (threadIdx.x & 63) == 0) dbg[k] = clock64(); } while (0)
-#else
-#define DSVT_ITEM_CLK(k) do {} while (0)
-#endif
 
   __device__ __forceinline__ GemmPhase(const T* wp, int wave_) : Wp(wp), wave(wave_) {}
 
@@ -209,7 +203,6 @@ struct GemmPhase {
   __device__ __forceinline__ void run(const T* Xs, int ldx, int RT, const float* __restrict__ bias, Epi epi, int swap_og = N_OG) {
     static_assert(KSPLIT == 1, "run() holds the whole K");
     const int h0 = RSPLIT == 1 ? RT : (RT + 1) >> 1;
-    DSVT_ITEM_CLK(0);
 #pragma unroll
     for (int it = 0; it < IPW; ++it) {
       const int item = wave + it * NW;
@@ -258,7 +251,6 @@ struct GemmPhase {
         }
       }
       if (!DOUBLE_A && it + 1 < IPW && item + NW < N_ITEMS) load_a<T, NT, NKF>(a[0], Wp, ((item + NW) % N_OG) * NT);
-      DSVT_ITEM_CLK(it + 1);
     }
   }
 

@@ -656,13 +656,6 @@ __global__ void __launch_bounds__(1024) k_tiles(Jobs jobs, GenJobs gen) {
               G.tile_rows, G.tile_pos, G.set_p, J.set_loc, G.fill_sets, J.status);
 }
 
-#ifdef DSVT_PHASE_CLOCKS
-long long* g_front_clocks = nullptr;       // [16] shader-clock stamps of thread 0 of k_front (debug builds)
-#define DSVT_FCLK(k) do { if (clk && threadIdx.x == 0) clk[k] = clock64(); } while (0)
-#else
-#define DSVT_FCLK(k) do {} while (0)
-#endif
-
 // Scan over the 1024 threads of a workgroup, continued from one call to the next through `carry`:
 // inclusive sums of a and b, and in xm the maximum of m over the threads before this one (and over
 // earlier calls).  Every thread of the workgroup calls it; two barriers inside.
@@ -742,11 +735,7 @@ __device__ __forceinline__ int32_t block_scan1(int32_t v, int32_t* wave_tot, int
 // it, tiles started before it, last rows before it [5 * n_windows] | per tile: first set, rows before it [2 * (tile_cap + 1)],
 // launch slot [tile_cap] | when there is room, 9 bytes per set for the filled tiles.
 template <int NAX>
-__global__ void __launch_bounds__(1024) k_front(Jobs jobs
-#ifdef DSVT_PHASE_CLOCKS
-                                                , long long* clk
-#endif
-                                                ) {
+__global__ void __launch_bounds__(1024) k_front(Jobs jobs) {
   const Job& J = jobs.j[blockIdx.x];
   const PartGeom& g = J.g;
   const AxisSet& ax = J.ax;
@@ -758,7 +747,6 @@ __global__ void __launch_bounds__(1024) k_front(Jobs jobs
   int32_t* __restrict__ set_loc = J.set_loc;
   const int32_t n_words = J.n_words, max_sets = J.max_sets, set_cap = J.set_cap, tile_cap = J.tile_cap;
   extern __shared__ uint32_t smem[];
-  DSVT_FCLK(0);
   __shared__ int32_t wave_tot[3][16], carry1[3], carry2[3];
   __shared__ int32_t p_cap, over_s, over_p;
   __shared__ int32_t hist[32], running[32], wave_cnt[16][32];
@@ -805,8 +793,6 @@ __global__ void __launch_bounds__(1024) k_front(Jobs jobs
       }
   }
   lds_barrier();
-  DSVT_FCLK(1);
-  DSVT_FCLK(2);
   // ---- a thread per window: count, word prefixes, then scans over the windows of (sets, padded rows,
   // last set's rows of the latest non-empty window) and of the tiles its sets start
   for (int32_t base = 0; base < nw; base += 1024) {
@@ -906,7 +892,6 @@ __global__ void __launch_bounds__(1024) k_front(Jobs jobs
     }
   }
   lds_barrier();
-  DSVT_FCLK(3);
   const int32_t n_tot = carry1[0];
   if (tid == 0) {
     *n_sets = n_tot;
@@ -987,8 +972,6 @@ __global__ void __launch_bounds__(1024) k_front(Jobs jobs
     }
     lds_barrier();
   }
-
-  DSVT_FCLK(4);
   // ---- per set: its descriptor slot, its place among the tile's sets and its first row, for k_emit
   for (int32_t w = tid; w < nw; w += 1024) {
     const int32_t N = wN[w], S = (int32_t)div_magic((uint32_t)(N + tau - 1), g.magic_tau), soff = wSoff[w];
@@ -1008,7 +991,6 @@ __global__ void __launch_bounds__(1024) k_front(Jobs jobs
       P += set_rows(nu);
     }
   }
-  DSVT_FCLK(5);
 }
 
 // One thread per voxel, axis (blockIdx.y) and job (blockIdx.z): rank d inside its window, then the slots t with
@@ -1342,11 +1324,7 @@ int run_partitions(const PartRequest* reqs, int32_t n, const int32_t* coords, in
   if (hipGetLastError() != hipSuccess) return DSVT_EHIP;      // nothing was enqueued
   if (n_front) {
     dsvt_prof_scope ps(DSVT_K_PART_TILES, st);
-    front<<<n_front, 1024, front_lds, st>>>(front_jobs
-#ifdef DSVT_PHASE_CLOCKS
-                                            , g_front_clocks
-#endif
-                                            );
+    front<<<n_front, 1024, front_lds, st>>>(front_jobs);
   }
   if (n_gen) {
     {
@@ -1379,9 +1357,6 @@ int run_partitions(const PartRequest* reqs, int32_t n, const int32_t* coords, in
 
 }  // namespace
 
-#ifdef DSVT_PHASE_CLOCKS
-extern "C" void dsvt_debug_front_clocks(long long* dev_buf) { g_front_clocks = dev_buf; }
-#endif
 
 extern "C" int dsvt_partition_bound(const dsvt_part_cfg* cfg, int32_t n_voxels, int32_t* max_sets, int32_t* max_tiles,
                                     size_t* ws_bytes) {

@@ -90,12 +90,6 @@ __device__ __forceinline__ void load_row(float (&dst)[D], const T* src) {
   }
 }
 
-#ifdef DSVT_PHASE_CLOCKS
-__device__ long long g_pool_clk[16];       // shader-clock stamps of thread 0 of workgroup 0 (debug builds)
-#define DSVT_PCLK(k) do { if (blockIdx.x == 0 && threadIdx.x == 0) g_pool_clk[k] = clock64(); } while (0)
-#else
-#define DSVT_PCLK(k) do {} while (0)
-#endif
 
 template <typename T, int C> struct PoolLds {
   static constexpr int PAD = lds_pad<T>();
@@ -139,8 +133,6 @@ kp_attention(PoolDev p, const int32_t* __restrict__ pool_inds, const int32_t* __
   int32_t* wcnt = reinterpret_cast<int32_t*>(smem + L::off_wcnt);
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), g = lane >> 4;
   const int P = p.P;
-
-  DSVT_PCLK(0);
   // (a wavefront's loads return in order: the weights are requested after the loads whose results are needed first;
   // the barriers wait for LDS traffic only, so none of them waits for weights still on their way)
   GemmPhase<T, NT_C, C, C, NW, 2> qp(reinterpret_cast<const T*>(p.w_q), wave);   // C x C phases: 4 feature groups x 2 halves of the row tiles
@@ -169,7 +161,6 @@ kp_attention(PoolDev p, const int32_t* __restrict__ pool_inds, const int32_t* __
     carry = all;
     lds_barrier();
   }
-  DSVT_PCLK(1);
   for (int c = tid; c < 2 * C; c += NTHREADS) Kb[c] = (T)p.b_kv[c];
   qp.prefetch();
   for (int mm = tid; mm <= mr; mm += NTHREADS) {
@@ -180,19 +171,15 @@ kp_attention(PoolDev p, const int32_t* __restrict__ pool_inds, const int32_t* __
   }
   lds_barrier();
   const int n_pass = reg_cum[mr - 1] / W + 1;
-
-  DSVT_PCLK(2);
   for (int idx = tid; idx < kRegs * CH; idx += NTHREADS)     // pooled rows past the last region stay zero
     if (idx / CH >= mr)
       *reinterpret_cast<uint4*>(reinterpret_cast<unsigned char*>(Ps) + (size_t)(idx / CH) * LDX * sizeof(T) + (idx % CH) * 16) =
           make_uint4(0u, 0u, 0u, 0u);
-  DSVT_PCLK(3);
   GemmPhase<T, NT_KV, C, 2 * C, NW> kv(reinterpret_cast<const T*>(p.w_kv), wave);
 
   // ---- passes: K, V of the occupied slots, then Eq. (7) per (region, head): softmax over the region's slots;
   // O replaces the head's Q entries
   const float scale = rsqrtf((float)D);
-  DSVT_PCLK(4);
   for (int ps = 0; ps < n_pass; ++ps) {
     const int ma = pass_first[ps], mb = pass_first[ps + 1];
     const int base = reg_cum[ma], rows = reg_cum[mb] - base;
@@ -222,7 +209,6 @@ kp_attention(PoolDev p, const int32_t* __restrict__ pool_inds, const int32_t* __
       }
     }
     lds_barrier();
-    DSVT_PCLK(5);
     // Eq. (6): channel-wise max over a region's occupied slots, which are consecutive rows of the tile
     for (int idx = tid; idx < (mb - ma) * CH; idx += NTHREADS) {
       const int mm = ma + idx / CH, c = idx % CH;
@@ -261,7 +247,6 @@ kp_attention(PoolDev p, const int32_t* __restrict__ pool_inds, const int32_t* __
       }
     });
     lds_barrier();
-    DSVT_PCLK(6);
     // Eq. (7) per (region, head): softmax over the region's slots; O replaces the head's Q entries.  The
     // occupied slots are rows r0 .. r0 + cnt - 1; the P - cnt empty ones all have the bias vectors as key and
     // value, so they enter as one key of that weight (or not at all when empty slots are masked).
@@ -308,8 +293,6 @@ kp_attention(PoolDev p, const int32_t* __restrict__ pool_inds, const int32_t* __
     }
     lds_barrier();
   }
-
-  DSVT_PCLK(7);
   // ---- out = LN(P + O Wo^T + bo)
   GemmPhase<T, NT_C, C, C, NW, 2> op(reinterpret_cast<const T*>(p.w_o), wave);
   op.prefetch();
@@ -337,7 +320,6 @@ kp_attention(PoolDev p, const int32_t* __restrict__ pool_inds, const int32_t* __
       }
   layer_norm_tile<T, NT_C, C, RH>(keep, o_own, og_own, rt_own, HC, stat, ga, be, p.ln_eps, Ps, LDX);
   lds_barrier();
-  DSVT_PCLK(8);
   for (int idx = tid; idx < mr * CH; idx += NTHREADS) {
     const int r = idx / CH, c = idx - r * CH;
     reinterpret_cast<uint4*>(out + (size_t)(m0 + r) * C)[c] =
@@ -433,11 +415,6 @@ int launch_pool_attention(const dsvt_pool_cfg& c, const PoolPlan& pl, const int3
 
 }  // namespace
 
-#ifdef DSVT_PHASE_CLOCKS
-extern "C" int dsvt_debug_pool_clocks(long long* host16) {
-  return hipMemcpyFromSymbol(host16, HIP_SYMBOL(g_pool_clk), 16 * sizeof(long long)) == hipSuccess ? 0 : -1;
-}
-#endif
 
 extern "C" int dsvt_pool_packed_size(const dsvt_pool_cfg* cfg, size_t* bytes) {
   if (!cfg || !bytes) return DSVT_EINVAL;
