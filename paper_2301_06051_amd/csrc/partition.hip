@@ -465,17 +465,33 @@ __device__ __forceinline__ void build_tiles(const int32_t* set_w, const int32_t*
   // Frames of many rounds over the compute units: a tile costs a fixed amount plus its rows, so tiles are filled
   // as far as they go (84 rows per tile on average instead of rows_per_cut), see fill_tile_starts.
   bool filled = false;
-  if (n_sets <= fill_sets && n_sets < 65535 && fill_wanted(set_p[n_sets], n_sets, rows_per_cut)) {
+  if (fill_sets > 0 && fill_wanted(set_p[n_sets], n_sets, rows_per_cut)) {
     int32_t* P = reinterpret_cast<int32_t*>(fill_lds);                       // [fill_sets + 1]
     uint16_t* jump = reinterpret_cast<uint16_t*>(P + fill_sets + 1);         // [2][fill_sets + 1]
     uint16_t* jump2 = jump + fill_sets + 1;
     uint8_t* mark = reinterpret_cast<uint8_t*>(jump2 + fill_sets + 1);       // [fill_sets + 1]
-    for (int32_t s = tid; s <= n_sets; s += 1024) P[s] = set_p[s];
-    __syncthreads();
-    filled = fill_tiles(P, jump, jump2, mark, n_sets, rows_per_cut);
-    if (filled)
-      for (int32_t s = tid; s < n_sets; s += 1024)
-        if (mark[s]) set_loc[s] = -2;
+    if (n_sets <= fill_sets && n_sets < 65535) {
+      for (int32_t s = tid; s <= n_sets; s += 1024) P[s] = set_p[s];
+      __syncthreads();
+      filled = fill_tiles(P, jump, jump2, mark, n_sets, rows_per_cut);
+      if (filled)
+        for (int32_t s = tid; s < n_sets; s += 1024)
+          if (mark[s]) set_loc[s] = -2;
+    } else {
+      // More sets than the tables hold (a frame of many rounds): the sequence is taken in pieces of fill_sets sets,
+      // every piece starting a tile of its own, tiles filled to the full 96 rows (one short tile per piece at most).
+      filled = true;
+      const int32_t piece = fill_sets < 65534 ? fill_sets : 65534;
+      for (int32_t c0 = 0; c0 < n_sets; c0 += piece) {
+        const int32_t n_c = n_sets - c0 < piece ? n_sets - c0 : piece;
+        for (int32_t s = tid; s <= n_c; s += 1024) P[s] = set_p[c0 + s];
+        __syncthreads();
+        fill_tile_starts(P, jump, jump2, mark, n_c, kTileRows);
+        for (int32_t s = tid; s < n_c; s += 1024)
+          if (mark[s]) set_loc[c0 + s] = -2;
+        __syncthreads();
+      }
+    }
   }
   __threadfence_block();
   __syncthreads();
@@ -1294,8 +1310,11 @@ int run_partitions(const PartRequest* reqs, int32_t n, const int32_t* coords, in
       G.set_bound = p.set_bound;
       G.want_tiles = P.want_tiles ? 1 : 0;
       // tables of the tile filling (see build_tiles), when this frame's sets fit the LDS
-      const size_t need = ((size_t)p.set_bound + 1) * 9 + 16;
-      G.fill_sets = (P.want_tiles && need <= kFrontLds) ? p.set_bound : 0;
+      // (9 bytes per set; frames with more sets than the LDS holds are filled in pieces of kFillPiece sets)
+      constexpr int32_t kFillPiece = 16384;
+      G.fill_sets = P.want_tiles ? (p.set_bound < kFillPiece ? p.set_bound : kFillPiece) : 0;
+      const size_t need = ((size_t)G.fill_sets + 1) * 9 + 16;
+      static_assert(((size_t)kFillPiece + 1) * 9 + 16 <= kFrontLds, "tables of one piece fit the LDS k_tiles may ask for");
       if (G.fill_sets) fill_lds = need > fill_lds ? need : fill_lds;
       any_tiles |= G.want_tiles;
       int32_t group = 1;

@@ -122,7 +122,7 @@ def test_small_frames_spread_over_the_compute_units(n):
             assert nt <= 256
 
 
-@pytest.mark.parametrize("cid,n", [(2, 45000), (2, 64000), (3, None)])
+@pytest.mark.parametrize("cid,n", [(2, 45000), (2, 64000), (3, None), (5, None)])
 def test_large_frames_get_filled_tiles(cid, n):
     """Frames of several rounds over the compute units: a set starts a tile only when it no longer fits the tile before,
     so tiles hold more than the 64 rows a fixed cut gives; for a frame of a few rounds the tile count ends just under a
