@@ -320,7 +320,8 @@ int dsvt_vfe(const dsvt_vfe_cfg* cfg, const float* points, const int32_t* point_
 
 /* ---------------------------------------------------------------------------------------
  * Instrumentation for benchmarks (not part of the method): per-kernel time from hipEvent pairs
- * recorded around every launch while enabled.  Host-only; not thread-safe.
+ * recorded around every launch while enabled (launches of one kernel that follow one another on a
+ * stream share a pair: begin before the first, end after the last).  Host-only; not thread-safe.
  * dsvt_prof_enable creates events for up to max_launches launches (later ones go unrecorded);
  * dsvt_prof_collect waits for them, fills total_ms[k] / launches[k] for the
  * dsvt_prof_kernel_count() kernel ids (names from dsvt_prof_kernel_name), destroys the events
