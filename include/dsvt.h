@@ -280,8 +280,8 @@ int dsvt_bev_scatter(const int32_t* coords, const void* x, int32_t n_voxels, int
                      int32_t batch, const int32_t grid[3], void* out, int32_t* status, void* stream);
 
 /* ---------------------------------------------------------------------------------------
- * Voxel feature encoding (Sec. 3.1, overview: the input points are first converted into sparse
- * voxels by a voxel feature encoding module, each voxel then being one token).  The paper names
+ * Voxel feature encoding (Sec. 3.1, overview): points are binned into the occupied cells of the grid
+ * and reduced per cell to one feature row, the token the first block takes.  The paper names
  * the step and cites earlier pillar encoders; built here is the plain member of that family:
  *   x[v] = max over the points p of voxel v of (w f_p + b), channel by channel, then max(., 0)
  *   if relu; w == NULL: x[v] = max over p of f_p (C == f_in).

@@ -1,6 +1,7 @@
-// dsvt_bev_scatter: the step after the last DSVT block (Sec. 3.1 overview: the voxel features are
-// projected to a bird's-eye-view feature map for the 2D backbone).  Pure bandwidth: the dense map is
-// written once (zeros, then the occupied cells' rows), the sparse rows are read once.
+// dsvt_bev_scatter: the step after the last DSVT block (Sec. 3.1, overview): each occupied cell's
+// row is placed at its cell of a dense channels-last map, the image a 2D network takes.  Pure
+// bandwidth: the dense map is written once (zeros, then the occupied cells' rows), the sparse rows
+// are read once.
 #include "common.h"
 
 namespace {
