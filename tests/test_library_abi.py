@@ -30,6 +30,17 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(lib, name), name
 
 
+def test_library_exports_nothing_the_header_does_not_declare():
+    """Every exported dsvt_* function is a declared one: no debug or instrumentation entry points beside the header's."""
+    import subprocess
+    if not os.path.exists(LIB):
+        import __graft_entry__
+        __graft_entry__.build()
+    out = subprocess.run(["nm", "-D", "--defined-only", LIB], capture_output=True, text=True, check=True).stdout
+    exported = {l.split()[-1] for l in out.splitlines() if l.split() and l.split()[-2] in ("T", "t") and l.split()[-1].startswith("dsvt_")}
+    assert exported and exported <= set(_declared()), sorted(exported - set(_declared()))
+
+
 def test_host_only_calls_work_without_a_gpu():
     """dsvt_partition_bound is pure host arithmetic: the set bound and a positive scratch size."""
     if not os.path.exists(LIB):
