@@ -73,6 +73,11 @@ __device__ __forceinline__ int opaque_tid() {
 // of 64 bytes) then have a pitch that is an odd multiple of 32 bytes, the one pitch at which the
 // 16-byte fragment loads of a wavefront (16 rows x 4 k-slices) run at the full LDS rate; measured
 // on gfx950: 225 B/clk per CU against 125-150 B/clk for pitches of 16, 48 or 0 mod 64 bytes.
+// Declares v defined, with whatever its registers hold and without an instruction.  For variables that are assigned
+// on some paths only and read on those paths only: in a loop, the compiler otherwise moves the "undefined" definition
+// of the other paths in front of the loop and keeps registers for it through every iteration.
+template <typename V> __device__ __forceinline__ void opaque_def(V& v) { asm volatile("" : "=v"(v)); }
+
 template <typename T> constexpr int lds_pad() { return 32 / (int)sizeof(T); }
 
 // Packed weights.  A matrix W [OUT, K] is stored fragment by fragment in the order the MFMA "A"
@@ -168,6 +173,17 @@ struct GemmPhase {
   bool bias0_set = false;
 
   __device__ __forceinline__ GemmPhase(const T* wp, int wave_) : Wp(wp), wave(wave_) {}
+
+  // In a loop that requests the weights anew in every trip: called at the top of the trip, it ends the life of the
+  // weight registers of the trip before (see opaque_def).
+  __device__ __forceinline__ void forget() {
+#pragma unroll
+    for (int k = 0; k < (int)(sizeof(a) / sizeof(a[0])); ++k)
+#pragma unroll
+      for (int kf = 0; kf < NKF; ++kf)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) opaque_def(a[k].f[kf][nt]);
+  }
 
   // Request the weights of this wavefront's first item (may be called long before run()), and
   // with them, if given, the bias run() starts that item from.

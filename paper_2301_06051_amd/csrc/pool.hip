@@ -19,6 +19,7 @@ namespace {
 constexpr int kMaxPool = 8;                       // slots of a pooling region
 constexpr int kRegs = 48;                         // regions (pooled rows) of a workgroup: three MFMA row tiles
 constexpr int kSlots = kRegs * kMaxPool;          // their dense slots at most
+constexpr int kPoolGrid = 256;                    // workgroups of the attention kernel: the compute units of an MI355X
 
 struct PoolGeom {
   int32_t grid[3], pool[3], pg[3];                // cells, region size, pooled cells per axis
@@ -108,6 +109,10 @@ template <typename T, int C> struct PoolLds {
   static_assert(kStat <= kTile && total <= 160 * 1024 && off_bias % 16 == 0, "pooling tile does not fit the LDS");
 };
 
+// A workgroup walks over groups of kRegs regions (group blockIdx.x, then every gridDim.x-th), software-pipelined: the
+// slot table of the next group is requested during the softmax of the current one, and its occupancy scan and the
+// request for its rows come before the current group's output projection and LayerNorm, so that the two memory
+// round trips of a group (slots, then rows) are behind arithmetic of its predecessor.  One workgroup fits a CU.
 template <typename T, int C, int HEADS, int NT_KV, int NT_C>
 __global__ void __launch_bounds__(kWaves * 64)
 kp_attention(PoolDev p, const int32_t* __restrict__ pool_inds, const int32_t* __restrict__ n_out_ptr,
@@ -116,6 +121,7 @@ kp_attention(PoolDev p, const int32_t* __restrict__ pool_inds, const int32_t* __
   typedef typename Mma<T>::Vec4 Vec4;
   constexpr int LDX = L::LDX, D = C / HEADS, NW = kWaves, NTHREADS = NW * 64;
   constexpr int CH = C * (int)sizeof(T) / 16, EPC = 16 / (int)sizeof(T);     // 16-byte chunks of a row, elements per chunk
+  static_assert(kSlots <= NTHREADS, "one slot per thread");
   extern __shared__ __align__(16) unsigned char smem[];
   T* Xs = reinterpret_cast<T*>(smem + L::off_x);      // occupied slots of the pass, one row each
   T* Ks = reinterpret_cast<T*>(smem + L::off_k);
@@ -131,199 +137,239 @@ kp_attention(PoolDev p, const int32_t* __restrict__ pool_inds, const int32_t* __
   T* Kb = reinterpret_cast<T*>(smem + L::off_bias);   // key and value of an empty slot
   T* Vb = Kb + C;
   int32_t* wcnt = reinterpret_cast<int32_t*>(smem + L::off_wcnt);
-  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), g = lane >> 4;
+  const int tid0 = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid0 >> 6);
   const int P = p.P;
-  // (a wavefront's loads return in order: the weights are requested after the loads whose results are needed first;
-  // the barriers wait for LDS traffic only, so none of them waits for weights still on their way)
-  GemmPhase<T, NT_C, C, C, NW, 2> qp(reinterpret_cast<const T*>(p.w_q), wave);   // C x C phases: 4 feature groups x 2 halves of the row tiles
   const int n_out = __builtin_amdgcn_readfirstlane(*n_out_ptr);
-  const int m0 = blockIdx.x * kRegs;
-  if (m0 >= n_out) return;
-  const int mr = (n_out - m0) < kRegs ? (n_out - m0) : kRegs;
-  const int slots = mr * P;
+  const int n_groups = (n_out + kRegs - 1) / kRegs;
+  if ((int)blockIdx.x >= n_groups) return;
   const int W = kRowsMax + 1 - P;                  // a pass takes the regions whose first occupied slot number lies in one
                                                    // run of W: together at most W - 1 + P = 96 rows
-
-  // ---- slots: voxel and number of occupied slots before it
-  int carry = 0;
-  for (int s0 = 0; s0 < slots; s0 += NTHREADS) {
-    const int sl = s0 + tid;
-    const int v = sl < slots ? pool_inds[(size_t)m0 * P + sl] : -1;
-    const unsigned long long occ = __ballot(v >= 0);
-    if (lane == 0) wcnt[wave] = __popcll(occ);
-    lds_barrier();
-    int before = carry;
-    for (int k = 0; k < wave; ++k) before += wcnt[k];
-    int all = carry;
-    for (int k = 0; k < NW; ++k) all += wcnt[k];
-    const int cum = before + __popcll(occ & ((1ull << lane) - 1ull));
-    if (sl < slots) { slot_vox[sl] = v; slot_cum[sl] = (uint16_t)cum; }
-    carry = all;
-    lds_barrier();
-  }
-  for (int c = tid; c < 2 * C; c += NTHREADS) Kb[c] = (T)p.b_kv[c];
-  qp.prefetch();
-  for (int mm = tid; mm <= mr; mm += NTHREADS) {
-    const int cum = mm < mr ? slot_cum[mm * P] : carry;
-    reg_cum[mm] = cum;
-    if (mm == mr) pass_first[(slot_cum[(mr - 1) * P] / W) + 1] = mr;
-    else if (mm == 0 || slot_cum[(mm - 1) * P] / W != cum / W) pass_first[cum / W] = mm;
-  }
-  lds_barrier();
-  const int n_pass = reg_cum[mr - 1] / W + 1;
-  for (int idx = tid; idx < kRegs * CH; idx += NTHREADS)     // pooled rows past the last region stay zero
-    if (idx / CH >= mr)
-      *reinterpret_cast<uint4*>(reinterpret_cast<unsigned char*>(Ps) + (size_t)(idx / CH) * LDX * sizeof(T) + (idx % CH) * 16) =
-          make_uint4(0u, 0u, 0u, 0u);
-  GemmPhase<T, NT_KV, C, 2 * C, NW> kv(reinterpret_cast<const T*>(p.w_kv), wave);
-
-  // ---- passes: K, V of the occupied slots, then Eq. (7) per (region, head): softmax over the region's slots;
-  // O replaces the head's Q entries
   const float scale = rsqrtf((float)D);
-  for (int ps = 0; ps < n_pass; ++ps) {
-    const int ma = pass_first[ps], mb = pass_first[ps + 1];
-    const int base = reg_cum[ma], rows = reg_cum[mb] - base;
-    const int RT = (rows + 15) >> 4;
-    for (int r = rows + tid; r < RT * 16; r += NTHREADS) row_vox[r] = -1;
-    for (int sl = ma * P + tid; sl < mb * P; sl += NTHREADS) {
-      const int v = slot_vox[sl];
-      if (v >= 0) row_vox[slot_cum[sl] - base] = v;
-    }
-    lds_barrier();
-    {
-      constexpr int G = (kRowsMax * CH + NTHREADS - 1) / NTHREADS;      // gather: every load requested before the first store
-      uint4 val[G];
-#pragma unroll
-      for (int k = 0; k < G; ++k) {
-        const int idx = tid + k * NTHREADS, r = idx / CH, c = idx - r * CH;
-        const int v = idx < RT * 16 * CH ? row_vox[r] : -1;
-        val[k] = make_uint4(0u, 0u, 0u, 0u);
-        if (v >= 0) val[k] = reinterpret_cast<const uint4*>(x + (size_t)v * C)[c];
-      }
-      if (ps == 0) kv.prefetch();
-#pragma unroll
-      for (int k = 0; k < G; ++k) {
-        const int idx = tid + k * NTHREADS, r = idx / CH, c = idx - r * CH;
-        if (idx < RT * 16 * CH)
-          *reinterpret_cast<uint4*>(reinterpret_cast<unsigned char*>(Xs) + (size_t)r * LDX * sizeof(T) + c * 16) = val[k];
-      }
-    }
-    lds_barrier();
-    // Eq. (6): channel-wise max over a region's occupied slots, which are consecutive rows of the tile
-    for (int idx = tid; idx < (mb - ma) * CH; idx += NTHREADS) {
-      const int mm = ma + idx / CH, c = idx % CH;
-      const int r0 = reg_cum[mm] - base, cnt = reg_cum[mm + 1] - reg_cum[mm];
-      float best[EPC];
-#pragma unroll
-      for (int e = 0; e < EPC; ++e) best[e] = -INFINITY;
-      for (int r = r0; r < r0 + cnt; ++r) {
-        const uint4 raw = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(Xs) + (size_t)r * LDX * sizeof(T) + c * 16);
-        const T* e4 = reinterpret_cast<const T*>(&raw);
-#pragma unroll
-        for (int e = 0; e < EPC; ++e) best[e] = fmaxf(best[e], to_f32<T>(e4[e]));
-      }
-      uint4 packed;
-      T* o4 = reinterpret_cast<T*>(&packed);
-#pragma unroll
-      for (int e = 0; e < EPC; ++e) o4[e] = (T)best[e];
-      *reinterpret_cast<uint4*>(reinterpret_cast<unsigned char*>(Ps) + (size_t)mm * LDX * sizeof(T) + c * 16) = packed;
-    }
-    kv.run(Xs, LDX, RT, p.b_kv, [&](int o0, int r, f32x4 (&acc)[NT_KV], bool) {
-      const int row = 16 * r + (lane & 15);
-#pragma unroll
-      for (int nt = 0; nt < NT_KV; ++nt) {
-        const int ot = o0 + 16 * nt, o = ot + 4 * g;
-        if (ot < C) *reinterpret_cast<Vec4*>(Ks + row * LDX + o) = pack4<T>(acc[nt]);
-        else *reinterpret_cast<Vec4*>(Vs + row * LDX + (o - C)) = pack4<T>(acc[nt]);
-      }
-    });
-    lds_barrier();
-    // Q of the pooled rows of this pass (the rows of earlier passes hold their results already)
-    qp.run(Ps, LDX, kRegs / 16, p.b_q, [&](int o0, int r, f32x4 (&acc)[NT_C], bool) {
-      const int row = 16 * r + (lane & 15);
-      if (row >= ma && row < mb) {
-#pragma unroll
-        for (int nt = 0; nt < NT_C; ++nt) *reinterpret_cast<Vec4*>(Qs + row * LDX + o0 + 16 * nt + 4 * g) = pack4<T>(acc[nt]);
-      }
-    });
-    lds_barrier();
-    // Eq. (7) per (region, head): softmax over the region's slots; O replaces the head's Q entries.  The
-    // occupied slots are rows r0 .. r0 + cnt - 1; the P - cnt empty ones all have the bias vectors as key and
-    // value, so they enter as one key of that weight (or not at all when empty slots are masked).
-    for (int it = tid; it < (mb - ma) * HEADS; it += NTHREADS) {
-      const int mm = ma + it / HEADS, h = it % HEADS;
-      const int r0 = reg_cum[mm] - base, cnt = reg_cum[mm + 1] - reg_cum[mm];
-      const float holes = p.mask_empty ? 0.f : (float)(P - cnt);
-      T* q = Qs + mm * LDX + h * D;
-      float qv[D], o[D], logit[kMaxPool + 1];
-      load_row<T, D>(qv, q);
-      float mx = -INFINITY;
-#pragma unroll
-      for (int s = 0; s <= kMaxPool; ++s) {
-        logit[s] = -INFINITY;
-        const bool real = s < cnt, hole = s == kMaxPool && holes > 0.f;
-        if (real || hole) {
-          float kvv[D];
-          load_row<T, D>(kvv, real ? Ks + (r0 + s) * LDX + h * D : Kb + h * D);
-          float acc = 0.f;
-#pragma unroll
-          for (int j = 0; j < D; ++j) acc = fmaf(qv[j], kvv[j], acc);
-          logit[s] = acc * scale;
-          mx = fmaxf(mx, logit[s]);
-        }
-      }
-#pragma unroll
-      for (int j = 0; j < D; ++j) o[j] = 0.f;
-      float sum = 0.f;
-#pragma unroll
-      for (int s = 0; s <= kMaxPool; ++s) {
-        const bool real = s < cnt, hole = s == kMaxPool && holes > 0.f;
-        if (real || hole) {
-          const float e = __expf(logit[s] - mx) * (hole ? holes : 1.f);
-          sum += e;
-          float kvv[D];
-          load_row<T, D>(kvv, real ? Vs + (r0 + s) * LDX + h * D : Vb + h * D);
-#pragma unroll
-          for (int j = 0; j < D; ++j) o[j] = fmaf(e, kvv[j], o[j]);
-        }
-      }
-      const float inv = 1.0f / sum;
-#pragma unroll
-      for (int j = 0; j < D; ++j) q[j] = (T)(o[j] * inv);
-    }
-    lds_barrier();
-  }
-  // ---- out = LN(P + O Wo^T + bo)
+  // (a wavefront's loads return in order: weights are requested after the loads whose results are needed first; the
+  // barriers wait for LDS traffic only, so none of them waits for weights or rows still on their way)
+  GemmPhase<T, NT_KV, C, 2 * C, NW> kv(reinterpret_cast<const T*>(p.w_kv), wave);
+  GemmPhase<T, NT_C, C, C, NW, 2> qp(reinterpret_cast<const T*>(p.w_q), wave);   // C x C phases: 4 feature groups x 2 halves of the row tiles
   GemmPhase<T, NT_C, C, C, NW, 2> op(reinterpret_cast<const T*>(p.w_o), wave);
-  op.prefetch();
   constexpr int N_OG = C / (16 * NT_C), RH = kRowTiles / 2;
   static_assert(2 * N_OG == NW && kRegs / 16 <= 2 * RH - 1, "one output-projection item per wavefront");
   const int og_own = wave % N_OG, half = wave / N_OG;
   const int o_own = og_own * 16 * NT_C, rt_own = half ? 2 : 0, HC = half ? kRegs / 16 - 2 : 2;
-  f32x4 bo4[NT_C], ga[NT_C], be[NT_C];
+  constexpr int G = (kRowsMax * CH + NTHREADS - 1) / NTHREADS;      // 16-byte pieces of a pass's rows per thread
+
+  for (int c = tid0; c < 2 * C; c += NTHREADS) Kb[c] = (T)p.b_kv[c];
+  auto slot_of = [&](int grp, int tid) {                              // this thread's slot of a group: its voxel or -1
+    const int m0 = grp * kRegs, mr = (n_out - m0) < kRegs ? (n_out - m0) : kRegs;
+    return tid < mr * P ? pool_inds[(size_t)m0 * P + tid] : -1;
+  };
+  int v_slot = slot_of((int)blockIdx.x, tid0);
+  int m0_prev = 0, mr_prev = 0;
+
+  for (int grp = (int)blockIdx.x;; grp += (int)gridDim.x) {
+    // (the thread index is taken anew in every trip, or the compiler computes every address that depends on it
+    // once, in front of the loop, and keeps -- spills -- them all)
+    const int tid = opaque_tid(), lane = tid & 63, g = lane >> 4;
+    const bool have = grp < n_groups, have_prev = grp != (int)blockIdx.x;     // (uniform)
+    const int m0 = grp * kRegs;
+    const int mr = have ? ((n_out - m0) < kRegs ? (n_out - m0) : kRegs) : 0;
+    int n_pass = 0, RT0 = 0;
+    uint4 val[G];
 #pragma unroll
-  for (int nt = 0; nt < NT_C; ++nt) {
-    bo4[nt] = *reinterpret_cast<const f32x4*>(p.b_o + o_own + 16 * nt + 4 * g);
-    ga[nt] = *reinterpret_cast<const f32x4*>(p.ln_g + o_own + 16 * nt + 4 * g);
-    be[nt] = *reinterpret_cast<const f32x4*>(p.ln_b + o_own + 16 * nt + 4 * g);
-  }
-  f32x4 keep[NT_C][RH];
-  if (HC == 1) op.template run_keep<1>(Qs, LDX, rt_own, bo4, keep);
-  else op.template run_keep<2>(Qs, LDX, rt_own, bo4, keep);
-#pragma unroll
-  for (int nt = 0; nt < NT_C; ++nt)
-#pragma unroll
-    for (int r = 0; r < RH; ++r)
-      if (r < HC) {
-        const Vec4 xr = *reinterpret_cast<const Vec4*>(Ps + (16 * (rt_own + r) + (lane & 15)) * LDX + o_own + 16 * nt + 4 * g);
-        keep[nt][r] += f32x4{to_f32<T>(xr[0]), to_f32<T>(xr[1]), to_f32<T>(xr[2]), to_f32<T>(xr[3])};
+    for (int k = 0; k < G; ++k) opaque_def(val[k]);
+    qp.forget();
+    op.forget();
+    if (have_prev) op.prefetch();                  // ahead of this group's rows in the queue
+    if (have) {
+      // ---- slots: voxel and number of occupied slots before it (what the row loads below need to know)
+      const unsigned long long occ = __ballot(v_slot >= 0);
+      if (lane == 0) wcnt[wave] = __popcll(occ);
+      lds_barrier();
+      int before = 0, all = 0;
+      for (int k = 0; k < NW; ++k) { const int w = wcnt[k]; all += w; if (k < wave) before += w; }
+      if (tid < mr * P) { slot_vox[tid] = v_slot; slot_cum[tid] = (uint16_t)(before + __popcll(occ & ((1ull << lane) - 1ull))); }
+      lds_barrier();
+      for (int mm = tid; mm <= mr; mm += NTHREADS) {
+        const int cum = mm < mr ? slot_cum[mm * P] : all;
+        reg_cum[mm] = cum;
+        if (mm == mr) pass_first[(slot_cum[(mr - 1) * P] / W) + 1] = mr;
+        else if (mm == 0 || slot_cum[(mm - 1) * P] / W != cum / W) pass_first[cum / W] = mm;
       }
-  layer_norm_tile<T, NT_C, C, RH>(keep, o_own, og_own, rt_own, HC, stat, ga, be, p.ln_eps, Ps, LDX);
-  lds_barrier();
-  for (int idx = tid; idx < mr * CH; idx += NTHREADS) {
-    const int r = idx / CH, c = idx - r * CH;
-    reinterpret_cast<uint4*>(out + (size_t)(m0 + r) * C)[c] =
-        *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(Ps) + (size_t)r * LDX * sizeof(T) + c * 16);
+      lds_barrier();
+      n_pass = reg_cum[mr - 1] / W + 1;
+      // ---- rows of the first pass: requested now, stored once the tile is free
+      const int mb0 = pass_first[1], rows0 = reg_cum[mb0];
+      RT0 = (rows0 + 15) >> 4;
+      for (int r = rows0 + tid; r < RT0 * 16; r += NTHREADS) row_vox[r] = -1;
+      if (tid < mb0 * P && v_slot >= 0) row_vox[slot_cum[tid]] = v_slot;
+      lds_barrier();
+#pragma unroll
+      for (int k = 0; k < G; ++k) {
+        const int idx = tid + k * NTHREADS, r = idx / CH, c = idx - r * CH;
+        const int v = idx < RT0 * 16 * CH ? row_vox[r] : -1;
+        val[k] = make_uint4(0u, 0u, 0u, 0u);
+        if (v >= 0) val[k] = reinterpret_cast<const uint4*>(x + (size_t)v * C)[c];
+      }
+    }
+    if (have_prev) {
+      // ---- the group before: out = LN(P + O Wo^T + bo), its rows to memory
+      f32x4 bo4[NT_C], ga[NT_C], be[NT_C];
+#pragma unroll
+      for (int nt = 0; nt < NT_C; ++nt) bo4[nt] = *reinterpret_cast<const f32x4*>(p.b_o + o_own + 16 * nt + 4 * g);
+      f32x4 keep[NT_C][RH];
+      if (HC == 1) op.template run_keep<1>(Qs, LDX, rt_own, bo4, keep);
+      else op.template run_keep<2>(Qs, LDX, rt_own, bo4, keep);
+#pragma unroll
+      for (int nt = 0; nt < NT_C; ++nt) {
+        ga[nt] = *reinterpret_cast<const f32x4*>(p.ln_g + o_own + 16 * nt + 4 * g);
+        be[nt] = *reinterpret_cast<const f32x4*>(p.ln_b + o_own + 16 * nt + 4 * g);
+      }
+#pragma unroll
+      for (int nt = 0; nt < NT_C; ++nt)
+#pragma unroll
+        for (int r = 0; r < RH; ++r)
+          if (r < HC) {
+            const Vec4 xr = *reinterpret_cast<const Vec4*>(Ps + (16 * (rt_own + r) + (lane & 15)) * LDX + o_own + 16 * nt + 4 * g);
+            keep[nt][r] += f32x4{to_f32<T>(xr[0]), to_f32<T>(xr[1]), to_f32<T>(xr[2]), to_f32<T>(xr[3])};
+          }
+      layer_norm_tile<T, NT_C, C, RH>(keep, o_own, og_own, rt_own, HC, stat, ga, be, p.ln_eps, Ps, LDX);
+      lds_barrier();
+      for (int idx = tid; idx < mr_prev * CH; idx += NTHREADS) {
+        const int r = idx / CH, c = idx - r * CH;
+        reinterpret_cast<uint4*>(out + (size_t)(m0_prev + r) * C)[c] =
+            *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(Ps) + (size_t)r * LDX * sizeof(T) + c * 16);
+      }
+      lds_barrier();                               // (the pooled rows and the statistics are free from here)
+    }
+    if (!have) break;
+    m0_prev = m0; mr_prev = mr;
+    kv.prefetch();
+#pragma unroll
+    for (int k = 0; k < G; ++k) {
+      const int idx = tid + k * NTHREADS, r = idx / CH, c = idx - r * CH;
+      if (idx < RT0 * 16 * CH)
+        *reinterpret_cast<uint4*>(reinterpret_cast<unsigned char*>(Xs) + (size_t)r * LDX * sizeof(T) + c * 16) = val[k];
+    }
+    if (mr < kRegs)
+      for (int idx = tid; idx < kRegs * CH; idx += NTHREADS)     // pooled rows past the last region are zero
+        if (idx / CH >= mr)
+          *reinterpret_cast<uint4*>(reinterpret_cast<unsigned char*>(Ps) + (size_t)(idx / CH) * LDX * sizeof(T) + (idx % CH) * 16) =
+              make_uint4(0u, 0u, 0u, 0u);
+
+    // ---- passes: K, V of the occupied slots, then Eq. (7) per (region, head): softmax over the region's slots;
+    // O replaces the head's Q entries
+    for (int ps = 0; ps < n_pass; ++ps) {
+      const int ma = pass_first[ps], mb = pass_first[ps + 1];
+      const int base = reg_cum[ma], rows = reg_cum[mb] - base;
+      const int RT = (rows + 15) >> 4;
+      if (ps > 0) {                                // (the first pass's rows are on their way into the tile already)
+        for (int r = rows + tid; r < RT * 16; r += NTHREADS) row_vox[r] = -1;
+        for (int sl = ma * P + tid; sl < mb * P; sl += NTHREADS) {
+          const int v = slot_vox[sl];
+          if (v >= 0) row_vox[slot_cum[sl] - base] = v;
+        }
+        lds_barrier();
+        uint4 val2[G];                             // gather: every load requested before the first store
+#pragma unroll
+        for (int k = 0; k < G; ++k) {
+          const int idx = tid + k * NTHREADS, r = idx / CH, c = idx - r * CH;
+          const int v = idx < RT * 16 * CH ? row_vox[r] : -1;
+          val2[k] = make_uint4(0u, 0u, 0u, 0u);
+          if (v >= 0) val2[k] = reinterpret_cast<const uint4*>(x + (size_t)v * C)[c];
+        }
+        kv.prefetch();
+#pragma unroll
+        for (int k = 0; k < G; ++k) {
+          const int idx = tid + k * NTHREADS, r = idx / CH, c = idx - r * CH;
+          if (idx < RT * 16 * CH)
+            *reinterpret_cast<uint4*>(reinterpret_cast<unsigned char*>(Xs) + (size_t)r * LDX * sizeof(T) + c * 16) = val2[k];
+        }
+      }
+      lds_barrier();
+      // Eq. (6): channel-wise max over a region's occupied slots, which are consecutive rows of the tile
+      for (int idx = tid; idx < (mb - ma) * CH; idx += NTHREADS) {
+        const int mm = ma + idx / CH, c = idx % CH;
+        const int r0 = reg_cum[mm] - base, cnt = reg_cum[mm + 1] - reg_cum[mm];
+        float best[EPC];
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) best[e] = -INFINITY;
+        for (int r = r0; r < r0 + cnt; ++r) {
+          const uint4 raw = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(Xs) + (size_t)r * LDX * sizeof(T) + c * 16);
+          const T* e4 = reinterpret_cast<const T*>(&raw);
+#pragma unroll
+          for (int e = 0; e < EPC; ++e) best[e] = fmaxf(best[e], to_f32<T>(e4[e]));
+        }
+        uint4 packed;
+        T* o4 = reinterpret_cast<T*>(&packed);
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) o4[e] = (T)best[e];
+        *reinterpret_cast<uint4*>(reinterpret_cast<unsigned char*>(Ps) + (size_t)mm * LDX * sizeof(T) + c * 16) = packed;
+      }
+      kv.run(Xs, LDX, RT, p.b_kv, [&](int o0, int r, f32x4 (&acc)[NT_KV], bool) {
+        const int row = 16 * r + (lane & 15);
+#pragma unroll
+        for (int nt = 0; nt < NT_KV; ++nt) {
+          const int ot = o0 + 16 * nt, o = ot + 4 * g;
+          if (ot < C) *reinterpret_cast<Vec4*>(Ks + row * LDX + o) = pack4<T>(acc[nt]);
+          else *reinterpret_cast<Vec4*>(Vs + row * LDX + (o - C)) = pack4<T>(acc[nt]);
+        }
+      });
+      qp.prefetch();
+      lds_barrier();
+      // Q of the pooled rows of this pass (the rows of earlier passes hold their results already)
+      qp.run(Ps, LDX, kRegs / 16, p.b_q, [&](int o0, int r, f32x4 (&acc)[NT_C], bool) {
+        const int row = 16 * r + (lane & 15);
+        if (row >= ma && row < mb) {
+#pragma unroll
+          for (int nt = 0; nt < NT_C; ++nt) *reinterpret_cast<Vec4*>(Qs + row * LDX + o0 + 16 * nt + 4 * g) = pack4<T>(acc[nt]);
+        }
+      });
+      if (ps == n_pass - 1) v_slot = grp + (int)gridDim.x < n_groups ? slot_of(grp + (int)gridDim.x, tid) : -1;   // used after the softmax
+      lds_barrier();
+      // Eq. (7) per (region, head): softmax over the region's slots; O replaces the head's Q entries.  The
+      // occupied slots are rows r0 .. r0 + cnt - 1; the P - cnt empty ones all have the bias vectors as key and
+      // value, so they enter as one key of that weight (or not at all when empty slots are masked).
+      for (int it = tid; it < (mb - ma) * HEADS; it += NTHREADS) {
+        const int mm = ma + it / HEADS, h = it % HEADS;
+        const int r0 = reg_cum[mm] - base, cnt = reg_cum[mm + 1] - reg_cum[mm];
+        const float holes = p.mask_empty ? 0.f : (float)(P - cnt);
+        T* q = Qs + mm * LDX + h * D;
+        float qv[D], o[D], logit[kMaxPool + 1];
+        load_row<T, D>(qv, q);
+        float mx = -INFINITY;
+#pragma unroll
+        for (int s = 0; s <= kMaxPool; ++s) {
+          logit[s] = -INFINITY;
+          const bool real = s < cnt, hole = s == kMaxPool && holes > 0.f;
+          if (real || hole) {
+            float kvv[D];
+            load_row<T, D>(kvv, real ? Ks + (r0 + s) * LDX + h * D : Kb + h * D);
+            float acc = 0.f;
+#pragma unroll
+            for (int j = 0; j < D; ++j) acc = fmaf(qv[j], kvv[j], acc);
+            logit[s] = acc * scale;
+            mx = fmaxf(mx, logit[s]);
+          }
+        }
+#pragma unroll
+        for (int j = 0; j < D; ++j) o[j] = 0.f;
+        float sum = 0.f;
+#pragma unroll
+        for (int s = 0; s <= kMaxPool; ++s) {
+          const bool real = s < cnt, hole = s == kMaxPool && holes > 0.f;
+          if (real || hole) {
+            const float e = __expf(logit[s] - mx) * (hole ? holes : 1.f);
+            sum += e;
+            float kvv[D];
+            load_row<T, D>(kvv, real ? Vs + (r0 + s) * LDX + h * D : Vb + h * D);
+#pragma unroll
+            for (int j = 0; j < D; ++j) o[j] = fmaf(e, kvv[j], o[j]);
+          }
+        }
+        const float inv = 1.0f / sum;
+#pragma unroll
+        for (int j = 0; j < D; ++j) q[j] = (T)(o[j] * inv);
+      }
+      lds_barrier();
+    }
   }
 }
 
@@ -408,8 +454,10 @@ int launch_pool_attention(const dsvt_pool_cfg& c, const PoolPlan& pl, const int3
   d.b_q = c.b_q; d.b_o = c.b_o; d.ln_g = c.ln_g; d.ln_b = c.ln_b; d.ln_eps = c.ln_eps;
   d.P = pl.g.P; d.mask_empty = c.mask_empty;
   dsvt_prof_scope ps(DSVT_K_POOL_ATTN, st);
-  kern<<<(unsigned)dsvt_ceil_div(n_voxels, kRegs), kWaves * 64, lds, st>>>(d, pool_inds, n_out, reinterpret_cast<const T*>(x),
-                                                                        reinterpret_cast<T*>(out));
+  // one workgroup per compute unit (the LDS tile fills it), each walking over every grid-th group of regions
+  const int64_t groups = dsvt_ceil_div(n_voxels, kRegs);
+  kern<<<(unsigned)(groups < kPoolGrid ? groups : kPoolGrid), kWaves * 64, lds, st>>>(d, pool_inds, n_out, reinterpret_cast<const T*>(x),
+                                                                                    reinterpret_cast<T*>(out));
   return DSVT_OK;
 }
 
