@@ -57,8 +57,16 @@ def layer_traffic(workload):
     return None, "not measured for this workload"
 
 
+SETTLE_S = 0.2       # untimed steps before the warm-up: the GPU's clocks take some 100 ms of load to settle after the set-up's idle gaps
+
+
 def timed(run, steps, warmup):
     import torch
+    t_end = time.perf_counter() + SETTLE_S
+    while time.perf_counter() < t_end:
+        for _ in range(10):
+            run()
+        torch.cuda.synchronize()
     for _ in range(warmup):
         run()
     torch.cuda.synchronize()
@@ -587,6 +595,8 @@ def main():
     ap.add_argument("--frames-in-flight", type=int, choices=[1, 2], default=1,
                     help="2: also time a loop that keeps two frames in flight on two streams (an extra field of the JSON "
                          "line; `value` and `ms_per_step` are always the single-stream figures)")
+    ap.add_argument("--settle-ms", type=float, default=200.0,
+                    help="untimed steps for this long before the warm-up steps of every timed loop (clock settling; 0 = none)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one plain 256 MiB device copy (a kernel of known traffic, to scale rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE readings)")
@@ -598,6 +608,8 @@ def main():
 
     import torch
     torch.cuda.set_device(0)
+    global SETTLE_S
+    SETTLE_S = args.settle_ms * 1e-3
     if args.workload in STACKS:
         body, dt = stack_workload(args, args.workload)
     elif args.workload == "dsvtv":
@@ -610,7 +622,8 @@ def main():
         body, dt = bev_workload(args)
     line = {"metric": body.pop("metric"), "value": body.pop("value"), "unit": body.pop("unit"), "n_gpus": 1,
             "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(dt / args.steps * 1e3, 4),
-            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": body.pop("dtype"), "data": "synthetic"}
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": body.pop("dtype"), "data": "synthetic",
+            "settle_ms": args.settle_ms}
     line.update(body)
     print(json.dumps(line))
 
