@@ -274,15 +274,41 @@ def stack_workload(args, name):
     launches = 6 * len(kinds) + 2 * cfg["blocks"]           # (an upper bound: small frames take 3 partition launches)
     per_launch_us, per_step_ms = per_kernel(step, launches, min(args.steps, 50))
 
+    # The layer kernel's launch duration in the configuration the frame is timed in: the frame's layer launches alone
+    # (maps as the partitions left them), replayed from a graph, an event pair around every replay, / launches.  (The
+    # event pairs around eager launches above also span the gap to the next eager launch, 2-3 us that a replayed
+    # frame does not have; that figure is kept beside it.)
+    def layers_only():
+        src = x0
+        for b, pair in enumerate(layers):
+            dsvt.dsvt_block(pair, maps[plan[b]], cd, src, x_out=buf, ws=ws)
+            src = buf
+
+    layer_us_eager = per_launch_us["layer"]
+    layer_us = layer_us_eager
+    if use_graph:
+        run_layers = capture(layers_only, check)
+        timed(run_layers, 0, args.warmup)
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(min(args.steps, 100))]
+        for a, b in ev:
+            a.record()
+            run_layers()
+            b.record()
+        torch.cuda.synchronize()
+        layer_us = 1e3 * float(np.mean([a.elapsed_time(b) for a, b in ev])) / (2 * cfg["blocks"])
+
     # Roofline of the dominant kernel, the fused layer.  Algorithmic flops per voxel per layer
     # (duplicate-row and tile-padding work not counted): 16 C^2 + 4 tau C rho.
     rho = np.mean([n_sets[k] for k in plan]) * tau / N
     flops = N * (16 * C * C + 4 * tau * C * rho)
-    achieved = flops / (per_launch_us["layer"] * 1e-6) / 1e12
+    achieved = flops / (layer_us * 1e-6) / 1e12
     traffic, traffic_from = layer_traffic(name)
     roofline = {"bound": "mfma", "kernel": "layer", "achieved": round(achieved, 2), "peak": 2500.0, "unit": "TFLOP/s",
                 "frac": round(achieved / 2500.0, 5), "traffic": traffic, "traffic_from": traffic_from,
-                "avg_launch_us": round(per_launch_us["layer"], 2), "flops_per_launch": flops}
+                "avg_launch_us": round(layer_us, 2), "avg_launch_us_eager": round(layer_us_eager, 2),
+                "timing": (f"hipEvent pair around a graph replay of the frame's {2 * cfg['blocks']} layer launches / {2 * cfg['blocks']}"
+                           if use_graph else "hipEvent pairs around eager launches"),
+                "flops_per_launch": flops}
 
     # The partition chain against the HBM roofline: algorithmic bytes per voxel and map = 16 B of coordinates read,
     # 4 rho B of set_inds, 4 B of voxel_slot and 8 B of descriptor row written; latency-bound at these sizes.
