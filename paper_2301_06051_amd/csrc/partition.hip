@@ -388,6 +388,201 @@ __device__ __forceinline__ void desc_set(int32_t* d, int32_t ls, int32_t r0, int
 // What k_emit needs to know about a set with a tile: descriptor slot, place among the tile's sets, first row.
 __device__ __forceinline__ int32_t set_loc_code(int32_t pos, int32_t ls, int32_t r0) { return (pos << 12) | (ls << 7) | r0; }
 
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int32_t dpp_or(int32_t identity, int32_t v) {       // v of the lane CTRL names, identity where there is none
+  return __builtin_amdgcn_update_dpp(identity, v, CTRL, ROW_MASK, 0xF, false);
+}
+// Inclusive scans over a wavefront by data-parallel-primitive moves: shifts by 1, 2, 4, 8 inside rows of
+// 16 lanes, then lane 15 of rows 0 and 2 into rows 1 and 3, then lane 31 into rows 2 and 3.
+__device__ __forceinline__ int32_t wave_scan_add(int32_t v) {
+  v += dpp_or<0x111, 0xF>(0, v);
+  v += dpp_or<0x112, 0xF>(0, v);
+  v += dpp_or<0x114, 0xF>(0, v);
+  v += dpp_or<0x118, 0xF>(0, v);
+  v += dpp_or<0x142, 0xA>(0, v);
+  v += dpp_or<0x143, 0xC>(0, v);
+  return v;
+}
+__device__ __forceinline__ int32_t wave_scan_max(int32_t v, int32_t lowest) {
+  int32_t t;
+  t = dpp_or<0x111, 0xF>(lowest, v); v = t > v ? t : v;
+  t = dpp_or<0x112, 0xF>(lowest, v); v = t > v ? t : v;
+  t = dpp_or<0x114, 0xF>(lowest, v); v = t > v ? t : v;
+  t = dpp_or<0x118, 0xF>(lowest, v); v = t > v ? t : v;
+  t = dpp_or<0x142, 0xA>(lowest, v); v = t > v ? t : v;
+  t = dpp_or<0x143, 0xC>(lowest, v); v = t > v ? t : v;
+  return v;
+}
+
+
+// The work list of a frame whose sets fit the LDS tables (n_sets <= fill_sets, below 65,535): the same result as
+// build_tiles below, with the rows before every set, the tile starts and the tiles' launch slots kept in LDS from the
+// first pass to the last, so that the passes are separated by workgroup barriers only -- no pass reads memory that
+// an earlier pass wrote.  P [fill_sets + 1] | first set of every tile, 16 bit [fill_sets + 1] | launch slot of every
+// tile, 16 bit [fill_sets + 1] | tile-start marks [fill_sets + 1]; the two 16-bit tables are the fill's scratch first.
+__device__ __forceinline__ void build_tiles_lds(const int32_t* set_w, const int32_t* win_count, const int32_t* win_soff,
+                                                int32_t n_sets, int32_t tau, int32_t n_windows, int32_t rows_per_cut,
+                                                TileOut out, int32_t* set_loc, int32_t fill_sets, int32_t* status) {
+  extern __shared__ uint32_t fill_lds[];
+  __shared__ int32_t wave_tot[16];
+  __shared__ int32_t carry_s, over_s;
+  __shared__ int32_t hist[32], running[32], wave_cnt[16][32];
+  const int32_t tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  int32_t* P = reinterpret_cast<int32_t*>(fill_lds);
+  uint16_t* t_first = reinterpret_cast<uint16_t*>(P + fill_sets + 1);
+  uint16_t* t_pos = t_first + fill_sets + 1;
+  uint8_t* mark = reinterpret_cast<uint8_t*>(t_pos + fill_sets + 1);
+  if (tid == 0) { carry_s = 0; over_s = -1; }
+  lds_barrier();
+  // pass 1: padded rows per set, their running sum (four consecutive sets per thread and trip: the two dependent
+  // loads of a set -- its window, then the window's count and first set -- are in flight for four sets at once)
+  constexpr int32_t kPer = 4;
+  for (int32_t base = 0; base < n_sets; base += 1024 * kPer) {
+    const int32_t s0 = base + tid * kPer;
+    int32_t w[kPer], cnt[kPer], soff[kPer], rows[kPer], pre[kPer];
+#pragma unroll
+    for (int32_t j = 0; j < kPer; ++j) {
+      const int32_t wj = s0 + j < n_sets ? set_w[s0 + j] : 0;
+      w[j] = wj < 0 ? 0 : (wj >= n_windows ? n_windows - 1 : wj);
+    }
+#pragma unroll
+    for (int32_t j = 0; j < kPer; ++j) { cnt[j] = win_count[w[j]]; soff[j] = win_soff[w[j]]; }
+    int32_t mine = 0;
+#pragma unroll
+    for (int32_t j = 0; j < kPer; ++j) {
+      const int64_t N = cnt[j] > 0 ? cnt[j] : 1, S = (N + tau - 1) / tau;
+      rows[j] = s0 + j < n_sets ? set_rows(set_distinct(N, S, s0 + j - soff[j], tau)) : 0;
+      pre[j] = mine;
+      mine += rows[j];
+    }
+    const int32_t incl = wave_scan_add(mine);
+    if (lane == 63) wave_tot[wv] = incl;
+    lds_barrier();
+    int32_t before = carry_s;
+    for (int32_t k = 0; k < wv; ++k) before += wave_tot[k];
+#pragma unroll
+    for (int32_t j = 0; j < kPer; ++j)
+      if (s0 + j < n_sets) P[s0 + j] = before + incl - mine + pre[j];
+    if (s0 <= n_sets - 1 && n_sets - 1 < s0 + kPer) P[n_sets] = before + incl;
+    lds_barrier();
+    if (tid == 1023) carry_s = before + incl;
+    lds_barrier();
+  }
+  // tile starts: filled tiles (see fill_tile_starts) for frames of many rounds over the compute units, else a set
+  // starts a tile when the running row count crosses a multiple of rows_per_cut between its predecessor's start and
+  // its own (a tile then holds at most rows_per_cut - 4 + pad4(tau) <= 96 rows)
+  rows_per_cut = tile_cut(P[n_sets], rows_per_cut);
+  if (!fill_tiles(P, t_first, t_pos, mark, n_sets, rows_per_cut)) {
+    lds_barrier();
+    for (int32_t s = tid; s <= n_sets; s += 1024) mark[s] = s < n_sets && (s == 0 || P[s - 1] / rows_per_cut != P[s] / rows_per_cut);
+  }
+  if (tid == 0) carry_s = 0;
+  lds_barrier();
+  // pass 2: the tiles are numbered by counting their starts (a scan), so none is empty
+  const int32_t tile_lim = out.max_tiles < fill_sets ? out.max_tiles : fill_sets;
+  for (int32_t base = 0; base < n_sets; base += 1024 * kPer) {
+    const int32_t s0 = base + tid * kPer;
+    int32_t pre[kPer], mine = 0;
+#pragma unroll
+    for (int32_t j = 0; j < kPer; ++j) {
+      mine += (s0 + j < n_sets && mark[s0 + j]) ? 1 : 0;
+      pre[j] = mine;
+    }
+    const int32_t incl = wave_scan_add(mine);
+    if (lane == 63) wave_tot[wv] = incl;
+    lds_barrier();
+    int32_t before = carry_s;
+    for (int32_t k = 0; k < wv; ++k) before += wave_tot[k];
+#pragma unroll
+    for (int32_t j = 0; j < kPer; ++j) {
+      const int32_t s = s0 + j;
+      if (s < n_sets && mark[s]) {
+        const int32_t tile = before + incl - mine + pre[j] - 1;
+        if (tile < tile_lim) { t_first[tile] = (uint16_t)s; out.tile_first[tile] = s; }
+        else if (tile == tile_lim) over_s = s;               // first set that no tile is left for
+      }
+    }
+    lds_barrier();
+    if (tid == 1023) carry_s = before + incl;
+    lds_barrier();
+  }
+  const bool tiles_short = carry_s > tile_lim;               // the caller's list is shorter than the frame needs
+  const int32_t nt = tiles_short ? tile_lim : carry_s;
+  const int32_t n_eff = tiles_short ? over_s : n_sets;
+  if (tid == 0) {
+    if (tiles_short) atomicOr(status, DSVT_ST_TILE_OVERFLOW);   // the sets past the last tile get none
+    *out.n_tiles = nt;
+    out.tile_first[nt] = n_eff;
+    t_first[nt] = (uint16_t)n_eff;
+  }
+  if (tid < 32) hist[tid] = 0;
+  lds_barrier();
+  // pass 3: launch order = tiles with more rows first (a stable counting sort on rows / 4), so that the short tiles
+  // fill the tail of the launch
+  for (int32_t t = tid; t < nt; t += 1024) {
+    int32_t b = 24 - (P[t_first[t + 1]] - P[t_first[t]]) / 4;
+    b = b < 0 ? 0 : (b > 31 ? 31 : b);
+    atomicAdd(&hist[b], 1);
+  }
+  lds_barrier();
+  if (wv == 0) {
+    const int32_t h = lane < 32 ? hist[lane] : 0, incl = wave_scan_add(h);
+    if (lane < 32) running[lane] = incl - h;
+  }
+  lds_barrier();
+  for (int32_t base = 0; base < nt; base += 1024) {
+    const int32_t t = base + tid;
+    int32_t b = -1, rows = 0;
+    if (t < nt) {
+      rows = P[t_first[t + 1]] - P[t_first[t]];
+      b = 24 - rows / 4;
+      b = b < 0 ? 0 : (b > 31 ? 31 : b);
+    }
+    for (int32_t k = lane; k < 32; k += 64) wave_cnt[wv][k] = 0;
+    // lanes of this wavefront with the same bucket: those that agree with this lane in each of its 5 bits
+    unsigned long long same = __ballot(b >= 0);
+#pragma unroll
+    for (int32_t bit = 0; bit < 5; ++bit) {
+      const bool one = (b >> bit) & 1;
+      const unsigned long long ones = __ballot(one);
+      same &= one ? ones : ~ones;
+    }
+    const unsigned long long below = same & ((1ull << lane) - 1ull);
+    const int32_t rank = __popcll(below);                     // among this wavefront's lanes of the same bucket
+    if (b >= 0 && below == 0ull) wave_cnt[wv][b] = __popcll(same);
+    lds_barrier();
+    if (tid < 512) {                                          // a row of 16 lanes per bucket, a lane per wavefront
+      const int32_t bb = tid >> 4, k = tid & 15;
+      const int32_t cnt = wave_cnt[k][bb];
+      int32_t incl = cnt;
+      incl += dpp_or<0x111, 0xF>(0, incl);
+      incl += dpp_or<0x112, 0xF>(0, incl);
+      incl += dpp_or<0x114, 0xF>(0, incl);
+      incl += dpp_or<0x118, 0xF>(0, incl);
+      const int32_t first = running[bb];
+      wave_cnt[k][bb] = first + incl - cnt;
+      if (k == 15) running[bb] = first + incl;                // (read by this row only, all of it before this write)
+    }
+    lds_barrier();
+    if (b >= 0) {
+      const int32_t pos = wave_cnt[wv][b] + rank;
+      out.tile_order[pos] = t;
+      t_pos[t] = (uint16_t)pos;
+      desc_header(out, pos, rows, (int32_t)t_first[t + 1] - (int32_t)t_first[t]);
+    }
+    lds_barrier();
+  }
+  // pass 4: per set, its descriptor slot, its place among the tile's sets and its first row (a thread per tile)
+  for (int32_t t = tid; t < nt; t += 1024) {
+    const int32_t s_begin = t_first[t], s_end = t_first[t + 1], pos = t_pos[t], p0 = P[s_begin];
+    for (int32_t s = s_begin; s < s_end; ++s) {
+      const int32_t ls = s - s_begin, r0 = P[s] - p0;
+      set_loc[s] = (ls < kDescSets && r0 <= kTileRows - 4) ? set_loc_code(pos, ls, r0) : -1;
+    }
+  }
+  for (int32_t s = n_eff + tid; s < n_sets; s += 1024) set_loc[s] = -1;
+}
+
 // One workgroup: cut the set sequence into tiles for the layer kernels, order the tiles for launch
 // and write the descriptor headers.  With P(s) the running sum of padded rows before set s, set s
 // starts a tile when P crosses a multiple of rows_per_cut; a tile then holds at most
@@ -405,6 +600,10 @@ __device__ __forceinline__ void build_tiles(const int32_t* set_w, const int32_t*
   n_sets = n_sets < set_cap ? n_sets : set_cap;
   if (n_sets <= 0) {
     if (tid == 0) { *out.n_tiles = 0; out.tile_first[0] = 0; }
+    return;
+  }
+  if (fill_sets > 0 && n_sets <= fill_sets && n_sets < 65535) {
+    build_tiles_lds(set_w, win_count, win_soff, n_sets, tau, n_windows, rows_per_cut, out, set_loc, fill_sets, status);
     return;
   }
   if (tid == 0) carry_s = 0;
@@ -672,32 +871,6 @@ __global__ void __launch_bounds__(1024) k_tiles(Jobs jobs, GenJobs gen) {
 // Scan over the 1024 threads of a workgroup, continued from one call to the next through `carry`:
 // inclusive sums of a and b, and in xm the maximum of m over the threads before this one (and over
 // earlier calls).  Every thread of the workgroup calls it; two barriers inside.
-template <int CTRL, int ROW_MASK>
-__device__ __forceinline__ int32_t dpp_or(int32_t identity, int32_t v) {       // v of the lane CTRL names, identity where there is none
-  return __builtin_amdgcn_update_dpp(identity, v, CTRL, ROW_MASK, 0xF, false);
-}
-// Inclusive scans over a wavefront by data-parallel-primitive moves: shifts by 1, 2, 4, 8 inside rows of
-// 16 lanes, then lane 15 of rows 0 and 2 into rows 1 and 3, then lane 31 into rows 2 and 3.
-__device__ __forceinline__ int32_t wave_scan_add(int32_t v) {
-  v += dpp_or<0x111, 0xF>(0, v);
-  v += dpp_or<0x112, 0xF>(0, v);
-  v += dpp_or<0x114, 0xF>(0, v);
-  v += dpp_or<0x118, 0xF>(0, v);
-  v += dpp_or<0x142, 0xA>(0, v);
-  v += dpp_or<0x143, 0xC>(0, v);
-  return v;
-}
-__device__ __forceinline__ int32_t wave_scan_max(int32_t v, int32_t lowest) {
-  int32_t t;
-  t = dpp_or<0x111, 0xF>(lowest, v); v = t > v ? t : v;
-  t = dpp_or<0x112, 0xF>(lowest, v); v = t > v ? t : v;
-  t = dpp_or<0x114, 0xF>(lowest, v); v = t > v ? t : v;
-  t = dpp_or<0x118, 0xF>(lowest, v); v = t > v ? t : v;
-  t = dpp_or<0x142, 0xA>(lowest, v); v = t > v ? t : v;
-  t = dpp_or<0x143, 0xC>(lowest, v); v = t > v ? t : v;
-  return v;
-}
-
 struct Scan3 { int32_t a, b, m, xm; };
 __device__ __forceinline__ Scan3 block_scan3(Scan3 v, int32_t (*wave_tot)[16], int32_t* carry) {
   const int32_t tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
