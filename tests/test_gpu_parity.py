@@ -140,8 +140,22 @@ def test_large_frames_get_filled_tiles(cid, n):
     rows = int(((first.sum(1) + 3) // 4 * 4).sum())
     nt = int(pair[0].n_tiles.item())
     _say(f"  rows {rows}, tiles {nt}, rows per tile {rows / nt:.1f}")
-    if nt > 8 * 256:
-        assert rows / nt > 75                              # (a greedy fill of the skewed batch's sets gives 76.2)
+    if nt > 4 * 256:
+        # frames of more than four rounds: tiles of up to 96 rows, filled greedily inside pieces of 4,096 rows (the
+        # first set that begins in a piece starts a tile, and so does every 16,384th set of a frame with more sets
+        # than that); the count follows from the sets' padded rows alone
+        per_set = (first.sum(1) + 3) // 4 * 4
+        before = np.concatenate([[0], np.cumsum(per_set)])
+        want, s = 0, 0
+        while s < len(per_set):
+            want += 1
+            t = s + 1
+            while (t < len(per_set) and before[t + 1] - before[s] <= 96 and before[t] >> 12 == before[s] >> 12
+                   and not (len(per_set) > 16384 and t % 16384 == 0)):
+                t += 1
+            s = t
+        assert nt == want
+        assert rows / nt > 75                              # (an unbroken greedy fill of the skewed batch's sets gives 76.2)
     else:
         assert rows / nt > 66 and 0.88 < (nt / 256) / np.ceil(nt / 256) <= 1.0
 
