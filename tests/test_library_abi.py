@@ -65,3 +65,32 @@ def test_bench_refuses_more_than_one_gpu():
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
     assert r.returncode == 2 and "single-GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_bench_reports_layer_traffic_only_for_the_sources_it_was_measured_with(tmp_path, monkeypatch):
+    """bench.py takes the layer kernel's HBM bytes per launch from profiles/k_layer_hbm_traffic.txt, by workload, and
+    only when the file's hash of layer.hip + mma.h is that of the sources in the tree."""
+    import sys
+    sys.path.insert(0, ROOT)
+    import bench
+    f = tmp_path / "traffic.txt"
+    f.write_text("# comment\n"
+                 f"workload=frame commit=abc1234 sources={bench.layer_source_hash()} fetch_kib=100 write_kib=28\n"
+                 "workload=voxel commit=abc1234 sources=0000000000000000 fetch_kib=1 write_kib=1\n")
+    monkeypatch.setattr(bench, "TRAFFIC_FILE", str(f))
+    nbytes, where = bench.layer_traffic("frame")
+    assert nbytes == 128 * 1024 and "abc1234" in where
+    assert bench.layer_traffic("voxel")[0] is None and "other kernel sources" in bench.layer_traffic("voxel")[1]
+    assert bench.layer_traffic("skewed") == (None, "not measured for this workload")
+    monkeypatch.setattr(bench, "TRAFFIC_FILE", str(tmp_path / "missing.txt"))
+    assert bench.layer_traffic("frame") == (None, "no traffic file")
+
+
+def test_committed_traffic_file_matches_the_committed_kernel_sources():
+    """The tracked traffic figures belong to the tracked layer.hip and mma.h (a change to either needs a new measurement)."""
+    import sys
+    sys.path.insert(0, ROOT)
+    import bench
+    for w in ("frame", "skewed", "voxel"):
+        nbytes, where = bench.layer_traffic(w)
+        assert nbytes is not None and nbytes > 0, (w, where)
