@@ -420,6 +420,7 @@ __device__ __forceinline__ int32_t wave_scan_max(int32_t v, int32_t lowest) {
 // first pass to the last, so that the passes are separated by workgroup barriers only -- no pass reads memory that
 // an earlier pass wrote.  P [fill_sets + 1] | first set of every tile, 16 bit [fill_sets + 1] | launch slot of every
 // tile, 16 bit [fill_sets + 1] | tile-start marks [fill_sets + 1]; the two 16-bit tables are the fill's scratch first.
+// set_w == nullptr: P [0 .. n_sets] is in place already (k_scan_windows wrote it while it scanned the windows).
 __device__ __forceinline__ void build_tiles_lds(const int32_t* set_w, const int32_t* win_count, const int32_t* win_soff,
                                                 int32_t n_sets, int32_t tau, int32_t n_windows, int32_t rows_per_cut,
                                                 TileOut out, int32_t* set_loc, int32_t fill_sets, int32_t* status) {
@@ -437,7 +438,7 @@ __device__ __forceinline__ void build_tiles_lds(const int32_t* set_w, const int3
   // pass 1: padded rows per set, their running sum (four consecutive sets per thread and trip: the two dependent
   // loads of a set -- its window, then the window's count and first set -- are in flight for four sets at once)
   constexpr int32_t kPer = 4;
-  for (int32_t base = 0; base < n_sets; base += 1024 * kPer) {
+  for (int32_t base = 0; set_w != nullptr && base < n_sets; base += 1024 * kPer) {
     const int32_t s0 = base + tid * kPer;
     int32_t w[kPer], cnt[kPer], soff[kPer], rows[kPer], pre[kPer];
 #pragma unroll
@@ -581,6 +582,63 @@ __device__ __forceinline__ void build_tiles_lds(const int32_t* set_w, const int3
     }
   }
   for (int32_t s = n_eff + tid; s < n_sets; s += 1024) set_loc[s] = -1;
+}
+
+// k_scan_windows for a job whose sets fit the LDS tables of the work-list builder: the scans of voxels- and
+// sets-per-window as in scan_windows(), and with them the rows before every set (a thread per window walks its
+// sets), straight into the builder's table -- the builder then starts from there, in the same launch, instead of
+// finding every set's window and size again in a launch of its own.
+__device__ __forceinline__ void scan_windows_and_tiles(const int32_t* __restrict__ win_count, int32_t* __restrict__ win_soff,
+                                                       int32_t n_windows, int32_t tau, int32_t max_sets, int32_t set_cap,
+                                                       int32_t* __restrict__ n_sets_out, int32_t* __restrict__ status,
+                                                       int32_t rows_per_cut, TileOut out, int32_t* set_loc, int32_t fill_sets) {
+  extern __shared__ uint32_t fill_lds[];
+  __shared__ int32_t wave_tot[2][16];
+  __shared__ int32_t carry_sr[2];
+  int32_t* P = reinterpret_cast<int32_t*>(fill_lds);            // [fill_sets + 1], as build_tiles_lds lays it out
+  const int32_t tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  if (tid == 0) { carry_sr[0] = 0; carry_sr[1] = 0; }
+  lds_barrier();
+  for (int32_t base = 0; base < n_windows; base += 1024) {
+    const int32_t w = base + tid;
+    const int32_t nvox = w < n_windows ? win_count[w] : 0;
+    const int32_t S = (nvox + tau - 1) / tau;
+    SetWalk walk(nvox, S, tau);
+    int32_t R = 0;
+    for (int32_t j = 0; j < S; ++j) R += set_rows(walk.next());
+    const int32_t s_incl = wave_scan_add(S), r_incl = wave_scan_add(R);
+    if (lane == 63) { wave_tot[0][wv] = s_incl; wave_tot[1][wv] = r_incl; }
+    lds_barrier();
+    int32_t s_before = carry_sr[0], r_before = carry_sr[1];
+    for (int32_t k = 0; k < wv; ++k) { s_before += wave_tot[0][k]; r_before += wave_tot[1][k]; }
+    if (w < n_windows) {
+      const int32_t soff = s_before + s_incl - S;
+      win_soff[w] = soff;
+      int32_t p = r_before + r_incl - R;
+      walk.restart();
+      for (int32_t j = 0; j < S; ++j) {
+        if (soff + j <= fill_sets) P[soff + j] = p;
+        p += set_rows(walk.next());
+      }
+    }
+    lds_barrier();
+    if (tid == 1023) { carry_sr[0] = s_before + s_incl; carry_sr[1] = r_before + r_incl; }
+    lds_barrier();
+  }
+  const int32_t n_all = carry_sr[0];
+  if (tid == 0) {
+    *n_sets_out = n_all;
+    if (n_all > max_sets) atomicOr(status, DSVT_ST_SET_OVERFLOW);
+  }
+  int32_t n_sets = n_all < set_cap ? n_all : set_cap;
+  n_sets = n_sets < fill_sets ? n_sets : fill_sets;
+  if (n_sets <= 0) {
+    if (tid == 0) { *out.n_tiles = 0; out.tile_first[0] = 0; }
+    return;
+  }
+  if (tid == 0 && n_sets == n_all) P[n_sets] = carry_sr[1];     // (of a clipped list, P[n_sets] is the row count before the first set left out)
+  lds_barrier();
+  build_tiles_lds(nullptr, nullptr, nullptr, n_sets, tau, n_windows, rows_per_cut, out, set_loc, fill_sets, status);
 }
 
 // One workgroup: cut the set sequence into tiles for the layer kernels, order the tiles for launch
@@ -830,6 +888,7 @@ __device__ __forceinline__ void build_tiles(const int32_t* set_w, const int32_t*
 struct GenJob {
   int32_t *ws_setwin, *tile_rows, *tile_pos, *set_p;
   int32_t set_bound, want_tiles, fill_sets;
+  int32_t merged;                            // k_scan_windows also builds the work list (sets fit the LDS tables)
 };
 struct GenJobs { GenJob j[kMaxJobs]; };
 
@@ -856,14 +915,18 @@ __global__ void k_window_count(Jobs jobs) {
 __global__ void __launch_bounds__(1024) k_scan_windows(Jobs jobs, GenJobs gen) {
   const Job& J = jobs.j[blockIdx.x];
   const GenJob& G = gen.j[blockIdx.x];
-  scan_windows(J.win_count, J.win_soff, J.g.n_windows, J.g.tau, J.max_sets, J.n_sets, J.status, G.ws_setwin, G.set_bound);
+  if (G.merged)
+    scan_windows_and_tiles(J.win_count, J.win_soff, J.g.n_windows, J.g.tau, J.max_sets, J.set_cap, J.n_sets, J.status,
+                           J.rows_per_cut, J.out, J.set_loc, G.fill_sets);
+  else
+    scan_windows(J.win_count, J.win_soff, J.g.n_windows, J.g.tau, J.max_sets, J.n_sets, J.status, G.ws_setwin, G.set_bound);
 }
 
 // One workgroup per job that wants a work list.
 __global__ void __launch_bounds__(1024) k_tiles(Jobs jobs, GenJobs gen) {
   const Job& J = jobs.j[blockIdx.x];
   const GenJob& G = gen.j[blockIdx.x];
-  if (!G.want_tiles) return;
+  if (!G.want_tiles || G.merged) return;
   build_tiles(G.ws_setwin, J.win_count, J.win_soff, J.n_sets, J.set_cap, J.g.tau, J.g.n_windows, J.rows_per_cut, J.out,
               G.tile_rows, G.tile_pos, G.set_p, J.set_loc, G.fill_sets, J.status);
 }
@@ -1459,7 +1522,7 @@ int run_partitions(const PartRequest* reqs, int32_t n, const int32_t* coords, in
   // the general one (three launches) for the others, then emit.
   Jobs jobs = {}, front_jobs = {}, gen_jobs = {};
   GenJobs gen = {};
-  int32_t n_front = 0, n_gen = 0, max_tiles = 0, any_tiles = 0;
+  int32_t n_front = 0, n_gen = 0, max_tiles = 0, any_tiles = 0, any_merged = 0;
   size_t front_lds = 0, fill_lds = 0;
   int64_t count_threads = 0;
   for (int32_t q = 0; q < n; ++q) {
@@ -1486,7 +1549,10 @@ int run_partitions(const PartRequest* reqs, int32_t n, const int32_t* coords, in
       const size_t need = ((size_t)G.fill_sets + 1) * 9 + 16;
       static_assert(((size_t)kFillPiece + 1) * 9 + 16 <= kFrontLds, "tables of one piece fit the LDS k_tiles may ask for");
       if (G.fill_sets) fill_lds = need > fill_lds ? need : fill_lds;
-      any_tiles |= G.want_tiles;
+      // every set has a place in the tables: the scan of the windows builds the work list too (no k_tiles launch)
+      G.merged = (G.want_tiles && p.set_bound <= G.fill_sets && p.set_bound < 65535 && p.g.tau > 1) ? 1 : 0;
+      any_merged |= G.merged;
+      any_tiles |= (G.want_tiles && !G.merged) ? 1 : 0;
       int32_t group = 1;
       while (group < 64 && group < p.g.words_per_win) group <<= 1;
       const int64_t threads = (int64_t)p.g.n_windows * group;
@@ -1505,6 +1571,10 @@ int run_partitions(const PartRequest* reqs, int32_t n, const int32_t* coords, in
     static std::atomic<uint64_t> tiles_allowed{0};
     if (int rc = dsvt_allow_lds((const void*)k_tiles, kFrontLds, tiles_allowed)) return rc;
   }
+  if (n_gen && any_merged) {
+    static std::atomic<uint64_t> scan_allowed{0};
+    if (int rc = dsvt_allow_lds((const void*)k_scan_windows, kFrontLds, scan_allowed)) return rc;
+  }
   DSVT_HIP_TRY(hipGetLastError());                            // (an error left by an earlier call is not this chain's)
   {
     dsvt_prof_scope ps(DSVT_K_PART_MARK, st);
@@ -1522,7 +1592,7 @@ int run_partitions(const PartRequest* reqs, int32_t n, const int32_t* coords, in
     }
     {
       dsvt_prof_scope ps(DSVT_K_PART_SCAN, st);
-      k_scan_windows<<<n_gen, 1024, 0, st>>>(gen_jobs, gen);
+      k_scan_windows<<<n_gen, 1024, any_merged ? fill_lds : 0, st>>>(gen_jobs, gen);
     }
     if (any_tiles) {
       dsvt_prof_scope ps(DSVT_K_PART_TILES, st);
