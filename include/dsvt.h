@@ -73,9 +73,9 @@ int dsvt_partition_bound(const dsvt_part_cfg* cfg, int32_t n_voxels, int32_t* ma
  *   tile_first [max_tiles+1]     tile t covers sets tile_first[t] .. tile_first[t+1]-1
  *   n_tiles    scalar            number of tiles (<= max_tiles)
  *   tile_order [max_tiles]       tiles in launch order (most rows first)
- *   tile_desc  [max_tiles][256]  per tile in launch order: [0] rows, [1] sets, [2+s] first row and
- *                                [26+s] distinct voxels of its s-th set, [64+r] voxel of row r (-1 =
- *                                padding), [160+r] (slots holding that voxel << 24) | position code
+ *   tile_desc  [max_tiles][256]  (8-byte aligned) per tile in launch order: [0] rows, [1] sets, [2+s] first row and
+ *                                [26+s] distinct voxels of its s-th set, [64+2r] voxel of row r (-1 =
+ *                                padding), [65+2r] (slots holding that voxel << 24) | position code
  *                                (x*(2W-1) + y)*(2H-1) + z.  The arrays need no clearing: every
  *                                entry of the first n_tiles descriptors that a kernel reads is
  *                                written by the call; the rest keeps what it held.

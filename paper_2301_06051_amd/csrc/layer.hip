@@ -299,11 +299,14 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
         for (int hh = 0; hh < ngr; ++hh)
           if (n < kMaxItems) items[n++] = ls | (qt << 8) | (hh << 12) | (kts << 16);
       if (lane == 63) items[kMaxItems] = incl < kMaxItems ? incl : kMaxItems;   // published by the barrier below
-    } else if (tid >= 64 && tid < 64 + kRowsMax) {
-      row_vox[tid - 64] = (word >= 0 && word < mp.n_voxels) ? word : -1;
-    } else if (tid >= 160 && tid < 160 + kRowsMax) {
-      row_lin[tid - 160] = word & 0xFFFFFF;
-      row_mult[tid - 160] = (float)((unsigned)word >> 24);
+    } else if (tid < 64 + 2 * kRowsMax) {           // words 64 + 2 r and 65 + 2 r: voxel and (slots << 24 | position code) of row r
+      const int r = (tid - 64) >> 1;
+      if ((tid & 1) == 0) {
+        row_vox[r] = (word >= 0 && word < mp.n_voxels) ? word : -1;
+      } else {
+        row_lin[r] = word & 0xFFFFFF;
+        row_mult[r] = (float)((unsigned)word >> 24);
+      }
     }
     lds_barrier();
     ns = __builtin_amdgcn_readfirstlane(set_nu[kMaxSets]);

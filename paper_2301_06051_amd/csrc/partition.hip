@@ -159,8 +159,9 @@ __device__ __forceinline__ void scan_windows(const int32_t* __restrict__ win_cou
 // Tile descriptor, one per workgroup tile of the layer kernels, in launch order (256 ints):
 //   [0] rows R (sets padded to multiples of 4)   [1] sets ns
 //   [2 + s] first row of set s                    [2 + 24 + s] distinct voxels of set s   (s < ns <= 24)
-//   [64 + r] voxel of row r, -1 for padding rows  [160 + r] (multiplicity << 24) | position code of row r
-constexpr int kDescInts = 256, kDescSets = 24, kDescR0 = 2, kDescNu = 2 + kDescSets, kDescVox = 64, kDescLin = 160;
+//   [64 + 2 r] voxel of row r, -1 for padding rows  [65 + 2 r] (multiplicity << 24) | position code of row r
+// (the two words of a row side by side: k_emit writes them with one 8-byte store)
+constexpr int kDescInts = 256, kDescSets = 24, kDescR0 = 2, kDescNu = 2 + kDescSets, kDescRow = 64;
 constexpr int kTileRows = 96;
 constexpr int32_t kComputeUnits = 256;            // MI355X
 
@@ -382,7 +383,7 @@ __device__ __forceinline__ void desc_set(int32_t* d, int32_t ls, int32_t r0, int
   const int32_t r1 = r0 + set_rows(nu) < kTileRows ? r0 + set_rows(nu) : kTileRows;
   d[kDescR0 + ls] = r0;
   d[kDescNu + ls] = nu;
-  for (int32_t r = r0 + nu; r < r1; ++r) { d[kDescVox + r] = -1; d[kDescLin + r] = -1; }
+  for (int32_t r = r0 + nu; r < r1; ++r) *reinterpret_cast<int2*>(d + kDescRow + 2 * r) = make_int2(-1, -1);
 }
 
 // What k_emit needs to know about a set with a tile: descriptor slot, place among the tile's sets, first row.
@@ -1268,7 +1269,7 @@ __global__ void k_emit(Jobs jobs, const int4* __restrict__ coords, int32_t n, in
     if (pos >= nt) return;
     int32_t* dd = tile_desc + (int64_t)pos * kDescInts;
     const int32_t rows = dd[0];
-    for (int32_t r = rows + part; r < kTileRows; r += 16) { dd[kDescVox + r] = -1; dd[kDescLin + r] = -1; }
+    for (int32_t r = rows + part; r < kTileRows; r += 16) *reinterpret_cast<int2*>(dd + kDescRow + 2 * r) = make_int2(-1, -1);
     return;
   }
   int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -1337,8 +1338,7 @@ __global__ void k_emit(Jobs jobs, const int4* __restrict__ coords, int32_t n, in
       if (slot >= 0 && slot < n_desc_slots && row < kTileRows) {
         const int32_t lin = (c.y * (2 * g.win[1] - 1) + c.z) * (2 * g.win[2] - 1) + c.w;
         int32_t* dd = tile_desc + (int64_t)slot * kDescInts;
-        dd[kDescVox + row] = i;
-        dd[kDescLin + row] = (int32_t)((uint32_t)lin | ((uint32_t)(t_hi - t_lo) << 24));
+        *reinterpret_cast<int2*>(dd + kDescRow + 2 * row) = make_int2(i, (int32_t)((uint32_t)lin | ((uint32_t)(t_hi - t_lo) << 24)));
       }
     }
   }
@@ -1454,6 +1454,7 @@ int prepare(const PartRequest& r, int32_t n_voxels, Prepared* out) {
     const dsvt_tile_list* t = r.tiles;
     if (!t->tile_first || !t->n_tiles || !t->tile_order || !t->tile_desc || t->max_tiles <= 0) return DSVT_EINVAL;
     if (r.n_axes == 2 && !r.tile_desc_2) return DSVT_EINVAL;
+    if (((uintptr_t)t->tile_desc | (uintptr_t)r.tile_desc_2) & 7u) return DSVT_EINVAL;   // a row's two words go out as one 8-byte store
     if (!p.desc_ok) return DSVT_EUNSUPPORTED;
     tout.tile_first = t->tile_first; tout.n_tiles = t->n_tiles; tout.tile_order = t->tile_order;
     tout.tile_desc[0] = t->tile_desc;

@@ -76,13 +76,14 @@ def assert_tiles_valid(gm, om, coords=None, win=None):
         for ls, s in enumerate(range(tf[t], tf[t + 1])):
             members = si[s][first[s]]
             assert desc[pos, 2 + ls] == r and desc[pos, 26 + ls] == len(members)
-            assert np.array_equal(desc[pos, 64 + r:64 + r + len(members)], members)
+            vox, code = desc[pos, 64:256:2], desc[pos, 65:256:2]        # the two words of a row sit side by side
+            assert np.array_equal(vox[r:r + len(members)], members)
             mult = np.diff(np.append(np.flatnonzero(first[s]), si.shape[1]))
-            assert np.array_equal((desc[pos, 160 + r:160 + r + len(members)].view(np.uint32) >> 24), mult)
+            assert np.array_equal((code[r:r + len(members)].view(np.uint32) >> 24), mult)
             pad = (len(members) + 3) // 4 * 4
-            assert np.all(desc[pos, 64 + r + len(members):64 + r + pad] == -1)
+            assert np.all(vox[r + len(members):r + pad] == -1)
             r += pad
-        assert np.all(desc[pos, 64 + r:160] == -1)
+        assert np.all(desc[pos, 64 + 2 * r:256:2] == -1)
 
 
 def assert_maps_equal(gm, om):
