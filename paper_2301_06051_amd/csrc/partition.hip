@@ -91,21 +91,37 @@ __device__ __forceinline__ uint32_t voxel_key(const PartGeom& g, int32_t axis, u
 
 // `group` lanes (a power of two <= 64) per window: pop-count the window's words, leave in
 // word_prefix[] the number of set bits in the window's earlier words, and the window total.
+// y_words != nullptr: the group also sets, in its LDS words y_words[0 .. words_per_win) (zero on entry), the bits of
+// the window's voxels in the other inner order (x and y exchanged), for a second call with lds_src = those words.
 __device__ __forceinline__ void window_count(int32_t tid, uint32_t* __restrict__ mark, uint32_t* __restrict__ bitmap,
                                              uint32_t* __restrict__ word_prefix, int32_t* __restrict__ win_count,
-                                             int32_t n_windows, int32_t words_per_win, int32_t group) {
+                                             int32_t n_windows, int32_t words_per_win, int32_t group,
+                                             const uint32_t* lds_src = nullptr, uint32_t* y_words = nullptr,
+                                             int32_t win_l = 1, int32_t win_w = 1, int32_t win_h = 1) {
   int32_t w = tid / group, lane = tid & (group - 1);
   if (w >= n_windows) return;               // whole groups leave together
   const int64_t base = (int64_t)w * words_per_win;
+  const float rcp_h = __frcp_rn((float)win_h), rcp_w = __frcp_rn((float)win_w);
   uint32_t running = 0;
   for (int32_t w0 = 0; w0 < words_per_win; w0 += group) {
     int32_t j = w0 + lane;
     uint32_t v = 0u;
     if (j < words_per_win) {                 // the word moves from the mark bitmap (left zero) to this call's copy
-      const uint32_t bits = mark[base + j];
-      mark[base + j] = 0u;
+      uint32_t bits;
+      if (lds_src != nullptr) bits = lds_src[j];
+      else { bits = mark[base + j]; mark[base + j] = 0u; }
       bitmap[base + j] = bits;
       v = (uint32_t)__popc(bits);
+      if (y_words != nullptr) {
+        // inner key (x W + y) H + z -> (y L + x) H + z; keys are below 2^16, where (k + 0.5) / d in float truncates to floor(k / d)
+        for (uint32_t rest = bits; rest; rest &= rest - 1u) {
+          const int32_t key = j * 32 + (__ffs((int)rest) - 1);
+          const int32_t t = (int32_t)(((float)key + 0.5f) * rcp_h), z = key - t * win_h;
+          const int32_t x = (int32_t)(((float)t + 0.5f) * rcp_w), y = t - x * win_w;
+          const int32_t yk = (y * win_l + x) * win_h + z;
+          atomicOr(&y_words[yk >> 5], 1u << (yk & 31));
+        }
+      }
     }
     uint32_t incl = v;
     for (int32_t d = 1; d < group; d <<= 1) {
@@ -325,6 +341,7 @@ struct Job {
   int32_t *win_count, *win_soff, *n_sets, *status, *set_win, *set_loc;
   int32_t n_words, max_sets, set_cap, rows_per_cut, tile_cap;
   int32_t fill_sets;                         // k_front: sets its LDS has tables for (filled tiles), 0 = none
+  int32_t derive_y;                          // general front end: k_mark sets the X-order bits only, k_window_count transposes them
 };
 constexpr int32_t kMaxJobs = 4;
 struct Jobs { Job j[kMaxJobs]; };
@@ -343,7 +360,8 @@ __global__ void k_mark(Jobs jobs, const int4* __restrict__ coords, int32_t n) {
     atomicOr(J.status, DSVT_ST_COORD_RANGE);
     return;
   }
-  for (int32_t k = 0; k < J.ax.n; ++k) {
+  const int32_t n_mark = J.derive_y ? 1 : J.ax.n;
+  for (int32_t k = 0; k < n_mark; ++k) {
     const uint32_t key = voxel_key(J.g, J.ax.axis0 + k, wkey, xi, yi, zi), bit = 1u << (key & 31u);
     const uint32_t old = atomicOr(&J.ax.a[k].mark[key >> 5], bit);
     if (old & bit) atomicOr(J.status, DSVT_ST_COORD_REPEAT);
@@ -906,6 +924,19 @@ __global__ void k_window_count(Jobs jobs) {
   if (!ws_ready(ax)) {
     const int32_t w = tid / group;
     if (w < n_windows && blockIdx.y == 0 && (tid & (group - 1)) == 0) J.win_count[w] = 0;
+    return;
+  }
+  if (J.derive_y) {
+    // only the X-order bits were marked: the group that moves a window's X words also transposes them, bit by bit,
+    // into LDS words of its own, and then treats those as the window's Y-order words (a group is part of one
+    // wavefront, whose LDS operations execute in order)
+    if (blockIdx.y != 0) return;
+    extern __shared__ uint32_t y_lds[];
+    uint32_t* mine = y_lds + (threadIdx.x / group) * words_per_win;
+    for (int32_t j = threadIdx.x & (group - 1); j < words_per_win; j += group) mine[j] = 0u;
+    window_count(tid, ax.a[0].mark, ax.a[0].bitmap, ax.a[0].prefix, J.win_count, n_windows, words_per_win, group,
+                 nullptr, mine, J.g.win[0], J.g.win[1], J.g.win[2]);
+    window_count(tid, nullptr, ax.a[1].bitmap, ax.a[1].prefix, J.win_count, n_windows, words_per_win, group, mine);
     return;
   }
   window_count(tid, ax.a[blockIdx.y].mark, ax.a[blockIdx.y].bitmap, ax.a[blockIdx.y].prefix, J.win_count, n_windows,
@@ -1501,6 +1532,10 @@ int prepare(const PartRequest& r, int32_t n_voxels, Prepared* out) {
     J.fill_sets = p.set_bound;
     out->front_lds += fill_lds;
   }
+  // Frames for the general front end, X-/Y-axis pair of the plain or the "Sparse" order (their bitmaps are keyed alike):
+  // the Y-order bits of a window are its X-order bits with x and y exchanged, so only the X-order bits are set by
+  // atomics and k_window_count derives the others window by window (half the atomics of k_mark).
+  J.derive_y = (!out->front_ok && r.n_axes == 2 && (r.axis0 & ~4) == 0 && p.g.vol <= (1u << 16)) ? 1 : 0;
   J.g = p.g;
   return DSVT_OK;
 }
@@ -1524,7 +1559,7 @@ int run_partitions(const PartRequest* reqs, int32_t n, const int32_t* coords, in
   Jobs jobs = {}, front_jobs = {}, gen_jobs = {};
   GenJobs gen = {};
   int32_t n_front = 0, n_gen = 0, max_tiles = 0, any_tiles = 0, any_merged = 0;
-  size_t front_lds = 0, fill_lds = 0;
+  size_t front_lds = 0, fill_lds = 0, count_lds = 0;
   int64_t count_threads = 0;
   for (int32_t q = 0; q < n; ++q) {
     const Prepared& P = prep[q];
@@ -1558,6 +1593,10 @@ int run_partitions(const PartRequest* reqs, int32_t n, const int32_t* coords, in
       while (group < 64 && group < p.g.words_per_win) group <<= 1;
       const int64_t threads = (int64_t)p.g.n_windows * group;
       count_threads = threads > count_threads ? threads : count_threads;
+      if (P.job.derive_y) {
+        const size_t need_y = (size_t)(tb / group) * p.g.words_per_win * 4;
+        count_lds = need_y > count_lds ? need_y : count_lds;
+      }
       gen_jobs.j[n_gen++] = P.job;
     }
   }
@@ -1589,7 +1628,7 @@ int run_partitions(const PartRequest* reqs, int32_t n, const int32_t* coords, in
   if (n_gen) {
     {
       dsvt_prof_scope ps(DSVT_K_PART_COUNT, st);
-      k_window_count<<<dim3((unsigned)dsvt_ceil_div(count_threads, tb), n_axes, n_gen), tb, 0, st>>>(gen_jobs);
+      k_window_count<<<dim3((unsigned)dsvt_ceil_div(count_threads, tb), n_axes, n_gen), tb, count_lds, st>>>(gen_jobs);
     }
     {
       dsvt_prof_scope ps(DSVT_K_PART_SCAN, st);
