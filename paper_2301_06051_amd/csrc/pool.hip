@@ -522,7 +522,7 @@ int run_attn_pool(const dsvt_pool_cfg* cfg, const PoolPlan& pl, const int32_t* c
     kp_clear<<<(unsigned)dsvt_ceil_div(n_clear, tb), tb, 0, st>>>(bitmap, pl.n_words, inds, n_inds);
     kp_mark<<<(unsigned)dsvt_ceil_div(n_voxels, tb), tb, 0, st>>>(pl.g, reinterpret_cast<const int4*>(coords), n_voxels,
                                                                   bitmap, status);
-    k_block_scan<true><<<1, 1024, 0, st>>>(bitmap, prefix, pl.n_words, nullptr, n_out);
+    k_block_scan<true><<<block_scan_grid(pl.n_words), 1024, 0, st>>>(bitmap, prefix, pl.n_words, nullptr, n_out);
     kp_emit<<<(unsigned)dsvt_ceil_div(n_voxels, tb), tb, 0, st>>>(pl.g, reinterpret_cast<const int4*>(coords), n_voxels,
                                                                   bitmap, prefix, inds, out_coords);
   }

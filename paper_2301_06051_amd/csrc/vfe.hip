@@ -315,9 +315,9 @@ extern "C" int dsvt_vfe(const dsvt_vfe_cfg* cfg, const float* points, const int3
     kv_clear<<<(unsigned)dsvt_ceil_div(n_clear, tb), tb, 0, st>>>(reinterpret_cast<uint4*>(cells), n16, count, n_count);
     kv_mark<<<pb, tb, 0, st>>>(pl.g, points, point_batch, n_points, cells, keys);
     kv_pack<<<(unsigned)dsvt_ceil_div(pl.n_words, tb), tb, 0, st>>>(reinterpret_cast<const uint4*>(cells), pl.n_words, bitmap);
-    k_block_scan<true><<<1, 1024, 0, st>>>(bitmap, prefix, pl.n_words, nullptr, n_voxels);
+    k_block_scan<true><<<block_scan_grid(pl.n_words), 1024, 0, st>>>(bitmap, prefix, pl.n_words, nullptr, n_voxels);
     kv_count<<<pb, tb, 0, st>>>(keys, n_points, bitmap, prefix, max_voxels, count, vox, pos, status);
-    k_block_scan<false, true><<<1, 1024, 0, st>>>(reinterpret_cast<const uint32_t*>(count), offs, max_voxels, n_voxels, n_rows);
+    k_block_scan<false, true><<<block_scan_grid(max_voxels), 1024, 0, st>>>(reinterpret_cast<const uint32_t*>(count), offs, max_voxels, n_voxels, n_rows);
     float4* sorted4 = reinterpret_cast<float4*>(sorted);
     switch ((cfg->f_in + 3) / 4) {
       case 1: kv_place<1><<<pb, tb, 0, st>>>(pl.g, points, point_batch, vox, pos, offs, n_points, sorted4, run_info, coords); break;
