@@ -91,6 +91,27 @@ def test_vfe_lidar_frame_feeds_the_partition(grid_z, n_points):
         assert_maps_equal(pair[axis], orc.partition(rc, grid, win, (6, 6, 0), tau, axis))
 
 
+@pytest.mark.parametrize("n_vox", [16384, 16385, 32768, 40000])
+def test_vfe_voxel_counts_at_the_scan_chunk_edges(n_vox):
+    """The two scans of the encoder work in chunks of 16,384 elements (a workgroup per chunk): voxel counts of exactly
+    one chunk, one more, exactly two, and a bitmap of exactly one chunk of words (1024 x 512 cells)."""
+    grid, lo, size = (1024, 512, 1), (0.0, 0.0, 0.0), (1.0, 1.0, 1.0)
+    rng = np.random.default_rng(27)
+    cells = rng.choice(grid[0] * grid[1], n_vox, replace=False)
+    reps = rng.integers(1, 4, n_vox)
+    cell_of = np.repeat(cells, reps)
+    rng.shuffle(cell_of)
+    pts = np.empty((len(cell_of), 4), dtype=np.float32)
+    pts[:, 0] = cell_of // grid[1] + rng.uniform(0.1, 0.9, len(cell_of))
+    pts[:, 1] = cell_of % grid[1] + rng.uniform(0.1, 0.9, len(cell_of))
+    pts[:, 2] = 0.5
+    pts[:, 3] = rng.random(len(cell_of))
+    _say(f"vfe scan edges voxels={n_vox} points={len(pts)}")
+    rc, rx = orc.voxel_max_vfe(pts, None, lo, size, grid, 1)
+    assert len(rc) == n_vox
+    _check(_run(grid, 1, lo, size, pts, None, 4, "f32", max_voxels=n_vox + 7), rc, rx, 0)
+
+
 def test_vfe_capacity_and_host_errors():
     grid, lo, size = (16, 16, 1), (-4.0, -2.0, -1.0), (0.5, 0.25, 2.0)
     pts, _ = synth.make_points(26, 3000, lo, (4.0, 2.0, 1.0), f_in=5)
