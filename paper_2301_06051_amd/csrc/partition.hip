@@ -434,15 +434,29 @@ __device__ __forceinline__ int32_t wave_scan_max(int32_t v, int32_t lowest) {
 }
 
 
-// The work list of a frame whose sets fit the LDS tables (n_sets <= fill_sets, below 65,535): the same result as
-// build_tiles below, with the rows before every set, the tile starts and the tiles' launch slots kept in LDS from the
-// first pass to the last, so that the passes are separated by workgroup barriers only -- no pass reads memory that
-// an earlier pass wrote.  P [fill_sets + 1] | first set of every tile, 16 bit [fill_sets + 1] | launch slot of every
-// tile, 16 bit [fill_sets + 1] | tile-start marks [fill_sets + 1]; the two 16-bit tables are the fill's scratch first.
+// A frame with more sets than the tables hold is taken in pieces of kTilePiece sets, a workgroup per piece, every piece
+// starting a tile of its own; what a piece has to know of the others are their tile counts per launch-order bucket.
+constexpr int32_t kTilePiece = 4096;
+struct TilePiece {
+  int32_t mode;                   // 0: the whole frame; 1: a piece, counting its tiles per bucket; 2: a piece, writing
+  int32_t s_base;                 // first set of the piece
+  int32_t tile_base;              // mode 2: tiles of the pieces before this one
+  int32_t* hist_out;              // mode 1: [32] this piece's tiles per bucket
+  const int32_t* bucket_base;     // mode 2: [32] in LDS, launch slots before this piece's tiles of a bucket
+};
+
+// The work list of a frame, or of a piece of one, whose sets fit the LDS tables (n_sets <= fill_sets, below 65,535): one
+// workgroup cuts the set sequence into tiles for the layer kernels, orders the tiles for launch and writes the
+// descriptor headers; set_loc[s] = set_loc_code(descriptor slot, place in the tile, first row), for k_emit.  The rows
+// before every set, the tile starts and the tiles' first sets stay in LDS from the first pass to the last, so that the
+// passes are separated by workgroup barriers only -- no pass reads memory that an earlier pass wrote.
+// P [fill_sets + 1] | first set of every tile, 16 bit [fill_sets + 1] | 16 bit [fill_sets + 1] | tile-start marks
+// [fill_sets + 1]; the two 16-bit tables are the fill's scratch first.  Sets are counted from the piece's first.
 // set_w == nullptr: P [0 .. n_sets] is in place already (k_scan_windows wrote it while it scanned the windows).
 __device__ __forceinline__ void build_tiles_lds(const int32_t* set_w, const int32_t* win_count, const int32_t* win_soff,
                                                 int32_t n_sets, int32_t tau, int32_t n_windows, int32_t rows_per_cut,
-                                                TileOut out, int32_t* set_loc, int32_t fill_sets, int32_t* status) {
+                                                TileOut out, int32_t* set_loc, int32_t fill_sets, int32_t* status,
+                                                const TilePiece pc) {
   extern __shared__ uint32_t fill_lds[];
   __shared__ int32_t wave_tot[16];
   __shared__ int32_t carry_s, over_s;
@@ -450,8 +464,8 @@ __device__ __forceinline__ void build_tiles_lds(const int32_t* set_w, const int3
   const int32_t tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   int32_t* P = reinterpret_cast<int32_t*>(fill_lds);
   uint16_t* t_first = reinterpret_cast<uint16_t*>(P + fill_sets + 1);
-  uint16_t* t_pos = t_first + fill_sets + 1;
-  uint8_t* mark = reinterpret_cast<uint8_t*>(t_pos + fill_sets + 1);
+  uint16_t* scratch16 = t_first + fill_sets + 1;
+  uint8_t* mark = reinterpret_cast<uint8_t*>(scratch16 + fill_sets + 1);
   if (tid == 0) { carry_s = 0; over_s = -1; }
   lds_barrier();
   // pass 1: padded rows per set, their running sum (four consecutive sets per thread and trip: the two dependent
@@ -462,7 +476,7 @@ __device__ __forceinline__ void build_tiles_lds(const int32_t* set_w, const int3
     int32_t w[kPer], cnt[kPer], soff[kPer], rows[kPer], pre[kPer];
 #pragma unroll
     for (int32_t j = 0; j < kPer; ++j) {
-      const int32_t wj = s0 + j < n_sets ? set_w[s0 + j] : 0;
+      const int32_t wj = s0 + j < n_sets ? set_w[pc.s_base + s0 + j] : 0;
       w[j] = wj < 0 ? 0 : (wj >= n_windows ? n_windows - 1 : wj);
     }
 #pragma unroll
@@ -471,7 +485,7 @@ __device__ __forceinline__ void build_tiles_lds(const int32_t* set_w, const int3
 #pragma unroll
     for (int32_t j = 0; j < kPer; ++j) {
       const int64_t N = cnt[j] > 0 ? cnt[j] : 1, S = (N + tau - 1) / tau;
-      rows[j] = s0 + j < n_sets ? set_rows(set_distinct(N, S, s0 + j - soff[j], tau)) : 0;
+      rows[j] = s0 + j < n_sets ? set_rows(set_distinct(N, S, pc.s_base + s0 + j - soff[j], tau)) : 0;
       pre[j] = mine;
       mine += rows[j];
     }
@@ -488,18 +502,24 @@ __device__ __forceinline__ void build_tiles_lds(const int32_t* set_w, const int3
     if (tid == 1023) carry_s = before + incl;
     lds_barrier();
   }
-  // tile starts: filled tiles (see fill_tile_starts) for frames of many rounds over the compute units, else a set
-  // starts a tile when the running row count crosses a multiple of rows_per_cut between its predecessor's start and
-  // its own (a tile then holds at most rows_per_cut - 4 + pad4(tau) <= 96 rows)
-  rows_per_cut = tile_cut(P[n_sets], rows_per_cut);
-  if (!fill_tiles(P, t_first, t_pos, mark, n_sets, rows_per_cut)) {
-    lds_barrier();
-    for (int32_t s = tid; s <= n_sets; s += 1024) mark[s] = s < n_sets && (s == 0 || P[s - 1] / rows_per_cut != P[s] / rows_per_cut);
+  // tile starts.  The whole frame: filled tiles (see fill_tile_starts) if it takes many rounds over the compute units,
+  // else a set starts a tile when the running row count crosses a multiple of rows_per_cut between its predecessor's
+  // start and its own (a tile then holds at most rows_per_cut - 4 + pad4(tau) <= 96 rows).  A piece (a frame of very
+  // many rounds): tiles filled to the full 96 rows.
+  if (pc.mode != 0) {
+    fill_tile_starts(P, t_first, scratch16, mark, n_sets, kTileRows);
+  } else {
+    rows_per_cut = tile_cut(P[n_sets], rows_per_cut);
+    if (!fill_tiles(P, t_first, scratch16, mark, n_sets, rows_per_cut)) {
+      lds_barrier();
+      for (int32_t s = tid; s <= n_sets; s += 1024) mark[s] = s < n_sets && (s == 0 || P[s - 1] / rows_per_cut != P[s] / rows_per_cut);
+    }
   }
   if (tid == 0) carry_s = 0;
   lds_barrier();
-  // pass 2: the tiles are numbered by counting their starts (a scan), so none is empty
-  const int32_t tile_lim = out.max_tiles < fill_sets ? out.max_tiles : fill_sets;
+  // pass 2: the tiles are numbered by counting their starts (a scan), so none is empty.  (A piece never has more
+  // tiles than sets, so only the whole-frame list can turn out too short here.)
+  const int32_t tile_lim = (pc.mode == 0 && out.max_tiles < fill_sets) ? out.max_tiles : fill_sets;
   for (int32_t base = 0; base < n_sets; base += 1024 * kPer) {
     const int32_t s0 = base + tid * kPer;
     int32_t pre[kPer], mine = 0;
@@ -518,8 +538,12 @@ __device__ __forceinline__ void build_tiles_lds(const int32_t* set_w, const int3
       const int32_t s = s0 + j;
       if (s < n_sets && mark[s]) {
         const int32_t tile = before + incl - mine + pre[j] - 1;
-        if (tile < tile_lim) { t_first[tile] = (uint16_t)s; out.tile_first[tile] = s; }
-        else if (tile == tile_lim) over_s = s;               // first set that no tile is left for
+        if (tile < tile_lim) {
+          t_first[tile] = (uint16_t)s;
+          if (pc.mode != 1) out.tile_first[pc.tile_base + tile] = pc.s_base + s;
+        } else if (tile == tile_lim) {
+          over_s = s;                                        // first set that no tile is left for
+        }
       }
     }
     lds_barrier();
@@ -531,8 +555,7 @@ __device__ __forceinline__ void build_tiles_lds(const int32_t* set_w, const int3
   const int32_t n_eff = tiles_short ? over_s : n_sets;
   if (tid == 0) {
     if (tiles_short) atomicOr(status, DSVT_ST_TILE_OVERFLOW);   // the sets past the last tile get none
-    *out.n_tiles = nt;
-    out.tile_first[nt] = n_eff;
+    if (pc.mode == 0) { *out.n_tiles = nt; out.tile_first[nt] = n_eff; }
     t_first[nt] = (uint16_t)n_eff;
   }
   if (tid < 32) hist[tid] = 0;
@@ -545,9 +568,13 @@ __device__ __forceinline__ void build_tiles_lds(const int32_t* set_w, const int3
     atomicAdd(&hist[b], 1);
   }
   lds_barrier();
+  if (pc.mode == 1) {
+    if (tid < 32) pc.hist_out[tid] = hist[tid];
+    return;
+  }
   if (wv == 0) {
     const int32_t h = lane < 32 ? hist[lane] : 0, incl = wave_scan_add(h);
-    if (lane < 32) running[lane] = incl - h;
+    if (lane < 32) running[lane] = pc.mode == 2 ? pc.bucket_base[lane] : incl - h;
   }
   lds_barrier();
   for (int32_t base = 0; base < nt; base += 1024) {
@@ -585,22 +612,20 @@ __device__ __forceinline__ void build_tiles_lds(const int32_t* set_w, const int3
     }
     lds_barrier();
     if (b >= 0) {
+      // the tile's launch slot; then, per set of the tile, its descriptor slot, its place among the tile's sets and
+      // its first row
       const int32_t pos = wave_cnt[wv][b] + rank;
-      out.tile_order[pos] = t;
-      t_pos[t] = (uint16_t)pos;
-      desc_header(out, pos, rows, (int32_t)t_first[t + 1] - (int32_t)t_first[t]);
+      const int32_t s_begin = t_first[t], s_end = t_first[t + 1], p0 = P[s_begin];
+      out.tile_order[pos] = pc.tile_base + t;
+      desc_header(out, pos, rows, s_end - s_begin);
+      for (int32_t s = s_begin; s < s_end; ++s) {
+        const int32_t ls = s - s_begin, r0 = P[s] - p0;
+        set_loc[pc.s_base + s] = (ls < kDescSets && r0 <= kTileRows - 4) ? set_loc_code(pos, ls, r0) : -1;
+      }
     }
     lds_barrier();
   }
-  // pass 4: per set, its descriptor slot, its place among the tile's sets and its first row (a thread per tile)
-  for (int32_t t = tid; t < nt; t += 1024) {
-    const int32_t s_begin = t_first[t], s_end = t_first[t + 1], pos = t_pos[t], p0 = P[s_begin];
-    for (int32_t s = s_begin; s < s_end; ++s) {
-      const int32_t ls = s - s_begin, r0 = P[s] - p0;
-      set_loc[s] = (ls < kDescSets && r0 <= kTileRows - 4) ? set_loc_code(pos, ls, r0) : -1;
-    }
-  }
-  for (int32_t s = n_eff + tid; s < n_sets; s += 1024) set_loc[s] = -1;
+  for (int32_t s = n_eff + tid; s < n_sets; s += 1024) set_loc[pc.s_base + s] = -1;
 }
 
 // k_scan_windows for a job whose sets fit the LDS tables of the work-list builder: the scans of voxels- and
@@ -657,255 +682,68 @@ __device__ __forceinline__ void scan_windows_and_tiles(const int32_t* __restrict
   }
   if (tid == 0 && n_sets == n_all) P[n_sets] = carry_sr[1];     // (of a clipped list, P[n_sets] is the row count before the first set left out)
   lds_barrier();
-  build_tiles_lds(nullptr, nullptr, nullptr, n_sets, tau, n_windows, rows_per_cut, out, set_loc, fill_sets, status);
+  build_tiles_lds(nullptr, nullptr, nullptr, n_sets, tau, n_windows, rows_per_cut, out, set_loc, fill_sets, status,
+                  TilePiece{0, 0, 0, nullptr, nullptr});
 }
 
-// One workgroup: cut the set sequence into tiles for the layer kernels, order the tiles for launch
-// and write the descriptor headers.  With P(s) the running sum of padded rows before set s, set s
-// starts a tile when P crosses a multiple of rows_per_cut; a tile then holds at most
-// rows_per_cut - 4 + pad4(tau) rows.  set_loc[s] = set_loc_code(descriptor slot, place in the tile, first row), for k_emit.
+// k_tiles for one window configuration: the whole frame in the first workgroup if its sets fit the tables, else a
+// workgroup per piece of kTilePiece sets, in two launches -- phase 0 counts every piece's tiles per launch-order bucket,
+// phase 1 places them (a piece's tiles come after those of the pieces before it, bucket by bucket, so the order is the
+// one a single stable sort of all tiles would give).
 __device__ __forceinline__ void build_tiles(const int32_t* set_w, const int32_t* win_count, const int32_t* win_soff,
                                             const int32_t* n_sets_ptr, int32_t set_cap, int32_t tau, int32_t n_windows,
-                                            int32_t rows_per_cut, TileOut out, int32_t* tile_rows, int32_t* tile_pos,
-                                            int32_t* set_p, int32_t* set_loc, int32_t fill_sets, int32_t* status) {
-  extern __shared__ uint32_t fill_lds[];                     // filled tiles: rows before every set, two jump tables, marks
-  __shared__ int32_t wave_tot[16];
-  __shared__ int32_t carry_s;
-  __shared__ int32_t hist[32], running[32], wave_cnt[16][32];
-  const int32_t tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+                                            int32_t rows_per_cut, TileOut out, int32_t* piece_hist, int32_t* set_loc,
+                                            int32_t fill_sets, int32_t* status, int32_t phase) {
+  __shared__ int32_t bucket_base_s[32];
+  __shared__ int32_t tile_base_s, total_s;
+  const int32_t tid = threadIdx.x, lane = tid & 63, piece = blockIdx.y;
   int32_t n_sets = *n_sets_ptr;
   n_sets = n_sets < set_cap ? n_sets : set_cap;
   if (n_sets <= 0) {
-    if (tid == 0) { *out.n_tiles = 0; out.tile_first[0] = 0; }
+    if (tid == 0 && piece == 0 && phase == 1) { *out.n_tiles = 0; out.tile_first[0] = 0; }
     return;
   }
-  if (fill_sets > 0 && n_sets <= fill_sets && n_sets < 65535) {
-    build_tiles_lds(set_w, win_count, win_soff, n_sets, tau, n_windows, rows_per_cut, out, set_loc, fill_sets, status);
+  if (n_sets <= fill_sets && n_sets < 65535) {
+    if (piece == 0 && phase == 1)
+      build_tiles_lds(set_w, win_count, win_soff, n_sets, tau, n_windows, rows_per_cut, out, set_loc, fill_sets, status,
+                      TilePiece{0, 0, 0, nullptr, nullptr});
     return;
   }
-  if (tid == 0) carry_s = 0;
-  __syncthreads();
-  // pass 1: padded rows per set, their running sum.  Four consecutive sets per thread and trip, so that the two
-  // dependent loads of a set (its window, then the window's count and first set) are in flight for four sets at once
-  // and a frame of 6,500 sets takes two trips instead of seven.
-  constexpr int32_t kPer = 4;
-  for (int32_t base = 0; base < n_sets; base += 1024 * kPer) {
-    const int32_t s0 = base + tid * kPer;
-    int32_t w[kPer], cnt[kPer], soff[kPer], rows[kPer], pre[kPer];
-#pragma unroll
-    for (int32_t j = 0; j < kPer; ++j) {
-      const int32_t s = s0 + j;
-      int32_t wj = s < n_sets ? set_w[s] : 0;
-      w[j] = wj < 0 ? 0 : (wj >= n_windows ? n_windows - 1 : wj);
-    }
-#pragma unroll
-    for (int32_t j = 0; j < kPer; ++j) { cnt[j] = win_count[w[j]]; soff[j] = win_soff[w[j]]; }
-    int32_t mine = 0;
-#pragma unroll
-    for (int32_t j = 0; j < kPer; ++j) {
-      const int32_t s = s0 + j;
-      const int64_t N = cnt[j] > 0 ? cnt[j] : 1, S = (N + tau - 1) / tau;
-      rows[j] = s < n_sets ? set_rows(set_distinct(N, S, s - soff[j], tau)) : 0;
-      pre[j] = mine;
-      mine += rows[j];
-    }
-    int32_t incl = mine;
-    for (int32_t d = 1; d < 64; d <<= 1) {
-      int32_t up = __shfl_up(incl, d, 64);
-      if (lane >= d) incl += up;
-    }
-    if (lane == 63) wave_tot[wv] = incl;
-    __syncthreads();
-    int32_t before = carry_s;
-    for (int32_t k = 0; k < wv; ++k) before += wave_tot[k];
-    const int32_t first_p = before + incl - mine;            // rows before set s0
-#pragma unroll
-    for (int32_t j = 0; j < kPer; ++j) {
-      const int32_t s = s0 + j;
-      if (s < n_sets) {
-        set_p[s] = first_p + pre[j];
-        set_loc[s] = -1;                                     // set in pass 4
-        if (s == n_sets - 1) set_p[n_sets] = first_p + pre[j] + rows[j];
+  const int32_t n_pieces = (n_sets + kTilePiece - 1) / kTilePiece;
+  if (piece >= n_pieces) return;
+  const int32_t s_base = piece * kTilePiece, n_mine = n_sets - s_base < kTilePiece ? n_sets - s_base : kTilePiece;
+  if (phase == 0) {
+    build_tiles_lds(set_w, win_count, win_soff, n_mine, tau, n_windows, rows_per_cut, out, set_loc, fill_sets, status,
+                    TilePiece{1, s_base, 0, piece_hist + piece * 32, nullptr});
+    return;
+  }
+  if (tid < 64) {
+    int32_t all = 0, mine = 0;                               // tiles of bucket `lane`: of every piece, of the pieces before
+    if (lane < 32)
+      for (int32_t q = 0; q < n_pieces; ++q) {
+        const int32_t h = piece_hist[q * 32 + lane];
+        all += h;
+        mine += q < piece ? h : 0;
       }
-    }
-    __syncthreads();
-    if (tid == 1023) carry_s = before + incl;
-    __syncthreads();
+    const int32_t all_incl = wave_scan_add(all), mine_incl = wave_scan_add(mine);
+    if (lane < 32) bucket_base_s[lane] = all_incl - all + mine;
+    if (lane == 63) { total_s = all_incl; tile_base_s = mine_incl; }
   }
-  __threadfence_block();
-  __syncthreads();
-  rows_per_cut = tile_cut(set_p[n_sets], rows_per_cut);
-  // Frames of many rounds over the compute units: a tile costs a fixed amount plus its rows, so tiles are filled
-  // as far as they go (84 rows per tile on average instead of rows_per_cut), see fill_tile_starts.
-  bool filled = false;
-  if (fill_sets > 0 && fill_wanted(set_p[n_sets], n_sets, rows_per_cut)) {
-    int32_t* P = reinterpret_cast<int32_t*>(fill_lds);                       // [fill_sets + 1]
-    uint16_t* jump = reinterpret_cast<uint16_t*>(P + fill_sets + 1);         // [2][fill_sets + 1]
-    uint16_t* jump2 = jump + fill_sets + 1;
-    uint8_t* mark = reinterpret_cast<uint8_t*>(jump2 + fill_sets + 1);       // [fill_sets + 1]
-    if (n_sets <= fill_sets && n_sets < 65535) {
-      for (int32_t s = tid; s <= n_sets; s += 1024) P[s] = set_p[s];
-      __syncthreads();
-      filled = fill_tiles(P, jump, jump2, mark, n_sets, rows_per_cut);
-      if (filled)
-        for (int32_t s = tid; s < n_sets; s += 1024)
-          if (mark[s]) set_loc[s] = -2;
-    } else {
-      // More sets than the tables hold (a frame of many rounds): the sequence is taken in pieces of fill_sets sets,
-      // every piece starting a tile of its own, tiles filled to the full 96 rows (one short tile per piece at most).
-      filled = true;
-      const int32_t piece = fill_sets < 65534 ? fill_sets : 65534;
-      for (int32_t c0 = 0; c0 < n_sets; c0 += piece) {
-        const int32_t n_c = n_sets - c0 < piece ? n_sets - c0 : piece;
-        for (int32_t s = tid; s <= n_c; s += 1024) P[s] = set_p[c0 + s];
-        __syncthreads();
-        fill_tile_starts(P, jump, jump2, mark, n_c, kTileRows);
-        for (int32_t s = tid; s < n_c; s += 1024)
-          if (mark[s]) set_loc[c0 + s] = -2;
-        __syncthreads();
-      }
-    }
+  lds_barrier();
+  const int32_t total = total_s;
+  if (total > out.max_tiles) {                               // the caller's list is shorter than the frame needs:
+    for (int32_t s = tid; s < n_mine; s += 1024) set_loc[s_base + s] = -1;     // no set gets a tile
+    if (tid == 0 && piece == 0) { atomicOr(status, DSVT_ST_TILE_OVERFLOW); *out.n_tiles = 0; out.tile_first[0] = 0; }
+    return;
   }
-  __threadfence_block();
-  __syncthreads();
-  // pass 2: tile boundaries.  A set starts a tile when the running row count crosses a multiple of
-  // rows_per_cut between its predecessor's start and its own; tiles are numbered by counting these
-  // starts (a scan), so none is empty even when one set is longer than rows_per_cut.  A tile then
-  // holds at most rows_per_cut - 4 + pad4(tau) <= 96 rows.
-  if (tid == 0) carry_s = 0;
-  __syncthreads();
-  for (int32_t base = 0; base < n_sets; base += 1024 * kPer) {
-    const int32_t s0 = base + tid * kPer;
-    int32_t pv[kPer + 1], mk[kPer];                          // rows before sets s0 - 1 .. s0 + 3; the fill's marks
-#pragma unroll
-    for (int32_t j = 0; j <= kPer; ++j) {
-      const int32_t s = s0 + j - 1;
-      pv[j] = (s >= 0 && s < n_sets) ? set_p[s] : 0;
-    }
-#pragma unroll
-    for (int32_t j = 0; j < kPer; ++j) mk[j] = (filled && s0 + j < n_sets) ? set_loc[s0 + j] : 0;
-    bool first[kPer];
-    int32_t pre[kPer], mine = 0;
-#pragma unroll
-    for (int32_t j = 0; j < kPer; ++j) {
-      const int32_t s = s0 + j;
-      first[j] = s < n_sets && (filled ? mk[j] == -2 : (s == 0 || pv[j] / rows_per_cut != pv[j + 1] / rows_per_cut));
-      mine += first[j] ? 1 : 0;
-      pre[j] = mine;                                         // tile starts among sets s0 .. s0 + j
-    }
-    int32_t incl = mine;
-    for (int32_t d = 1; d < 64; d <<= 1) {
-      int32_t up = __shfl_up(incl, d, 64);
-      if (lane >= d) incl += up;
-    }
-    if (lane == 63) wave_tot[wv] = incl;
-    __syncthreads();
-    int32_t before = carry_s;
-    for (int32_t k = 0; k < wv; ++k) before += wave_tot[k];
-    const int32_t starts_before = before + incl - mine;      // tile starts among sets 0 .. s0 - 1
-#pragma unroll
-    for (int32_t j = 0; j < kPer; ++j) {
-      const int32_t s = s0 + j;
-      if (s < n_sets) {
-        const int32_t tile = starts_before + pre[j] - 1;     // tile of set s
-        set_loc[s] = tile;                                   // until pass 4 replaces it
-        if (first[j] && tile < out.max_tiles) { out.tile_first[tile] = s; tile_rows[tile] = pv[j + 1]; }
-        if (s == n_sets - 1) {
-          const int32_t nt = tile + 1 < out.max_tiles ? tile + 1 : out.max_tiles;
-          if (tile + 1 > out.max_tiles) atomicOr(status, DSVT_ST_TILE_OVERFLOW);   // the sets past the last tile get none
-          *out.n_tiles = nt;
-          out.tile_first[nt] = n_sets;
-          tile_rows[nt] = set_p[n_sets];
-        }
-      }
-    }
-    __syncthreads();
-    if (tid == 1023) carry_s = before + incl;
-    __syncthreads();
-  }
-  __threadfence_block();
-  __syncthreads();
-  // pass 3: launch order = tiles with more rows first (a stable counting sort on rows / 4), so
-  // that the short tiles fill the tail of the launch
-  const int32_t nt = *out.n_tiles;
-  if (tid < 32) hist[tid] = 0;
-  __syncthreads();
-  for (int32_t base = 0; base < nt; base += 1024) {
-    const int32_t t = base + tid;
-    if (t < nt) {
-      int32_t b = 24 - (tile_rows[t + 1] - tile_rows[t]) / 4;
-      b = b < 0 ? 0 : (b > 31 ? 31 : b);
-      atomicAdd(&hist[b], 1);
-    }
-  }
-  __syncthreads();
-  if (tid == 0) { int32_t acc = 0; for (int32_t b = 0; b < 32; ++b) { running[b] = acc; acc += hist[b]; } }
-  __syncthreads();
-  for (int32_t base = 0; base < nt; base += 1024) {
-    const int32_t t = base + tid;
-    int32_t b = -1;
-    if (t < nt) {
-      b = 24 - (tile_rows[t + 1] - tile_rows[t]) / 4;
-      b = b < 0 ? 0 : (b > 31 ? 31 : b);
-    }
-    for (int32_t k = lane; k < 32; k += 64) wave_cnt[wv][k] = 0;
-    int32_t rank = 0;                                       // among this wavefront's lanes of the same bucket
-    unsigned long long todo = __ballot(b >= 0);
-    while (todo) {
-      const int32_t leader = __ffsll((long long)todo) - 1;
-      const int32_t lb = __shfl(b, leader, 64);
-      const unsigned long long same = __ballot(b == lb);
-      if (b == lb) rank = __popcll(same & ((1ull << lane) - 1ull));
-      if (lane == leader) wave_cnt[wv][lb] = __popcll(same);
-      todo &= ~same;
-    }
-    __syncthreads();
-    if (b >= 0) {
-      int32_t pos = running[b] + rank;
-      for (int32_t k = 0; k < wv; ++k) pos += wave_cnt[k][b];
-      out.tile_order[pos] = t;
-      tile_pos[t] = pos;
-      desc_header(out, pos, tile_rows[t + 1] - tile_rows[t], out.tile_first[t + 1] - out.tile_first[t]);
-    }
-    __syncthreads();
-    if (tid < 32) { int32_t add = 0; for (int32_t k = 0; k < 16; ++k) add += wave_cnt[k][tid]; running[tid] += add; }
-    __syncthreads();
-  }
-  // pass 4: per set, its descriptor slot, its place among the tile's sets and its first row
-  for (int32_t base = 0; base < n_sets; base += 1024 * kPer) {
-    const int32_t s0 = base + tid * kPer;
-    int32_t t[kPer], sp[kPer], pos[kPer], tf[kPer], tr[kPer];
-#pragma unroll
-    for (int32_t j = 0; j < kPer; ++j) {
-      const int32_t s = s0 + j;
-      t[j] = s < n_sets ? set_loc[s] : -1;
-      sp[j] = s < n_sets ? set_p[s] : 0;
-    }
-#pragma unroll
-    for (int32_t j = 0; j < kPer; ++j) {
-      const bool ok = t[j] >= 0 && t[j] < nt;
-      pos[j] = ok ? tile_pos[t[j]] : 0;
-      tf[j] = ok ? out.tile_first[t[j]] : 0;
-      tr[j] = ok ? tile_rows[t[j]] : 0;
-    }
-#pragma unroll
-    for (int32_t j = 0; j < kPer; ++j) {
-      const int32_t s = s0 + j;
-      if (s < n_sets) {
-        int32_t loc = -1;
-        if (t[j] >= 0 && t[j] < nt) {
-          const int32_t ls = s - tf[j], r0 = sp[j] - tr[j];
-          if (ls >= 0 && ls < kDescSets && r0 >= 0 && r0 <= kTileRows - 4) loc = set_loc_code(pos[j], ls, r0);
-        }
-        set_loc[s] = loc;
-      }
-    }
-  }
+  build_tiles_lds(set_w, win_count, win_soff, n_mine, tau, n_windows, rows_per_cut, out, set_loc, fill_sets, status,
+                  TilePiece{2, s_base, tile_base_s, nullptr, bucket_base_s});
+  if (tid == 0 && piece == n_pieces - 1) { *out.n_tiles = total; out.tile_first[total] = n_sets; }
 }
 
 // The general front end's own arguments for one window configuration (frames too large for k_front).
 struct GenJob {
-  int32_t *ws_setwin, *tile_rows, *tile_pos, *set_p;
+  int32_t *ws_setwin, *piece_hist;
   int32_t set_bound, want_tiles, fill_sets;
   int32_t merged;                            // k_scan_windows also builds the work list (sets fit the LDS tables)
 };
@@ -954,13 +792,13 @@ __global__ void __launch_bounds__(1024) k_scan_windows(Jobs jobs, GenJobs gen) {
     scan_windows(J.win_count, J.win_soff, J.g.n_windows, J.g.tau, J.max_sets, J.n_sets, J.status, G.ws_setwin, G.set_bound);
 }
 
-// One workgroup per job that wants a work list.
-__global__ void __launch_bounds__(1024) k_tiles(Jobs jobs, GenJobs gen) {
+// Jobs that want a work list and did not get it from k_scan_windows: blockIdx.x = job, blockIdx.y = piece.
+__global__ void __launch_bounds__(1024) k_tiles(Jobs jobs, GenJobs gen, int32_t phase) {
   const Job& J = jobs.j[blockIdx.x];
   const GenJob& G = gen.j[blockIdx.x];
   if (!G.want_tiles || G.merged) return;
   build_tiles(G.ws_setwin, J.win_count, J.win_soff, J.n_sets, J.set_cap, J.g.tau, J.g.n_windows, J.rows_per_cut, J.out,
-              G.tile_rows, G.tile_pos, G.set_p, J.set_loc, G.fill_sets, J.status);
+              G.piece_hist, J.set_loc, G.fill_sets, J.status, phase);
 }
 
 // Scan over the 1024 threads of a workgroup, continued from one call to the next through `carry`:
@@ -1377,7 +1215,7 @@ __global__ void k_emit(Jobs jobs, const int4* __restrict__ coords, int32_t n, in
 
 struct PartPlan {
   PartGeom g;
-  size_t off_mark, off_bitmap, off_prefix, off_count, off_soff, off_setwin, off_tilerows, off_tilepos, off_setp, off_setloc, total;
+  size_t off_mark, off_bitmap, off_prefix, off_count, off_soff, off_setwin, off_piecehist, off_setloc, total;
   bool desc_ok;
   int64_t n_words;
   int32_t set_bound, tile_bound, rows_per_cut;
@@ -1431,9 +1269,7 @@ int make_plan(const dsvt_part_cfg* cfg, int32_t n_voxels, PartPlan* p) {
   const int64_t pad_tau = (cfg->tau + 3) & ~3;
   p->rows_per_cut = (int32_t)(100 - pad_tau);
   p->tile_bound = p->rows_per_cut > 0 ? (int32_t)((n_voxels + 4 * bound) / p->rows_per_cut + 1 + kComputeUnits) : 0;   // (see tile_cut)
-  p->off_tilerows = o; o = dsvt_align_up(o + (size_t)(p->tile_bound + 1) * 4, 256);
-  p->off_tilepos = o;  o = dsvt_align_up(o + (size_t)(p->tile_bound + 1) * 4, 256);
-  p->off_setp = o;     o = dsvt_align_up(o + (size_t)(bound + 1) * 4, 256);
+  p->off_piecehist = o; o = dsvt_align_up(o + (size_t)(bound / kTilePiece + 1) * 32 * 4, 256);   // (see build_tiles)
   p->off_setloc = o;   o = dsvt_align_up(o + (size_t)(bound + 1) * 4, 256);
   // set_loc packs (slot << 12 | place << 7 | row), a descriptor (multiplicity << 24 | position code) into 32 bits
   p->desc_ok = p->rows_per_cut >= 4 && p->tile_bound < (1 << 19) &&
@@ -1558,7 +1394,7 @@ int run_partitions(const PartRequest* reqs, int32_t n, const int32_t* coords, in
   // the general one (three launches) for the others, then emit.
   Jobs jobs = {}, front_jobs = {}, gen_jobs = {};
   GenJobs gen = {};
-  int32_t n_front = 0, n_gen = 0, max_tiles = 0, any_tiles = 0, any_merged = 0;
+  int32_t n_front = 0, n_gen = 0, max_tiles = 0, any_tiles = 0, any_merged = 0, tile_pieces = 0;
   size_t front_lds = 0, fill_lds = 0, count_lds = 0;
   int64_t count_threads = 0;
   for (int32_t q = 0; q < n; ++q) {
@@ -1573,17 +1409,19 @@ int run_partitions(const PartRequest* reqs, int32_t n, const int32_t* coords, in
       char* base = (char*)reqs[q].ws;
       GenJob& G = gen.j[n_gen];
       G.ws_setwin = (int32_t*)(base + p.off_setwin);
-      G.tile_rows = (int32_t*)(base + p.off_tilerows);
-      G.tile_pos = (int32_t*)(base + p.off_tilepos);
-      G.set_p = (int32_t*)(base + p.off_setp);
+      G.piece_hist = (int32_t*)(base + p.off_piecehist);
       G.set_bound = p.set_bound;
       G.want_tiles = P.want_tiles ? 1 : 0;
-      // tables of the tile filling (see build_tiles), when this frame's sets fit the LDS
-      // (9 bytes per set; frames with more sets than the LDS holds are filled in pieces of kFillPiece sets)
-      constexpr int32_t kFillPiece = 16384;
-      G.fill_sets = P.want_tiles ? (p.set_bound < kFillPiece ? p.set_bound : kFillPiece) : 0;
+      // LDS tables of the work-list builder (see build_tiles_lds; 9 bytes per set): for the whole frame if it has at
+      // most kFillMax sets, else for the pieces it is taken in (see build_tiles)
+      constexpr int32_t kFillMax = 16384;
+      G.fill_sets = P.want_tiles ? (p.set_bound < kFillMax ? p.set_bound : kFillMax) : 0;
       const size_t need = ((size_t)G.fill_sets + 1) * 9 + 16;
-      static_assert(((size_t)kFillPiece + 1) * 9 + 16 <= kFrontLds, "tables of one piece fit the LDS k_tiles may ask for");
+      static_assert(((size_t)kFillMax + 1) * 9 + 16 <= kFrontLds && kTilePiece <= kFillMax, "the tables fit the LDS k_tiles may ask for");
+      if (G.want_tiles && p.set_bound > G.fill_sets) {
+        const int32_t pieces = (p.set_bound + kTilePiece - 1) / kTilePiece;
+        tile_pieces = pieces > tile_pieces ? pieces : tile_pieces;
+      }
       if (G.fill_sets) fill_lds = need > fill_lds ? need : fill_lds;
       // every set has a place in the tables: the scan of the windows builds the work list too (no k_tiles launch)
       G.merged = (G.want_tiles && p.set_bound <= G.fill_sets && p.set_bound < 65535 && p.g.tau > 1) ? 1 : 0;
@@ -1636,7 +1474,8 @@ int run_partitions(const PartRequest* reqs, int32_t n, const int32_t* coords, in
     }
     if (any_tiles) {
       dsvt_prof_scope ps(DSVT_K_PART_TILES, st);
-      k_tiles<<<n_gen, 1024, fill_lds, st>>>(gen_jobs, gen);
+      if (tile_pieces) k_tiles<<<dim3(n_gen, tile_pieces), 1024, fill_lds, st>>>(gen_jobs, gen, 0);
+      k_tiles<<<dim3(n_gen, tile_pieces ? tile_pieces : 1), 1024, fill_lds, st>>>(gen_jobs, gen, 1);
     }
   }
   {

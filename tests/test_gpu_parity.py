@@ -142,18 +142,20 @@ def test_large_frames_get_filled_tiles(cid, n):
     _say(f"  rows {rows}, tiles {nt}, rows per tile {rows / nt:.1f}")
     if nt > 4 * 256:
         # frames of more than four rounds: tiles of up to 96 rows, filled greedily inside pieces of 4,096 rows (the
-        # first set that begins in a piece starts a tile, and so does every 16,384th set of a frame with more sets
-        # than that); the count follows from the sets' padded rows alone
+        # first set that begins in a piece starts a tile); a frame of more than 16,384 sets is taken 4,096 sets at a
+        # time, each such run with rows counted from its own start; the count follows from the sets' padded rows alone
         per_set = (first.sum(1) + 3) // 4 * 4
-        before = np.concatenate([[0], np.cumsum(per_set)])
-        want, s = 0, 0
-        while s < len(per_set):
-            want += 1
-            t = s + 1
-            while (t < len(per_set) and before[t + 1] - before[s] <= 96 and before[t] >> 12 == before[s] >> 12
-                   and not (len(per_set) > 16384 and t % 16384 == 0)):
-                t += 1
-            s = t
+        runs = [per_set] if len(per_set) <= 16384 else [per_set[i:i + 4096] for i in range(0, len(per_set), 4096)]
+        want = 0
+        for run in runs:
+            before = np.concatenate([[0], np.cumsum(run)])
+            s = 0
+            while s < len(run):
+                want += 1
+                t = s + 1
+                while t < len(run) and before[t + 1] - before[s] <= 96 and before[t] >> 12 == before[s] >> 12:
+                    t += 1
+                s = t
         assert nt == want
         assert rows / nt > 75                              # (an unbroken greedy fill of the skewed batch's sets gives 76.2)
     else:
