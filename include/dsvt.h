@@ -80,8 +80,8 @@ int dsvt_partition_bound(const dsvt_part_cfg* cfg, int32_t n_voxels, int32_t* ma
  *                                entry of the first n_tiles descriptors that a kernel reads is
  *                                written by the call; the rest keeps what it held.
  * Needs tau <= 96, grid[0]*(2W-1)*(2H-1) < 2^24 and max_tiles of at least the bound dsvt_partition_bound
- * reports (with fewer, the sets past the last tile get none, their voxels are not processed by a layer, and
- * the partition sets DSVT_ST_TILE_OVERFLOW in *status).
+ * reports (with fewer, the sets past the last tile -- or, in a frame of more than 16,384 sets, all sets -- get
+ * none, their voxels are not processed by a layer, and the partition sets DSVT_ST_TILE_OVERFLOW in *status).
  * Tiles hold 100 - 4*ceil(tau/4) rows on average; a frame whose tiles would not occupy the 256 compute
  * units once is cut into more, shorter tiles, and a frame of several rounds over the compute units gets tiles
  * filled as far as their sets go (up to 96 rows) when that saves a round or the frame has many rounds. */
