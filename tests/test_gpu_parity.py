@@ -326,6 +326,42 @@ def test_partition_buffer_survives_calls_that_report_errors(cid, n):
         assert_maps_equal(pair[axis], oms[axis])
 
 
+def test_short_tile_list_on_a_frame_built_in_pieces():
+    """The skewed batch has more sets than one workgroup's tables hold, so its work list is built piece by piece; with
+    a tile list shorter than it needs, the call reports DSVT_ST_TILE_OVERFLOW, leaves the list empty (the maps are
+    still exact) and a block over it runs without touching a row; the same buffers then take the full list."""
+    cfg = synth.CONFIGS[5]
+    coords = synth.make_frame(5, n=None)
+    shift = cfg["shifts"][0]
+    pc = dsvt.part_cfg(cfg["grid"], cfg["win"], shift, cfg["tau"], cfg["batch"], 0)
+    _say(f"short tile list, cfg5 n={len(coords)}")
+    cd = dev_coords(coords)
+    oms = [orc.partition(coords, cfg["grid"], cfg["win"], shift, cfg["tau"], a) for a in (0, 1)]
+    assert oms[0]["n_sets"] > 16384
+    short = dsvt.SetMapsXY(pc, len(coords), max_tiles=1000)
+    dsvt.dsvt_partition_xy(pc, cd, out=short)
+    torch.cuda.synchronize()
+    assert int(short.x.status.item()) == dsvt.binding.ST_TILE_OVERFLOW and int(short.x.n_tiles.item()) == 0
+    for axis in (0, 1):
+        ns = oms[axis]["n_sets"]
+        assert int(short[axis].n_sets.item()) == ns
+        assert np.array_equal(short[axis].set_inds[:ns].cpu().numpy(), oms[axis]["set_inds"])
+        assert np.array_equal(short[axis].voxel_slot.cpu().numpy(), oms[axis]["voxel_slot"])
+    x = dev_feats(synth.make_features(35, len(coords), cfg["C"], cfg["dtype"]), cfg["dtype"])
+    mk = lambda sd: synth.make_layer_weights(sd, cfg["C"], cfg["heads"], cfg["hidden"], cfg["win"], cfg["dtype"], True)
+    out = torch.full_like(x, 7.0)
+    dsvt.dsvt_block([dsvt.LayerWeights(mk(66)), dsvt.LayerWeights(mk(67))], short, cd, x, x_out=out)
+    torch.cuda.synchronize()
+    assert torch.all(out == 7.0)
+    full = dsvt.SetMapsXY(pc, len(coords))
+    full.x.ws = full.y.ws = short.x.ws
+    dsvt.dsvt_partition_xy(pc, cd, out=full)
+    torch.cuda.synchronize()
+    assert int(full.x.status.item()) == 0
+    for axis in (0, 1):
+        assert_maps_equal(full[axis], oms[axis])
+
+
 # ------------------------------------------------------------------ set attention / block
 def _layer_case(cid, n, seed, rel_bias=True, shift=None):
     cfg = synth.CONFIGS[cid]
