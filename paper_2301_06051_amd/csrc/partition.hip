@@ -218,27 +218,39 @@ __device__ __forceinline__ void fill_tile_starts(const int32_t* P, uint16_t* jum
         piece_first[atomicAdd(&n_pieces, 1)] = s;
     }
     for (int32_t step = 0; step < 7; ++step) {               // 2^7 > 96 / 4 + 2
+      int32_t mid[kB], pv[kB];                               // (no branches: the kB reads of a step go out together)
+#pragma unroll
+      for (int32_t k = 0; k < kB; ++k) { mid[k] = (lo[k] + hi[k]) >> 1; pv[k] = P[min(mid[k] + 1, n_sets)]; }
 #pragma unroll
       for (int32_t k = 0; k < kB; ++k) {
-        if (lo[k] < hi[k]) {
-          const int32_t mid = (lo[k] + hi[k]) >> 1;
-          if (P[mid + 1] > lim[k]) hi[k] = mid; else lo[k] = mid + 1;
-        }
+        const bool open = lo[k] < hi[k], over = pv[k] > lim[k];
+        hi[k] = (open && over) ? mid[k] : hi[k];
+        lo[k] = (open && !over) ? mid[k] + 1 : lo[k];
       }
+    }
+    // the walk below stays inside a piece: a jump that leaves the piece of its set ends it (n_sets)
+    int32_t here[kB], there[kB];
+#pragma unroll
+    for (int32_t k = 0; k < kB; ++k) {
+      const int32_t s = base + tid + k * 1024;
+      here[k] = P[min(s, n_sets)];
+      there[k] = P[lo[k]];                                   // (lo <= n_sets)
     }
 #pragma unroll
     for (int32_t k = 0; k < kB; ++k) {
       const int32_t s = base + tid + k * 1024;
-      if (s <= n_sets) { jump[s] = (uint16_t)lo[k]; mark[s] = 0; }     // (mark[n_sets] is a dummy)
+      if (s <= n_sets) {                                     // (mark[n_sets] is a dummy)
+        jump[s] = (uint16_t)((here[k] >> kFillPieceShift) == (there[k] >> kFillPieceShift) ? lo[k] : n_sets);
+        mark[s] = 0;
+      }
     }
   }
   lds_barrier();
   const int32_t np = n_pieces;
   for (int32_t i = tid; i < np; i += 1024) {
     int32_t s = piece_first[i];
-    const int32_t piece = P[s] >> kFillPieceShift;
     // at most kFillPieceRows / 4 + 1 sets begin in a piece; the bound also ends the walk on tables that are not sorted
-    for (int32_t step = 0; step <= kFillPieceRows / 4 && s < n_sets && (P[s] >> kFillPieceShift) == piece; ++step) {
+    for (int32_t step = 0; step <= kFillPieceRows / 4 && s < n_sets; ++step) {
       mark[s] = 1;
       s = jump[s];
     }
@@ -643,9 +655,11 @@ __device__ __forceinline__ void scan_windows_and_tiles(const int32_t* __restrict
   const int32_t tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   if (tid == 0) { carry_sr[0] = 0; carry_sr[1] = 0; }
   lds_barrier();
+  int32_t nvox_next = tid < n_windows ? win_count[tid] : 0;  // (a trip's counts are requested during the trip before)
   for (int32_t base = 0; base < n_windows; base += 1024) {
     const int32_t w = base + tid;
-    const int32_t nvox = w < n_windows ? win_count[w] : 0;
+    const int32_t nvox = nvox_next;
+    nvox_next = w + 1024 < n_windows ? win_count[w + 1024] : 0;
     const int32_t S = (nvox + tau - 1) / tau;
     SetWalk walk(nvox, S, tau);
     int32_t R = 0;
