@@ -326,6 +326,26 @@ def test_partition_buffer_survives_calls_that_report_errors(cid, n):
         assert_maps_equal(pair[axis], oms[axis])
 
 
+def test_work_list_of_a_frame_whose_bound_exceeds_the_tables_but_whose_sets_do_not():
+    """Two uniformly filled frames of 150,000 voxels: the bound on their sets (voxels / tau + windows = 20,501) is above
+    the 16,384 sets one workgroup's tables hold, so the host prepares the piece-wise launches, but the 12,317 sets
+    there are fit, and the first workgroup builds the whole list."""
+    grid, win, tau, batch, n = (468, 468, 32), (12, 12, 8), 36, 2, 150000
+    frames = []
+    for b in range(batch):
+        c = synth.frame_uniform(700 + b, grid, n)
+        frames.append(np.concatenate([np.full((len(c), 1), b, np.int64), c], 1))
+    coords = np.concatenate(frames).astype(np.int32)
+    pc = dsvt.part_cfg(grid, win, (0, 0, 0), tau, batch, 0)
+    bound = dsvt.binding.dsvt_partition_bound(pc, len(coords))[0]
+    oms = [orc.partition(coords, grid, win, (0, 0, 0), tau, a) for a in (0, 1)]
+    _say(f"work list, bound {bound} sets, {oms[0]['n_sets']} sets")
+    assert bound > 16384 >= oms[0]["n_sets"]
+    pair = dsvt.dsvt_partition_xy(pc, dev_coords(coords))
+    for axis in (0, 1):
+        assert_maps_equal(pair[axis], oms[axis])
+
+
 def test_short_tile_list_on_a_frame_built_in_pieces():
     """The skewed batch has more sets than one workgroup's tables hold, so its work list is built piece by piece; with
     a tile list shorter than it needs, the call reports DSVT_ST_TILE_OVERFLOW, leaves the list empty (the maps are
