@@ -16,9 +16,12 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=f
          "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-Wall", "-Wno-unused-function"]
 
 
-def _compile(src):
-    obj = os.path.join(OBJ_DIR, os.path.basename(src) + ".o")
-    r = subprocess.run([HIPCC, *FLAGS, "-c", src, "-o", obj], capture_output=True, text=True)
+PHASE_LIB = os.path.join(OBJ_DIR, "libdsvt_phase.so")    # the layer kernel with its optional phase clocks (csrc/phase_clock.h)
+
+
+def _compile(src, extra=(), suffix=".o"):
+    obj = os.path.join(OBJ_DIR, os.path.basename(src) + suffix)
+    r = subprocess.run([HIPCC, *FLAGS, *extra, "-c", src, "-o", obj], capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
     err = "\n".join(l for l in r.stderr.splitlines() if noise not in l)
     if r.returncode != 0:
@@ -45,5 +48,23 @@ def build_library(verbose=True):
     return LIB
 
 
+def build_phase_library(verbose=True):
+    """The same library with -DDSVT_PHASE_CLOCKS on layer.hip, beside the product library's objects (which must have
+    been built): what `python -m paper_2301_06051_amd.phase_clocks` loads.  Nothing else loads it."""
+    srcs = sorted(glob.glob(os.path.join(CSRC, "*.hip")))
+    objs = [os.path.join(OBJ_DIR, os.path.basename(src) + ".o") for src in srcs if os.path.basename(src) != "layer.hip"]
+    missing = [o for o in objs if not os.path.exists(o)]
+    if missing:
+        raise RuntimeError(f"build the product library first ({missing[0]} is missing)")
+    objs.append(_compile(os.path.join(CSRC, "layer.hip"), ("-DDSVT_PHASE_CLOCKS",), ".phase.o"))
+    r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", PHASE_LIB, *objs], capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("link failed:\n" + r.stderr)
+    if verbose:
+        print(f"built {PHASE_LIB}")
+    return PHASE_LIB
+
+
 if __name__ == "__main__":
     build_library()
+    build_phase_library()

@@ -12,6 +12,7 @@
 // output (every voxel is in exactly one set, Thm A.2-A.3), so a layer reads and writes [N, C] once.
 #include "common.h"
 #include "mma.h"
+#include "phase_clock.h"
 
 namespace {
 
@@ -272,6 +273,7 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
 #define DSVT_REFRESH_LANE() do { tid = opaque_tid(); lane = tid & 63; m = lane & 15; g = lane >> 4; } while (0)
   GemmPhase<T, NT_QKV, C, 3 * C, NW, 1, false> qkv(reinterpret_cast<const T*>(p.w_qkv), wave);
 
+  DSVT_PHASE(0);
   int ns;
   if (mp.tile_desc != nullptr) {
     // ---- 1a. rows from the tile descriptor the partition wrote for this workgroup (1 KB, one load)
@@ -359,6 +361,7 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
     }
     lds_barrier();
   }
+  DSVT_PHASE(1);                                 // rows known
   const int R = __builtin_amdgcn_readfirstlane(set_r0[ns]);
   const int RT = (R + 15) >> 4;
   const int RTK = ((RT + 1) >> 1) << 1;          // the LayerNorm phases run on an even number of row tiles
@@ -392,6 +395,7 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
   }
   lds_barrier();
   DSVT_REFRESH_LANE();
+  DSVT_PHASE(2);                                 // rows in LDS
   qkv.prefetch(p.b_qkv, 2 * C / (16 * NT_QKV));
 
   // ---- 3. Q, K, V = X W^T + b; V stored transposed
@@ -428,6 +432,7 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
   lds_barrier();
   DSVT_REFRESH_LANE();
 
+  DSVT_PHASE(3);                                 // Q, K, V^T in LDS
   // ---- 4. attention inside every set; O overwrites Q
   {
     const int n_items = __builtin_amdgcn_readfirstlane(items[kMaxItems]);
@@ -443,6 +448,7 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
   for (int nt = 0; nt < NT_O; ++nt) bo4[nt] = *reinterpret_cast<const f32x4*>(p.b_o + o_own + 16 * nt + 4 * g);
   lds_barrier();
   DSVT_REFRESH_LANE();
+  DSVT_PHASE(4);                                 // attention done
   // attention is done with V^T: the GELU table of the MLP takes its place (published by the
   // barriers of the LayerNorm below)
   constexpr bool kGeluTable = sizeof(T) == 2;
@@ -491,6 +497,7 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
     lds_barrier();
     DSVT_REFRESH_LANE();
 
+    DSVT_PHASE(5);                               // x1 in LDS
     // ---- 6. MLP: H = gelu(x1 W1^T + b1) over the dead Q/K tiles; x2 = LN(x1 + H W2^T + b2)
     ffn1.run(Xs, LDX, RT, p.b_1, [&](int o0, int r, f32x4 (&acc)[NT_1], bool) {
 #pragma unroll
@@ -512,6 +519,7 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
     for (int nt = 0; nt < NT_2; ++nt) b24[nt] = *reinterpret_cast<const f32x4*>(p.b_2 + o_own2 + 16 * nt + 4 * g);
     lds_barrier();
     DSVT_REFRESH_LANE();
+    DSVT_PHASE(6);                               // H in LDS
     f32x4 keep2[NT_2][kHalfTiles];
     if (HC == 1) ffn2.template run_keep<1>(Hs, LDH, rt_own, b24, keep2);
     else if (HC == 2) ffn2.template run_keep<2>(Hs, LDH, rt_own, b24, keep2);
@@ -538,6 +546,7 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
   lds_barrier();
   DSVT_REFRESH_LANE();
 
+  DSVT_PHASE(7);                                 // x2 in LDS
   // ---- 7. scatter: rows of Xs -> the voxels' rows of out, 16 bytes per thread
   {
     constexpr int CH = C * (int)sizeof(T) / 16;
@@ -549,6 +558,7 @@ k_layer(LayerDev p, MapsDev mp, const int4* __restrict__ coords, const T* x, T* 
             *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(Xs) + (size_t)r * LDX * sizeof(T) + c * 16);
     }
   }
+  DSVT_PHASE(8);
 }
 
 // ------------------------------------------------------------------------------------------
