@@ -23,6 +23,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--build", action="store_true")
     ap.add_argument("--config", type=int, default=2, help="synth.CONFIGS id (2: the benchmark's pillar frame)")
+    ap.add_argument("--no-position-term", action="store_true", help="layers without the relative position table")
     args = ap.parse_args()
     if args.build:
         _build.build_library()
@@ -42,7 +43,7 @@ def main():
     x = torch.as_tensor(synth.make_features(31, len(coords), cfg["C"], cfg["dtype"])).cuda()
     x = x.to(torch.bfloat16) if cfg["dtype"] == "bf16" else x
     cd = torch.as_tensor(coords).cuda()
-    mk = lambda s: dsvt.LayerWeights(synth.make_layer_weights(s, cfg["C"], cfg["heads"], cfg["hidden"], cfg["win"], cfg["dtype"], True))
+    mk = lambda s: dsvt.LayerWeights(synth.make_layer_weights(s, cfg["C"], cfg["heads"], cfg["hidden"], cfg["win"], cfg["dtype"], not args.no_position_term))
     layers = [mk(61), mk(62)]
     pair = dsvt.dsvt_partition_xy(dsvt.part_cfg(cfg["grid"], cfg["win"], cfg["shifts"][0], cfg["tau"], cfg["batch"], 0), cd)
     out = torch.empty_like(x)
