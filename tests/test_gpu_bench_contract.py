@@ -33,3 +33,22 @@ def test_bench_prints_one_json_line_with_the_agreed_fields():
     assert abs(roof["frac"] - roof["achieved"] / roof["peak"]) < 1e-4 and 0.02 < roof["frac"] < 1.0
     cpu = d["cpu_baseline"]
     assert cpu["kind"] == "oracle" and cpu["cores"] >= 1 and cpu["value"] > 0 and cpu["unit"] == "voxels/s" and cpu["sample"]
+
+
+@pytest.mark.timeout(200)
+def test_phase_clock_tool_prints_its_table():
+    """The optional instrumented build of the layer kernel (csrc/phase_clock.h) runs and reports clocks that add up: as
+    a child process, so that this process keeps the product library."""
+    from paper_2301_06051_amd.build import PHASE_LIB
+    if not os.path.exists(PHASE_LIB):
+        pytest.skip("instrumented library not built")
+    print("[case] python -m paper_2301_06051_amd.phase_clocks --config 2 as a child process", flush=True)
+    r = subprocess.run([sys.executable, "-m", "paper_2301_06051_amd.phase_clocks", "--config", "2"],
+                       capture_output=True, text=True, timeout=180, cwd=ROOT)
+    assert r.returncode == 0, r.stderr[-2000:]
+    rows = {l.split("|")[1].strip(): l.split("|")[2].strip() for l in r.stdout.splitlines() if l.startswith("| ") and "---" not in l}
+    clocks = lambda k: int(rows[k].replace(",", ""))
+    parts = [k for k in rows if k not in ("phase", "whole tile", "rows")]
+    assert len(parts) == 8 and all(clocks(k) > 0 for k in parts)
+    assert abs(sum(clocks(k) for k in parts) - clocks("whole tile")) <= len(parts)
+    assert 10_000 < clocks("whole tile") < 200_000
