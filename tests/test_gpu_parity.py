@@ -326,6 +326,31 @@ def test_partition_buffer_survives_calls_that_report_errors(cid, n):
         assert_maps_equal(pair[axis], oms[axis])
 
 
+@pytest.mark.parametrize("seed", [2, 5, 8])
+def test_large_random_frames_through_the_general_front_end(seed):
+    """Seeded random geometries (odd window sizes, shifts on every axis, two to four frames, 190,000-520,000 voxels):
+    bounds of 15,000-25,000 sets, i.e. work lists built by the window scan itself, by one workgroup, or piece by piece."""
+    rng = np.random.Generator(np.random.Philox(9900 + seed))
+    win = (int(rng.integers(6, 25)), int(rng.integers(6, 25)), int(rng.choice([1, 2, 4, 8, 16])))
+    grid = (int(rng.integers(200, 470)), int(rng.integers(200, 470)), int(win[2] * rng.integers(1, 5)))
+    shift = tuple(int(rng.integers(0, w)) for w in win)
+    tau = int(rng.choice([24, 36, 48, 60]))
+    batch = int(rng.choice([1, 1, 2, 4]))
+    n = int(min(rng.integers(40000, 160000), max(grid[0] * grid[1] * grid[2] // 3, 1)))
+    frames = []
+    for b in range(batch):
+        c = synth.frame_radial(9950 + 16 * seed + b, grid, n)
+        frames.append(np.concatenate([np.full((len(c), 1), b, np.int64), c], 1))
+    coords = np.concatenate(frames).astype(np.int32)
+    pc = dsvt.part_cfg(grid, win, shift, tau, batch, 0)
+    oms = [orc.partition(coords, grid, win, shift, tau, a) for a in (0, 1)]
+    _say(f"general front end seed={seed} grid={grid} win={win} shift={shift} tau={tau} batch={batch} n={len(coords)} "
+         f"bound={dsvt.binding.dsvt_partition_bound(pc, len(coords))[0]} sets={oms[0]['n_sets']}")
+    pair = dsvt.dsvt_partition_xy(pc, dev_coords(coords))
+    for axis in (0, 1):
+        assert_maps_equal(pair[axis], oms[axis])
+
+
 def test_work_list_of_a_frame_whose_bound_exceeds_the_tables_but_whose_sets_do_not():
     """Two uniformly filled frames of 150,000 voxels: the bound on their sets (voxels / tau + windows = 20,501) is above
     the 16,384 sets one workgroup's tables hold, so the host prepares the piece-wise launches, but the 12,317 sets
